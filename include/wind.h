@@ -1,0 +1,151 @@
+/*
+ * wind.h — C ABI of the MI355X (gfx950) WIND greedy decoder for RNN-T models.
+ *
+ * The library decodes a batch of encoder outputs with windowed non-blank detection: for every
+ * active utterance the joint network is evaluated on up to W consecutive encoder frames against
+ * the current prediction-network output, each row is argmaxed, the pointer jumps to the first
+ * non-blank row, that label is emitted and the prediction network takes one step (Method,
+ * Algorithm 2; its result equals the frame-by-frame loop of Algorithm 1).  All utterances of a
+ * batch advance together, each with its own frame pointer.
+ *
+ * Model (the paper names only "encoder, decoder, joiner"; this is the usual RNN-T factorisation):
+ *   joiner(f, g) = W_out relu(W_enc f + b_enc + W_pred g + b_pred) + b_out  -> V+1 logits
+ *   decoder      = embedding [V+1, E] + L stacked LSTM cells (gate order i, f, g, o; two bias
+ *                  vectors per layer); its output g is the top layer's hidden vector
+ *   blank id = V; the decoder's start token is also id V; argmax ties go to the lowest id.
+ *
+ * Conventions
+ *   - Every `const void *` / `float *` / `int32_t *` argument marked DEVICE is a pointer to GPU
+ *     memory owned by the caller (for example a torch tensor's data_ptr()); HOST pointers are
+ *     ordinary process memory.  The library never frees caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every function returns WIND_OK (0) or a negative wind_status; none throws or aborts.
+ *     wind_last_error() gives a thread-local, library-owned description of the last failure.
+ *   - wind_greedy_decode / wind_sequential_decode return after the decode has finished on
+ *     `stream` (they poll a completion word); outputs are then complete in device memory.
+ *   - Calls on one wind_model must not overlap: the model owns the decode workspace.
+ */
+#ifndef WIND_H_
+#define WIND_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  WIND_OK = 0,
+  WIND_ERR_ARG = -1,        /* null pointer, size out of range, inconsistent shapes */
+  WIND_ERR_HIP = -2,        /* a HIP runtime call failed; see wind_last_error()      */
+  WIND_ERR_OVERFLOW = -3,   /* an utterance produced more than `cap` labels          */
+  WIND_ERR_UNSUPPORTED = -4 /* a shape the kernels do not cover                      */
+} wind_status;
+
+typedef enum { WIND_F32 = 0, WIND_BF16 = 1 } wind_dtype;
+
+#define WIND_MAX_LAYERS 4
+#define WIND_MAX_WINDOW 64
+
+typedef struct wind_model wind_model; /* opaque, library-owned */
+
+/*
+ * Weights as the caller holds them: HOST pointers to fp32 arrays, row-major.  With
+ * dtype == WIND_BF16 the library stores every matrix (emb, w_ih, w_hh, w_enc, w_pred, w_out) as
+ * bf16, rounding to nearest-even, and computes with fp32 accumulation; biases stay fp32.  With
+ * WIND_F32 everything stays fp32.
+ */
+typedef struct {
+  int32_t D, E, Hp, L, Hj, V;
+  int32_t dtype;                               /* wind_dtype */
+  const float *emb;                            /* [V+1, E]                         */
+  const float *w_ih[WIND_MAX_LAYERS];          /* layer l: [4Hp, in_l], in_0 = E, in_l = Hp */
+  const float *w_hh[WIND_MAX_LAYERS];          /* [4Hp, Hp]                        */
+  const float *b_ih[WIND_MAX_LAYERS];          /* [4Hp]                            */
+  const float *b_hh[WIND_MAX_LAYERS];          /* [4Hp]                            */
+  const float *w_enc, *b_enc;                  /* [Hj, D], [Hj]                    */
+  const float *w_pred, *b_pred;                /* [Hj, Hp], [Hj]                   */
+  const float *w_out, *b_out;                  /* [V+1, Hj], [V+1]                 */
+} wind_weights;
+
+/* Counters of the last decode call on a model (Analysis, "Jump Distribution"). */
+typedef struct {
+  int64_t iterations;       /* loop iterations that had at least one active utterance        */
+  int64_t windows;          /* (utterance, iteration) pairs = joiner calls on a window       */
+  int64_t rows;             /* window rows evaluated = sum of n over windows                 */
+  int64_t useful_rows;      /* rows at or before the first non-blank of their window         */
+  int64_t labels;           /* labels emitted                                                */
+  int64_t forced_advances;  /* pointer advances taken because S labels sat on one frame      */
+  int64_t rechecks;         /* rows whose argmax was re-decided in fp32 after the bf16 pass  */
+  int64_t jump_hist[WIND_MAX_WINDOW + 1]; /* pointer advance per window, 0..W                 */
+} wind_stats;
+
+/*
+ * Copies the weights to the GPU in the layouts the kernels want and returns a model handle.
+ * The caller may free its arrays afterwards.  Limits: 1 <= L <= 4; D, E, Hp, Hj >= 1; V >= 1.
+ * With WIND_BF16, D, E, Hp and Hj must be multiples of 32.
+ */
+int wind_load_weights(const wind_weights *w, void *stream, wind_model **out);
+int wind_free(wind_model *m);
+
+/*
+ * Method, Algorithm 2, batched with one frame pointer per utterance.
+ *   enc_out   DEVICE [B, T, D] fp32 row-major; frames at or beyond lengths[b] are never used for a
+ *             decision and may hold anything.  With WIND_BF16 each value is rounded to bf16 on load.
+ *   lengths   DEVICE [B] int32, 0 <= lengths[b] <= T
+ *   W         window size, 1..WIND_MAX_WINDOW
+ *   max_symbols_per_step  S >= 1: after S labels on one frame the pointer moves to the next frame
+ *             without another joiner call (Algorithm 1 has no such bound; this is the usual guard)
+ *   out_tokens, out_frames  DEVICE [B, cap] int32: label k of utterance b and the 0-based frame it
+ *             was emitted on; entries beyond out_counts[b] are left untouched
+ *   out_counts DEVICE [B] int32
+ *   cap       capacity per utterance; T * S always suffices.  If an utterance needs more, its
+ *             extra labels are dropped, out_counts[b] is clamped to cap, and the call returns
+ *             WIND_ERR_OVERFLOW after finishing the decode.
+ * Returns WIND_ERR_ARG for null pointers, B < 1, T < 0, W or S out of range, cap < 1.
+ */
+int wind_greedy_decode(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T,
+                       int W, int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
+                       int32_t *out_counts, int cap, void *stream);
+
+/*
+ * Method, Algorithm 1 (the standard frame-by-frame loop; Table 1's window-size-1 row), batched
+ * the same way.  Same arguments without W.  Implemented as its own code path: one joiner row per
+ * utterance and iteration.
+ */
+int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T,
+                           int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
+                           int32_t *out_counts, int cap, void *stream);
+
+/* Counters of the last decode call; HOST pointer. */
+int wind_get_stats(wind_model *m, wind_stats *out);
+
+/*
+ * Debug: joiner logits of one window.  Steps the prediction network from nothing over
+ * prefix[0..prefix_len) (HOST int32 labels), then evaluates the joiner on frames t0..t0+n-1 of
+ * utterance b of enc_out (DEVICE [B, T, D]).  Writes DEVICE float [n, V+1] (Algorithm 2's
+ * `joined`; n = 16, V+1 = 1025 gives the 16400 floats of Analysis, "Memory Footprint").
+ *   exact = 0: the values the MFMA pass sees (bf16 hidden vector, fp32 accumulation; for
+ *              WIND_F32 models the same as exact = 1)
+ *   exact = 1: fp32 hidden vector, fp32 FMA (what near-tie decisions are re-decided with)
+ */
+int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, int b, int t0, int n,
+                            const int32_t *prefix, int prefix_len, int exact, float *logits,
+                            void *stream);
+
+/*
+ * Tuning knobs, for benchmarks and tests.  key/value pairs:
+ *   "graph"   1 (default): the decode loop is replayed from a captured HIP graph; 0: kernels are
+ *             launched one by one (the with / without graph rows of Table 5)
+ *   "unroll"  loop iterations per graph launch (default 16)
+ *   "recheck_kappa_milli"  width of the near-tie band of the bf16 pass, in thousandths
+ */
+int wind_set_option(wind_model *m, const char *key, int64_t value);
+
+const char *wind_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WIND_H_ */
