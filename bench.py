@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the WIND greedy-decoding hot path on one MI355X.
+
+A step is one wind_greedy_decode call over one batch of synthetic encoder outputs that already
+sit in HBM: encoder projection, then the loop of window gather, output contraction with row
+argmax, first-non-blank decision, pointer update and prediction-network step until every
+utterance is done.  The headline workload is benchmark configs[1] (B=1, T=1000, the window
+sweep of the paper's Table 1); the roofline object is measured on configs[3] (B=128, V=8192),
+the workload on which the joint kernel is MFMA-bound.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+FRAME_SECONDS = 0.080          # configs[1]: 80 ms of audio per encoder frame
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def timed_decodes(torch, model, d_enc, d_len, W, S, steps, warmup, out):
+    tok, frm, cnt = out
+    for _ in range(warmup):
+        model.greedy_decode(d_enc, d_len, W, S, tok, frm, cnt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        model.greedy_decode(d_enc, d_len, W, S, tok, frm, cnt)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def run_workload(torch, wi, WindModel, name, windows, steps, warmup, with_sequential):
+    cfg = wi.CONFIGS[name]
+    w = wi.make_weights(cfg)
+    enc, lens = wi.make_batch(cfg)
+    frames = int(lens.sum())
+    model = WindModel.from_config(cfg, w)
+    d_enc = torch.from_numpy(enc).cuda()
+    d_len = torch.from_numpy(lens).cuda()
+    B, T, _ = enc.shape
+    cap = T * cfg.S
+    out = (torch.zeros((B, cap), dtype=torch.int32, device="cuda"),
+           torch.zeros((B, cap), dtype=torch.int32, device="cuda"),
+           torch.zeros((B,), dtype=torch.int32, device="cuda"))
+    res = {}
+    ws = list(windows or cfg.windows)
+    for W in ([None] if with_sequential else []) + ws:
+        sec = timed_decodes(torch, model, d_enc, d_len, W, cfg.S, steps, warmup, out)
+        st = model.stats()
+        res["seq" if W is None else str(W)] = {
+            "frames_per_s": frames / sec, "rtfx": frames * FRAME_SECONDS / sec, "ms_per_step": sec * 1e3,
+            "iterations": int(st.iterations), "rows": int(st.rows), "useful_rows": int(st.useful_rows),
+            "labels": int(st.labels), "rechecks": int(st.rechecks)}
+    return cfg, model, (d_enc, d_len, out), frames, res, (enc, lens, w)
+
+
+def roofline_leg(torch, cfg, model, dev, W):
+    """Times every kernel launch of one decode with events (the library's profile mode) and prices
+    the joint kernel against the bf16 MFMA peak: algorithmic flops = 2 * Hj * (V+1) per window row
+    the method evaluates (rows past an utterance's end and tile padding do not count)."""
+    d_enc, d_len, out = dev
+    model.set_option("profile", 1)
+    model.greedy_decode(d_enc, d_len, W, cfg.S, *out)     # warm (allocations)
+    model.set_option("profile", 1)                        # resets the accumulators
+    model.greedy_decode(d_enc, d_len, W, cfg.S, *out)
+    st = model.stats()
+    kt = model.kernel_times()
+    model.set_option("profile", 0)
+    ms, n = kt["joint"]
+    flops = 2.0 * cfg.Hj * (cfg.V + 1) * st.rows
+    achieved = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+    # bytes the joint kernel must move per launch: W_out once, the window rows once, the keys out
+    return {
+        "bound": "mfma", "kernel": "joint_mfma_kernel", "workload": f"{cfg.name} W={W}",
+        "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+        "traffic": None, "launches": int(n), "avg_launch_us": ms * 1e3 / max(n, 1),
+        "rows_per_launch": st.rows / max(n, 1), "flops_per_row": 2.0 * cfg.Hj * (cfg.V + 1),
+        "kernel_ms": {k: round(v[0], 3) for k, v in kt.items()},
+        "kernel_launches": {k: int(v[1]) for k, v in kt.items()},
+    }
+
+
+def cpu_baseline(wi, cfg, enc, lens, w, budget_frames):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+
+    o = oracle.Oracle.from_config(cfg, w)
+    threads = min(16, os.cpu_count() or 1, oracle.num_threads())
+    # sample: the shortest utterances whose frames add up to about the budget (all of them for B=1)
+    order = np.argsort(lens)
+    pick, tot = [], 0
+    for b in order:
+        if pick and tot + lens[b] > budget_frames:
+            break
+        pick.append(int(b))
+        tot += int(lens[b])
+    sub_enc = np.ascontiguousarray(enc[pick])
+    sub_len = np.ascontiguousarray(lens[pick])
+    t0 = time.perf_counter()
+    o.greedy_batch(sub_enc, sub_len, cfg.S, threads=threads)
+    sec = time.perf_counter() - t0
+    used = min(threads, len(pick))
+    return {"value": tot / sec, "unit": "frames/s", "cores": used, "kind": "oracle",
+            "sample": f"{len(pick)} of {len(lens)} utterances of {cfg.name} ({tot} frames), "
+                      f"sequential greedy in fp64, one thread per utterance", "seconds": sec}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="greedy_b1")
+    ap.add_argument("--roofline-workload", default="largevocab_b128")
+    ap.add_argument("--roofline-window", type=int, default=16)
+    ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU (utterances are independent; more GPUs would "
+                 "each decode their own share with no exchange); --gpus must be 1")
+
+    import torch
+
+    import wind_inputs as wi
+    from paper_2505_13765_amd import WindModel
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+
+    cfg, model, dev, frames, res, host = run_workload(torch, wi, WindModel, args.workload, None,
+                                                      args.steps, args.warmup, with_sequential=True)
+    best_w = max((k for k in res if k != "seq"), key=lambda k: res[k]["frames_per_s"])
+    line = {
+        "metric": "encoder frames decoded/sec", "value": res[best_w]["frames_per_s"], "unit": "frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res[best_w]["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} T~{cfg.len_hi} D={cfg.D} Hj={cfg.Hj} V={cfg.V}+blank "
+                               f"L={cfg.L} S={cfg.S}", "window": int(best_w), "frames_per_step": frames},
+        "rtfx": res[best_w]["rtfx"],
+        "sweep": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()}
+                  for k, v in res.items()},
+        "speedup_vs_w1": {k: res[k]["frames_per_s"] / res["1"]["frames_per_s"] for k in res if "1" in res},
+        "paper_context": "paper: up to 2.4x greedy (W=8/16 vs W=1), 1.26x batched, on 2x A6000, encoder included",
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wi, cfg, host[0], host[1], host[2], budget_frames=1500)
+    model.close()
+    del dev, model
+    torch.cuda.empty_cache()
+
+    if not args.no_roofline:
+        rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload, None,
+                                                            max(1, min(args.steps, 3)), 1, with_sequential=False)
+        roof = roofline_leg(torch, rcfg, rmodel, rdev, args.roofline_window)
+        roof["frames_per_s"] = {k: round(v["frames_per_s"], 1) for k, v in rres.items()}
+        roof["ms_per_step"] = {k: round(v["ms_per_step"], 3) for k, v in rres.items()}
+        line["roofline"] = roof
+        rmodel.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

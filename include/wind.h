@@ -84,7 +84,7 @@ typedef struct {
 /*
  * Copies the weights to the GPU in the layouts the kernels want and returns a model handle.
  * The caller may free its arrays afterwards.  Limits: 1 <= L <= 4; D, E, Hp, Hj >= 1; V >= 1.
- * With WIND_BF16, D, E, Hp and Hj must be multiples of 32.
+ * With WIND_BF16, D, E, Hp and Hj must be multiples of 64 and Hj <= 2048 (WIND_ERR_UNSUPPORTED otherwise).
  */
 int wind_load_weights(const wind_weights *w, void *stream, wind_model **out);
 int wind_free(wind_model *m);
@@ -111,8 +111,7 @@ int wind_greedy_decode(wind_model *m, const float *enc_out, const int32_t *lengt
 
 /*
  * Method, Algorithm 1 (the standard frame-by-frame loop; Table 1's window-size-1 row), batched
- * the same way.  Same arguments without W.  Implemented as its own code path: one joiner row per
- * utterance and iteration.
+ * the same way: one joiner row per utterance and iteration.  Same arguments without W.
  */
 int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T,
                            int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
@@ -135,10 +134,28 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
                             void *stream);
 
 /*
+ * Per-kernel device time, for the roofline report.  With option "profile" = 1 the decode loop is
+ * launched kernel by kernel (no graph) with an event pair around every launch; this call returns
+ * the accumulated milliseconds and launch counts since the option was last set, indexed by
+ * wind_kernel_id.  HOST pointers to WIND_NUM_KERNELS entries each.
+ */
+typedef enum {
+  WIND_K_ENC_PROJ = 0,  /* encoder projection, once per call           */
+  WIND_K_BUILD_Z = 1,   /* window gather + activation                  */
+  WIND_K_JOINT = 2,     /* output contraction + row argmax             */
+  WIND_K_DECIDE = 3,    /* first non-blank, pointer update, compaction */
+  WIND_K_LSTM = 4,      /* all LSTM layers of one step                 */
+  WIND_K_PRED_PROJ = 5, /* prediction projection                       */
+  WIND_NUM_KERNELS = 6
+} wind_kernel_id;
+int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
+
+/*
  * Tuning knobs, for benchmarks and tests.  key/value pairs:
  *   "graph"   1 (default): the decode loop is replayed from a captured HIP graph; 0: kernels are
  *             launched one by one (the with / without graph rows of Table 5)
- *   "unroll"  loop iterations per graph launch (default 16)
+ *   "unroll"  loop iterations per graph launch (default 16, even)
+ *   "profile" 1: time every kernel launch with events (see wind_get_kernel_times); implies no graph
  *   "recheck_kappa_milli"  width of the near-tie band of the bf16 pass, in thousandths
  */
 int wind_set_option(wind_model *m, const char *key, int64_t value);

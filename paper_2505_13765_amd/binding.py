@@ -1,0 +1,183 @@
+"""ctypes binding of include/wind.h.  Argument marshalling only: every step of decoding runs in
+the HIP kernels of libwind.so.  torch supplies device memory and the stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+WIND_MAX_LAYERS = 4
+WIND_MAX_WINDOW = 64
+WIND_F32, WIND_BF16 = 0, 1
+WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0, -1, -2, -3, -4
+
+EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
+           "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
+           "wind_get_kernel_times")
+KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
+
+
+class WindError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"wind error {code}: {msg}")
+        self.code = code
+
+
+class _Weights(C.Structure):
+    _fields_ = [
+        ("D", C.c_int32), ("E", C.c_int32), ("Hp", C.c_int32), ("L", C.c_int32), ("Hj", C.c_int32),
+        ("V", C.c_int32), ("dtype", C.c_int32),
+        ("emb", C.c_void_p),
+        ("w_ih", C.c_void_p * WIND_MAX_LAYERS), ("w_hh", C.c_void_p * WIND_MAX_LAYERS),
+        ("b_ih", C.c_void_p * WIND_MAX_LAYERS), ("b_hh", C.c_void_p * WIND_MAX_LAYERS),
+        ("w_enc", C.c_void_p), ("b_enc", C.c_void_p), ("w_pred", C.c_void_p), ("b_pred", C.c_void_p),
+        ("w_out", C.c_void_p), ("b_out", C.c_void_p),
+    ]
+
+
+class WindStats(C.Structure):
+    _fields_ = [
+        ("iterations", C.c_int64), ("windows", C.c_int64), ("rows", C.c_int64), ("useful_rows", C.c_int64),
+        ("labels", C.c_int64), ("forced_advances", C.c_int64), ("rechecks", C.c_int64),
+        ("jump_hist", C.c_int64 * (WIND_MAX_WINDOW + 1)),
+    ]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libwind.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libwind.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise FileNotFoundError(f"{path} is missing: run `python -m paper_2505_13765_amd.build` first")
+        lib = C.CDLL(path)
+        lib.wind_last_error.restype = C.c_char_p
+        lib.wind_load_weights.argtypes = [C.POINTER(_Weights), C.c_void_p, C.POINTER(C.c_void_p)]
+        lib.wind_free.argtypes = [C.c_void_p]
+        lib.wind_greedy_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        lib.wind_sequential_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        lib.wind_get_stats.argtypes = [C.c_void_p, C.POINTER(WindStats)]
+        lib.wind_debug_joint_logits.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        lib.wind_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
+        lib.wind_get_kernel_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int, allow_overflow: bool = False) -> int:
+    if rc == WIND_OK or (allow_overflow and rc == WIND_ERR_OVERFLOW):
+        return rc
+    raise WindError(rc, load_library().wind_last_error().decode())
+
+
+def _stream_ptr() -> int:
+    import torch
+
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+class WindModel:
+    """Owns a wind_model handle.  `weights` are fp32 numpy arrays named as in wind_inputs.make_weights."""
+
+    def __init__(self, D: int, E: int, Hp: int, L: int, Hj: int, V: int, dtype: str,
+                 weights: Dict[str, np.ndarray]):
+        self._lib = load_library()
+        self.D, self.E, self.Hp, self.L, self.Hj, self.V = D, E, Hp, L, Hj, V
+        w = {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in weights.items()}
+        ws = _Weights()
+        ws.D, ws.E, ws.Hp, ws.L, ws.Hj, ws.V = D, E, Hp, L, Hj, V
+        ws.dtype = {"f32": WIND_F32, "bf16": WIND_BF16}[dtype]
+        ws.emb = w["emb"].ctypes.data
+        for l in range(min(L, WIND_MAX_LAYERS)):
+            ws.w_ih[l] = w[f"w_ih{l}"].ctypes.data
+            ws.w_hh[l] = w[f"w_hh{l}"].ctypes.data
+            ws.b_ih[l] = w[f"b_ih{l}"].ctypes.data
+            ws.b_hh[l] = w[f"b_hh{l}"].ctypes.data
+        ws.w_enc, ws.b_enc = w["w_enc"].ctypes.data, w["b_enc"].ctypes.data
+        ws.w_pred, ws.b_pred = w["w_pred"].ctypes.data, w["b_pred"].ctypes.data
+        ws.w_out, ws.b_out = w["w_out"].ctypes.data, w["b_out"].ctypes.data
+        h = C.c_void_p()
+        _check(self._lib.wind_load_weights(C.byref(ws), None, C.byref(h)))
+        self._h = h
+
+    @classmethod
+    def from_config(cls, cfg, weights):
+        return cls(cfg.D, cfg.E, cfg.Hp, cfg.L, cfg.Hj, cfg.V, cfg.dtype, weights)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.wind_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_option(self, key: str, value: int) -> None:
+        _check(self._lib.wind_set_option(self._h, key.encode(), int(value)))
+
+    def greedy_decode(self, enc_out, lengths, W: Optional[int], S: int, out_tokens, out_frames, out_counts,
+                      allow_overflow: bool = False) -> int:
+        """enc_out [B,T,D] float32 cuda, lengths [B] int32 cuda, outputs [B,cap] / [B] int32 cuda.
+        W=None calls wind_sequential_decode."""
+        B, T, D = enc_out.shape
+        assert D == self.D and enc_out.is_contiguous() and lengths.is_contiguous()
+        cap = out_tokens.shape[1]
+        args = (self._h, enc_out.data_ptr(), lengths.data_ptr(), B, T)
+        tail = (S, out_tokens.data_ptr(), out_frames.data_ptr(), out_counts.data_ptr(), cap, _stream_ptr())
+        if W is None:
+            rc = self._lib.wind_sequential_decode(*args, *tail)
+        else:
+            rc = self._lib.wind_greedy_decode(*args, W, *tail)
+        return _check(rc, allow_overflow)
+
+    def decode(self, enc_out, lengths, W: Optional[int], S: int, cap: Optional[int] = None):
+        """Convenience wrapper: allocates outputs with torch and returns per-utterance numpy lists."""
+        import torch
+
+        B, T, _ = enc_out.shape
+        cap = cap or max(1, T * S)
+        tok = torch.zeros((B, cap), dtype=torch.int32, device=enc_out.device)
+        frm = torch.zeros((B, cap), dtype=torch.int32, device=enc_out.device)
+        cnt = torch.zeros((B,), dtype=torch.int32, device=enc_out.device)
+        self.greedy_decode(enc_out, lengths, W, S, tok, frm, cnt)
+        tok, frm, cnt = tok.cpu().numpy(), frm.cpu().numpy(), cnt.cpu().numpy()
+        return [tok[b, : cnt[b]] for b in range(B)], [frm[b, : cnt[b]] for b in range(B)]
+
+    def stats(self) -> WindStats:
+        s = WindStats()
+        _check(self._lib.wind_get_stats(self._h, C.byref(s)))
+        return s
+
+    def kernel_times(self):
+        """{kernel: (total ms, launches)} accumulated since option "profile" was last set."""
+        ms = (C.c_double * len(KERNEL_NAMES))()
+        n = (C.c_int64 * len(KERNEL_NAMES))()
+        _check(self._lib.wind_get_kernel_times(self._h, ms, n))
+        return {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_NAMES)}
+
+    def debug_joint_logits(self, enc_out, b: int, t0: int, n: int, prefix: Sequence[int], exact: bool):
+        import torch
+
+        B, T, _ = enc_out.shape
+        pre = np.ascontiguousarray(list(prefix), dtype=np.int32)
+        out = torch.zeros((n, self.V + 1), dtype=torch.float32, device=enc_out.device)
+        _check(self._lib.wind_debug_joint_logits(self._h, enc_out.data_ptr(), B, T, b, t0, n,
+                                                 pre.ctypes.data if pre.size else None, int(pre.size),
+                                                 1 if exact else 0, out.data_ptr(), _stream_ptr()))
+        return out.cpu().numpy()

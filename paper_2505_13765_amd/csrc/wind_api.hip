@@ -1,0 +1,599 @@
+// Host side of libwind: the C ABI of include/wind.h, weight upload, workspace, the decode loop
+// (replayed from a captured HIP graph), statistics and the debug entry point.
+#include "../../include/wind.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "wind_kernels.h"
+
+using namespace wind;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string &msg) {
+  g_err = msg;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess)                                                                     \
+      return fail(WIND_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));           \
+  } while (0)
+
+using JointCfg = TileCfg<128, 128, 64, 64>;
+using EncCfg = TileCfg<128, 128, 64, 64>;
+constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height
+
+uint16_t host_bf16(float x) {
+  uint32_t u;
+  std::memcpy(&u, &x, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+float host_bf16_to_f32(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct GraphKey {
+  CallDev call;
+  int unroll;
+  bool operator==(const GraphKey &o) const { return std::memcmp(this, &o, sizeof(GraphKey)) == 0; }
+};
+
+}  // namespace
+
+struct wind_model {
+  ModelDev dev{};
+  int dtype = WIND_BF16;
+  std::vector<void *> allocs;
+  // workspace
+  void *ws = nullptr;
+  size_t ws_bytes = 0;
+  CallDev call{};
+  // loop replay
+  hipStream_t cap_stream = nullptr;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  GraphKey graph_key{};
+  bool graph_valid = false;
+  int opt_graph = 1, opt_unroll = 16;
+  double kappa = 8.0;
+  double wnorm_max = 0.0;
+  int *h_flag = nullptr;  // pinned
+  long long prev_iters = 0;
+  int prev_B = 0, prev_T = 0, prev_W = 0;
+  wind_stats last_stats{};
+  bool have_stats = false;
+  // per-kernel timing (option "profile"): event pairs recorded around each launch, read at every poll
+  int opt_profile = 0;
+  std::vector<hipEvent_t> ev_pool;
+  std::vector<int> ev_kind;   // kind of pair i (events 2i, 2i+1)
+  double prof_ms[WIND_NUM_KERNELS] = {0};
+  long long prof_n[WIND_NUM_KERNELS] = {0};
+};
+
+namespace {
+
+template <class T>
+int upload(wind_model *m, const std::vector<T> &host, const void **dev_out) {
+  void *d = nullptr;
+  HIP_TRY(hipMalloc(&d, host.size() * sizeof(T) + 256));
+  m->allocs.push_back(d);
+  HIP_TRY(hipMemcpy(d, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  *dev_out = d;
+  return WIND_OK;
+}
+
+// matrix [rows, cols] fp32 -> model storage type, optionally padded with zero rows
+int upload_matrix(wind_model *m, const float *src, size_t rows, size_t cols, size_t rows_pad, const void **out) {
+  if (m->dtype == WIND_BF16) {
+    std::vector<uint16_t> h(rows_pad * cols, 0);
+    for (size_t i = 0; i < rows * cols; ++i) h[i] = host_bf16(src[i]);
+    return upload(m, h, out);
+  }
+  std::vector<float> h(rows_pad * cols, 0.f);
+  std::memcpy(h.data(), src, rows * cols * sizeof(float));
+  return upload(m, h, out);
+}
+
+void set_tau(wind_model *m) {
+  // bf16 rounding of the hidden vector: relative error uniform within half an ulp (2^-8), rms
+  // about 1.5e-3 of the value; the difference of two screened logits then has standard deviation
+  // about 2.1e-3 * |w| * |z| / sqrt(Hj) for weights that are not aligned with z.  kappa such
+  // deviations make the band.
+  m->dev.tau_scale = (float)(m->kappa * 2.1e-3 * m->wnorm_max / std::sqrt((double)m->dev.Hj));
+}
+
+int ensure_workspace(wind_model *m, int B, int T, int W) {
+  const ModelDev &d = m->dev;
+  const size_t Mpad = round_up((size_t)B * W, kRowPad);
+  const int ntiles = (d.V + JointCfg::BN - 1) / JointCfg::BN;
+  const int nparts = ntiles * JointCfg::WAVES_N;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += round_up(bytes, 256);
+    return o;
+  };
+  const size_t o_e = take((size_t)B * T * d.Hj * 4);
+  const size_t o_len = take((size_t)B * 4), o_t = take((size_t)B * 4), o_sym = take((size_t)B * 4);
+  const size_t o_count = take((size_t)B * 4), o_flag = take((size_t)B * 4), o_etok = take((size_t)B * 4);
+  const size_t o_act = take((size_t)2 * B * 4), o_nact = take(8), o_eidx = take((size_t)B * 4);
+  const size_t o_nemit = take(4), o_ticket = take(4);
+  const size_t st = (size_t)d.L * B * d.Hp * 4;
+  const size_t o_h = take(st), o_c = take(st), o_hn = take(st);
+  const size_t o_p = take((size_t)B * d.Hj * 4);
+  const size_t o_z = take(Mpad * d.Hj * 2);
+  const size_t o_bl = take(Mpad * 4), o_zn = take(Mpad * 4);
+  const size_t o_parts = take(Mpad * nparts * 8);
+  const size_t o_rl = take(Mpad * 4);
+  const size_t o_stats = take(kNumStats * 8);
+  if (off > m->ws_bytes) {
+    HIP_TRY(hipDeviceSynchronize());
+    if (m->ws) HIP_TRY(hipFree(m->ws));
+    m->ws = nullptr;
+    m->ws_bytes = 0;
+    m->graph_valid = false;
+    HIP_TRY(hipMalloc(&m->ws, off));
+    m->ws_bytes = off;
+    // window-row buffers are read tile-wide: start them defined
+    HIP_TRY(hipMemset(m->ws, 0, off));
+  }
+  char *base = (char *)m->ws;
+  CallDev &c = m->call;
+  c.e = (float *)(base + o_e);
+  c.len = (int *)(base + o_len); c.t = (int *)(base + o_t); c.sym = (int *)(base + o_sym);
+  c.count = (int *)(base + o_count); c.flag = (int *)(base + o_flag); c.emit_tok = (int *)(base + o_etok);
+  c.active_idx = (int *)(base + o_act); c.n_active = (int *)(base + o_nact);
+  c.emit_idx = (int *)(base + o_eidx); c.n_emit = (int *)(base + o_nemit);
+  c.ticket = (unsigned *)(base + o_ticket);
+  c.h = (float *)(base + o_h); c.c = (float *)(base + o_c); c.hn = (float *)(base + o_hn);
+  c.p = (float *)(base + o_p);
+  c.z = (bf16_t *)(base + o_z);
+  c.blank_logit = (float *)(base + o_bl); c.znorm = (float *)(base + o_zn);
+  c.parts = (int2 *)(base + o_parts);
+  c.nparts = nparts;
+  c.part_width = JointCfg::WN;
+  c.row_label = (int *)(base + o_rl);
+  c.stats = (unsigned long long *)(base + o_stats);
+  return WIND_OK;
+}
+
+int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(WIND_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+  return WIND_OK;
+}
+
+// ---- per-kernel timing -------------------------------------------------------------------------
+struct ProfScope {
+  wind_model *m;
+  hipStream_t s;
+  bool on;
+  ProfScope(wind_model *m_, hipStream_t s_, int kind, bool capturing) : m(m_), s(s_), on(m_->opt_profile && !capturing) {
+    if (!on) return;
+    const size_t i = m->ev_kind.size();
+    while (m->ev_pool.size() < 2 * (i + 1)) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+      m->ev_pool.push_back(e);
+    }
+    m->ev_kind.push_back(kind);
+    (void)hipEventRecord(m->ev_pool[2 * i], s);
+  }
+  ~ProfScope() {
+    if (on) (void)hipEventRecord(m->ev_pool[2 * (m->ev_kind.size() - 1) + 1], s);
+  }
+};
+
+// call after the stream has been synchronised
+void prof_collect(wind_model *m) {
+  for (size_t i = 0; i < m->ev_kind.size(); ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, m->ev_pool[2 * i], m->ev_pool[2 * i + 1]) == hipSuccess) {
+      m->prof_ms[m->ev_kind[i]] += ms;
+      m->prof_n[m->ev_kind[i]] += 1;
+    }
+  }
+  m->ev_kind.clear();
+}
+
+// prediction-network step for the utterances on the emit list, then their projection
+int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
+  const ModelDev &d = m->dev;
+  const CallDev &c = m->call;
+  const int lstm_blocks = (d.Hp + 3) / 4, proj_blocks = (d.Hj + 3) / 4;
+  {
+    ProfScope ps(m, s, WIND_K_LSTM, capturing);
+    for (int l = 0; l < d.L; ++l) {
+      if (m->dtype == WIND_BF16) lstm_layer_kernel<bf16_t, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
+      else lstm_layer_kernel<float, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
+    }
+  }
+  {
+    ProfScope ps(m, s, WIND_K_PRED_PROJ, capturing);
+    if (m->dtype == WIND_BF16) pred_proj_kernel<bf16_t, 4><<<proj_blocks, 256, 0, s>>>(d, c);
+    else pred_proj_kernel<float, 4><<<proj_blocks, 256, 0, s>>>(d, c);
+  }
+  return check_launch("prediction step");
+}
+
+int enqueue_prologue(wind_model *m, hipStream_t s) {
+  const ModelDev &d = m->dev;
+  const CallDev &c = m->call;
+  init_state_kernel<<<1, 256, 0, s>>>(d, c);
+  if (c.T > 0) {
+    ProfScope ps(m, s, WIND_K_ENC_PROJ, false);
+    if (m->dtype == WIND_BF16) {
+      const int tiles_per_utt = (c.T + EncCfg::BM - 1) / EncCfg::BM;
+      dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncCfg::BN - 1) / EncCfg::BN));
+      enc_proj_mfma_kernel<EncCfg><<<grid, EncCfg::NT, EncCfg::SMEM_BYTES, s>>>(d, c, tiles_per_utt);
+    } else {
+      dim3 grid((unsigned)c.T, (unsigned)c.B);
+      enc_proj_f32_kernel<<<grid, 256, (size_t)d.D * 4, s>>>(d, c);
+    }
+  }
+  int rc = check_launch("prologue");
+  if (rc) return rc;
+  return enqueue_pred_step(m, s, false);
+}
+
+int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) {
+  const ModelDev &d = m->dev;
+  const CallDev &c = m->call;
+  const int max_rows = c.B * c.W;
+  const int decide_threads = 64 * (c.W < 16 ? c.W : 16);
+  if (m->dtype == WIND_BF16) {
+    {
+      ProfScope ps(m, s, WIND_K_BUILD_Z, capturing);
+      build_z_kernel<<<(max_rows + 3) / 4, 256, 0, s>>>(d, c, parity);
+    }
+    {
+      ProfScope ps(m, s, WIND_K_JOINT, capturing);
+      dim3 grid((unsigned)((max_rows + JointCfg::BM - 1) / JointCfg::BM),
+                (unsigned)((d.V + JointCfg::BN - 1) / JointCfg::BN));
+      joint_mfma_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, c, parity);
+    }
+    {
+      ProfScope ps(m, s, WIND_K_DECIDE, capturing);
+      decide_kernel<bf16_t><<<c.B, decide_threads, 0, s>>>(d, c, parity, 0);
+    }
+  } else {
+    {
+      ProfScope ps(m, s, WIND_K_JOINT, capturing);
+      joint_exact_kernel<float><<<max_rows, 256, (size_t)d.Hj * 4, s>>>(d, c, parity, 1, 0, 0, 0, nullptr, 0,
+                                                                       nullptr, nullptr);
+    }
+    {
+      ProfScope ps(m, s, WIND_K_DECIDE, capturing);
+      decide_kernel<float><<<c.B, decide_threads, 0, s>>>(d, c, parity, 1);
+    }
+  }
+  int rc = check_launch("iteration");
+  if (rc) return rc;
+  return enqueue_pred_step(m, s, capturing);
+}
+
+int ensure_graph(wind_model *m) {
+  GraphKey key{};
+  key.call = m->call;
+  key.unroll = m->opt_unroll;
+  if (m->graph_valid && key == m->graph_key) return WIND_OK;
+  if (m->graph_exec) { (void)hipGraphExecDestroy(m->graph_exec); m->graph_exec = nullptr; }
+  if (m->graph) { (void)hipGraphDestroy(m->graph); m->graph = nullptr; }
+  m->graph_valid = false;
+  if (!m->cap_stream) HIP_TRY(hipStreamCreateWithFlags(&m->cap_stream, hipStreamNonBlocking));
+  HIP_TRY(hipStreamBeginCapture(m->cap_stream, hipStreamCaptureModeThreadLocal));
+  int rc = WIND_OK;
+  for (int it = 0; it < m->opt_unroll && rc == WIND_OK; ++it) rc = enqueue_iteration(m, m->cap_stream, it & 1, true);
+  hipGraph_t g = nullptr;
+  hipError_t e = hipStreamEndCapture(m->cap_stream, &g);
+  if (rc != WIND_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
+  if (e != hipSuccess) return fail(WIND_ERR_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+  m->graph = g;
+  HIP_TRY(hipGraphInstantiate(&m->graph_exec, m->graph, nullptr, nullptr, 0));
+  m->graph_key = key;
+  m->graph_valid = true;
+  return WIND_OK;
+}
+
+int fetch_stats(wind_model *m, hipStream_t s) {
+  unsigned long long h[kNumStats];
+  HIP_TRY(hipMemcpyAsync(h, m->call.stats, sizeof(h), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  wind_stats &st = m->last_stats;
+  std::memset(&st, 0, sizeof(st));
+  st.iterations = (int64_t)h[ST_ITER];
+  st.windows = (int64_t)h[ST_WINDOWS];
+  st.rows = (int64_t)h[ST_ROWS];
+  st.useful_rows = (int64_t)h[ST_USEFUL];
+  st.labels = (int64_t)h[ST_LABELS];
+  st.forced_advances = (int64_t)h[ST_FORCED];
+  st.rechecks = (int64_t)h[ST_RECHECK];
+  for (int i = 0; i <= WIND_MAX_WINDOW; ++i) st.jump_hist[i] = (int64_t)h[kStatJump0 + i];
+  m->have_stats = true;
+  return h[ST_OVERFLOW] ? WIND_ERR_OVERFLOW : WIND_OK;
+}
+
+int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T, int W, int S,
+           int32_t *out_tokens, int32_t *out_frames, int32_t *out_counts, int cap, void *stream) {
+  if (!m) return fail(WIND_ERR_ARG, "model is null");
+  if (!lengths || !out_tokens || !out_frames || !out_counts) return fail(WIND_ERR_ARG, "null pointer argument");
+  if (B < 1 || T < 0 || cap < 1) return fail(WIND_ERR_ARG, "B >= 1, T >= 0, cap >= 1 required");
+  if (T > 0 && !enc) return fail(WIND_ERR_ARG, "enc_out is null");
+  if (W < 1 || W > WIND_MAX_WINDOW) return fail(WIND_ERR_ARG, "W must be in 1..64");
+  if (S < 1) return fail(WIND_ERR_ARG, "max_symbols_per_step must be >= 1");
+  if ((long long)B * T > (1ll << 31) - 1) return fail(WIND_ERR_ARG, "B*T too large");
+  if (m->dtype == WIND_BF16 && m->dev.Hj > kDecideMaxHj) return fail(WIND_ERR_UNSUPPORTED, "Hj > 2048");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_workspace(m, B, T, W);
+  if (rc) return rc;
+  CallDev &c = m->call;
+  c.B = B; c.T = T; c.W = W; c.S = S; c.cap = cap;
+  c.enc = enc; c.lengths = lengths;
+  c.out_tokens = out_tokens; c.out_frames = out_frames; c.out_counts = out_counts;
+
+  rc = enqueue_prologue(m, s);
+  if (rc) return rc;
+  const int U = m->opt_unroll;
+  const bool use_graph = m->opt_graph && !m->opt_profile;   // events cannot sit between graph nodes
+  if (use_graph) {
+    rc = ensure_graph(m);
+    if (rc) return rc;
+  }
+  // Launch ahead by what the previous call of the same shape needed, then poll once per replay.
+  long long ahead = 1;
+  if (m->prev_B == B && m->prev_T == T && m->prev_W == W && m->prev_iters > 0) ahead = m->prev_iters / U;
+  if (ahead < 1) ahead = 1;
+  const long long max_launches = ((long long)T * (S + 1) + 2 * U) / U + 2;  // every iteration moves some pointer or emits
+  long long launches = 0;
+  for (;;) {
+    for (long long i = 0; i < ahead; ++i, ++launches) {
+      if (use_graph) {
+        HIP_TRY(hipGraphLaunch(m->graph_exec, s));
+      } else {
+        for (int it = 0; it < U; ++it) {
+          rc = enqueue_iteration(m, s, it & 1, false);
+          if (rc) return rc;
+        }
+      }
+    }
+    ahead = 1;
+    HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    prof_collect(m);
+    if (*m->h_flag == 0) break;
+    if (launches > max_launches) return fail(WIND_ERR_HIP, "decode loop did not terminate");
+  }
+  rc = fetch_stats(m, s);
+  m->prev_B = B; m->prev_T = T; m->prev_W = W;
+  m->prev_iters = m->last_stats.iterations;
+  if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *wind_last_error(void) { return g_err.c_str(); }
+
+int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
+  (void)stream;
+  if (!w || !out) return fail(WIND_ERR_ARG, "null argument");
+  *out = nullptr;
+  if (w->L < 1 || w->L > WIND_MAX_LAYERS) return fail(WIND_ERR_ARG, "L must be in 1..4");
+  if (w->D < 1 || w->E < 1 || w->Hp < 1 || w->Hj < 1 || w->V < 1) return fail(WIND_ERR_ARG, "sizes must be >= 1");
+  if (w->dtype != WIND_F32 && w->dtype != WIND_BF16) return fail(WIND_ERR_ARG, "unknown dtype");
+  if (!w->emb || !w->w_enc || !w->b_enc || !w->w_pred || !w->b_pred || !w->w_out || !w->b_out)
+    return fail(WIND_ERR_ARG, "null weight pointer");
+  for (int l = 0; l < w->L; ++l)
+    if (!w->w_ih[l] || !w->w_hh[l] || !w->b_ih[l] || !w->b_hh[l]) return fail(WIND_ERR_ARG, "null LSTM weight pointer");
+  if (w->dtype == WIND_BF16 && (w->D % 64 || w->E % 64 || w->Hp % 64 || w->Hj % 64))
+    return fail(WIND_ERR_UNSUPPORTED, "bf16 models need D, E, Hp, Hj to be multiples of 64");
+  if ((long long)(w->V + 1) * w->Hj > (1ll << 31) - 1) return fail(WIND_ERR_UNSUPPORTED, "(V+1)*Hj too large");
+
+  wind_model *m = new wind_model();
+  m->dtype = w->dtype;
+  ModelDev &d = m->dev;
+  d.D = w->D; d.E = w->E; d.Hp = w->Hp; d.L = w->L; d.Hj = w->Hj; d.V = w->V;
+  d.Vpad = (int)round_up((size_t)w->V + 1, 256);
+  int rc = WIND_OK;
+  auto chk = [&](int r) { if (rc == WIND_OK) rc = r; };
+  const int Hp = w->Hp;
+  chk(upload_matrix(m, w->emb, (size_t)w->V + 1, w->E, (size_t)w->V + 1, &d.emb));
+  for (int l = 0; l < w->L && rc == WIND_OK; ++l) {
+    const int in = l == 0 ? w->E : Hp, K = in + Hp;
+    std::vector<float> cat((size_t)4 * Hp * K), bias((size_t)4 * Hp);
+    for (int g = 0; g < 4; ++g)
+      for (int j = 0; j < Hp; ++j) {
+        const size_t src = (size_t)g * Hp + j, dst = (size_t)j * 4 + g;
+        std::memcpy(&cat[dst * K], w->w_ih[l] + src * in, sizeof(float) * in);
+        std::memcpy(&cat[dst * K + in], w->w_hh[l] + src * Hp, sizeof(float) * Hp);
+        bias[dst] = w->b_ih[l][src] + w->b_hh[l][src];
+      }
+    chk(upload_matrix(m, cat.data(), (size_t)4 * Hp, K, (size_t)4 * Hp, &d.w_cat[l]));
+    const void *bp = nullptr;
+    chk(upload(m, bias, &bp));
+    d.b_cat[l] = (const float *)bp;
+  }
+  const void *tmp = nullptr;
+  chk(upload_matrix(m, w->w_enc, w->Hj, w->D, round_up(w->Hj, 256), &d.w_enc));
+  chk(upload(m, std::vector<float>(w->b_enc, w->b_enc + w->Hj), &tmp)); d.b_enc = (const float *)tmp;
+  chk(upload_matrix(m, w->w_pred, w->Hj, Hp, w->Hj, &d.w_pred));
+  chk(upload(m, std::vector<float>(w->b_pred, w->b_pred + w->Hj), &tmp)); d.b_pred = (const float *)tmp;
+  chk(upload_matrix(m, w->w_out, (size_t)w->V + 1, w->Hj, d.Vpad, &d.w_out));
+  chk(upload(m, std::vector<float>(w->b_out, w->b_out + w->V + 1), &tmp)); d.b_out = (const float *)tmp;
+  {
+    std::vector<float> wb(w->Hj);
+    for (int k = 0; k < w->Hj; ++k) {
+      float x = w->w_out[(size_t)w->V * w->Hj + k];
+      wb[k] = m->dtype == WIND_BF16 ? host_bf16_to_f32(host_bf16(x)) : x;
+    }
+    chk(upload(m, wb, &tmp)); d.w_blank = (const float *)tmp;
+    double wmax = 0.0;
+    for (int v = 0; v < w->V; ++v) {
+      double s2 = 0.0;
+      for (int k = 0; k < w->Hj; ++k) { double x = w->w_out[(size_t)v * w->Hj + k]; s2 += x * x; }
+      wmax = s2 > wmax ? s2 : wmax;
+    }
+    m->wnorm_max = std::sqrt(wmax);
+    set_tau(m);
+  }
+  if (rc == WIND_OK) {
+    hipError_t e = hipHostMalloc((void **)&m->h_flag, 64, hipHostMallocDefault);
+    if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
+  }
+  if (rc == WIND_OK) {
+    hipError_t e = hipFuncSetAttribute((const void *)joint_mfma_kernel<JointCfg>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)enc_proj_mfma_kernel<EncCfg>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, EncCfg::SMEM_BYTES);
+    if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
+  }
+  if (rc != WIND_OK) {
+    std::string keep = g_err;
+    wind_free(m);
+    g_err = keep;
+    return rc;
+  }
+  *out = m;
+  return WIND_OK;
+}
+
+int wind_free(wind_model *m) {
+  if (!m) return WIND_OK;
+  (void)hipDeviceSynchronize();
+  if (m->graph_exec) (void)hipGraphExecDestroy(m->graph_exec);
+  if (m->graph) (void)hipGraphDestroy(m->graph);
+  if (m->cap_stream) (void)hipStreamDestroy(m->cap_stream);
+  for (void *p : m->allocs) (void)hipFree(p);
+  if (m->ws) (void)hipFree(m->ws);
+  if (m->h_flag) (void)hipHostFree(m->h_flag);
+  for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
+  delete m;
+  return WIND_OK;
+}
+
+int wind_greedy_decode(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, int W,
+                       int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
+                       int32_t *out_counts, int cap, void *stream) {
+  return decode(m, enc_out, lengths, B, T, W, max_symbols_per_step, out_tokens, out_frames, out_counts, cap, stream);
+}
+
+int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T,
+                           int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
+                           int32_t *out_counts, int cap, void *stream) {
+  return decode(m, enc_out, lengths, B, T, 1, max_symbols_per_step, out_tokens, out_frames, out_counts, cap, stream);
+}
+
+int wind_get_stats(wind_model *m, wind_stats *out) {
+  if (!m || !out) return fail(WIND_ERR_ARG, "null argument");
+  if (!m->have_stats) return fail(WIND_ERR_ARG, "no decode call yet");
+  *out = m->last_stats;
+  return WIND_OK;
+}
+
+int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches) {
+  if (!m || !ms || !launches) return fail(WIND_ERR_ARG, "null argument");
+  for (int k = 0; k < WIND_NUM_KERNELS; ++k) { ms[k] = m->prof_ms[k]; launches[k] = m->prof_n[k]; }
+  return WIND_OK;
+}
+
+int wind_set_option(wind_model *m, const char *key, int64_t value) {
+  if (!m || !key) return fail(WIND_ERR_ARG, "null argument");
+  if (!std::strcmp(key, "graph")) { m->opt_graph = value != 0; return WIND_OK; }
+  if (!std::strcmp(key, "profile")) {
+    m->opt_profile = value != 0;
+    for (int k = 0; k < WIND_NUM_KERNELS; ++k) { m->prof_ms[k] = 0.0; m->prof_n[k] = 0; }
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "unroll")) {
+    if (value < 2 || value > 256 || (value & 1)) return fail(WIND_ERR_ARG, "unroll must be even, 2..256");
+    m->opt_unroll = (int)value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "recheck_kappa_milli")) {
+    if (value < 0) return fail(WIND_ERR_ARG, "kappa must be >= 0");
+    m->kappa = (double)value / 1000.0;
+    set_tau(m);
+    m->graph_valid = false;
+    return WIND_OK;
+  }
+  return fail(WIND_ERR_ARG, std::string("unknown option ") + key);
+}
+
+int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, int b, int t0, int n,
+                            const int32_t *prefix, int prefix_len, int exact, float *logits, void *stream) {
+  if (!m || !enc_out || !logits) return fail(WIND_ERR_ARG, "null argument");
+  if (B < 1 || T < 1 || b < 0 || b >= B || t0 < 0 || n < 1 || t0 + n > T || n > WIND_MAX_WINDOW)
+    return fail(WIND_ERR_ARG, "window out of range");
+  if (prefix_len < 0 || (prefix_len > 0 && !prefix)) return fail(WIND_ERR_ARG, "bad prefix");
+  for (int i = 0; i < prefix_len; ++i)
+    if (prefix[i] < 0 || prefix[i] >= m->dev.V) return fail(WIND_ERR_ARG, "prefix label out of range");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_workspace(m, B, T, WIND_MAX_WINDOW);
+  if (rc) return rc;
+  CallDev &c = m->call;
+  // a device array of full lengths, so that every frame is projected
+  std::vector<int> full(B, T);
+  int *d_len = nullptr, *d_scr = nullptr;
+  HIP_TRY(hipMalloc((void **)&d_len, sizeof(int) * B));
+  HIP_TRY(hipMalloc((void **)&d_scr, sizeof(int) * (size_t)(3 * B + 2)));
+  HIP_TRY(hipMemcpyAsync(d_len, full.data(), sizeof(int) * B, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  c.B = B; c.T = T; c.W = WIND_MAX_WINDOW; c.S = 1; c.cap = 1;
+  c.enc = enc_out; c.lengths = d_len;
+  c.out_tokens = d_scr; c.out_frames = d_scr + B; c.out_counts = d_scr + 2 * B;
+  m->graph_valid = false;
+  rc = enqueue_prologue(m, s);  // start-token step on every utterance, all frames projected
+  for (int i = 0; i < prefix_len && rc == WIND_OK; ++i) {
+    // feed prefix[i] to utterance b only
+    const int one = 1, tok = prefix[i];
+    HIP_TRY(hipMemcpyAsync(c.n_emit, &one, sizeof(int), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c.emit_idx, &b, sizeof(int), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c.emit_tok + b, &tok, sizeof(int), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    rc = enqueue_pred_step(m, s, false);
+  }
+  if (rc == WIND_OK) {
+    const ModelDev &d = m->dev;
+    const float *pb = c.p + (size_t)b * d.Hj;
+    if (m->dtype == WIND_F32) {
+      joint_exact_kernel<float><<<n, 256, (size_t)d.Hj * 4, s>>>(d, c, 0, 0, b, t0, n, pb, 0, logits, nullptr);
+    } else if (exact) {
+      joint_exact_kernel<bf16_t><<<n, 256, (size_t)d.Hj * 4, s>>>(d, c, 0, 0, b, t0, n, pb, 0, logits, nullptr);
+    } else {
+      // hidden vectors rounded to bf16 into the window buffer, then the MFMA tile core with stores
+      joint_exact_kernel<bf16_t><<<n, 256, (size_t)d.Hj * 4, s>>>(d, c, 0, 0, b, t0, n, pb, 1, nullptr, c.z);
+      dim3 grid(1, (unsigned)((d.V + 1 + JointCfg::BN - 1) / JointCfg::BN));
+      joint_mfma_store_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, c.z, n, logits);
+    }
+    rc = check_launch("debug joint");
+  }
+  hipError_t e = hipStreamSynchronize(s);
+  (void)hipFree(d_len);
+  (void)hipFree(d_scr);
+  if (rc == WIND_OK && e != hipSuccess) return fail(WIND_ERR_HIP, std::string("debug sync: ") + hipGetErrorString(e));
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,650 @@
+// Device kernels of the WIND greedy decoder (gfx950).  See include/wind.h for the model.
+//
+// One loop iteration (Method, Algorithm 2, all active utterances at once):
+//   build_z        window gather: z[r,j,:] = relu(e[b, t_b + j, :] + p[b,:]) in bf16, plus the
+//                  blank logit of every row in fp32
+//   joint_mfma     label logits of every window row on bf16 MFMA; per row and per column part
+//                  the two largest (logit, column) keys are kept, nothing else is stored
+//   decide         per utterance: row argmax from the keys, near-ties re-decided with fp32 dot
+//                  products, first non-blank row by wavefront ballot, pointer / hypothesis update,
+//                  and (last workgroup) compaction of the active and emitting lists
+//   lstm_layer xL  one prediction-network step for the utterances that emitted
+//   pred_proj      p = W_pred h + b_pred for those utterances
+// fp32 models replace build_z + joint_mfma by joint_exact (fp32 FMA, argmax taken directly).
+#pragma once
+#include "wind_mfma.h"
+
+namespace wind {
+
+constexpr int kMaxLayers = 4;
+constexpr int kMaxWindow = 64;
+constexpr int kStatJump0 = 8;  // index of jump_hist[0] in the device counter array
+constexpr int kNumStats = kStatJump0 + kMaxWindow + 1;
+enum { ST_ITER = 0, ST_WINDOWS, ST_ROWS, ST_USEFUL, ST_LABELS, ST_FORCED, ST_RECHECK, ST_OVERFLOW };
+
+// Weights on the device.  WT-typed matrices are bf16 (bf16 models) or fp32 (fp32 models).
+struct ModelDev {
+  int D, E, Hp, L, Hj, V;
+  int Vpad;                     // rows of w_out (>= V+1, zero filled past V)
+  const void *emb;              // [V+1, E]
+  const void *w_cat[kMaxLayers];  // [4Hp, in_l + Hp]; row 4*j+g = gate g (i,f,g,o) of unit j; [w_ih | w_hh]
+  const float *b_cat[kMaxLayers]; // [4Hp] same row order, b_ih + b_hh
+  const void *w_enc;            // [Hj_pad, D]
+  const float *b_enc;           // [Hj]
+  const void *w_pred;           // [Hj, Hp]
+  const float *b_pred;          // [Hj]
+  const void *w_out;            // [Vpad, Hj]; row V = blank
+  const float *b_out;           // [V+1]
+  const float *w_blank;         // [Hj] fp32 copy of row V
+  float tau_scale;              // near-tie band = tau_scale * |z|_2 (+ key truncation)
+};
+
+// One decode call: caller buffers, sizes, and the library's state arrays.
+struct CallDev {
+  int B, T, W, S, cap;
+  const float *enc;             // [B,T,D]
+  const int *lengths;           // [B] as given
+  int *out_tokens, *out_frames, *out_counts;
+  float *e;                     // [B*T, Hj]
+  int *len;                     // [B] clamped to [0,T]
+  int *t, *sym, *count;         // [B]
+  int *flag;                    // [B] bit0 still active, bit1 emitted and still active
+  int *emit_tok;                // [B]
+  int *active_idx;              // [2][B] ping-pong by iteration parity
+  int *n_active;                // [2]
+  int *emit_idx;                // [B]
+  int *n_emit;                  // [1]
+  unsigned *ticket;             // [1]
+  float *h, *c, *hn;            // [L][B][Hp]
+  float *p;                     // [B][Hj]
+  bf16_t *z;                    // [Mpad][Hj]
+  float *blank_logit;           // [Mpad]
+  float *znorm;                 // [Mpad]
+  int2 *parts;                  // [Mpad][nparts]
+  int nparts;
+  int part_width;              // label columns per part (the joint tile's wave width)
+  int *row_label;               // [Mpad] (fp32 models)
+  unsigned long long *stats;    // [kNumStats]
+};
+
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kNumStats; i += 256) c.stats[i] = 0ull;
+  const size_t nstate = (size_t)m.L * c.B * m.Hp;
+  for (size_t i = tid; i < nstate; i += 256) { c.h[i] = 0.f; c.c[i] = 0.f; c.hn[i] = 0.f; }
+  for (int b = tid; b < c.B; b += 256) {
+    int len = c.lengths[b];
+    len = len < 0 ? 0 : (len > c.T ? c.T : len);
+    c.len[b] = len;
+    c.t[b] = 0; c.sym[b] = 0; c.count[b] = 0; c.out_counts[b] = 0;
+    c.flag[b] = len > 0 ? 1 : 0;
+    c.emit_tok[b] = m.V;       // start token
+    c.emit_idx[b] = b;         // the first prediction-network step runs on every utterance
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int na = 0;
+    for (int b = 0; b < c.B; ++b)
+      if (c.len[b] > 0) c.active_idx[na++] = b;
+    c.n_active[0] = na;
+    c.n_active[1] = 0;
+    *c.n_emit = c.B;
+    *c.ticket = 0u;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// e[b,t,:] = W_enc enc_out[b,t,:] + b_enc for t < len[b]: bf16 MFMA, fp32 accumulate, fp32 out.
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void enc_proj_mfma_kernel(ModelDev m, CallDev c, int tiles_per_utt) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+  const int b = blockIdx.x / tiles_per_utt, t0 = (blockIdx.x % tiles_per_utt) * Cfg::BM;
+  const int len = c.len[b];
+  if (t0 >= len) return;
+  const int n0 = blockIdx.y * Cfg::BN, D = m.D;
+  const float *base = c.enc + (size_t)b * c.T * D;
+  auto aload = [&](int row, int k) -> u32x4 {
+    int t = t0 + row;
+    t = t < len ? t : len - 1;
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(base + (size_t)t * D + k);
+    const f32x4 x0 = src[0], x1 = src[1];
+    u32x4 o;
+    o.x = pack_bf16x2(x0.x, x0.y); o.y = pack_bf16x2(x0.z, x0.w);
+    o.z = pack_bf16x2(x1.x, x1.y); o.w = pack_bf16x2(x1.z, x1.w);
+    return o;
+  };
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_enc) + (size_t)n0 * D, D, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int col = n0 + wn * Cfg::WN + ni * 32 + (lane & 31);
+    if (col >= m.Hj) continue;
+    const float bias = m.b_enc[col];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = t0 + wm * Cfg::WM + acc_row(mi, r, lane);
+        if (t < len) c.e[((size_t)b * c.T + t) * m.Hj + col] = acc[mi][ni][r] + bias;
+      }
+  }
+}
+
+// fp32 models: out[row, j] = bias[j] + sum_k w[j,k] x[row,k] for the valid frames of each utterance.
+__global__ __launch_bounds__(256) void enc_proj_f32_kernel(ModelDev m, CallDev c) {
+  extern __shared__ float xs[];
+  const int b = blockIdx.y, t = blockIdx.x;
+  if (t >= c.len[b]) return;
+  const float *x = c.enc + ((size_t)b * c.T + t) * m.D;
+  for (int k = threadIdx.x; k < m.D; k += 256) xs[k] = x[k];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float *w = reinterpret_cast<const float *>(m.w_enc);
+  for (int j = wave; j < m.Hj; j += 4) {
+    float a = 0.f;
+    for (int k = lane; k < m.D; k += 64) a = fmaf(w[(size_t)j * m.D + k], xs[k], a);
+    a = wave_sum(a);
+    if (lane == 0) c.e[((size_t)b * c.T + t) * m.Hj + j] = a + m.b_enc[j];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Window gather (Algorithm 2, joiner(enc[t:t+n], dec[-1]), first half): one wave per window row.
+__global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int parity) {
+  const int na = c.n_active[parity];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= na * c.W) return;
+  const int a = row / c.W, j = row - a * c.W;
+  const int b = c.active_idx[parity * c.B + a];
+  const int tt = c.t[b] + j;
+  const bool valid = tt < c.len[b];
+  const int Hj = m.Hj;
+  const float *er = c.e + ((size_t)b * c.T + (valid ? tt : 0)) * Hj;
+  const float *pr = c.p + (size_t)b * Hj;
+  bf16_t *zr = c.z + (size_t)row * Hj;
+  float dot = 0.f, nrm = 0.f;
+  for (int k = lane * 4; k < Hj; k += 256) {
+    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (valid) {
+      const float4 ev = *reinterpret_cast<const float4 *>(er + k);
+      const float4 pv = *reinterpret_cast<const float4 *>(pr + k);
+      x.x = fmaxf(ev.x + pv.x, 0.f); x.y = fmaxf(ev.y + pv.y, 0.f);
+      x.z = fmaxf(ev.z + pv.z, 0.f); x.w = fmaxf(ev.w + pv.w, 0.f);
+    }
+    const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
+    dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot);
+    dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
+    nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm);
+    nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+    *reinterpret_cast<uint2 *>(zr + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+  }
+  dot = wave_sum(dot);
+  nrm = wave_sum(nrm);
+  if (lane == 0) {
+    c.blank_logit[row] = dot + m.b_out[m.V];
+    c.znorm[row] = sqrtf(nrm);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Output contraction of the joiner on bf16 MFMA, with the row argmax folded into the epilogue:
+// the tile's logits never leave registers; each wave reduces its WM x WN block to two keys per row.
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void joint_mfma_kernel(ModelDev m, CallDev c, int parity) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+  const int n_rows = c.n_active[parity] * c.W;
+  const int row0 = blockIdx.x * Cfg::BM;
+  if (row0 >= n_rows) return;
+  const int n0 = blockIdx.y * Cfg::BN, Hj = m.Hj;
+  const bf16_t *zt = c.z + (size_t)row0 * Hj;
+  auto aload = [&](int row, int k) -> u32x4 {
+    return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k);
+  };
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj, smem, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+  constexpr int NS = Cfg::MI * 16;
+  int k1[NS], k2[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) { k1[s] = kKeyNone; k2[s] = kKeyNone; }
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int cip = ni * 32 + (lane & 31);
+    const int col = n0 + wn * Cfg::WN + cip;
+    const bool ok = col < m.V;
+    const float bias = ok ? m.b_out[col] : 0.f;
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = ok ? make_key(acc[mi][ni][r] + bias, cip) : kKeyNone;
+        push_top2(k1[mi * 16 + r], k2[mi * 16 + r], key);
+      }
+  }
+  constexpr int SPL = rowtop2_slots_per_lane<NS>();
+  int o1[SPL], o2[SPL];
+  RowTop2<NS, 16>::run(k1, k2, lane, o1, o2);
+  const int s0 = rowtop2_first_slot<NS>(lane);
+  const int part = blockIdx.y * Cfg::WAVES_N + wn;
+#pragma unroll
+  for (int i = 0; i < SPL; ++i) {
+    const int s = s0 + i;
+    const int row = row0 + wm * Cfg::WM + acc_row(s >> 4, s & 15, lane);
+    c.parts[(size_t)row * c.nparts + part] = make_int2(o1[i], o2[i]);
+  }
+}
+
+// Debug: the same tile core with the logits stored, bias added (columns 0..V, blank included).
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void joint_mfma_store_kernel(ModelDev m, const bf16_t *z, int n_rows,
+                                                                  float *logits) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+  const int row0 = blockIdx.x * Cfg::BM, n0 = blockIdx.y * Cfg::BN, Hj = m.Hj;
+  const bf16_t *zt = z + (size_t)row0 * Hj;
+  auto aload = [&](int row, int k) -> u32x4 {
+    return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k);
+  };
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int col = n0 + wn * Cfg::WN + ni * 32 + (lane & 31);
+    if (col > m.V) continue;
+    const float bias = m.b_out[col];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = row0 + wm * Cfg::WM + acc_row(mi, r, lane);
+        if (row < n_rows) logits[(size_t)row * (m.V + 1) + col] = acc[mi][ni][r] + bias;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Joiner rows in fp32 FMA with the argmax taken directly (ties to the lowest id).  One workgroup
+// per window row.  Used by fp32 models in the loop, and by the debug entry point for any model.
+//   rows_from_state = 1: row r = (active utterance r / W, window offset r % W)
+//   rows_from_state = 0: row r = frame t0 + r of utterance b0 (debug), p taken from p_dbg
+template <class WT>
+__global__ __launch_bounds__(256) void joint_exact_kernel(ModelDev m, CallDev c, int parity, int rows_from_state,
+                                                          int b0, int t0, int n_dbg, const float *p_dbg,
+                                                          int round_z, float *logits_out, bf16_t *z_out) {
+  extern __shared__ float zs[];
+  __shared__ float s_val[4];
+  __shared__ int s_idx[4];
+  const int row = blockIdx.x;
+  int b, tt;
+  bool valid;
+  const float *pr;
+  if (rows_from_state) {
+    const int na = c.n_active[parity];
+    if (row >= na * c.W) return;
+    const int a = row / c.W, j = row - a * c.W;
+    b = c.active_idx[parity * c.B + a];
+    tt = c.t[b] + j;
+    valid = tt < c.len[b];
+    pr = c.p + (size_t)b * m.Hj;
+  } else {
+    if (row >= n_dbg) return;
+    b = b0; tt = t0 + row; valid = true; pr = p_dbg;
+  }
+  const float *er = c.e + ((size_t)b * c.T + (valid ? tt : 0)) * m.Hj;
+  for (int k = threadIdx.x; k < m.Hj; k += 256) {
+    float x = valid ? fmaxf(er[k] + pr[k], 0.f) : 0.f;
+    if (round_z) x = bf16_bits_to_f32(f32_to_bf16_bits(x));
+    zs[k] = x;
+    if (z_out) z_out[(size_t)row * m.Hj + k] = (bf16_t)f32_to_bf16_bits(x);
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const WT *w = reinterpret_cast<const WT *>(m.w_out);
+  float best = -INFINITY;
+  int best_i = 0x7FFFFFFF;
+  for (int v = wave; v <= m.V; v += 4) {
+    float a = 0.f;
+    for (int k = lane; k < m.Hj; k += 64) a = fmaf(ldw(w, (size_t)v * m.Hj + k), zs[k], a);
+    a = wave_sum(a) + m.b_out[v];
+    if (logits_out && lane == 0) logits_out[(size_t)row * (m.V + 1) + v] = a;
+    if (a > best) { best = a; best_i = v; }   // v ascends within a wave: first maximum kept
+  }
+  if (lane == 0) { s_val[wave] = best; s_idx[wave] = best_i; }
+  __syncthreads();
+  if (threadIdx.x == 0 && rows_from_state) {
+    float bv = s_val[0];
+    int bi = s_idx[0];
+    for (int w2 = 1; w2 < 4; ++w2)
+      if (s_val[w2] > bv || (s_val[w2] == bv && s_idx[w2] < bi)) { bv = s_val[w2]; bi = s_idx[w2]; }
+    c.row_label[row] = valid ? bi : m.V;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 logit of label `col` for the hidden vector a wave holds (zr[i] = z[2*lane + 128*i .. +1]).
+template <class WT, int NZ>
+__device__ __forceinline__ float exact_logit(const ModelDev &m, const float2 (&zr)[NZ], int col, int lane) {
+  const WT *w = reinterpret_cast<const WT *>(m.w_out) + (size_t)col * m.Hj;
+  float a = 0.f;
+#pragma unroll
+  for (int i = 0; i < NZ; ++i) {
+    const int k = 2 * lane + 128 * i;
+    if (k < m.Hj) {
+      const float2 wv = ldw2(w, k);
+      a = fmaf(wv.x, zr[i].x, a);
+      a = fmaf(wv.y, zr[i].y, a);
+    }
+  }
+  return wave_sum(a) + m.b_out[col];
+}
+
+constexpr int kDecideMaxHj = 2048;  // exact_logit keeps Hj/128 float2 per lane
+
+// Row argmax, first non-blank by ballot, pointer and hypothesis update, list compaction.
+// One workgroup per active utterance, one wave per window row (rows round-robin past 16 waves).
+template <class WT>
+__global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int parity, int exact_mode) {
+  __shared__ int s_label[kMaxWindow];
+  __shared__ int s_is_last;
+  const int na = c.n_active[parity];
+  const int a = blockIdx.x;
+  if (na == 0 && a == 0 && threadIdx.x == 0) c.n_active[parity ^ 1] = 0;  // keep both slots at "done"
+  if (a >= na) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  const int b = c.active_idx[parity * c.B + a];
+  const int t = c.t[b], len = c.len[b], V = m.V;
+  const int n = min(c.W, len - t);
+  int n_recheck = 0;
+
+  for (int j = wave; j < c.W; j += nwaves) {
+    int label = V;
+    if (j < n) {
+      const int row = a * c.W + j;
+      if (exact_mode) {
+        label = c.row_label[row];
+      } else {
+        // keys of this row: lane i holds part i (and i + 64, ... for wide vocabularies)
+        int k1 = kKeyNone, k2 = kKeyNone;
+        for (int pi = lane; pi < c.nparts; pi += 64) {
+          const int2 kk = c.parts[(size_t)row * c.nparts + pi];
+          // remember which part a key came from: parts are revisited below by index
+          merge_top2(k1, k2, kk.x, kk.y);
+        }
+        const int kbest = wave_max_i32(k1);
+        const float vbest = key_val(kbest);
+        const float vblank = c.blank_logit[row];
+        const float top = fmaxf(vbest, vblank);
+        const float tau = m.tau_scale * c.znorm[row] + 6.2e-5f * fabsf(top);
+        const float thresh = top - tau;
+        if (vbest < thresh) {
+          label = V;                                   // blank clear of every label
+        } else {
+          // how many label keys are inside the band?
+          int cnt = 0;
+          for (int pi = lane; pi < c.nparts; pi += 64) {
+            const int2 kk = c.parts[(size_t)row * c.nparts + pi];
+            cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
+          }
+#pragma unroll
+          for (int msk = 32; msk >= 1; msk >>= 1) cnt += __shfl_xor(cnt, msk, kWave);
+          if (cnt == 1 && vblank < thresh) {
+            // a single label clear of blank and of every other label: find its part
+            int col = -1;
+            for (int pi = lane; pi < c.nparts; pi += 64)
+              if (c.parts[(size_t)row * c.nparts + pi].x == kbest) col = pi * c.part_width + key_col(kbest);
+            label = wave_max_i32(col);
+          } else {
+            // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
+            ++n_recheck;
+            constexpr int NZ = kDecideMaxHj / 128;
+            float2 zr[NZ];
+            const float *er = c.e + ((size_t)b * c.T + t + j) * m.Hj;
+            const float *pr = c.p + (size_t)b * m.Hj;
+#pragma unroll
+            for (int i = 0; i < NZ; ++i) {
+              const int k = 2 * lane + 128 * i;
+              zr[i] = make_float2(0.f, 0.f);
+              if (k < m.Hj) {
+                const float2 ev = *reinterpret_cast<const float2 *>(er + k);
+                const float2 pv = *reinterpret_cast<const float2 *>(pr + k);
+                zr[i] = make_float2(fmaxf(ev.x + pv.x, 0.f), fmaxf(ev.y + pv.y, 0.f));
+              }
+            }
+            float bestv = vblank;     // blank has the highest id: it wins only if strictly larger
+            int besti = V;
+            for (int p0 = 0; p0 < c.nparts; p0 += 64) {
+              const int pi = p0 + lane;
+              int2 kk = make_int2(kKeyNone, kKeyNone);
+              if (pi < c.nparts) kk = c.parts[(size_t)row * c.nparts + pi];
+#pragma unroll
+              for (int which = 0; which < 2; ++which) {
+                const int key = which ? kk.y : kk.x;
+                unsigned long long mask = __ballot(pi < c.nparts && key_val(key) >= thresh);
+                while (mask) {
+                  const int src = __ffsll((long long)mask) - 1;
+                  mask &= mask - 1;
+                  const int skey = __shfl(key, src, kWave);
+                  const int col = (p0 + src) * c.part_width + key_col(skey);
+                  const float v = exact_logit<WT, NZ>(m, zr, col, lane);
+                  if (v > bestv || (v == bestv && col < besti)) { bestv = v; besti = col; }
+                }
+              }
+            }
+            label = besti;
+          }
+        }
+      }
+    }
+    if (lane == 0) s_label[j] = label;
+  }
+  __syncthreads();
+
+  if (wave == 0) {
+    const bool nb = lane < n && s_label[lane] != V;
+    const unsigned long long mask = __ballot(nb);
+    if (lane == 0) {
+      const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
+      int tn = t, sym = c.sym[b], cnt = c.count[b], jump, emitted = 0, forced = 0, tok = V;
+      if (i < 0) {
+        tn += n; sym = 0; jump = n;
+      } else {
+        tok = s_label[i];
+        if (cnt < c.cap) {
+          c.out_tokens[(size_t)b * c.cap + cnt] = tok;
+          c.out_frames[(size_t)b * c.cap + cnt] = t + i;
+          ++cnt;
+        } else {
+          atomicAdd(&c.stats[ST_OVERFLOW], 1ull);
+        }
+        tn += i;
+        sym = (i == 0) ? sym + 1 : 1;
+        jump = i;
+        emitted = 1;
+        if (sym >= c.S) { tn += 1; sym = 0; jump += 1; forced = 1; }
+      }
+      c.t[b] = tn; c.sym[b] = sym; c.count[b] = cnt; c.out_counts[b] = cnt;
+      const int active = tn < len;
+      c.flag[b] = active | ((emitted & active) << 1);
+      c.emit_tok[b] = tok;
+      atomicAdd(&c.stats[ST_WINDOWS], 1ull);
+      atomicAdd(&c.stats[ST_ROWS], (unsigned long long)n);
+      atomicAdd(&c.stats[ST_USEFUL], (unsigned long long)(i < 0 ? n : i + 1));
+      if (emitted) atomicAdd(&c.stats[ST_LABELS], 1ull);
+      if (forced) atomicAdd(&c.stats[ST_FORCED], 1ull);
+      atomicAdd(&c.stats[kStatJump0 + jump], 1ull);
+    }
+  }
+  if (lane == 0 && n_recheck) atomicAdd(&c.stats[ST_RECHECK], (unsigned long long)n_recheck);
+
+  // The last workgroup to finish rebuilds the lists for the prediction network and the next iteration.
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    const unsigned tk = atomicAdd(c.ticket, 1u);
+    s_is_last = (tk == (unsigned)(na - 1));
+  }
+  __syncthreads();
+  if (!s_is_last) return;
+  __threadfence();
+  if (wave == 0) {
+    const int *src = c.active_idx + parity * c.B;
+    int *dst = c.active_idx + (parity ^ 1) * c.B;
+    int n_act = 0, n_em = 0;
+    for (int base = 0; base < na; base += 64) {
+      const int idx = base + lane;
+      int ub = 0, f = 0;
+      if (idx < na) {
+        ub = src[idx];
+        f = __atomic_load_n(&c.flag[ub], __ATOMIC_RELAXED);
+      }
+      const unsigned long long ma = __ballot(f & 1), me = __ballot((f >> 1) & 1);
+      const unsigned long long below = (1ull << lane) - 1ull;
+      if (f & 1) dst[n_act + __popcll(ma & below)] = ub;
+      if (f & 2) c.emit_idx[n_em + __popcll(me & below)] = ub;
+      n_act += __popcll(ma);
+      n_em += __popcll(me);
+    }
+    if (lane == 0) {
+      c.n_active[parity ^ 1] = n_act;
+      *c.n_emit = n_em;
+      *c.ticket = 0u;
+      atomicAdd(&c.stats[ST_ITER], 1ull);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// One LSTM cell for the utterances on the emit list.  One wave per hidden unit: its four gate rows
+// are dotted with [x ; h_prev] of R utterances at a time (weights are read once per group).
+//   x = embedding of the emitted label (layer 0) or the new h of the layer below.
+template <class WT, int R>
+__global__ __launch_bounds__(256) void lstm_layer_kernel(ModelDev m, CallDev c, int layer) {
+  const int n_emit = *c.n_emit;
+  if (n_emit == 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int unit = blockIdx.x * 4 + wave;
+  if (unit >= m.Hp) return;
+  const int Hp = m.Hp, in = layer == 0 ? m.E : Hp, K = in + Hp;
+  const WT *w = reinterpret_cast<const WT *>(m.w_cat[layer]) + (size_t)unit * 4 * K;
+  const float *bias = m.b_cat[layer] + unit * 4;
+  const size_t lofs = (size_t)layer * c.B * Hp;
+  constexpr int VEC = sizeof(WT) == 2 ? 2 : 1;
+
+  for (int r0 = 0; r0 < n_emit; r0 += R) {
+    float acc[4][R];
+    int ub[R];
+    const WT *xe[R];     // layer 0 input: embedding row of the emitted label
+    const float *xh[R];  // deeper layers: new hidden vector of the layer below
+    const float *hp[R];  // this layer's previous hidden vector
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      ub[r] = c.emit_idx[min(r0 + r, n_emit - 1)];
+      xe[r] = reinterpret_cast<const WT *>(m.emb) + (size_t)c.emit_tok[ub[r]] * m.E;
+      xh[r] = c.hn + (layer == 0 ? 0 : lofs - (size_t)c.B * Hp) + (size_t)ub[r] * Hp;
+      hp[r] = c.h + lofs + (size_t)ub[r] * Hp;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g][r] = 0.f;
+    }
+    for (int k = lane * VEC; k < K; k += 64 * VEC) {
+      float wv[4][VEC];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        if constexpr (VEC == 2) {
+          const float2 t2 = ldw2(w, (size_t)g * K + k);
+          wv[g][0] = t2.x; wv[g][1] = t2.y;
+        } else {
+          wv[g][0] = ldw(w, (size_t)g * K + k);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float xv[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) {
+          const int kk = k + q;
+          if (kk < in) xv[q] = layer == 0 ? ldw(xe[r], kk) : xh[r][kk];
+          else xv[q] = hp[r][kk - in];
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int q = 0; q < VEC; ++q) acc[g][r] = fmaf(wv[g][q], xv[q], acc[g][r]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g][r] = wave_sum(acc[g][r]);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (lane == r && r0 + r < n_emit) {
+        const size_t si = lofs + (size_t)ub[r] * Hp + unit;
+        const float ig = 1.f / (1.f + expf(-(acc[0][r] + bias[0])));
+        const float fg = 1.f / (1.f + expf(-(acc[1][r] + bias[1])));
+        const float gg = tanhf(acc[2][r] + bias[2]);
+        const float og = 1.f / (1.f + expf(-(acc[3][r] + bias[3])));
+        const float cn = fg * c.c[si] + ig * gg;
+        c.c[si] = cn;
+        c.hn[si] = og * tanhf(cn);
+      }
+    }
+  }
+}
+
+// p[b,:] = W_pred h_top + b_pred for the utterances on the emit list; also commits the new hidden
+// vectors (hn -> h) now that every layer has read the old ones.
+template <class WT, int R>
+__global__ __launch_bounds__(256) void pred_proj_kernel(ModelDev m, CallDev c) {
+  const int n_emit = *c.n_emit;
+  if (n_emit == 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int Hp = m.Hp;
+  // commit: grid-strided copy over [L][n_emit][Hp]
+  {
+    const size_t total = (size_t)m.L * n_emit * Hp;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+      const int k = (int)(i % Hp);
+      const size_t q = i / Hp;
+      const int r = (int)(q % n_emit), l = (int)(q / n_emit);
+      const size_t si = ((size_t)l * c.B + c.emit_idx[r]) * Hp + k;
+      c.h[si] = c.hn[si];
+    }
+  }
+  const int j = blockIdx.x * 4 + wave;
+  if (j >= m.Hj) return;
+  const WT *w = reinterpret_cast<const WT *>(m.w_pred) + (size_t)j * Hp;
+  const float *htop = c.hn + (size_t)(m.L - 1) * c.B * Hp;
+  constexpr int VEC = sizeof(WT) == 2 ? 2 : 1;
+  for (int r0 = 0; r0 < n_emit; r0 += R) {
+    float acc[R];
+    int ub[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) { ub[r] = c.emit_idx[min(r0 + r, n_emit - 1)]; acc[r] = 0.f; }
+    for (int k = lane * VEC; k < Hp; k += 64 * VEC) {
+      float wv[VEC];
+      if constexpr (VEC == 2) { const float2 t2 = ldw2(w, k); wv[0] = t2.x; wv[1] = t2.y; }
+      else wv[0] = ldw(w, k);
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[r] = fmaf(wv[q], htop[(size_t)ub[r] * Hp + k + q], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      acc[r] = wave_sum(acc[r]);
+      if (lane == r && r0 + r < n_emit) c.p[(size_t)ub[r] * m.Hj + j] = acc[r] + m.b_pred[j];
+    }
+  }
+}
+
+}  // namespace wind

@@ -1,0 +1,91 @@
+// Small device helpers shared by the WIND kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace wind {
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // 16 bytes = 8 bf16
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kWave = 64;
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN-ish, never used for a decision)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// load one weight element as fp32
+__device__ __forceinline__ float ldw(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ldw(const bf16_t *p, size_t i) { return bf16_bits_to_f32(p[i]); }
+
+// two consecutive weights (i even) as fp32
+__device__ __forceinline__ float2 ldw2(const float *p, size_t i) {
+  return *reinterpret_cast<const float2 *>(p + i);
+}
+__device__ __forceinline__ float2 ldw2(const bf16_t *p, size_t i) {
+  uint32_t u = *reinterpret_cast<const uint32_t *>(p + i);
+  return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xFFFF0000u));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_max_i32(int v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    int o = __shfl_xor(v, m, kWave);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+// Order-preserving map between fp32 and int32 (signed compare), used to carry (logit, column) in
+// one sortable word.
+__device__ __forceinline__ int f32_to_key(float v) {
+  int k = __float_as_int(v);
+  return k ^ ((k >> 31) & 0x7FFFFFFF);
+}
+__device__ __forceinline__ float key_to_f32(int k) {
+  return __int_as_float(k ^ ((k >> 31) & 0x7FFFFFFF));
+}
+
+constexpr int kKeyColBits = 7;                      // a key carries a column 0..127 within its part
+constexpr int kKeyColMask = (1 << kKeyColBits) - 1;
+constexpr int kKeyNone = INT32_MIN;                 // below every real key
+
+// The low bits of the value give way to (127 - column): of two equal values the lower column wins.
+__device__ __forceinline__ int make_key(float v, int col_in_part) {
+  return (f32_to_key(v) & ~kKeyColMask) | (kKeyColMask - col_in_part);
+}
+__device__ __forceinline__ int key_col(int k) { return kKeyColMask - (k & kKeyColMask); }
+__device__ __forceinline__ float key_val(int k) { return key_to_f32(k & ~kKeyColMask); }
+
+// top-2 of the union of two sorted pairs (a1 >= a2), (b1 >= b2)
+__device__ __forceinline__ void merge_top2(int &a1, int &a2, int b1, int b2) {
+  int hi = a1 > b1 ? a1 : b1;
+  int lo = a1 > b1 ? b1 : a1;
+  int s = a2 > b2 ? a2 : b2;
+  a1 = hi;
+  a2 = lo > s ? lo : s;
+}
+__device__ __forceinline__ void push_top2(int &a1, int &a2, int k) {
+  const int lo = k < a1 ? k : a1;
+  a1 = k > a1 ? k : a1;
+  a2 = lo > a2 ? lo : a2;
+}
+
+}  // namespace wind

@@ -1,0 +1,276 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Tokens and frames must be identical except at oracle near-ties (top-2 gap < 1e-3), which
+are followed with a forced choice (see parity.py).  Logits: 2e-2 absolute for bf16 models, 1e-4 for
+fp32 (the tolerances the benchmark spec states)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import wind_inputs as wi
+from parity import compare_batch, wind_counts_from_trace
+
+pytestmark = pytest.mark.gpu
+
+TOL_GAP = 1e-3
+TOL_BF16 = 2e-2
+TOL_F32 = 1e-4
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def to_dev(torch, enc, lens):
+    return torch.from_numpy(enc).cuda(), torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+
+
+def load(cfg, weights=None):
+    from paper_2505_13765_amd import WindModel
+
+    w = weights if weights is not None else wi.make_weights(cfg)
+    return WindModel.from_config(cfg, w), oracle.Oracle.from_config(cfg, w), w
+
+
+def check_outputs(cfg, lens, toks, frs):
+    for b in range(len(lens)):
+        assert len(toks[b]) == len(frs[b])
+        if len(toks[b]):
+            assert (np.diff(frs[b]) >= 0).all() and frs[b].max() < lens[b] and frs[b].min() >= 0
+            assert toks[b].min() >= 0 and toks[b].max() < cfg.V
+            assert np.bincount(frs[b]).max() <= cfg.S
+
+
+# ---------------------------------------------------------------------------------------------
+def test_tiny_workload_every_window(torch_cuda):
+    cfg = wi.CONFIGS["tiny"]
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    ref_tok, ref_fr, _ = o.greedy(enc[0], cfg.S)
+    assert len(ref_tok) > 0
+    for W in (None, 1, 2, 3, 4, 5, 8, 16, 63, 64):
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        excl = compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP)
+        assert excl == 0, f"fp32 model should not need exclusions (W={W})"
+        if W is not None:
+            st = m.stats()
+            n, hist = wind_counts_from_trace(ref_fr.tolist(), int(lens[0]), W, cfg.S)
+            assert st.iterations == n and st.windows == n
+            assert list(st.jump_hist[: W + 1]) == hist.tolist()
+            assert st.labels == len(ref_tok) and st.rows >= st.useful_rows >= n
+    m.close()
+
+
+def test_f32_ragged_batch_with_poisoned_padding(torch_cuda):
+    base = wi.CONFIGS["tiny"]
+    cfg = base.replace(name="tiny_ragged", B=7, len_lo=0, len_hi=45, D=72, E=40, Hp=48, Hj=56, V=37, L=2, S=3)
+    w = wi.make_weights(cfg, blank_bias=2.5, pred_gain=4.0)
+    m, o, _ = load(cfg, w)
+    enc, lens = wi.make_batch(cfg)
+    lens[2] = 0
+    lens[5] = 1
+    for b in range(cfg.B):
+        enc[b, lens[b]:] = np.nan
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    for W in (1, 4, 7):
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        check_outputs(cfg, lens, toks, frs)
+        assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) == 0
+        assert len(toks[2]) == 0
+    toks_s, frs_s = m.decode(d_enc, d_len, None, cfg.S)
+    assert all(a.tolist() == b.tolist() for a, b in zip(toks, toks_s))
+    m.close()
+
+
+# bf16 models at sizes the oracle finishes in seconds: several row tiles, ragged lengths.
+SMALL = [
+    ("greedy_b1", 1, 150, 150, (1, 2, 4, 8, 16)),
+    ("batch32", 9, 30, 140, (8,)),
+    ("largevocab_b128", 10, 30, 90, (4, 8, 16)),
+    ("lowblank_b256", 37, 20, 90, (16,)),
+]
+
+
+@pytest.mark.parametrize("name,B,lo,hi,windows", SMALL)
+def test_bf16_scaled_workloads(torch_cuda, name, B, lo, hi, windows):
+    cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    toks_ref, frs_ref, _ = o.greedy_batch(enc, lens, cfg.S)
+    first = None
+    for W in windows:
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        check_outputs(cfg, lens, toks, frs)
+        excl = compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP)
+        st = m.stats()
+        print(f"{name} W={W}: labels {st.labels} iterations {st.iterations} rows {st.rows} "
+              f"rechecks {st.rechecks} excluded {excl}")
+        assert st.labels == sum(len(t) for t in toks)
+        assert excl <= 2
+        if excl == 0:
+            tot_iter = 0
+            for b in range(B):
+                n, _ = wind_counts_from_trace(frs_ref[b].tolist(), int(lens[b]), W, cfg.S)
+                tot_iter += n
+            assert st.windows == tot_iter
+        # the result does not depend on the window size
+        if first is None:
+            first = (toks, frs)
+        else:
+            assert all(a.tolist() == b.tolist() for a, b in zip(first[0], toks))
+            assert all(a.tolist() == b.tolist() for a, b in zip(first[1], frs))
+    toks_s, frs_s = m.decode(d_enc, d_len, None, cfg.S)
+    assert compare_batch(o, enc, lens, cfg.S, toks_s, frs_s, tol=TOL_GAP) <= 2
+    m.close()
+
+
+# ---------------------------------------------------------------------------------------------
+def test_joint_logits_against_oracle(torch_cuda):
+    for name, n, t0 in (("greedy_b1", 16, 3), ("largevocab_b128", 5, 0)):
+        cfg = wi.scaled(wi.CONFIGS[name], 2, 24, 24)
+        m, o, _ = load(cfg)
+        enc, lens = wi.make_batch(cfg)
+        d_enc, _ = to_dev(torch_cuda, enc, lens)
+        prefix = [5, 17, 3]
+        g = o.decoder_from_scratch(prefix)
+        ref = np.stack([o.joiner(enc[1, t0 + j], g) for j in range(n)])
+        mfma = m.debug_joint_logits(d_enc, 1, t0, n, prefix, exact=False)
+        exact = m.debug_joint_logits(d_enc, 1, t0, n, prefix, exact=True)
+        assert mfma.shape == ref.shape == (n, cfg.V + 1)
+        if name == "greedy_b1":
+            assert mfma.size == 16400          # Analysis, "Memory Footprint": 16 x 1025 floats
+        err_mfma = np.abs(mfma - ref).max()
+        err_exact = np.abs(exact - ref).max()
+        print(f"{name}: max |mfma - oracle| = {err_mfma:.3e}, max |fp32 - oracle| = {err_exact:.3e}")
+        assert err_mfma < TOL_BF16
+        assert err_exact < TOL_F32
+        assert err_mfma > 1e-6               # the bf16 pass really rounds the hidden vector
+        m.close()
+    cfg = wi.CONFIGS["tiny"]
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, _ = to_dev(torch_cuda, enc, lens)
+    g = o.decoder_from_scratch([1, 2])
+    ref = np.stack([o.joiner(enc[0, 10 + j], g) for j in range(4)])
+    got = m.debug_joint_logits(d_enc, 0, 10, 4, [1, 2], exact=False)
+    assert np.abs(got - ref).max() < TOL_F32
+    m.close()
+
+
+def test_edge_cases(torch_cuda):
+    torch = torch_cuda
+    cfg = wi.scaled(wi.CONFIGS["batch32"], 3, 5, 20)
+    enc, lens = wi.make_batch(cfg)
+    # always blank / never blank
+    for bias, expect in ((1e4, "none"), (-1e4, "all")):
+        w = wi.make_weights(cfg)
+        w["b_out"][cfg.V] = bias
+        m, o, _ = load(cfg, w)
+        d_enc, d_len = to_dev(torch, enc, lens)
+        for W in (1, 8):
+            toks, frs = m.decode(d_enc, d_len, W, 3)
+            for b in range(cfg.B):
+                if expect == "none":
+                    assert len(toks[b]) == 0
+                else:
+                    assert frs[b].tolist() == [t for t in range(lens[b]) for _ in range(3)]
+            st = m.stats()
+            if expect == "none":
+                assert st.windows == sum(-(-int(l) // W) for l in lens) and st.forced_advances == 0
+            else:
+                assert st.forced_advances == int(lens.sum()) and st.labels == 3 * int(lens.sum())
+            assert compare_batch(o, enc, lens, 3, toks, frs) <= 1
+        m.close()
+    m, o, _ = load(cfg)
+    # all lengths zero
+    d_enc, d_len = to_dev(torch, enc, np.zeros(cfg.B, np.int32))
+    toks, frs = m.decode(d_enc, d_len, 4, cfg.S)
+    assert all(len(t) == 0 for t in toks) and m.stats().iterations == 0
+    # capacity overflow is reported and counts are clamped
+    from paper_2505_13765_amd.binding import WIND_ERR_OVERFLOW
+
+    w = wi.make_weights(cfg)
+    w["b_out"][cfg.V] = -1e4
+    m2, _, _ = load(cfg, w)
+    d_enc, d_len = to_dev(torch, enc, lens)
+    cap = 4
+    tok = torch.full((cfg.B, cap), -7, dtype=torch.int32, device="cuda")
+    frm = torch.full((cfg.B, cap), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    rc = m2.greedy_decode(d_enc, d_len, 4, 2, tok, frm, cnt, allow_overflow=True)
+    assert rc == WIND_ERR_OVERFLOW
+    assert cnt.cpu().tolist() == [cap] * cfg.B and (frm.cpu().numpy() == [[0, 0, 1, 1]] * cfg.B).all()
+    # argument errors leave a message and do not touch the GPU state
+    from paper_2505_13765_amd import WindError
+
+    for W in (0, 65):
+        with pytest.raises(WindError):
+            m2.greedy_decode(d_enc, d_len, W, 2, tok, frm, cnt)
+    with pytest.raises(WindError):
+        m2.greedy_decode(d_enc, d_len, 4, 0, tok, frm, cnt)
+    m.close()
+    m2.close()
+
+
+def test_determinism_and_graph_off(torch_cuda):
+    cfg = wi.scaled(wi.CONFIGS["batch32"], 12, 40, 100)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    a = m.decode(d_enc, d_len, 8, cfg.S)
+    b = m.decode(d_enc, d_len, 8, cfg.S)
+    m.set_option("graph", 0)
+    c = m.decode(d_enc, d_len, 8, cfg.S)
+    m.set_option("graph", 1)
+    m.set_option("unroll", 4)
+    d = m.decode(d_enc, d_len, 8, cfg.S)
+    for other in (b, c, d):
+        assert all(x.tolist() == y.tolist() for x, y in zip(a[0], other[0]))
+        assert all(x.tolist() == y.tolist() for x, y in zip(a[1], other[1]))
+    m.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# Full-size workloads in the launch configuration bench.py times.  The oracle checks a sample of
+# utterances one by one; properties that hold at any size are checked on all of them.
+FULL = [("greedy_b1", [0]), ("batch32", "sample3"), ("largevocab_b128", "sample3"), ("lowblank_b256", "sample3")]
+
+
+@pytest.mark.parametrize("name,which", FULL)
+def test_full_size_workloads(torch_cuda, name, which):
+    cfg = wi.CONFIGS[name]
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    if which == "sample3":
+        order = np.argsort(lens)
+        which = [int(order[0]), int(order[len(order) // 3]), int(order[-1])]
+        if name == "largevocab_b128":
+            which = [int(order[0]), int(order[1]), int(order[len(order) // 4])]
+    ref = None
+    for W in cfg.windows:
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        check_outputs(cfg, lens, toks, frs)
+        st = m.stats()
+        assert st.labels == sum(len(t) for t in toks)
+        assert st.rows >= st.useful_rows and st.windows >= st.iterations
+        print(f"{name} W={W}: frames {int(lens.sum())} labels {st.labels} iterations {st.iterations} "
+              f"rows {st.rows} useful {st.useful_rows} rechecks {st.rechecks}")
+        if ref is None:
+            ref = (toks, frs)
+            excl = compare_batch(o, enc, lens, cfg.S, toks, frs, utterances=which, tol=TOL_GAP,
+                                 threads=min(16, os.cpu_count() or 1))
+            print(f"{name}: utterances {which} checked against the oracle, excluded near-ties: {excl}")
+            assert excl <= 3
+        else:
+            same = sum(a.tolist() == b.tolist() and c.tolist() == d.tolist()
+                       for a, b, c, d in zip(ref[0], toks, ref[1], frs))
+            assert same == cfg.B, f"W={W}: {cfg.B - same} utterances differ from W={cfg.windows[0]}"
+    m.close()

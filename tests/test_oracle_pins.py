@@ -13,6 +13,7 @@ import pytest
 
 import oracle
 import wind_inputs as wi
+from parity import compare_utterance, wind_counts_from_trace
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -262,34 +263,6 @@ def test_argmax_ties_go_to_lowest_id():
 # ---------------------------------------------------------------------------------------------
 # Invariants of the output, and the closed form that ties Algorithm 2's window count and jump
 # sizes to the sequential trace.
-def wind_counts_from_trace(frames, T, W, S):
-    """Walk the emission frames of the sequential result and count the windows Algorithm 2 needs:
-    from a pointer t, a label at frame f costs (f - t) // W all-blank windows and one emitting
-    window; the trailing blank frames cost ceil(r / W)."""
-    hist = np.zeros(W + 1, np.int64)
-    t, sym, n = 0, 0, 0
-    prev = None
-    for f in frames:
-        full, rem = divmod(f - t, W)
-        hist[W] += full
-        n += full + 1
-        sym = sym + 1 if (full == 0 and rem == 0 and prev == f) else 1
-        t = f
-        jump = rem
-        if sym == S:
-            t, sym, jump = t + 1, 0, jump + 1
-        hist[jump] += 1
-        prev = f
-    r = T - t
-    full, rem = divmod(r, W)
-    hist[W] += full
-    n += full
-    if rem:
-        hist[rem] += 1
-        n += 1
-    return n, hist
-
-
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_invariants_and_window_count_closed_form(seed):
     T = 60
