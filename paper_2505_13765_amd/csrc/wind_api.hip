@@ -32,6 +32,8 @@ int fail(int code, const std::string &msg) {
 
 using JointCfg = TileCfg<128, 128, 64, 64>;
 using EncCfg = TileCfg<128, 128, 64, 64>;
+using PredCfg = TileCfg<64, 64, 32, 32>;   // 32 utterances (hi and lo rows) x 64 columns
+constexpr int kPredMfmaMinBatch = 16;      // below this the FMA prediction network is used
 constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height
 
 uint16_t host_bf16(float x) {
@@ -71,6 +73,7 @@ struct wind_model {
   GraphKey graph_key{};
   bool graph_valid = false;
   int opt_graph = 1, opt_unroll = 16;
+  int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
@@ -217,16 +220,25 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
   const int lstm_blocks = (d.Hp + 3) / 4, proj_blocks = (d.Hj + 3) / 4;
+  const bool mfma = m->dtype == WIND_BF16 && c.B >= m->opt_pred_mfma_min_batch;
+  constexpr int R = PredCfg::BM / 2;
+  const unsigned mtiles = (unsigned)((c.B + R - 1) / R);
   {
     ProfScope ps(m, s, WIND_K_LSTM, capturing);
     for (int l = 0; l < d.L; ++l) {
-      if (m->dtype == WIND_BF16) lstm_layer_kernel<bf16_t, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
+      if (mfma)
+        lstm_layer_mfma_kernel<PredCfg><<<dim3(mtiles, (unsigned)(4 * d.Hp / PredCfg::BN)), PredCfg::NT,
+                                          PredCfg::SMEM_BYTES, s>>>(d, c, l);
+      else if (m->dtype == WIND_BF16) lstm_layer_kernel<bf16_t, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
       else lstm_layer_kernel<float, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
     }
   }
   {
     ProfScope ps(m, s, WIND_K_PRED_PROJ, capturing);
-    if (m->dtype == WIND_BF16) pred_proj_kernel<bf16_t, 4><<<proj_blocks, 256, 0, s>>>(d, c);
+    if (mfma)
+      pred_proj_mfma_kernel<PredCfg><<<dim3(mtiles, (unsigned)(d.Hj / PredCfg::BN)), PredCfg::NT,
+                                       PredCfg::SMEM_BYTES, s>>>(d, c);
+    else if (m->dtype == WIND_BF16) pred_proj_kernel<bf16_t, 4><<<proj_blocks, 256, 0, s>>>(d, c);
     else pred_proj_kernel<float, 4><<<proj_blocks, 256, 0, s>>>(d, c);
   }
   return check_launch("prediction step");
@@ -430,6 +442,20 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     const void *bp = nullptr;
     chk(upload(m, bias, &bp));
     d.b_cat[l] = (const float *)bp;
+    if (m->dtype == WIND_BF16) {
+      // MFMA layout: tile column n0 + g*UB + u = gate g of unit n0/4 + u
+      constexpr int UB = PredCfg::BN / 4;
+      std::vector<float> cat_t((size_t)4 * Hp * K), bias_t((size_t)4 * Hp);
+      for (int g = 0; g < 4; ++g)
+        for (int j = 0; j < Hp; ++j) {
+          const size_t src = (size_t)j * 4 + g, dst = (size_t)(j / UB) * PredCfg::BN + (size_t)g * UB + j % UB;
+          std::memcpy(&cat_t[dst * K], &cat[src * K], sizeof(float) * K);
+          bias_t[dst] = bias[src];
+        }
+      chk(upload_matrix(m, cat_t.data(), (size_t)4 * Hp, K, (size_t)4 * Hp, &d.w_cat_t[l]));
+      chk(upload(m, bias_t, &bp));
+      d.b_cat_t[l] = (const float *)bp;
+    }
   }
   const void *tmp = nullptr;
   chk(upload_matrix(m, w->w_enc, w->Hj, w->D, round_up(w->Hj, 256), &d.w_enc));
@@ -467,6 +493,12 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)enc_proj_mfma_kernel<EncCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, EncCfg::SMEM_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)lstm_layer_mfma_kernel<PredCfg>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, PredCfg::SMEM_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)pred_proj_mfma_kernel<PredCfg>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, PredCfg::SMEM_BYTES);
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
   }
   if (rc != WIND_OK) {
@@ -529,6 +561,11 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "unroll")) {
     if (value < 2 || value > 256 || (value & 1)) return fail(WIND_ERR_ARG, "unroll must be even, 2..256");
     m->opt_unroll = (int)value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "pred_mfma_min_batch")) {
+    m->opt_pred_mfma_min_batch = (int)value;
+    m->graph_valid = false;
     return WIND_OK;
   }
   if (!std::strcmp(key, "recheck_kappa_milli")) {

@@ -29,6 +29,8 @@ struct ModelDev {
   const void *emb;              // [V+1, E]
   const void *w_cat[kMaxLayers];  // [4Hp, in_l + Hp]; row 4*j+g = gate g (i,f,g,o) of unit j; [w_ih | w_hh]
   const float *b_cat[kMaxLayers]; // [4Hp] same row order, b_ih + b_hh
+  const void *w_cat_t[kMaxLayers]; // bf16 models: the same rows grouped for MFMA tiles, see lstm_layer_mfma_kernel
+  const float *b_cat_t[kMaxLayers];
   const void *w_enc;            // [Hj_pad, D]
   const float *b_enc;           // [Hj]
   const void *w_pred;           // [Hj, Hp]
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(Cfg::NT) void enc_proj_mfma_kernel(ModelDev m, Call
   if (t0 >= len) return;
   const int n0 = blockIdx.y * Cfg::BN, D = m.D;
   const float *base = c.enc + (size_t)b * c.T * D;
-  auto aload = [&](int row, int k) -> u32x4 {
+  auto aload = [&](int, int row, int k) -> u32x4 {
     int t = t0 + row;
     t = t < len ? t : len - 1;
     const f32x4 *src = reinterpret_cast<const f32x4 *>(base + (size_t)t * D + k);
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(Cfg::NT) void joint_mfma_kernel(ModelDev m, CallDev
   if (row0 >= n_rows) return;
   const int n0 = blockIdx.y * Cfg::BN, Hj = m.Hj;
   const bf16_t *zt = c.z + (size_t)row0 * Hj;
-  auto aload = [&](int row, int k) -> u32x4 {
+  auto aload = [&](int, int row, int k) -> u32x4 {
     return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k);
   };
   f32x16 acc[Cfg::MI][Cfg::NI];
@@ -250,7 +252,7 @@ __global__ __launch_bounds__(Cfg::NT) void joint_mfma_store_kernel(ModelDev m, c
   bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
   const int row0 = blockIdx.x * Cfg::BM, n0 = blockIdx.y * Cfg::BN, Hj = m.Hj;
   const bf16_t *zt = z + (size_t)row0 * Hj;
-  auto aload = [&](int row, int k) -> u32x4 {
+  auto aload = [&](int, int row, int k) -> u32x4 {
     return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k);
   };
   f32x16 acc[Cfg::MI][Cfg::NI];
@@ -644,6 +646,149 @@ __global__ __launch_bounds__(256) void pred_proj_kernel(ModelDev m, CallDev c) {
       acc[r] = wave_sum(acc[r]);
       if (lane == r && r0 + r < n_emit) c.p[(size_t)ub[r] * m.Hj + j] = acc[r] + m.b_pred[j];
     }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Prediction network on bf16 MFMA, for batches large enough to fill tiles.  The activations are
+// fp32; each is split into hi + lo bf16 (hi = RNE(x), lo = RNE(x - hi), relative error 2^-17, the
+// size of fp32 accumulation noise over these K), products with the bf16 weights are exact and the
+// accumulation is fp32.  The split costs rows, not K: a tile's first R rows hold the hi parts of R
+// utterances, the next R rows their lo parts, and the epilogue adds the two halves.
+__device__ __forceinline__ u32x4 split_pack(const f32x4 &a, const f32x4 &b, int part) {
+  float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  uint32_t o[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const uint32_t hi = f32_to_bf16_bits(x[q]);
+    const uint32_t lo = f32_to_bf16_bits(x[q] - bf16_bits_to_f32(hi));
+    o[q] = part ? lo : hi;
+  }
+  u32x4 r;
+  r.x = o[0] | (o[1] << 16); r.y = o[2] | (o[3] << 16); r.z = o[4] | (o[5] << 16); r.w = o[6] | (o[7] << 16);
+  return r;
+}
+
+// Gate columns of w_cat_t are grouped per tile: column n0 + g*UB + u is gate g of unit n0/4 + u
+// (UB = BN/4), so one tile holds all four gates of its UB units.
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void lstm_layer_mfma_kernel(ModelDev m, CallDev c, int layer) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+  constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
+  const int n_emit = *c.n_emit;
+  const int row0 = blockIdx.x * R;
+  if (row0 >= n_emit) return;
+  const int n0 = blockIdx.y * Cfg::BN;
+  const int Hp = m.Hp, in = layer == 0 ? m.E : Hp, K = in + Hp;
+  const size_t lofs = (size_t)layer * c.B * Hp;
+  const int tid = threadIdx.x;
+  const bf16_t *src_e[Cfg::A_PER_T];
+  const float *src_x[Cfg::A_PER_T], *src_h[Cfg::A_PER_T];
+  int part[Cfg::A_PER_T];
+#pragma unroll
+  for (int i = 0; i < Cfg::A_PER_T; ++i) {
+    const int row = (tid + i * Cfg::NT) >> 3;
+    part[i] = row >= R;
+    const int ub = c.emit_idx[min(row0 + row - part[i] * R, n_emit - 1)];
+    src_e[i] = reinterpret_cast<const bf16_t *>(m.emb) + (size_t)c.emit_tok[ub] * m.E;
+    src_x[i] = c.hn + (layer == 0 ? 0 : lofs - (size_t)c.B * Hp) + (size_t)ub * Hp;
+    src_h[i] = c.h + lofs + (size_t)ub * Hp;
+  }
+  auto aload = [&](int i, int, int k) -> u32x4 {
+    if (k < in && layer == 0) {               // embedding rows are bf16 already: lo part is zero
+      u32x4 raw = *reinterpret_cast<const u32x4 *>(src_e[i] + k);
+      u32x4 zero = {0u, 0u, 0u, 0u};
+      return part[i] ? zero : raw;
+    }
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(k < in ? src_x[i] + k : src_h[i] + (k - in));
+    return split_pack(src[0], src[1], part[i]);
+  };
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_cat_t[layer]) + (size_t)n0 * K, K, smem, acc);
+
+  float *tile = reinterpret_cast<float *>(smem_raw);
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
+  __syncthreads();
+  const float *bias = m.b_cat_t[layer] + n0;
+  for (int idx = tid; idx < R * UB; idx += Cfg::NT) {
+    const int r = idx / UB, u = idx - r * UB;
+    if (row0 + r >= n_emit) continue;
+    const int ub = c.emit_idx[row0 + r];
+    const float *hi = tile + r * TS + u, *lo = tile + (R + r) * TS + u;
+    const float gi = hi[0] + lo[0] + bias[u];
+    const float gf = hi[UB] + lo[UB] + bias[UB + u];
+    const float gg = hi[2 * UB] + lo[2 * UB] + bias[2 * UB + u];
+    const float go = hi[3 * UB] + lo[3 * UB] + bias[3 * UB + u];
+    const size_t si = lofs + (size_t)ub * Hp + (n0 >> 2) + u;
+    const float ig = 1.f / (1.f + expf(-gi)), fg = 1.f / (1.f + expf(-gf));
+    const float og = 1.f / (1.f + expf(-go));
+    const float cn = fg * c.c[si] + ig * tanhf(gg);
+    c.c[si] = cn;
+    c.hn[si] = og * tanhf(cn);
+  }
+}
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void pred_proj_mfma_kernel(ModelDev m, CallDev c) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+  constexpr int R = Cfg::BM / 2, TS = Cfg::BN + 4;
+  const int n_emit = *c.n_emit;
+  if (n_emit == 0) return;
+  const int Hp = m.Hp, tid = threadIdx.x;
+  {  // commit the new hidden vectors: every layer has read the old ones by now
+    const size_t total = (size_t)m.L * n_emit * Hp;
+    const size_t nthreads = (size_t)gridDim.x * gridDim.y * Cfg::NT;
+    for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * Cfg::NT + tid; i < total; i += nthreads) {
+      const int k = (int)(i % Hp);
+      const size_t q = i / Hp;
+      const int r = (int)(q % n_emit), l = (int)(q / n_emit);
+      const size_t si = ((size_t)l * c.B + c.emit_idx[r]) * Hp + k;
+      c.h[si] = c.hn[si];
+    }
+  }
+  const int row0 = blockIdx.x * R;
+  if (row0 >= n_emit) return;
+  const int n0 = blockIdx.y * Cfg::BN;
+  const float *htop = c.hn + (size_t)(m.L - 1) * c.B * Hp;
+  const float *src[Cfg::A_PER_T];
+  int part[Cfg::A_PER_T];
+#pragma unroll
+  for (int i = 0; i < Cfg::A_PER_T; ++i) {
+    const int row = (tid + i * Cfg::NT) >> 3;
+    part[i] = row >= R;
+    src[i] = htop + (size_t)c.emit_idx[min(row0 + row - part[i] * R, n_emit - 1)] * Hp;
+  }
+  auto aload = [&](int i, int, int k) -> u32x4 {
+    const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src[i] + k);
+    return split_pack(s4[0], s4[1], part[i]);
+  };
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)n0 * Hp, Hp, smem, acc);
+  float *tile = reinterpret_cast<float *>(smem_raw);
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
+  __syncthreads();
+  for (int idx = tid; idx < R * Cfg::BN; idx += Cfg::NT) {
+    const int r = idx / Cfg::BN, col = idx - r * Cfg::BN;
+    if (row0 + r >= n_emit || n0 + col >= m.Hj) continue;
+    c.p[(size_t)c.emit_idx[row0 + r] * m.Hj + n0 + col] = tile[r * TS + col] + tile[(R + r) * TS + col] + m.b_pred[n0 + col];
   }
 }
 

@@ -31,7 +31,8 @@ struct TileCfg {
   static_assert(WN <= 128, "a key carries 7 column bits");
 };
 
-// aload(row_in_tile, k) returns 8 consecutive bf16 of A's row as a u32x4.
+// aload(i, row_in_tile, k) returns 8 consecutive bf16 of A's row as a u32x4; i is the index of the
+// chunk among this thread's A_PER_T chunks (its row is the same at every K step).
 // Bw points at row n0 of B ([N, K] bf16, at least BN rows readable).  K % 64 == 0.
 template <class Cfg, class ALoad>
 __device__ __forceinline__ void tile_gload(const ALoad &aload, const bf16_t *__restrict__ Bw, int K, int kt,
@@ -39,7 +40,7 @@ __device__ __forceinline__ void tile_gload(const ALoad &aload, const bf16_t *__r
 #pragma unroll
   for (int i = 0; i < Cfg::A_PER_T; ++i) {
     const int c = tid + i * Cfg::NT;
-    ra[i] = aload(c >> 3, kt * 64 + (c & 7) * 8);
+    ra[i] = aload(i, c >> 3, kt * 64 + (c & 7) * 8);
   }
 #pragma unroll
   for (int i = 0; i < Cfg::B_PER_T; ++i) {

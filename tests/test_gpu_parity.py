@@ -131,6 +131,24 @@ def test_bf16_scaled_workloads(torch_cuda, name, B, lo, hi, windows):
     m.close()
 
 
+@pytest.mark.parametrize("name,B,lo,hi,W", [("batch32", 9, 30, 140, 8), ("largevocab_b128", 35, 20, 60, 4)])
+def test_prediction_network_on_mfma_tiles(torch_cuda, name, B, lo, hi, W):
+    """Both prediction-network implementations (fp32 FMA per hidden unit, hi/lo-split bf16 MFMA
+    tiles) against the oracle, on one and on two LSTM layers, with ragged emit lists."""
+    cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    res = []
+    for min_batch in (1, 10 ** 6):
+        m.set_option("pred_mfma_min_batch", min_batch)
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
+        res.append((toks, frs))
+    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[1][0]))
+    m.close()
+
+
 # ---------------------------------------------------------------------------------------------
 def test_joint_logits_against_oracle(torch_cuda):
     for name, n, t0 in (("greedy_b1", 16, 3), ("largevocab_b128", 5, 0)):
