@@ -157,6 +157,8 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "unroll"  loop iterations per graph launch (default 16, even)
  *   "profile" 1: time every kernel launch with events (see wind_get_kernel_times); implies no graph
  *   "recheck_kappa_milli"  width of the near-tie band of the bf16 pass, in thousandths
+ *   "joint_split_rows"  iterations with more window rows than this use the 256 x 256 joint tiles,
+ *             the others 128 x 128 tiles (default 1536)
  *   "pred_mfma_min_batch"  smallest B for which the prediction network runs on MFMA tiles
  *             (default 16; bf16 models only; below it one wave per hidden unit does fp32 FMA)
  */

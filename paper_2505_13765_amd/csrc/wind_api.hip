@@ -30,7 +30,10 @@ int fail(int code, const std::string &msg) {
       return fail(WIND_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));           \
   } while (0)
 
-using JointCfg = TileCfg<128, 128, 64, 64>;
+using JointCfg = TileCfg<128, 128, 64, 64>;            // debug store kernel
+using JointSmallCfg = DmaCfg<128, 128, 64, 64, 64, 2>;  // rows <= kJointSplitRows
+using JointBigCfg = Ring5Cfg<256, 64, 128>;             // rows > kJointSplitRows
+constexpr int kJointSplitRows = 1536;                   // measured crossover of the two joint kernels
 using EncCfg = TileCfg<128, 128, 64, 64>;
 using PredCfg = TileCfg<64, 64, 32, 32>;   // 32 utterances (hi and lo rows) x 64 columns
 constexpr int kPredMfmaMinBatch = 16;      // below this the FMA prediction network is used
@@ -74,6 +77,7 @@ struct wind_model {
   bool graph_valid = false;
   int opt_graph = 1, opt_unroll = 16;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
+  int opt_joint_split_rows = kJointSplitRows;
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
@@ -124,8 +128,9 @@ void set_tau(wind_model *m) {
 int ensure_workspace(wind_model *m, int B, int T, int W) {
   const ModelDev &d = m->dev;
   const size_t Mpad = round_up((size_t)B * W, kRowPad);
-  const int ntiles = (d.V + JointCfg::BN - 1) / JointCfg::BN;
-  const int nparts = ntiles * JointCfg::WAVES_N;
+  const int ntiles = (d.V + JointSmallCfg::BN - 1) / JointSmallCfg::BN;
+  const int nparts = ntiles * JointSmallCfg::WAVES_N;
+  const int nparts_big = ((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN) * JointBigCfg::WAVES_N;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
@@ -168,9 +173,12 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.p = (float *)(base + o_p);
   c.z = (bf16_t *)(base + o_z);
   c.blank_logit = (float *)(base + o_bl); c.znorm = (float *)(base + o_zn);
-  c.parts = (int2 *)(base + o_parts);
+  c.parts = (float2 *)(base + o_parts);
   c.nparts = nparts;
-  c.part_width = JointCfg::WN;
+  c.part_width = JointSmallCfg::WN;
+  c.nparts_big = nparts_big;
+  c.part_width_big = JointBigCfg::WN;
+  c.joint_split_rows = m->opt_joint_split_rows;
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
   return WIND_OK;
@@ -276,9 +284,17 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
     }
     {
       ProfScope ps(m, s, WIND_K_JOINT, capturing);
-      dim3 grid((unsigned)((max_rows + JointCfg::BM - 1) / JointCfg::BM),
-                (unsigned)((d.V + JointCfg::BN - 1) / JointCfg::BN));
-      joint_mfma_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, c, parity);
+      // two tile shapes; each kernel returns at once when the iteration's row count is the other's
+      const int small_rows = max_rows < c.joint_split_rows ? max_rows : c.joint_split_rows;
+      dim3 grid((unsigned)((small_rows + JointSmallCfg::BM - 1) / JointSmallCfg::BM),
+                (unsigned)((d.V + JointSmallCfg::BN - 1) / JointSmallCfg::BN));
+      if (small_rows > 0)
+        joint_dma_kernel<JointSmallCfg><<<grid, JointSmallCfg::NT, JointSmallCfg::SMEM_BYTES, s>>>(d, c, parity);
+      if (max_rows > c.joint_split_rows) {
+        dim3 gbig((unsigned)((max_rows + JointBigCfg::BM - 1) / JointBigCfg::BM),
+                  (unsigned)((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN));
+        joint_ring5_kernel<JointBigCfg><<<gbig, JointBigCfg::NT, JointBigCfg::SMEM_BYTES, s>>>(d, c, parity);
+      }
     }
     {
       ProfScope ps(m, s, WIND_K_DECIDE, capturing);
@@ -485,8 +501,11 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
   }
   if (rc == WIND_OK) {
-    hipError_t e = hipFuncSetAttribute((const void *)joint_mfma_kernel<JointCfg>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void *)joint_dma_kernel<JointSmallCfg>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, JointSmallCfg::SMEM_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)joint_ring5_kernel<JointBigCfg>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
@@ -561,6 +580,12 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "unroll")) {
     if (value < 2 || value > 256 || (value & 1)) return fail(WIND_ERR_ARG, "unroll must be even, 2..256");
     m->opt_unroll = (int)value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "joint_split_rows")) {
+    if (value < 0) return fail(WIND_ERR_ARG, "joint_split_rows must be >= 0");
+    m->opt_joint_split_rows = value > (1 << 30) ? (1 << 30) : (int)value;
+    m->graph_valid = false;
     return WIND_OK;
   }
   if (!std::strcmp(key, "pred_mfma_min_batch")) {

@@ -13,6 +13,7 @@
 // fp32 models replace build_z + joint_mfma by joint_exact (fp32 FMA, argmax taken directly).
 #pragma once
 #include "wind_mfma.h"
+#include "wind_mfma_dma.h"
 
 namespace wind {
 
@@ -62,9 +63,11 @@ struct CallDev {
   bf16_t *z;                    // [Mpad][Hj]
   float *blank_logit;           // [Mpad]
   float *znorm;                 // [Mpad]
-  int2 *parts;                  // [Mpad][nparts]
-  int nparts;
-  int part_width;              // label columns per part (the joint tile's wave width)
+  float2 *parts;                // [Mpad][nparts] two largest (logit, column) keys per row and part
+  int nparts;                   // parts per row and label columns per part, as written by the
+  int part_width;               //   small-tile joint kernel (rows <= joint_split_rows)
+  int nparts_big, part_width_big;  // the same for the 256 x 256 kernel (rows > joint_split_rows)
+  int joint_split_rows;         // which of the two joint kernels handles an iteration
   int *row_label;               // [Mpad] (fp32 models)
   unsigned long long *stats;    // [kNumStats]
 };
@@ -194,6 +197,68 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
 }
 
 // ---------------------------------------------------------------------------------------------
+// Which (row tile, column tile) a workgroup of the joint kernel owns.  Workgroups are handed to the
+// 8 XCDs round-robin by linear id, and each XCD has its own 4 MB L2.  Column tiles are therefore
+// dealt by (linear id mod 8): an XCD always works on the same slice of W_out, which then stays in
+// its L2 across row tiles and across loop iterations, and only the window rows stream in.
+__device__ __forceinline__ void joint_tile_of_block(int &mt, int &nt) {
+  const int MT = gridDim.x, NT = gridDim.y;
+  if (NT % 8 != 0) { mt = blockIdx.x; nt = blockIdx.y; return; }
+  const int lin = blockIdx.y * MT + blockIdx.x;
+  const int xcd = lin & 7, idx = lin >> 3, npx = NT >> 3;
+  nt = xcd + 8 * (idx % npx);
+  mt = idx / npx;
+}
+
+// Accumulator start value for the joint kernels: the output bias of the lane's column, or a large
+// negative number for columns past the vocabulary, so that the epilogue needs neither an add nor a
+// mask.
+template <class Cfg>
+__device__ __forceinline__ void joint_init_acc(const ModelDev &m, f32x16 (&acc)[Cfg::MI][Cfg::NI], int n0) {
+  const int lane = threadIdx.x & 63, wn = (threadIdx.x >> 6) % Cfg::WAVES_N;
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int col = n0 + wn * Cfg::WN + ni * 32 + (lane & 31);
+    const float bias = col < m.V ? m.b_out[col < m.V ? col : 0] : kKeyNone;
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = bias;
+  }
+}
+
+// Epilogue of the joint kernels: (logit, column) keys, per-row top-2 over the wave's WN columns,
+// one float2 per (row, part) to memory.  The logits never leave registers.
+template <class Cfg>
+__device__ __forceinline__ void joint_keys_epilogue(const CallDev &c, f32x16 (&acc)[Cfg::MI][Cfg::NI],
+                                                    int row0, int nt, int nparts) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+  constexpr int NS = Cfg::MI * 16;
+  float k1[NS], k2[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) { k1[s] = kKeyNone; k2[s] = kKeyNone; }
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int cip = ni * 32 + (lane & 31);
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) push_top2(k1[mi * 16 + r], k2[mi * 16 + r], make_key(acc[mi][ni][r], cip));
+  }
+  constexpr int SPL = rowtop2_slots_per_lane<NS>();
+  float o1[SPL], o2[SPL];
+  RowTop2<NS, 16>::run(k1, k2, lane, o1, o2);
+  const int s0 = rowtop2_first_slot<NS>(lane);
+  const int part = nt * Cfg::WAVES_N + wn;
+#pragma unroll
+  for (int i = 0; i < SPL; ++i) {
+    const int s = s0 + i;
+    const int row = row0 + wm * Cfg::WM + acc_row(s >> 4, s & 15, lane);
+    c.parts[(size_t)row * nparts + part] = make_float2(o1[i], o2[i]);
+  }
+}
+
 // Output contraction of the joiner on bf16 MFMA, with the row argmax folded into the epilogue:
 // the tile's logits never leave registers; each wave reduces its WM x WN block to two keys per row.
 template <class Cfg>
@@ -201,47 +266,59 @@ __global__ __launch_bounds__(Cfg::NT) void joint_mfma_kernel(ModelDev m, CallDev
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
   const int n_rows = c.n_active[parity] * c.W;
-  const int row0 = blockIdx.x * Cfg::BM;
+  int mt, nt;
+  joint_tile_of_block(mt, nt);
+  const int row0 = mt * Cfg::BM;
   if (row0 >= n_rows) return;
-  const int n0 = blockIdx.y * Cfg::BN, Hj = m.Hj;
+  const int n0 = nt * Cfg::BN, Hj = m.Hj;
   const bf16_t *zt = c.z + (size_t)row0 * Hj;
   auto aload = [&](int, int row, int k) -> u32x4 {
     return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k);
   };
   f32x16 acc[Cfg::MI][Cfg::NI];
   gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj, smem, acc);
+  f32x16 bias[Cfg::MI][Cfg::NI];
+  joint_init_acc<Cfg>(m, bias, n0);
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni) acc[mi][ni] += bias[mi][ni];
+  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);
+}
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
-  constexpr int NS = Cfg::MI * 16;
-  int k1[NS], k2[NS];
-#pragma unroll
-  for (int s = 0; s < NS; ++s) { k1[s] = kKeyNone; k2[s] = kKeyNone; }
-#pragma unroll
-  for (int ni = 0; ni < Cfg::NI; ++ni) {
-    const int cip = ni * 32 + (lane & 31);
-    const int col = n0 + wn * Cfg::WN + cip;
-    const bool ok = col < m.V;
-    const float bias = ok ? m.b_out[col] : 0.f;
-#pragma unroll
-    for (int mi = 0; mi < Cfg::MI; ++mi)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = ok ? make_key(acc[mi][ni][r] + bias, cip) : kKeyNone;
-        push_top2(k1[mi * 16 + r], k2[mi * 16 + r], key);
-      }
-  }
-  constexpr int SPL = rowtop2_slots_per_lane<NS>();
-  int o1[SPL], o2[SPL];
-  RowTop2<NS, 16>::run(k1, k2, lane, o1, o2);
-  const int s0 = rowtop2_first_slot<NS>(lane);
-  const int part = blockIdx.y * Cfg::WAVES_N + wn;
-#pragma unroll
-  for (int i = 0; i < SPL; ++i) {
-    const int s = s0 + i;
-    const int row = row0 + wm * Cfg::WM + acc_row(s >> 4, s & 15, lane);
-    c.parts[(size_t)row * c.nparts + part] = make_int2(o1[i], o2[i]);
-  }
+// The same contraction with the direct-to-LDS, multi-stage tile core (both operands are dense
+// bf16 rows in memory: the window rows z and W_out).
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void joint_dma_kernel(ModelDev m, CallDev c, int parity) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int n_rows = c.n_active[parity] * c.W;
+  int mt, nt;
+  joint_tile_of_block(mt, nt);
+  const int row0 = mt * Cfg::BM;
+  if (row0 >= n_rows || n_rows > c.joint_split_rows) return;
+  const int n0 = nt * Cfg::BN, Hj = m.Hj;
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  joint_init_acc<Cfg>(m, acc, n0);
+  gemm_mainloop_dma<Cfg>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
+                         smem_raw, acc);
+  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);
+}
+
+// 256 x 256 tiles on the five-slot ring (see gemm_mainloop_ring5).
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void joint_ring5_kernel(ModelDev m, CallDev c, int parity) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int n_rows = c.n_active[parity] * c.W;
+  int mt, nt;
+  joint_tile_of_block(mt, nt);
+  const int row0 = mt * Cfg::BM;
+  if (row0 >= n_rows || n_rows <= c.joint_split_rows) return;
+  const int n0 = nt * Cfg::BN, Hj = m.Hj;
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  joint_init_acc<Cfg>(m, acc, n0);
+  gemm_mainloop_ring5<Cfg>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
+                           smem_raw, acc);
+  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts_big);
 }
 
 // Debug: the same tile core with the logits stored, bias added (columns 0..V, blank included).
@@ -367,6 +444,8 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   const int t = c.t[b], len = c.len[b], V = m.V;
   const int n = min(c.W, len - t);
   int n_recheck = 0;
+  const bool big = na * c.W > c.joint_split_rows;   // which joint kernel wrote the keys
+  const int nparts = big ? c.nparts_big : c.nparts, part_width = big ? c.part_width_big : c.part_width;
 
   for (int j = wave; j < c.W; j += nwaves) {
     int label = V;
@@ -376,13 +455,9 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
         label = c.row_label[row];
       } else {
         // keys of this row: lane i holds part i (and i + 64, ... for wide vocabularies)
-        int k1 = kKeyNone, k2 = kKeyNone;
-        for (int pi = lane; pi < c.nparts; pi += 64) {
-          const int2 kk = c.parts[(size_t)row * c.nparts + pi];
-          // remember which part a key came from: parts are revisited below by index
-          merge_top2(k1, k2, kk.x, kk.y);
-        }
-        const int kbest = wave_max_i32(k1);
+        float k1 = kKeyNone;
+        for (int pi = lane; pi < nparts; pi += 64) k1 = fmaxf(k1, c.parts[(size_t)row * nparts + pi].x);
+        const float kbest = wave_max_f32(k1);
         const float vbest = key_val(kbest);
         const float vblank = c.blank_logit[row];
         const float top = fmaxf(vbest, vblank);
@@ -393,8 +468,8 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
         } else {
           // how many label keys are inside the band?
           int cnt = 0;
-          for (int pi = lane; pi < c.nparts; pi += 64) {
-            const int2 kk = c.parts[(size_t)row * c.nparts + pi];
+          for (int pi = lane; pi < nparts; pi += 64) {
+            const float2 kk = c.parts[(size_t)row * nparts + pi];
             cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
           }
 #pragma unroll
@@ -402,8 +477,8 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
           if (cnt == 1 && vblank < thresh) {
             // a single label clear of blank and of every other label: find its part
             int col = -1;
-            for (int pi = lane; pi < c.nparts; pi += 64)
-              if (c.parts[(size_t)row * c.nparts + pi].x == kbest) col = pi * c.part_width + key_col(kbest);
+            for (int pi = lane; pi < nparts; pi += 64)
+              if (c.parts[(size_t)row * nparts + pi].x == kbest) col = pi * part_width + key_col(kbest);
             label = wave_max_i32(col);
           } else {
             // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
@@ -424,19 +499,19 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
             }
             float bestv = vblank;     // blank has the highest id: it wins only if strictly larger
             int besti = V;
-            for (int p0 = 0; p0 < c.nparts; p0 += 64) {
+            for (int p0 = 0; p0 < nparts; p0 += 64) {
               const int pi = p0 + lane;
-              int2 kk = make_int2(kKeyNone, kKeyNone);
-              if (pi < c.nparts) kk = c.parts[(size_t)row * c.nparts + pi];
+              float2 kk = make_float2(kKeyNone, kKeyNone);
+              if (pi < nparts) kk = c.parts[(size_t)row * nparts + pi];
 #pragma unroll
               for (int which = 0; which < 2; ++which) {
-                const int key = which ? kk.y : kk.x;
-                unsigned long long mask = __ballot(pi < c.nparts && key_val(key) >= thresh);
+                const float key = which ? kk.y : kk.x;
+                unsigned long long mask = __ballot(pi < nparts && key_val(key) >= thresh);
                 while (mask) {
                   const int src = __ffsll((long long)mask) - 1;
                   mask &= mask - 1;
-                  const int skey = __shfl(key, src, kWave);
-                  const int col = (p0 + src) * c.part_width + key_col(skey);
+                  const float skey = __shfl(key, src, kWave);
+                  const int col = (p0 + src) * part_width + key_col(skey);
                   const float v = exact_logit<WT, NZ>(m, zr, col, lane);
                   if (v > bestv || (v == bestv && col < besti)) { bestv = v; besti = col; }
                 }

@@ -119,29 +119,29 @@ __device__ __forceinline__ int acc_row(int mi, int r, int lane) {
 
 // ---------------------------------------------------------------------------------------------
 // Row-wise top-2 across the 32 lanes that share lane/32 (they hold the 32 columns of a block).
-// Every lane enters with N sorted key pairs, one per accumulator row slot; each step hands half of
+// Every lane enters with N sorted (logit, column) key pairs, one per accumulator row slot; each step hands half of
 // the slots to the partner lane and merges the partner's half, so after log2 steps every lane owns
 // N/32 slots (at least one), fully reduced.  MASK walks 16, 8, 4, 2, 1.
 template <int N, int MASK>
 struct RowTop2 {
   template <int NO>
-  static __device__ __forceinline__ void run(int (&k1)[N], int (&k2)[N], int lane, int (&o1)[NO], int (&o2)[NO]) {
+  static __device__ __forceinline__ void run(float (&k1)[N], float (&k2)[N], int lane, float (&o1)[NO], float (&o2)[NO]) {
     if constexpr (MASK == 0) {
       static_assert(N == NO, "slots per lane");
 #pragma unroll
       for (int i = 0; i < N; ++i) { o1[i] = k1[i]; o2[i] = k2[i]; }
     } else if constexpr (N == 1) {
-      int r1 = __shfl_xor(k1[0], MASK, kWave), r2 = __shfl_xor(k2[0], MASK, kWave);
+      float r1 = __shfl_xor(k1[0], MASK, kWave), r2 = __shfl_xor(k2[0], MASK, kWave);
       merge_top2(k1[0], k2[0], r1, r2);
       RowTop2<1, MASK / 2>::run(k1, k2, lane, o1, o2);
     } else {
       const bool up = (lane & MASK) != 0;
-      int n1[N / 2], n2[N / 2];
+      float n1[N / 2], n2[N / 2];
 #pragma unroll
       for (int i = 0; i < N / 2; ++i) {
-        int keep1 = up ? k1[i + N / 2] : k1[i], keep2 = up ? k2[i + N / 2] : k2[i];
-        int send1 = up ? k1[i] : k1[i + N / 2], send2 = up ? k2[i] : k2[i + N / 2];
-        int r1 = __shfl_xor(send1, MASK, kWave), r2 = __shfl_xor(send2, MASK, kWave);
+        float keep1 = up ? k1[i + N / 2] : k1[i], keep2 = up ? k2[i + N / 2] : k2[i];
+        float send1 = up ? k1[i] : k1[i + N / 2], send2 = up ? k2[i] : k2[i + N / 2];
+        float r1 = __shfl_xor(send1, MASK, kWave), r2 = __shfl_xor(send2, MASK, kWave);
         merge_top2(keep1, keep2, r1, r2);
         n1[i] = keep1;
         n2[i] = keep2;

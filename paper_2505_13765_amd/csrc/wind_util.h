@@ -53,39 +53,33 @@ __device__ __forceinline__ int wave_max_i32(int v) {
   return v;
 }
 
-// Order-preserving map between fp32 and int32 (signed compare), used to carry (logit, column) in
-// one sortable word.
-__device__ __forceinline__ int f32_to_key(float v) {
-  int k = __float_as_int(v);
-  return k ^ ((k >> 31) & 0x7FFFFFFF);
-}
-__device__ __forceinline__ float key_to_f32(int k) {
-  return __int_as_float(k ^ ((k >> 31) & 0x7FFFFFFF));
-}
+// (logit, column) carried in one fp32 word: the low 7 mantissa bits of the logit give way to
+// 127 - column (column within a part of at most 128), which costs 2^-16 of relative precision and
+// keeps ordinary float ordering, so top-2 selection is v_max_f32 / v_med3_f32 on the packed words.
+// Among equal truncated positive values the lower column compares larger.
+constexpr uint32_t kKeyColMask = 127u;
+constexpr float kKeyNone = -3.0e38f;   // below every real logit; finite, so packing never makes a NaN
 
-constexpr int kKeyColBits = 7;                      // a key carries a column 0..127 within its part
-constexpr int kKeyColMask = (1 << kKeyColBits) - 1;
-constexpr int kKeyNone = INT32_MIN;                 // below every real key
-
-// The low bits of the value give way to (127 - column): of two equal values the lower column wins.
-__device__ __forceinline__ int make_key(float v, int col_in_part) {
-  return (f32_to_key(v) & ~kKeyColMask) | (kKeyColMask - col_in_part);
+__device__ __forceinline__ float make_key(float v, int col_in_part) {
+  return __uint_as_float((__float_as_uint(v) & ~kKeyColMask) | (kKeyColMask - (uint32_t)col_in_part));
 }
-__device__ __forceinline__ int key_col(int k) { return kKeyColMask - (k & kKeyColMask); }
-__device__ __forceinline__ float key_val(int k) { return key_to_f32(k & ~kKeyColMask); }
+__device__ __forceinline__ int key_col(float k) { return (int)(kKeyColMask - (__float_as_uint(k) & kKeyColMask)); }
+__device__ __forceinline__ float key_val(float k) { return __uint_as_float(__float_as_uint(k) & ~kKeyColMask); }
 
 // top-2 of the union of two sorted pairs (a1 >= a2), (b1 >= b2)
-__device__ __forceinline__ void merge_top2(int &a1, int &a2, int b1, int b2) {
-  int hi = a1 > b1 ? a1 : b1;
-  int lo = a1 > b1 ? b1 : a1;
-  int s = a2 > b2 ? a2 : b2;
-  a1 = hi;
-  a2 = lo > s ? lo : s;
+__device__ __forceinline__ void merge_top2(float &a1, float &a2, float b1, float b2) {
+  const float m = fmaxf(a2, b2);
+  a2 = __builtin_amdgcn_fmed3f(a1, b1, m);
+  a1 = fmaxf(a1, b1);
 }
-__device__ __forceinline__ void push_top2(int &a1, int &a2, int k) {
-  const int lo = k < a1 ? k : a1;
-  a1 = k > a1 ? k : a1;
-  a2 = lo > a2 ? lo : a2;
+__device__ __forceinline__ void push_top2(float &a1, float &a2, float k) {
+  a2 = __builtin_amdgcn_fmed3f(k, a1, a2);
+  a1 = fmaxf(a1, k);
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+  return v;
 }
 
 }  // namespace wind

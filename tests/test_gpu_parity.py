@@ -149,6 +149,28 @@ def test_prediction_network_on_mfma_tiles(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
+@pytest.mark.parametrize("name,B,lo,hi,W", [("largevocab_b128", 20, 20, 70, 16), ("lowblank_b256", 40, 20, 80, 16),
+                                            ("batch32", 9, 30, 140, 8)])
+def test_both_joint_tile_shapes(torch_cuda, name, B, lo, hi, W):
+    """The 128 x 128 and the 256 x 256 joint kernels must give the oracle's result; the split point
+    is moved so that each of them handles every iteration once, and once so that the decode
+    switches from one to the other as utterances finish."""
+    cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    res = []
+    for split in (1 << 30, 0, (B * W) // 2):
+        m.set_option("joint_split_rows", split)
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
+        res.append((toks, frs))
+    for other in res[1:]:
+        assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], other[0]))
+        assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], other[1]))
+    m.close()
+
+
 # ---------------------------------------------------------------------------------------------
 def test_joint_logits_against_oracle(torch_cuda):
     for name, n, t0 in (("greedy_b1", 16, 3), ("largevocab_b128", 5, 0)):
