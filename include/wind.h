@@ -157,6 +157,8 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "unroll"  loop iterations per graph launch (default 16, even)
  *   "profile" 1: time every kernel launch with events (see wind_get_kernel_times); implies no graph
  *   "recheck_kappa_milli"  width of the near-tie band of the bf16 pass, in thousandths
+ *   "tiny_rows"  decodes with at most this many window rows (B * W) run window gather, joint and
+ *             decision as one kernel per iteration (default 64, the maximum; 0 turns it off)
  *   "joint_split_rows"  iterations with more window rows than this use the 256 x 256 joint tiles,
  *             the others 128 x 128 tiles (default 1536)
  *   "pred_mfma_min_batch"  smallest B for which the prediction network runs on MFMA tiles

@@ -33,6 +33,7 @@ int fail(int code, const std::string &msg) {
 using JointCfg = TileCfg<128, 128, 64, 64>;            // debug store kernel
 using JointSmallCfg = DmaCfg<128, 128, 64, 64, 64, 2>;  // rows <= kJointSplitRows
 using JointBigCfg = Ring5Cfg<256, 64, 128>;             // rows > kJointSplitRows
+constexpr int kTinyRowsDefault = 64;                    // at most this many window rows: one fused kernel
 constexpr int kJointSplitRows = 1536;                   // measured crossover of the two joint kernels
 using EncCfg = TileCfg<128, 128, 64, 64>;
 using PredCfg = TileCfg<64, 64, 32, 32>;   // 32 utterances (hi and lo rows) x 64 columns
@@ -78,6 +79,7 @@ struct wind_model {
   int opt_graph = 1, opt_unroll = 16;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_joint_split_rows = kJointSplitRows;
+  int opt_tiny_rows = kTinyRowsDefault;
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
@@ -131,6 +133,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   const int ntiles = (d.V + JointSmallCfg::BN - 1) / JointSmallCfg::BN;
   const int nparts = ntiles * JointSmallCfg::WAVES_N;
   const int nparts_big = ((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN) * JointBigCfg::WAVES_N;
+  const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
@@ -140,14 +143,15 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   const size_t o_e = take((size_t)B * T * d.Hj * 4);
   const size_t o_len = take((size_t)B * 4), o_t = take((size_t)B * 4), o_sym = take((size_t)B * 4);
   const size_t o_count = take((size_t)B * 4), o_flag = take((size_t)B * 4), o_etok = take((size_t)B * 4);
+  const size_t o_event = take((size_t)B * 4);
   const size_t o_act = take((size_t)2 * B * 4), o_nact = take(8), o_eidx = take((size_t)B * 4);
-  const size_t o_nemit = take(4), o_ticket = take(4);
+  const size_t o_nemit = take(4), o_ticket = take(8);
   const size_t st = (size_t)d.L * B * d.Hp * 4;
   const size_t o_h = take(st), o_c = take(st), o_hn = take(st);
   const size_t o_p = take((size_t)B * d.Hj * 4);
   const size_t o_z = take(Mpad * d.Hj * 2);
   const size_t o_bl = take(Mpad * 4), o_zn = take(Mpad * 4);
-  const size_t o_parts = take(Mpad * nparts * 8);
+  const size_t o_parts = take(Mpad * (size_t)(nparts_tiny > nparts ? nparts_tiny : nparts) * 8);
   const size_t o_rl = take(Mpad * 4);
   const size_t o_stats = take(kNumStats * 8);
   if (off > m->ws_bytes) {
@@ -166,6 +170,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.e = (float *)(base + o_e);
   c.len = (int *)(base + o_len); c.t = (int *)(base + o_t); c.sym = (int *)(base + o_sym);
   c.count = (int *)(base + o_count); c.flag = (int *)(base + o_flag); c.emit_tok = (int *)(base + o_etok);
+  c.event = (unsigned *)(base + o_event);
   c.active_idx = (int *)(base + o_act); c.n_active = (int *)(base + o_nact);
   c.emit_idx = (int *)(base + o_eidx); c.n_emit = (int *)(base + o_nemit);
   c.ticket = (unsigned *)(base + o_ticket);
@@ -179,6 +184,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.nparts_big = nparts_big;
   c.part_width_big = JointBigCfg::WN;
   c.joint_split_rows = m->opt_joint_split_rows;
+  c.nparts_tiny = nparts_tiny;
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
   return WIND_OK;
@@ -272,12 +278,25 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
   return enqueue_pred_step(m, s, false);
 }
 
+// the fused few-rows kernel keeps all window rows in LDS
+bool tiny_rows_ok(const wind_model *m, int max_rows) {
+  const int cap = m->dev.Hj <= 1024 ? 64 : 32;
+  return max_rows <= (m->opt_tiny_rows < cap ? m->opt_tiny_rows : cap);
+}
+size_t tiny_smem_bytes(const ModelDev &d, int max_rows) {
+  const size_t z = (size_t)((max_rows + 31) / 32) * 32 * (d.Hj + 8) * 2;
+  return z > 32768 ? z : 32768;
+}
+
 int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
   const int max_rows = c.B * c.W;
   const int decide_threads = 64 * (c.W < 16 ? c.W : 16);
-  if (m->dtype == WIND_BF16) {
+  if (m->dtype == WIND_BF16 && tiny_rows_ok(m, max_rows)) {
+    ProfScope ps(m, s, WIND_K_JOINT, capturing);
+    joint_tiny_kernel<bf16_t><<<(unsigned)c.nparts_tiny, 256, tiny_smem_bytes(d, max_rows), s>>>(d, c, parity);
+  } else if (m->dtype == WIND_BF16) {
     {
       ProfScope ps(m, s, WIND_K_BUILD_Z, capturing);
       build_z_kernel<<<(max_rows + 3) / 4, 256, 0, s>>>(d, c, parity);
@@ -504,6 +523,9 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     hipError_t e = hipFuncSetAttribute((const void *)joint_dma_kernel<JointSmallCfg>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, JointSmallCfg::SMEM_BYTES);
     if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)joint_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)tiny_smem_bytes(m->dev, 64));
+    if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_ring5_kernel<JointBigCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
@@ -580,6 +602,12 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "unroll")) {
     if (value < 2 || value > 256 || (value & 1)) return fail(WIND_ERR_ARG, "unroll must be even, 2..256");
     m->opt_unroll = (int)value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "tiny_rows")) {
+    if (value < 0 || value > 64) return fail(WIND_ERR_ARG, "tiny_rows must be 0..64");
+    m->opt_tiny_rows = (int)value;
+    m->graph_valid = false;
     return WIND_OK;
   }
   if (!std::strcmp(key, "joint_split_rows")) {

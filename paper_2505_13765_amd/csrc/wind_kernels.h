@@ -52,12 +52,13 @@ struct CallDev {
   int *len;                     // [B] clamped to [0,T]
   int *t, *sym, *count;         // [B]
   int *flag;                    // [B] bit0 still active, bit1 emitted and still active
+  unsigned *event;              // [B] this iteration's counters of the utterance, packed (see decide_kernel)
   int *emit_tok;                // [B]
   int *active_idx;              // [2][B] ping-pong by iteration parity
   int *n_active;                // [2]
   int *emit_idx;                // [B]
   int *n_emit;                  // [1]
-  unsigned *ticket;             // [1]
+  unsigned *ticket;             // [2] workgroups done: decide_kernel, joint_tiny_kernel
   float *h, *c, *hn;            // [L][B][Hp]
   float *p;                     // [B][Hj]
   bf16_t *z;                    // [Mpad][Hj]
@@ -68,6 +69,7 @@ struct CallDev {
   int part_width;               //   small-tile joint kernel (rows <= joint_split_rows)
   int nparts_big, part_width_big;  // the same for the 256 x 256 kernel (rows > joint_split_rows)
   int joint_split_rows;         // which of the two joint kernels handles an iteration
+  int nparts_tiny;              // parts per row of the few-rows kernel (32 columns each)
   int *row_label;               // [Mpad] (fp32 models)
   unsigned long long *stats;    // [kNumStats]
 };
@@ -95,7 +97,8 @@ __global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) 
     c.n_active[0] = na;
     c.n_active[1] = 0;
     *c.n_emit = c.B;
-    *c.ticket = 0u;
+    c.ticket[0] = 0u;
+    c.ticket[1] = 0u;
   }
 }
 
@@ -429,119 +432,122 @@ __device__ __forceinline__ float exact_logit(const ModelDev &m, const float2 (&z
 
 constexpr int kDecideMaxHj = 2048;  // exact_logit keeps Hj/128 float2 per lane
 
-// Row argmax, first non-blank by ballot, pointer and hypothesis update, list compaction.
-// One workgroup per active utterance, one wave per window row (rows round-robin past 16 waves).
+struct DecideShared {
+  int label[kMaxWindow];
+  unsigned hist[kMaxWindow + 1];
+  int recheck;
+  int is_last;
+};
+
+// Label of one window row, decided by a whole wave: argmax over the row's keys, with every key
+// inside the near-tie band re-evaluated in fp32 (see the header comment of this file).
 template <class WT>
-__global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int parity, int exact_mode) {
-  __shared__ int s_label[kMaxWindow];
-  __shared__ int s_is_last;
-  const int na = c.n_active[parity];
-  const int a = blockIdx.x;
-  if (na == 0 && a == 0 && threadIdx.x == 0) c.n_active[parity ^ 1] = 0;  // keep both slots at "done"
-  if (a >= na) return;
+__device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
+                                          int nparts, int part_width, int &n_recheck) {
+  const int lane = threadIdx.x & 63, V = m.V;
+  // keys of this row: lane i holds part i (and i + 64, ... for wide vocabularies)
+  float k1 = kKeyNone;
+  for (int pi = lane; pi < nparts; pi += 64) k1 = fmaxf(k1, c.parts[(size_t)row * nparts + pi].x);
+  const float kbest = wave_max_f32(k1);
+  const float vbest = key_val(kbest);
+  const float vblank = c.blank_logit[row];
+  const float top = fmaxf(vbest, vblank);
+  const float tau = m.tau_scale * c.znorm[row] + 6.2e-5f * fabsf(top);
+  const float thresh = top - tau;
+  if (vbest < thresh) return V;                  // blank clear of every label
+  // how many label keys are inside the band?
+  int cnt = 0;
+  for (int pi = lane; pi < nparts; pi += 64) {
+    const float2 kk = c.parts[(size_t)row * nparts + pi];
+    cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
+  }
+#pragma unroll
+  for (int msk = 32; msk >= 1; msk >>= 1) cnt += __shfl_xor(cnt, msk, kWave);
+  if (cnt == 1 && vblank < thresh) {
+    // a single label clear of blank and of every other label: find its part
+    int col = -1;
+    for (int pi = lane; pi < nparts; pi += 64)
+      if (c.parts[(size_t)row * nparts + pi].x == kbest) col = pi * part_width + key_col(kbest);
+    return wave_max_i32(col);
+  }
+  // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
+  ++n_recheck;
+  constexpr int NZ = kDecideMaxHj / 128;
+  float2 zr[NZ];
+  const float *er = c.e + ((size_t)b * c.T + frame) * m.Hj;
+  const float *pr = c.p + (size_t)b * m.Hj;
+#pragma unroll
+  for (int i = 0; i < NZ; ++i) {
+    const int k = 2 * lane + 128 * i;
+    zr[i] = make_float2(0.f, 0.f);
+    if (k < m.Hj) {
+      const float2 ev = *reinterpret_cast<const float2 *>(er + k);
+      const float2 pv = *reinterpret_cast<const float2 *>(pr + k);
+      zr[i] = make_float2(fmaxf(ev.x + pv.x, 0.f), fmaxf(ev.y + pv.y, 0.f));
+    }
+  }
+  float bestv = vblank;     // blank has the highest id: it wins only if strictly larger
+  int besti = V;
+  for (int p0 = 0; p0 < nparts; p0 += 64) {
+    const int pi = p0 + lane;
+    float2 kk = make_float2(kKeyNone, kKeyNone);
+    if (pi < nparts) kk = c.parts[(size_t)row * nparts + pi];
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      const float key = which ? kk.y : kk.x;
+      unsigned long long mask = __ballot(pi < nparts && key_val(key) >= thresh);
+      while (mask) {
+        const int src = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        const float skey = __shfl(key, src, kWave);
+        const int col = (p0 + src) * part_width + key_col(skey);
+        const float v = exact_logit<WT, NZ>(m, zr, col, lane);
+        if (v > bestv || (v == bestv && col < besti)) { bestv = v; besti = col; }
+      }
+    }
+  }
+  return besti;
+}
+
+// One utterance (slot a of the active list), handled by the whole calling workgroup: one wave per
+// window row (rows round-robin over the waves), then the first non-blank row by ballot and the
+// pointer / hypothesis update of Algorithm 2.  Ends with a workgroup barrier.
+template <class WT>
+__device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int parity, int a,
+                                                 int exact_mode, int nparts, int part_width, DecideShared &sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int b = c.active_idx[parity * c.B + a];
   const int t = c.t[b], len = c.len[b], V = m.V;
   const int n = min(c.W, len - t);
   int n_recheck = 0;
-  const bool big = na * c.W > c.joint_split_rows;   // which joint kernel wrote the keys
-  const int nparts = big ? c.nparts_big : c.nparts, part_width = big ? c.part_width_big : c.part_width;
-
+  if (threadIdx.x == 0) sh.recheck = 0;
+  __syncthreads();
   for (int j = wave; j < c.W; j += nwaves) {
     int label = V;
     if (j < n) {
       const int row = a * c.W + j;
-      if (exact_mode) {
-        label = c.row_label[row];
-      } else {
-        // keys of this row: lane i holds part i (and i + 64, ... for wide vocabularies)
-        float k1 = kKeyNone;
-        for (int pi = lane; pi < nparts; pi += 64) k1 = fmaxf(k1, c.parts[(size_t)row * nparts + pi].x);
-        const float kbest = wave_max_f32(k1);
-        const float vbest = key_val(kbest);
-        const float vblank = c.blank_logit[row];
-        const float top = fmaxf(vbest, vblank);
-        const float tau = m.tau_scale * c.znorm[row] + 6.2e-5f * fabsf(top);
-        const float thresh = top - tau;
-        if (vbest < thresh) {
-          label = V;                                   // blank clear of every label
-        } else {
-          // how many label keys are inside the band?
-          int cnt = 0;
-          for (int pi = lane; pi < nparts; pi += 64) {
-            const float2 kk = c.parts[(size_t)row * nparts + pi];
-            cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
-          }
-#pragma unroll
-          for (int msk = 32; msk >= 1; msk >>= 1) cnt += __shfl_xor(cnt, msk, kWave);
-          if (cnt == 1 && vblank < thresh) {
-            // a single label clear of blank and of every other label: find its part
-            int col = -1;
-            for (int pi = lane; pi < nparts; pi += 64)
-              if (c.parts[(size_t)row * nparts + pi].x == kbest) col = pi * part_width + key_col(kbest);
-            label = wave_max_i32(col);
-          } else {
-            // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
-            ++n_recheck;
-            constexpr int NZ = kDecideMaxHj / 128;
-            float2 zr[NZ];
-            const float *er = c.e + ((size_t)b * c.T + t + j) * m.Hj;
-            const float *pr = c.p + (size_t)b * m.Hj;
-#pragma unroll
-            for (int i = 0; i < NZ; ++i) {
-              const int k = 2 * lane + 128 * i;
-              zr[i] = make_float2(0.f, 0.f);
-              if (k < m.Hj) {
-                const float2 ev = *reinterpret_cast<const float2 *>(er + k);
-                const float2 pv = *reinterpret_cast<const float2 *>(pr + k);
-                zr[i] = make_float2(fmaxf(ev.x + pv.x, 0.f), fmaxf(ev.y + pv.y, 0.f));
-              }
-            }
-            float bestv = vblank;     // blank has the highest id: it wins only if strictly larger
-            int besti = V;
-            for (int p0 = 0; p0 < nparts; p0 += 64) {
-              const int pi = p0 + lane;
-              float2 kk = make_float2(kKeyNone, kKeyNone);
-              if (pi < nparts) kk = c.parts[(size_t)row * nparts + pi];
-#pragma unroll
-              for (int which = 0; which < 2; ++which) {
-                const float key = which ? kk.y : kk.x;
-                unsigned long long mask = __ballot(pi < nparts && key_val(key) >= thresh);
-                while (mask) {
-                  const int src = __ffsll((long long)mask) - 1;
-                  mask &= mask - 1;
-                  const float skey = __shfl(key, src, kWave);
-                  const int col = (p0 + src) * part_width + key_col(skey);
-                  const float v = exact_logit<WT, NZ>(m, zr, col, lane);
-                  if (v > bestv || (v == bestv && col < besti)) { bestv = v; besti = col; }
-                }
-              }
-            }
-            label = besti;
-          }
-        }
-      }
+      label = exact_mode ? c.row_label[row] : decide_row<WT>(m, c, row, b, t + j, nparts, part_width, n_recheck);
     }
-    if (lane == 0) s_label[j] = label;
+    if (lane == 0) sh.label[j] = label;
   }
+  if (lane == 0 && n_recheck) atomicAdd(&sh.recheck, n_recheck);
   __syncthreads();
-
   if (wave == 0) {
-    const bool nb = lane < n && s_label[lane] != V;
+    const bool nb = lane < n && sh.label[lane] != V;
     const unsigned long long mask = __ballot(nb);
     if (lane == 0) {
       const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
-      int tn = t, sym = c.sym[b], cnt = c.count[b], jump, emitted = 0, forced = 0, tok = V;
+      int tn = t, sym = c.sym[b], cnt = c.count[b], jump, emitted = 0, forced = 0, tok = V, overflow = 0;
       if (i < 0) {
         tn += n; sym = 0; jump = n;
       } else {
-        tok = s_label[i];
+        tok = sh.label[i];
         if (cnt < c.cap) {
           c.out_tokens[(size_t)b * c.cap + cnt] = tok;
           c.out_frames[(size_t)b * c.cap + cnt] = t + i;
           ++cnt;
         } else {
-          atomicAdd(&c.stats[ST_OVERFLOW], 1ull);
+          overflow = 1;
         }
         tn += i;
         sym = (i == 0) ? sym + 1 : 1;
@@ -553,50 +559,207 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
       const int active = tn < len;
       c.flag[b] = active | ((emitted & active) << 1);
       c.emit_tok[b] = tok;
-      atomicAdd(&c.stats[ST_WINDOWS], 1ull);
-      atomicAdd(&c.stats[ST_ROWS], (unsigned long long)n);
-      atomicAdd(&c.stats[ST_USEFUL], (unsigned long long)(i < 0 ? n : i + 1));
-      if (emitted) atomicAdd(&c.stats[ST_LABELS], 1ull);
-      if (forced) atomicAdd(&c.stats[ST_FORCED], 1ull);
-      atomicAdd(&c.stats[kStatJump0 + jump], 1ull);
+      // counters of this window, summed by the last workgroup: n (7 bits), useful rows (7), jump (7),
+      // rechecks (7), emitted, forced, overflow
+      const int useful = i < 0 ? n : i + 1;
+      c.event[b] = (unsigned)n | ((unsigned)useful << 7) | ((unsigned)jump << 14) |
+                   ((unsigned)min(sh.recheck, 127) << 21) | ((unsigned)emitted << 28) | ((unsigned)forced << 29) |
+                   ((unsigned)overflow << 30);
     }
   }
-  if (lane == 0 && n_recheck) atomicAdd(&c.stats[ST_RECHECK], (unsigned long long)n_recheck);
-
-  // The last workgroup to finish rebuilds the lists for the prediction network and the next iteration.
   __syncthreads();
+}
+
+// Rebuilds the active list (other parity slot) and the emit list from the per-utterance flags, and
+// adds the iteration's counters to the statistics.  Called by wave 0 of one workgroup per
+// iteration, after every utterance has been decided and those writes have been fenced.
+__device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int na, DecideShared &sh) {
+  const int lane = threadIdx.x & 63;
+  const int *src = c.active_idx + parity * c.B;
+  int *dst = c.active_idx + (parity ^ 1) * c.B;
+  int n_act = 0, n_em = 0;
+  unsigned sum_rows = 0, sum_useful = 0, sum_recheck = 0, sum_labels = 0, sum_forced = 0, sum_over = 0;
+  for (int base = 0; base < na; base += 64) {
+    const int idx = base + lane;
+    int ub = 0, f = 0;
+    if (idx < na) {
+      ub = src[idx];
+      f = __atomic_load_n(&c.flag[ub], __ATOMIC_RELAXED);
+      const unsigned ev = __atomic_load_n(&c.event[ub], __ATOMIC_RELAXED);
+      sum_rows += ev & 127u; sum_useful += (ev >> 7) & 127u; sum_recheck += (ev >> 21) & 127u;
+      sum_labels += (ev >> 28) & 1u; sum_forced += (ev >> 29) & 1u; sum_over += (ev >> 30) & 1u;
+      atomicAdd(&sh.hist[(ev >> 14) & 127u], 1u);
+    }
+    const unsigned long long ma = __ballot(f & 1), me = __ballot((f >> 1) & 1);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (f & 1) dst[n_act + __popcll(ma & below)] = ub;
+    if (f & 2) c.emit_idx[n_em + __popcll(me & below)] = ub;
+    n_act += __popcll(ma);
+    n_em += __popcll(me);
+  }
+#pragma unroll
+  for (int msk = 32; msk >= 1; msk >>= 1) {
+    sum_rows += __shfl_xor(sum_rows, msk, kWave); sum_useful += __shfl_xor(sum_useful, msk, kWave);
+    sum_recheck += __shfl_xor(sum_recheck, msk, kWave); sum_labels += __shfl_xor(sum_labels, msk, kWave);
+    sum_forced += __shfl_xor(sum_forced, msk, kWave); sum_over += __shfl_xor(sum_over, msk, kWave);
+  }
+  // one writer per iteration, iterations are ordered on the stream: plain read-modify-write
+  for (int j = lane; j <= kMaxWindow; j += 64)
+    if (sh.hist[j]) c.stats[kStatJump0 + j] += sh.hist[j];
+  if (lane == 0) {
+    c.n_active[parity ^ 1] = n_act;
+    *c.n_emit = n_em;
+    *c.ticket = 0u;
+    c.stats[ST_ITER] += 1ull; c.stats[ST_WINDOWS] += (unsigned long long)na;
+    c.stats[ST_ROWS] += sum_rows; c.stats[ST_USEFUL] += sum_useful; c.stats[ST_RECHECK] += sum_recheck;
+    c.stats[ST_LABELS] += sum_labels; c.stats[ST_FORCED] += sum_forced; c.stats[ST_OVERFLOW] += sum_over;
+  }
+}
+
+// Row argmax, first non-blank by ballot, pointer and hypothesis update, list compaction.
+// One workgroup per active utterance; the last workgroup to finish rebuilds the lists.
+template <class WT>
+__global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int parity, int exact_mode) {
+  __shared__ DecideShared sh;
+  for (int j = threadIdx.x; j <= kMaxWindow; j += blockDim.x) sh.hist[j] = 0u;
+  const int na = c.n_active[parity];
+  const int a = blockIdx.x;
+  if (na == 0 && a == 0 && threadIdx.x == 0) c.n_active[parity ^ 1] = 0;  // keep both slots at "done"
+  if (a >= na) return;
+  const bool big = na * c.W > c.joint_split_rows;   // which joint kernel wrote the keys
+  decide_utterance<WT>(m, c, parity, a, exact_mode, big ? c.nparts_big : c.nparts,
+                       big ? c.part_width_big : c.part_width, sh);
   if (threadIdx.x == 0) {
     __threadfence();
     const unsigned tk = atomicAdd(c.ticket, 1u);
-    s_is_last = (tk == (unsigned)(na - 1));
+    sh.is_last = (tk == (unsigned)(na - 1));
   }
   __syncthreads();
-  if (!s_is_last) return;
+  if (!sh.is_last) return;
   __threadfence();
-  if (wave == 0) {
-    const int *src = c.active_idx + parity * c.B;
-    int *dst = c.active_idx + (parity ^ 1) * c.B;
-    int n_act = 0, n_em = 0;
-    for (int base = 0; base < na; base += 64) {
-      const int idx = base + lane;
-      int ub = 0, f = 0;
-      if (idx < na) {
-        ub = src[idx];
-        f = __atomic_load_n(&c.flag[ub], __ATOMIC_RELAXED);
+  if (threadIdx.x < 64) compact_lists(c, parity, na, sh);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Few window rows (at most 64; one utterance with any window, or a handful of utterances): the
+// whole iteration up to the prediction network in one kernel.  Every workgroup rebuilds the window
+// rows z in LDS from fp32 e and p (cheaper than a kernel boundary), multiplies them with its 32
+// columns of W_out on MFMA, the four waves splitting K and loading their W_out fragments straight
+// from memory into registers (no staging, no barrier inside the K loop), and writes the rows' keys;
+// the last workgroup to finish takes the decisions for every utterance and rebuilds the lists.
+constexpr int kTinyCols = 32;
+template <class WT>
+__global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, int parity) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  __shared__ DecideShared sh;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
+  const int na = c.n_active[parity];
+  if (na == 0) {
+    if (blockIdx.x == 0 && tid == 0) c.n_active[parity ^ 1] = 0;
+    return;
+  }
+  const int n_rows = na * c.W, Hj = m.Hj, W = c.W;
+  const int RB = (n_rows + 31) >> 5;                 // 32-row blocks in use (1 or 2)
+  const int zstride = Hj + 8;                        // bf16 elements; odd number of 16-byte units
+  bf16_t *zs = reinterpret_cast<bf16_t *>(smem_raw);
+  // phase 1: window rows into LDS; workgroup 0 also computes the fp32 blank logits and |z|
+  for (int row = wave; row < RB * 32; row += 4) {
+    bool valid = false;
+    const float *er = nullptr, *pr = nullptr;
+    if (row < n_rows) {
+      const int a = row / W, j = row - a * W;
+      const int b = c.active_idx[parity * c.B + a];
+      const int tt = c.t[b] + j;
+      valid = tt < c.len[b];
+      er = c.e + ((size_t)b * c.T + (valid ? tt : 0)) * Hj;
+      pr = c.p + (size_t)b * Hj;
+    }
+    float dot = 0.f, nrm = 0.f;
+    for (int k = lane * 4; k < Hj; k += 256) {
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (valid) {
+        const float4 ev = *reinterpret_cast<const float4 *>(er + k);
+        const float4 pv = *reinterpret_cast<const float4 *>(pr + k);
+        x.x = fmaxf(ev.x + pv.x, 0.f); x.y = fmaxf(ev.y + pv.y, 0.f);
+        x.z = fmaxf(ev.z + pv.z, 0.f); x.w = fmaxf(ev.w + pv.w, 0.f);
       }
-      const unsigned long long ma = __ballot(f & 1), me = __ballot((f >> 1) & 1);
-      const unsigned long long below = (1ull << lane) - 1ull;
-      if (f & 1) dst[n_act + __popcll(ma & below)] = ub;
-      if (f & 2) c.emit_idx[n_em + __popcll(me & below)] = ub;
-      n_act += __popcll(ma);
-      n_em += __popcll(me);
+      *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+      if (blockIdx.x == 0) {
+        const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
+        dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
+        nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+      }
     }
-    if (lane == 0) {
-      c.n_active[parity ^ 1] = n_act;
-      *c.n_emit = n_em;
-      *c.ticket = 0u;
-      atomicAdd(&c.stats[ST_ITER], 1ull);
+    if (blockIdx.x == 0 && row < n_rows) {
+      dot = wave_sum(dot);
+      nrm = wave_sum(nrm);
+      if (lane == 0) { c.blank_logit[row] = dot + m.b_out[m.V]; c.znorm[row] = sqrtf(nrm); }
     }
+  }
+  __syncthreads();
+  // phase 2: this wave's quarter of K, 32 columns, RB row blocks
+  const int n0 = blockIdx.x * kTinyCols;
+  const int kq = Hj >> 2, k0 = wave * kq;           // Hj % 64 == 0, so kq % 16 == 0
+  f32x16 acc[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
+  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
+  const bf16_t *zrow = zs + (size_t)(lane & 31) * zstride + k0 + (lane >> 5) * 8;
+#pragma unroll 4
+  for (int ks = 0; ks < kq; ks += 16) {
+    const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(wrow + ks);
+    const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + ks);
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag, acc[0], 0, 0, 0);
+    if (RB > 1) {
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(zrow + 32 * zstride + ks);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfrag, acc[1], 0, 0, 0);
+    }
+  }
+  __syncthreads();   // every wave is done with z: its LDS is reused for the K-split partial sums
+  float *red = reinterpret_cast<float *>(smem_raw);   // [wave][rb][r][lane]
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[((wave * 2 + rb) * 16 + r) * 64 + lane] = acc[rb][r];
+  __syncthreads();
+  if (wave < RB) {
+    const int rb = wave, cip = lane & 31, col = n0 + cip;
+    const bool ok = col < m.V;
+    const float bias = ok ? m.b_out[ok ? col : 0] : kKeyNone;
+    float k1[16], k2[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float v = bias;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) v += red[((w2 * 2 + rb) * 16 + r) * 64 + lane];
+      k1[r] = make_key(ok ? v : kKeyNone, cip);
+      k2[r] = kKeyNone;
+    }
+    float o1[1], o2[1];
+    RowTop2<16, 16>::run(k1, k2, lane, o1, o2);
+    const int s = rowtop2_first_slot<16>(lane);
+    const int row = rb * 32 + acc_row(0, s, lane);
+    c.parts[(size_t)row * c.nparts_tiny + blockIdx.x] = make_float2(o1[0], o2[0]);
+  }
+  // phase 3: the last workgroup decides
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const unsigned tk = atomicAdd(c.ticket + 1, 1u);
+    sh.is_last = (tk == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (!sh.is_last) return;
+  __threadfence();
+  for (int a = 0; a < na; ++a) decide_utterance<WT>(m, c, parity, a, 0, c.nparts_tiny, kTinyCols, sh);
+  __threadfence();
+  __syncthreads();
+  if (tid < 64) {
+    compact_lists(c, parity, na, sh);
+    if (tid == 0) c.ticket[1] = 0u;
   }
 }
 

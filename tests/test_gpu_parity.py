@@ -149,6 +149,31 @@ def test_prediction_network_on_mfma_tiles(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
+@pytest.mark.parametrize("name,B,lo,hi,W", [("greedy_b1", 1, 120, 120, 16), ("batch32", 3, 30, 90, 16), ("batch32", 8, 20, 70, 8),
+                                            ("largevocab_b128", 4, 20, 60, 16), ("lowblank_b256", 5, 30, 60, 3)])
+def test_fused_few_rows_kernel(torch_cuda, name, B, lo, hi, W):
+    """Decodes with at most 64 window rows run gather + joint + decision as one kernel; it must
+    agree with the oracle and with the separate kernels (tiny_rows = 0), on one and two row blocks,
+    Hj = 640 and 1024, one and several utterances."""
+    cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    res, stats = [], []
+    for tiny in (64, 0):
+        m.set_option("tiny_rows", tiny)
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
+        st = m.stats()
+        res.append((toks, frs))
+        stats.append((st.iterations, st.windows, st.rows, st.useful_rows, st.labels, st.forced_advances,
+                      list(st.jump_hist)))
+    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[1][0]))
+    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], res[1][1]))
+    assert stats[0] == stats[1]
+    m.close()
+
+
 @pytest.mark.parametrize("name,B,lo,hi,W", [("largevocab_b128", 20, 20, 70, 16), ("lowblank_b256", 40, 20, 80, 16),
                                             ("batch32", 9, 30, 140, 8)])
 def test_both_joint_tile_shapes(torch_cuda, name, B, lo, hi, W):
