@@ -145,6 +145,8 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   const size_t o_count = take((size_t)B * 4), o_flag = take((size_t)B * 4), o_etok = take((size_t)B * 4);
   const size_t o_event = take((size_t)B * 4);
   const size_t o_act = take((size_t)2 * B * 4), o_nact = take(8), o_eidx = take((size_t)B * 4);
+  const size_t o_eltok = take((size_t)B * 4);
+  const size_t o_slot = take(2 * kTinyRows * 16), o_slotc = take(2 * kTinyRows * 4);
   const size_t o_nemit = take(4), o_ticket = take(8);
   const size_t st = (size_t)d.L * B * d.Hp * 4;
   const size_t o_h = take(st), o_c = take(st), o_hn = take(st);
@@ -173,6 +175,8 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.event = (unsigned *)(base + o_event);
   c.active_idx = (int *)(base + o_act); c.n_active = (int *)(base + o_nact);
   c.emit_idx = (int *)(base + o_eidx); c.n_emit = (int *)(base + o_nemit);
+  c.emit_list_tok = (int *)(base + o_eltok);
+  c.slot_state = (int4 *)(base + o_slot); c.slot_count = (int *)(base + o_slotc);
   c.ticket = (unsigned *)(base + o_ticket);
   c.h = (float *)(base + o_h); c.c = (float *)(base + o_c); c.hn = (float *)(base + o_hn);
   c.p = (float *)(base + o_p);
@@ -235,6 +239,7 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
   const CallDev &c = m->call;
   const int lstm_blocks = (d.Hp + 3) / 4, proj_blocks = (d.Hj + 3) / 4;
   const bool mfma = m->dtype == WIND_BF16 && c.B >= m->opt_pred_mfma_min_batch;
+  const bool small_k = d.E + d.Hp <= 512 * kSmallKSteps && 2 * d.Hp <= 512 * kSmallKSteps;   // the low-latency kernels' K range
   constexpr int R = PredCfg::BM / 2;
   const unsigned mtiles = (unsigned)((c.B + R - 1) / R);
   {
@@ -243,6 +248,7 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
       if (mfma)
         lstm_layer_mfma_kernel<PredCfg><<<dim3(mtiles, (unsigned)(4 * d.Hp / PredCfg::BN)), PredCfg::NT,
                                           PredCfg::SMEM_BYTES, s>>>(d, c, l);
+      else if (m->dtype == WIND_BF16 && small_k) lstm_small_kernel<2><<<lstm_blocks, 256, 0, s>>>(d, c, l);
       else if (m->dtype == WIND_BF16) lstm_layer_kernel<bf16_t, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
       else lstm_layer_kernel<float, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
     }
@@ -252,6 +258,7 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
     if (mfma)
       pred_proj_mfma_kernel<PredCfg><<<dim3(mtiles, (unsigned)(d.Hj / PredCfg::BN)), PredCfg::NT,
                                        PredCfg::SMEM_BYTES, s>>>(d, c);
+    else if (m->dtype == WIND_BF16 && small_k) pred_small_kernel<2><<<proj_blocks, 256, 0, s>>>(d, c);
     else if (m->dtype == WIND_BF16) pred_proj_kernel<bf16_t, 4><<<proj_blocks, 256, 0, s>>>(d, c);
     else pred_proj_kernel<float, 4><<<proj_blocks, 256, 0, s>>>(d, c);
   }
@@ -661,6 +668,7 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
     HIP_TRY(hipMemcpyAsync(c.n_emit, &one, sizeof(int), hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(c.emit_idx, &b, sizeof(int), hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(c.emit_tok + b, &tok, sizeof(int), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c.emit_list_tok, &tok, sizeof(int), hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     rc = enqueue_pred_step(m, s, false);
   }

@@ -19,6 +19,7 @@ namespace wind {
 
 constexpr int kMaxLayers = 4;
 constexpr int kMaxWindow = 64;
+constexpr int kTinyRows = 64;   // the fused few-rows kernel handles at most this many window rows
 constexpr int kStatJump0 = 8;  // index of jump_hist[0] in the device counter array
 constexpr int kNumStats = kStatJump0 + kMaxWindow + 1;
 enum { ST_ITER = 0, ST_WINDOWS, ST_ROWS, ST_USEFUL, ST_LABELS, ST_FORCED, ST_RECHECK, ST_OVERFLOW };
@@ -56,7 +57,10 @@ struct CallDev {
   int *emit_tok;                // [B]
   int *active_idx;              // [2][B] ping-pong by iteration parity
   int *n_active;                // [2]
-  int *emit_idx;                // [B]
+  int *emit_idx;                // [B] utterances that emitted and are still active, in order
+  int *emit_list_tok;           // [B] their labels, in the same order
+  int4 *slot_state;             // [2][64] few-rows path: (utterance, t, len, sym) per active slot, by parity
+  int *slot_count;              // [2][64] labels emitted so far, same order
   int *n_emit;                  // [1]
   unsigned *ticket;             // [2] workgroups done: decide_kernel, joint_tiny_kernel
   float *h, *c, *hn;            // [L][B][Hp]
@@ -88,12 +92,16 @@ __global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) 
     c.flag[b] = len > 0 ? 1 : 0;
     c.emit_tok[b] = m.V;       // start token
     c.emit_idx[b] = b;         // the first prediction-network step runs on every utterance
+    c.emit_list_tok[b] = m.V;
   }
   __syncthreads();
   if (tid == 0) {
     int na = 0;
     for (int b = 0; b < c.B; ++b)
-      if (c.len[b] > 0) c.active_idx[na++] = b;
+      if (c.len[b] > 0) {
+        if (na < kTinyRows) { c.slot_state[na] = make_int4(b, 0, c.len[b], 0); c.slot_count[na] = 0; }
+        c.active_idx[na++] = b;
+      }
     c.n_active[0] = na;
     c.n_active[1] = 0;
     *c.n_emit = c.B;
@@ -437,22 +445,29 @@ struct DecideShared {
   unsigned hist[kMaxWindow + 1];
   int recheck;
   int is_last;
+  // LOCAL mode (fused few-rows kernel): per-slot state and per-row scalars kept in LDS, so that the
+  // deciding workgroup does not go back to memory for them
+  int4 slot[kTinyRows];        // utterance id, t, len, sym
+  int cnt[kTinyRows];
+  int flag[kTinyRows];
+  int tok[kTinyRows];
+  unsigned event[kTinyRows];
+  float blank[kTinyRows], znorm[kTinyRows];
 };
 
 // Label of one window row, decided by a whole wave: argmax over the row's keys, with every key
 // inside the near-tie band re-evaluated in fp32 (see the header comment of this file).
 template <class WT>
 __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
-                                          int nparts, int part_width, int &n_recheck) {
+                                          int nparts, int part_width, float vblank, float znorm, int &n_recheck) {
   const int lane = threadIdx.x & 63, V = m.V;
   // keys of this row: lane i holds part i (and i + 64, ... for wide vocabularies)
   float k1 = kKeyNone;
   for (int pi = lane; pi < nparts; pi += 64) k1 = fmaxf(k1, c.parts[(size_t)row * nparts + pi].x);
   const float kbest = wave_max_f32(k1);
   const float vbest = key_val(kbest);
-  const float vblank = c.blank_logit[row];
   const float top = fmaxf(vbest, vblank);
-  const float tau = m.tau_scale * c.znorm[row] + 6.2e-5f * fabsf(top);
+  const float tau = m.tau_scale * znorm + 6.2e-5f * fabsf(top);
   const float thresh = top - tau;
   if (vbest < thresh) return V;                  // blank clear of every label
   // how many label keys are inside the band?
@@ -512,12 +527,12 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
 // One utterance (slot a of the active list), handled by the whole calling workgroup: one wave per
 // window row (rows round-robin over the waves), then the first non-blank row by ballot and the
 // pointer / hypothesis update of Algorithm 2.  Ends with a workgroup barrier.
-template <class WT>
+template <class WT, bool LOCAL>
 __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int parity, int a,
                                                  int exact_mode, int nparts, int part_width, DecideShared &sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-  const int b = c.active_idx[parity * c.B + a];
-  const int t = c.t[b], len = c.len[b], V = m.V;
+  const int b = LOCAL ? sh.slot[a].x : c.active_idx[parity * c.B + a];
+  const int t = LOCAL ? sh.slot[a].y : c.t[b], len = LOCAL ? sh.slot[a].z : c.len[b], V = m.V;
   const int n = min(c.W, len - t);
   int n_recheck = 0;
   if (threadIdx.x == 0) sh.recheck = 0;
@@ -526,7 +541,9 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
     int label = V;
     if (j < n) {
       const int row = a * c.W + j;
-      label = exact_mode ? c.row_label[row] : decide_row<WT>(m, c, row, b, t + j, nparts, part_width, n_recheck);
+      if (exact_mode) label = c.row_label[row];
+      else label = decide_row<WT>(m, c, row, b, t + j, nparts, part_width, LOCAL ? sh.blank[row] : c.blank_logit[row],
+                                  LOCAL ? sh.znorm[row] : c.znorm[row], n_recheck);
     }
     if (lane == 0) sh.label[j] = label;
   }
@@ -537,7 +554,8 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
     const unsigned long long mask = __ballot(nb);
     if (lane == 0) {
       const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
-      int tn = t, sym = c.sym[b], cnt = c.count[b], jump, emitted = 0, forced = 0, tok = V, overflow = 0;
+      int tn = t, sym = LOCAL ? sh.slot[a].w : c.sym[b], cnt = LOCAL ? sh.cnt[a] : c.count[b];
+      int jump, emitted = 0, forced = 0, tok = V, overflow = 0;
       if (i < 0) {
         tn += n; sym = 0; jump = n;
       } else {
@@ -562,9 +580,15 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
       // counters of this window, summed by the last workgroup: n (7 bits), useful rows (7), jump (7),
       // rechecks (7), emitted, forced, overflow
       const int useful = i < 0 ? n : i + 1;
-      c.event[b] = (unsigned)n | ((unsigned)useful << 7) | ((unsigned)jump << 14) |
-                   ((unsigned)min(sh.recheck, 127) << 21) | ((unsigned)emitted << 28) | ((unsigned)forced << 29) |
-                   ((unsigned)overflow << 30);
+      const unsigned ev = (unsigned)n | ((unsigned)useful << 7) | ((unsigned)jump << 14) |
+                          ((unsigned)min(sh.recheck, 127) << 21) | ((unsigned)emitted << 28) |
+                          ((unsigned)forced << 29) | ((unsigned)overflow << 30);
+      if (LOCAL) {
+        sh.flag[a] = active | ((emitted & active) << 1); sh.tok[a] = tok; sh.event[a] = ev;
+        sh.slot[a] = make_int4(b, tn, len, sym); sh.cnt[a] = cnt;
+      } else {
+        c.event[b] = ev;
+      }
     }
   }
   __syncthreads();
@@ -573,6 +597,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
 // Rebuilds the active list (other parity slot) and the emit list from the per-utterance flags, and
 // adds the iteration's counters to the statistics.  Called by wave 0 of one workgroup per
 // iteration, after every utterance has been decided and those writes have been fenced.
+template <bool LOCAL>
 __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int na, DecideShared &sh) {
   const int lane = threadIdx.x & 63;
   const int *src = c.active_idx + parity * c.B;
@@ -583,17 +608,28 @@ __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int 
     const int idx = base + lane;
     int ub = 0, f = 0;
     if (idx < na) {
-      ub = src[idx];
-      f = __atomic_load_n(&c.flag[ub], __ATOMIC_RELAXED);
-      const unsigned ev = __atomic_load_n(&c.event[ub], __ATOMIC_RELAXED);
+      ub = LOCAL ? sh.slot[idx].x : src[idx];
+      f = LOCAL ? sh.flag[idx] : __atomic_load_n(&c.flag[ub], __ATOMIC_RELAXED);
+      const unsigned ev = LOCAL ? sh.event[idx] : __atomic_load_n(&c.event[ub], __ATOMIC_RELAXED);
       sum_rows += ev & 127u; sum_useful += (ev >> 7) & 127u; sum_recheck += (ev >> 21) & 127u;
       sum_labels += (ev >> 28) & 1u; sum_forced += (ev >> 29) & 1u; sum_over += (ev >> 30) & 1u;
       atomicAdd(&sh.hist[(ev >> 14) & 127u], 1u);
     }
     const unsigned long long ma = __ballot(f & 1), me = __ballot((f >> 1) & 1);
     const unsigned long long below = (1ull << lane) - 1ull;
-    if (f & 1) dst[n_act + __popcll(ma & below)] = ub;
-    if (f & 2) c.emit_idx[n_em + __popcll(me & below)] = ub;
+    if (f & 1) {
+      const int pos = n_act + __popcll(ma & below);
+      dst[pos] = ub;
+      if (LOCAL) {   // next iteration's slot table: everything the few-rows kernel needs, in active order
+        c.slot_state[(parity ^ 1) * kTinyRows + pos] = sh.slot[idx];
+        c.slot_count[(parity ^ 1) * kTinyRows + pos] = sh.cnt[idx];
+      }
+    }
+    if (f & 2) {
+      const int pos = n_em + __popcll(me & below);
+      c.emit_idx[pos] = ub;
+      c.emit_list_tok[pos] = LOCAL ? sh.tok[idx] : c.emit_tok[ub];
+    }
     n_act += __popcll(ma);
     n_em += __popcll(me);
   }
@@ -627,8 +663,8 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   if (na == 0 && a == 0 && threadIdx.x == 0) c.n_active[parity ^ 1] = 0;  // keep both slots at "done"
   if (a >= na) return;
   const bool big = na * c.W > c.joint_split_rows;   // which joint kernel wrote the keys
-  decide_utterance<WT>(m, c, parity, a, exact_mode, big ? c.nparts_big : c.nparts,
-                       big ? c.part_width_big : c.part_width, sh);
+  decide_utterance<WT, false>(m, c, parity, a, exact_mode, big ? c.nparts_big : c.nparts,
+                              big ? c.part_width_big : c.part_width, sh);
   if (threadIdx.x == 0) {
     __threadfence();
     const unsigned tk = atomicAdd(c.ticket, 1u);
@@ -637,7 +673,7 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   __syncthreads();
   if (!sh.is_last) return;
   __threadfence();
-  if (threadIdx.x < 64) compact_lists(c, parity, na, sh);
+  if (threadIdx.x < 64) compact_lists<false>(c, parity, na, sh);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -648,32 +684,48 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
 // from memory into registers (no staging, no barrier inside the K loop), and writes the rows' keys;
 // the last workgroup to finish takes the decisions for every utterance and rebuilds the lists.
 constexpr int kTinyCols = 32;
+constexpr int kTinyPrefetch = 16;   // W_out fragments (K steps of 16) a wave requests before anything else
 template <class WT>
 __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, int parity) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   __shared__ DecideShared sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
+  const int Hj = m.Hj, W = c.W;
+  // round trip 1, all independent: the active count, the slot table (utterance, t, len, sym, count
+  // per active slot, written by the previous iteration's compaction), and this wave's W_out
+  // fragments for its quarter of K
   const int na = c.n_active[parity];
+  if (tid < kTinyRows) {
+    sh.slot[tid] = c.slot_state[parity * kTinyRows + tid];
+    sh.cnt[tid] = c.slot_count[parity * kTinyRows + tid];
+  }
+  const int n0 = blockIdx.x * kTinyCols;
+  const int kq = Hj >> 2, k0 = wave * kq, nk = kq >> 4;   // Hj % 64 == 0, so kq % 16 == 0
+  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
+  bf16x8 bpre[kTinyPrefetch];
+#pragma unroll
+  for (int i = 0; i < kTinyPrefetch; ++i)
+    if (i < nk) bpre[i] = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
+  for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
   if (na == 0) {
     if (blockIdx.x == 0 && tid == 0) c.n_active[parity ^ 1] = 0;
     return;
   }
-  const int n_rows = na * c.W, Hj = m.Hj, W = c.W;
+  __syncthreads();
+  const int n_rows = na * W;
   const int RB = (n_rows + 31) >> 5;                 // 32-row blocks in use (1 or 2)
   const int zstride = Hj + 8;                        // bf16 elements; odd number of 16-byte units
   bf16_t *zs = reinterpret_cast<bf16_t *>(smem_raw);
-  // phase 1: window rows into LDS; workgroup 0 also computes the fp32 blank logits and |z|
+  // round trip 2: window rows into LDS, with their fp32 blank logit and norm
   for (int row = wave; row < RB * 32; row += 4) {
     bool valid = false;
     const float *er = nullptr, *pr = nullptr;
     if (row < n_rows) {
       const int a = row / W, j = row - a * W;
-      const int b = c.active_idx[parity * c.B + a];
-      const int tt = c.t[b] + j;
-      valid = tt < c.len[b];
-      er = c.e + ((size_t)b * c.T + (valid ? tt : 0)) * Hj;
-      pr = c.p + (size_t)b * Hj;
+      const int4 st = sh.slot[a];
+      valid = st.y + j < st.z;
+      er = c.e + ((size_t)st.x * c.T + (valid ? st.y + j : 0)) * Hj;
+      pr = c.p + (size_t)st.x * Hj;
     }
     float dot = 0.f, nrm = 0.f;
     for (int k = lane * 4; k < Hj; k += 256) {
@@ -685,36 +737,41 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
         x.z = fmaxf(ev.z + pv.z, 0.f); x.w = fmaxf(ev.w + pv.w, 0.f);
       }
       *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
-      if (blockIdx.x == 0) {
-        const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
-        dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
-        nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
-      }
+      const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
+      dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
+      nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
     }
-    if (blockIdx.x == 0 && row < n_rows) {
+    if (row < n_rows) {
       dot = wave_sum(dot);
       nrm = wave_sum(nrm);
-      if (lane == 0) { c.blank_logit[row] = dot + m.b_out[m.V]; c.znorm[row] = sqrtf(nrm); }
+      if (lane == 0) { sh.blank[row] = dot + m.b_out[m.V]; sh.znorm[row] = sqrtf(nrm); }
     }
   }
   __syncthreads();
-  // phase 2: this wave's quarter of K, 32 columns, RB row blocks
-  const int n0 = blockIdx.x * kTinyCols;
-  const int kq = Hj >> 2, k0 = wave * kq;           // Hj % 64 == 0, so kq % 16 == 0
+  // this wave's quarter of K, 32 columns, RB row blocks
   f32x16 acc[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
-  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
   const bf16_t *zrow = zs + (size_t)(lane & 31) * zstride + k0 + (lane >> 5) * 8;
-#pragma unroll 4
-  for (int ks = 0; ks < kq; ks += 16) {
-    const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(wrow + ks);
-    const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + ks);
+#pragma unroll
+  for (int i = 0; i < kTinyPrefetch; ++i) {
+    if (i < nk) {
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bpre[i], acc[0], 0, 0, 0);
+      if (RB > 1) {
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(zrow + 32 * zstride + i * 16);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bpre[i], acc[1], 0, 0, 0);
+      }
+    }
+  }
+  for (int i = kTinyPrefetch; i < nk; ++i) {   // Hj > 1024
+    const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
+    const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
     acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag, acc[0], 0, 0, 0);
     if (RB > 1) {
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(zrow + 32 * zstride + ks);
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(zrow + 32 * zstride + i * 16);
       acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfrag, acc[1], 0, 0, 0);
     }
   }
@@ -744,7 +801,7 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
     const int row = rb * 32 + acc_row(0, s, lane);
     c.parts[(size_t)row * c.nparts_tiny + blockIdx.x] = make_float2(o1[0], o2[0]);
   }
-  // phase 3: the last workgroup decides
+  // the last workgroup to get here decides, from the keys in memory and the state it holds in LDS
   __syncthreads();
   if (tid == 0) {
     __threadfence();
@@ -754,11 +811,9 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
   __syncthreads();
   if (!sh.is_last) return;
   __threadfence();
-  for (int a = 0; a < na; ++a) decide_utterance<WT>(m, c, parity, a, 0, c.nparts_tiny, kTinyCols, sh);
-  __threadfence();
-  __syncthreads();
+  for (int a = 0; a < na; ++a) decide_utterance<WT, true>(m, c, parity, a, 0, c.nparts_tiny, kTinyCols, sh);
   if (tid < 64) {
-    compact_lists(c, parity, na, sh);
+    compact_lists<true>(c, parity, na, sh);
     if (tid == 0) c.ticket[1] = 0u;
   }
 }
@@ -883,6 +938,185 @@ __global__ __launch_bounds__(256) void pred_proj_kernel(ModelDev m, CallDev c) {
     for (int r = 0; r < R; ++r) {
       acc[r] = wave_sum(acc[r]);
       if (lane == r && r0 + r < n_emit) c.p[(size_t)ub[r] * m.Hj + j] = acc[r] + m.b_pred[j];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Low-latency prediction network for a handful of emitting utterances (bf16 models).  The cost of
+// a step at batch 1 is not arithmetic but dependent memory round trips, about a microsecond each
+// on this chip, so these kernels are built to need two: first the emit list (count, utterance ids
+// and tokens, read side by side), then everything else at once: each lane's share of the weight
+// rows as 16-byte loads, the input / hidden vectors, the cell state.
+constexpr int kSmallKSteps = 4;   // lanes cover K in steps of 512: K = in + Hp <= 2048
+
+__device__ __forceinline__ void unpack_bf16x8(const u32x4 &v, float (&o)[8]) {
+  o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void lstm_small_kernel(ModelDev m, CallDev c, int layer) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int unit = blockIdx.x * 4 + wave;
+  const int Hp = m.Hp, in = layer == 0 ? m.E : Hp, K = in + Hp;
+  const size_t lofs = (size_t)layer * c.B * Hp;
+  // round trip 1: the emit list (entries past n_emit hold valid, stale ids: harmless to read)
+  const int n_emit = *c.n_emit;
+  int ub0[R], tok0[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int idx = r < c.B ? r : c.B - 1;
+    ub0[r] = c.emit_idx[idx];
+    tok0[r] = c.emit_list_tok[idx];
+  }
+  // weights do not depend on the list: they go out in the same breath
+  const bf16_t *w = reinterpret_cast<const bf16_t *>(m.w_cat[layer]) + (size_t)(unit < Hp ? unit : 0) * 4 * K;
+  u32x4 wv[4][kSmallKSteps];
+#pragma unroll
+  for (int s2 = 0; s2 < kSmallKSteps; ++s2) {
+    const int k = lane * 8 + 512 * s2;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      wv[g][s2] = u32x4{0u, 0u, 0u, 0u};
+      if (k < K) wv[g][s2] = *reinterpret_cast<const u32x4 *>(w + (size_t)g * K + k);
+    }
+  }
+  if (n_emit == 0 || unit >= Hp) return;
+  const float *bias = m.b_cat[layer] + unit * 4;
+  for (int r0 = 0; r0 < n_emit; r0 += R) {
+    int ub[R], tok[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (r0 == 0) { ub[r] = ub0[r]; tok[r] = tok0[r]; }
+      else { const int idx = min(r0 + r, n_emit - 1); ub[r] = c.emit_idx[idx]; tok[r] = c.emit_list_tok[idx]; }
+    }
+    // round trip 2: inputs, previous hidden vectors, cell state
+    float xv[R][kSmallKSteps][8];
+    float cprev[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const size_t si = lofs + (size_t)ub[r] * Hp;
+      cprev[r] = c.c[si + unit];
+#pragma unroll
+      for (int s2 = 0; s2 < kSmallKSteps; ++s2) {
+        const int k = lane * 8 + 512 * s2;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) xv[r][s2][q] = 0.f;
+        if (k < in) {
+          if (layer == 0) {
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.emb) + (size_t)tok[r] * m.E + k);
+            unpack_bf16x8(raw, xv[r][s2]);
+          } else {
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(c.hn + si - (size_t)c.B * Hp + k);
+            const f32x4 a = src[0], b2 = src[1];
+            xv[r][s2][0] = a.x; xv[r][s2][1] = a.y; xv[r][s2][2] = a.z; xv[r][s2][3] = a.w;
+            xv[r][s2][4] = b2.x; xv[r][s2][5] = b2.y; xv[r][s2][6] = b2.z; xv[r][s2][7] = b2.w;
+          }
+        } else if (k < K) {
+          const f32x4 *src = reinterpret_cast<const f32x4 *>(c.h + si + (k - in));
+          const f32x4 a = src[0], b2 = src[1];
+          xv[r][s2][0] = a.x; xv[r][s2][1] = a.y; xv[r][s2][2] = a.z; xv[r][s2][3] = a.w;
+          xv[r][s2][4] = b2.x; xv[r][s2][5] = b2.y; xv[r][s2][6] = b2.z; xv[r][s2][7] = b2.w;
+        }
+      }
+    }
+    float acc[4][R];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int r = 0; r < R; ++r) acc[g][r] = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < kSmallKSteps; ++s2)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float wf[8];
+        unpack_bf16x8(wv[g][s2], wf);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc[g][r] = fmaf(wf[q], xv[r][s2][q], acc[g][r]);
+      }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g][r] = wave_sum(acc[g][r]);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (lane == r && r0 + r < n_emit) {
+        const size_t si = lofs + (size_t)ub[r] * Hp + unit;
+        const float ig = 1.f / (1.f + expf(-(acc[0][r] + bias[0])));
+        const float fg = 1.f / (1.f + expf(-(acc[1][r] + bias[1])));
+        const float gg = tanhf(acc[2][r] + bias[2]);
+        const float og = 1.f / (1.f + expf(-(acc[3][r] + bias[3])));
+        const float cn = fg * cprev[r] + ig * gg;
+        c.c[si] = cn;
+        c.hn[si] = og * tanhf(cn);
+      }
+    }
+  }
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void pred_small_kernel(ModelDev m, CallDev c) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int Hp = m.Hp, j = blockIdx.x * 4 + wave;
+  const int n_emit = *c.n_emit;
+  int ub0[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) ub0[r] = c.emit_idx[r < c.B ? r : c.B - 1];
+  const bf16_t *w = reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)(j < m.Hj ? j : 0) * Hp;
+  u32x4 wv[kSmallKSteps];
+#pragma unroll
+  for (int s2 = 0; s2 < kSmallKSteps; ++s2) {
+    const int k = lane * 8 + 512 * s2;
+    wv[s2] = u32x4{0u, 0u, 0u, 0u};
+    if (k < Hp) wv[s2] = *reinterpret_cast<const u32x4 *>(w + k);
+  }
+  if (n_emit == 0) return;
+  {  // commit the new hidden vectors: every layer has read the old ones by now
+    const size_t total = (size_t)m.L * n_emit * Hp;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+      const int k = (int)(i % Hp);
+      const size_t q = i / Hp;
+      const int r = (int)(q % n_emit), l = (int)(q / n_emit);
+      const size_t si = ((size_t)l * c.B + c.emit_idx[r]) * Hp + k;
+      c.h[si] = c.hn[si];
+    }
+  }
+  if (j >= m.Hj) return;
+  const float *htop = c.hn + (size_t)(m.L - 1) * c.B * Hp;
+  const float bias = m.b_pred[j];
+  for (int r0 = 0; r0 < n_emit; r0 += R) {
+    float acc[R];
+    int ub[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      ub[r] = r0 == 0 ? ub0[r] : c.emit_idx[min(r0 + r, n_emit - 1)];
+      acc[r] = 0.f;
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < kSmallKSteps; ++s2) {
+      const int k = lane * 8 + 512 * s2;
+      float wf[8];
+      unpack_bf16x8(wv[s2], wf);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        if (k < Hp) {
+          const f32x4 *src = reinterpret_cast<const f32x4 *>(htop + (size_t)ub[r] * Hp + k);
+          const f32x4 a = src[0], b2 = src[1];
+          acc[r] = fmaf(wf[0], a.x, acc[r]); acc[r] = fmaf(wf[1], a.y, acc[r]); acc[r] = fmaf(wf[2], a.z, acc[r]);
+          acc[r] = fmaf(wf[3], a.w, acc[r]); acc[r] = fmaf(wf[4], b2.x, acc[r]); acc[r] = fmaf(wf[5], b2.y, acc[r]);
+          acc[r] = fmaf(wf[6], b2.z, acc[r]); acc[r] = fmaf(wf[7], b2.w, acc[r]);
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      acc[r] = wave_sum(acc[r]);
+      if (lane == r && r0 + r < n_emit) c.p[(size_t)ub[r] * m.Hj + j] = acc[r] + bias;
     }
   }
 }
