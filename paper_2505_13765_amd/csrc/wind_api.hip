@@ -80,6 +80,7 @@ struct wind_model {
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_joint_split_rows = kJointSplitRows;
   int opt_tiny_rows = kTinyRowsDefault;
+  int opt_debug_stamps = 0;
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
@@ -156,6 +157,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   const size_t o_parts = take(Mpad * (size_t)(nparts_tiny > nparts ? nparts_tiny : nparts) * 8);
   const size_t o_rl = take(Mpad * 4);
   const size_t o_stats = take(kNumStats * 8);
+  const size_t o_dbg = take(64);
   if (off > m->ws_bytes) {
     HIP_TRY(hipDeviceSynchronize());
     if (m->ws) HIP_TRY(hipFree(m->ws));
@@ -191,6 +193,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.nparts_tiny = nparts_tiny;
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
+  c.dbg = m->opt_debug_stamps ? (long long *)(base + o_dbg) : nullptr;
   return WIND_OK;
 }
 
@@ -287,8 +290,7 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
 
 // the fused few-rows kernel keeps all window rows in LDS
 bool tiny_rows_ok(const wind_model *m, int max_rows) {
-  const int cap = m->dev.Hj <= 1024 ? 64 : 32;
-  return max_rows <= (m->opt_tiny_rows < cap ? m->opt_tiny_rows : cap);
+  return m->dev.Hj <= kTinyMaxHj && max_rows <= m->opt_tiny_rows;
 }
 size_t tiny_smem_bytes(const ModelDev &d, int max_rows) {
   const size_t z = (size_t)((max_rows + 31) / 32) * 32 * (d.Hj + 8) * 2;
@@ -380,6 +382,13 @@ int fetch_stats(wind_model *m, hipStream_t s) {
   st.rechecks = (int64_t)h[ST_RECHECK];
   for (int i = 0; i <= WIND_MAX_WINDOW; ++i) st.jump_hist[i] = (int64_t)h[kStatJump0 + i];
   m->have_stats = true;
+  if (m->call.dbg) {
+    long long d[8];
+    if (hipMemcpy(d, m->call.dbg, sizeof(d), hipMemcpyDeviceToHost) == hipSuccess && d[5] > 0)
+      std::fprintf(stderr, "[wind debug] few-rows kernel, deciding workgroup, avg us: setup+gather %.2f  mfma+keys %.2f  hand-over %.2f  decide %.2f  compact %.2f  (%lld launches)\n",
+                   d[0] / 100.0 / d[5], d[1] / 100.0 / d[5], d[2] / 100.0 / d[5], d[3] / 100.0 / d[5], d[4] / 100.0 / d[5], d[5]);
+    (void)hipMemset(m->call.dbg, 0, 64);
+  }
   return h[ST_OVERFLOW] ? WIND_ERR_OVERFLOW : WIND_OK;
 }
 
@@ -609,6 +618,11 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "unroll")) {
     if (value < 2 || value > 256 || (value & 1)) return fail(WIND_ERR_ARG, "unroll must be even, 2..256");
     m->opt_unroll = (int)value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "debug_stamps")) {
+    m->opt_debug_stamps = value != 0;
+    m->graph_valid = false;
     return WIND_OK;
   }
   if (!std::strcmp(key, "tiny_rows")) {

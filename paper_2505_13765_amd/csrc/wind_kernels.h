@@ -76,6 +76,7 @@ struct CallDev {
   int nparts_tiny;              // parts per row of the few-rows kernel (32 columns each)
   int *row_label;               // [Mpad] (fp32 models)
   unsigned long long *stats;    // [kNumStats]
+  long long *dbg;               // optional [8] phase time stamps of the few-rows kernel's deciding workgroup (100 MHz clock)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -457,13 +458,16 @@ struct DecideShared {
 
 // Label of one window row, decided by a whole wave: argmax over the row's keys, with every key
 // inside the near-tie band re-evaluated in fp32 (see the header comment of this file).
+// kk0 = this lane's keys of the row for part `lane` (the caller loads them, possibly for several
+// rows at once so that the loads overlap); parts 64 and up are read here.
 template <class WT>
 __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
-                                          int nparts, int part_width, float vblank, float znorm, int &n_recheck) {
+                                          int nparts, int part_width, float vblank, float znorm, float2 kk0,
+                                          int &n_recheck) {
   const int lane = threadIdx.x & 63, V = m.V;
-  // keys of this row: lane i holds part i (and i + 64, ... for wide vocabularies)
-  float k1 = kKeyNone;
-  for (int pi = lane; pi < nparts; pi += 64) k1 = fmaxf(k1, c.parts[(size_t)row * nparts + pi].x);
+  const float2 *prow = c.parts + (size_t)row * nparts;
+  float k1 = kk0.x;
+  for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, prow[pi].x);
   const float kbest = wave_max_f32(k1);
   const float vbest = key_val(kbest);
   const float top = fmaxf(vbest, vblank);
@@ -471,18 +475,18 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
   const float thresh = top - tau;
   if (vbest < thresh) return V;                  // blank clear of every label
   // how many label keys are inside the band?
-  int cnt = 0;
-  for (int pi = lane; pi < nparts; pi += 64) {
-    const float2 kk = c.parts[(size_t)row * nparts + pi];
+  int cnt = (key_val(kk0.x) >= thresh) + (key_val(kk0.y) >= thresh);
+  for (int pi = lane + 64; pi < nparts; pi += 64) {
+    const float2 kk = prow[pi];
     cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
   }
 #pragma unroll
   for (int msk = 32; msk >= 1; msk >>= 1) cnt += __shfl_xor(cnt, msk, kWave);
   if (cnt == 1 && vblank < thresh) {
     // a single label clear of blank and of every other label: find its part
-    int col = -1;
-    for (int pi = lane; pi < nparts; pi += 64)
-      if (c.parts[(size_t)row * nparts + pi].x == kbest) col = pi * part_width + key_col(kbest);
+    int col = kk0.x == kbest ? lane * part_width + key_col(kbest) : -1;
+    for (int pi = lane + 64; pi < nparts; pi += 64)
+      if (prow[pi].x == kbest) col = pi * part_width + key_col(kbest);
     return wave_max_i32(col);
   }
   // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
@@ -506,11 +510,12 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
   for (int p0 = 0; p0 < nparts; p0 += 64) {
     const int pi = p0 + lane;
     float2 kk = make_float2(kKeyNone, kKeyNone);
-    if (pi < nparts) kk = c.parts[(size_t)row * nparts + pi];
+    if (p0 == 0) kk = kk0;
+    else if (pi < nparts) kk = prow[pi];
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
       const float key = which ? kk.y : kk.x;
-      unsigned long long mask = __ballot(pi < nparts && key_val(key) >= thresh);
+      unsigned long long mask = __ballot(key_val(key) >= thresh);
       while (mask) {
         const int src = __ffsll((long long)mask) - 1;
         mask &= mask - 1;
@@ -537,15 +542,34 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
   int n_recheck = 0;
   if (threadIdx.x == 0) sh.recheck = 0;
   __syncthreads();
-  for (int j = wave; j < c.W; j += nwaves) {
+  // the first 64 parts' keys of this wave's rows, requested together so that the loads overlap
+  constexpr int kRowsAhead = 4;
+  float2 kk0[kRowsAhead];
+#pragma unroll
+  for (int q = 0; q < kRowsAhead; ++q) {
+    const int j = wave + q * nwaves;
+    kk0[q] = make_float2(kKeyNone, kKeyNone);
+    if (!exact_mode && j < n && lane < nparts) kk0[q] = c.parts[(size_t)(a * c.W + j) * nparts + lane];
+  }
+  auto one_row = [&](int j, float2 k0) {
     int label = V;
     if (j < n) {
       const int row = a * c.W + j;
       if (exact_mode) label = c.row_label[row];
       else label = decide_row<WT>(m, c, row, b, t + j, nparts, part_width, LOCAL ? sh.blank[row] : c.blank_logit[row],
-                                  LOCAL ? sh.znorm[row] : c.znorm[row], n_recheck);
+                                  LOCAL ? sh.znorm[row] : c.znorm[row], k0, n_recheck);
     }
     if (lane == 0) sh.label[j] = label;
+  };
+#pragma unroll
+  for (int q = 0; q < kRowsAhead; ++q) {
+    const int j = wave + q * nwaves;
+    if (j < c.W) one_row(j, kk0[q]);
+  }
+  for (int j = wave + kRowsAhead * nwaves; j < c.W; j += nwaves) {
+    float2 k0 = make_float2(kKeyNone, kKeyNone);
+    if (!exact_mode && j < n && lane < nparts) k0 = c.parts[(size_t)(a * c.W + j) * nparts + lane];
+    one_row(j, k0);
   }
   if (lane == 0 && n_recheck) atomicAdd(&sh.recheck, n_recheck);
   __syncthreads();
@@ -684,6 +708,7 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
 // from memory into registers (no staging, no barrier inside the K loop), and writes the rows' keys;
 // the last workgroup to finish takes the decisions for every utterance and rebuilds the lists.
 constexpr int kTinyCols = 32;
+constexpr int kTinyMaxHj = 1024;    // the window rows of the few-rows kernel live in registers, then LDS
 constexpr int kTinyPrefetch = 16;   // W_out fragments (K steps of 16) a wave requests before anything else
 template <class WT>
 __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, int parity) {
@@ -694,6 +719,7 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
   // round trip 1, all independent: the active count, the slot table (utterance, t, len, sym, count
   // per active slot, written by the previous iteration's compaction), and this wave's W_out
   // fragments for its quarter of K
+  const long long ts0 = c.dbg ? wall_clock64() : 0;
   const int na = c.n_active[parity];
   if (tid < kTinyRows) {
     sh.slot[tid] = c.slot_state[parity * kTinyRows + tid];
@@ -716,38 +742,61 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
   const int RB = (n_rows + 31) >> 5;                 // 32-row blocks in use (1 or 2)
   const int zstride = Hj + 8;                        // bf16 elements; odd number of 16-byte units
   bf16_t *zs = reinterpret_cast<bf16_t *>(smem_raw);
-  // round trip 2: window rows into LDS, with their fp32 blank logit and norm
-  for (int row = wave; row < RB * 32; row += 4) {
-    bool valid = false;
-    const float *er = nullptr, *pr = nullptr;
-    if (row < n_rows) {
-      const int a = row / W, j = row - a * W;
-      const int4 st = sh.slot[a];
-      valid = st.y + j < st.z;
-      er = c.e + ((size_t)st.x * c.T + (valid ? st.y + j : 0)) * Hj;
-      pr = c.p + (size_t)st.x * Hj;
-    }
-    float dot = 0.f, nrm = 0.f;
-    for (int k = lane * 4; k < Hj; k += 256) {
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (valid) {
-        const float4 ev = *reinterpret_cast<const float4 *>(er + k);
-        const float4 pv = *reinterpret_cast<const float4 *>(pr + k);
-        x.x = fmaxf(ev.x + pv.x, 0.f); x.y = fmaxf(ev.y + pv.y, 0.f);
-        x.z = fmaxf(ev.z + pv.z, 0.f); x.w = fmaxf(ev.w + pv.w, 0.f);
+  // round trip 2: window rows into LDS, with their fp32 blank logit and norm.  A wave takes rows
+  // wave, wave + 4, ...; the loads of four rows go out together so that they share one round trip.
+  constexpr int KI = kTinyMaxHj / 256;   // float4 per lane per row
+  for (int q0 = 0; q0 < RB * 8; q0 += 4) {
+    float4 ev[4][KI], pv[4][KI];
+    bool valid[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = wave + 4 * (q0 + q);
+      valid[q] = false;
+      const float *er = c.e, *pr = c.p;
+      if (row < n_rows) {
+        const int a = row / W, j = row - a * W;
+        const int4 st = sh.slot[a];
+        valid[q] = st.y + j < st.z;
+        er = c.e + ((size_t)st.x * c.T + (valid[q] ? st.y + j : 0)) * Hj;
+        pr = c.p + (size_t)st.x * Hj;
       }
-      *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
-      const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
-      dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
-      nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+#pragma unroll
+      for (int i = 0; i < KI; ++i) {
+        const int k = lane * 4 + 256 * i;
+        ev[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        pv[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (valid[q] && k < Hj) {
+          ev[q][i] = *reinterpret_cast<const float4 *>(er + k);
+          pv[q][i] = *reinterpret_cast<const float4 *>(pr + k);
+        }
+      }
     }
-    if (row < n_rows) {
-      dot = wave_sum(dot);
-      nrm = wave_sum(nrm);
-      if (lane == 0) { sh.blank[row] = dot + m.b_out[m.V]; sh.znorm[row] = sqrtf(nrm); }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = wave + 4 * (q0 + q);
+      float dot = 0.f, nrm = 0.f;
+#pragma unroll
+      for (int i = 0; i < KI; ++i) {
+        const int k = lane * 4 + 256 * i;
+        if (k < Hj) {
+          float4 x;
+          x.x = fmaxf(ev[q][i].x + pv[q][i].x, 0.f); x.y = fmaxf(ev[q][i].y + pv[q][i].y, 0.f);
+          x.z = fmaxf(ev[q][i].z + pv[q][i].z, 0.f); x.w = fmaxf(ev[q][i].w + pv[q][i].w, 0.f);
+          *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+          const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
+          dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
+          nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+        }
+      }
+      if (row < n_rows) {
+        dot = wave_sum(dot);
+        nrm = wave_sum(nrm);
+        if (lane == 0) { sh.blank[row] = dot + m.b_out[m.V]; sh.znorm[row] = sqrtf(nrm); }
+      }
     }
   }
   __syncthreads();
+  const long long ts1 = c.dbg ? wall_clock64() : 0;
   // this wave's quarter of K, 32 columns, RB row blocks
   f32x16 acc[2];
 #pragma unroll
@@ -803,6 +852,7 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
   }
   // the last workgroup to get here decides, from the keys in memory and the state it holds in LDS
   __syncthreads();
+  const long long ts2 = c.dbg ? wall_clock64() : 0;
   if (tid == 0) {
     __threadfence();
     const unsigned tk = atomicAdd(c.ticket + 1, 1u);
@@ -811,10 +861,16 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
   __syncthreads();
   if (!sh.is_last) return;
   __threadfence();
+  const long long ts3 = c.dbg ? wall_clock64() : 0;
   for (int a = 0; a < na; ++a) decide_utterance<WT, true>(m, c, parity, a, 0, c.nparts_tiny, kTinyCols, sh);
+  const long long ts4 = c.dbg ? wall_clock64() : 0;
   if (tid < 64) {
     compact_lists<true>(c, parity, na, sh);
     if (tid == 0) c.ticket[1] = 0u;
+  }
+  if (c.dbg && tid == 0) {
+    const long long ts5 = wall_clock64();
+    c.dbg[0] += ts1 - ts0; c.dbg[1] += ts2 - ts1; c.dbg[2] += ts3 - ts2; c.dbg[3] += ts4 - ts3; c.dbg[4] += ts5 - ts4; c.dbg[5] += 1;
   }
 }
 
