@@ -63,6 +63,18 @@ def run_workload(torch, wi, WindModel, name, windows, steps, warmup, with_sequen
     return cfg, model, (d_enc, d_len, out), frames, res, (enc, lens, w)
 
 
+def measured_traffic(cfg, W):
+    """HBM bytes per joint launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a copy kernel of known size), if there is one for this workload."""
+    path = os.path.join(ROOT, "profiles", f"joint_hbm_traffic_{cfg.name}_w{W}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
 def roofline_leg(torch, cfg, model, dev, W):
     """Times every kernel launch of one decode with events (the library's profile mode) and prices
     the joint kernel against the bf16 MFMA peak: algorithmic flops = 2 * Hj * (V+1) per window row
@@ -82,7 +94,7 @@ def roofline_leg(torch, cfg, model, dev, W):
     return {
         "bound": "mfma", "kernel": "joint_mfma_kernel", "workload": f"{cfg.name} W={W}",
         "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-        "traffic": None, "launches": int(n), "avg_launch_us": ms * 1e3 / max(n, 1),
+        "traffic": measured_traffic(cfg, W), "launches": int(n), "avg_launch_us": ms * 1e3 / max(n, 1),
         "rows_per_launch": st.rows / max(n, 1), "flops_per_row": 2.0 * cfg.Hj * (cfg.V + 1),
         "kernel_ms": {k: round(v[0], 3) for k, v in kt.items()},
         "kernel_launches": {k: int(v[1]) for k, v in kt.items()},
@@ -125,6 +137,10 @@ def main():
     ap.add_argument("--roofline-workload", default="largevocab_b128")
     ap.add_argument("--roofline-window", type=int, default=16)
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="skip the headline workload; used under rocprofv3 --pmc, where every dispatch is serialised")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB device copy, the known-size reference for the HBM byte counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -138,6 +154,18 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.roofline_only:
+        rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload,
+                                                            [args.roofline_window], 1, 0, with_sequential=False)
+        roof = roofline_leg(torch, rcfg, rmodel, rdev, args.roofline_window)
+        print(json.dumps({"roofline": roof}))
+        return
 
     cfg, model, dev, frames, res, host = run_workload(torch, wi, WindModel, args.workload, None,
                                                       args.steps, args.warmup, with_sequential=True)

@@ -36,7 +36,7 @@ using JointBigCfg = Ring5Cfg<256, 64, 128>;             // rows > kJointSplitRow
 constexpr int kTinyRowsDefault = 64;                    // at most this many window rows: one fused kernel
 constexpr int kJointSplitRows = 1536;                   // measured crossover of the two joint kernels
 using EncCfg = TileCfg<128, 128, 64, 64>;
-using PredCfg = TileCfg<64, 64, 32, 32>;   // 32 utterances (hi and lo rows) x 64 columns
+using PredCfg = DmaCfg<64, 64, 32, 32, 64, 4>;   // 32 utterances (hi and lo rows) x 64 columns, 4-stage ring
 constexpr int kPredMfmaMinBatch = 16;      // below this the FMA prediction network is used
 constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height
 
@@ -151,6 +151,8 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   const size_t o_nemit = take(4), o_ticket = take(8);
   const size_t st = (size_t)d.L * B * d.Hp * 4;
   const size_t o_h = take(st), o_c = take(st), o_hn = take(st);
+  const size_t o_hb = take(2 * st);   // four bf16 arrays
+  const size_t o_hz = take((size_t)(d.E > d.Hp ? d.E : d.Hp) * 2 + 256);
   const size_t o_p = take((size_t)B * d.Hj * 4);
   const size_t o_z = take(Mpad * d.Hj * 2);
   const size_t o_bl = take(Mpad * 4), o_zn = take(Mpad * 4);
@@ -181,6 +183,8 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.slot_state = (int4 *)(base + o_slot); c.slot_count = (int *)(base + o_slotc);
   c.ticket = (unsigned *)(base + o_ticket);
   c.h = (float *)(base + o_h); c.c = (float *)(base + o_c); c.hn = (float *)(base + o_hn);
+  c.hb_hi = (bf16_t *)(base + o_hb); c.hb_lo = c.hb_hi + st / 4; c.hbn_hi = c.hb_lo + st / 4; c.hbn_lo = c.hbn_hi + st / 4;
+  c.hb_zero = (const bf16_t *)(base + o_hz);
   c.p = (float *)(base + o_p);
   c.z = (bf16_t *)(base + o_z);
   c.blank_logit = (float *)(base + o_bl); c.znorm = (float *)(base + o_zn);
@@ -249,8 +253,8 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
     ProfScope ps(m, s, WIND_K_LSTM, capturing);
     for (int l = 0; l < d.L; ++l) {
       if (mfma)
-        lstm_layer_mfma_kernel<PredCfg><<<dim3(mtiles, (unsigned)(4 * d.Hp / PredCfg::BN)), PredCfg::NT,
-                                          PredCfg::SMEM_BYTES, s>>>(d, c, l);
+        lstm_layer_dma_kernel<PredCfg><<<dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles), PredCfg::NT,
+                                         PredCfg::SMEM_BYTES, s>>>(d, c, l);
       else if (m->dtype == WIND_BF16 && small_k) lstm_small_kernel<2><<<lstm_blocks, 256, 0, s>>>(d, c, l);
       else if (m->dtype == WIND_BF16) lstm_layer_kernel<bf16_t, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
       else lstm_layer_kernel<float, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
@@ -259,8 +263,8 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
   {
     ProfScope ps(m, s, WIND_K_PRED_PROJ, capturing);
     if (mfma)
-      pred_proj_mfma_kernel<PredCfg><<<dim3(mtiles, (unsigned)(d.Hj / PredCfg::BN)), PredCfg::NT,
-                                       PredCfg::SMEM_BYTES, s>>>(d, c);
+      pred_proj_dma_kernel<PredCfg><<<dim3((unsigned)(d.Hj / PredCfg::BN), mtiles), PredCfg::NT,
+                                      PredCfg::SMEM_BYTES, s>>>(d, c);
     else if (m->dtype == WIND_BF16 && small_k) pred_small_kernel<2><<<proj_blocks, 256, 0, s>>>(d, c);
     else if (m->dtype == WIND_BF16) pred_proj_kernel<bf16_t, 4><<<proj_blocks, 256, 0, s>>>(d, c);
     else pred_proj_kernel<float, 4><<<proj_blocks, 256, 0, s>>>(d, c);
@@ -551,10 +555,10 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
       e = hipFuncSetAttribute((const void *)enc_proj_mfma_kernel<EncCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, EncCfg::SMEM_BYTES);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)lstm_layer_mfma_kernel<PredCfg>,
+      e = hipFuncSetAttribute((const void *)lstm_layer_dma_kernel<PredCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, PredCfg::SMEM_BYTES);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)pred_proj_mfma_kernel<PredCfg>,
+      e = hipFuncSetAttribute((const void *)pred_proj_dma_kernel<PredCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, PredCfg::SMEM_BYTES);
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e));
   }

@@ -64,6 +64,8 @@ struct CallDev {
   int *n_emit;                  // [1]
   unsigned *ticket;             // [2] workgroups done: decide_kernel, joint_tiny_kernel
   float *h, *c, *hn;            // [L][B][Hp]
+  bf16_t *hb_hi, *hb_lo, *hbn_hi, *hbn_lo;  // [L][B][Hp] large-batch path: h and new h as bf16 hi + lo
+  const bf16_t *hb_zero;        // [max(E,Hp)] zeros (the lo part of an embedding row)
   float *p;                     // [B][Hj]
   bf16_t *z;                    // [Mpad][Hj]
   float *blank_logit;           // [Mpad]
@@ -84,7 +86,10 @@ __global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) 
   const int tid = threadIdx.x;
   for (int i = tid; i < kNumStats; i += 256) c.stats[i] = 0ull;
   const size_t nstate = (size_t)m.L * c.B * m.Hp;
-  for (size_t i = tid; i < nstate; i += 256) { c.h[i] = 0.f; c.c[i] = 0.f; c.hn[i] = 0.f; }
+  for (size_t i = tid; i < nstate; i += 256) {
+    c.h[i] = 0.f; c.c[i] = 0.f; c.hn[i] = 0.f;
+    c.hb_hi[i] = 0; c.hb_lo[i] = 0; c.hbn_hi[i] = 0; c.hbn_lo[i] = 0;
+  }
   for (int b = tid; b < c.B; b += 256) {
     int len = c.lengths[b];
     len = len < 0 ? 0 : (len > c.T ? c.T : len);
@@ -1178,65 +1183,82 @@ __global__ __launch_bounds__(256) void pred_small_kernel(ModelDev m, CallDev c) 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Prediction network on bf16 MFMA, for batches large enough to fill tiles.  The activations are
-// fp32; each is split into hi + lo bf16 (hi = RNE(x), lo = RNE(x - hi), relative error 2^-17, the
-// size of fp32 accumulation noise over these K), products with the bf16 weights are exact and the
-// accumulation is fp32.  The split costs rows, not K: a tile's first R rows hold the hi parts of R
-// utterances, the next R rows their lo parts, and the epilogue adds the two halves.
-__device__ __forceinline__ u32x4 split_pack(const f32x4 &a, const f32x4 &b, int part) {
-  float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-  uint32_t o[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const uint32_t hi = f32_to_bf16_bits(x[q]);
-    const uint32_t lo = f32_to_bf16_bits(x[q] - bf16_bits_to_f32(hi));
-    o[q] = part ? lo : hi;
+// The prediction network for large batches on the direct-to-LDS MFMA tile core.  The activations
+// are fp32 values carried as bf16 hi + lo (hi = RNE(x), lo = RNE(x - hi): relative error 2^-17,
+// the size of fp32 accumulation noise over these K); products with the bf16 weights are exact and
+// the accumulation is fp32.  The split costs rows, not K.  Hidden vectors are kept in memory
+// already split (hb_*), so the GEMM operands are plain bf16 rows that the loads can fetch without
+// a conversion pass; rows are gathered through the
+// emit list by giving every lane its own source address.  A tile's first R rows are the hi parts
+// of R utterances, the next R rows their lo parts; K runs over [x | h_prev].
+template <class Cfg>
+struct PredRows {
+  const bf16_t *px[Cfg::LPW];   // x part at K = 0 (embedding row, or hi/lo of the layer below, or zeros)
+  const bf16_t *ph[Cfg::LPW];   // h part at K = in
+  int xstep[Cfg::LPW];          // 1: advance with K; 0: the shared zero row
+  int kin;                      // K steps of the x part
+  __device__ __forceinline__ const bf16_t *operator()(int i, int, int, int kt, int BK) const {
+    return kt < kin ? px[i] + kt * BK * xstep[i] : ph[i] + (kt - kin) * BK;
   }
-  u32x4 r;
-  r.x = o[0] | (o[1] << 16); r.y = o[2] | (o[3] << 16); r.z = o[4] | (o[5] << 16); r.w = o[6] | (o[7] << 16);
-  return r;
+};
+
+__device__ __forceinline__ void store_hi_lo(bf16_t *hi, bf16_t *lo, size_t idx, float v) {
+  const uint32_t h = f32_to_bf16_bits(v);
+  hi[idx] = (bf16_t)h;
+  lo[idx] = (bf16_t)f32_to_bf16_bits(v - bf16_bits_to_f32(h));
 }
 
-// Gate columns of w_cat_t are grouped per tile: column n0 + g*UB + u is gate g of unit n0/4 + u
-// (UB = BN/4), so one tile holds all four gates of its UB units.
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void lstm_layer_mfma_kernel(ModelDev m, CallDev c, int layer) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+__global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, CallDev c, int layer) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
   const int n_emit = *c.n_emit;
-  const int row0 = blockIdx.x * R;
+  // grid = (column tiles, row tiles): workgroups with consecutive ids share the row tile, and the
+  // row tiles of one column tile land on the same XCD (id mod 8), which then fetches that slice of
+  // the weights once
+  const int row0 = blockIdx.y * R;
   if (row0 >= n_emit) return;
-  const int n0 = blockIdx.y * Cfg::BN;
+  const int n0 = blockIdx.x * Cfg::BN;
   const int Hp = m.Hp, in = layer == 0 ? m.E : Hp, K = in + Hp;
   const size_t lofs = (size_t)layer * c.B * Hp;
-  const int tid = threadIdx.x;
-  const bf16_t *src_e[Cfg::A_PER_T];
-  const float *src_x[Cfg::A_PER_T], *src_h[Cfg::A_PER_T];
-  int part[Cfg::A_PER_T];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  PredRows<Cfg> rows;
+  rows.kin = in / Cfg::BK;
 #pragma unroll
-  for (int i = 0; i < Cfg::A_PER_T; ++i) {
-    const int row = (tid + i * Cfg::NT) >> 3;
-    part[i] = row >= R;
-    const int ub = c.emit_idx[min(row0 + row - part[i] * R, n_emit - 1)];
-    src_e[i] = reinterpret_cast<const bf16_t *>(m.emb) + (size_t)c.emit_tok[ub] * m.E;
-    src_x[i] = c.hn + (layer == 0 ? 0 : lofs - (size_t)c.B * Hp) + (size_t)ub * Hp;
-    src_h[i] = c.h + lofs + (size_t)ub * Hp;
-  }
-  auto aload = [&](int i, int, int k) -> u32x4 {
-    if (k < in && layer == 0) {               // embedding rows are bf16 already: lo part is zero
-      u32x4 raw = *reinterpret_cast<const u32x4 *>(src_e[i] + k);
-      u32x4 zero = {0u, 0u, 0u, 0u};
-      return part[i] ? zero : raw;
+  for (int i = 0; i < Cfg::LPW; ++i) {
+    const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
+    const int chunk = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
+    rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
+    if (row < Cfg::BM) {
+      const int part = row >= R;
+      const int r = row - part * R;
+      const int ub = c.emit_idx[min(row0 + r, n_emit - 1)];
+      const size_t si = lofs + (size_t)ub * Hp;
+      if (layer == 0) {
+        if (!part) {
+          rows.px[i] = reinterpret_cast<const bf16_t *>(m.emb) + (size_t)c.emit_list_tok[min(row0 + r, n_emit - 1)] * m.E + chunk * 8;
+          rows.xstep[i] = 1;
+        } else {
+          rows.px[i] = c.hb_zero + chunk * 8;
+        }
+      } else {
+        rows.px[i] = (part ? c.hbn_lo : c.hbn_hi) + si - (size_t)c.B * Hp + chunk * 8;
+        rows.xstep[i] = 1;
+      }
+      rows.ph[i] = (part ? c.hb_lo : c.hb_hi) + si + chunk * 8;
     }
-    const f32x4 *src = reinterpret_cast<const f32x4 *>(k < in ? src_x[i] + k : src_h[i] + (k - in));
-    return split_pack(src[0], src[1], part[i]);
-  };
+  }
   f32x16 acc[Cfg::MI][Cfg::NI];
-  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_cat_t[layer]) + (size_t)n0 * K, K, smem, acc);
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+  gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_cat_t[layer]) + (size_t)n0 * K, K, smem_raw, acc);
+  __syncthreads();   // every wave is done with the ring: reuse it for the gate tile
 
   float *tile = reinterpret_cast<float *>(smem_raw);
-  const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 #pragma unroll
   for (int mi = 0; mi < Cfg::MI; ++mi)
@@ -1261,19 +1283,18 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_mfma_kernel(ModelDev m, Ca
     const float og = 1.f / (1.f + expf(-go));
     const float cn = fg * c.c[si] + ig * tanhf(gg);
     c.c[si] = cn;
-    c.hn[si] = og * tanhf(cn);
+    store_hi_lo(c.hbn_hi, c.hbn_lo, si, og * tanhf(cn));
   }
 }
 
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void pred_proj_mfma_kernel(ModelDev m, CallDev c) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+__global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, CallDev c) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   constexpr int R = Cfg::BM / 2, TS = Cfg::BN + 4;
   const int n_emit = *c.n_emit;
   if (n_emit == 0) return;
-  const int Hp = m.Hp, tid = threadIdx.x;
-  {  // commit the new hidden vectors: every layer has read the old ones by now
+  const int Hp = m.Hp, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  {  // commit the new hidden vectors (hi and lo): every layer has read the old ones by now
     const size_t total = (size_t)m.L * n_emit * Hp;
     const size_t nthreads = (size_t)gridDim.x * gridDim.y * Cfg::NT;
     for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * Cfg::NT + tid; i < total; i += nthreads) {
@@ -1281,29 +1302,40 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_mfma_kernel(ModelDev m, Cal
       const size_t q = i / Hp;
       const int r = (int)(q % n_emit), l = (int)(q / n_emit);
       const size_t si = ((size_t)l * c.B + c.emit_idx[r]) * Hp + k;
-      c.h[si] = c.hn[si];
+      c.hb_hi[si] = c.hbn_hi[si];
+      c.hb_lo[si] = c.hbn_lo[si];
     }
   }
-  const int row0 = blockIdx.x * R;
+  // grid = (column tiles, row tiles): workgroups with consecutive ids share the row tile, and the
+  // row tiles of one column tile land on the same XCD (id mod 8), which then fetches that slice of
+  // the weights once
+  const int row0 = blockIdx.y * R;
   if (row0 >= n_emit) return;
-  const int n0 = blockIdx.y * Cfg::BN;
-  const float *htop = c.hn + (size_t)(m.L - 1) * c.B * Hp;
-  const float *src[Cfg::A_PER_T];
-  int part[Cfg::A_PER_T];
+  const int n0 = blockIdx.x * Cfg::BN;
+  const size_t top = (size_t)(m.L - 1) * c.B * Hp;
+  PredRows<Cfg> rows;
+  rows.kin = 0;
 #pragma unroll
-  for (int i = 0; i < Cfg::A_PER_T; ++i) {
-    const int row = (tid + i * Cfg::NT) >> 3;
-    part[i] = row >= R;
-    src[i] = htop + (size_t)c.emit_idx[min(row0 + row - part[i] * R, n_emit - 1)] * Hp;
+  for (int i = 0; i < Cfg::LPW; ++i) {
+    const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
+    const int chunk = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
+    rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
+    if (row < Cfg::BM) {
+      const int part = row >= R;
+      const int ub = c.emit_idx[min(row0 + row - part * R, n_emit - 1)];
+      rows.ph[i] = (part ? c.hbn_lo : c.hbn_hi) + top + (size_t)ub * Hp + chunk * 8;
+    }
   }
-  auto aload = [&](int i, int, int k) -> u32x4 {
-    const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src[i] + k);
-    return split_pack(s4[0], s4[1], part[i]);
-  };
   f32x16 acc[Cfg::MI][Cfg::NI];
-  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)n0 * Hp, Hp, smem, acc);
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+  gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)n0 * Hp, Hp, smem_raw, acc);
+  __syncthreads();
   float *tile = reinterpret_cast<float *>(smem_raw);
-  const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 #pragma unroll
   for (int mi = 0; mi < Cfg::MI; ++mi)

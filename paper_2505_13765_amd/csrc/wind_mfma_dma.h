@@ -70,27 +70,44 @@ __device__ __forceinline__ void wait_vmcnt() {
 // then: the barrier certifies that tile kt+1 has landed (every wave waited for its own loads
 // first) and that every wave has completed its LDS reads of tile kt (lgkmcnt(0) first), so the
 // stage of tile kt is refilled at once with tile kt+NSTAGE.  NSTAGE-1 tiles stay in flight.
-template <class Cfg>
-__device__ __forceinline__ void gemm_mainloop_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Bw,
-                                                  int K, unsigned char *smem,
-                                                  f32x16 (&acc)[Cfg::MI][Cfg::NI]) {
+// Where a lane finds its 16 bytes of an A load: dense rows (the joint kernel) ...
+struct DenseRows {
+  const bf16_t *base;
+  int ld;
+  __device__ __forceinline__ const bf16_t *operator()(int, int row, int chunk, int kt, int BK) const {
+    return base + (size_t)row * ld + kt * BK + chunk * 8;
+  }
+};
+
+// asrc(i, row, chunk, kt, BK) returns the global address of the 8 bf16 at K offset kt*BK + chunk*8
+// of A's row `row` (i = index of the load among the wave's LPW loads of a stage, for sources that
+// cache per-load state); it is called once per load and K step, so gathered rows or rows stitched from two
+// arrays cost a few integer operations per load, not a staging pass.
+template <class Cfg, class ASrc>
+__device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf16_t *__restrict__ Bw,
+                                                      int K, unsigned char *smem,
+                                                      f32x16 (&acc)[Cfg::MI][Cfg::NI]) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 
-  // this lane's global source for each of the wave's loads, at K offset 0
-  const bf16_t *src[Cfg::LPW];
+  // the wave's loads of a stage: rows below BM are A rows, the rest B rows
+  int lrow[Cfg::LPW], lchunk[Cfg::LPW];
+  const bf16_t *bsrc[Cfg::LPW];
 #pragma unroll
   for (int i = 0; i < Cfg::LPW; ++i) {
     const int q = wave * Cfg::LPW + i;
-    const int row = q * Cfg::RPI + lane / Cfg::CPR;
-    const int c = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
-    src[i] = (row < Cfg::BM ? A + (size_t)row * K : Bw + (size_t)(row - Cfg::BM) * K) + c * 8;
+    lrow[i] = q * Cfg::RPI + lane / Cfg::CPR;
+    lchunk[i] = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(lrow[i]);
+    bsrc[i] = Bw + (size_t)(lrow[i] - Cfg::BM) * K + lchunk[i] * 8;
   }
   auto issue = [&](int kt, int stage) {
     unsigned char *dst = smem + stage * Cfg::STAGE_BYTES + wave * Cfg::LPW * 1024;
 #pragma unroll
-    for (int i = 0; i < Cfg::LPW; ++i)
-      __builtin_amdgcn_global_load_lds((gmem_cptr *)(src[i] + kt * Cfg::BK), (lds_ptr *)(dst + i * 1024), 16, 0, 0);
+    for (int i = 0; i < Cfg::LPW; ++i) {
+      const bool is_a = (wave * Cfg::LPW + i) * Cfg::RPI < Cfg::BM;   // wave-uniform
+      const bf16_t *p = is_a ? asrc(i, lrow[i], lchunk[i], kt, Cfg::BK) : bsrc[i] + kt * Cfg::BK;
+      __builtin_amdgcn_global_load_lds((gmem_cptr *)p, (lds_ptr *)(dst + i * 1024), 16, 0, 0);
+    }
   };
 
   const int KT = K / Cfg::BK;
@@ -157,6 +174,13 @@ __device__ __forceinline__ void gemm_mainloop_dma(const bf16_t *__restrict__ A, 
     }
   }
   wait_vmcnt<0>();   // the redundant refills must not outlive the kernel's use of LDS
+}
+
+template <class Cfg>
+__device__ __forceinline__ void gemm_mainloop_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Bw,
+                                                  int K, unsigned char *smem,
+                                                  f32x16 (&acc)[Cfg::MI][Cfg::NI]) {
+  gemm_mainloop_dma_src<Cfg>(DenseRows{A, K}, Bw, K, smem, acc);
 }
 
 // ---------------------------------------------------------------------------------------------
