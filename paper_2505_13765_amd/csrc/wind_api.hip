@@ -31,14 +31,28 @@ int fail(int code, const std::string &msg) {
   } while (0)
 
 using JointCfg = TileCfg<128, 128, 64, 64>;            // debug store kernel
-using JointSmallCfg = DmaCfg<128, 128, 64, 64, 64, 2>;  // rows <= kJointSplitRows
-using JointBigCfg = Ring5Cfg<256, 64, 128>;             // rows > kJointSplitRows
+using JointRows1 = JointRowsCfg<1>::type;              // joint_rows_kernel: 128-column tiles, 64..256 rows
+using JointBigCfg = Ring5Cfg<256, 64, 128>;             // more rows than the rows kernel balances: 256 x 256 tiles
 constexpr int kTinyRowsDefault = 64;                    // at most this many window rows: one fused kernel
-constexpr int kJointSplitRows = 1536;                   // measured crossover of the two joint kernels
 using EncCfg = TileCfg<128, 128, 64, 64>;
 using PredCfg = DmaCfg<64, 64, 32, 32, 64, 4>;   // 32 utterances (hi and lo rows) x 64 columns, 4-stage ring
 constexpr int kPredMfmaMinBatch = 16;      // below this the FMA prediction network is used
-constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height
+constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height, plus one block
+
+// Row tiles of joint_rows_kernel for a vocabulary of NT 128-column tiles and at most `rows` window
+// rows: enough to cover the rows with the tallest tile, and otherwise as many as fill the 256 CUs
+// (but never more than tiles of the smallest height would need).
+int joint_rows_grid_x(int NT, int rows) {
+  const int cover = (rows + 255) / 256, fill = NT >= 256 ? 1 : 256 / NT, fine = (rows + 63) / 64;
+  const int g = fill < fine ? fill : fine;
+  return cover > g ? cover : g;
+}
+// Default hand-over point between the two joint kernels: the rows kernel keeps 256 equal
+// workgroups busy up to 256 rows per row tile.
+int joint_split_default(int V) {
+  const int NT = (V + 127) / 128, fill = NT >= 256 ? 1 : 256 / NT;
+  return 256 * (fill > 4 ? fill : 4);
+}
 
 uint16_t host_bf16(float x) {
   uint32_t u;
@@ -78,7 +92,7 @@ struct wind_model {
   bool graph_valid = false;
   int opt_graph = 1, opt_unroll = 16;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
-  int opt_joint_split_rows = kJointSplitRows;
+  int opt_joint_split_rows = -1;   // -1: joint_split_default(V)
   int opt_tiny_rows = kTinyRowsDefault;
   int opt_debug_stamps = 0;
   double kappa = 8.0;
@@ -130,9 +144,9 @@ void set_tau(wind_model *m) {
 
 int ensure_workspace(wind_model *m, int B, int T, int W) {
   const ModelDev &d = m->dev;
-  const size_t Mpad = round_up((size_t)B * W, kRowPad);
-  const int ntiles = (d.V + JointSmallCfg::BN - 1) / JointSmallCfg::BN;
-  const int nparts = ntiles * JointSmallCfg::WAVES_N;
+  const size_t Mpad = round_up((size_t)B * W, kRowPad) + kRowPad;   // a 192-row tile may run past the 256 multiple
+  const int ntiles = (d.V + JointRows1::BN - 1) / JointRows1::BN;
+  const int nparts = ntiles * JointRows1::WAVES_N;
   const int nparts_big = ((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN) * JointBigCfg::WAVES_N;
   const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
   size_t off = 0;
@@ -142,12 +156,12 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
     return o;
   };
   const size_t o_e = take((size_t)B * T * d.Hj * 4);
-  const size_t o_len = take((size_t)B * 4), o_t = take((size_t)B * 4), o_sym = take((size_t)B * 4);
-  const size_t o_count = take((size_t)B * 4), o_flag = take((size_t)B * 4), o_etok = take((size_t)B * 4);
-  const size_t o_event = take((size_t)B * 4);
-  const size_t o_act = take((size_t)2 * B * 4), o_nact = take(8), o_eidx = take((size_t)B * 4);
+  const int slot_stride = B > kTinyRows ? B : kTinyRows;
+  const size_t o_len = take((size_t)B * 4);
+  const size_t o_nact = take(8), o_eidx = take((size_t)B * 4);
   const size_t o_eltok = take((size_t)B * 4);
-  const size_t o_slot = take(2 * kTinyRows * 16), o_slotc = take(2 * kTinyRows * 4);
+  const size_t o_slot = take((size_t)2 * slot_stride * 16), o_slotc = take((size_t)2 * slot_stride * 4);
+  const size_t o_rst = take((size_t)B * 16), o_raux = take((size_t)B * 16);
   const size_t o_nemit = take(4), o_ticket = take(8);
   const size_t st = (size_t)d.L * B * d.Hp * 4;
   const size_t o_h = take(st), o_c = take(st), o_hn = take(st);
@@ -174,10 +188,10 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   char *base = (char *)m->ws;
   CallDev &c = m->call;
   c.e = (float *)(base + o_e);
-  c.len = (int *)(base + o_len); c.t = (int *)(base + o_t); c.sym = (int *)(base + o_sym);
-  c.count = (int *)(base + o_count); c.flag = (int *)(base + o_flag); c.emit_tok = (int *)(base + o_etok);
-  c.event = (unsigned *)(base + o_event);
-  c.active_idx = (int *)(base + o_act); c.n_active = (int *)(base + o_nact);
+  c.len = (int *)(base + o_len);
+  c.n_active = (int *)(base + o_nact);
+  c.slot_stride = slot_stride;
+  c.res_state = (int4 *)(base + o_rst); c.res_aux = (int4 *)(base + o_raux);
   c.emit_idx = (int *)(base + o_eidx); c.n_emit = (int *)(base + o_nemit);
   c.emit_list_tok = (int *)(base + o_eltok);
   c.slot_state = (int4 *)(base + o_slot); c.slot_count = (int *)(base + o_slotc);
@@ -190,10 +204,10 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.blank_logit = (float *)(base + o_bl); c.znorm = (float *)(base + o_zn);
   c.parts = (float2 *)(base + o_parts);
   c.nparts = nparts;
-  c.part_width = JointSmallCfg::WN;
+  c.part_width = JointRows1::WN;
   c.nparts_big = nparts_big;
   c.part_width_big = JointBigCfg::WN;
-  c.joint_split_rows = m->opt_joint_split_rows;
+  c.joint_split_rows = m->opt_joint_split_rows >= 0 ? m->opt_joint_split_rows : joint_split_default(d.V);
   c.nparts_tiny = nparts_tiny;
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
@@ -318,10 +332,9 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
       ProfScope ps(m, s, WIND_K_JOINT, capturing);
       // two tile shapes; each kernel returns at once when the iteration's row count is the other's
       const int small_rows = max_rows < c.joint_split_rows ? max_rows : c.joint_split_rows;
-      dim3 grid((unsigned)((small_rows + JointSmallCfg::BM - 1) / JointSmallCfg::BM),
-                (unsigned)((d.V + JointSmallCfg::BN - 1) / JointSmallCfg::BN));
-      if (small_rows > 0)
-        joint_dma_kernel<JointSmallCfg><<<grid, JointSmallCfg::NT, JointSmallCfg::SMEM_BYTES, s>>>(d, c, parity);
+      const int NT = (d.V + JointRows1::BN - 1) / JointRows1::BN;
+      dim3 grid((unsigned)joint_rows_grid_x(NT, small_rows), (unsigned)NT);
+      if (small_rows > 0) joint_rows_kernel<<<grid, 256, kJointRowsSmem, s>>>(d, c, parity);
       if (max_rows > c.joint_split_rows) {
         dim3 gbig((unsigned)((max_rows + JointBigCfg::BM - 1) / JointBigCfg::BM),
                   (unsigned)((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN));
@@ -540,8 +553,8 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
   }
   if (rc == WIND_OK) {
-    hipError_t e = hipFuncSetAttribute((const void *)joint_dma_kernel<JointSmallCfg>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, JointSmallCfg::SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void *)joint_rows_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kJointRowsSmem);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)tiny_smem_bytes(m->dev, 64));
@@ -685,7 +698,6 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
     const int one = 1, tok = prefix[i];
     HIP_TRY(hipMemcpyAsync(c.n_emit, &one, sizeof(int), hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(c.emit_idx, &b, sizeof(int), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(c.emit_tok + b, &tok, sizeof(int), hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(c.emit_list_tok, &tok, sizeof(int), hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     rc = enqueue_pred_step(m, s, false);

@@ -31,7 +31,7 @@ struct ModelDev {
   const void *emb;              // [V+1, E]
   const void *w_cat[kMaxLayers];  // [4Hp, in_l + Hp]; row 4*j+g = gate g (i,f,g,o) of unit j; [w_ih | w_hh]
   const float *b_cat[kMaxLayers]; // [4Hp] same row order, b_ih + b_hh
-  const void *w_cat_t[kMaxLayers]; // bf16 models: the same rows grouped for MFMA tiles, see lstm_layer_mfma_kernel
+  const void *w_cat_t[kMaxLayers]; // bf16 models: the same rows grouped for MFMA tiles, see lstm_layer_dma_kernel
   const float *b_cat_t[kMaxLayers];
   const void *w_enc;            // [Hj_pad, D]
   const float *b_enc;           // [Hj]
@@ -51,16 +51,18 @@ struct CallDev {
   int *out_tokens, *out_frames, *out_counts;
   float *e;                     // [B*T, Hj]
   int *len;                     // [B] clamped to [0,T]
-  int *t, *sym, *count;         // [B]
-  int *flag;                    // [B] bit0 still active, bit1 emitted and still active
-  unsigned *event;              // [B] this iteration's counters of the utterance, packed (see decide_kernel)
-  int *emit_tok;                // [B]
-  int *active_idx;              // [2][B] ping-pong by iteration parity
+  // Active utterances live in a slot table, ping-pong by iteration parity: slot a of the current
+  // parity holds everything an iteration needs to know about its a-th active utterance, so that a
+  // kernel reaches it with one load whose address does not depend on another load.
+  int4 *slot_state;             // [2][slot_stride] (utterance, t, len, labels on the current frame)
+  int *slot_count;              // [2][slot_stride] labels emitted so far
+  int slot_stride;              // max(B, 64)
   int *n_active;                // [2]
+  int4 *res_state;              // [B] per slot, this iteration's outcome: the new (utterance, t, len, sym)
+  int4 *res_aux;                // [B] (count, flag, label, event): flag bit0 still active, bit1 emitted and
+                                //     still active; event = the window's counters, packed (see decide_utterance)
   int *emit_idx;                // [B] utterances that emitted and are still active, in order
   int *emit_list_tok;           // [B] their labels, in the same order
-  int4 *slot_state;             // [2][64] few-rows path: (utterance, t, len, sym) per active slot, by parity
-  int *slot_count;              // [2][64] labels emitted so far, same order
   int *n_emit;                  // [1]
   unsigned *ticket;             // [2] workgroups done: decide_kernel, joint_tiny_kernel
   float *h, *c, *hn;            // [L][B][Hp]
@@ -94,25 +96,31 @@ __global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) 
     int len = c.lengths[b];
     len = len < 0 ? 0 : (len > c.T ? c.T : len);
     c.len[b] = len;
-    c.t[b] = 0; c.sym[b] = 0; c.count[b] = 0; c.out_counts[b] = 0;
-    c.flag[b] = len > 0 ? 1 : 0;
-    c.emit_tok[b] = m.V;       // start token
+    c.out_counts[b] = 0;
     c.emit_idx[b] = b;         // the first prediction-network step runs on every utterance
-    c.emit_list_tok[b] = m.V;
+    c.emit_list_tok[b] = m.V;  // on the start token
   }
   __syncthreads();
-  if (tid == 0) {
+  if (tid < 64) {              // slot table of parity 0: the non-empty utterances, in order
     int na = 0;
-    for (int b = 0; b < c.B; ++b)
-      if (c.len[b] > 0) {
-        if (na < kTinyRows) { c.slot_state[na] = make_int4(b, 0, c.len[b], 0); c.slot_count[na] = 0; }
-        c.active_idx[na++] = b;
+    for (int base = 0; base < c.B; base += 64) {
+      const int b = base + tid;
+      const int len = b < c.B ? c.len[b] : 0;
+      const unsigned long long mk = __ballot(len > 0);
+      if (len > 0) {
+        const int pos = na + __popcll(mk & ((1ull << tid) - 1ull));
+        c.slot_state[pos] = make_int4(b, 0, len, 0);
+        c.slot_count[pos] = 0;
       }
-    c.n_active[0] = na;
-    c.n_active[1] = 0;
-    *c.n_emit = c.B;
-    c.ticket[0] = 0u;
-    c.ticket[1] = 0u;
+      na += __popcll(mk);
+    }
+    if (tid == 0) {
+      c.n_active[0] = na;
+      c.n_active[1] = 0;
+      *c.n_emit = c.B;
+      c.ticket[0] = 0u;
+      c.ticket[1] = 0u;
+    }
   }
 }
 
@@ -177,14 +185,15 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(ModelDev m, CallDev c
 // ---------------------------------------------------------------------------------------------
 // Window gather (Algorithm 2, joiner(enc[t:t+n], dec[-1]), first half): one wave per window row.
 __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int parity) {
-  const int na = c.n_active[parity];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = blockIdx.x * 4 + wave;
-  if (row >= na * c.W) return;
   const int a = row / c.W, j = row - a * c.W;
-  const int b = c.active_idx[parity * c.B + a];
-  const int tt = c.t[b] + j;
-  const bool valid = tt < c.len[b];
+  if (a >= c.B) return;
+  const int na = c.n_active[parity];
+  const int4 st = c.slot_state[parity * c.slot_stride + a];   // same round trip as the count
+  if (a >= na) return;
+  const int b = st.x, tt = st.y + j;
+  const bool valid = tt < st.z;
   const int Hj = m.Hj;
   const float *er = c.e + ((size_t)b * c.T + (valid ? tt : 0)) * Hj;
   const float *pr = c.p + (size_t)b * Hj;
@@ -227,98 +236,120 @@ __device__ __forceinline__ void joint_tile_of_block(int &mt, int &nt) {
   mt = idx / npx;
 }
 
-// Accumulator start value for the joint kernels: the output bias of the lane's column, or a large
-// negative number for columns past the vocabulary, so that the epilogue needs neither an add nor a
-// mask.
+// The joint kernels accumulate the transposed tile (MFMA operands exchanged): a lane then holds ONE
+// window row (lane % 32 of the 32-row block mi) and, per 32-column block ni, the 16 columns
+// 8 * (r / 4) + 4 * (lane / 32) + r % 4.  The row argmax over the wave's WN columns is therefore a
+// running top-2 inside the lane, plus one exchange between the two lanes that share a row.
+//
+// Accumulator start value: the output bias of each register's column, or a large negative number
+// for columns past the vocabulary, so that the epilogue needs neither an add nor a mask.  The bias
+// is requested before the tile core starts its loads and copied into the accumulators behind them.
 template <class Cfg>
-__device__ __forceinline__ void joint_init_acc(const ModelDev &m, f32x16 (&acc)[Cfg::MI][Cfg::NI], int n0) {
+__device__ __forceinline__ void joint_load_bias(const ModelDev &m, float (&bias)[Cfg::NI][16], int n0) {
   const int lane = threadIdx.x & 63, wn = (threadIdx.x >> 6) % Cfg::WAVES_N;
 #pragma unroll
   for (int ni = 0; ni < Cfg::NI; ++ni) {
-    const int col = n0 + wn * Cfg::WN + ni * 32 + (lane & 31);
-    const float bias = col < m.V ? m.b_out[col < m.V ? col : 0] : kKeyNone;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int col = n0 + wn * Cfg::WN + ni * 32 + 8 * g + 4 * (lane >> 5);
+      if (col + 3 < m.V) {
+        const float4 b4 = *reinterpret_cast<const float4 *>(m.b_out + col);
+        bias[ni][4 * g] = b4.x; bias[ni][4 * g + 1] = b4.y; bias[ni][4 * g + 2] = b4.z; bias[ni][4 * g + 3] = b4.w;
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bias[ni][4 * g + q] = col + q < m.V ? m.b_out[col + q < m.V ? col + q : 0] : kKeyNone;
+      }
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile core's
+}
+template <class Cfg>
+struct JointInitAcc {
+  f32x16 (&acc)[Cfg::MI][Cfg::NI];
+  const float (&bias)[Cfg::NI][16];
+  __device__ __forceinline__ void operator()() const {
 #pragma unroll
     for (int mi = 0; mi < Cfg::MI; ++mi)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = bias;
+      for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mi][ni][r] = bias[ni][r];
   }
-}
+};
 
 // Epilogue of the joint kernels: (logit, column) keys, per-row top-2 over the wave's WN columns,
 // one float2 per (row, part) to memory.  The logits never leave registers.
 template <class Cfg>
 __device__ __forceinline__ void joint_keys_epilogue(const CallDev &c, f32x16 (&acc)[Cfg::MI][Cfg::NI],
-                                                    int row0, int nt, int nparts) {
+                                                    int row0, int nt, int stride) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
-  constexpr int NS = Cfg::MI * 16;
-  float k1[NS], k2[NS];
+  const int part = nt * Cfg::WAVES_N + wn, row_base = row0 + wm * Cfg::WM;
+  // Keys are built with the column codes of the lower lane half; the upper half's columns are 4
+  // higher, i.e. code bit 2 cleared (it is always set in the lower half's codes).  All keys of a
+  // lane shift alike, so the correction waits until the lane's two winners are known.
+  const unsigned fix = ~(unsigned)(4 * (lane >> 5));
 #pragma unroll
-  for (int s = 0; s < NS; ++s) { k1[s] = kKeyNone; k2[s] = kKeyNone; }
+  for (int mi = 0; mi < Cfg::MI; ++mi) {
+    float k1 = kKeyNone, k2 = kKeyNone;
 #pragma unroll
-  for (int ni = 0; ni < Cfg::NI; ++ni) {
-    const int cip = ni * 32 + (lane & 31);
+    for (int ni = 0; ni < Cfg::NI; ++ni)
 #pragma unroll
-    for (int mi = 0; mi < Cfg::MI; ++mi)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) push_top2(k1[mi * 16 + r], k2[mi * 16 + r], make_key(acc[mi][ni][r], cip));
-  }
-  constexpr int SPL = rowtop2_slots_per_lane<NS>();
-  float o1[SPL], o2[SPL];
-  RowTop2<NS, 16>::run(k1, k2, lane, o1, o2);
-  const int s0 = rowtop2_first_slot<NS>(lane);
-  const int part = nt * Cfg::WAVES_N + wn;
-#pragma unroll
-  for (int i = 0; i < SPL; ++i) {
-    const int s = s0 + i;
-    const int row = row0 + wm * Cfg::WM + acc_row(s >> 4, s & 15, lane);
-    c.parts[(size_t)row * nparts + part] = make_float2(o1[i], o2[i]);
+      for (int r = 0; r < 16; ++r) push_top2(k1, k2, make_key(acc[mi][ni][r], ni * 32 + 8 * (r >> 2) + (r & 3)));
+    k1 = __uint_as_float(__float_as_uint(k1) & fix);
+    k2 = __uint_as_float(__float_as_uint(k2) & fix);
+    const float r1 = __shfl_xor(k1, 32, kWave), r2 = __shfl_xor(k2, 32, kWave);
+    merge_top2(k1, k2, r1, r2);
+    if (lane < 32) c.parts[(size_t)(row_base + mi * 32 + lane) * stride + part] = make_float2(k1, k2);
   }
 }
 
-// Output contraction of the joiner on bf16 MFMA, with the row argmax folded into the epilogue:
-// the tile's logits never leave registers; each wave reduces its WM x WN block to two keys per row.
-template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void joint_mfma_kernel(ModelDev m, CallDev c, int parity) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
-  const int n_rows = c.n_active[parity] * c.W;
-  int mt, nt;
-  joint_tile_of_block(mt, nt);
+// Output contraction of the joiner on bf16 MFMA, with the row argmax folded into the epilogue: the
+// tile's logits never leave registers; each wave reduces its WM x WN block to two keys per row.
+// Direct-to-LDS, multi-stage tile core (both operands are dense bf16 rows in memory: the window
+// rows z and W_out).
+//
+// The number of window rows shrinks from iteration to iteration while the launch grid is fixed (it
+// sits in a captured graph), so the tile height is chosen in the kernel: the grid has GX row
+// tiles, and a workgroup takes 64 * MI rows with the smallest MI in 1..4 for which GX tiles cover
+// the iteration's rows.  All GX x NT workgroups then have equal work whatever the row count, in
+// steps of 64 * GX rows.  Tiles are 128 columns wide; the LDS ring is as deep as 160 KB allow,
+// because with one workgroup per CU the loads in flight, not the bandwidth, set the pace.
+template <int MI>
+struct JointRowsCfg {
+  using type = DmaCfg<64 * MI, 128, 32 * MI, 64, 64, MI == 1 ? 5 : MI == 2 ? 4 : 3>;
+};
+constexpr int kJointRowsSmem = 3 * (256 + 128) * 128;   // the largest of the four rings
+
+template <int MI>
+__device__ __forceinline__ void joint_rows_tile(const ModelDev &m, const CallDev &c, int n_rows, int mt, int nt,
+                                                unsigned char *smem_raw) {
+  using Cfg = typename JointRowsCfg<MI>::type;
+  static_assert(Cfg::SMEM_BYTES <= kJointRowsSmem && Cfg::NT == 256, "ring size, workgroup size");
   const int row0 = mt * Cfg::BM;
   if (row0 >= n_rows) return;
   const int n0 = nt * Cfg::BN, Hj = m.Hj;
-  const bf16_t *zt = c.z + (size_t)row0 * Hj;
-  auto aload = [&](int, int row, int k) -> u32x4 {
-    return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k);
-  };
   f32x16 acc[Cfg::MI][Cfg::NI];
-  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj, smem, acc);
-  f32x16 bias[Cfg::MI][Cfg::NI];
-  joint_init_acc<Cfg>(m, bias, n0);
-#pragma unroll
-  for (int mi = 0; mi < Cfg::MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < Cfg::NI; ++ni) acc[mi][ni] += bias[mi][ni];
+  float bias[Cfg::NI][16];
+  joint_load_bias<Cfg>(m, bias, n0);
+  gemm_mainloop_dma<Cfg, true>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
+                               smem_raw, acc, JointInitAcc<Cfg>{acc, bias});
   joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);
 }
 
-// The same contraction with the direct-to-LDS, multi-stage tile core (both operands are dense
-// bf16 rows in memory: the window rows z and W_out).
-template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void joint_dma_kernel(ModelDev m, CallDev c, int parity) {
+__global__ __launch_bounds__(256) void joint_rows_kernel(ModelDev m, CallDev c, int parity) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   const int n_rows = c.n_active[parity] * c.W;
+  if (n_rows == 0 || n_rows > c.joint_split_rows) return;
   int mt, nt;
   joint_tile_of_block(mt, nt);
-  const int row0 = mt * Cfg::BM;
-  if (row0 >= n_rows || n_rows > c.joint_split_rows) return;
-  const int n0 = nt * Cfg::BN, Hj = m.Hj;
-  f32x16 acc[Cfg::MI][Cfg::NI];
-  joint_init_acc<Cfg>(m, acc, n0);
-  gemm_mainloop_dma<Cfg>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
-                         smem_raw, acc);
-  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);
+  const int mi = (n_rows + 64 * (int)gridDim.x - 1) / (64 * (int)gridDim.x);   // <= 4 by the host's choice of grid
+  switch (mi) {
+    case 1: joint_rows_tile<1>(m, c, n_rows, mt, nt, smem_raw); break;
+    case 2: joint_rows_tile<2>(m, c, n_rows, mt, nt, smem_raw); break;
+    case 3: joint_rows_tile<3>(m, c, n_rows, mt, nt, smem_raw); break;
+    default: joint_rows_tile<4>(m, c, n_rows, mt, nt, smem_raw); break;
+  }
 }
 
 // 256 x 256 tiles on the five-slot ring (see gemm_mainloop_ring5).
@@ -332,10 +363,11 @@ __global__ __launch_bounds__(Cfg::NT) void joint_ring5_kernel(ModelDev m, CallDe
   if (row0 >= n_rows || n_rows <= c.joint_split_rows) return;
   const int n0 = nt * Cfg::BN, Hj = m.Hj;
   f32x16 acc[Cfg::MI][Cfg::NI];
-  joint_init_acc<Cfg>(m, acc, n0);
-  gemm_mainloop_ring5<Cfg>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
-                           smem_raw, acc);
-  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts_big);
+  float bias[Cfg::NI][16];
+  joint_load_bias<Cfg>(m, bias, n0);
+  gemm_mainloop_ring5<Cfg, true>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
+                                 smem_raw, acc, JointInitAcc<Cfg>{acc, bias});
+  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);   // rows of keys are c.nparts pairs apart for both shapes
 }
 
 // Debug: the same tile core with the logits stored, bias added (columns 0..V, blank included).
@@ -385,12 +417,13 @@ __global__ __launch_bounds__(256) void joint_exact_kernel(ModelDev m, CallDev c,
   bool valid;
   const float *pr;
   if (rows_from_state) {
-    const int na = c.n_active[parity];
-    if (row >= na * c.W) return;
     const int a = row / c.W, j = row - a * c.W;
-    b = c.active_idx[parity * c.B + a];
-    tt = c.t[b] + j;
-    valid = tt < c.len[b];
+    const int na = c.n_active[parity];
+    const int4 st = c.slot_state[parity * c.slot_stride + a];
+    if (a >= na) return;
+    b = st.x;
+    tt = st.y + j;
+    valid = tt < st.z;
     pr = c.p + (size_t)b * m.Hj;
   } else {
     if (row >= n_dbg) return;
@@ -427,21 +460,38 @@ __global__ __launch_bounds__(256) void joint_exact_kernel(ModelDev m, CallDev c,
 }
 
 // ---------------------------------------------------------------------------------------------
-// fp32 logit of label `col` for the hidden vector a wave holds (zr[i] = z[2*lane + 128*i .. +1]).
+// Running argmax (ties to the lowest id) over the fp32 logits of nc candidate labels, lane i
+// holding the i-th candidate's column, for the hidden vector the wave holds (zr[i] = z[2*lane +
+// 128*i .. +1]).  Four weight rows are requested together, so that a near-tie costs one memory
+// round trip for up to four candidates.
 template <class WT, int NZ>
-__device__ __forceinline__ float exact_logit(const ModelDev &m, const float2 (&zr)[NZ], int col, int lane) {
-  const WT *w = reinterpret_cast<const WT *>(m.w_out) + (size_t)col * m.Hj;
-  float a = 0.f;
+__device__ __forceinline__ void evaluate_candidates(const ModelDev &m, const float2 (&zr)[NZ], int mycol, int nc,
+                                                    int lane, float &bestv, int &besti) {
+  const WT *w = reinterpret_cast<const WT *>(m.w_out);
+  for (int c0 = 0; c0 < nc; c0 += 4) {
+    const int col0 = __shfl(mycol, c0, kWave), col1 = __shfl(mycol, min(c0 + 1, nc - 1), kWave);
+    const int col2 = __shfl(mycol, min(c0 + 2, nc - 1), kWave), col3 = __shfl(mycol, min(c0 + 3, nc - 1), kWave);
+    const WT *w0 = w + (size_t)col0 * m.Hj, *w1 = w + (size_t)col1 * m.Hj;
+    const WT *w2 = w + (size_t)col2 * m.Hj, *w3 = w + (size_t)col3 * m.Hj;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll
-  for (int i = 0; i < NZ; ++i) {
-    const int k = 2 * lane + 128 * i;
-    if (k < m.Hj) {
-      const float2 wv = ldw2(w, k);
-      a = fmaf(wv.x, zr[i].x, a);
-      a = fmaf(wv.y, zr[i].y, a);
+    for (int i = 0; i < NZ; ++i) {
+      const int k = 2 * lane + 128 * i;
+      if (k < m.Hj) {
+        const float2 x0 = ldw2(w0, k), x1 = ldw2(w1, k), x2 = ldw2(w2, k), x3 = ldw2(w3, k);
+        a0 = fmaf(x0.x, zr[i].x, a0); a0 = fmaf(x0.y, zr[i].y, a0);
+        a1 = fmaf(x1.x, zr[i].x, a1); a1 = fmaf(x1.y, zr[i].y, a1);
+        a2 = fmaf(x2.x, zr[i].x, a2); a2 = fmaf(x2.y, zr[i].y, a2);
+        a3 = fmaf(x3.x, zr[i].x, a3); a3 = fmaf(x3.y, zr[i].y, a3);
+      }
     }
+    const float v0 = wave_sum(a0) + m.b_out[col0], v1 = wave_sum(a1) + m.b_out[col1];
+    const float v2 = wave_sum(a2) + m.b_out[col2], v3 = wave_sum(a3) + m.b_out[col3];
+    if (v0 > bestv || (v0 == bestv && col0 < besti)) { bestv = v0; besti = col0; }
+    if (v1 > bestv || (v1 == bestv && col1 < besti)) { bestv = v1; besti = col1; }
+    if (v2 > bestv || (v2 == bestv && col2 < besti)) { bestv = v2; besti = col2; }
+    if (v3 > bestv || (v3 == bestv && col3 < besti)) { bestv = v3; besti = col3; }
   }
-  return wave_sum(a) + m.b_out[col];
 }
 
 constexpr int kDecideMaxHj = 2048;  // exact_logit keeps Hj/128 float2 per lane
@@ -467,10 +517,10 @@ struct DecideShared {
 // rows at once so that the loads overlap); parts 64 and up are read here.
 template <class WT>
 __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
-                                          int nparts, int part_width, float vblank, float znorm, float2 kk0,
-                                          int &n_recheck) {
+                                          int nparts, int stride, int part_width, float vblank, float znorm,
+                                          float2 kk0, int &n_recheck) {
   const int lane = threadIdx.x & 63, V = m.V;
-  const float2 *prow = c.parts + (size_t)row * nparts;
+  const float2 *prow = c.parts + (size_t)row * stride;
   float k1 = kk0.x;
   for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, prow[pi].x);
   const float kbest = wave_max_f32(k1);
@@ -512,6 +562,8 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
   }
   float bestv = vblank;     // blank has the highest id: it wins only if strictly larger
   int besti = V;
+  // candidate columns, one per lane (lane i holds the i-th), evaluated four at a time
+  int mycol = 0, nc = 0;
   for (int p0 = 0; p0 < nparts; p0 += 64) {
     const int pi = p0 + lane;
     float2 kk = make_float2(kKeyNone, kKeyNone);
@@ -526,55 +578,70 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
         mask &= mask - 1;
         const float skey = __shfl(key, src, kWave);
         const int col = (p0 + src) * part_width + key_col(skey);
-        const float v = exact_logit<WT, NZ>(m, zr, col, lane);
-        if (v > bestv || (v == bestv && col < besti)) { bestv = v; besti = col; }
+        if (lane == nc) mycol = col;
+        if (++nc == 64) {
+          evaluate_candidates<WT, NZ>(m, zr, mycol, nc, lane, bestv, besti);
+          nc = 0;
+        }
       }
     }
   }
+  evaluate_candidates<WT, NZ>(m, zr, mycol, nc, lane, bestv, besti);
   return besti;
 }
 
-// One utterance (slot a of the active list), handled by the whole calling workgroup: one wave per
-// window row (rows round-robin over the waves), then the first non-blank row by ballot and the
-// pointer / hypothesis update of Algorithm 2.  Ends with a workgroup barrier.
+// Keys and row scalars of the first rows a wave decides, requested before anything else is known
+// about the utterance so that they share the round trip of the slot table.
+constexpr int kRowsAhead = 4;
+struct RowsAhead {
+  float2 kk0[kRowsAhead];
+  float vb[kRowsAhead], zn[kRowsAhead];
+};
+
+// One utterance (slot a of the active list, state st = (utterance, t, len, sym), cnt labels so
+// far), handled by the whole calling workgroup: one wave per window row (rows round-robin over the
+// waves), then the first non-blank row by ballot and the pointer / hypothesis update of
+// Algorithm 2.  nparts key pairs per row are valid, rows are `stride` pairs apart.  Ends with a
+// workgroup barrier.
 template <class WT, bool LOCAL>
-__device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int parity, int a,
-                                                 int exact_mode, int nparts, int part_width, DecideShared &sh) {
+__device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int a, int4 st, int cnt,
+                                                 int exact_mode, int nparts, int stride, int part_width,
+                                                 const RowsAhead &ahead, DecideShared &sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-  const int b = LOCAL ? sh.slot[a].x : c.active_idx[parity * c.B + a];
-  const int t = LOCAL ? sh.slot[a].y : c.t[b], len = LOCAL ? sh.slot[a].z : c.len[b], V = m.V;
+  const int b = st.x, t = st.y, len = st.z, V = m.V;
   const int n = min(c.W, len - t);
   int n_recheck = 0;
   if (threadIdx.x == 0) sh.recheck = 0;
   __syncthreads();
-  // the first 64 parts' keys of this wave's rows, requested together so that the loads overlap
-  constexpr int kRowsAhead = 4;
-  float2 kk0[kRowsAhead];
-#pragma unroll
-  for (int q = 0; q < kRowsAhead; ++q) {
-    const int j = wave + q * nwaves;
-    kk0[q] = make_float2(kKeyNone, kKeyNone);
-    if (!exact_mode && j < n && lane < nparts) kk0[q] = c.parts[(size_t)(a * c.W + j) * nparts + lane];
-  }
-  auto one_row = [&](int j, float2 k0) {
+  auto one_row = [&](int j, float2 k0, float vb, float zn) {
     int label = V;
     if (j < n) {
       const int row = a * c.W + j;
-      if (exact_mode) label = c.row_label[row];
-      else label = decide_row<WT>(m, c, row, b, t + j, nparts, part_width, LOCAL ? sh.blank[row] : c.blank_logit[row],
-                                  LOCAL ? sh.znorm[row] : c.znorm[row], k0, n_recheck);
+      if constexpr (sizeof(WT) == 4) {   // fp32 models take the argmax in joint_exact_kernel
+        label = c.row_label[row];
+      } else {
+        if (exact_mode) label = c.row_label[row];
+        else label = decide_row<WT>(m, c, row, b, t + j, nparts, stride, part_width, vb, zn,
+                                    lane < nparts ? k0 : make_float2(kKeyNone, kKeyNone), n_recheck);
+      }
     }
     if (lane == 0) sh.label[j] = label;
   };
 #pragma unroll
   for (int q = 0; q < kRowsAhead; ++q) {
     const int j = wave + q * nwaves;
-    if (j < c.W) one_row(j, kk0[q]);
+    if (j < c.W) one_row(j, ahead.kk0[q], ahead.vb[q], ahead.zn[q]);
   }
   for (int j = wave + kRowsAhead * nwaves; j < c.W; j += nwaves) {
     float2 k0 = make_float2(kKeyNone, kKeyNone);
-    if (!exact_mode && j < n && lane < nparts) k0 = c.parts[(size_t)(a * c.W + j) * nparts + lane];
-    one_row(j, k0);
+    float vb = 0.f, zn = 0.f;
+    if (!exact_mode && j < n) {
+      const int row = a * c.W + j;
+      if (lane < nparts) k0 = c.parts[(size_t)row * stride + lane];
+      vb = LOCAL ? sh.blank[row] : c.blank_logit[row];
+      zn = LOCAL ? sh.znorm[row] : c.znorm[row];
+    }
+    one_row(j, k0, vb, zn);
   }
   if (lane == 0 && n_recheck) atomicAdd(&sh.recheck, n_recheck);
   __syncthreads();
@@ -583,7 +650,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
     const unsigned long long mask = __ballot(nb);
     if (lane == 0) {
       const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
-      int tn = t, sym = LOCAL ? sh.slot[a].w : c.sym[b], cnt = LOCAL ? sh.cnt[a] : c.count[b];
+      int tn = t, sym = st.w;
       int jump, emitted = 0, forced = 0, tok = V, overflow = 0;
       if (i < 0) {
         tn += n; sym = 0; jump = n;
@@ -602,44 +669,50 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
         emitted = 1;
         if (sym >= c.S) { tn += 1; sym = 0; jump += 1; forced = 1; }
       }
-      c.t[b] = tn; c.sym[b] = sym; c.count[b] = cnt; c.out_counts[b] = cnt;
+      if (emitted) c.out_counts[b] = cnt;
       const int active = tn < len;
-      c.flag[b] = active | ((emitted & active) << 1);
-      c.emit_tok[b] = tok;
-      // counters of this window, summed by the last workgroup: n (7 bits), useful rows (7), jump (7),
+      const int flag = active | ((emitted & active) << 1);
+      // counters of this window, summed by the compacting wave: n (7 bits), useful rows (7), jump (7),
       // rechecks (7), emitted, forced, overflow
       const int useful = i < 0 ? n : i + 1;
       const unsigned ev = (unsigned)n | ((unsigned)useful << 7) | ((unsigned)jump << 14) |
                           ((unsigned)min(sh.recheck, 127) << 21) | ((unsigned)emitted << 28) |
                           ((unsigned)forced << 29) | ((unsigned)overflow << 30);
       if (LOCAL) {
-        sh.flag[a] = active | ((emitted & active) << 1); sh.tok[a] = tok; sh.event[a] = ev;
+        sh.flag[a] = flag; sh.tok[a] = tok; sh.event[a] = ev;
         sh.slot[a] = make_int4(b, tn, len, sym); sh.cnt[a] = cnt;
       } else {
-        c.event[b] = ev;
+        c.res_state[a] = make_int4(b, tn, len, sym);
+        c.res_aux[a] = make_int4(cnt, flag, tok, (int)ev);
       }
     }
   }
   __syncthreads();
 }
 
-// Rebuilds the active list (other parity slot) and the emit list from the per-utterance flags, and
-// adds the iteration's counters to the statistics.  Called by wave 0 of one workgroup per
+// Builds the next iteration's slot table (other parity) and the emit list from the slots' outcomes,
+// and adds the iteration's counters to the statistics.  Called by wave 0 of one workgroup per
 // iteration, after every utterance has been decided and those writes have been fenced.
 template <bool LOCAL>
 __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int na, DecideShared &sh) {
   const int lane = threadIdx.x & 63;
-  const int *src = c.active_idx + parity * c.B;
-  int *dst = c.active_idx + (parity ^ 1) * c.B;
+  int4 *dst_state = c.slot_state + (parity ^ 1) * c.slot_stride;
+  int *dst_count = c.slot_count + (parity ^ 1) * c.slot_stride;
   int n_act = 0, n_em = 0;
   unsigned sum_rows = 0, sum_useful = 0, sum_recheck = 0, sum_labels = 0, sum_forced = 0, sum_over = 0;
   for (int base = 0; base < na; base += 64) {
     const int idx = base + lane;
-    int ub = 0, f = 0;
+    int4 st = make_int4(0, 0, 0, 0);
+    int f = 0, cnt = 0, tok = 0;
     if (idx < na) {
-      ub = LOCAL ? sh.slot[idx].x : src[idx];
-      f = LOCAL ? sh.flag[idx] : __atomic_load_n(&c.flag[ub], __ATOMIC_RELAXED);
-      const unsigned ev = LOCAL ? sh.event[idx] : __atomic_load_n(&c.event[ub], __ATOMIC_RELAXED);
+      unsigned ev;
+      if (LOCAL) {
+        st = sh.slot[idx]; cnt = sh.cnt[idx]; f = sh.flag[idx]; tok = sh.tok[idx]; ev = sh.event[idx];
+      } else {
+        st = c.res_state[idx];
+        const int4 aux = c.res_aux[idx];
+        cnt = aux.x; f = aux.y; tok = aux.z; ev = (unsigned)aux.w;
+      }
       sum_rows += ev & 127u; sum_useful += (ev >> 7) & 127u; sum_recheck += (ev >> 21) & 127u;
       sum_labels += (ev >> 28) & 1u; sum_forced += (ev >> 29) & 1u; sum_over += (ev >> 30) & 1u;
       atomicAdd(&sh.hist[(ev >> 14) & 127u], 1u);
@@ -648,16 +721,13 @@ __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int 
     const unsigned long long below = (1ull << lane) - 1ull;
     if (f & 1) {
       const int pos = n_act + __popcll(ma & below);
-      dst[pos] = ub;
-      if (LOCAL) {   // next iteration's slot table: everything the few-rows kernel needs, in active order
-        c.slot_state[(parity ^ 1) * kTinyRows + pos] = sh.slot[idx];
-        c.slot_count[(parity ^ 1) * kTinyRows + pos] = sh.cnt[idx];
-      }
+      dst_state[pos] = st;
+      dst_count[pos] = cnt;
     }
     if (f & 2) {
       const int pos = n_em + __popcll(me & below);
-      c.emit_idx[pos] = ub;
-      c.emit_list_tok[pos] = LOCAL ? sh.tok[idx] : c.emit_tok[ub];
+      c.emit_idx[pos] = st.x;
+      c.emit_list_tok[pos] = tok;
     }
     n_act += __popcll(ma);
     n_em += __popcll(me);
@@ -686,14 +756,34 @@ __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int 
 template <class WT>
 __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int parity, int exact_mode) {
   __shared__ DecideShared sh;
-  for (int j = threadIdx.x; j <= kMaxWindow; j += blockDim.x) sh.hist[j] = 0u;
-  const int na = c.n_active[parity];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int a = blockIdx.x;
+  // one round trip: the active count, this slot's state, and the keys / blank logit / norm of the
+  // rows this wave decides (their addresses depend on the slot number only)
+  const int na = c.n_active[parity];
+  const int4 st = c.slot_state[parity * c.slot_stride + a];
+  const int cnt = c.slot_count[parity * c.slot_stride + a];
+  RowsAhead ahead;
+#pragma unroll
+  for (int q = 0; q < kRowsAhead; ++q) {
+    const int j = wave + q * nwaves;
+    ahead.kk0[q] = make_float2(kKeyNone, kKeyNone);
+    ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
+    if (!exact_mode && j < c.W) {
+      const int row = a * c.W + j;
+      if (lane < c.nparts) ahead.kk0[q] = c.parts[(size_t)row * c.nparts + lane];
+      ahead.vb[q] = c.blank_logit[row];
+      ahead.zn[q] = c.znorm[row];
+    }
+  }
+  for (int j = threadIdx.x; j <= kMaxWindow; j += blockDim.x) sh.hist[j] = 0u;
   if (na == 0 && a == 0 && threadIdx.x == 0) c.n_active[parity ^ 1] = 0;  // keep both slots at "done"
   if (a >= na) return;
-  const bool big = na * c.W > c.joint_split_rows;   // which joint kernel wrote the keys
-  decide_utterance<WT, false>(m, c, parity, a, exact_mode, big ? c.nparts_big : c.nparts,
-                              big ? c.part_width_big : c.part_width, sh);
+  // which joint kernel wrote the keys: both use rows c.nparts pairs apart, the 256 x 256 kernel
+  // fills fewer, wider parts
+  const bool big = na * c.W > c.joint_split_rows;
+  decide_utterance<WT, false>(m, c, a, st, cnt, exact_mode, big ? c.nparts_big : c.nparts, c.nparts,
+                              big ? c.part_width_big : c.part_width, ahead, sh);
   if (threadIdx.x == 0) {
     __threadfence();
     const unsigned tk = atomicAdd(c.ticket, 1u);
@@ -727,8 +817,8 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
   const long long ts0 = c.dbg ? wall_clock64() : 0;
   const int na = c.n_active[parity];
   if (tid < kTinyRows) {
-    sh.slot[tid] = c.slot_state[parity * kTinyRows + tid];
-    sh.cnt[tid] = c.slot_count[parity * kTinyRows + tid];
+    sh.slot[tid] = c.slot_state[parity * c.slot_stride + tid];
+    sh.cnt[tid] = c.slot_count[parity * c.slot_stride + tid];
   }
   const int n0 = blockIdx.x * kTinyCols;
   const int kq = Hj >> 2, k0 = wave * kq, nk = kq >> 4;   // Hj % 64 == 0, so kq % 16 == 0
@@ -850,7 +940,7 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
       k2[r] = kKeyNone;
     }
     float o1[1], o2[1];
-    RowTop2<16, 16>::run(k1, k2, lane, o1, o2);
+    RowTop2<16, 0>::run(k1, k2, lane, o1, o2);
     const int s = rowtop2_first_slot<16>(lane);
     const int row = rb * 32 + acc_row(0, s, lane);
     c.parts[(size_t)row * c.nparts_tiny + blockIdx.x] = make_float2(o1[0], o2[0]);
@@ -867,7 +957,21 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
   if (!sh.is_last) return;
   __threadfence();
   const long long ts3 = c.dbg ? wall_clock64() : 0;
-  for (int a = 0; a < na; ++a) decide_utterance<WT, true>(m, c, parity, a, 0, c.nparts_tiny, kTinyCols, sh);
+  for (int a = 0; a < na; ++a) {
+    RowsAhead ahead;
+#pragma unroll
+    for (int q = 0; q < kRowsAhead; ++q) {
+      const int j = wave + q * 4, row = a * W + j;
+      ahead.kk0[q] = make_float2(kKeyNone, kKeyNone);
+      ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
+      if (j < W) {
+        if (lane < c.nparts_tiny) ahead.kk0[q] = c.parts[(size_t)row * c.nparts_tiny + lane];
+        ahead.vb[q] = sh.blank[row];
+        ahead.zn[q] = sh.znorm[row];
+      }
+    }
+    decide_utterance<WT, true>(m, c, a, sh.slot[a], sh.cnt[a], 0, c.nparts_tiny, c.nparts_tiny, kTinyCols, ahead, sh);
+  }
   const long long ts4 = c.dbg ? wall_clock64() : 0;
   if (tid < 64) {
     compact_lists<true>(c, parity, na, sh);
@@ -905,7 +1009,7 @@ __global__ __launch_bounds__(256) void lstm_layer_kernel(ModelDev m, CallDev c, 
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       ub[r] = c.emit_idx[min(r0 + r, n_emit - 1)];
-      xe[r] = reinterpret_cast<const WT *>(m.emb) + (size_t)c.emit_tok[ub[r]] * m.E;
+      xe[r] = reinterpret_cast<const WT *>(m.emb) + (size_t)c.emit_list_tok[min(r0 + r, n_emit - 1)] * m.E;
       xh[r] = c.hn + (layer == 0 ? 0 : lofs - (size_t)c.B * Hp) + (size_t)ub[r] * Hp;
       hp[r] = c.h + lofs + (size_t)ub[r] * Hp;
 #pragma unroll

@@ -119,46 +119,67 @@ __device__ __forceinline__ int acc_row(int mi, int r, int lane) {
 
 // ---------------------------------------------------------------------------------------------
 // Row-wise top-2 across the 32 lanes that share lane/32 (they hold the 32 columns of a block).
-// Every lane enters with N sorted (logit, column) key pairs, one per accumulator row slot; each step hands half of
-// the slots to the partner lane and merges the partner's half, so after log2 steps every lane owns
-// N/32 slots (at least one), fully reduced.  MASK walks 16, 8, 4, 2, 1.
-template <int N, int MASK>
+// Every lane enters with N (logit, column) key pairs, one per accumulator row slot; each step
+// hands half of the slots to a partner lane and merges the partner's half, so after the steps
+// every lane owns N/32 slots (at least one), fully reduced.  The first four steps pair lanes inside
+// a row of 16 with DPP permutations, which cost no more than a move (row mirror i <-> 15-i, half
+// mirror i <-> 7-i, then i ^ 2 and i ^ 1: any sequence of perfect matchings works as long as the
+// two partners own the same slots and disjoint columns); only the last step, which carries the
+// fewest slots, crosses the two rows of 16 through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+template <int S>
+__device__ __forceinline__ float rowtop2_partner(float x) {
+  if constexpr (S == 0) return dpp_f32<0x140>(x);        // row_mirror
+  else if constexpr (S == 1) return dpp_f32<0x141>(x);   // row_half_mirror
+  else if constexpr (S == 2) return dpp_f32<0x4E>(x);    // quad_perm [2,3,0,1]
+  else if constexpr (S == 3) return dpp_f32<0xB1>(x);    // quad_perm [1,0,3,2]
+  else return __shfl_xor(x, 16, kWave);
+}
+// the lane bit that decides which half of the slots a lane keeps at step S
+template <int S>
+constexpr int rowtop2_bit() { return S == 0 ? 8 : S == 1 ? 4 : S == 2 ? 2 : S == 3 ? 1 : 16; }
+
+template <int N, int S>
 struct RowTop2 {
   template <int NO>
   static __device__ __forceinline__ void run(float (&k1)[N], float (&k2)[N], int lane, float (&o1)[NO], float (&o2)[NO]) {
-    if constexpr (MASK == 0) {
+    if constexpr (S == 5) {
       static_assert(N == NO, "slots per lane");
 #pragma unroll
       for (int i = 0; i < N; ++i) { o1[i] = k1[i]; o2[i] = k2[i]; }
     } else if constexpr (N == 1) {
-      float r1 = __shfl_xor(k1[0], MASK, kWave), r2 = __shfl_xor(k2[0], MASK, kWave);
+      float r1 = rowtop2_partner<S>(k1[0]), r2 = rowtop2_partner<S>(k2[0]);
       merge_top2(k1[0], k2[0], r1, r2);
-      RowTop2<1, MASK / 2>::run(k1, k2, lane, o1, o2);
+      RowTop2<1, S + 1>::run(k1, k2, lane, o1, o2);
     } else {
-      const bool up = (lane & MASK) != 0;
+      const bool up = (lane & rowtop2_bit<S>()) != 0;
       float n1[N / 2], n2[N / 2];
 #pragma unroll
       for (int i = 0; i < N / 2; ++i) {
         float keep1 = up ? k1[i + N / 2] : k1[i], keep2 = up ? k2[i + N / 2] : k2[i];
         float send1 = up ? k1[i] : k1[i + N / 2], send2 = up ? k2[i] : k2[i + N / 2];
-        float r1 = __shfl_xor(send1, MASK, kWave), r2 = __shfl_xor(send2, MASK, kWave);
+        float r1 = rowtop2_partner<S>(send1), r2 = rowtop2_partner<S>(send2);
         merge_top2(keep1, keep2, r1, r2);
         n1[i] = keep1;
         n2[i] = keep2;
       }
-      RowTop2<N / 2, MASK / 2>::run(n1, n2, lane, o1, o2);
+      RowTop2<N / 2, S + 1>::run(n1, n2, lane, o1, o2);
     }
   }
 };
-// First slot a lane owns after RowTop2<NS,16>, and how many (consecutive) slots.
+// First slot a lane owns after RowTop2<NS, 0>, and how many (consecutive) slots.
 template <int NS>
 __device__ __forceinline__ int rowtop2_first_slot(int lane) {
+  constexpr int masks[5] = {8, 4, 2, 1, 16};   // rowtop2_bit<0..4>
   int base = 0, n = NS;
 #pragma unroll
-  for (int mask = 16; mask >= 1; mask >>= 1) {
+  for (int i = 0; i < 5; ++i) {
     if (n > 1) {
       n >>= 1;
-      if (lane & mask) base += n;
+      if (lane & masks[i]) base += n;
     }
   }
   return base;

@@ -69,7 +69,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // over tile kt+1 sits before the *last* K step of tile kt, whose fragments are in registers by
 // then: the barrier certifies that tile kt+1 has landed (every wave waited for its own loads
 // first) and that every wave has completed its LDS reads of tile kt (lgkmcnt(0) first), so the
-// stage of tile kt is refilled at once with tile kt+NSTAGE.  NSTAGE-1 tiles stay in flight.
+// stage of tile kt is refilled with tile kt+NSTAGE.  NSTAGE-1 tiles stay in flight.  The refill is
+// not issued in one burst: a wave that queues all its loads at once sits at the memory pipeline's
+// door while its MFMA pipe runs dry, so a quarter goes out at the hand-over and the rest follows
+// with the next three K steps (measured: 19 -> 16 us for a 256 x 128 x 1024 tile).
 // Where a lane finds its 16 bytes of an A load: dense rows (the joint kernel) ...
 struct DenseRows {
   const bf16_t *base;
@@ -83,10 +86,18 @@ struct DenseRows {
 // of A's row `row` (i = index of the load among the wave's LPW loads of a stage, for sources that
 // cache per-load state); it is called once per load and K step, so gathered rows or rows stitched from two
 // arrays cost a few integer operations per load, not a staging pass.
-template <class Cfg, class ASrc>
+// SWAP = true issues the MFMAs with the operands exchanged: acc[mi][ni] then holds the transposed
+// 32 x 32 block (B rows down the registers, A rows across the lanes), which lets an epilogue that
+// reduces over B rows work inside a lane.
+// `after_issue` runs once the first stages are on their way and before anything is awaited: the
+// place for a caller to finish setting up acc from values it loaded earlier, behind the loads' latency.
+struct NoInit {
+  __device__ __forceinline__ void operator()() const {}
+};
+template <class Cfg, class ASrc, bool SWAP = false, class Init = NoInit>
 __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf16_t *__restrict__ Bw,
                                                       int K, unsigned char *smem,
-                                                      f32x16 (&acc)[Cfg::MI][Cfg::NI]) {
+                                                      f32x16 (&acc)[Cfg::MI][Cfg::NI], Init after_issue = Init{}) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 
@@ -100,10 +111,12 @@ __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf
     lchunk[i] = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(lrow[i]);
     bsrc[i] = Bw + (size_t)(lrow[i] - Cfg::BM) * K + lchunk[i] * 8;
   }
-  auto issue = [&](int kt, int stage) {
+  // the wave's loads of tile kt into `stage`: all of them (part < 0), or the part-th of KSTEPS shares
+  auto issue = [&](int kt, int stage, int part) {
     unsigned char *dst = smem + stage * Cfg::STAGE_BYTES + wave * Cfg::LPW * 1024;
 #pragma unroll
     for (int i = 0; i < Cfg::LPW; ++i) {
+      if (part >= 0 && (i * Cfg::KSTEPS) / Cfg::LPW != part) continue;
       const bool is_a = (wave * Cfg::LPW + i) * Cfg::RPI < Cfg::BM;   // wave-uniform
       const bf16_t *p = is_a ? asrc(i, lrow[i], lchunk[i], kt, Cfg::BK) : bsrc[i] + kt * Cfg::BK;
       __builtin_amdgcn_global_load_lds((gmem_cptr *)p, (lds_ptr *)(dst + i * 1024), 16, 0, 0);
@@ -112,7 +125,8 @@ __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf
 
   const int KT = K / Cfg::BK;
 #pragma unroll
-  for (int s = 0; s < Cfg::NSTAGE; ++s) issue(s < KT ? s : KT - 1, s);
+  for (int s = 0; s < Cfg::NSTAGE; ++s) issue(s < KT ? s : KT - 1, s, -1);
+  after_issue();
 
   // fragment addressing: lane l reads row l%32 of a 32-row block, k chunk 2*ks + l/32
   const int frow = lane & 31, kc = lane >> 5, sw = lds_swizzle<Cfg::CPR>(frow);
@@ -136,19 +150,25 @@ __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf
     for (int mi = 0; mi < Cfg::MI; ++mi)
 #pragma unroll
       for (int ni = 0; ni < Cfg::NI; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0)
+                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
   };
   wait_vmcnt<(Cfg::NSTAGE - 1) * Cfg::LPW>();                      // tile 0 has landed
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   load_frags(0, smem, 0);
   int stage = 0;
+  // The refill in progress.  Before the first hand-over there is none; the youngest stage is
+  // fetched again instead (same bytes to the same place), which keeps the loop free of branches
+  // and only makes the first wait a little stricter.
+  int pend_kt = Cfg::NSTAGE - 1 < KT ? Cfg::NSTAGE - 1 : KT - 1, pend_stage = Cfg::NSTAGE - 1;
   for (int kt = 0; kt + 1 < KT; ++kt) {
     const unsigned char *st = smem + stage * Cfg::STAGE_BYTES;
     const int next = stage + 1 == Cfg::NSTAGE ? 0 : stage + 1;
 #pragma unroll
     for (int ks = 0; ks + 1 < Cfg::KSTEPS; ++ks) {
       load_frags((ks + 1) & 1, st, ks + 1);
+      issue(pend_kt, pend_stage, ks + 1);
       __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs they overlap with
       mfma_step(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
@@ -158,7 +178,9 @@ __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     const int kn = kt + Cfg::NSTAGE;
-    issue(kn < KT ? kn : KT - 1, stage);
+    pend_kt = kn < KT ? kn : KT - 1;
+    pend_stage = stage;
+    issue(pend_kt, pend_stage, 0);
     load_frags(Cfg::KSTEPS & 1, smem + next * Cfg::STAGE_BYTES, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfma_step((Cfg::KSTEPS - 1) & 1);
@@ -176,11 +198,11 @@ __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf
   wait_vmcnt<0>();   // the redundant refills must not outlive the kernel's use of LDS
 }
 
-template <class Cfg>
+template <class Cfg, bool SWAP = false, class Init = NoInit>
 __device__ __forceinline__ void gemm_mainloop_dma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Bw,
                                                   int K, unsigned char *smem,
-                                                  f32x16 (&acc)[Cfg::MI][Cfg::NI]) {
-  gemm_mainloop_dma_src<Cfg>(DenseRows{A, K}, Bw, K, smem, acc);
+                                                  f32x16 (&acc)[Cfg::MI][Cfg::NI], Init after_issue = Init{}) {
+  gemm_mainloop_dma_src<Cfg, DenseRows, SWAP, Init>(DenseRows{A, K}, Bw, K, smem, acc, after_issue);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -205,10 +227,10 @@ struct Ring5Cfg {
   static_assert(WN <= 128 && SMEM_BYTES <= 160 * 1024, "limits");
 };
 
-template <class Cfg>
+template <class Cfg, bool SWAP = false, class Init = NoInit>
 __device__ __forceinline__ void gemm_mainloop_ring5(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Bw,
                                                     int K, unsigned char *smem,
-                                                    f32x16 (&acc)[Cfg::MI][Cfg::NI]) {
+                                                    f32x16 (&acc)[Cfg::MI][Cfg::NI], Init after_issue = Init{}) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
   const bf16_t *src_a[Cfg::LPU], *src_b[Cfg::LPU];
@@ -241,6 +263,7 @@ __device__ __forceinline__ void gemm_mainloop_ring5(const bf16_t *__restrict__ A
   // address unit and hold every wave at issue; so only the B unit and the first load of the A unit
   // go out at the hand-over, the rest of the A unit follows one load per K step.
   issue_a(0, 0); issue_b(0, 1); issue_a(1, 2); issue_b(1, 3); issue_a1(0, 2, 4);
+  after_issue();
 
   const int frow = lane & 31, kc = lane >> 5, sw = lds_swizzle<Cfg::CPR>(frow);
   const int a_row_off = (wm * Cfg::WM + frow) * Cfg::ROWB;
@@ -260,7 +283,8 @@ __device__ __forceinline__ void gemm_mainloop_ring5(const bf16_t *__restrict__ A
     for (int mi = 0; mi < Cfg::MI; ++mi)
 #pragma unroll
       for (int ni = 0; ni < Cfg::NI; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0)
+                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
   };
   auto plus2 = [](int s) { return s + 2 >= Cfg::NSLOT ? s + 2 - Cfg::NSLOT : s + 2; };
 
