@@ -92,7 +92,7 @@ def roofline_leg(torch, cfg, model, dev, W):
     achieved = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
     # bytes the joint kernel must move per launch: W_out once, the window rows once, the keys out
     return {
-        "bound": "mfma", "kernel": "joint_mfma_kernel", "workload": f"{cfg.name} W={W}",
+        "bound": "mfma", "kernel": "joint_kernel", "workload": f"{cfg.name} W={W}",
         "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
         "traffic": measured_traffic(cfg, W), "launches": int(n), "avg_launch_us": ms * 1e3 / max(n, 1),
         "rows_per_launch": st.rows / max(n, 1), "flops_per_row": 2.0 * cfg.Hj * (cfg.V + 1),

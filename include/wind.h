@@ -160,9 +160,12 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "tiny_rows"  decodes with at most this many window rows (B * W) run window gather, joint and
  *             decision as one kernel per iteration (default 64, the maximum; 0 turns it off)
  *   "joint_split_rows"  iterations with more window rows than this use the 256 x 256 joint tiles,
- *             the others 128 x 128 tiles (default 1536)
+ *             the others 128-column tiles whose height follows the row count (default: 256 rows
+ *             per row tile that it takes to fill the chip; 1024 for V = 8192)
  *   "pred_mfma_min_batch"  smallest B for which the prediction network runs on MFMA tiles
  *             (default 16; bf16 models only; below it one wave per hidden unit does fp32 FMA)
+ *   "debug_stamps"  1: the fused few-rows kernel records phase time stamps, which the next decode
+ *             prints to stderr (development aid; default 0)
  */
 int wind_set_option(wind_model *m, const char *key, int64_t value);
 

@@ -330,16 +330,15 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
     }
     {
       ProfScope ps(m, s, WIND_K_JOINT, capturing);
-      // two tile shapes; each kernel returns at once when the iteration's row count is the other's
+      // one launch, two groups of workgroups: the rows path (rows <= joint_split_rows) and the 256 x 256 tiles
       const int small_rows = max_rows < c.joint_split_rows ? max_rows : c.joint_split_rows;
       const int NT = (d.V + JointRows1::BN - 1) / JointRows1::BN;
-      dim3 grid((unsigned)joint_rows_grid_x(NT, small_rows), (unsigned)NT);
-      if (small_rows > 0) joint_rows_kernel<<<grid, 256, kJointRowsSmem, s>>>(d, c, parity);
-      if (max_rows > c.joint_split_rows) {
-        dim3 gbig((unsigned)((max_rows + JointBigCfg::BM - 1) / JointBigCfg::BM),
-                  (unsigned)((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN));
-        joint_ring5_kernel<JointBigCfg><<<gbig, JointBigCfg::NT, JointBigCfg::SMEM_BYTES, s>>>(d, c, parity);
-      }
+      const int gx = small_rows > 0 ? joint_rows_grid_x(NT, small_rows) : 0;
+      const int rows_blocks = (gx * NT + 7) / 8 * 8;
+      int big_mt = 0, big_nt = (d.V + JointBigCfg::BN - 1) / JointBigCfg::BN;
+      if (max_rows > c.joint_split_rows) big_mt = (max_rows + JointBigCfg::BM - 1) / JointBigCfg::BM;
+      joint_kernel<JointBigCfg><<<(unsigned)(rows_blocks + big_mt * big_nt), JointBigCfg::NT, JointBigCfg::SMEM_BYTES, s>>>(
+          d, c, parity, gx, NT, rows_blocks, big_mt, big_nt);
     }
     {
       ProfScope ps(m, s, WIND_K_DECIDE, capturing);
@@ -553,14 +552,11 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
   }
   if (rc == WIND_OK) {
-    hipError_t e = hipFuncSetAttribute((const void *)joint_rows_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kJointRowsSmem);
+    hipError_t e = hipFuncSetAttribute((const void *)joint_kernel<JointBigCfg>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)tiny_smem_bytes(m->dev, 64));
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)joint_ring5_kernel<JointBigCfg>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);

@@ -1,16 +1,22 @@
 // Device kernels of the WIND greedy decoder (gfx950).  See include/wind.h for the model.
 //
-// One loop iteration (Method, Algorithm 2, all active utterances at once):
+// One loop iteration (Method, Algorithm 2, all active utterances at once), bf16 models:
 //   build_z        window gather: z[r,j,:] = relu(e[b, t_b + j, :] + p[b,:]) in bf16, plus the
-//                  blank logit of every row in fp32
-//   joint_mfma     label logits of every window row on bf16 MFMA; per row and per column part
-//                  the two largest (logit, column) keys are kept, nothing else is stored
+//                  blank logit and the norm of every row in fp32
+//   joint          label logits of every window row on bf16 MFMA; per row and per column part
+//                  the two largest (logit, column) keys are kept, nothing else is stored.  Two
+//                  tile shapes in one launch: 128-column tiles whose height follows the row
+//                  count, and 256 x 256 tiles for the iterations with many rows
 //   decide         per utterance: row argmax from the keys, near-ties re-decided with fp32 dot
 //                  products, first non-blank row by wavefront ballot, pointer / hypothesis update,
-//                  and (last workgroup) compaction of the active and emitting lists
+//                  and (last workgroup) the next iteration's slot table and the emit list
 //   lstm_layer xL  one prediction-network step for the utterances that emitted
 //   pred_proj      p = W_pred h + b_pred for those utterances
-// fp32 models replace build_z + joint_mfma by joint_exact (fp32 FMA, argmax taken directly).
+// With at most 64 window rows, build_z + joint + decide are one kernel (joint_tiny).  The
+// prediction network has three implementations: MFMA tiles with the hidden state split into bf16
+// hi + lo (large batches), low-latency wave-per-unit kernels (a few utterances), generic FMA (fp32
+// models and everything else).  fp32 models replace build_z + joint by joint_exact (fp32 FMA,
+// argmax taken directly).
 #pragma once
 #include "wind_mfma.h"
 #include "wind_mfma_dma.h"
@@ -223,14 +229,13 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Which (row tile, column tile) a workgroup of the joint kernel owns.  Workgroups are handed to the
-// 8 XCDs round-robin by linear id, and each XCD has its own 4 MB L2.  Column tiles are therefore
+// Which (row tile, column tile) of an MT x NT tile grid the workgroup with linear id `lin` owns (lin
+// must be congruent to the workgroup's launch id modulo 8).  Workgroups are handed to the 8 XCDs
+// round-robin by launch id, and each XCD has its own 4 MB L2.  Column tiles are therefore
 // dealt by (linear id mod 8): an XCD always works on the same slice of W_out, which then stays in
 // its L2 across row tiles and across loop iterations, and only the window rows stream in.
-__device__ __forceinline__ void joint_tile_of_block(int &mt, int &nt) {
-  const int MT = gridDim.x, NT = gridDim.y;
-  if (NT % 8 != 0) { mt = blockIdx.x; nt = blockIdx.y; return; }
-  const int lin = blockIdx.y * MT + blockIdx.x;
+__device__ __forceinline__ void joint_tile_of_block(int lin, int MT, int NT, int &mt, int &nt) {
+  if (NT % 8 != 0) { mt = lin % MT; nt = lin / MT; return; }
   const int xcd = lin & 7, idx = lin >> 3, npx = NT >> 3;
   nt = xcd + 8 * (idx % npx);
   mt = idx / npx;
@@ -337,30 +342,13 @@ __device__ __forceinline__ void joint_rows_tile(const ModelDev &m, const CallDev
   joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);
 }
 
-__global__ __launch_bounds__(256) void joint_rows_kernel(ModelDev m, CallDev c, int parity) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  const int n_rows = c.n_active[parity] * c.W;
-  if (n_rows == 0 || n_rows > c.joint_split_rows) return;
-  int mt, nt;
-  joint_tile_of_block(mt, nt);
-  const int mi = (n_rows + 64 * (int)gridDim.x - 1) / (64 * (int)gridDim.x);   // <= 4 by the host's choice of grid
-  switch (mi) {
-    case 1: joint_rows_tile<1>(m, c, n_rows, mt, nt, smem_raw); break;
-    case 2: joint_rows_tile<2>(m, c, n_rows, mt, nt, smem_raw); break;
-    case 3: joint_rows_tile<3>(m, c, n_rows, mt, nt, smem_raw); break;
-    default: joint_rows_tile<4>(m, c, n_rows, mt, nt, smem_raw); break;
-  }
-}
-
-// 256 x 256 tiles on the five-slot ring (see gemm_mainloop_ring5).
+// 256 x 256 tiles on the five-slot ring (see gemm_mainloop_ring5), for iterations with more rows
+// than the rows path balances over the chip.
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void joint_ring5_kernel(ModelDev m, CallDev c, int parity) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  const int n_rows = c.n_active[parity] * c.W;
-  int mt, nt;
-  joint_tile_of_block(mt, nt);
+__device__ __forceinline__ void joint_big_tile(const ModelDev &m, const CallDev &c, int n_rows, int mt, int nt,
+                                               unsigned char *smem_raw) {
   const int row0 = mt * Cfg::BM;
-  if (row0 >= n_rows || n_rows <= c.joint_split_rows) return;
+  if (row0 >= n_rows) return;
   const int n0 = nt * Cfg::BN, Hj = m.Hj;
   f32x16 acc[Cfg::MI][Cfg::NI];
   float bias[Cfg::NI][16];
@@ -368,6 +356,36 @@ __global__ __launch_bounds__(Cfg::NT) void joint_ring5_kernel(ModelDev m, CallDe
   gemm_mainloop_ring5<Cfg, true>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
                                  smem_raw, acc, JointInitAcc<Cfg>{acc, bias});
   joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);   // rows of keys are c.nparts pairs apart for both shapes
+}
+
+// One launch per iteration carries both tile shapes: the first rows_blocks workgroups (a multiple
+// of 8) form the GX x NT grid of the rows path and use four of their eight waves, the others the
+// grid of 256 x 256 tiles.  The iteration's row count decides which of the two groups works; the
+// other group's workgroups return at once.
+template <class BigCfg>
+__global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int parity, int rows_gx, int rows_nt,
+                                                    int rows_blocks, int big_mt, int big_nt) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  static_assert(BigCfg::NT == 512 && BigCfg::SMEM_BYTES >= kJointRowsSmem, "one launch shape for both paths");
+  const int n_rows = c.n_active[parity] * c.W;
+  if (n_rows == 0) return;
+  int mt, nt;
+  if ((int)blockIdx.x < rows_blocks) {
+    if (n_rows > c.joint_split_rows || threadIdx.x >= 256) return;
+    joint_tile_of_block((int)blockIdx.x, rows_gx, rows_nt, mt, nt);
+    if (mt >= rows_gx) return;   // padding of the group to a multiple of 8
+    const int mi = (n_rows + 64 * rows_gx - 1) / (64 * rows_gx);   // <= 4 by the host's choice of rows_gx
+    switch (mi) {
+      case 1: joint_rows_tile<1>(m, c, n_rows, mt, nt, smem_raw); break;
+      case 2: joint_rows_tile<2>(m, c, n_rows, mt, nt, smem_raw); break;
+      case 3: joint_rows_tile<3>(m, c, n_rows, mt, nt, smem_raw); break;
+      default: joint_rows_tile<4>(m, c, n_rows, mt, nt, smem_raw); break;
+    }
+  } else {
+    if (n_rows <= c.joint_split_rows) return;
+    joint_tile_of_block((int)blockIdx.x - rows_blocks, big_mt, big_nt, mt, nt);
+    joint_big_tile<BigCfg>(m, c, n_rows, mt, nt, smem_raw);
+  }
 }
 
 // Debug: the same tile core with the logits stored, bias added (columns 0..V, blank included).
