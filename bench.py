@@ -59,7 +59,9 @@ def run_workload(torch, wi, WindModel, name, windows, steps, warmup, with_sequen
         res["seq" if W is None else str(W)] = {
             "frames_per_s": frames / sec, "rtfx": frames * FRAME_SECONDS / sec, "ms_per_step": sec * 1e3,
             "iterations": int(st.iterations), "rows": int(st.rows), "useful_rows": int(st.useful_rows),
-            "labels": int(st.labels), "rechecks": int(st.rechecks)}
+            "labels": int(st.labels), "rechecks": int(st.rechecks),
+            # pointer advance per window, 0..W (Analysis, Jump Distribution)
+            "jump_hist": [int(x) for x in st.jump_hist[:(1 if W is None else W) + 1]]}
     return cfg, model, (d_enc, d_len, out), frames, res, (enc, lens, w)
 
 
@@ -99,6 +101,36 @@ def roofline_leg(torch, cfg, model, dev, W):
         "kernel_ms": {k: round(v[0], 3) for k, v in kt.items()},
         "kernel_launches": {k: int(v[1]) for k, v in kt.items()},
     }
+
+
+def graph_ablation(torch, wi, WindModel, steps, warmup):
+    """The structure of the paper's graph ablation (Analysis, Incorporation with CUDA-graphs: batch 16,
+    sequential against window 8, each with and without graph replay) on the batch32 model cut to 16
+    utterances.  Times are whole decode calls on device-resident encoder outputs, i.e. the paper's
+    decoder-only time plus the encoder projection.  Without the graph the same kernels are launched
+    one by one; the host still polls once per 16 iterations in both modes."""
+    cfg = wi.scaled(wi.CONFIGS["batch32"], 16, wi.CONFIGS["batch32"].len_lo, wi.CONFIGS["batch32"].len_hi)
+    w = wi.make_weights(cfg)
+    enc, lens = wi.make_batch(cfg)
+    model = WindModel.from_config(cfg, w)
+    d_enc = torch.from_numpy(enc).cuda()
+    d_len = torch.from_numpy(lens).cuda()
+    B, T, _ = enc.shape
+    cap = T * cfg.S
+    out = (torch.zeros((B, cap), dtype=torch.int32, device="cuda"),
+           torch.zeros((B, cap), dtype=torch.int32, device="cuda"),
+           torch.zeros((B,), dtype=torch.int32, device="cuda"))
+    res = {"workload": f"batch32 model, B=16, {int(lens.sum())} frames", "unit": "ms per decode call"}
+    for name, W in (("sequential", None), ("wind_w8", 8)):
+        row = {}
+        for graph in (0, 1):
+            model.set_option("graph", graph)
+            row["graph" if graph else "no_graph"] = round(
+                timed_decodes(torch, model, d_enc, d_len, W, cfg.S, steps, warmup, out) * 1e3, 3)
+        res[name] = row
+    model.set_option("graph", 1)
+    model.close()
+    return res
 
 
 def cpu_baseline(wi, cfg, enc, lens, w, budget_frames):
@@ -142,6 +174,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy, the known-size reference for the HBM byte counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ablation", action="store_true", help="skip the graph / no-graph table at batch 16")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (utterances are independent; more GPUs would "
@@ -189,6 +222,8 @@ def main():
     del dev, model
     torch.cuda.empty_cache()
 
+    if not args.no_ablation:
+        line["graph_ablation"] = graph_ablation(torch, wi, WindModel, max(1, min(args.steps, 3)), 1)
     if not args.no_roofline:
         rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload, None,
                                                             max(1, min(args.steps, 3)), 1, with_sequential=False)
