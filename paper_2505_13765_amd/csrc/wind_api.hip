@@ -260,7 +260,7 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
   const CallDev &c = m->call;
   const int lstm_blocks = (d.Hp + 3) / 4, proj_blocks = (d.Hj + 3) / 4;
   const bool mfma = m->dtype == WIND_BF16 && c.B >= m->opt_pred_mfma_min_batch;
-  const bool small_k = d.E + d.Hp <= 512 * kSmallKSteps && 2 * d.Hp <= 512 * kSmallKSteps;   // the low-latency kernels' K range
+  const bool small_k = 2 * d.Hp <= 512 * kSmallKSteps;   // the low-latency kernels' K range
   constexpr int R = PredCfg::BM / 2;
   const unsigned mtiles = (unsigned)((c.B + R - 1) / R);
   {
@@ -496,12 +496,13 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
   const int Hp = w->Hp;
   chk(upload_matrix(m, w->emb, (size_t)w->V + 1, w->E, (size_t)w->V + 1, &d.emb));
   for (int l = 0; l < w->L && rc == WIND_OK; ++l) {
-    const int in = l == 0 ? w->E : Hp, K = in + Hp;
+    // layer 0 keeps only its recurrent half here; its input half becomes the emb_gates table below
+    const int in = l == 0 ? 0 : Hp, K = in + Hp;
     std::vector<float> cat((size_t)4 * Hp * K), bias((size_t)4 * Hp);
     for (int g = 0; g < 4; ++g)
       for (int j = 0; j < Hp; ++j) {
         const size_t src = (size_t)g * Hp + j, dst = (size_t)j * 4 + g;
-        std::memcpy(&cat[dst * K], w->w_ih[l] + src * in, sizeof(float) * in);
+        if (in) std::memcpy(&cat[dst * K], w->w_ih[l] + src * in, sizeof(float) * in);
         std::memcpy(&cat[dst * K + in], w->w_hh[l] + src * Hp, sizeof(float) * Hp);
         bias[dst] = w->b_ih[l][src] + w->b_hh[l][src];
       }
@@ -509,6 +510,34 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     const void *bp = nullptr;
     chk(upload(m, bias, &bp));
     d.b_cat[l] = (const float *)bp;
+    if (l == 0 && rc == WIND_OK) {
+      // emb_gates[v][4j+g] = b_ih + b_hh + w_ih[gate g of unit j] . emb[v], in the model's storage precision
+      std::vector<float> ih((size_t)4 * Hp * w->E);
+      for (int g = 0; g < 4; ++g)
+        for (int j = 0; j < Hp; ++j)
+          std::memcpy(&ih[((size_t)j * 4 + g) * w->E], w->w_ih[0] + ((size_t)g * Hp + j) * w->E, sizeof(float) * w->E);
+      const void *d_ih = nullptr;
+      chk(upload_matrix(m, ih.data(), (size_t)4 * Hp, w->E, (size_t)4 * Hp, &d_ih));
+      void *table = nullptr;
+      if (rc == WIND_OK) {
+        hipError_t e = hipMalloc(&table, (size_t)(w->V + 1) * 4 * Hp * sizeof(float));
+        if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipMalloc(emb_gates): ") + hipGetErrorString(e));
+        else m->allocs.push_back(table);
+      }
+      if (rc == WIND_OK) {
+        dim3 grid((unsigned)((w->V + 1 + 63) / 64), (unsigned)((4 * Hp + 63) / 64));
+        if (m->dtype == WIND_BF16)
+          emb_gates_kernel<bf16_t><<<grid, 256>>>((const bf16_t *)d.emb, (const bf16_t *)d_ih, d.b_cat[0], (float *)table,
+                                                  w->V + 1, 4 * Hp, w->E);
+        else
+          emb_gates_kernel<float><<<grid, 256>>>((const float *)d.emb, (const float *)d_ih, d.b_cat[0], (float *)table,
+                                                 w->V + 1, 4 * Hp, w->E);
+        chk(check_launch("emb_gates"));
+        hipError_t e = hipDeviceSynchronize();
+        if (rc == WIND_OK && e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("emb_gates: ") + hipGetErrorString(e));
+        d.emb_gates = (const float *)table;
+      }
+    }
     if (m->dtype == WIND_BF16) {
       // MFMA layout: tile column n0 + g*UB + u = gate g of unit n0/4 + u
       constexpr int UB = PredCfg::BN / 4;

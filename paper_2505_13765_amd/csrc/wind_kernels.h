@@ -35,8 +35,13 @@ struct ModelDev {
   int D, E, Hp, L, Hj, V;
   int Vpad;                     // rows of w_out (>= V+1, zero filled past V)
   const void *emb;              // [V+1, E]
-  const void *w_cat[kMaxLayers];  // [4Hp, in_l + Hp]; row 4*j+g = gate g (i,f,g,o) of unit j; [w_ih | w_hh]
-  const float *b_cat[kMaxLayers]; // [4Hp] same row order, b_ih + b_hh
+  // The first layer's input is an embedding row, so its input half of the gate sums is a table
+  // lookup: emb_gates[v][4*j+g] = b_ih + b_hh + w_ih[gate g of unit j] . emb[v], built once at load.
+  const float *emb_gates;       // [V+1, 4Hp] fp32
+  // Recurrent weights.  Layer 0: [4Hp, Hp] = w_hh (in_0 = 0 below); layer l > 0: [4Hp, in_l + Hp] =
+  // [w_ih | w_hh] with in_l = Hp.  Row 4*j+g = gate g (i,f,g,o) of unit j.
+  const void *w_cat[kMaxLayers];
+  const float *b_cat[kMaxLayers]; // [4Hp] same row order, b_ih + b_hh (layers > 0)
   const void *w_cat_t[kMaxLayers]; // bf16 models: the same rows grouped for MFMA tiles, see lstm_layer_dma_kernel
   const float *b_cat_t[kMaxLayers];
   const void *w_enc;            // [Hj_pad, D]
@@ -1002,9 +1007,52 @@ __global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Load time: out[v][r] = bias[r] + sum_k w[r][k] * emb[v][k] for v < nv, r < nr (fp32 accumulation,
+// k ascending).  Plain LDS-tiled product, 64 x 64 outputs per workgroup, 4 x 4 per thread.
+template <class WT>
+__global__ __launch_bounds__(256) void emb_gates_kernel(const WT *emb, const WT *w, const float *bias, float *out,
+                                                        int nv, int nr, int E) {
+  __shared__ float as[16][65], bs[16][65];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int v0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+  for (int k0 = 0; k0 < E; k0 += 16) {
+    for (int idx = threadIdx.x; idx < 64 * 16; idx += 256) {
+      const int row = idx >> 4, kk = idx & 15, k = k0 + kk;
+      as[kk][row] = (v0 + row < nv && k < E) ? ldw(emb, (size_t)(v0 + row) * E + k) : 0.f;
+      bs[kk][row] = (r0 + row < nr && k < E) ? ldw(w, (size_t)(r0 + row) * E + k) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = as[kk][ty * 4 + i]; b[i] = bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int v = v0 + ty * 4 + i, r = r0 + tx * 4 + j;
+      if (v < nv && r < nr) out[(size_t)v * nr + r] = acc[i][j] + bias[r];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // One LSTM cell for the utterances on the emit list.  One wave per hidden unit: its four gate rows
 // are dotted with [x ; h_prev] of R utterances at a time (weights are read once per group).
-//   x = embedding of the emitted label (layer 0) or the new h of the layer below.
+//   x = the new h of the layer below; layer 0 has no x part, the emitted label's row of emb_gates
+//   carries its input sums and biases.
 template <class WT, int R>
 __global__ __launch_bounds__(256) void lstm_layer_kernel(ModelDev m, CallDev c, int layer) {
   const int n_emit = *c.n_emit;
@@ -1012,7 +1060,7 @@ __global__ __launch_bounds__(256) void lstm_layer_kernel(ModelDev m, CallDev c, 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int unit = blockIdx.x * 4 + wave;
   if (unit >= m.Hp) return;
-  const int Hp = m.Hp, in = layer == 0 ? m.E : Hp, K = in + Hp;
+  const int Hp = m.Hp, in = layer == 0 ? 0 : Hp, K = in + Hp;
   const WT *w = reinterpret_cast<const WT *>(m.w_cat[layer]) + (size_t)unit * 4 * K;
   const float *bias = m.b_cat[layer] + unit * 4;
   const size_t lofs = (size_t)layer * c.B * Hp;
@@ -1021,13 +1069,13 @@ __global__ __launch_bounds__(256) void lstm_layer_kernel(ModelDev m, CallDev c, 
   for (int r0 = 0; r0 < n_emit; r0 += R) {
     float acc[4][R];
     int ub[R];
-    const WT *xe[R];     // layer 0 input: embedding row of the emitted label
+    const float *xg[R];  // layer 0: the label's row of input gate sums
     const float *xh[R];  // deeper layers: new hidden vector of the layer below
     const float *hp[R];  // this layer's previous hidden vector
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       ub[r] = c.emit_idx[min(r0 + r, n_emit - 1)];
-      xe[r] = reinterpret_cast<const WT *>(m.emb) + (size_t)c.emit_list_tok[min(r0 + r, n_emit - 1)] * m.E;
+      xg[r] = m.emb_gates + (size_t)c.emit_list_tok[min(r0 + r, n_emit - 1)] * 4 * Hp + unit * 4;
       xh[r] = c.hn + (layer == 0 ? 0 : lofs - (size_t)c.B * Hp) + (size_t)ub[r] * Hp;
       hp[r] = c.h + lofs + (size_t)ub[r] * Hp;
 #pragma unroll
@@ -1050,8 +1098,7 @@ __global__ __launch_bounds__(256) void lstm_layer_kernel(ModelDev m, CallDev c, 
 #pragma unroll
         for (int q = 0; q < VEC; ++q) {
           const int kk = k + q;
-          if (kk < in) xv[q] = layer == 0 ? ldw(xe[r], kk) : xh[r][kk];
-          else xv[q] = hp[r][kk - in];
+          xv[q] = kk < in ? xh[r][kk] : hp[r][kk - in];
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g)
@@ -1067,10 +1114,11 @@ __global__ __launch_bounds__(256) void lstm_layer_kernel(ModelDev m, CallDev c, 
     for (int r = 0; r < R; ++r) {
       if (lane == r && r0 + r < n_emit) {
         const size_t si = lofs + (size_t)ub[r] * Hp + unit;
-        const float ig = 1.f / (1.f + expf(-(acc[0][r] + bias[0])));
-        const float fg = 1.f / (1.f + expf(-(acc[1][r] + bias[1])));
-        const float gg = tanhf(acc[2][r] + bias[2]);
-        const float og = 1.f / (1.f + expf(-(acc[3][r] + bias[3])));
+        const float *add = layer == 0 ? xg[r] : bias;
+        const float ig = 1.f / (1.f + expf(-(acc[0][r] + add[0])));
+        const float fg = 1.f / (1.f + expf(-(acc[1][r] + add[1])));
+        const float gg = tanhf(acc[2][r] + add[2]);
+        const float og = 1.f / (1.f + expf(-(acc[3][r] + add[3])));
         const float cn = fg * c.c[si] + ig * gg;
         c.c[si] = cn;
         c.hn[si] = og * tanhf(cn);
@@ -1144,7 +1192,7 @@ template <int R>
 __global__ __launch_bounds__(256) void lstm_small_kernel(ModelDev m, CallDev c, int layer) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int unit = blockIdx.x * 4 + wave;
-  const int Hp = m.Hp, in = layer == 0 ? m.E : Hp, K = in + Hp;
+  const int Hp = m.Hp, in = layer == 0 ? 0 : Hp, K = in + Hp;   // layer 0: input sums come from emb_gates
   const size_t lofs = (size_t)layer * c.B * Hp;
   // round trip 1: the emit list (entries past n_emit hold valid, stale ids: harmless to read)
   const int n_emit = *c.n_emit;
@@ -1176,28 +1224,25 @@ __global__ __launch_bounds__(256) void lstm_small_kernel(ModelDev m, CallDev c, 
       if (r0 == 0) { ub[r] = ub0[r]; tok[r] = tok0[r]; }
       else { const int idx = min(r0 + r, n_emit - 1); ub[r] = c.emit_idx[idx]; tok[r] = c.emit_list_tok[idx]; }
     }
-    // round trip 2: inputs, previous hidden vectors, cell state
+    // round trip 2: inputs, previous hidden vectors, cell state, the label's input gate sums
     float xv[R][kSmallKSteps][8];
     float cprev[R];
+    float4 add[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const size_t si = lofs + (size_t)ub[r] * Hp;
       cprev[r] = c.c[si + unit];
+      add[r] = *reinterpret_cast<const float4 *>(layer == 0 ? m.emb_gates + (size_t)tok[r] * 4 * Hp + unit * 4 : bias);
 #pragma unroll
       for (int s2 = 0; s2 < kSmallKSteps; ++s2) {
         const int k = lane * 8 + 512 * s2;
 #pragma unroll
         for (int q = 0; q < 8; ++q) xv[r][s2][q] = 0.f;
         if (k < in) {
-          if (layer == 0) {
-            const u32x4 raw = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.emb) + (size_t)tok[r] * m.E + k);
-            unpack_bf16x8(raw, xv[r][s2]);
-          } else {
-            const f32x4 *src = reinterpret_cast<const f32x4 *>(c.hn + si - (size_t)c.B * Hp + k);
-            const f32x4 a = src[0], b2 = src[1];
-            xv[r][s2][0] = a.x; xv[r][s2][1] = a.y; xv[r][s2][2] = a.z; xv[r][s2][3] = a.w;
-            xv[r][s2][4] = b2.x; xv[r][s2][5] = b2.y; xv[r][s2][6] = b2.z; xv[r][s2][7] = b2.w;
-          }
+          const f32x4 *src = reinterpret_cast<const f32x4 *>(c.hn + si - (size_t)c.B * Hp + k);
+          const f32x4 a = src[0], b2 = src[1];
+          xv[r][s2][0] = a.x; xv[r][s2][1] = a.y; xv[r][s2][2] = a.z; xv[r][s2][3] = a.w;
+          xv[r][s2][4] = b2.x; xv[r][s2][5] = b2.y; xv[r][s2][6] = b2.z; xv[r][s2][7] = b2.w;
         } else if (k < K) {
           const f32x4 *src = reinterpret_cast<const f32x4 *>(c.h + si + (k - in));
           const f32x4 a = src[0], b2 = src[1];
@@ -1230,10 +1275,10 @@ __global__ __launch_bounds__(256) void lstm_small_kernel(ModelDev m, CallDev c, 
     for (int r = 0; r < R; ++r) {
       if (lane == r && r0 + r < n_emit) {
         const size_t si = lofs + (size_t)ub[r] * Hp + unit;
-        const float ig = 1.f / (1.f + expf(-(acc[0][r] + bias[0])));
-        const float fg = 1.f / (1.f + expf(-(acc[1][r] + bias[1])));
-        const float gg = tanhf(acc[2][r] + bias[2]);
-        const float og = 1.f / (1.f + expf(-(acc[3][r] + bias[3])));
+        const float ig = 1.f / (1.f + expf(-(acc[0][r] + add[r].x)));
+        const float fg = 1.f / (1.f + expf(-(acc[1][r] + add[r].y)));
+        const float gg = tanhf(acc[2][r] + add[r].z);
+        const float og = 1.f / (1.f + expf(-(acc[3][r] + add[r].w)));
         const float cn = fg * cprev[r] + ig * gg;
         c.c[si] = cn;
         c.hn[si] = og * tanhf(cn);
@@ -1341,7 +1386,7 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
   const int row0 = blockIdx.y * R;
   if (row0 >= n_emit) return;
   const int n0 = blockIdx.x * Cfg::BN;
-  const int Hp = m.Hp, in = layer == 0 ? m.E : Hp, K = in + Hp;
+  const int Hp = m.Hp, in = layer == 0 ? 0 : Hp, K = in + Hp;   // layer 0: input sums come from emb_gates
   const size_t lofs = (size_t)layer * c.B * Hp;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   PredRows<Cfg> rows;
@@ -1356,14 +1401,7 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
       const int r = row - part * R;
       const int ub = c.emit_idx[min(row0 + r, n_emit - 1)];
       const size_t si = lofs + (size_t)ub * Hp;
-      if (layer == 0) {
-        if (!part) {
-          rows.px[i] = reinterpret_cast<const bf16_t *>(m.emb) + (size_t)c.emit_list_tok[min(row0 + r, n_emit - 1)] * m.E + chunk * 8;
-          rows.xstep[i] = 1;
-        } else {
-          rows.px[i] = c.hb_zero + chunk * 8;
-        }
-      } else {
+      if (layer > 0) {
         rows.px[i] = (part ? c.hbn_lo : c.hbn_hi) + si - (size_t)c.B * Hp + chunk * 8;
         rows.xstep[i] = 1;
       }
@@ -1396,10 +1434,13 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
     if (row0 + r >= n_emit) continue;
     const int ub = c.emit_idx[row0 + r];
     const float *hi = tile + r * TS + u, *lo = tile + (R + r) * TS + u;
-    const float gi = hi[0] + lo[0] + bias[u];
-    const float gf = hi[UB] + lo[UB] + bias[UB + u];
-    const float gg = hi[2 * UB] + lo[2 * UB] + bias[2 * UB + u];
-    const float go = hi[3 * UB] + lo[3 * UB] + bias[3 * UB + u];
+    float4 add = make_float4(bias[u], bias[UB + u], bias[2 * UB + u], bias[3 * UB + u]);
+    if (layer == 0)
+      add = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)c.emit_list_tok[row0 + r] * 4 * Hp + n0 + 4 * u);
+    const float gi = hi[0] + lo[0] + add.x;
+    const float gf = hi[UB] + lo[UB] + add.y;
+    const float gg = hi[2 * UB] + lo[2 * UB] + add.z;
+    const float go = hi[3 * UB] + lo[3 * UB] + add.w;
     const size_t si = lofs + (size_t)ub * Hp + (n0 >> 2) + u;
     const float ig = 1.f / (1.f + expf(-gi)), fg = 1.f / (1.f + expf(-gf));
     const float og = 1.f / (1.f + expf(-go));
