@@ -1379,16 +1379,47 @@ template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, CallDev c, int layer) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
-  const int n_emit = *c.n_emit;
   // grid = (column tiles, row tiles): workgroups with consecutive ids share the row tile, and the
   // row tiles of one column tile land on the same XCD (id mod 8), which then fetches that slice of
   // the weights once
   const int row0 = blockIdx.y * R;
-  if (row0 >= n_emit) return;
   const int n0 = blockIdx.x * Cfg::BN;
   const int Hp = m.Hp, in = layer == 0 ? 0 : Hp, K = in + Hp;   // layer 0: input sums come from emb_gates
   const size_t lofs = (size_t)layer * c.B * Hp;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // round trip 1: the emit count and the list entries this thread will need (entries past the
+  // count hold stale but valid ids, so the reads need not wait for the count)
+  const int n_emit = *c.n_emit;
+  int ub_row[Cfg::LPW];
+#pragma unroll
+  for (int i = 0; i < Cfg::LPW; ++i) {
+    const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
+    const int r = row < Cfg::BM ? (row >= R ? row - R : row) : 0;
+    ub_row[i] = c.emit_idx[min(row0 + r, c.B - 1)];
+  }
+  constexpr int EPI = (R * UB + Cfg::NT - 1) / Cfg::NT;   // (utterance, unit) pairs per thread in the epilogue
+  int ub_e[EPI], tok_e[EPI];
+#pragma unroll
+  for (int q = 0; q < EPI; ++q) {
+    const int r = min((tid + q * Cfg::NT) / UB, R - 1);
+    ub_e[q] = c.emit_idx[min(row0 + r, c.B - 1)];
+    tok_e[q] = c.emit_list_tok[min(row0 + r, c.B - 1)];
+  }
+  if (row0 >= n_emit) return;
+  // round trip 2, requested ahead of the tile core's loads and used after it: cell state and the
+  // additive term (bias, or the label's row of input gate sums) of this thread's pairs
+  const float *bias = m.b_cat_t[layer] + n0;
+  float c_prev[EPI];
+  float4 add_e[EPI];
+#pragma unroll
+  for (int q = 0; q < EPI; ++q) {
+    const int idx = tid + q * Cfg::NT, r = min(idx / UB, R - 1), u = idx % UB;
+    c_prev[q] = c.c[lofs + (size_t)ub_e[q] * Hp + (n0 >> 2) + u];
+    add_e[q] = make_float4(bias[u], bias[UB + u], bias[2 * UB + u], bias[3 * UB + u]);
+    if (layer == 0) add_e[q] = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok_e[q] * 4 * Hp + n0 + 4 * u);
+    (void)r;
+  }
+  __builtin_amdgcn_sched_barrier(0);   // these requests stay ahead of the tile core's
   PredRows<Cfg> rows;
   rows.kin = in / Cfg::BK;
 #pragma unroll
@@ -1398,9 +1429,7 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
     rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
     if (row < Cfg::BM) {
       const int part = row >= R;
-      const int r = row - part * R;
-      const int ub = c.emit_idx[min(row0 + r, n_emit - 1)];
-      const size_t si = lofs + (size_t)ub * Hp;
+      const size_t si = lofs + (size_t)ub_row[i] * Hp;
       if (layer > 0) {
         rows.px[i] = (part ? c.hbn_lo : c.hbn_hi) + si - (size_t)c.B * Hp + chunk * 8;
         rows.xstep[i] = 1;
@@ -1428,23 +1457,20 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
       for (int r = 0; r < 16; ++r)
         tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
   __syncthreads();
-  const float *bias = m.b_cat_t[layer] + n0;
-  for (int idx = tid; idx < R * UB; idx += Cfg::NT) {
+#pragma unroll
+  for (int q = 0; q < EPI; ++q) {
+    const int idx = tid + q * Cfg::NT;
     const int r = idx / UB, u = idx - r * UB;
-    if (row0 + r >= n_emit) continue;
-    const int ub = c.emit_idx[row0 + r];
+    if (idx >= R * UB || row0 + r >= n_emit) continue;
     const float *hi = tile + r * TS + u, *lo = tile + (R + r) * TS + u;
-    float4 add = make_float4(bias[u], bias[UB + u], bias[2 * UB + u], bias[3 * UB + u]);
-    if (layer == 0)
-      add = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)c.emit_list_tok[row0 + r] * 4 * Hp + n0 + 4 * u);
-    const float gi = hi[0] + lo[0] + add.x;
-    const float gf = hi[UB] + lo[UB] + add.y;
-    const float gg = hi[2 * UB] + lo[2 * UB] + add.z;
-    const float go = hi[3 * UB] + lo[3 * UB] + add.w;
-    const size_t si = lofs + (size_t)ub * Hp + (n0 >> 2) + u;
+    const float gi = hi[0] + lo[0] + add_e[q].x;
+    const float gf = hi[UB] + lo[UB] + add_e[q].y;
+    const float gg = hi[2 * UB] + lo[2 * UB] + add_e[q].z;
+    const float go = hi[3 * UB] + lo[3 * UB] + add_e[q].w;
+    const size_t si = lofs + (size_t)ub_e[q] * Hp + (n0 >> 2) + u;
     const float ig = 1.f / (1.f + expf(-gi)), fg = 1.f / (1.f + expf(-gf));
     const float og = 1.f / (1.f + expf(-go));
-    const float cn = fg * c.c[si] + ig * tanhf(gg);
+    const float cn = fg * c_prev[q] + ig * tanhf(gg);
     c.c[si] = cn;
     store_hi_lo(c.hbn_hi, c.hbn_lo, si, og * tanhf(cn));
   }
@@ -1454,10 +1480,60 @@ template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, CallDev c) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   constexpr int R = Cfg::BM / 2, TS = Cfg::BN + 4;
-  const int n_emit = *c.n_emit;
-  if (n_emit == 0) return;
   const int Hp = m.Hp, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  {  // commit the new hidden vectors (hi and lo): every layer has read the old ones by now
+  // grid = (column tiles, row tiles): workgroups with consecutive ids share the row tile, and the
+  // row tiles of one column tile land on the same XCD (id mod 8), which then fetches that slice of
+  // the weights once
+  const int row0 = blockIdx.y * R;
+  const int n0 = blockIdx.x * Cfg::BN;
+  // one round trip for the emit count and the list entries (entries past the count are stale but valid)
+  const int n_emit = *c.n_emit;
+  int ub_row[Cfg::LPW];
+#pragma unroll
+  for (int i = 0; i < Cfg::LPW; ++i) {
+    const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
+    const int r = row < Cfg::BM ? (row >= R ? row - R : row) : 0;
+    ub_row[i] = c.emit_idx[min(row0 + r, c.B - 1)];
+  }
+  if (n_emit == 0) return;
+  if (row0 < n_emit) {
+    const size_t top = (size_t)(m.L - 1) * c.B * Hp;
+    PredRows<Cfg> rows;
+    rows.kin = 0;
+#pragma unroll
+    for (int i = 0; i < Cfg::LPW; ++i) {
+      const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
+      const int chunk = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
+      rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
+      if (row < Cfg::BM) rows.ph[i] = (row >= R ? c.hbn_lo : c.hbn_hi) + top + (size_t)ub_row[i] * Hp + chunk * 8;
+    }
+    f32x16 acc[Cfg::MI][Cfg::NI];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+    gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)n0 * Hp, Hp, smem_raw, acc);
+    __syncthreads();
+    float *tile = reinterpret_cast<float *>(smem_raw);
+    const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
+    __syncthreads();
+    for (int idx = tid; idx < R * Cfg::BN; idx += Cfg::NT) {
+      const int r = idx / Cfg::BN, col = idx - r * Cfg::BN;
+      if (row0 + r >= n_emit || n0 + col >= m.Hj) continue;
+      c.p[(size_t)c.emit_idx[row0 + r] * m.Hj + n0 + col] = tile[r * TS + col] + tile[(R + r) * TS + col] + m.b_pred[n0 + col];
+    }
+  }
+  {  // commit the new hidden vectors (hi and lo): every layer has read the old ones by now.  Last,
+     // so that the copy's round trips do not delay the projection.
     const size_t total = (size_t)m.L * n_emit * Hp;
     const size_t nthreads = (size_t)gridDim.x * gridDim.y * Cfg::NT;
     for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * Cfg::NT + tid; i < total; i += nthreads) {
@@ -1468,50 +1544,6 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, Call
       c.hb_hi[si] = c.hbn_hi[si];
       c.hb_lo[si] = c.hbn_lo[si];
     }
-  }
-  // grid = (column tiles, row tiles): workgroups with consecutive ids share the row tile, and the
-  // row tiles of one column tile land on the same XCD (id mod 8), which then fetches that slice of
-  // the weights once
-  const int row0 = blockIdx.y * R;
-  if (row0 >= n_emit) return;
-  const int n0 = blockIdx.x * Cfg::BN;
-  const size_t top = (size_t)(m.L - 1) * c.B * Hp;
-  PredRows<Cfg> rows;
-  rows.kin = 0;
-#pragma unroll
-  for (int i = 0; i < Cfg::LPW; ++i) {
-    const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
-    const int chunk = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
-    rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
-    if (row < Cfg::BM) {
-      const int part = row >= R;
-      const int ub = c.emit_idx[min(row0 + row - part * R, n_emit - 1)];
-      rows.ph[i] = (part ? c.hbn_lo : c.hbn_hi) + top + (size_t)ub * Hp + chunk * 8;
-    }
-  }
-  f32x16 acc[Cfg::MI][Cfg::NI];
-#pragma unroll
-  for (int mi = 0; mi < Cfg::MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < Cfg::NI; ++ni)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-  gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)n0 * Hp, Hp, smem_raw, acc);
-  __syncthreads();
-  float *tile = reinterpret_cast<float *>(smem_raw);
-  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
-#pragma unroll
-  for (int mi = 0; mi < Cfg::MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < Cfg::NI; ++ni)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
-  __syncthreads();
-  for (int idx = tid; idx < R * Cfg::BN; idx += Cfg::NT) {
-    const int r = idx / Cfg::BN, col = idx - r * Cfg::BN;
-    if (row0 + r >= n_emit || n0 + col >= m.Hj) continue;
-    c.p[(size_t)c.emit_idx[row0 + r] * m.Hj + n0 + col] = tile[r * TS + col] + tile[(R + r) * TS + col] + m.b_pred[n0 + col];
   }
 }
 

@@ -174,12 +174,14 @@ def test_fused_few_rows_kernel(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
-@pytest.mark.parametrize("name,B,lo,hi,W", [("largevocab_b128", 20, 20, 70, 16), ("lowblank_b256", 40, 20, 80, 16),
+@pytest.mark.parametrize("name,B,lo,hi,W", [("largevocab_b128", 60, 20, 70, 16), ("lowblank_b256", 40, 20, 80, 16),
                                             ("batch32", 9, 30, 140, 8)])
 def test_both_joint_tile_shapes(torch_cuda, name, B, lo, hi, W):
-    """The 128 x 128 and the 256 x 256 joint kernels must give the oracle's result; the split point
-    is moved so that each of them handles every iteration once, and once so that the decode
-    switches from one to the other as utterances finish."""
+    """Both groups of the joint kernel (128-column tiles of 64 to 256 rows, and 256 x 256 tiles) must
+    give the oracle's result; the split point is moved so that each of them handles every iteration
+    once, and once so that the decode switches from one to the other as utterances finish.  The
+    first case starts at 960 rows, so the 128-column tiles run at all four heights as utterances
+    finish."""
     cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
     m, o, _ = load(cfg)
     enc, lens = wi.make_batch(cfg)
