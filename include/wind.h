@@ -135,7 +135,8 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
 
 /*
  * Per-kernel device time, for the roofline report.  With option "profile" = 1 the decode loop is
- * launched kernel by kernel (no graph) with an event pair around every launch; this call returns
+ * launched kernel by kernel (no graph) and every launch carries an event pair that receives the
+ * dispatch's begin and end time stamps (the kernel's own duration, without launch gaps); this call returns
  * the accumulated milliseconds and launch counts since the option was last set, indexed by
  * wind_kernel_id.  HOST pointers to WIND_NUM_KERNELS entries each.
  */

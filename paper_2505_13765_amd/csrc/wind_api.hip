@@ -3,6 +3,7 @@
 #include "../../include/wind.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdio>
@@ -222,25 +223,28 @@ int check_launch(const char *what) {
 }
 
 // ---- per-kernel timing -------------------------------------------------------------------------
-struct ProfScope {
-  wind_model *m;
-  hipStream_t s;
-  bool on;
-  ProfScope(wind_model *m_, hipStream_t s_, int kind, bool capturing) : m(m_), s(s_), on(m_->opt_profile && !capturing) {
-    if (!on) return;
+// Launches a kernel; with option "profile" the launch carries an event pair that receives the
+// dispatch's own begin and end time stamps (the duration a profiler reports for the kernel).
+template <class... KArgs, class... Args>
+void launch(wind_model *m, hipStream_t s, int kind, bool capturing, void (*kernel)(KArgs...), dim3 grid, dim3 block,
+            size_t smem, Args... args) {
+  if (m->opt_profile && !capturing) {
     const size_t i = m->ev_kind.size();
-    while (m->ev_pool.size() < 2 * (i + 1)) {
+    bool ok = true;
+    while (ok && m->ev_pool.size() < 2 * (i + 1)) {
       hipEvent_t e = nullptr;
-      if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
-      m->ev_pool.push_back(e);
+      ok = hipEventCreate(&e) == hipSuccess;
+      if (ok) m->ev_pool.push_back(e);
     }
-    m->ev_kind.push_back(kind);
-    (void)hipEventRecord(m->ev_pool[2 * i], s);
+    if (ok) {
+      m->ev_kind.push_back(kind);
+      hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, s, m->ev_pool[2 * i], m->ev_pool[2 * i + 1], 0,
+                            static_cast<KArgs>(args)...);
+      return;
+    }
   }
-  ~ProfScope() {
-    if (on) (void)hipEventRecord(m->ev_pool[2 * (m->ev_kind.size() - 1) + 1], s);
-  }
-};
+  hipLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, s, static_cast<KArgs>(args)...);
+}
 
 // call after the stream has been synchronised
 void prof_collect(wind_model *m) {
@@ -263,26 +267,26 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
   const bool small_k = 2 * d.Hp <= 512 * kSmallKSteps;   // the low-latency kernels' K range
   constexpr int R = PredCfg::BM / 2;
   const unsigned mtiles = (unsigned)((c.B + R - 1) / R);
-  {
-    ProfScope ps(m, s, WIND_K_LSTM, capturing);
-    for (int l = 0; l < d.L; ++l) {
-      if (mfma)
-        lstm_layer_dma_kernel<PredCfg><<<dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles), PredCfg::NT,
-                                         PredCfg::SMEM_BYTES, s>>>(d, c, l);
-      else if (m->dtype == WIND_BF16 && small_k) lstm_small_kernel<2><<<lstm_blocks, 256, 0, s>>>(d, c, l);
-      else if (m->dtype == WIND_BF16) lstm_layer_kernel<bf16_t, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
-      else lstm_layer_kernel<float, 4><<<lstm_blocks, 256, 0, s>>>(d, c, l);
-    }
-  }
-  {
-    ProfScope ps(m, s, WIND_K_PRED_PROJ, capturing);
+  for (int l = 0; l < d.L; ++l) {
     if (mfma)
-      pred_proj_dma_kernel<PredCfg><<<dim3((unsigned)(d.Hj / PredCfg::BN), mtiles), PredCfg::NT,
-                                      PredCfg::SMEM_BYTES, s>>>(d, c);
-    else if (m->dtype == WIND_BF16 && small_k) pred_small_kernel<2><<<proj_blocks, 256, 0, s>>>(d, c);
-    else if (m->dtype == WIND_BF16) pred_proj_kernel<bf16_t, 4><<<proj_blocks, 256, 0, s>>>(d, c);
-    else pred_proj_kernel<float, 4><<<proj_blocks, 256, 0, s>>>(d, c);
+      launch(m, s, WIND_K_LSTM, capturing, lstm_layer_dma_kernel<PredCfg>, dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles),
+             dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l);
+    else if (m->dtype == WIND_BF16 && small_k)
+      launch(m, s, WIND_K_LSTM, capturing, lstm_small_kernel<2>, dim3(lstm_blocks), dim3(256), 0, d, c, l);
+    else if (m->dtype == WIND_BF16)
+      launch(m, s, WIND_K_LSTM, capturing, lstm_layer_kernel<bf16_t, 4>, dim3(lstm_blocks), dim3(256), 0, d, c, l);
+    else
+      launch(m, s, WIND_K_LSTM, capturing, lstm_layer_kernel<float, 4>, dim3(lstm_blocks), dim3(256), 0, d, c, l);
   }
+  if (mfma)
+    launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_dma_kernel<PredCfg>, dim3((unsigned)(d.Hj / PredCfg::BN), mtiles),
+           dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c);
+  else if (m->dtype == WIND_BF16 && small_k)
+    launch(m, s, WIND_K_PRED_PROJ, capturing, pred_small_kernel<2>, dim3(proj_blocks), dim3(256), 0, d, c);
+  else if (m->dtype == WIND_BF16)
+    launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_kernel<bf16_t, 4>, dim3(proj_blocks), dim3(256), 0, d, c);
+  else
+    launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_kernel<float, 4>, dim3(proj_blocks), dim3(256), 0, d, c);
   return check_launch("prediction step");
 }
 
@@ -291,14 +295,14 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
   const CallDev &c = m->call;
   init_state_kernel<<<1, 256, 0, s>>>(d, c);
   if (c.T > 0) {
-    ProfScope ps(m, s, WIND_K_ENC_PROJ, false);
     if (m->dtype == WIND_BF16) {
       const int tiles_per_utt = (c.T + EncCfg::BM - 1) / EncCfg::BM;
       dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncCfg::BN - 1) / EncCfg::BN));
-      enc_proj_mfma_kernel<EncCfg><<<grid, EncCfg::NT, EncCfg::SMEM_BYTES, s>>>(d, c, tiles_per_utt);
+      launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_mfma_kernel<EncCfg>, grid, dim3(EncCfg::NT), EncCfg::SMEM_BYTES, d, c,
+             tiles_per_utt);
     } else {
-      dim3 grid((unsigned)c.T, (unsigned)c.B);
-      enc_proj_f32_kernel<<<grid, 256, (size_t)d.D * 4, s>>>(d, c);
+      launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_f32_kernel, dim3((unsigned)c.T, (unsigned)c.B), dim3(256),
+             (size_t)d.D * 4, d, c);
     }
   }
   int rc = check_launch("prologue");
@@ -321,15 +325,11 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
   const int max_rows = c.B * c.W;
   const int decide_threads = 64 * (c.W < 16 ? c.W : 16);
   if (m->dtype == WIND_BF16 && tiny_rows_ok(m, max_rows)) {
-    ProfScope ps(m, s, WIND_K_JOINT, capturing);
-    joint_tiny_kernel<bf16_t><<<(unsigned)c.nparts_tiny, 256, tiny_smem_bytes(d, max_rows), s>>>(d, c, parity);
+    launch(m, s, WIND_K_JOINT, capturing, joint_tiny_kernel<bf16_t>, dim3((unsigned)c.nparts_tiny), dim3(256),
+           tiny_smem_bytes(d, max_rows), d, c, parity);
   } else if (m->dtype == WIND_BF16) {
+    launch(m, s, WIND_K_BUILD_Z, capturing, build_z_kernel, dim3((unsigned)((max_rows + 3) / 4)), dim3(256), 0, d, c, parity);
     {
-      ProfScope ps(m, s, WIND_K_BUILD_Z, capturing);
-      build_z_kernel<<<(max_rows + 3) / 4, 256, 0, s>>>(d, c, parity);
-    }
-    {
-      ProfScope ps(m, s, WIND_K_JOINT, capturing);
       // one launch, two groups of workgroups: the rows path (rows <= joint_split_rows) and the 256 x 256 tiles
       const int small_rows = max_rows < c.joint_split_rows ? max_rows : c.joint_split_rows;
       const int NT = (d.V + JointRows1::BN - 1) / JointRows1::BN;
@@ -337,23 +337,14 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
       const int rows_blocks = (gx * NT + 7) / 8 * 8;
       int big_mt = 0, big_nt = (d.V + JointBigCfg::BN - 1) / JointBigCfg::BN;
       if (max_rows > c.joint_split_rows) big_mt = (max_rows + JointBigCfg::BM - 1) / JointBigCfg::BM;
-      joint_kernel<JointBigCfg><<<(unsigned)(rows_blocks + big_mt * big_nt), JointBigCfg::NT, JointBigCfg::SMEM_BYTES, s>>>(
-          d, c, parity, gx, NT, rows_blocks, big_mt, big_nt);
+      launch(m, s, WIND_K_JOINT, capturing, joint_kernel<JointBigCfg>, dim3((unsigned)(rows_blocks + big_mt * big_nt)),
+             dim3(JointBigCfg::NT), JointBigCfg::SMEM_BYTES, d, c, parity, gx, NT, rows_blocks, big_mt, big_nt);
     }
-    {
-      ProfScope ps(m, s, WIND_K_DECIDE, capturing);
-      decide_kernel<bf16_t><<<c.B, decide_threads, 0, s>>>(d, c, parity, 0);
-    }
+    launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
   } else {
-    {
-      ProfScope ps(m, s, WIND_K_JOINT, capturing);
-      joint_exact_kernel<float><<<max_rows, 256, (size_t)d.Hj * 4, s>>>(d, c, parity, 1, 0, 0, 0, nullptr, 0,
-                                                                       nullptr, nullptr);
-    }
-    {
-      ProfScope ps(m, s, WIND_K_DECIDE, capturing);
-      decide_kernel<float><<<c.B, decide_threads, 0, s>>>(d, c, parity, 1);
-    }
+    launch(m, s, WIND_K_JOINT, capturing, joint_exact_kernel<float>, dim3((unsigned)max_rows), dim3(256), (size_t)d.Hj * 4,
+           d, c, parity, 1, 0, 0, 0, (const float *)nullptr, 0, (float *)nullptr, (bf16_t *)nullptr);
+    launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<float>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 1);
   }
   int rc = check_launch("iteration");
   if (rc) return rc;
