@@ -151,12 +151,16 @@ def cpu_baseline(wi, cfg, enc, lens, w, budget_frames):
         tot += int(lens[b])
     sub_enc = np.ascontiguousarray(enc[pick])
     sub_len = np.ascontiguousarray(lens[pick])
-    t0 = time.perf_counter()
-    o.greedy_batch(sub_enc, sub_len, cfg.S, threads=threads)
-    sec = time.perf_counter() - t0
+    # the sample is decoded again and again until about ten seconds of CPU work have been timed
+    reps, sec = 0, 0.0
+    while sec < 10.0 and reps < 64:
+        t0 = time.perf_counter()
+        o.greedy_batch(sub_enc, sub_len, cfg.S, threads=threads)
+        sec += time.perf_counter() - t0
+        reps += 1
     used = min(threads, len(pick))
-    return {"value": tot / sec, "unit": "frames/s", "cores": used, "kind": "oracle",
-            "sample": f"{len(pick)} of {len(lens)} utterances of {cfg.name} ({tot} frames), "
+    return {"value": tot * reps / sec, "unit": "frames/s", "cores": used, "kind": "oracle",
+            "sample": f"{len(pick)} of {len(lens)} utterances of {cfg.name} ({tot} frames), decoded {reps} times, "
                       f"sequential greedy in fp64, one thread per utterance", "seconds": sec}
 
 
