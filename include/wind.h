@@ -165,7 +165,13 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *             per row tile that it takes to fill the chip; 1024 for V = 8192)
  *   "pred_mfma_min_batch"  smallest B for which the prediction network runs on MFMA tiles
  *             (default 16; bf16 models only; below it one wave per hidden unit does fp32 FMA)
- *   "debug_stamps"  1: the fused few-rows kernel records phase time stamps, which the next decode
+ *   "loop_kernel"  1 (default): decodes of one or two utterances with at most 32 window rows (bf16, one
+ *             LSTM layer, weights that fit the chip's LDS) run the whole loop as one resident kernel
+ *             whose workgroups meet at grid barriers; 0: always the graph of per-step kernels
+ *   "loop_spin_limit"  polls a workgroup of that kernel waits at a barrier before it gives up
+ *             (default 2^21, about a second); the decode then returns WIND_ERR_HIP.  Tests set it
+ *             to 0 to exercise that path: every workgroup still leaves the kernel normally
+ *   "debug_stamps"  1: the few-rows kernels record phase time stamps, which the next decode
  *             prints to stderr (development aid; default 0)
  */
 int wind_set_option(wind_model *m, const char *key, int64_t value);

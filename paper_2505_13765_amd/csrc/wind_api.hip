@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
+#include <algorithm>
 
 #include <cmath>
 #include <cstdio>
@@ -95,7 +96,10 @@ struct wind_model {
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_joint_split_rows = -1;   // -1: joint_split_default(V)
   int opt_tiny_rows = kTinyRowsDefault;
+  int opt_loop_kernel = 1;
+  long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
+  LoopDev loop{};
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
@@ -174,7 +178,9 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   const size_t o_parts = take(Mpad * (size_t)(nparts_tiny > nparts ? nparts_tiny : nparts) * 8);
   const size_t o_rl = take(Mpad * 4);
   const size_t o_stats = take(kNumStats * 8);
-  const size_t o_dbg = take(64);
+  const size_t o_dbg = take(128);
+  const size_t o_lbar = take((size_t)(1 + 256) * kLoopFlagStride * 4), o_lh = take((size_t)kLoopMaxB * d.Hp * 4), o_lp = take((size_t)kLoopMaxB * d.Hj * 4);
+  const size_t o_lparts = take((size_t)2 * kLoopRows * nparts_tiny * 8);
   if (off > m->ws_bytes) {
     HIP_TRY(hipDeviceSynchronize());
     if (m->ws) HIP_TRY(hipFree(m->ws));
@@ -213,6 +219,10 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
   c.dbg = m->opt_debug_stamps ? (long long *)(base + o_dbg) : nullptr;
+  m->loop.bar = (unsigned *)(base + o_lbar);
+  m->loop.h_x = (float *)(base + o_lh);
+  m->loop.p_x = (float *)(base + o_lp);
+  m->loop.parts_x = (float2 *)(base + o_lparts);
   return WIND_OK;
 }
 
@@ -390,13 +400,38 @@ int fetch_stats(wind_model *m, hipStream_t s) {
   for (int i = 0; i <= WIND_MAX_WINDOW; ++i) st.jump_hist[i] = (int64_t)h[kStatJump0 + i];
   m->have_stats = true;
   if (m->call.dbg) {
-    long long d[8];
-    if (hipMemcpy(d, m->call.dbg, sizeof(d), hipMemcpyDeviceToHost) == hipSuccess && d[5] > 0)
+    long long d[16];
+    if (hipMemcpy(d, m->call.dbg, sizeof(d), hipMemcpyDeviceToHost) == hipSuccess && d[10] > 0)
+      std::fprintf(stderr, "[wind debug] resident loop, workgroup 0, avg us per iteration: gather %.2f  mfma+keys %.2f  barrier1 %.2f  decide %.2f | per emitting iteration: lstm %.2f  barrier2 %.2f  hcopy+pred %.2f  barrier3 %.2f  pcopy %.2f  (%lld iterations, %lld emitting)\n",
+                   d[0] / 100.0 / d[10], d[1] / 100.0 / d[10], d[2] / 100.0 / d[10], d[3] / 100.0 / d[10], d[4] / 100.0 / (d[11] ? d[11] : 1),
+                   d[5] / 100.0 / (d[11] ? d[11] : 1), d[6] / 100.0 / (d[11] ? d[11] : 1), d[7] / 100.0 / (d[11] ? d[11] : 1), d[8] / 100.0 / (d[11] ? d[11] : 1), d[10], d[11]);
+    else if (d[5] > 0)
       std::fprintf(stderr, "[wind debug] few-rows kernel, deciding workgroup, avg us: setup+gather %.2f  mfma+keys %.2f  hand-over %.2f  decide %.2f  compact %.2f  (%lld launches)\n",
                    d[0] / 100.0 / d[5], d[1] / 100.0 / d[5], d[2] / 100.0 / d[5], d[3] / 100.0 / d[5], d[4] / 100.0 / d[5], d[5]);
-    (void)hipMemset(m->call.dbg, 0, 64);
+    (void)hipMemset(m->call.dbg, 0, 128);
   }
   return h[ST_OVERFLOW] ? WIND_ERR_OVERFLOW : WIND_OK;
+}
+
+// Shape of the resident loop kernel for this call, or false if the call does not qualify: bf16, one
+// LSTM layer, at most 2 utterances and 32 window rows, every workgroup's weight slice within LDS,
+// at most one workgroup per CU.
+bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *smem) {
+  const ModelDev &d = m->dev;
+  if (m->dtype != WIND_BF16 || d.L != 1 || B > kLoopMaxB || B * W > kLoopRows || d.Hj > kTinyMaxHj) return false;
+  if (!m->opt_loop_kernel || m->opt_profile || !m->opt_graph) return false;
+  const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
+  const int widest = d.Hp > d.Hj ? d.Hp : d.Hj;
+  int G = (widest + 15) / 16;
+  if (G < nparts_tiny) G = nparts_tiny;
+  if (G > 256) return false;
+  lp->G = G;
+  lp->upw = ((d.Hp + G - 1) / G + 3) / 4 * 4;
+  lp->ppw = ((d.Hj + G - 1) / G + 3) / 4 * 4;
+  *smem = loop_smem_bytes(d.Hp, d.Hj, B, lp->upw, lp->ppw);
+  if (lp->upw > 16) return false;                                   // a wave steps at most four units
+  if (nparts_tiny * 8 > (d.Hj + 8) * 2) return false;              // a row's keys fit where its hidden vector was
+  return *smem + 6144 <= 160 * 1024;   // room for the kernel's static LDS
 }
 
 int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T, int W, int S,
@@ -419,6 +454,25 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
 
   rc = enqueue_prologue(m, s);
   if (rc) return rc;
+  LoopDev lp = m->loop;
+  size_t loop_smem = 0;
+  if (loop_kernel_shape(m, B, W, &lp, &loop_smem)) {
+    // the whole loop as one resident kernel
+    lp.max_iters = (int)std::min<long long>((long long)T * (S + 1) + 2, 1 << 30);
+    lp.spin_limit = (unsigned)m->opt_loop_spin_limit;
+    HIP_TRY(hipMemsetAsync(lp.bar, 0, (size_t)(1 + lp.G) * kLoopFlagStride * 4, s));
+    wind_loop_kernel<<<(unsigned)lp.G, 256, loop_smem, s>>>(m->dev, c, lp);
+    rc = check_launch("resident loop");
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(m->h_flag + 1, lp.bar, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (m->h_flag[1] != 0) return fail(WIND_ERR_HIP, "resident loop: a grid barrier timed out (workgroups not all resident?)");
+    if (m->h_flag[0] != 0) return fail(WIND_ERR_HIP, "decode loop did not terminate");
+    rc = fetch_stats(m, s);
+    if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
+    return rc;
+  }
   const int U = m->opt_unroll;
   const bool use_graph = m->opt_graph && !m->opt_profile;   // events cannot sit between graph nodes
   if (use_graph) {
@@ -578,6 +632,8 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
       e = hipFuncSetAttribute((const void *)joint_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)tiny_smem_bytes(m->dev, 64));
     if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)wind_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 154 * 1024);
+    if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
     if (e == hipSuccess)
@@ -668,6 +724,15 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
     if (value < 0) return fail(WIND_ERR_ARG, "joint_split_rows must be >= 0");
     m->opt_joint_split_rows = value > (1 << 30) ? (1 << 30) : (int)value;
     m->graph_valid = false;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "loop_kernel")) {
+    m->opt_loop_kernel = value != 0;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "loop_spin_limit")) {
+    if (value < 0 || value > (1ll << 30)) return fail(WIND_ERR_ARG, "loop_spin_limit must be in 0..2^30");
+    m->opt_loop_spin_limit = value;
     return WIND_OK;
   }
   if (!std::strcmp(key, "pred_mfma_min_batch")) {

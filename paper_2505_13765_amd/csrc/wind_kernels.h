@@ -629,7 +629,7 @@ struct RowsAhead {
 template <class WT, bool LOCAL>
 __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int a, int4 st, int cnt,
                                                  int exact_mode, int nparts, int stride, int part_width,
-                                                 const RowsAhead &ahead, DecideShared &sh) {
+                                                 const RowsAhead &ahead, DecideShared &sh, bool write_out = true) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int b = st.x, t = st.y, len = st.z, V = m.V;
   const int n = min(c.W, len - t);
@@ -680,8 +680,10 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
       } else {
         tok = sh.label[i];
         if (cnt < c.cap) {
-          c.out_tokens[(size_t)b * c.cap + cnt] = tok;
-          c.out_frames[(size_t)b * c.cap + cnt] = t + i;
+          if (write_out) {
+            c.out_tokens[(size_t)b * c.cap + cnt] = tok;
+            c.out_frames[(size_t)b * c.cap + cnt] = t + i;
+          }
           ++cnt;
         } else {
           overflow = 1;
@@ -692,7 +694,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
         emitted = 1;
         if (sym >= c.S) { tn += 1; sym = 0; jump += 1; forced = 1; }
       }
-      if (emitted) c.out_counts[b] = cnt;
+      if (emitted && write_out) c.out_counts[b] = cnt;
       const int active = tn < len;
       const int flag = active | ((emitted & active) << 1);
       // counters of this window, summed by the compacting wave: n (7 bits), useful rows (7), jump (7),
@@ -1545,6 +1547,516 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, Call
       c.hb_lo[si] = c.hbn_lo[si];
     }
   }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Small decodes as ONE resident kernel.  With one or two utterances and at most 32 window rows the
+// loop of Algorithm 2 is a chain of short dependent steps, and between kernels every hand-over costs
+// a launch gap plus cold caches.  Here G workgroups stay on the chip for the whole decode; each
+// keeps its slice of the weights next to its ALUs for all iterations: 32 columns of W_out as MFMA
+// fragments in registers, the recurrent weights of `upw` LSTM units and `ppw` rows of W_pred in LDS.
+// What an iteration needs from the other workgroups goes through three exchanges in memory, each
+// behind a grid barrier: the rows' keys (every workgroup then takes the same decisions and keeps
+// the same pointers, so no state travels), the new hidden vector, the new projection.  An
+// iteration without a label has one barrier.
+//
+// The barrier is one arrival word per workgroup that only grows; a workgroup that waits longer than
+// spin_limit polls, or sees the abort word set, sets it and leaves the kernel, so every wave
+// reaches the end whatever happens to the others.  The host treats a set abort word as an error.  All G workgroups must be
+// resident at once; the host launches at most one per CU.
+struct LoopDev {
+  unsigned *bar;       // word 0: abort; word (1 + g) * 32: barriers workgroup g has reached; all zero at launch
+  float *h_x;          // [B][Hp] new hidden vectors
+  float *p_x;          // [B][Hj] new projections
+  float2 *parts_x;     // [2][32][nparts_tiny] keys, by iteration parity
+  int G, upw, ppw;     // workgroups; LSTM units and W_pred rows per workgroup (multiples of 4)
+  int max_iters;       // more iterations than any decode of this call can take
+  unsigned spin_limit;
+};
+constexpr int kLoopMaxB = 2;
+constexpr int kLoopRows = 32;
+
+struct LoopShared {
+  int4 nslot[kLoopMaxB];
+  int ncnt[kLoopMaxB];
+  int emit_ub[kLoopMaxB], emit_tok[kLoopMaxB];
+  int n_act, n_emit, ok;
+};
+
+// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: 32 rows of Hj+8 bf16][hfull: B*Hp f32]
+//      [pfull: B*Hj f32][cst: B*upw f32]
+__host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw) {
+  return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + (size_t)kLoopRows * (Hj + 8) * 2 + (size_t)B * Hp * 4 +
+         (size_t)B * Hj * 4 + (size_t)B * upw * 4;
+}
+
+// Values that another workgroup of the running kernel wrote are read and written with agent-scope
+// atomics (they go past the caches that are private to a CU or an XCD), so that the barrier needs
+// no cache invalidation and the read-only operands stay in L2 from iteration to iteration.
+__device__ __forceinline__ float ld_shared_f32(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_shared_f32(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_shared_f32x2(const float2 *p) {
+  const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+}
+__device__ __forceinline__ void st_shared_f32x2(float2 *p, float2 v) {
+  const unsigned long long u = (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kLoopFlagStride = 32;   // one 128-byte line per workgroup's arrival word
+__device__ __forceinline__ bool loop_barrier(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
+  __syncthreads();   // this workgroup's stores of the phase have been issued and acknowledged
+  if (threadIdx.x < 64) {
+    const unsigned epoch = ++passed;
+    if (threadIdx.x == 0) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and are visible to the agent before the arrival is
+      __hip_atomic_store(&lp.bar[(1 + blockIdx.x) * kLoopFlagStride], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // every workgroup publishes the number of barriers it has reached; wave 0 watches all of them,
+    // one lane per workgroup (no read-modify-write on a shared word: the arrivals do not queue up)
+    unsigned spins = 0;
+    int good = 1;
+    for (;;) {
+      bool here = true;
+      for (int w0 = 0; w0 < lp.G; w0 += 64) {
+        const int w = w0 + (int)threadIdx.x;
+        unsigned v = epoch;
+        if (w < lp.G) v = __hip_atomic_load(&lp.bar[(1 + w) * kLoopFlagStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        here = here && (int)(v - epoch) >= 0;
+      }
+      if (__all(here)) break;
+      const unsigned ab = __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (++spins > lp.spin_limit || ab) { good = 0; break; }
+    }
+    if (threadIdx.x == 0) {
+      if (!good) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ls.ok = good;
+    }
+  } else {
+    ++passed;
+  }
+  __syncthreads();
+  asm volatile("" ::: "memory");   // the exchange reads that follow stay behind the wait
+  return ls.ok != 0;
+}
+
+// Sums of 16 (4) per-lane values over the wave with a halving exchange: lanes 4v..4v+3 (16v..16v+15)
+// end up holding the wave's total of value v.
+__device__ __forceinline__ float wave_sum16_scatter(const float (&v)[16], int lane) {
+  float a[8], b[4], c2[2];
+  const bool u5 = (lane & 32) != 0, u4 = (lane & 16) != 0, u3 = (lane & 8) != 0, u2 = (lane & 4) != 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = (u5 ? v[i + 8] : v[i]) + __shfl_xor(u5 ? v[i] : v[i + 8], 32, kWave);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = (u4 ? a[i + 4] : a[i]) + __shfl_xor(u4 ? a[i] : a[i + 4], 16, kWave);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) c2[i] = (u3 ? b[i + 2] : b[i]) + __shfl_xor(u3 ? b[i] : b[i + 2], 8, kWave);
+  float d = (u2 ? c2[1] : c2[0]) + __shfl_xor(u2 ? c2[0] : c2[1], 4, kWave);
+  d += __shfl_xor(d, 2, kWave);
+  d += __shfl_xor(d, 1, kWave);
+  return d;
+}
+__device__ __forceinline__ float wave_sum8_scatter(const float (&v)[8], int lane) {   // lanes 8v..8v+7 get value v
+  float a[4], b[2];
+  const bool u5 = (lane & 32) != 0, u4 = (lane & 16) != 0, u3 = (lane & 8) != 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = (u5 ? v[i + 4] : v[i]) + __shfl_xor(u5 ? v[i] : v[i + 4], 32, kWave);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) b[i] = (u4 ? a[i + 2] : a[i]) + __shfl_xor(u4 ? a[i] : a[i + 2], 16, kWave);
+  float d = (u3 ? b[1] : b[0]) + __shfl_xor(u3 ? b[0] : b[1], 8, kWave);
+#pragma unroll
+  for (int msk = 4; msk >= 1; msk >>= 1) d += __shfl_xor(d, msk, kWave);
+  return d;
+}
+__device__ __forceinline__ float wave_sum4_scatter(const float (&v)[4], int lane) {
+  float a[2];
+  const bool u5 = (lane & 32) != 0, u4 = (lane & 16) != 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) a[i] = (u5 ? v[i + 2] : v[i]) + __shfl_xor(u5 ? v[i] : v[i + 2], 32, kWave);
+  float d = (u4 ? a[1] : a[0]) + __shfl_xor(u4 ? a[0] : a[1], 16, kWave);
+#pragma unroll
+  for (int msk = 8; msk >= 1; msk >>= 1) d += __shfl_xor(d, msk, kWave);
+  return d;
+}
+
+__global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, LoopDev lp) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  __shared__ DecideShared sh;
+  __shared__ LoopShared ls;
+  __shared__ unsigned long long lstats[kNumStats];   // workgroup 0: the call's counters, written out at the end
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = blockIdx.x;
+  const int Hj = m.Hj, Hp = m.Hp, W = c.W, B = c.B;
+  const int zstride = Hj + 8;
+  bf16_t *wl = reinterpret_cast<bf16_t *>(smem_raw);
+  bf16_t *wp = wl + (size_t)lp.upw * 4 * Hp;
+  bf16_t *zs = wp + (size_t)lp.ppw * Hp;
+  float *hfull = reinterpret_cast<float *>(zs + (size_t)kLoopRows * zstride);
+  float *pfull = hfull + (size_t)B * Hp;
+  float *cst = pfull + (size_t)B * Hj;
+
+  // ---- once: this workgroup's weights, the state after the start-token step, the slot table
+  const int unit0 = g * lp.upw, prow0 = g * lp.ppw;
+  for (int i = tid * 8; i < lp.upw * 4 * Hp; i += 256 * 8) {
+    const int row = i / Hp, k = i - row * Hp;           // row = 4 * local unit + gate
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (unit0 + (row >> 2) < Hp)
+      v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.w_cat[0]) + ((size_t)unit0 * 4 + row) * Hp + k);
+    *reinterpret_cast<u32x4 *>(wl + i) = v;
+  }
+  for (int i = tid * 8; i < lp.ppw * Hp; i += 256 * 8) {
+    const int row = i / Hp, k = i - row * Hp;
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (prow0 + row < Hj) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)(prow0 + row) * Hp + k);
+    *reinterpret_cast<u32x4 *>(wp + i) = v;
+  }
+  for (int i = tid; i < B * Hp; i += 256) hfull[i] = c.h[i];
+  for (int i = tid; i < B * Hj; i += 256) pfull[i] = c.p[i];
+  for (int i = tid; i < B * lp.upw; i += 256) {
+    const int b = i / lp.upw, u = i - b * lp.upw;
+    cst[i] = unit0 + u < Hp ? c.c[(size_t)b * Hp + unit0 + u] : 0.f;
+  }
+  if (tid < kLoopMaxB) {
+    sh.slot[tid] = c.slot_state[tid];
+    sh.cnt[tid] = c.slot_count[tid];
+  }
+  for (int i = tid; i < kNumStats; i += 256) lstats[i] = 0ull;
+  // Read-only operands are fetched ahead into this XCD's L2, which nothing invalidates while the
+  // kernel runs: here this workgroup's columns of every row of emb_gates, below the encoder
+  // projections of the window after the current one.
+  float warm = 0.f, pend[2] = {0.f, 0.f};
+  {
+    const int lines = (lp.upw * 16 + 127) / 128;   // 128-byte lines per table row slice
+    for (int i = tid; i < (m.V + 1) * lines; i += 256) {
+      const int v = i / lines, l = i - v * lines;
+      const size_t off = (size_t)v * 4 * Hp + (size_t)unit0 * 4 + l * 32;
+      if (unit0 * 4 + l * 32 < 4 * Hp) warm += m.emb_gates[off];
+    }
+  }
+  int na = c.n_active[0];
+  // W_out fragments of this workgroup's 32 columns, this wave's quarter of K
+  const bool has_cols = g < c.nparts_tiny;
+  const int n0 = (has_cols ? g : 0) * kTinyCols;
+  const int kq = Hj >> 2, k0 = wave * kq, nk = kq >> 4;
+  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
+  bf16x8 bfrag[kTinyPrefetch];
+#pragma unroll
+  for (int i = 0; i < kTinyPrefetch; ++i)
+    if (i < nk) bfrag[i] = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
+  const int cip = lane & 31, col = n0 + cip;
+  const bool col_ok = has_cols && col < m.V;
+  const float col_bias = col_ok ? m.b_out[col_ok ? col : 0] : kKeyNone;
+  const float b_blank = m.b_out[m.V];
+  CallDev cl = c;   // the decision code reads the keys through parts and, for near-ties, the current projections through p
+  cl.p = pfull;
+  cl.parts = reinterpret_cast<float2 *>(zs);   // the iteration's keys are copied over the window rows once those are used up
+  constexpr int KI = kTinyMaxHj / 256;
+  float4 wblank[KI];
+#pragma unroll
+  for (int i = 0; i < KI; ++i) {
+    const int k = lane * 4 + 256 * i;
+    wblank[i] = k < Hj ? *reinterpret_cast<const float4 *>(m.w_blank + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  unsigned passed = 0;
+  __syncthreads();
+
+  const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
+  long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
+  for (int it = 0; it < lp.max_iters && na > 0; ++it) {
+    const int par = it & 1;
+    const long long t0 = dbg ? wall_clock64() : 0;
+    const int n_rows = na * W;
+    float2 *parts = lp.parts_x + (size_t)par * kLoopRows * c.nparts_tiny;
+    for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
+    // ---- window rows into LDS with their fp32 blank logit and norm (every workgroup: all rows)
+    for (int q0 = 0; q0 < 8; q0 += 4) {
+      if (q0 * 4 >= n_rows) continue;   // no window rows in this pass (what those rows of z hold is never looked at)
+      float4 ev[4][KI];
+      bool valid[4];
+      int arow[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = wave + 4 * (q0 + q);
+        valid[q] = false;
+        arow[q] = 0;
+        const float *er = c.e;
+        if (row < n_rows) {
+          const int a = row / W, j = row - a * W;
+          const int4 st = sh.slot[a];
+          valid[q] = st.y + j < st.z;
+          arow[q] = st.x;
+          er = c.e + ((size_t)st.x * c.T + (valid[q] ? st.y + j : 0)) * Hj;
+        }
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+          const int k = lane * 4 + 256 * i;
+          ev[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (valid[q] && k < Hj) ev[q][i] = *reinterpret_cast<const float4 *>(er + k);
+        }
+      }
+      float dn[8];   // [q][blank-logit part, squared norm]
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = wave + 4 * (q0 + q);
+        float dot = 0.f, nrm = 0.f;
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+          const int k = lane * 4 + 256 * i;
+          if (k < Hj) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (valid[q]) {
+              const float4 pv = *reinterpret_cast<const float4 *>(pfull + (size_t)arow[q] * Hj + k);
+              x.x = fmaxf(ev[q][i].x + pv.x, 0.f); x.y = fmaxf(ev[q][i].y + pv.y, 0.f);
+              x.z = fmaxf(ev[q][i].z + pv.z, 0.f); x.w = fmaxf(ev[q][i].w + pv.w, 0.f);
+            }
+            *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+            const float4 wb = wblank[i];
+            dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
+            nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+          }
+        }
+        dn[2 * q] = dot;
+        dn[2 * q + 1] = nrm;
+      }
+      const float tot = wave_sum8_scatter(dn, lane);   // lanes 16q..16q+7: row q's dot; 16q+8..16q+15: its squared norm
+      const int rowq = wave + 4 * (q0 + (lane >> 4));
+      if (rowq < n_rows) {
+        if ((lane & 15) == 0) sh.blank[rowq] = tot + b_blank;
+        if ((lane & 15) == 8) sh.znorm[rowq] = sqrtf(tot);
+      }
+    }
+    // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
+    // are consumed one iteration later, so that no wave ever waits for these loads.
+    {
+      warm += pend[0] + pend[1];
+      pend[0] = 0.f; pend[1] = 0.f;
+      const int lines_per_row = (Hj * 4 + 127) / 128;
+      for (int a = 0; a < na; ++a) {
+        const int4 st = sh.slot[a];
+        const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
+        const int nl = (t_end - t_first) * lines_per_row;
+#pragma unroll
+        for (int i2 = 0; i2 < 2; ++i2) {
+          const int i = tid + 256 * i2;
+          if (i < nl) {
+            const int tr = i / lines_per_row, l = i - tr * lines_per_row;
+            pend[i2] += c.e[((size_t)st.x * c.T + t_first + tr) * Hj + l * 32];
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const long long t1 = dbg ? wall_clock64() : 0;
+    // ---- this workgroup's 32 columns: K split over the four waves, W_out from registers
+    if (has_cols) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      const bf16_t *zrow = zs + (size_t)(lane & 31) * zstride + k0 + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < kTinyPrefetch; ++i)
+        if (i < nk) {
+          const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag[i], acc, 0, 0, 0);
+        }
+      __syncthreads();   // every wave is done with z: its LDS takes the K-split partial sums
+      float *red = reinterpret_cast<float *>(zs);   // [wave][r][lane]
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
+      __syncthreads();
+      if (wave == 0) {
+        float k1[16], k2[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = col_bias;
+#pragma unroll
+          for (int w2 = 0; w2 < 4; ++w2) v += red[(w2 * 16 + r) * 64 + lane];
+          k1[r] = make_key(col_ok ? v : kKeyNone, cip);
+          k2[r] = kKeyNone;
+        }
+        float o1[1], o2[1];
+        RowTop2<16, 0>::run(k1, k2, lane, o1, o2);
+        const int s0 = rowtop2_first_slot<16>(lane);
+        st_shared_f32x2(&parts[(size_t)acc_row(0, s0, lane) * c.nparts_tiny + g], make_float2(o1[0], o2[0]));
+      }
+    }
+    const long long t2 = dbg ? wall_clock64() : 0;
+    if (!loop_barrier(lp, passed, ls)) return;            // exchange 1: every row's keys are in memory
+    const long long t3 = dbg ? wall_clock64() : 0;
+    // ---- the decisions, taken alike by every workgroup; workgroup 0 writes the outputs
+    // With at most 64 parts per row and 4 rows per wave the decision only looks at the keys its
+    // caller hands it, which are read here straight from the exchange buffer; otherwise the keys
+    // are copied to LDS first.
+    float2 *lparts = reinterpret_cast<float2 *>(zs);
+    const bool direct = c.nparts_tiny <= 64 && W <= 4 * kRowsAhead;
+    if (!direct) {
+      for (int i = tid; i < n_rows * c.nparts_tiny; i += 256) lparts[i] = ld_shared_f32x2(parts + i);
+      __syncthreads();
+    }
+    for (int a = 0; a < na; ++a) {
+      RowsAhead ahead;
+#pragma unroll
+      for (int q = 0; q < kRowsAhead; ++q) {
+        const int j = wave + q * 4, row = a * W + j;
+        ahead.kk0[q] = make_float2(kKeyNone, kKeyNone);
+        ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
+        if (j < W) {
+          if (lane < c.nparts_tiny)
+            ahead.kk0[q] = direct ? ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + lane) : lparts[(size_t)row * c.nparts_tiny + lane];
+          ahead.vb[q] = sh.blank[row];
+          ahead.zn[q] = sh.znorm[row];
+        }
+      }
+      decide_utterance<bf16_t, true>(m, cl, a, sh.slot[a], sh.cnt[a], 0, c.nparts_tiny, c.nparts_tiny, kTinyCols, ahead, sh,
+                                     g == 0);
+    }
+    if (wave == 0) {
+      // survivors keep their order; the emit list is the survivors that produced a label
+      if (lane == 0) {
+        int n_act = 0, n_em = 0;
+        for (int a = 0; a < na; ++a) {
+          const int f = sh.flag[a];
+          if (f & 2) { ls.emit_ub[n_em] = sh.slot[a].x; ls.emit_tok[n_em] = sh.tok[a]; ++n_em; }
+          if (f & 1) { ls.nslot[n_act] = sh.slot[a]; ls.ncnt[n_act] = sh.cnt[a]; ++n_act; }
+          if (g == 0) {   // the window's counters (see decide_utterance for the packing)
+            const unsigned ev = sh.event[a];
+            lstats[ST_ROWS] += ev & 127u; lstats[ST_USEFUL] += (ev >> 7) & 127u; lstats[ST_RECHECK] += (ev >> 21) & 127u;
+            lstats[ST_LABELS] += (ev >> 28) & 1u; lstats[ST_FORCED] += (ev >> 29) & 1u; lstats[ST_OVERFLOW] += (ev >> 30) & 1u;
+            lstats[kStatJump0 + ((ev >> 14) & 127u)] += 1ull;
+          }
+        }
+        if (g == 0) { lstats[ST_ITER] += 1ull; lstats[ST_WINDOWS] += (unsigned long long)na; }
+        ls.n_act = n_act;
+        ls.n_emit = n_em;
+      }
+    }
+    __syncthreads();
+    na = ls.n_act;
+    const int n_emit = ls.n_emit;
+    if (tid < na) { sh.slot[tid] = ls.nslot[tid]; sh.cnt[tid] = ls.ncnt[tid]; }
+    __syncthreads();
+    const long long t4 = dbg ? wall_clock64() : 0;
+    if (dbg) { tsum[0] += t1 - t0; tsum[1] += t2 - t1; tsum[2] += t3 - t2; tsum[3] += t4 - t3; ++n_it; }
+    if (n_emit == 0 || na == 0) continue;
+    // ---- one LSTM step for the utterances that emitted: this workgroup's units, weights from LDS
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r], tok = ls.emit_tok[r];
+      // the label's input gate sums of this wave's (at most four) units: one round trip for all
+      float4 addq[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int unit = unit0 + wave + 4 * q;
+        addq[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (wave + 4 * q < lp.upw && unit < Hp) addq[q] = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok * 4 * Hp + unit * 4);
+      }
+      float part[16];   // [unit q][gate]
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int u = wave + 4 * q;
+#pragma unroll
+        for (int gate = 0; gate < 4; ++gate) part[4 * q + gate] = 0.f;
+        if (u >= lp.upw) continue;
+        for (int k = lane * 8; k < Hp; k += 512) {
+          const f32x4 *hs = reinterpret_cast<const f32x4 *>(hfull + (size_t)ub * Hp + k);
+          const f32x4 ha = hs[0], hb2 = hs[1];
+#pragma unroll
+          for (int gate = 0; gate < 4; ++gate) {
+            float wf[8];
+            unpack_bf16x8(*reinterpret_cast<const u32x4 *>(wl + ((size_t)u * 4 + gate) * Hp + k), wf);
+            float a2 = part[4 * q + gate];
+            a2 = fmaf(wf[0], ha.x, a2); a2 = fmaf(wf[1], ha.y, a2); a2 = fmaf(wf[2], ha.z, a2); a2 = fmaf(wf[3], ha.w, a2);
+            a2 = fmaf(wf[4], hb2.x, a2); a2 = fmaf(wf[5], hb2.y, a2); a2 = fmaf(wf[6], hb2.z, a2); a2 = fmaf(wf[7], hb2.w, a2);
+            part[4 * q + gate] = a2;
+          }
+        }
+      }
+      // lanes 16q + 4*gate .. +3 now get the sum of (unit q, gate): every gate's nonlinearity runs on
+      // its own lanes, then lane 16q gathers its unit's four
+      const float tot = wave_sum16_scatter(part, lane);
+      const int q = lane >> 4, gate = (lane >> 2) & 3;
+      float4 aq = addq[0];
+      if (q == 1) aq = addq[1];
+      if (q == 2) aq = addq[2];
+      if (q == 3) aq = addq[3];
+      const float pre = tot + (gate == 0 ? aq.x : gate == 1 ? aq.y : gate == 2 ? aq.z : aq.w);
+      const float act = gate == 2 ? tanhf(pre) : 1.f / (1.f + expf(-pre));
+      const int base = lane & 48;
+      const float ig = __shfl(act, base, kWave), fg = __shfl(act, base + 4, kWave);
+      const float gg = __shfl(act, base + 8, kWave), og = __shfl(act, base + 12, kWave);
+      const int u = wave + 4 * q, unit = unit0 + u;
+      if ((lane & 15) == 0 && u < lp.upw && unit < Hp) {
+        const float cn = fg * cst[ub * lp.upw + u] + ig * gg;
+        cst[ub * lp.upw + u] = cn;
+        st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit], og * tanhf(cn));
+      }
+    }
+    const long long t5 = dbg ? wall_clock64() : 0;
+    if (!loop_barrier(lp, passed, ls)) return;            // exchange 2: the new hidden vectors
+    const long long t6 = dbg ? wall_clock64() : 0;
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r];
+      for (int k = tid; k < Hp; k += 256) hfull[(size_t)ub * Hp + k] = ld_shared_f32(&lp.h_x[(size_t)ub * Hp + k]);
+    }
+    __syncthreads();
+    // ---- this workgroup's rows of the prediction projection
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r];
+      // this wave's rows jl = wave + 4q, q < ppw / 4, four at a time
+      for (int q0 = 0; q0 * 4 < lp.ppw; q0 += 4) {
+        float part[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int jl = wave + 4 * (q0 + q);
+          part[q] = 0.f;
+          if (jl >= lp.ppw) continue;
+          for (int k = lane * 8; k < Hp; k += 512) {
+            const f32x4 *hs = reinterpret_cast<const f32x4 *>(hfull + (size_t)ub * Hp + k);
+            const f32x4 ha = hs[0], hb2 = hs[1];
+            float wf[8];
+            unpack_bf16x8(*reinterpret_cast<const u32x4 *>(wp + (size_t)jl * Hp + k), wf);
+            float a2 = part[q];
+            a2 = fmaf(wf[0], ha.x, a2); a2 = fmaf(wf[1], ha.y, a2); a2 = fmaf(wf[2], ha.z, a2); a2 = fmaf(wf[3], ha.w, a2);
+            a2 = fmaf(wf[4], hb2.x, a2); a2 = fmaf(wf[5], hb2.y, a2); a2 = fmaf(wf[6], hb2.z, a2); a2 = fmaf(wf[7], hb2.w, a2);
+            part[q] = a2;
+          }
+        }
+        const float tot = wave_sum4_scatter(part, lane);   // lanes 16q .. 16q+15 hold row q's sum
+        const int jl = wave + 4 * (q0 + (lane >> 4)), j = prow0 + jl;
+        if ((lane & 15) == 0 && jl < lp.ppw && j < Hj) st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], tot + m.b_pred[j]);
+      }
+    }
+    const long long t7 = dbg ? wall_clock64() : 0;
+    if (!loop_barrier(lp, passed, ls)) return;            // exchange 3: the new projections
+    const long long t8 = dbg ? wall_clock64() : 0;
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r];
+      for (int k = tid; k < Hj; k += 256) pfull[(size_t)ub * Hj + k] = ld_shared_f32(&lp.p_x[(size_t)ub * Hj + k]);
+    }
+    __syncthreads();
+    if (dbg) {
+      const long long t9 = wall_clock64();
+      tsum[4] += t5 - t4; tsum[5] += t6 - t5; tsum[6] += t7 - t6; tsum[7] += t8 - t7; tsum[8] += t9 - t8; ++n_em_it;
+    }
+  }
+  if (dbg) {
+    for (int i = 0; i < 9; ++i) c.dbg[i] += tsum[i];
+    c.dbg[10] += n_it; c.dbg[11] += n_em_it;
+  }
+  __syncthreads();
+  if (g == 0) {
+    for (int i = tid; i < kNumStats; i += 256) c.stats[i] = lstats[i];
+    if (tid == 0) {
+      c.n_active[0] = na;   // zero unless max_iters ran out
+      c.n_active[1] = na;
+    }
+  }
+  if (warm == 1.2345e-30f && lp.spin_limit == 0u) lp.h_x[0] = warm;   // keeps the warming loads alive; never true
 }
 
 }  // namespace wind

@@ -174,6 +174,51 @@ def test_fused_few_rows_kernel(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
+@pytest.mark.parametrize("name,B,lo,hi,W", [("greedy_b1", 1, 150, 150, 16), ("greedy_b1", 1, 130, 130, 1), ("greedy_b1", 1, 120, 120, 32),
+                                            ("greedy_b1", 1, 90, 90, 5), ("greedy_b1", 2, 60, 120, 16), ("batch32", 2, 50, 90, 3)])
+def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
+    """One or two utterances with at most 32 window rows decode in one resident kernel whose
+    workgroups exchange keys, hidden vectors and projections behind grid barriers; it must agree
+    with the oracle and, label for label and counter for counter, with the graph of per-step
+    kernels (loop_kernel = 0)."""
+    cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    res, stats = [], []
+    for lk in (1, 0):
+        m.set_option("loop_kernel", lk)
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        check_outputs(cfg, lens, toks, frs)
+        assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
+        st = m.stats()
+        res.append((toks, frs))
+        stats.append((st.iterations, st.windows, st.rows, st.useful_rows, st.labels, st.forced_advances, st.rechecks,
+                      list(st.jump_hist)))
+    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[1][0]))
+    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], res[1][1]))
+    assert stats[0] == stats[1]
+    m.close()
+
+
+def test_resident_loop_barrier_timeout_is_an_error(torch_cuda):
+    """A workgroup that waits too long at a grid barrier gives up and the call fails loudly.  The
+    wait limit is set to zero polls from the host, so the condition is reached with every workgroup
+    still leaving the kernel normally; the next call with the default limit works again."""
+    cfg = wi.scaled(wi.CONFIGS["greedy_b1"], 1, 60, 60)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    good_t, good_f = m.decode(d_enc, d_len, 8, cfg.S)
+    m.set_option("loop_spin_limit", 0)
+    with pytest.raises(RuntimeError, match="barrier"):
+        m.decode(d_enc, d_len, 8, cfg.S)
+    m.set_option("loop_spin_limit", 1 << 21)
+    toks, frs = m.decode(d_enc, d_len, 8, cfg.S)
+    assert toks[0].tolist() == good_t[0].tolist() and frs[0].tolist() == good_f[0].tolist()
+    m.close()
+
+
 @pytest.mark.parametrize("name,B,lo,hi,W", [("largevocab_b128", 60, 20, 70, 16), ("lowblank_b256", 40, 20, 80, 16),
                                             ("batch32", 9, 30, 140, 8)])
 def test_both_joint_tile_shapes(torch_cuda, name, B, lo, hi, W):
