@@ -429,7 +429,7 @@ bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *s
   lp->upw = ((d.Hp + G - 1) / G + 3) / 4 * 4;
   lp->ppw = ((d.Hj + G - 1) / G + 3) / 4 * 4;
   *smem = loop_smem_bytes(d.Hp, d.Hj, B, lp->upw, lp->ppw);
-  if (lp->upw > 16) return false;                                   // a wave steps at most four units
+  if (lp->upw > 16 || lp->ppw > 16) return false;                   // a wave steps at most four units / rows
   if (nparts_tiny * 8 > (d.Hj + 8) * 2) return false;              // a row's keys fit where its hidden vector was
   return *smem + 6144 <= 160 * 1024;   // room for the kernel's static LDS
 }

@@ -1787,7 +1787,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
         arow[q] = 0;
         const float *er = c.e;
         if (row < n_rows) {
-          const int a = row / W, j = row - a * W;
+          const int a = row >= W ? 1 : 0, j = row - a * W;   // at most two utterances
           const int4 st = sh.slot[a];
           valid[q] = st.y + j < st.z;
           arow[q] = st.x;
@@ -1836,19 +1836,13 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     {
       warm += pend[0] + pend[1];
       pend[0] = 0.f; pend[1] = 0.f;
-      const int lines_per_row = (Hj * 4 + 127) / 128;
+      const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
       for (int a = 0; a < na; ++a) {
         const int4 st = sh.slot[a];
         const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
-        const int nl = (t_end - t_first) * lines_per_row;
-#pragma unroll
-        for (int i2 = 0; i2 < 2; ++i2) {
-          const int i = tid + 256 * i2;
-          if (i < nl) {
-            const int tr = i / lines_per_row, l = i - tr * lines_per_row;
-            pend[i2] += c.e[((size_t)st.x * c.T + t_first + tr) * Hj + l * 32];
-          }
-        }
+        const int l = tid & 31;
+        for (int tr = t_first + (tid >> 5), i2 = 0; tr < t_end; tr += 8, ++i2)
+          if (l < lines_per_row) pend[i2 & 1] += c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
       }
     }
     __syncthreads();
