@@ -558,8 +558,7 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
     const float2 kk = prow[pi];
     cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
   }
-#pragma unroll
-  for (int msk = 32; msk >= 1; msk >>= 1) cnt += __shfl_xor(cnt, msk, kWave);
+  cnt = wave_sum_i32(cnt);
   if (cnt == 1 && vblank < thresh) {
     // a single label clear of blank and of every other label: find its part
     int col = kk0.x == kbest ? lane * part_width + key_col(kbest) : -1;
@@ -757,12 +756,9 @@ __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int 
     n_act += __popcll(ma);
     n_em += __popcll(me);
   }
-#pragma unroll
-  for (int msk = 32; msk >= 1; msk >>= 1) {
-    sum_rows += __shfl_xor(sum_rows, msk, kWave); sum_useful += __shfl_xor(sum_useful, msk, kWave);
-    sum_recheck += __shfl_xor(sum_recheck, msk, kWave); sum_labels += __shfl_xor(sum_labels, msk, kWave);
-    sum_forced += __shfl_xor(sum_forced, msk, kWave); sum_over += __shfl_xor(sum_over, msk, kWave);
-  }
+  sum_rows = (unsigned)wave_sum_i32((int)sum_rows); sum_useful = (unsigned)wave_sum_i32((int)sum_useful);
+  sum_recheck = (unsigned)wave_sum_i32((int)sum_recheck); sum_labels = (unsigned)wave_sum_i32((int)sum_labels);
+  sum_forced = (unsigned)wave_sum_i32((int)sum_forced); sum_over = (unsigned)wave_sum_i32((int)sum_over);
   // one writer per iteration, iterations are ordered on the stream: plain read-modify-write
   for (int j = lane; j <= kMaxWindow; j += 64)
     if (sh.hist[j]) c.stats[kStatJump0 + j] += sh.hist[j];
@@ -1647,42 +1643,52 @@ __device__ __forceinline__ bool loop_barrier(const LoopDev &lp, unsigned &passed
   return ls.ok != 0;
 }
 
-// Sums of 16 (4) per-lane values over the wave with a halving exchange: lanes 4v..4v+3 (16v..16v+15)
-// end up holding the wave's total of value v.
+// Sums of 16 / 8 / 4 per-lane values over the wave with a halving exchange: each step a lane keeps
+// half of its values and adds the partner's copies of them, until one value is left, which the
+// last steps sum over the lanes that still hold parts of it.  The steps that carry the most values
+// pair lanes inside a row of 16 with DPP permutations (row mirror, half mirror); the lane bit that
+// decides which half is kept gives the value's index one bit per step:
+//   16 values: index = b3 b2 b4 b5 (lane bits), i.e. value v ends up, complete, in the four lanes
+//              32*(v&1) + 16*((v>>1)&1) + 4*(v>>2) + 0..3
+//    8 values: index = b3 b2 b4; lanes 16*(v&1) + 4*(v>>1) + 0..3 and the same + 32
+//    4 values: index = b3 b2; lanes 4*v + 0..3 of every row
 __device__ __forceinline__ float wave_sum16_scatter(const float (&v)[16], int lane) {
   float a[8], b[4], c2[2];
-  const bool u5 = (lane & 32) != 0, u4 = (lane & 16) != 0, u3 = (lane & 8) != 0, u2 = (lane & 4) != 0;
+  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0, u4 = (lane & 16) != 0, u5 = (lane & 32) != 0;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a[i] = (u5 ? v[i + 8] : v[i]) + __shfl_xor(u5 ? v[i] : v[i + 8], 32, kWave);
+  for (int i = 0; i < 8; ++i) a[i] = (u3 ? v[i + 8] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 8]);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) b[i] = (u4 ? a[i + 4] : a[i]) + __shfl_xor(u4 ? a[i] : a[i + 4], 16, kWave);
+  for (int i = 0; i < 4; ++i) b[i] = (u2 ? a[i + 4] : a[i]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[i] : a[i + 4]);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) c2[i] = (u3 ? b[i + 2] : b[i]) + __shfl_xor(u3 ? b[i] : b[i + 2], 8, kWave);
-  float d = (u2 ? c2[1] : c2[0]) + __shfl_xor(u2 ? c2[0] : c2[1], 4, kWave);
-  d += __shfl_xor(d, 2, kWave);
-  d += __shfl_xor(d, 1, kWave);
+  for (int i = 0; i < 2; ++i) c2[i] = (u4 ? b[i + 2] : b[i]) + __shfl_xor(u4 ? b[i] : b[i + 2], 16, kWave);
+  float d = (u5 ? c2[1] : c2[0]) + __shfl_xor(u5 ? c2[0] : c2[1], 32, kWave);
+  d += dpp_f32<kDppQuadXor2>(d);
+  d += dpp_f32<kDppQuadXor1>(d);
   return d;
 }
-__device__ __forceinline__ float wave_sum8_scatter(const float (&v)[8], int lane) {   // lanes 8v..8v+7 get value v
+__device__ __forceinline__ float wave_sum8_scatter(const float (&v)[8], int lane) {
   float a[4], b[2];
-  const bool u5 = (lane & 32) != 0, u4 = (lane & 16) != 0, u3 = (lane & 8) != 0;
+  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0, u4 = (lane & 16) != 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a[i] = (u5 ? v[i + 4] : v[i]) + __shfl_xor(u5 ? v[i] : v[i + 4], 32, kWave);
+  for (int i = 0; i < 4; ++i) a[i] = (u3 ? v[i + 4] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 4]);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) b[i] = (u4 ? a[i + 2] : a[i]) + __shfl_xor(u4 ? a[i] : a[i + 2], 16, kWave);
-  float d = (u3 ? b[1] : b[0]) + __shfl_xor(u3 ? b[0] : b[1], 8, kWave);
-#pragma unroll
-  for (int msk = 4; msk >= 1; msk >>= 1) d += __shfl_xor(d, msk, kWave);
+  for (int i = 0; i < 2; ++i) b[i] = (u2 ? a[i + 2] : a[i]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[i] : a[i + 2]);
+  float d = (u4 ? b[1] : b[0]) + __shfl_xor(u4 ? b[0] : b[1], 16, kWave);
+  d += __shfl_xor(d, 32, kWave);
+  d += dpp_f32<kDppQuadXor2>(d);
+  d += dpp_f32<kDppQuadXor1>(d);
   return d;
 }
 __device__ __forceinline__ float wave_sum4_scatter(const float (&v)[4], int lane) {
   float a[2];
-  const bool u5 = (lane & 32) != 0, u4 = (lane & 16) != 0;
+  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) a[i] = (u5 ? v[i + 2] : v[i]) + __shfl_xor(u5 ? v[i] : v[i + 2], 32, kWave);
-  float d = (u4 ? a[1] : a[0]) + __shfl_xor(u4 ? a[0] : a[1], 16, kWave);
-#pragma unroll
-  for (int msk = 8; msk >= 1; msk >>= 1) d += __shfl_xor(d, msk, kWave);
+  for (int i = 0; i < 2; ++i) a[i] = (u3 ? v[i + 2] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 2]);
+  float d = (u2 ? a[1] : a[0]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[0] : a[1]);
+  d += __shfl_xor(d, 16, kWave);
+  d += __shfl_xor(d, 32, kWave);
+  d += dpp_f32<kDppQuadXor2>(d);
+  d += dpp_f32<kDppQuadXor1>(d);
   return d;
 }
 
@@ -1808,7 +1814,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
 #pragma unroll
         for (int i = 0; i < KI; ++i) {
           const int k = lane * 4 + 256 * i;
-          if (k < Hj) {
+          if (k < Hj && row < n_rows) {   // rows past the windows: what z holds there is never looked at
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
             if (valid[q]) {
               const float4 pv = *reinterpret_cast<const float4 *>(pfull + (size_t)arow[q] * Hj + k);
@@ -1824,11 +1830,11 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
         dn[2 * q] = dot;
         dn[2 * q + 1] = nrm;
       }
-      const float tot = wave_sum8_scatter(dn, lane);   // lanes 16q..16q+7: row q's dot; 16q+8..16q+15: its squared norm
-      const int rowq = wave + 4 * (q0 + (lane >> 4));
-      if (rowq < n_rows) {
-        if ((lane & 15) == 0) sh.blank[rowq] = tot + b_blank;
-        if ((lane & 15) == 8) sh.znorm[rowq] = sqrtf(tot);
+      const float tot = wave_sum8_scatter(dn, lane);   // lane 4q: row q's dot; lane 4q + 16: its squared norm
+      const int rowq = wave + 4 * (q0 + ((lane >> 2) & 3));
+      if (rowq < n_rows && (lane & 0x23) == 0) {
+        if (lane & 16) sh.znorm[rowq] = sqrtf(tot);
+        else sh.blank[rowq] = tot + b_blank;
       }
     }
     // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
@@ -1970,21 +1976,21 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
           }
         }
       }
-      // lanes 16q + 4*gate .. +3 now get the sum of (unit q, gate): every gate's nonlinearity runs on
-      // its own lanes, then lane 16q gathers its unit's four
+      // value 4q + gate lands in lanes 4q + 16*(gate>>1) + 32*(gate&1) + 0..3: every gate's
+      // nonlinearity runs on its own lanes, then lane 4q gathers its unit's four
       const float tot = wave_sum16_scatter(part, lane);
-      const int q = lane >> 4, gate = (lane >> 2) & 3;
+      const int q = (lane >> 2) & 3, gate = ((lane >> 4) & 1) * 2 + (lane >> 5);
       float4 aq = addq[0];
       if (q == 1) aq = addq[1];
       if (q == 2) aq = addq[2];
       if (q == 3) aq = addq[3];
       const float pre = tot + (gate == 0 ? aq.x : gate == 1 ? aq.y : gate == 2 ? aq.z : aq.w);
       const float act = gate == 2 ? tanhf(pre) : 1.f / (1.f + expf(-pre));
-      const int base = lane & 48;
-      const float ig = __shfl(act, base, kWave), fg = __shfl(act, base + 4, kWave);
-      const float gg = __shfl(act, base + 8, kWave), og = __shfl(act, base + 12, kWave);
+      const int base = lane & 12;
+      const float ig = __shfl(act, base, kWave), fg = __shfl(act, base + 32, kWave);
+      const float gg = __shfl(act, base + 16, kWave), og = __shfl(act, base + 48, kWave);
       const int u = wave + 4 * q, unit = unit0 + u;
-      if ((lane & 15) == 0 && u < lp.upw && unit < Hp) {
+      if ((lane & 0x33) == 0 && u < lp.upw && unit < Hp) {
         const float cn = fg * cst[ub * lp.upw + u] + ig * gg;
         cst[ub * lp.upw + u] = cn;
         st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit], og * tanhf(cn));
@@ -2020,9 +2026,9 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
             part[q] = a2;
           }
         }
-        const float tot = wave_sum4_scatter(part, lane);   // lanes 16q .. 16q+15 hold row q's sum
-        const int jl = wave + 4 * (q0 + (lane >> 4)), j = prow0 + jl;
-        if ((lane & 15) == 0 && jl < lp.ppw && j < Hj) st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], tot + m.b_pred[j]);
+        const float tot = wave_sum4_scatter(part, lane);   // lanes 4q .. 4q+3 of every row of 16 hold row q's sum
+        const int jl = wave + 4 * (q0 + ((lane >> 2) & 3)), j = prow0 + jl;
+        if ((lane & 0x33) == 0 && jl < lp.ppw && j < Hj) st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], tot + m.b_pred[j]);
       }
     }
     const long long t7 = dbg ? wall_clock64() : 0;

@@ -126,10 +126,6 @@ __device__ __forceinline__ int acc_row(int mi, int r, int lane) {
 // mirror i <-> 7-i, then i ^ 2 and i ^ 1: any sequence of perfect matchings works as long as the
 // two partners own the same slots and disjoint columns); only the last step, which carries the
 // fewest slots, crosses the two rows of 16 through the LDS crossbar.
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
-}
 template <int S>
 __device__ __forceinline__ float rowtop2_partner(float x) {
   if constexpr (S == 0) return dpp_f32<0x140>(x);        // row_mirror

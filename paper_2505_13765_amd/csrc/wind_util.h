@@ -39,18 +39,46 @@ __device__ __forceinline__ float2 ldw2(const bf16_t *p, size_t i) {
   return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xFFFF0000u));
 }
 
+// Wave-wide reductions.  Inside a row of 16 lanes the partners come from DPP permutations, which cost
+// no more than a move (row mirror i <-> 15-i, half mirror i <-> 7-i, then i ^ 2 and i ^ 1: after the
+// four steps every lane of the row holds the row's result); the four row results are then read
+// with v_readlane.  No step goes through the LDS crossbar, whose latency dominated the shuffle
+// version in the latency-bound kernels.  All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int x) {
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, false);
+}
+constexpr int kDppRowMirror = 0x140, kDppRowHalfMirror = 0x141, kDppQuadXor2 = 0x4E, kDppQuadXor1 = 0xB1;
+__device__ __forceinline__ float readlane_f32(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-  return v;
+  v += dpp_f32<kDppRowMirror>(v);
+  v += dpp_f32<kDppRowHalfMirror>(v);
+  v += dpp_f32<kDppQuadXor2>(v);
+  v += dpp_f32<kDppQuadXor1>(v);
+  return (readlane_f32(v, 0) + readlane_f32(v, 16)) + (readlane_f32(v, 32) + readlane_f32(v, 48));
+}
+__device__ __forceinline__ int wave_sum_i32(int v) {
+  v += dpp_i32<kDppRowMirror>(v);
+  v += dpp_i32<kDppRowHalfMirror>(v);
+  v += dpp_i32<kDppQuadXor2>(v);
+  v += dpp_i32<kDppQuadXor1>(v);
+  return (__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16)) +
+         (__builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
 }
 __device__ __forceinline__ int wave_max_i32(int v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    int o = __shfl_xor(v, m, kWave);
-    v = o > v ? o : v;
-  }
-  return v;
+  v = max(v, dpp_i32<kDppRowMirror>(v));
+  v = max(v, dpp_i32<kDppRowHalfMirror>(v));
+  v = max(v, dpp_i32<kDppQuadXor2>(v));
+  v = max(v, dpp_i32<kDppQuadXor1>(v));
+  return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+             max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 // (logit, column) carried in one fp32 word: the low 7 mantissa bits of the logit give way to
@@ -77,9 +105,11 @@ __device__ __forceinline__ void push_top2(float &a1, float &a2, float k) {
   a1 = fmaxf(a1, k);
 }
 __device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
-  return v;
+  v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppRowHalfMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppQuadXor2>(v));
+  v = fmaxf(v, dpp_f32<kDppQuadXor1>(v));
+  return fmaxf(fmaxf(readlane_f32(v, 0), readlane_f32(v, 16)), fmaxf(readlane_f32(v, 32), readlane_f32(v, 48)));
 }
 
 }  // namespace wind
