@@ -133,6 +133,36 @@ def graph_ablation(torch, wi, WindModel, steps, warmup):
     return res
 
 
+def beam_scoring(torch, wi, WindModel, steps):
+    """Time of the beam-search scoring step (Eq. 1 and lines 10-13 of Algorithm 3) on the headline
+    model: 16 hypotheses on a window of 16 frames, 8 expansions each.  Whole calls, device-resident
+    inputs and outputs; the call waits for completion."""
+    import numpy as np
+
+    cfg = wi.CONFIGS["greedy_b1"]
+    w = wi.make_weights(cfg)
+    model = WindModel.from_config(cfg, w)
+    rng = np.random.default_rng(5)
+    Bh, n, K = 16, 16, 8
+    win = torch.from_numpy(wi.round_to_bf16(rng.normal(size=(n, cfg.D)).astype(np.float32))).cuda()
+    g = torch.from_numpy(np.tanh(rng.normal(size=(Bh, cfg.Hp))).astype(np.float32)).cuda()
+    out = (torch.zeros((Bh, K), dtype=torch.int32, device="cuda"), torch.zeros((Bh, K), dtype=torch.int32, device="cuda"),
+           torch.zeros((Bh, K), dtype=torch.float32, device="cuda"))
+    for _ in range(3):
+        model.beam_window_scores(win, g, K, out)
+    torch.cuda.synchronize()
+    reps = max(10, steps * 10)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        model.beam_window_scores(win, g, K, out)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / reps
+    model.close()
+    return {"workload": f"greedy_b1 model, {Bh} hypotheses x {n} frames, K={K}", "us_per_call": round(sec * 1e6, 2),
+            "rows": Bh * n, "logit_bytes": Bh * n * (cfg.V + 1) * 4,
+            "joiner_gflops": round(2.0 * Bh * n * cfg.Hj * (cfg.V + 1) / 1e9, 3)}
+
+
 def cpu_baseline(wi, cfg, enc, lens, w, budget_frames):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -228,6 +258,7 @@ def main():
 
     if not args.no_ablation:
         line["graph_ablation"] = graph_ablation(torch, wi, WindModel, max(1, min(args.steps, 3)), 1)
+        line["beam_scoring"] = beam_scoring(torch, wi, WindModel, args.steps)
     if not args.no_roofline:
         rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload, None,
                                                             max(1, min(args.steps, 3)), 1, with_sequential=False)

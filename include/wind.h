@@ -117,6 +117,27 @@ int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *l
                            int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
                            int32_t *out_counts, int cap, void *stream);
 
+/*
+ * Method, "A Novel Beam-search Algorithm for WIND": the scoring step of Algorithm 3 (its lines
+ * 10-13) for Bh hypotheses that sit on the same frame.  For every hypothesis b the joiner is
+ * evaluated on the n frames of the window against that hypothesis' prediction-network output, the
+ * rows are soft-maxed, and P'(v, t) of Eq. 1 is formed: the probability that v is the first output
+ * in the window and comes at frame t (blank: only as "no output in the whole window", t = n - 1).
+ * Returns the K best (label, jump) pairs of every hypothesis, best first; equal scores are
+ * ordered by earlier frame, then lower label.
+ *   enc_window  DEVICE [n, D] fp32: encoder frames t0 .. t0+n-1 (1 <= n <= 64)
+ *   dec_out     DEVICE [Bh, Hp] fp32: the top LSTM layer's hidden vector of every hypothesis
+ *   K           1..32
+ *   out_labels  DEVICE [Bh, K] int32: label (blank = V); -1 if fewer than K entries have P' > 0
+ *   out_jumps   DEVICE [Bh, K] int32: frame offset inside the window (blank: n - 1)
+ *   out_scores  DEVICE [Bh, K] fp32: log P' of the pair
+ * Hypothesis bookkeeping (Algorithm 3's map from frames to hypotheses, recombination, pruning)
+ * stays with the caller.  Allocates its workspace on first use; returns after completion.
+ * Returns WIND_ERR_ARG for null pointers or sizes out of range (Bh * n <= 65536).
+ */
+int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
+                            int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream);
+
 /* Counters of the last decode call; HOST pointer. */
 int wind_get_stats(wind_model *m, wind_stats *out);
 

@@ -16,7 +16,7 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0
 
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
-           "wind_get_kernel_times")
+           "wind_get_kernel_times", "wind_beam_window_scores")
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
 
 
@@ -73,6 +73,8 @@ def load_library():
                                                 C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         lib.wind_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
         lib.wind_get_kernel_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -170,6 +172,25 @@ class WindModel:
         n = (C.c_int64 * len(KERNEL_NAMES))()
         _check(self._lib.wind_get_kernel_times(self._h, ms, n))
         return {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_NAMES)}
+
+    def beam_window_scores(self, enc_window, dec_out, K: int, out=None):
+        """wind_beam_window_scores on device tensors enc_window [n, D] and dec_out [Bh, Hp] (fp32).
+        Returns (labels, jumps, scores) as numpy arrays [Bh, K]; with `out` = three device tensors the
+        results are left there and nothing is copied back."""
+        import torch
+
+        n, Bh = int(enc_window.shape[0]), int(dec_out.shape[0])
+        if out is None:
+            lab = torch.zeros((Bh, K), dtype=torch.int32, device=enc_window.device)
+            jmp = torch.zeros((Bh, K), dtype=torch.int32, device=enc_window.device)
+            sc = torch.zeros((Bh, K), dtype=torch.float32, device=enc_window.device)
+        else:
+            lab, jmp, sc = out
+        _check(self._lib.wind_beam_window_scores(self._h, enc_window.data_ptr(), n, dec_out.data_ptr(), Bh, int(K),
+                                                 lab.data_ptr(), jmp.data_ptr(), sc.data_ptr(), _stream_ptr()))
+        if out is not None:
+            return None
+        return lab.cpu().numpy(), jmp.cpu().numpy(), sc.cpu().numpy()
 
     def debug_joint_logits(self, enc_out, b: int, t0: int, n: int, prefix: Sequence[int], exact: bool):
         import torch

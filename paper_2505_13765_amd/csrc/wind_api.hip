@@ -13,6 +13,8 @@
 #include <vector>
 
 #include "wind_kernels.h"
+#include "wind_beam.h"
+#include "wind_beam.h"
 
 using namespace wind;
 
@@ -100,6 +102,8 @@ struct wind_model {
   long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
   LoopDev loop{};
+  void *beam_ws = nullptr;   // workspace of wind_beam_window_scores
+  size_t beam_ws_bytes = 0;
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
@@ -665,6 +669,7 @@ int wind_free(wind_model *m) {
   if (m->cap_stream) (void)hipStreamDestroy(m->cap_stream);
   for (void *p : m->allocs) (void)hipFree(p);
   if (m->ws) (void)hipFree(m->ws);
+  if (m->beam_ws) (void)hipFree(m->beam_ws);
   if (m->h_flag) (void)hipHostFree(m->h_flag);
   for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
   delete m;
@@ -681,6 +686,53 @@ int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *l
                            int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
                            int32_t *out_counts, int cap, void *stream) {
   return decode(m, enc_out, lengths, B, T, 1, max_symbols_per_step, out_tokens, out_frames, out_counts, cap, stream);
+}
+
+int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
+                            int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream) {
+  if (!m || !enc_window || !dec_out || !out_labels || !out_jumps || !out_scores) return fail(WIND_ERR_ARG, "null argument");
+  if (n < 1 || n > kBeamMaxWindow) return fail(WIND_ERR_ARG, "window must have 1..64 frames");
+  if (K < 1 || K > kBeamMaxK) return fail(WIND_ERR_ARG, "K must be in 1..32");
+  if (Bh < 1 || (long long)Bh * n > 65536) return fail(WIND_ERR_ARG, "Bh >= 1 and Bh * n <= 65536 required");
+  const ModelDev &d = m->dev;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t rows = (size_t)Bh * n, rows_pad = round_up(rows, JointCfg::BM), V1 = (size_t)d.V + 1;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
+  const size_t o_e = take((size_t)n * d.Hj * 4), o_p = take((size_t)Bh * d.Hj * 4);
+  const size_t o_z = take(rows_pad * d.Hj * 2), o_lg = take(rows * V1 * 4);
+  if (off > m->beam_ws_bytes) {
+    HIP_TRY(hipDeviceSynchronize());
+    if (m->beam_ws) HIP_TRY(hipFree(m->beam_ws));
+    m->beam_ws = nullptr;
+    m->beam_ws_bytes = 0;
+    HIP_TRY(hipMalloc(&m->beam_ws, off));
+    m->beam_ws_bytes = off;
+    HIP_TRY(hipMemset(m->beam_ws, 0, off));   // the MFMA pass reads whole row tiles
+  }
+  char *base = (char *)m->beam_ws;
+  float *e = (float *)(base + o_e), *p = (float *)(base + o_p), *logits = (float *)(base + o_lg);
+  bf16_t *z = (bf16_t *)(base + o_z);
+  constexpr int kR = 8;                                 // rows that share one pass over a weight row
+  const unsigned jb = (unsigned)((d.Hj + 3) / 4);
+  if (m->dtype == WIND_BF16) {
+    beam_linear_kernel<bf16_t, true, kR><<<dim3(jb, (unsigned)((n + kR - 1) / kR)), 256, 0, s>>>((const bf16_t *)d.w_enc, d.b_enc, enc_window, e, n, d.Hj, d.D);
+    beam_linear_kernel<bf16_t, false, kR><<<dim3(jb, (unsigned)((Bh + kR - 1) / kR)), 256, 0, s>>>((const bf16_t *)d.w_pred, d.b_pred, dec_out, p, Bh, d.Hj, d.Hp);
+    beam_hidden_kernel<<<(unsigned)rows, 256, 0, s>>>(e, p, z, n, d.Hj);
+    dim3 grid((unsigned)(rows_pad / JointCfg::BM), (unsigned)((V1 + JointCfg::BN - 1) / JointCfg::BN));
+    joint_mfma_store_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, z, (int)rows, logits);
+  } else {
+    beam_linear_kernel<float, false, kR><<<dim3(jb, (unsigned)((n + kR - 1) / kR)), 256, 0, s>>>((const float *)d.w_enc, d.b_enc, enc_window, e, n, d.Hj, d.D);
+    beam_linear_kernel<float, false, kR><<<dim3(jb, (unsigned)((Bh + kR - 1) / kR)), 256, 0, s>>>((const float *)d.w_pred, d.b_pred, dec_out, p, Bh, d.Hj, d.Hp);
+    beam_logits_f32_kernel<<<(unsigned)rows, 256, (size_t)d.Hj * 4, s>>>(d, e, p, n, logits);
+  }
+  if (K <= 8) beam_score_kernel<8><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
+  else if (K <= 16) beam_score_kernel<16><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
+  else beam_score_kernel<32><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
+  int rc = check_launch("beam window scores");
+  if (rc) return rc;
+  HIP_TRY(hipStreamSynchronize(s));
+  return WIND_OK;
 }
 
 int wind_get_stats(wind_model *m, wind_stats *out) {

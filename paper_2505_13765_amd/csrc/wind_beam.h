@@ -1,0 +1,225 @@
+// Scoring step of WIND beam search (section "A Novel Beam-search Algorithm for WIND": Eq. 1 and
+// lines 10-13 of Algorithm 3) for Bh hypotheses that sit on the same frame:
+//   logits[b, t, :] = joiner(enc_window[t], dec_out[b])            t < n
+//   log P'(v, t)    = log softmax(logits[b, t])[v] + sum_{t' < t} log softmax(logits[b, t'])[blank]
+//   log P'(blank, n-1) = sum_{t' < n} log softmax(logits[b, t'])[blank];   P'(blank, t < n-1) = 0
+//   the K best (label, jump) pairs of every hypothesis under P'
+// Order among equal scores: earlier frame, then lower label.  The logits take the same route as in
+// the greedy path (bf16 models: hidden vector rounded to bf16, bf16 MFMA, fp32 accumulation; fp32
+// models: fp32 FMA); everything after them is fp32.
+#pragma once
+#include "wind_kernels.h"
+
+namespace wind {
+
+constexpr int kBeamMaxK = 32;
+constexpr int kBeamMaxWindow = 64;
+
+// out[r, j] = bias[j] + sum_k w[j, k] * x[r, k]: one wave per output j and group of R rows, so that a
+// weight row is read once per group.  ROUND_X rounds x to bf16 first (what the encoder projection
+// of a bf16 model does with its input).  grid = (ceil(n_out / 4), ceil(rows / R)).
+template <class WT, bool ROUND_X, int R>
+__global__ __launch_bounds__(256) void beam_linear_kernel(const WT *w, const float *bias, const float *x, float *out,
+                                                          int rows, int n_out, int K) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 4 + wave, r0 = blockIdx.y * R;
+  if (j >= n_out) return;
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  for (int k = lane; k < K; k += 64) {
+    const float wv = ldw(w, (size_t)j * K + k);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float xv = x[(size_t)min(r0 + r, rows - 1) * K + k];
+      if (ROUND_X) xv = bf16_bits_to_f32(f32_to_bf16_bits(xv));
+      acc[r] = fmaf(wv, xv, acc[r]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const float tot = wave_sum(acc[r]);
+    if (lane == 0 && r0 + r < rows) out[(size_t)(r0 + r) * n_out + j] = tot + bias[j];
+  }
+}
+
+// Row (b, t) of the joiner's hidden layer, relu(e[t] + p[b]), as bf16 for the MFMA pass.
+__global__ __launch_bounds__(256) void beam_hidden_kernel(const float *e, const float *p, bf16_t *z, int n, int Hj) {
+  const int row = blockIdx.x, b = row / n, t = row - b * n;
+  for (int k = threadIdx.x; k < Hj; k += 256)
+    z[(size_t)row * Hj + k] = (bf16_t)f32_to_bf16_bits(fmaxf(e[(size_t)t * Hj + k] + p[(size_t)b * Hj + k], 0.f));
+}
+
+// fp32 models: logits of row (b, t) by fp32 FMA, one workgroup per row.
+__global__ __launch_bounds__(256) void beam_logits_f32_kernel(ModelDev m, const float *e, const float *p, int n,
+                                                              float *logits) {
+  extern __shared__ float zs[];
+  const int row = blockIdx.x, b = row / n, t = row - b * n;
+  for (int k = threadIdx.x; k < m.Hj; k += 256) zs[k] = fmaxf(e[(size_t)t * m.Hj + k] + p[(size_t)b * m.Hj + k], 0.f);
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float *w = reinterpret_cast<const float *>(m.w_out);
+  for (int v = wave; v <= m.V; v += 4) {
+    float a = 0.f;
+    for (int k = lane; k < m.Hj; k += 64) a = fmaf(w[(size_t)v * m.Hj + k], zs[k], a);
+    a = wave_sum(a);
+    if (lane == 0) logits[(size_t)row * (m.V + 1) + v] = a + m.b_out[v];
+  }
+}
+
+// (score, frame, label) ordering of Algorithm 3's top-K: a comes before b
+__device__ __forceinline__ bool beam_before(float sa, int ka, float sb, int kb) {
+  return sa > sb || (sa == sb && ka < kb);   // k = frame * (V+1) + label: earlier frame, then lower label
+}
+
+// The same ordering on a pair of unsigned words that compare like integers: hi = the score's bits
+// mapped so that larger floats give larger integers, lo = ~key (smaller key = larger word).
+__device__ __forceinline__ unsigned beam_order_bits(float s) {
+  const unsigned u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float beam_score_of(unsigned hi) {
+  return __uint_as_float((hi & 0x80000000u) ? (hi & 0x7FFFFFFFu) : ~hi);
+}
+// Largest (hi, lo) pair of the wave, in every lane.  DPP row permutations inside the rows of 16, then
+// the four row winners by v_readlane: no trip through the LDS crossbar.
+__device__ __forceinline__ void wave_max_pair(unsigned &hi, unsigned &lo) {
+  auto take = [&](unsigned oh, unsigned ol) {
+    const bool better = oh > hi || (oh == hi && ol > lo);
+    hi = better ? oh : hi;
+    lo = better ? ol : lo;
+  };
+  take((unsigned)dpp_i32<kDppRowMirror>((int)hi), (unsigned)dpp_i32<kDppRowMirror>((int)lo));
+  take((unsigned)dpp_i32<kDppRowHalfMirror>((int)hi), (unsigned)dpp_i32<kDppRowHalfMirror>((int)lo));
+  take((unsigned)dpp_i32<kDppQuadXor2>((int)hi), (unsigned)dpp_i32<kDppQuadXor2>((int)lo));
+  take((unsigned)dpp_i32<kDppQuadXor1>((int)hi), (unsigned)dpp_i32<kDppQuadXor1>((int)lo));
+  unsigned bh = (unsigned)__builtin_amdgcn_readlane((int)hi, 0), bl = (unsigned)__builtin_amdgcn_readlane((int)lo, 0);
+#pragma unroll
+  for (int row = 16; row < 64; row += 16) {
+    const unsigned oh = (unsigned)__builtin_amdgcn_readlane((int)hi, row), ol = (unsigned)__builtin_amdgcn_readlane((int)lo, row);
+    const bool better = oh > bh || (oh == bh && ol > bl);
+    bh = better ? oh : bh;
+    bl = better ? ol : bl;
+  }
+  hi = bh;
+  lo = bl;
+}
+
+// One workgroup per hypothesis.  Pass 1: log-sum-exp of every row, blank log-probabilities and their
+// running sum.  Pass 2: every thread keeps the K best of the entries it visits, sorted, in
+// registers (KMAX slots).  Then every wave merges its 64 lists by K rounds of "best head", and wave
+// 0 merges the four results.
+template <int KMAX>
+__global__ __launch_bounds__(256) void beam_score_kernel(const float *logits, int n, int V, int K, int *out_labels,
+                                                         int *out_jumps, float *out_scores) {
+  __shared__ float s_lse[kBeamMaxWindow], s_blank[kBeamMaxWindow], s_run[kBeamMaxWindow + 1];
+  __shared__ unsigned s_hi[4][KMAX], s_lo[4][KMAX];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, V1 = V + 1;
+  const float *lg = logits + (size_t)blockIdx.x * n * V1;
+  // ---- pass 1: a wave takes rows wave, wave + 4, ...; one sweep per row with a running maximum and a
+  // running sum of exponentials.  Loads go out 32 at a time: these rows come from the memory side,
+  // and one dependent round trip per element would cost far more than the arithmetic.
+  for (int t = wave; t < n; t += 4) {
+    const float *row = lg + (size_t)t * V1;
+    float mx = -INFINITY, sum = 0.f;
+    for (int v0 = lane; v0 < V1; v0 += 64 * 32) {
+      float x[32];
+#pragma unroll
+      for (int i = 0; i < 32; ++i) x[i] = v0 + 64 * i < V1 ? row[v0 + 64 * i] : -INFINITY;
+      float cm = x[0];
+#pragma unroll
+      for (int i = 1; i < 32; ++i) cm = fmaxf(cm, x[i]);
+      const float nm = fmaxf(mx, cm);
+      float cs = 0.f;
+      if (nm > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) cs += expf(x[i] - nm);
+        sum = sum * expf(mx - nm) + cs;
+        mx = nm;
+      }
+    }
+    const float wm = wave_max_f32(mx);
+    sum = wave_sum(mx > -INFINITY ? sum * expf(mx - wm) : 0.f);
+    if (lane == 0) {
+      const float lse = wm + logf(sum);
+      s_lse[t] = lse;
+      s_blank[t] = row[V] - lse;   // log P(blank | t)
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float run = 0.f;
+    for (int t = 0; t < n; ++t) {
+      s_run[t] = run;                                   // blanks on every frame before t
+      run += s_blank[t];
+    }
+    s_run[n] = run;                                     // blanks on every frame of the window
+  }
+  __syncthreads();
+  // ---- pass 2: thread-local K best as ordered (hi, lo) words, best first; slots >= K stay empty
+  unsigned lh[KMAX], ll[KMAX];
+#pragma unroll
+  for (int i = 0; i < KMAX; ++i) { lh[i] = 0u; ll[i] = 0u; }
+  unsigned thr_h = 0u, thr_l = 0u;   // the K-th slot: what an entry has to beat to get in
+  auto offer = [&](float s, int key) {
+    unsigned h = beam_order_bits(s), l = ~(unsigned)key;
+    if (!(h > thr_h || (h == thr_h && l > thr_l))) return;
+    // one pass of compare-and-swap down the list: the new entry sinks to its place, the last one drops out
+#pragma unroll
+    for (int i = 0; i < KMAX; ++i) {
+      const bool better = i < K && (h > lh[i] || (h == lh[i] && l > ll[i]));
+      const unsigned th = lh[i], tl = ll[i];
+      lh[i] = better ? h : th; ll[i] = better ? l : tl;
+      h = better ? th : h; l = better ? tl : l;
+      if (i == K - 1) { thr_h = lh[i]; thr_l = ll[i]; }
+    }
+  };
+  for (int t = 0; t < n; ++t) {
+    const float *row = lg + (size_t)t * V1;
+    const float add = s_run[t] - s_lse[t];
+    for (int v0 = tid; v0 < V; v0 += 256 * 32) {
+      float x[32];
+#pragma unroll
+      for (int i = 0; i < 32; ++i) x[i] = v0 + 256 * i < V ? row[v0 + 256 * i] : -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 32; ++i)
+        if (v0 + 256 * i < V) offer(x[i] + add, t * V1 + v0 + 256 * i);
+    }
+  }
+  if (tid == 0) offer(s_run[n], (n - 1) * V1 + V);        // blank: only as "jump out of the window"
+  // ---- merge, level 1: K rounds over the heads of the wave's 64 lists; lane r keeps the r-th winner
+  unsigned win_h = 0u, win_l = 0u;
+  for (int r = 0; r < K; ++r) {
+    unsigned h = lh[0], l = ll[0];
+    const unsigned myh = h, myl = l;
+    wave_max_pair(h, l);
+    if (myh == h && myl == l && h != 0u) {   // this lane's head won: pop it
+#pragma unroll
+      for (int i = 0; i + 1 < KMAX; ++i) { lh[i] = lh[i + 1]; ll[i] = ll[i + 1]; }
+      lh[KMAX - 1] = 0u; ll[KMAX - 1] = 0u;
+    }
+    if (lane == r) { win_h = h; win_l = l; }
+  }
+  if (lane < K) { s_hi[wave][lane] = win_h; s_lo[wave][lane] = win_l; }
+  __syncthreads();
+  // ---- level 2: wave 0 merges the four sorted lists of K (lanes 0..3 hold the heads)
+  if (wave == 0) {
+    int h2 = 0;
+    for (int r = 0; r < K; ++r) {
+      unsigned h = (lane < 4 && h2 < K) ? s_hi[lane][h2] : 0u, l = (lane < 4 && h2 < K) ? s_lo[lane][h2] : 0u;
+      const unsigned myh = h, myl = l;
+      wave_max_pair(h, l);
+      if (lane < 4 && myh == h && myl == l && h != 0u) ++h2;
+      if (lane == 0) {
+        const size_t o = (size_t)blockIdx.x * K + r;
+        const bool any = h != 0u;
+        const int key = (int)~l;
+        out_labels[o] = any ? key % V1 : -1;
+        out_jumps[o] = any ? key / V1 : -1;
+        out_scores[o] = any ? beam_score_of(h) : -INFINITY;
+      }
+    }
+  }
+}
+
+}  // namespace wind
