@@ -701,6 +701,7 @@ int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
   const size_t o_e = take((size_t)n * d.Hj * 4), o_p = take((size_t)Bh * d.Hj * 4);
   const size_t o_z = take(rows_pad * d.Hj * 2), o_lg = take(rows * V1 * 4);
+  const size_t o_lse = take(rows * 4), o_blp = take(rows * 4), o_cl = take(rows * kBeamMaxK * 4), o_cv = take(rows * kBeamMaxK * 4);
   if (off > m->beam_ws_bytes) {
     HIP_TRY(hipDeviceSynchronize());
     if (m->beam_ws) HIP_TRY(hipFree(m->beam_ws));
@@ -726,9 +727,20 @@ int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const
     beam_linear_kernel<float, false, kR><<<dim3(jb, (unsigned)((Bh + kR - 1) / kR)), 256, 0, s>>>((const float *)d.w_pred, d.b_pred, dec_out, p, Bh, d.Hj, d.Hp);
     beam_logits_f32_kernel<<<(unsigned)rows, 256, (size_t)d.Hj * 4, s>>>(d, e, p, n, logits);
   }
-  if (K <= 8) beam_score_kernel<8><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
-  else if (K <= 16) beam_score_kernel<16><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
-  else beam_score_kernel<32><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
+  if (V1 <= 256 * 36) {
+    // one workgroup per row, then one wave per hypothesis
+    float *lse = (float *)(base + o_lse), *blp = (float *)(base + o_blp), *cl = (float *)(base + o_cl);
+    int *cv = (int *)(base + o_cv);
+    if (V1 <= 256 * 8) beam_row_kernel<8><<<(unsigned)rows, 256, 0, s>>>(logits, d.V, K, lse, blp, cl, cv);
+    else beam_row_kernel<36><<<(unsigned)rows, 256, 0, s>>>(logits, d.V, K, lse, blp, cl, cv);
+    beam_merge_kernel<<<(unsigned)Bh, 64, 0, s>>>(lse, blp, cl, cv, n, d.V, K, out_labels, out_jumps, out_scores);
+  } else if (K <= 8) {
+    beam_score_kernel<8><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
+  } else if (K <= 16) {
+    beam_score_kernel<16><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
+  } else {
+    beam_score_kernel<32><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
+  }
   int rc = check_launch("beam window scores");
   if (rc) return rc;
   HIP_TRY(hipStreamSynchronize(s));

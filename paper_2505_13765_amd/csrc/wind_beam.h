@@ -81,28 +81,31 @@ __device__ __forceinline__ unsigned beam_order_bits(float s) {
 __device__ __forceinline__ float beam_score_of(unsigned hi) {
   return __uint_as_float((hi & 0x80000000u) ? (hi & 0x7FFFFFFFu) : ~hi);
 }
-// Largest (hi, lo) pair of the wave, in every lane.  DPP row permutations inside the rows of 16, then
-// the four row winners by v_readlane: no trip through the LDS crossbar.
+// Largest (hi, lo) pair of the wave, in every lane.  The pair is compared as one 64-bit integer.  DPP
+// row permutations inside the rows of 16, then the four row winners by v_readlane: no trip through
+// the LDS crossbar.
 __device__ __forceinline__ void wave_max_pair(unsigned &hi, unsigned &lo) {
-  auto take = [&](unsigned oh, unsigned ol) {
-    const bool better = oh > hi || (oh == hi && ol > lo);
-    hi = better ? oh : hi;
-    lo = better ? ol : lo;
-  };
-  take((unsigned)dpp_i32<kDppRowMirror>((int)hi), (unsigned)dpp_i32<kDppRowMirror>((int)lo));
-  take((unsigned)dpp_i32<kDppRowHalfMirror>((int)hi), (unsigned)dpp_i32<kDppRowHalfMirror>((int)lo));
-  take((unsigned)dpp_i32<kDppQuadXor2>((int)hi), (unsigned)dpp_i32<kDppQuadXor2>((int)lo));
-  take((unsigned)dpp_i32<kDppQuadXor1>((int)hi), (unsigned)dpp_i32<kDppQuadXor1>((int)lo));
-  unsigned bh = (unsigned)__builtin_amdgcn_readlane((int)hi, 0), bl = (unsigned)__builtin_amdgcn_readlane((int)lo, 0);
-#pragma unroll
-  for (int row = 16; row < 64; row += 16) {
-    const unsigned oh = (unsigned)__builtin_amdgcn_readlane((int)hi, row), ol = (unsigned)__builtin_amdgcn_readlane((int)lo, row);
-    const bool better = oh > bh || (oh == bh && ol > bl);
-    bh = better ? oh : bh;
-    bl = better ? ol : bl;
+  unsigned long long v = ((unsigned long long)hi << 32) | lo;
+#define WIND_PAIR_STEP(CTRL)                                                                                   \
+  {                                                                                                             \
+    const unsigned oh = (unsigned)dpp_i32<CTRL>((int)(v >> 32)), ol = (unsigned)dpp_i32<CTRL>((int)(unsigned)v); \
+    const unsigned long long o = ((unsigned long long)oh << 32) | ol;                                           \
+    v = o > v ? o : v;                                                                                          \
   }
-  hi = bh;
-  lo = bl;
+  WIND_PAIR_STEP(kDppRowMirror)
+  WIND_PAIR_STEP(kDppRowHalfMirror)
+  WIND_PAIR_STEP(kDppQuadXor2)
+  WIND_PAIR_STEP(kDppQuadXor1)
+#undef WIND_PAIR_STEP
+#pragma unroll
+  for (int row = 0; row < 64; row += 16) {
+    const unsigned oh = (unsigned)__builtin_amdgcn_readlane((int)(v >> 32), row);
+    const unsigned ol = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, row);
+    const unsigned long long o = ((unsigned long long)oh << 32) | ol;
+    v = o > v ? o : v;
+  }
+  hi = (unsigned)(v >> 32);
+  lo = (unsigned)v;
 }
 
 // One workgroup per hypothesis.  Pass 1: log-sum-exp of every row, blank log-probabilities and their
@@ -219,6 +222,140 @@ __global__ __launch_bounds__(256) void beam_score_kernel(const float *logits, in
         out_scores[o] = any ? beam_score_of(h) : -INFINITY;
       }
     }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same scoring step in two short kernels for vocabularies of at most 256 * 36 entries, where a
+// row fits the registers of one workgroup: every row is read in one round trip.
+//
+// Kernel 1, one workgroup per row (b, t): log-sum-exp of the row, log P(blank | t), and the row's K
+// largest label logits with their labels (ties: lower label first).  Adding the row's constant
+// (blank prefix sum minus log-sum-exp) keeps their order, so these are the only entries of the row
+// that can be among the hypothesis' K best.
+template <int EPT>
+__global__ __launch_bounds__(256) void beam_row_kernel(const float *logits, int V, int K, float *lse_out,
+                                                       float *blank_lp, float *cand_logit, int *cand_label) {
+  __shared__ float s_f[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, V1 = V + 1;
+  const float *row = logits + (size_t)blockIdx.x * V1;
+  float x[EPT];
+#pragma unroll
+  for (int i = 0; i < EPT; ++i) x[i] = tid + 256 * i < V1 ? row[tid + 256 * i] : -INFINITY;
+  float mx = x[0];
+#pragma unroll
+  for (int i = 1; i < EPT; ++i) mx = fmaxf(mx, x[i]);
+  mx = wave_max_f32(mx);
+  if (lane == 0) s_f[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
+  __syncthreads();
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < EPT; ++i) sum += expf(x[i] - mx);
+  sum = wave_sum(sum);
+  if (lane == 0) s_f[wave] = sum;
+  __syncthreads();
+  const float lse = mx + logf((s_f[0] + s_f[1]) + (s_f[2] + s_f[3]));
+  if (tid == 0) {
+    lse_out[blockIdx.x] = lse;
+    blank_lp[blockIdx.x] = row[V] - lse;
+  }
+  // The row's K largest label logits.  Level 1: every wave takes K rounds of "largest remaining entry of
+  // my 64 lanes" (no workgroup barrier); level 2: wave 0 merges the four sorted lists.
+  __shared__ unsigned s_wh[4][kBeamMaxK], s_wl[4][kBeamMaxK];
+  unsigned hi[EPT];
+#pragma unroll
+  for (int i = 0; i < EPT; ++i) hi[i] = tid + 256 * i < V ? beam_order_bits(x[i]) : 0u;   // blank and padding never compete
+  for (int r = 0; r < K; ++r) {
+    unsigned bh = 0u, bl = 0u;
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+      const unsigned l = ~(unsigned)(tid + 256 * i);
+      const bool better = hi[i] > bh || (hi[i] == bh && hi[i] != 0u && l > bl);
+      bh = better ? hi[i] : bh;
+      bl = better ? l : bl;
+    }
+    unsigned wh = bh, wl = bl;
+    wave_max_pair(wh, wl);
+    const int v = (int)~wl;
+    if (wh != 0u && (v & 255) == tid) {   // the winner's owner retires it
+#pragma unroll
+      for (int i = 0; i < EPT; ++i)
+        if (i == (v >> 8)) hi[i] = 0u;
+    }
+    if (lane == 0) { s_wh[wave][r] = wh; s_wl[wave][r] = wl; }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int h2 = 0;   // lanes 0..3: head of wave `lane`'s list
+    unsigned res_h = 0u, res_l = 0u;   // lane r keeps the r-th winner; stored after the rounds
+    for (int r = 0; r < K; ++r) {
+      unsigned h = (lane < 4 && h2 < K) ? s_wh[lane][h2] : 0u, l = (lane < 4 && h2 < K) ? s_wl[lane][h2] : 0u;
+      const unsigned myh = h, myl = l;
+      wave_max_pair(h, l);
+      if (lane < 4 && myh == h && myl == l && h != 0u) ++h2;
+      if (lane == r) { res_h = h; res_l = l; }
+    }
+    if (lane < K) {
+      cand_logit[(size_t)blockIdx.x * K + lane] = res_h != 0u ? beam_score_of(res_h) : -INFINITY;
+      cand_label[(size_t)blockIdx.x * K + lane] = res_h != 0u ? (int)~res_l : -1;
+    }
+  }
+}
+
+// Kernel 2, one wave per hypothesis: running sum of the blank log-probabilities, then K rounds over
+// the heads of the rows' candidate lists (lane t holds row t; the lists are sorted, and so are
+// their scores) with the all-blank entry competing as one more candidate.
+__global__ __launch_bounds__(64) void beam_merge_kernel(const float *lse, const float *blank_lp, const float *cand_logit,
+                                                        const int *cand_label, int n, int V, int K, int *out_labels,
+                                                        int *out_jumps, float *out_scores) {
+  __shared__ float s_cl[kBeamMaxWindow * kBeamMaxK];
+  __shared__ int s_cv[kBeamMaxWindow * kBeamMaxK];
+  const int lane = threadIdx.x, b = blockIdx.x, V1 = V + 1;
+  const bool has_row = lane < n;
+  // the hypothesis' candidates in one round trip: the rounds below walk them with dependent reads
+  for (int i = lane; i < n * K; i += 64) {
+    s_cl[i] = cand_logit[(size_t)b * n * K + i];
+    s_cv[i] = cand_label[(size_t)b * n * K + i];
+  }
+  __syncthreads();
+  const float my_blank = has_row ? blank_lp[(size_t)b * n + lane] : 0.f;
+  // exclusive prefix sum over the rows, in row order (fp32, the order the definition adds them in)
+  float run = 0.f, total = 0.f;
+  for (int t = 0; t < n; ++t) {
+    const float v = readlane_f32(my_blank, t);
+    if (lane == t) run = total;
+    total += v;
+  }
+  const float add = has_row ? run - lse[(size_t)b * n + lane] : 0.f;
+  const float *cl = s_cl + (has_row ? lane : 0) * K;
+  const int *cv = s_cv + (has_row ? lane : 0) * K;
+  unsigned blank_h = beam_order_bits(total), blank_l = ~(unsigned)((n - 1) * V1 + V);
+  int head = 0;
+  float cur = has_row ? cl[0] : -INFINITY;
+  int curv = has_row ? cv[0] : -1;
+  unsigned res_h = 0u, res_l = 0u;   // lane r keeps the r-th winner; label and jump are worked out after the rounds
+  for (int r = 0; r < K; ++r) {
+    unsigned h = 0u, l = 0u;
+    if (has_row && head < K && curv >= 0) { h = beam_order_bits(cur + add); l = ~(unsigned)(lane * V1 + curv); }
+    const unsigned myh = h, myl = l;
+    wave_max_pair(h, l);
+    const bool blank_wins = blank_h != 0u && (blank_h > h || (blank_h == h && blank_l > l));
+    if (blank_wins) { h = blank_h; l = blank_l; blank_h = 0u; }
+    else if (myh == h && myl == l && h != 0u) {   // this row's head won: move on to its next candidate
+      ++head;
+      cur = head < K ? cl[head] : -INFINITY;
+      curv = head < K ? cv[head] : -1;
+    }
+    if (lane == r) { res_h = h; res_l = l; }
+  }
+  if (lane < K) {
+    const size_t o = (size_t)b * K + lane;
+    const int key = (int)~res_l;
+    out_labels[o] = res_h != 0u ? key % V1 : -1;
+    out_jumps[o] = res_h != 0u ? key / V1 : -1;
+    out_scores[o] = res_h != 0u ? beam_score_of(res_h) : -INFINITY;
   }
 }
 
