@@ -41,6 +41,7 @@ constexpr int kTinyRowsDefault = 64;                    // at most this many win
 using EncCfg = TileCfg<128, 128, 64, 64>;
 using PredCfg = DmaCfg<64, 64, 32, 32, 64, 4>;   // 32 utterances (hi and lo rows) x 64 columns, 4-stage ring
 constexpr int kPredMfmaMinBatch = 16;      // below this the FMA prediction network is used
+constexpr size_t kEncRing5MinRows = 16384;   // B * T from which the encoder projection uses 256 x 256 tiles
 constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height, plus one block
 
 // Row tiles of joint_rows_kernel for a vocabulary of NT 128-column tiles and at most `rows` window
@@ -165,6 +166,8 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
     return o;
   };
   const size_t o_e = take((size_t)B * T * d.Hj * 4);
+  const bool big_enc = m->dtype == WIND_BF16 && (size_t)B * T >= kEncRing5MinRows;
+  const size_t o_encb = take(big_enc ? ((size_t)B * T + JointBigCfg::BM) * d.D * 2 : 0);
   const int slot_stride = B > kTinyRows ? B : kTinyRows;
   const size_t o_len = take((size_t)B * 4);
   const size_t o_nact = take(8), o_eidx = take((size_t)B * 4);
@@ -199,6 +202,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   char *base = (char *)m->ws;
   CallDev &c = m->call;
   c.e = (float *)(base + o_e);
+  c.enc_b = big_enc ? (bf16_t *)(base + o_encb) : nullptr;
   c.len = (int *)(base + o_len);
   c.n_active = (int *)(base + o_nact);
   c.slot_stride = slot_stride;
@@ -309,7 +313,14 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
   const CallDev &c = m->call;
   init_state_kernel<<<1, 256, 0, s>>>(d, c);
   if (c.T > 0) {
-    if (m->dtype == WIND_BF16) {
+    if (m->dtype == WIND_BF16 && c.enc_b) {
+      const long long rows = (long long)c.B * c.T;
+      launch(m, s, WIND_K_ENC_PROJ, false, enc_round_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, d, c);
+      const int tiles_per_utt = (c.T + JointBigCfg::BM - 1) / JointBigCfg::BM;
+      dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + JointBigCfg::BN - 1) / JointBigCfg::BN));
+      launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_ring5_kernel<JointBigCfg>, grid, dim3(JointBigCfg::NT),
+             JointBigCfg::SMEM_BYTES, d, c, tiles_per_utt);
+    } else if (m->dtype == WIND_BF16) {
       const int tiles_per_utt = (c.T + EncCfg::BM - 1) / EncCfg::BM;
       dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncCfg::BN - 1) / EncCfg::BN));
       launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_mfma_kernel<EncCfg>, grid, dim3(EncCfg::NT), EncCfg::SMEM_BYTES, d, c,
@@ -640,6 +651,9 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)enc_proj_ring5_kernel<JointBigCfg>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)enc_proj_mfma_kernel<EncCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, EncCfg::SMEM_BYTES);

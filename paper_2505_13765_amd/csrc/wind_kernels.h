@@ -61,6 +61,7 @@ struct CallDev {
   const int *lengths;           // [B] as given
   int *out_tokens, *out_frames, *out_counts;
   float *e;                     // [B*T, Hj]
+  bf16_t *enc_b;                // [B*T + 256, D] encoder outputs rounded to bf16 (large calls only, else null)
   int *len;                     // [B] clamped to [0,T]
   // Active utterances live in a slot table, ping-pong by iteration parity: slot a of the current
   // parity holds everything an iteration needs to know about its a-th active utterance, so that a
@@ -158,6 +159,57 @@ __global__ __launch_bounds__(Cfg::NT) void enc_proj_mfma_kernel(ModelDev m, Call
   };
   f32x16 acc[Cfg::MI][Cfg::NI];
   gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_enc) + (size_t)n0 * D, D, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int col = n0 + wn * Cfg::WN + ni * 32 + (lane & 31);
+    if (col >= m.Hj) continue;
+    const float bias = m.b_enc[col];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = t0 + wm * Cfg::WM + acc_row(mi, r, lane);
+        if (t < len) c.e[((size_t)b * c.T + t) * m.Hj + col] = acc[mi][ni][r] + bias;
+      }
+  }
+}
+
+// Large calls: the encoder outputs are first rounded to bf16 rows (valid frames only), so that the
+// projection can use the direct-to-LDS tile core at full tile size.
+__global__ __launch_bounds__(256) void enc_round_kernel(ModelDev m, CallDev c) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long row = (long long)blockIdx.x * 4 + wave;
+  if (row >= (long long)c.B * c.T) return;
+  const int b = (int)(row / c.T), t = (int)(row - (long long)b * c.T);
+  if (t >= c.len[b]) return;
+  const float *src = c.enc + (size_t)row * m.D;
+  bf16_t *dst = c.enc_b + (size_t)row * m.D;
+  for (int k = lane * 4; k < m.D; k += 256) {
+    const float4 x = *reinterpret_cast<const float4 *>(src + k);
+    *reinterpret_cast<uint2 *>(dst + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+  }
+}
+
+// e = W_enc enc + b_enc on 256 x 256 tiles of the five-slot ring: a row tile is 256 consecutive
+// frames of one utterance (rows past its length are computed and dropped).
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void enc_proj_ring5_kernel(ModelDev m, CallDev c, int tiles_per_utt) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int b = blockIdx.x / tiles_per_utt, t0 = (blockIdx.x % tiles_per_utt) * Cfg::BM;
+  const int len = c.len[b];
+  if (t0 >= len) return;
+  const int n0 = blockIdx.y * Cfg::BN, D = m.D;
+  f32x16 acc[Cfg::MI][Cfg::NI];
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+  gemm_mainloop_ring5<Cfg>(c.enc_b + ((size_t)b * c.T + t0) * D, reinterpret_cast<const bf16_t *>(m.w_enc) + (size_t)n0 * D, D,
+                           smem_raw, acc);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 #pragma unroll
