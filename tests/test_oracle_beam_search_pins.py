@@ -1,0 +1,249 @@
+"""Pins for the whole-search oracle (oracle/beam_search.py; section "A Novel Beam-search Algorithm
+for WIND", Algorithm 3) against things other than the oracle's own loop:
+
+  * every alignment of a tiny lattice enumerated by brute force (an unpruned search without the
+    prefix step must hold, for every label sequence, exactly the summed probability of its
+    alignments: checks Eq. 1's use, the map's time bookkeeping, recombination and the safeguard);
+  * beam 1 with window 1 is the sequential greedy decoder, and its score is the log-probability of
+    the greedy path evaluated with a library softmax;
+  * beam 1 with any window: the score is the log-probability of the single alignment that the
+    returned labels and time stamps spell out, walked frame by frame;
+  * the prefix step on hand-built hypothesis sets with completion probabilities computed directly,
+    including a chain of three where mass must not be counted twice;
+  * what the literal removal of prefixes does to the search, measured;
+  * invariants of the output.
+"""
+import itertools
+
+import numpy as np
+import pytest
+from scipy.special import log_softmax as scipy_log_softmax, logsumexp
+
+import oracle
+import wind_inputs as wi
+from oracle import beam_search as obs
+
+
+def tiny_model(seed, V=2, D=4, E=3, Hp=5, Hj=6, L=1, blank_bias=0.0, gain=3.0):
+    cfg = wi.WindConfig(f"b{seed}", seed, 1, 6, 6, D, E, L, Hp, Hj, V, "f32", (2,), 4, 0.5)
+    return cfg, oracle.Oracle.from_config(cfg, wi.make_weights(cfg, blank_bias=blank_bias, pred_gain=gain))
+
+
+def make_enc(seed, T, D):
+    return np.random.default_rng([seed, 77]).standard_normal((T, D)).astype(np.float32)
+
+
+def mixed_model(seed, T, S, target=0.6, **kw):
+    """A tiny model whose blank bias is picked from a grid so that greedy decoding sees both blanks
+    and labels on the test utterance."""
+    best = None
+    for bias in np.arange(-2.0, 6.01, 0.25):
+        cfg, o = tiny_model(seed, blank_bias=float(bias), **kw)
+        _, _, log = o.greedy(make_enc(seed, T, cfg.D), S)
+        miss = abs(float((log["label"] == cfg.V).mean()) - target)
+        if best is None or miss < best[0]:
+            best = (miss, cfg, o)
+    assert best[0] < 0.3
+    return best[1], best[2]
+
+
+def frame_log_probs(o, frame, tokens):
+    """log P(. | frame, decoder(tokens)) with the decoder rebuilt from nothing and scipy's softmax."""
+    return scipy_log_softmax(o.joiner(frame, o.decoder_from_scratch(list(tokens))))
+
+
+def enumerate_alignments(o, enc, S, max_labels=None):
+    """Every way of walking the lattice under the label-per-frame bound: {tokens: log of the summed
+    probability}.  On a frame, after fewer than S labels, the model may emit any label (stay) or
+    blank (next frame); after the S-th label the walk moves on without asking the model.
+    max_labels leaves out the sequences longer than that."""
+    T, V = enc.shape[0], o.V
+    total = {}
+
+    def walk(t, sym, tokens, lp):
+        if t == T:
+            total.setdefault(tokens, []).append(lp)
+            return
+        dist = frame_log_probs(o, enc[t], tokens)
+        walk(t + 1, 0, tokens, lp + dist[V])
+        for v in range(V if max_labels is None or len(tokens) < max_labels else 0):
+            if sym + 1 >= S:
+                walk(t + 1, 0, tokens + (v,), lp + dist[v])
+            else:
+                walk(t, sym + 1, tokens + (v,), lp + dist[v])
+
+    walk(0, 0, (), 0.0)
+    return {k: float(logsumexp(v)) for k, v in total.items()}
+
+
+@pytest.mark.parametrize("seed,T,V,S,N", [(0, 3, 2, 2, 1), (1, 3, 2, 3, 2), (2, 3, 2, 3, 3), (3, 4, 2, 2, 3),
+                                          (4, 2, 3, 3, 2), (5, 4, 2, 2, 8), (6, 3, 2, 1, 2)])
+def test_unpruned_search_sums_every_alignment(seed, T, V, S, N):
+    # A sequence with fewer than S labels never meets the label-per-frame bound, so its mass does not
+    # depend on how duplicates with different label counts were combined: it must be the sum over
+    # all of its alignments, exactly.  (With window 1 duplicates never meet in one round and every
+    # sequence is exact.)  The masses of all sequences together are the whole sample space.
+    cfg, o = tiny_model(seed, V=V, L=1 + seed % 2)
+    enc = make_enc(seed, T, cfg.D)
+    want = enumerate_alignments(o, enc, S)
+    everything = N * (V + 1) + 1
+    best, final, _ = obs.wind_beam_search(o, enc, N, K=10 ** 6, S=S, prefix_step="off", expansions_per_hyp=everything)
+    got = {h.tokens: h.score for h in final}
+    assert set(got) <= set(want)
+    exact = [k for k in want if len(k) < S or N == 1]
+    assert len(exact) >= 1 + (V if S > 1 else 0)
+    for k in exact:
+        assert abs(got[k] - want[k]) < 1e-10, (k, got[k], want[k])
+    assert abs(logsumexp(list(got.values()))) < 1e-10
+    assert abs(logsumexp(list(want.values()))) < 1e-10
+
+
+@pytest.mark.parametrize("seed,S", [(0, 1), (1, 2), (2, 4), (3, 3)])
+def test_beam_one_window_one_is_greedy(seed, S):
+    T = 17
+    cfg, o = mixed_model(10 + seed, T, S, V=4, Hp=6, Hj=8, L=1 + seed % 2)
+    enc = make_enc(10 + seed, T, cfg.D)
+    tok, fr, log = o.greedy(enc, S)
+    assert 0 < len(tok) < T * S
+    best, _, _ = obs.wind_beam_search(o, enc, N=1, K=1, S=S)
+    assert list(best.tokens) == tok.tolist() and list(best.frames) == fr.tolist()
+    # score of the greedy path from the evaluation log: one softmax per joiner call
+    want, prefix = 0.0, []
+    for ev in log:
+        want += frame_log_probs(o, enc[ev["t"]], prefix)[ev["label"]]
+        if ev["label"] != cfg.V:
+            prefix.append(int(ev["label"]))
+    assert abs(best.score - want) < 1e-9
+
+
+def alignment_log_prob(o, enc, tokens, frames, S):
+    """log-probability of the one alignment that puts tokens[i] on frames[i] and blank elsewhere
+    (no blank is charged on a frame that was left because it holds S labels)."""
+    T, V = enc.shape[0], o.V
+    lp, u, t, sym = 0.0, 0, 0, 0
+    while t < T:
+        dist = frame_log_probs(o, enc[t], tokens[:u])
+        if u < len(tokens) and frames[u] == t:
+            lp += dist[tokens[u]]
+            u += 1
+            sym += 1
+            if sym >= S:
+                t, sym = t + 1, 0
+        else:
+            lp += dist[V]
+            t, sym = t + 1, 0
+    assert u == len(tokens)
+    return lp
+
+
+@pytest.mark.parametrize("seed,N,S", [(0, 2, 2), (1, 4, 3), (2, 7, 1), (3, 16, 4), (4, 3, 2)])
+def test_beam_one_score_is_its_alignment(seed, N, S):
+    cfg, o = mixed_model(20 + seed, 19, S, V=5, Hp=6, Hj=8)
+    enc = make_enc(20 + seed, 19, cfg.D)
+    best, _, _ = obs.wind_beam_search(o, enc, N=N, K=1, S=S)
+    assert len(best.tokens) > 0
+    assert abs(best.score - alignment_log_prob(o, enc, best.tokens, best.frames, S)) < 1e-9
+
+
+def test_prefix_step_by_hand():
+    cfg, o = tiny_model(30, V=3)
+    frame = make_enc(30, 1, cfg.D)[0]
+    lp = lambda prefix, v: float(frame_log_probs(o, frame, prefix)[v])
+    A = obs.Hyp((1,), (0,), np.log(0.30), 0)
+    B = obs.Hyp((1, 2), (0, 3), np.log(0.10), 0)
+    C = obs.Hyp((0,), (2,), np.log(0.20), 0)          # no relation to the others
+    fresh = lambda hs: [obs.Hyp(h.tokens, h.frames, h.score, h.sym) for h in hs]
+    out, _, pairs = obs.recombine_prune_prefix_search(fresh([A, B, C]), K=5, S=4, log_prob=lp, prefix_step="remove")
+    got = {h.tokens: h.score for h in out}
+    assert pairs == 1 and set(got) == {(1, 2), (0,)}                      # the literal sentence: A is gone
+    kept, _, _ = obs.recombine_prune_prefix_search(fresh([A, B, C]), K=5, S=4, log_prob=lp)
+    assert {h.tokens: h.score for h in kept} == {**got, (1,): np.log(0.30)}   # the credited definition: A stays
+    p_complete = np.exp(frame_log_probs(o, frame, (1,))[2])
+    assert np.isclose(np.exp(got[(1, 2)]), 0.10 + 0.30 * p_complete, rtol=1e-12)
+    assert np.isclose(np.exp(got[(0,)]), 0.20, rtol=1e-12)
+    assert [h.frames for h in out if h.tokens == (1, 2)] == [(0, 3)]      # B keeps its own time stamps
+    # the safeguard forbids the completion when A already holds S - 1 labels on this frame
+    A2 = obs.Hyp((1,), (0,), np.log(0.30), 3)
+    out, _, pairs = obs.recombine_prune_prefix_search(fresh([A2, B, C]), K=5, S=4, log_prob=lp)
+    assert pairs == 0 and {h.tokens for h in out} == {(1,), (1, 2), (0,)}
+
+
+def test_prefix_step_chain_counts_mass_once():
+    cfg, o = tiny_model(31, V=3)
+    frame = make_enc(31, 1, cfg.D)[0]
+    lp = lambda prefix, v: float(frame_log_probs(o, frame, prefix)[v])
+    pa, pb, pc = 0.25, 0.05, 0.02
+    hyps = [obs.Hyp((2,), (0,), np.log(pa)), obs.Hyp((2, 0), (0, 1), np.log(pb)),
+            obs.Hyp((2, 0, 1), (0, 1, 1), np.log(pc))]
+    for order in itertools.permutations(range(3)):
+        out, _, pairs = obs.recombine_prune_prefix_search([obs.Hyp(h.tokens, h.frames, h.score) for h in
+                                                           (hyps[i] for i in order)], K=5, S=8, log_prob=lp, prefix_step="remove")
+        q0 = np.exp(frame_log_probs(o, frame, (2,))[0])
+        q1 = np.exp(frame_log_probs(o, frame, (2, 0))[1])
+        assert pairs == 3 and [h.tokens for h in out] == [(2, 0, 1)]
+        # paths into (2,0,1): its own, (2,0) plus label 1, (2,) plus labels 0 then 1 -- each once
+        assert np.isclose(np.exp(out[0].score), pc + pb * q1 + pa * q0 * q1, rtol=1e-12)
+        kept, _, _ = obs.recombine_prune_prefix_search([obs.Hyp(h.tokens, h.frames, h.score) for h in
+                                                        (hyps[i] for i in order)], K=5, S=8, log_prob=lp)
+        got = {h.tokens: np.exp(h.score) for h in kept}
+        assert np.isclose(got[(2,)], pa, rtol=1e-12) and np.isclose(got[(2, 0)], pb + pa * q0, rtol=1e-12)
+        assert np.isclose(got[(2, 0, 1)], pc + pb * q1 + pa * q0 * q1, rtol=1e-12)
+
+
+def test_duplicates_are_added_and_keep_the_likelier_time_stamps():
+    h1 = obs.Hyp((1, 2), (0, 4), np.log(0.02), 1)
+    h2 = obs.Hyp((1, 2), (1, 3), np.log(0.05), 0)
+    h3 = obs.Hyp((1, 2), (1, 3), np.log(0.01), 0)
+    out, margin = obs.recombine([h1, h2, h3])
+    assert len(out) == 1 and np.isclose(np.exp(out[0].score), 0.08, rtol=1e-12)
+    assert out[0].frames == (1, 3) and out[0].sym == 0
+    assert np.isclose(margin, np.log(0.05) - np.log(0.02))
+
+
+def test_pruning_keeps_the_k_best():
+    hyps = [obs.Hyp((i,), (0,), float(s)) for i, s in enumerate([-3.0, -1.0, -2.5, -0.5, -4.0])]
+    out, margin, _ = obs.recombine_prune_prefix_search(hyps, K=3, S=4, log_prob=None, prefix_step="off")
+    assert [h.tokens for h in out] == [(3,), (1,), (2,)] and np.isclose(margin, 0.5)
+
+
+@pytest.mark.parametrize("seed,N,K,S", [(0, 2, 2, 4), (1, 3, 3, 4), (5, 2, 3, 4)])
+def test_removing_prefixes_degrades_the_search(seed, N, K, S):
+    # Why the default keeps a prefix in the set: with the removal the search loses its most probable
+    # short hypotheses and drifts to outputs several times longer with much lower scores.
+    T = 12
+    cfg, o = mixed_model(40 + seed, T, S, target=0.8, V=4, Hp=6, Hj=8)
+    enc = make_enc(40 + seed, T, cfg.D)
+    off = obs.wind_beam_search(o, enc, N, K, S, prefix_step="off")[0]
+    remove = obs.wind_beam_search(o, enc, N, K, S, prefix_step="remove")[0]
+    assert remove.score < off.score - 5.0 and len(remove.tokens) > 2 * len(off.tokens) + 4
+
+
+@pytest.mark.parametrize("seed,N,K,S", [(0, 4, 4, 3), (1, 8, 2, 2), (2, 16, 8, 4), (3, 1, 4, 2)])
+def test_output_invariants_and_trace(seed, N, K, S):
+    T = 21
+    cfg, o = mixed_model(50 + seed, T, S, V=6, Hp=6, Hj=8, L=1 + seed % 2)
+    enc = make_enc(50 + seed, T, cfg.D)
+    trace = []
+    best, final, _ = obs.wind_beam_search(o, enc, N, K, S, trace=trace)
+    assert len(best.tokens) == len(best.frames) and best.score <= 0.0
+    assert all(0 <= v < cfg.V for v in best.tokens)
+    assert all(a <= b for a, b in zip(best.frames, best.frames[1:])) and all(0 <= f < T for f in best.frames)
+    assert max(np.bincount(best.frames, minlength=1)) <= S
+    assert len(final) == len({h.tokens for h in final})
+    ts = [r.t for r in trace]
+    assert ts == sorted(ts) and ts[0] == 0 and all(r.n == min(N, T - r.t) for r in trace)
+    for r in trace:
+        assert 1 <= len(r.hyps) <= K and len(r.expansions) == len(r.hyps)
+        assert all(len(e) <= K for e in r.expansions) and r.margin >= 0.0
+        for e in r.expansions:
+            assert all((v == cfg.V) == (j == r.n - 1 and v == cfg.V) or v != cfg.V for v, j, _ in e)
+            assert [s for _, _, s in e] == sorted((s for _, _, s in e), reverse=True)
+    # a wider beam never scores its best hypothesis below the greedy alignment's own probability
+    g = obs.wind_beam_search(o, enc, N, 1, S)[0]
+    assert best.score >= g.score - 1e-12 or best.tokens != g.tokens
+
+
+def test_empty_utterance():
+    cfg, o = tiny_model(60)
+    best, final, _ = obs.wind_beam_search(o, np.zeros((0, cfg.D), np.float32), 4, 3, 2)
+    assert best.tokens == () and best.score == 0.0
