@@ -163,6 +163,33 @@ def beam_scoring(torch, wi, WindModel, steps):
             "joiner_gflops": round(2.0 * Bh * n * cfg.Hj * (cfg.V + 1) / 1e9, 3)}
 
 
+def beam_search(torch, wi, WindModel):
+    """Whole WIND beam search (Algorithm 3) on the first 250 frames of the headline utterance: beam 4,
+    window 16 against window 1, in both logit modes (bf16 MFMA pass; fp32 hidden vector).  One call
+    each after a warm-up call; device-resident encoder outputs."""
+    cfg = wi.CONFIGS["greedy_b1"]
+    w = wi.sharpened(wi.make_weights(cfg), 8.0)   # peaked soft-max, as a trained model's; same greedy output
+    enc, lens = wi.make_batch(cfg)
+    T, K = 250, 4
+    model = WindModel.from_config(cfg, w)
+    d_enc = torch.from_numpy(enc[0, :T]).cuda()
+    res = {"workload": f"greedy_b1 model with its output layer times 8, first {T} frames, beam {K}, S={cfg.S}, "
+                       "prefix step 'keep'"}
+    for exact in (0, 1):
+        model.set_option("beam_exact", exact)
+        for N in (1, 16):
+            model.beam_decode(d_enc[:32].contiguous(), N, K, cfg.S)
+            t0 = time.perf_counter()
+            tok, frm, score, st = model.beam_decode(d_enc, N, K, cfg.S)
+            sec = time.perf_counter() - t0
+            res[f"{'fp32' if exact else 'bf16'}_logits_N{N}"] = {
+                "ms": round(sec * 1e3, 2), "frames_per_s": round(T / sec, 1), "passes": int(st.rounds),
+                "us_per_pass": round(sec * 1e6 / max(1, st.rounds), 1), "labels": int(len(tok)),
+                "decoder_steps": int(st.decoder_steps), "completions": int(st.completions), "score": round(score, 3)}
+    model.close()
+    return res
+
+
 def cpu_baseline(wi, cfg, enc, lens, w, budget_frames):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -259,6 +286,7 @@ def main():
     if not args.no_ablation:
         line["graph_ablation"] = graph_ablation(torch, wi, WindModel, max(1, min(args.steps, 3)), 1)
         line["beam_scoring"] = beam_scoring(torch, wi, WindModel, args.steps)
+        line["beam_search"] = beam_search(torch, wi, WindModel)
     if not args.no_roofline:
         rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload, None,
                                                             max(1, min(args.steps, 3)), 1, with_sequential=False)

@@ -138,6 +138,57 @@ int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *l
 int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
                             int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream);
 
+/*
+ * Method, "A Novel Beam-search Algorithm for WIND", Algorithm 3, whole: beam search over one
+ * utterance.  A map from frames to the hypotheses that rest there is kept on the host; the
+ * hypotheses of the smallest frame t are taken out, recombined, passed through the prefix step and
+ * pruned to K (the three steps listed under the algorithm), scored on the window of
+ * n = min(window, T - t) frames with P' of Eq. 1, and each of their K best (label, jump) pairs goes
+ * back into the map at the frame it leads to (label: t + jump, blank: t + n).  Every model
+ * evaluation runs on the GPU: the encoder projection of all frames once, one prediction-network
+ * step per new label sequence that survives pruning (states are kept for every sequence the
+ * search has touched), the joiner rows of each window, their soft-max, P' and the K best pairs,
+ * and the rows the prefix step needs.
+ *   enc_out     DEVICE [T, D] fp32 encoder outputs of the utterance
+ *   window      N of the algorithm, 1..64;  K  beam, 1..32
+ *   S           safeguard against staying on one frame for ever (the algorithm's footnote): after
+ *               the S-th consecutive label on a frame a hypothesis moves one frame on, at no cost,
+ *               as in the greedy decoders of this library; S >= 1
+ *   prefix_mode what the prefix step does with a hypothesis A that is a proper prefix of another
+ *               hypothesis B on the same frame.  In every mode but OFF, B gains A's probability
+ *               times the probability of emitting the missing labels on frame t (only completions
+ *               that the safeguard allows).  KEEP leaves A in the set (the definition in the work
+ *               the section credits for this step); REMOVE takes A out (the section's own sentence)
+ *   out_tokens, out_frames  HOST [cap] int32: labels of the most probable hypothesis at frame T and
+ *               the frame of each; out_count HOST: their number; out_score HOST: its log-probability
+ *   stats       HOST, may be NULL;  on_round  may be NULL: called after the scoring step of every
+ *               pass with the surviving hypotheses and their chosen pairs (HOST arrays that are
+ *               valid during the call only): hyp_tokens / hyp_frames are the hypotheses' labels and
+ *               label frames back to back (hyp_len[b] each), labels / jumps / scores are [n_hyps, K]
+ * Scores are natural-log probabilities, accumulated in fp64 on the host from fp32 log P' values.
+ * Equal scores: duplicates keep the lexicographically smaller time stamps; pruning and the final
+ * choice prefer the shorter, then the lexicographically smaller label sequence.
+ * Returns WIND_ERR_OVERFLOW (after setting out_count and out_score) if the result has more than
+ * cap labels.  Returns after completion; allocates on first use and when the search outgrows its
+ * state pool.
+ */
+typedef enum { WIND_PREFIX_OFF = 0, WIND_PREFIX_KEEP = 1, WIND_PREFIX_REMOVE = 2 } wind_prefix_mode;
+typedef struct {
+  int64_t rounds;          /* passes of the while-loop                                        */
+  int64_t hyps_scored;     /* hypotheses sent through the scoring step, over all passes       */
+  int64_t decoder_steps;   /* prediction-network steps (one per label sequence given a state) */
+  int64_t completions;     /* (A, B) pairs handled by the prefix step                         */
+  int64_t completion_rows; /* joiner rows evaluated for them                                  */
+  int64_t max_pending;     /* most hypotheses taken out of the map in one pass                */
+  int64_t nodes;           /* distinct label sequences created                                */
+} wind_beam_stats;
+typedef void (*wind_beam_round_fn)(void *user, int t, int n, int n_hyps, const int32_t *hyp_len, const int32_t *hyp_tokens,
+                                   const int32_t *hyp_frames, const double *hyp_score, const int32_t *hyp_sym, int K,
+                                   const int32_t *labels, const int32_t *jumps, const float *scores);
+int wind_beam_decode(wind_model *m, const float *enc_out, int T, int window, int K, int S, int prefix_mode,
+                     int32_t *out_tokens, int32_t *out_frames, int cap, int32_t *out_count, double *out_score,
+                     wind_beam_stats *stats, wind_beam_round_fn on_round, void *user, void *stream);
+
 /* Counters of the last decode call; HOST pointer. */
 int wind_get_stats(wind_model *m, wind_stats *out);
 
@@ -192,6 +243,9 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "loop_spin_limit"  polls a workgroup of that kernel waits at a barrier before it gives up
  *             (default 2^21, about a second); the decode then returns WIND_ERR_HIP.  Tests set it
  *             to 0 to exercise that path: every workgroup still leaves the kernel normally
+ *   "beam_exact"  1: the beam-search entry points evaluate bf16 models' joiner rows with an fp32
+ *             hidden vector and fp32 FMA instead of the bf16 MFMA pass, so that their choices do
+ *             not depend on the rounding of the hidden vector (default 0)
  *   "debug_stamps"  1: the few-rows kernels record phase time stamps, which the next decode
  *             prints to stderr (development aid; default 0)
  */

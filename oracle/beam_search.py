@@ -38,7 +38,8 @@ Readings where the paper is silent or leaves the detail to its implementation:
 
 Every discrete choice (which K pairs, which duplicate's time stamps, which K hypotheses, which
 final hypothesis) is recorded together with its margin: the score gap to the best alternative not
-chosen.  An implementation in lower precision may legitimately choose differently where a margin
+chosen.  Choices between hypotheses compare accumulated scores; the choice of a hypothesis' K
+pairs compares entries of one window, whose common history cancels: the two kinds are kept apart.  An implementation in lower precision may legitimately choose differently where a margin
 is below its error, and only there; the comparison protocol in tests/ uses these margins.
 
 Pins: tests/test_oracle_beam_search_pins.py.
@@ -77,7 +78,8 @@ class Round:
     n: int
     hyps: List[Hyp]                                  # after recombine_prune_prefix_search, best first
     expansions: List[List[Tuple[int, int, float]]]   # per hypothesis: (label, jump, log P'), best first
-    margin: float                                    # smallest gap of any choice made in this round
+    margin: float                                    # smallest gap of a choice between hypotheses (steps 1, 3)
+    expansion_margin: float = np.inf                 # smallest gap between a hypothesis' K-th and (K+1)-th pair
     n_completions: int = 0                           # (A, B) pairs handled by the prefix step
 
 
@@ -193,9 +195,9 @@ def wind_beam_search(model, enc: np.ndarray, N: int, K: int, S: int, prefix_step
         n = min(N, T - t)
         dec_out = np.stack([dec.out(h.tokens) for h in hyps])
         labels, jumps, scores, full = bs.beam_window(model, enc[t:t + n], dec_out, Kx)
-        rec = Round(t, n, [Hyp(h.tokens, h.frames, h.score, h.sym) for h in hyps], [], margin, n_pairs)
+        rec = Round(t, n, [Hyp(h.tokens, h.frames, h.score, h.sym) for h in hyps], [], margin, n_completions=n_pairs)
         for b, hyp in enumerate(hyps):
-            rec.margin = min(rec.margin, expansion_margin(full[b], Kx))
+            rec.expansion_margin = min(rec.expansion_margin, expansion_margin(full[b], Kx))
             rec.expansions.append([(int(labels[b, k]), int(jumps[b, k]), float(scores[b, k]))
                                    for k in range(Kx) if labels[b, k] >= 0])
             for k in range(Kx):

@@ -16,7 +16,8 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0
 
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
-           "wind_get_kernel_times", "wind_beam_window_scores")
+           "wind_get_kernel_times", "wind_beam_window_scores", "wind_beam_decode")
+PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
 
 
@@ -44,6 +45,18 @@ class WindStats(C.Structure):
         ("labels", C.c_int64), ("forced_advances", C.c_int64), ("rechecks", C.c_int64),
         ("jump_hist", C.c_int64 * (WIND_MAX_WINDOW + 1)),
     ]
+
+
+class WindBeamStats(C.Structure):
+    _fields_ = [
+        ("rounds", C.c_int64), ("hyps_scored", C.c_int64), ("decoder_steps", C.c_int64), ("completions", C.c_int64),
+        ("completion_rows", C.c_int64), ("max_pending", C.c_int64), ("nodes", C.c_int64),
+    ]
+
+
+_I32P = C.POINTER(C.c_int32)
+BEAM_ROUND_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_int, C.c_int, C.c_int, _I32P, _I32P, _I32P, C.POINTER(C.c_double), _I32P,
+                            C.c_int, _I32P, _I32P, C.POINTER(C.c_float))
 
 
 def lib_path() -> str:
@@ -75,6 +88,9 @@ def load_library():
         lib.wind_get_kernel_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.wind_beam_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                         C.c_void_p, C.c_void_p, C.c_int, _I32P, C.POINTER(C.c_double),
+                                         C.POINTER(WindBeamStats), C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -191,6 +207,36 @@ class WindModel:
         if out is not None:
             return None
         return lab.cpu().numpy(), jmp.cpu().numpy(), sc.cpu().numpy()
+
+    def beam_decode(self, enc_out, N: int, K: int, S: int, prefix_step: str = "keep", cap: Optional[int] = None,
+                    trace: Optional[list] = None):
+        """wind_beam_decode on a device tensor enc_out [T, D] (fp32).  Returns (tokens, frames, score,
+        stats).  With `trace` = a list, every pass appends a dict: t, n, hyps = [(tokens, frames, score,
+        sym)], expansions = per hypothesis [(label, jump, score)]."""
+        T = int(enc_out.shape[0])
+        assert enc_out.is_contiguous() and (T == 0 or int(enc_out.shape[1]) == self.D)
+        cap = cap if cap is not None else max(1, T * S)
+        tok = np.zeros(max(cap, 1), np.int32)
+        frm = np.zeros(max(cap, 1), np.int32)
+        cnt, score, st = C.c_int32(0), C.c_double(0.0), WindBeamStats()
+
+        def on_round(_user, t, n, n_hyps, hyp_len, hyp_tokens, hyp_frames, hyp_score, hyp_sym, Kc, labels, jumps, scores):
+            hyps, exps, o = [], [], 0
+            for b in range(n_hyps):
+                ln = hyp_len[b]
+                hyps.append((tuple(hyp_tokens[o:o + ln]), tuple(hyp_frames[o:o + ln]), hyp_score[b], hyp_sym[b]))
+                o += ln
+                exps.append([(labels[b * Kc + k], jumps[b * Kc + k], scores[b * Kc + k]) for k in range(Kc)
+                             if labels[b * Kc + k] >= 0])
+            trace.append({"t": t, "n": n, "hyps": hyps, "expansions": exps})
+
+        cb = BEAM_ROUND_FN(on_round) if trace is not None else None
+        rc = self._lib.wind_beam_decode(self._h, enc_out.data_ptr() if T else None, T, int(N), int(K), int(S),
+                                        PREFIX_MODES[prefix_step], tok.ctypes.data, frm.ctypes.data, int(cap),
+                                        C.byref(cnt), C.byref(score), C.byref(st),
+                                        C.cast(cb, C.c_void_p) if cb is not None else None, None, _stream_ptr())
+        _check(rc)
+        return tok[: cnt.value].copy(), frm[: cnt.value].copy(), score.value, st
 
     def debug_joint_logits(self, enc_out, b: int, t0: int, n: int, prefix: Sequence[int], exact: bool):
         import torch

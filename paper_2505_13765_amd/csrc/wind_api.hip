@@ -9,11 +9,12 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "wind_kernels.h"
-#include "wind_beam.h"
 #include "wind_beam.h"
 
 using namespace wind;
@@ -81,6 +82,17 @@ struct GraphKey {
 
 }  // namespace
 
+// Beam search: state slots of the label sequences it has touched, and staging for its round trips.
+struct BeamPool {
+  float *h = nullptr, *c = nullptr;   // [cap][L][Hp]
+  float *p = nullptr;                 // [cap][Hj]
+  int cap = 0;
+  float *e_all = nullptr;             // [T][Hj] every frame through the encoder projection
+  size_t e_bytes = 0;
+  int *d_stage = nullptr, *h_stage = nullptr;   // index lists, device and pinned host
+  void *d_res = nullptr, *h_res = nullptr;      // results of a round, device and pinned host
+};
+
 struct wind_model {
   ModelDev dev{};
   int dtype = WIND_BF16;
@@ -103,7 +115,9 @@ struct wind_model {
   long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
   LoopDev loop{};
-  void *beam_ws = nullptr;   // workspace of wind_beam_window_scores
+  void *beam_ws = nullptr;   // workspace of the beam scoring step
+  BeamPool beam_pool{};
+  int opt_beam_exact = 0;
   size_t beam_ws_bytes = 0;
   double kappa = 8.0;
   double wnorm_max = 0.0;
@@ -527,6 +541,8 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
 
 }  // namespace
 
+#include "wind_beam_search.h"
+
 extern "C" {
 
 const char *wind_last_error(void) { return g_err.c_str(); }
@@ -684,6 +700,7 @@ int wind_free(wind_model *m) {
   for (void *p : m->allocs) (void)hipFree(p);
   if (m->ws) (void)hipFree(m->ws);
   if (m->beam_ws) (void)hipFree(m->beam_ws);
+  beam_pool_free(m);
   if (m->h_flag) (void)hipHostFree(m->h_flag);
   for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
   delete m;
@@ -710,52 +727,14 @@ int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const
   if (Bh < 1 || (long long)Bh * n > 65536) return fail(WIND_ERR_ARG, "Bh >= 1 and Bh * n <= 65536 required");
   const ModelDev &d = m->dev;
   hipStream_t s = (hipStream_t)stream;
-  const size_t rows = (size_t)Bh * n, rows_pad = round_up(rows, JointCfg::BM), V1 = (size_t)d.V + 1;
-  size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
-  const size_t o_e = take((size_t)n * d.Hj * 4), o_p = take((size_t)Bh * d.Hj * 4);
-  const size_t o_z = take(rows_pad * d.Hj * 2), o_lg = take(rows * V1 * 4);
-  const size_t o_lse = take(rows * 4), o_blp = take(rows * 4), o_cl = take(rows * kBeamMaxK * 4), o_cv = take(rows * kBeamMaxK * 4);
-  if (off > m->beam_ws_bytes) {
-    HIP_TRY(hipDeviceSynchronize());
-    if (m->beam_ws) HIP_TRY(hipFree(m->beam_ws));
-    m->beam_ws = nullptr;
-    m->beam_ws_bytes = 0;
-    HIP_TRY(hipMalloc(&m->beam_ws, off));
-    m->beam_ws_bytes = off;
-    HIP_TRY(hipMemset(m->beam_ws, 0, off));   // the MFMA pass reads whole row tiles
-  }
-  char *base = (char *)m->beam_ws;
-  float *e = (float *)(base + o_e), *p = (float *)(base + o_p), *logits = (float *)(base + o_lg);
-  bf16_t *z = (bf16_t *)(base + o_z);
-  constexpr int kR = 8;                                 // rows that share one pass over a weight row
-  const unsigned jb = (unsigned)((d.Hj + 3) / 4);
-  if (m->dtype == WIND_BF16) {
-    beam_linear_kernel<bf16_t, true, kR><<<dim3(jb, (unsigned)((n + kR - 1) / kR)), 256, 0, s>>>((const bf16_t *)d.w_enc, d.b_enc, enc_window, e, n, d.Hj, d.D);
-    beam_linear_kernel<bf16_t, false, kR><<<dim3(jb, (unsigned)((Bh + kR - 1) / kR)), 256, 0, s>>>((const bf16_t *)d.w_pred, d.b_pred, dec_out, p, Bh, d.Hj, d.Hp);
-    beam_hidden_kernel<<<(unsigned)rows, 256, 0, s>>>(e, p, z, n, d.Hj);
-    dim3 grid((unsigned)(rows_pad / JointCfg::BM), (unsigned)((V1 + JointCfg::BN - 1) / JointCfg::BN));
-    joint_mfma_store_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, z, (int)rows, logits);
-  } else {
-    beam_linear_kernel<float, false, kR><<<dim3(jb, (unsigned)((n + kR - 1) / kR)), 256, 0, s>>>((const float *)d.w_enc, d.b_enc, enc_window, e, n, d.Hj, d.D);
-    beam_linear_kernel<float, false, kR><<<dim3(jb, (unsigned)((Bh + kR - 1) / kR)), 256, 0, s>>>((const float *)d.w_pred, d.b_pred, dec_out, p, Bh, d.Hj, d.Hp);
-    beam_logits_f32_kernel<<<(unsigned)rows, 256, (size_t)d.Hj * 4, s>>>(d, e, p, n, logits);
-  }
-  if (V1 <= 256 * 36) {
-    // one workgroup per row, then one wave per hypothesis
-    float *lse = (float *)(base + o_lse), *blp = (float *)(base + o_blp), *cl = (float *)(base + o_cl);
-    int *cv = (int *)(base + o_cv);
-    if (V1 <= 256 * 8) beam_row_kernel<8><<<(unsigned)rows, 256, 0, s>>>(logits, d.V, K, lse, blp, cl, cv);
-    else beam_row_kernel<36><<<(unsigned)rows, 256, 0, s>>>(logits, d.V, K, lse, blp, cl, cv);
-    beam_merge_kernel<<<(unsigned)Bh, 64, 0, s>>>(lse, blp, cl, cv, n, d.V, K, out_labels, out_jumps, out_scores);
-  } else if (K <= 8) {
-    beam_score_kernel<8><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
-  } else if (K <= 16) {
-    beam_score_kernel<16><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
-  } else {
-    beam_score_kernel<32><<<(unsigned)Bh, 256, 0, s>>>(logits, n, d.V, K, out_labels, out_jumps, out_scores);
-  }
-  int rc = check_launch("beam window scores");
+  BeamWs ws;
+  int rc = beam_workspace(m, (size_t)n, (size_t)Bh, (size_t)Bh * n, &ws);
+  if (rc) return rc;
+  beam_enqueue_linear(m, d.w_enc, d.b_enc, enc_window, ws.e, n, d.Hj, d.D, true, s);
+  beam_enqueue_linear(m, d.w_pred, d.b_pred, dec_out, ws.p, Bh, d.Hj, d.Hp, false, s);
+  beam_enqueue_logits(m, ws, ws.e, n, ws.p, nullptr, Bh, s);
+  beam_enqueue_topk(m, ws, n, Bh, K, out_labels, out_jumps, out_scores, s);
+  rc = check_launch("beam window scores");
   if (rc) return rc;
   HIP_TRY(hipStreamSynchronize(s));
   return WIND_OK;
@@ -785,6 +764,10 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "unroll")) {
     if (value < 2 || value > 256 || (value & 1)) return fail(WIND_ERR_ARG, "unroll must be even, 2..256");
     m->opt_unroll = (int)value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "beam_exact")) {
+    m->opt_beam_exact = value != 0;
     return WIND_OK;
   }
   if (!std::strcmp(key, "debug_stamps")) {

@@ -43,27 +43,142 @@ __global__ __launch_bounds__(256) void beam_linear_kernel(const WT *w, const flo
   }
 }
 
-// Row (b, t) of the joiner's hidden layer, relu(e[t] + p[b]), as bf16 for the MFMA pass.
-__global__ __launch_bounds__(256) void beam_hidden_kernel(const float *e, const float *p, bf16_t *z, int n, int Hj) {
+// Row (b, t) of the joiner's hidden layer, relu(e[t] + p[b]), as bf16 for the MFMA pass.  p_idx (may be
+// null) names the row of p that belongs to hypothesis b.
+__global__ __launch_bounds__(256) void beam_hidden_kernel(const float *e, const float *p, const int *p_idx, bf16_t *z,
+                                                          int n, int Hj) {
   const int row = blockIdx.x, b = row / n, t = row - b * n;
+  const float *pr = p + (size_t)(p_idx ? p_idx[b] : b) * Hj;
   for (int k = threadIdx.x; k < Hj; k += 256)
-    z[(size_t)row * Hj + k] = (bf16_t)f32_to_bf16_bits(fmaxf(e[(size_t)t * Hj + k] + p[(size_t)b * Hj + k], 0.f));
+    z[(size_t)row * Hj + k] = (bf16_t)f32_to_bf16_bits(fmaxf(e[(size_t)t * Hj + k] + pr[k], 0.f));
 }
 
-// fp32 models: logits of row (b, t) by fp32 FMA, one workgroup per row.
-__global__ __launch_bounds__(256) void beam_logits_f32_kernel(ModelDev m, const float *e, const float *p, int n,
-                                                              float *logits) {
+// Logits of row (b, t) by fp32 FMA on an fp32 hidden vector, one workgroup per row: fp32 models, and
+// bf16 models when the caller asks for decisions that do not depend on rounding the hidden vector.
+template <class WT>
+__global__ __launch_bounds__(256) void beam_logits_kernel(ModelDev m, const float *e, const float *p, const int *p_idx,
+                                                          int n, float *logits) {
   extern __shared__ float zs[];
   const int row = blockIdx.x, b = row / n, t = row - b * n;
-  for (int k = threadIdx.x; k < m.Hj; k += 256) zs[k] = fmaxf(e[(size_t)t * m.Hj + k] + p[(size_t)b * m.Hj + k], 0.f);
+  const float *pr = p + (size_t)(p_idx ? p_idx[b] : b) * m.Hj;
+  for (int k = threadIdx.x; k < m.Hj; k += 256) zs[k] = fmaxf(e[(size_t)t * m.Hj + k] + pr[k], 0.f);
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const float *w = reinterpret_cast<const float *>(m.w_out);
+  const WT *w = reinterpret_cast<const WT *>(m.w_out);
   for (int v = wave; v <= m.V; v += 4) {
     float a = 0.f;
-    for (int k = lane; k < m.Hj; k += 64) a = fmaf(w[(size_t)v * m.Hj + k], zs[k], a);
+    for (int k = lane; k < m.Hj; k += 64) a = fmaf(ldw(w, (size_t)v * m.Hj + k), zs[k], a);
     a = wave_sum(a);
     if (lane == 0) logits[(size_t)row * (m.V + 1) + v] = a + m.b_out[v];
+  }
+}
+
+// out[r] = log softmax(logits[r, :])[tok[r]]: one workgroup per row.
+__global__ __launch_bounds__(256) void beam_token_logp_kernel(const float *logits, int V1, const int *tok, float *out) {
+  __shared__ float s_f[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float *row = logits + (size_t)blockIdx.x * V1;
+  float mx = -INFINITY;
+  for (int v = tid; v < V1; v += 256) mx = fmaxf(mx, row[v]);
+  mx = wave_max_f32(mx);
+  if (lane == 0) s_f[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int v = tid; v < V1; v += 256) sum += expf(row[v] - mx);
+  sum = wave_sum(sum);
+  if (lane == 0) s_f[wave] = sum;
+  __syncthreads();
+  if (tid == 0) out[blockIdx.x] = row[tok[blockIdx.x]] - (mx + logf((s_f[0] + s_f[1]) + (s_f[2] + s_f[3])));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Prediction network for the hypotheses of a beam search.  States live in a pool of slots,
+// h and c as [slot][L][Hp], the projected output p as [slot][Hj]; a step reads the parent's slot
+// and writes the child's, so that every label sequence the search has touched keeps its state.
+// One wave per hidden unit, R rows at a time (a weight row is read once per group), fp32 FMA.
+template <class WT, int R>
+__global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float *h, float *c, int layer, int rows,
+                                                              const int *parent, const int *child, const int *tok) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int unit = blockIdx.x * 4 + wave;
+  if (unit >= m.Hp) return;
+  const int Hp = m.Hp, in = layer == 0 ? 0 : Hp, K = in + Hp;
+  const size_t slot_sz = (size_t)m.L * Hp;
+  const WT *w = reinterpret_cast<const WT *>(m.w_cat[layer]) + (size_t)unit * 4 * K;
+  for (int r0 = 0; r0 < rows; r0 += R) {
+    float acc[4][R];
+    const float *xh[R], *hp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int rr = min(r0 + r, rows - 1);
+      xh[r] = h + (size_t)child[rr] * slot_sz + (size_t)(layer > 0 ? layer - 1 : 0) * Hp;   // new h of the layer below
+      hp[r] = h + (size_t)parent[rr] * slot_sz + (size_t)layer * Hp;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g][r] = 0.f;
+    }
+    for (int k = lane; k < K; k += 64) {
+      float wv[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) wv[g] = ldw(w, (size_t)g * K + k);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float xv = k < in ? xh[r][k] : hp[r][k - in];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) acc[g][r] = fmaf(wv[g], xv, acc[g][r]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g][r] = wave_sum(acc[g][r]);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (lane == r && r0 + r < rows) {
+        // layer 0: the label's row of emb_gates carries the input sums and both biases
+        const float *add = layer == 0 ? m.emb_gates + (size_t)tok[r0 + r] * 4 * Hp + unit * 4 : m.b_cat[layer] + unit * 4;
+        const float ig = 1.f / (1.f + expf(-(acc[0][r] + add[0])));
+        const float fg = 1.f / (1.f + expf(-(acc[1][r] + add[1])));
+        const float gg = tanhf(acc[2][r] + add[2]);
+        const float og = 1.f / (1.f + expf(-(acc[3][r] + add[3])));
+        const size_t po = (size_t)parent[r0 + r] * slot_sz + (size_t)layer * Hp + unit;
+        const size_t co = (size_t)child[r0 + r] * slot_sz + (size_t)layer * Hp + unit;
+        const float cn = fg * c[po] + ig * gg;
+        c[co] = cn;
+        h[co] = og * tanhf(cn);
+      }
+    }
+  }
+}
+
+// p[child] = W_pred h_top[child] + b_pred for the new hypotheses.
+template <class WT, int R>
+__global__ __launch_bounds__(256) void beam_pred_kernel(ModelDev m, const float *h, float *p, int rows, const int *child) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 4 + wave;
+  if (j >= m.Hj) return;
+  const int Hp = m.Hp;
+  const size_t slot_sz = (size_t)m.L * Hp;
+  const WT *w = reinterpret_cast<const WT *>(m.w_pred) + (size_t)j * Hp;
+  for (int r0 = 0; r0 < rows; r0 += R) {
+    float acc[R];
+    const float *ht[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      ht[r] = h + (size_t)child[min(r0 + r, rows - 1)] * slot_sz + (size_t)(m.L - 1) * Hp;
+      acc[r] = 0.f;
+    }
+    for (int k = lane; k < Hp; k += 64) {
+      const float wv = ldw(w, k);
+#pragma unroll
+      for (int r = 0; r < R; ++r) acc[r] = fmaf(wv, ht[r][k], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float tot = wave_sum(acc[r]);
+      if (lane == 0 && r0 + r < rows) p[(size_t)child[r0 + r] * m.Hj + j] = tot + m.b_pred[j];
+    }
   }
 }
 

@@ -121,6 +121,17 @@ def make_weights(cfg: WindConfig, blank_bias: Optional[float] = None,
     return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in w.items()}
 
 
+def sharpened(weights: Dict[str, np.ndarray], gain: float = 8.0) -> Dict[str, np.ndarray]:
+    """The same model with its output layer (w_out, b_out) multiplied by `gain`: every argmax, hence
+    every greedy result, is unchanged, but the soft-max becomes peaked like a trained model's (a
+    random output layer gives nearly flat probabilities, under which a search over probabilities
+    never prefers "blank on every frame of the window").  A power of two keeps bf16 values bf16."""
+    w = dict(weights)
+    w["w_out"] = np.ascontiguousarray(weights["w_out"] * np.float32(gain))
+    w["b_out"] = np.ascontiguousarray(weights["b_out"] * np.float32(gain))
+    return w
+
+
 def make_batch(cfg: WindConfig) -> Tuple[np.ndarray, np.ndarray]:
     """Encoder outputs enc_out[B, T, D] ~ N(0,1) and lengths[B]; T = max(lengths).
 
