@@ -236,6 +236,7 @@ def main():
                     help="first run a plain 1 GiB device copy, the known-size reference for the HBM byte counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ablation", action="store_true", help="skip the graph / no-graph table at batch 16")
+    ap.add_argument("--beam-only", action="store_true", help="only the beam-search figures (for profiling them)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (utterances are independent; more GPUs would "
@@ -248,6 +249,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.beam_only:
+        print(json.dumps({"beam_scoring": beam_scoring(torch, wi, WindModel, args.steps),
+                          "beam_search": beam_search(torch, wi, WindModel)}))
+        return
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)

@@ -89,8 +89,8 @@ struct BeamPool {
   int cap = 0;
   float *e_all = nullptr;             // [T][Hj] every frame through the encoder projection
   size_t e_bytes = 0;
-  int *d_stage = nullptr, *h_stage = nullptr;   // index lists, device and pinned host
-  void *d_res = nullptr, *h_res = nullptr;      // results of a round, device and pinned host
+  int *d_stage = nullptr, *h_stage = nullptr;   // index lists of a large batch, device and pinned host
+  void *h_res = nullptr, *d_res = nullptr;      // results of a pass: pinned host memory and its device address
 };
 
 struct wind_model {
@@ -732,7 +732,7 @@ int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const
   if (rc) return rc;
   beam_enqueue_linear(m, d.w_enc, d.b_enc, enc_window, ws.e, n, d.Hj, d.D, true, s);
   beam_enqueue_linear(m, d.w_pred, d.b_pred, dec_out, ws.p, Bh, d.Hj, d.Hp, false, s);
-  beam_enqueue_logits(m, ws, ws.e, n, ws.p, nullptr, Bh, s);
+  beam_enqueue_logits(m, ws, ws.e, n, ws.p, beam_identity(), Bh, s);
   beam_enqueue_topk(m, ws, n, Bh, K, out_labels, out_jumps, out_scores, s);
   rc = check_launch("beam window scores");
   if (rc) return rc;
@@ -855,7 +855,7 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
       // hidden vectors rounded to bf16 into the window buffer, then the MFMA tile core with stores
       joint_exact_kernel<bf16_t><<<n, 256, (size_t)d.Hj * 4, s>>>(d, c, 0, 0, b, t0, n, pb, 1, nullptr, c.z);
       dim3 grid(1, (unsigned)((d.V + 1 + JointCfg::BN - 1) / JointCfg::BN));
-      joint_mfma_store_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, c.z, n, logits);
+      joint_mfma_store_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, c.z, nullptr, n, logits);
     }
     rc = check_launch("debug joint");
   }

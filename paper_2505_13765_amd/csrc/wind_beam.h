@@ -6,7 +6,8 @@
 //   the K best (label, jump) pairs of every hypothesis under P'
 // Order among equal scores: earlier frame, then lower label.  The logits take the same route as in
 // the greedy path (bf16 models: hidden vector rounded to bf16, bf16 MFMA, fp32 accumulation; fp32
-// models: fp32 FMA); everything after them is fp32.
+// models: fp32 FMA; bf16 models on request: fp32 hidden vector split into two bf16 vectors, both
+// through the MFMA pass); everything after them is fp32.
 #pragma once
 #include "wind_kernels.h"
 
@@ -14,6 +15,16 @@ namespace wind {
 
 constexpr int kBeamMaxK = 32;
 constexpr int kBeamMaxWindow = 64;
+
+// Which table row (or label) belongs to entry b of a launch: b itself, an entry of a device list, or
+// one of up to 32 values carried in the launch's own arguments (no copy to the device needed).
+constexpr int kBeamInline = 32;
+struct BeamIndex {
+  const int *ptr;
+  int n_inline;
+  int inl[kBeamInline];
+  __device__ __forceinline__ int operator()(int b) const { return ptr ? ptr[b] : (n_inline ? inl[b] : b); }
+};
 
 // out[r, j] = bias[j] + sum_k w[j, k] * x[r, k]: one wave per output j and group of R rows, so that a
 // weight row is read once per group.  ROUND_X rounds x to bf16 first (what the encoder projection
@@ -43,24 +54,28 @@ __global__ __launch_bounds__(256) void beam_linear_kernel(const WT *w, const flo
   }
 }
 
-// Row (b, t) of the joiner's hidden layer, relu(e[t] + p[b]), as bf16 for the MFMA pass.  p_idx (may be
-// null) names the row of p that belongs to hypothesis b.
-__global__ __launch_bounds__(256) void beam_hidden_kernel(const float *e, const float *p, const int *p_idx, bf16_t *z,
-                                                          int n, int Hj) {
+// Row (b, t) of the joiner's hidden layer, relu(e[t] + p[row pi(b)]), as bf16 for the MFMA pass.  With
+// z_lo the remainder after rounding is stored as a second bf16 vector (see joint_mfma_store_kernel).
+__global__ __launch_bounds__(256) void beam_hidden_kernel(const float *e, const float *p, BeamIndex pi, bf16_t *z,
+                                                          bf16_t *z_lo, int n, int Hj) {
   const int row = blockIdx.x, b = row / n, t = row - b * n;
-  const float *pr = p + (size_t)(p_idx ? p_idx[b] : b) * Hj;
-  for (int k = threadIdx.x; k < Hj; k += 256)
-    z[(size_t)row * Hj + k] = (bf16_t)f32_to_bf16_bits(fmaxf(e[(size_t)t * Hj + k] + pr[k], 0.f));
+  const float *pr = p + (size_t)pi(b) * Hj;
+  for (int k = threadIdx.x; k < Hj; k += 256) {
+    const float v = fmaxf(e[(size_t)t * Hj + k] + pr[k], 0.f);
+    const unsigned short hi = f32_to_bf16_bits(v);
+    z[(size_t)row * Hj + k] = (bf16_t)hi;
+    if (z_lo) z_lo[(size_t)row * Hj + k] = (bf16_t)f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
+  }
 }
 
 // Logits of row (b, t) by fp32 FMA on an fp32 hidden vector, one workgroup per row: fp32 models, and
 // bf16 models when the caller asks for decisions that do not depend on rounding the hidden vector.
 template <class WT>
-__global__ __launch_bounds__(256) void beam_logits_kernel(ModelDev m, const float *e, const float *p, const int *p_idx,
-                                                          int n, float *logits) {
+__global__ __launch_bounds__(256) void beam_logits_kernel(ModelDev m, const float *e, const float *p, BeamIndex pi, int n,
+                                                          float *logits) {
   extern __shared__ float zs[];
   const int row = blockIdx.x, b = row / n, t = row - b * n;
-  const float *pr = p + (size_t)(p_idx ? p_idx[b] : b) * m.Hj;
+  const float *pr = p + (size_t)pi(b) * m.Hj;
   for (int k = threadIdx.x; k < m.Hj; k += 256) zs[k] = fmaxf(e[(size_t)t * m.Hj + k] + pr[k], 0.f);
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -74,7 +89,7 @@ __global__ __launch_bounds__(256) void beam_logits_kernel(ModelDev m, const floa
 }
 
 // out[r] = log softmax(logits[r, :])[tok[r]]: one workgroup per row.
-__global__ __launch_bounds__(256) void beam_token_logp_kernel(const float *logits, int V1, const int *tok, float *out) {
+__global__ __launch_bounds__(256) void beam_token_logp_kernel(const float *logits, int V1, BeamIndex tok, float *out) {
   __shared__ float s_f[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float *row = logits + (size_t)blockIdx.x * V1;
@@ -90,7 +105,7 @@ __global__ __launch_bounds__(256) void beam_token_logp_kernel(const float *logit
   sum = wave_sum(sum);
   if (lane == 0) s_f[wave] = sum;
   __syncthreads();
-  if (tid == 0) out[blockIdx.x] = row[tok[blockIdx.x]] - (mx + logf((s_f[0] + s_f[1]) + (s_f[2] + s_f[3])));
+  if (tid == 0) out[blockIdx.x] = row[tok(blockIdx.x)] - (mx + logf((s_f[0] + s_f[1]) + (s_f[2] + s_f[3])));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -100,7 +115,7 @@ __global__ __launch_bounds__(256) void beam_token_logp_kernel(const float *logit
 // One wave per hidden unit, R rows at a time (a weight row is read once per group), fp32 FMA.
 template <class WT, int R>
 __global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float *h, float *c, int layer, int rows,
-                                                              const int *parent, const int *child, const int *tok) {
+                                                              BeamIndex parent, BeamIndex child, BeamIndex tok) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int unit = blockIdx.x * 4 + wave;
   if (unit >= m.Hp) return;
@@ -113,8 +128,8 @@ __global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float 
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int rr = min(r0 + r, rows - 1);
-      xh[r] = h + (size_t)child[rr] * slot_sz + (size_t)(layer > 0 ? layer - 1 : 0) * Hp;   // new h of the layer below
-      hp[r] = h + (size_t)parent[rr] * slot_sz + (size_t)layer * Hp;
+      xh[r] = h + (size_t)child(rr) * slot_sz + (size_t)(layer > 0 ? layer - 1 : 0) * Hp;   // new h of the layer below
+      hp[r] = h + (size_t)parent(rr) * slot_sz + (size_t)layer * Hp;
 #pragma unroll
       for (int g = 0; g < 4; ++g) acc[g][r] = 0.f;
     }
@@ -137,13 +152,13 @@ __global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float 
     for (int r = 0; r < R; ++r) {
       if (lane == r && r0 + r < rows) {
         // layer 0: the label's row of emb_gates carries the input sums and both biases
-        const float *add = layer == 0 ? m.emb_gates + (size_t)tok[r0 + r] * 4 * Hp + unit * 4 : m.b_cat[layer] + unit * 4;
+        const float *add = layer == 0 ? m.emb_gates + (size_t)tok(r0 + r) * 4 * Hp + unit * 4 : m.b_cat[layer] + unit * 4;
         const float ig = 1.f / (1.f + expf(-(acc[0][r] + add[0])));
         const float fg = 1.f / (1.f + expf(-(acc[1][r] + add[1])));
         const float gg = tanhf(acc[2][r] + add[2]);
         const float og = 1.f / (1.f + expf(-(acc[3][r] + add[3])));
-        const size_t po = (size_t)parent[r0 + r] * slot_sz + (size_t)layer * Hp + unit;
-        const size_t co = (size_t)child[r0 + r] * slot_sz + (size_t)layer * Hp + unit;
+        const size_t po = (size_t)parent(r0 + r) * slot_sz + (size_t)layer * Hp + unit;
+        const size_t co = (size_t)child(r0 + r) * slot_sz + (size_t)layer * Hp + unit;
         const float cn = fg * c[po] + ig * gg;
         c[co] = cn;
         h[co] = og * tanhf(cn);
@@ -154,7 +169,7 @@ __global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float 
 
 // p[child] = W_pred h_top[child] + b_pred for the new hypotheses.
 template <class WT, int R>
-__global__ __launch_bounds__(256) void beam_pred_kernel(ModelDev m, const float *h, float *p, int rows, const int *child) {
+__global__ __launch_bounds__(256) void beam_pred_kernel(ModelDev m, const float *h, float *p, int rows, BeamIndex child) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = blockIdx.x * 4 + wave;
   if (j >= m.Hj) return;
@@ -166,7 +181,7 @@ __global__ __launch_bounds__(256) void beam_pred_kernel(ModelDev m, const float 
     const float *ht[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      ht[r] = h + (size_t)child[min(r0 + r, rows - 1)] * slot_sz + (size_t)(m.L - 1) * Hp;
+      ht[r] = h + (size_t)child(min(r0 + r, rows - 1)) * slot_sz + (size_t)(m.L - 1) * Hp;
       acc[r] = 0.f;
     }
     for (int k = lane; k < Hp; k += 64) {
@@ -177,7 +192,7 @@ __global__ __launch_bounds__(256) void beam_pred_kernel(ModelDev m, const float 
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const float tot = wave_sum(acc[r]);
-      if (lane == 0 && r0 + r < rows) p[(size_t)child[r0 + r] * m.Hj + j] = tot + m.b_pred[j];
+      if (lane == 0 && r0 + r < rows) p[(size_t)child(r0 + r) * m.Hj + j] = tot + m.b_pred[j];
     }
   }
 }

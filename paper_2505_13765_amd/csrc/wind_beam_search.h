@@ -15,8 +15,16 @@ namespace {
 struct BeamWs {
   float *e, *p, *logits, *lse, *blp, *cl;
   int *cv;
-  bf16_t *z;
+  bf16_t *z, *z_lo;
 };
+
+BeamIndex beam_identity() { return BeamIndex{nullptr, 0, {0}}; }
+BeamIndex beam_list(const int *device_list) { return BeamIndex{device_list, 0, {0}}; }
+BeamIndex beam_inline(const int *host_values, int n) {
+  BeamIndex ix{nullptr, n, {0}};
+  for (int i = 0; i < n; ++i) ix.inl[i] = host_values[i];
+  return ix;
+}
 
 // Carves the scoring workspace for up to n frames, Bh hypotheses and `rows` joiner rows.
 int beam_workspace(wind_model *m, size_t n, size_t Bh, size_t rows, BeamWs *ws) {
@@ -25,7 +33,7 @@ int beam_workspace(wind_model *m, size_t n, size_t Bh, size_t rows, BeamWs *ws) 
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
   const size_t o_e = take(n * d.Hj * 4), o_p = take(Bh * d.Hj * 4);
-  const size_t o_z = take(rows_pad * d.Hj * 2), o_lg = take(rows * V1 * 4);
+  const size_t o_z = take(rows_pad * d.Hj * 2), o_zlo = take(rows_pad * d.Hj * 2), o_lg = take(rows * V1 * 4);
   const size_t o_lse = take(rows * 4), o_blp = take(rows * 4), o_cl = take(rows * kBeamMaxK * 4), o_cv = take(rows * kBeamMaxK * 4);
   if (off > m->beam_ws_bytes) {
     HIP_TRY(hipDeviceSynchronize());
@@ -39,25 +47,26 @@ int beam_workspace(wind_model *m, size_t n, size_t Bh, size_t rows, BeamWs *ws) 
   char *base = (char *)m->beam_ws;
   ws->e = (float *)(base + o_e); ws->p = (float *)(base + o_p); ws->logits = (float *)(base + o_lg);
   ws->z = (bf16_t *)(base + o_z);
+  ws->z_lo = (bf16_t *)(base + o_zlo);
   ws->lse = (float *)(base + o_lse); ws->blp = (float *)(base + o_blp); ws->cl = (float *)(base + o_cl);
   ws->cv = (int *)(base + o_cv);
   return WIND_OK;
 }
 
-// logits[(b, t), :] = joiner row of frame t of e_win ([n, Hj] projected frames) and hypothesis b
-// (row p_idx[b] of p, or row b if p_idx is null).
-void beam_enqueue_logits(wind_model *m, const BeamWs &ws, const float *e_win, int n, const float *p, const int *p_idx,
+// logits[(b, t), :] = joiner row of frame t of e_win ([n, Hj] projected frames) and hypothesis b (row
+// pi(b) of p).  bf16 models: the MFMA pass on the hidden vector rounded to bf16, or, with option
+// "beam_exact", on its split into two bf16 vectors (close to fp32 accuracy).  fp32 models: fp32 FMA.
+void beam_enqueue_logits(wind_model *m, const BeamWs &ws, const float *e_win, int n, const float *p, const BeamIndex &pi,
                          int Bh, hipStream_t s) {
   const ModelDev &d = m->dev;
   const size_t rows = (size_t)Bh * n, rows_pad = round_up(rows, JointCfg::BM), V1 = (size_t)d.V + 1;
-  if (m->dtype == WIND_BF16 && !m->opt_beam_exact) {
-    beam_hidden_kernel<<<(unsigned)rows, 256, 0, s>>>(e_win, p, p_idx, ws.z, n, d.Hj);
+  if (m->dtype == WIND_BF16) {
+    bf16_t *z_lo = m->opt_beam_exact ? ws.z_lo : nullptr;
+    beam_hidden_kernel<<<(unsigned)rows, 256, 0, s>>>(e_win, p, pi, ws.z, z_lo, n, d.Hj);
     dim3 grid((unsigned)(rows_pad / JointCfg::BM), (unsigned)((V1 + JointCfg::BN - 1) / JointCfg::BN));
-    joint_mfma_store_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, ws.z, (int)rows, ws.logits);
-  } else if (m->dtype == WIND_BF16) {
-    beam_logits_kernel<bf16_t><<<(unsigned)rows, 256, (size_t)d.Hj * 4, s>>>(d, e_win, p, p_idx, n, ws.logits);
+    joint_mfma_store_kernel<JointCfg><<<grid, JointCfg::NT, JointCfg::SMEM_BYTES, s>>>(d, ws.z, z_lo, (int)rows, ws.logits);
   } else {
-    beam_logits_kernel<float><<<(unsigned)rows, 256, (size_t)d.Hj * 4, s>>>(d, e_win, p, p_idx, n, ws.logits);
+    beam_logits_kernel<float><<<(unsigned)rows, 256, (size_t)d.Hj * 4, s>>>(d, e_win, p, pi, n, ws.logits);
   }
 }
 
@@ -95,8 +104,7 @@ void beam_enqueue_linear(wind_model *m, const void *w, const float *bias, const 
 
 // ---- state pool and staging ---------------------------------------------------------------------
 constexpr int kBeamCompRows = 1024;   // completion rows (prefix step) evaluated per batch
-constexpr int kBeamStageLstm = 0, kBeamStageScore = 3 * 64, kBeamStageComp = 4 * 64;
-constexpr int kBeamStageInts = 4 * 64 + 2 * kBeamCompRows;
+constexpr int kBeamStageInts = 2 * kBeamCompRows;   // device lists of a large completion batch: slots, labels
 constexpr int kBeamResScores = 0, kBeamResLabels = kBeamMaxK * kBeamMaxK, kBeamResJumps = 2 * kBeamMaxK * kBeamMaxK,
               kBeamResComp = 3 * kBeamMaxK * kBeamMaxK, kBeamResWords = 3 * kBeamMaxK * kBeamMaxK + kBeamCompRows;
 
@@ -104,10 +112,12 @@ int beam_pool_reserve(wind_model *m, int slots, hipStream_t s) {
   BeamPool &bp = m->beam_pool;
   const ModelDev &d = m->dev;
   if (!bp.h_stage) {
+    // results land in pinned host memory that the kernels write directly: a pass ends with a stream
+    // synchronisation and no copy
     HIP_TRY(hipHostMalloc((void **)&bp.h_stage, sizeof(int) * kBeamStageInts, hipHostMallocDefault));
     HIP_TRY(hipHostMalloc((void **)&bp.h_res, 4 * kBeamResWords, hipHostMallocDefault));
     HIP_TRY(hipMalloc((void **)&bp.d_stage, sizeof(int) * kBeamStageInts));
-    HIP_TRY(hipMalloc((void **)&bp.d_res, 4 * kBeamResWords));
+    HIP_TRY(hipHostGetDevicePointer(&bp.d_res, bp.h_res, 0));
   }
   if (slots <= bp.cap) return WIND_OK;
   int cap = bp.cap ? bp.cap : 1024;
@@ -135,25 +145,24 @@ void beam_pool_free(wind_model *m) {
   if (bp.p) (void)hipFree(bp.p);
   if (bp.e_all) (void)hipFree(bp.e_all);
   if (bp.d_stage) (void)hipFree(bp.d_stage);
-  if (bp.d_res) (void)hipFree(bp.d_res);
   if (bp.h_stage) (void)hipHostFree(bp.h_stage);
   if (bp.h_res) (void)hipHostFree(bp.h_res);
   bp = BeamPool{};
 }
 
-// One prediction-network step for `rows` new label sequences: staged (parent slot, child slot, label).
-void beam_enqueue_decoder_step(wind_model *m, int rows, hipStream_t s) {
+// One prediction-network step for `rows` (at most 32) new label sequences.
+void beam_enqueue_decoder_step(wind_model *m, int rows, const int *parent, const int *child, const int *tok, hipStream_t s) {
   const ModelDev &d = m->dev;
   BeamPool &bp = m->beam_pool;
-  const int *parent = bp.d_stage + kBeamStageLstm, *child = parent + 64, *tok = parent + 128;
+  const BeamIndex pa = beam_inline(parent, rows), ch = beam_inline(child, rows), tk = beam_inline(tok, rows);
   constexpr int R = 4;
   const unsigned lb = (unsigned)((d.Hp + 3) / 4), pb = (unsigned)((d.Hj + 3) / 4);
   for (int l = 0; l < d.L; ++l) {
-    if (m->dtype == WIND_BF16) beam_lstm_layer_kernel<bf16_t, R><<<lb, 256, 0, s>>>(d, bp.h, bp.c, l, rows, parent, child, tok);
-    else beam_lstm_layer_kernel<float, R><<<lb, 256, 0, s>>>(d, bp.h, bp.c, l, rows, parent, child, tok);
+    if (m->dtype == WIND_BF16) beam_lstm_layer_kernel<bf16_t, R><<<lb, 256, 0, s>>>(d, bp.h, bp.c, l, rows, pa, ch, tk);
+    else beam_lstm_layer_kernel<float, R><<<lb, 256, 0, s>>>(d, bp.h, bp.c, l, rows, pa, ch, tk);
   }
-  if (m->dtype == WIND_BF16) beam_pred_kernel<bf16_t, R><<<pb, 256, 0, s>>>(d, bp.h, bp.p, rows, child);
-  else beam_pred_kernel<float, R><<<pb, 256, 0, s>>>(d, bp.h, bp.p, rows, child);
+  if (m->dtype == WIND_BF16) beam_pred_kernel<bf16_t, R><<<pb, 256, 0, s>>>(d, bp.h, bp.p, rows, ch);
+  else beam_pred_kernel<float, R><<<pb, 256, 0, s>>>(d, bp.h, bp.p, rows, ch);
 }
 
 struct BeamNode {
@@ -218,9 +227,10 @@ extern "C" int wind_beam_decode(wind_model *m, const float *enc_out, int T, int 
   const size_t slot_sz = (size_t)d.L * d.Hp;
   HIP_TRY(hipMemsetAsync(bp.h, 0, slot_sz * 4, s));
   HIP_TRY(hipMemsetAsync(bp.c, 0, slot_sz * 4, s));
-  bp.h_stage[kBeamStageLstm] = 0; bp.h_stage[kBeamStageLstm + 64] = 1; bp.h_stage[kBeamStageLstm + 128] = V;
-  HIP_TRY(hipMemcpyAsync(bp.d_stage + kBeamStageLstm, bp.h_stage + kBeamStageLstm, sizeof(int) * 192, hipMemcpyHostToDevice, s));
-  beam_enqueue_decoder_step(m, 1, s);
+  {
+    const int zero_slot = 0, root_slot = 1, start_id = V;
+    beam_enqueue_decoder_step(m, 1, &zero_slot, &root_slot, &start_id, s);
+  }
   rc = check_launch("beam search set-up");
   if (rc) return rc;
   HIP_TRY(hipStreamSynchronize(s));
@@ -300,20 +310,23 @@ extern "C" int wind_beam_decode(wind_model *m, const float *enc_out, int T, int 
         std::vector<float> lp(row_node.size());
         for (size_t r0 = 0; r0 < row_node.size(); r0 += kBeamCompRows) {
           const int rows = (int)std::min<size_t>(kBeamCompRows, row_node.size() - r0);
-          int *slot = bp.h_stage + kBeamStageComp, *tok = slot + kBeamCompRows;
+          int *slot = bp.h_stage, *tok = slot + kBeamCompRows;
           for (int r = 0; r < rows; ++r) {
             const BeamNode &x = nodes[row_node[r0 + r]];
             slot[r] = nodes[x.parent].slot;
             tok[r] = x.token;
           }
-          HIP_TRY(hipMemcpyAsync(bp.d_stage + kBeamStageComp, slot, sizeof(int) * 2 * kBeamCompRows, hipMemcpyHostToDevice, s));
-          beam_enqueue_logits(m, ws, bp.e_all + (size_t)t * d.Hj, 1, bp.p, bp.d_stage + kBeamStageComp, rows, s);
-          beam_token_logp_kernel<<<(unsigned)rows, 256, 0, s>>>(ws.logits, V1, bp.d_stage + kBeamStageComp + kBeamCompRows,
-                                                                (float *)bp.d_res + kBeamResComp);
+          BeamIndex si, ti;
+          if (rows <= kBeamInline) {
+            si = beam_inline(slot, rows); ti = beam_inline(tok, rows);
+          } else {
+            HIP_TRY(hipMemcpyAsync(bp.d_stage, slot, sizeof(int) * 2 * kBeamCompRows, hipMemcpyHostToDevice, s));
+            si = beam_list(bp.d_stage); ti = beam_list(bp.d_stage + kBeamCompRows);
+          }
+          beam_enqueue_logits(m, ws, bp.e_all + (size_t)t * d.Hj, 1, bp.p, si, rows, s);
+          beam_token_logp_kernel<<<(unsigned)rows, 256, 0, s>>>(ws.logits, V1, ti, (float *)bp.d_res + kBeamResComp);
           rc = check_launch("beam prefix step");
           if (rc) return rc;
-          HIP_TRY(hipMemcpyAsync((float *)bp.h_res + kBeamResComp, (float *)bp.d_res + kBeamResComp, sizeof(float) * rows,
-                                 hipMemcpyDeviceToHost, s));
           HIP_TRY(hipStreamSynchronize(s));
           std::memcpy(lp.data() + r0, (float *)bp.h_res + kBeamResComp, sizeof(float) * rows);
           st.completion_rows += rows;
@@ -363,8 +376,7 @@ extern "C" int wind_beam_decode(wind_model *m, const float *enc_out, int T, int 
 
     // prediction-network step for the survivors whose label sequence is new
     {
-      int rows = 0;
-      int *parent = bp.h_stage + kBeamStageLstm, *child = parent + 64, *tok = parent + 128;
+      int rows = 0, parent[kBeamMaxK], child[kBeamMaxK], tok[kBeamMaxK];
       for (const BeamHyp &h : hyps) {
         BeamNode &nd = nodes[h.node];
         if (nd.slot >= 0) continue;
@@ -377,22 +389,22 @@ extern "C" int wind_beam_decode(wind_model *m, const float *enc_out, int T, int 
           rc = beam_pool_reserve(m, next_slot, s);
           if (rc) return rc;
         }
-        HIP_TRY(hipMemcpyAsync(bp.d_stage + kBeamStageLstm, parent, sizeof(int) * 192, hipMemcpyHostToDevice, s));
-        beam_enqueue_decoder_step(m, rows, s);
+        beam_enqueue_decoder_step(m, rows, parent, child, tok, s);
         st.decoder_steps += rows;
       }
     }
 
     // lines 9-13: the window's joiner rows, P' and the K best pairs of every hypothesis
     const int n = std::min(window, T - t);
-    for (int b = 0; b < Bh; ++b) bp.h_stage[kBeamStageScore + b] = nodes[hyps[b].node].slot;
-    HIP_TRY(hipMemcpyAsync(bp.d_stage + kBeamStageScore, bp.h_stage + kBeamStageScore, sizeof(int) * 64, hipMemcpyHostToDevice, s));
-    beam_enqueue_logits(m, ws, bp.e_all + (size_t)t * d.Hj, n, bp.p, bp.d_stage + kBeamStageScore, Bh, s);
+    {
+      int slots[kBeamMaxK];
+      for (int b = 0; b < Bh; ++b) slots[b] = nodes[hyps[b].node].slot;
+      beam_enqueue_logits(m, ws, bp.e_all + (size_t)t * d.Hj, n, bp.p, beam_inline(slots, Bh), Bh, s);
+    }
     beam_enqueue_topk(m, ws, n, Bh, K, (int32_t *)bp.d_res + kBeamResLabels, (int32_t *)bp.d_res + kBeamResJumps,
                       (float *)bp.d_res + kBeamResScores, s);
     rc = check_launch("beam scoring");
     if (rc) return rc;
-    HIP_TRY(hipMemcpyAsync(bp.h_res, bp.d_res, 4 * (size_t)kBeamResComp, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     st.hyps_scored += Bh;
     const float *scores = (const float *)bp.h_res + kBeamResScores;

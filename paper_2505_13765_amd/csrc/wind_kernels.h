@@ -445,19 +445,36 @@ __global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int p
   }
 }
 
-// Debug: the same tile core with the logits stored, bias added (columns 0..V, blank included).
+// The same tile core with the logits stored, bias added (columns 0..V, blank included): the debug entry
+// point and beam search.  With z_lo, every row is the sum of two bf16 vectors, z + z_lo (the fp32 hidden
+// vector split into a rounded value and the rounded remainder, about 16 mantissa bits together), and the
+// products with both are accumulated: logits at close to fp32 accuracy at MFMA speed.
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void joint_mfma_store_kernel(ModelDev m, const bf16_t *z, int n_rows,
-                                                                  float *logits) {
+__global__ __launch_bounds__(Cfg::NT) void joint_mfma_store_kernel(ModelDev m, const bf16_t *z, const bf16_t *z_lo,
+                                                                  int n_rows, float *logits) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
   const int row0 = blockIdx.x * Cfg::BM, n0 = blockIdx.y * Cfg::BN, Hj = m.Hj;
-  const bf16_t *zt = z + (size_t)row0 * Hj;
-  auto aload = [&](int, int row, int k) -> u32x4 {
-    return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k);
-  };
+  const bf16_t *w = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj;
   f32x16 acc[Cfg::MI][Cfg::NI];
-  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj, smem, acc);
+  {
+    const bf16_t *zt = z + (size_t)row0 * Hj;
+    auto aload = [&](int, int row, int k) -> u32x4 { return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k); };
+    gemm_mainloop<Cfg>(aload, w, Hj, smem, acc);
+  }
+  if (z_lo) {
+    f32x16 acc_lo[Cfg::MI][Cfg::NI];
+    const bf16_t *zt = z_lo + (size_t)row0 * Hj;
+    auto aload = [&](int, int row, int k) -> u32x4 { return *reinterpret_cast<const u32x4 *>(zt + (size_t)row * Hj + k); };
+    __syncthreads();   // the first pass may still be reading its last stage
+    gemm_mainloop<Cfg>(aload, w, Hj, smem, acc_lo);
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mi][ni][r] += acc_lo[mi][ni][r];
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 #pragma unroll
