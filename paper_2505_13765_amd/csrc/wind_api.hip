@@ -668,6 +668,9 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
     if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)beam_logits_tiny_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              2 * 32 * (kBeamTinyMaxHj + 8) * 2);
+    if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)enc_proj_ring5_kernel<JointBigCfg>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)

@@ -16,6 +16,15 @@ namespace wind {
 constexpr int kBeamMaxK = 32;
 constexpr int kBeamMaxWindow = 64;
 
+// Eight consecutive weights as floats: one 16-byte load for bf16 storage, two for fp32.
+__device__ __forceinline__ void ldw8(const bf16_t *w, size_t i, float (&o)[8]) {
+  unpack_bf16x8(*reinterpret_cast<const u32x4 *>(w + i), o);
+}
+__device__ __forceinline__ void ldw8(const float *w, size_t i, float (&o)[8]) {
+  const float4 a = *reinterpret_cast<const float4 *>(w + i), b = *reinterpret_cast<const float4 *>(w + i + 4);
+  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+
 // Which table row (or label) belongs to entry b of a launch: b itself, an entry of a device list, or
 // one of up to 32 values carried in the launch's own arguments (no copy to the device needed).
 constexpr int kBeamInline = 32;
@@ -88,6 +97,82 @@ __global__ __launch_bounds__(256) void beam_logits_kernel(ModelDev m, const floa
   }
 }
 
+// Few rows (bf16 models, Hj <= 1024): logits of one block of 32 rows x 32 columns per workgroup.  The
+// workgroup builds its hidden rows relu(e[t] + p[pi(b)]) in LDS itself (no separate pass, no trip
+// through memory), its four waves split K and read their W_out fragments straight from memory into
+// MFMA operands, all loads in flight at once; the four partial tiles are added through LDS.  With
+// `split` the remainder of the bf16 rounding is kept as a second vector and multiplied as well.
+// grid = (ceil((V+1) / 32), ceil(rows / 32)); dynamic LDS = (split ? 2 : 1) * 32 * (Hj + 8) * 2 bytes,
+// at least 16 KB.
+constexpr int kBeamTinyMaxHj = 1024;
+constexpr int kBeamTinyMaxRows = 256;
+__global__ __launch_bounds__(256) void beam_logits_tiny_kernel(ModelDev m, const float *e, const float *p, BeamIndex pi,
+                                                               int n, int rows, int split, float *logits) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int Hj = m.Hj, V1 = m.V + 1;
+  const int n0 = blockIdx.x * 32, row0 = blockIdx.y * 32;
+  const int nk = Hj / 64, k0 = wave * (Hj / 4);   // this wave's K steps of 16 and where they start
+  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
+  constexpr int kMaxSteps = kBeamTinyMaxHj / 64;
+  bf16x8 bfrag[kMaxSteps];
+#pragma unroll
+  for (int i = 0; i < kMaxSteps; ++i)
+    if (i < nk) bfrag[i] = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
+  const int zstride = Hj + 8;   // bf16 elements; an odd number of 16-byte units, so fragment reads spread over the banks
+  bf16_t *zs = reinterpret_cast<bf16_t *>(smem_raw), *zl = zs + 32 * zstride;
+  // hidden rows: a wave takes rows wave, wave + 4, ...
+  for (int r = wave; r < 32; r += 4) {
+    const int row = row0 + r;
+    const bool valid = row < rows;
+    const int b = valid ? row / n : 0, t = valid ? row - b * n : 0;
+    const float *er = e + (size_t)t * Hj, *pr = p + (size_t)pi(b) * Hj;
+    for (int k = lane * 4; k < Hj; k += 256) {
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (valid) {
+        const float4 ev = *reinterpret_cast<const float4 *>(er + k), pv = *reinterpret_cast<const float4 *>(pr + k);
+        x = make_float4(fmaxf(ev.x + pv.x, 0.f), fmaxf(ev.y + pv.y, 0.f), fmaxf(ev.z + pv.z, 0.f), fmaxf(ev.w + pv.w, 0.f));
+      }
+      const unsigned h01 = pack_bf16x2(x.x, x.y), h23 = pack_bf16x2(x.z, x.w);
+      *reinterpret_cast<uint2 *>(zs + (size_t)r * zstride + k) = make_uint2(h01, h23);
+      if (split) {
+        const float r0 = x.x - __uint_as_float(h01 << 16), r1 = x.y - __uint_as_float(h01 & 0xFFFF0000u);
+        const float r2 = x.z - __uint_as_float(h23 << 16), r3 = x.w - __uint_as_float(h23 & 0xFFFF0000u);
+        *reinterpret_cast<uint2 *>(zl + (size_t)r * zstride + k) = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+      }
+    }
+  }
+  __syncthreads();
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const bf16_t *zrow = zs + (size_t)(lane & 31) * zstride + k0 + (lane >> 5) * 8;
+#pragma unroll
+  for (int i = 0; i < kMaxSteps; ++i) {
+    if (i < nk) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(zrow + i * 16), bfrag[i], acc, 0, 0, 0);
+      if (split)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(zrow + 32 * zstride + i * 16), bfrag[i],
+                                                      acc, 0, 0, 0);
+    }
+  }
+  __syncthreads();   // every wave is done with the hidden rows: their LDS now takes the partial tiles
+  float *red = reinterpret_cast<float *>(smem_raw);   // [wave][r][lane]
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
+  __syncthreads();
+  const int col = n0 + (lane & 31);
+  if (col >= V1) return;
+  const float bias = m.b_out[col];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {   // wave w adds up and stores accumulator registers 4w .. 4w+3
+    const int r = wave * 4 + q;
+    const float v = (red[r * 64 + lane] + red[(16 + r) * 64 + lane]) + (red[(32 + r) * 64 + lane] + red[(48 + r) * 64 + lane]);
+    const int row = row0 + acc_row(0, r, lane);
+    if (row < rows) logits[(size_t)row * V1 + col] = v + bias;
+  }
+}
+
 // out[r] = log softmax(logits[r, :])[tok[r]]: one workgroup per row.
 __global__ __launch_bounds__(256) void beam_token_logp_kernel(const float *logits, int V1, BeamIndex tok, float *out) {
   __shared__ float s_f[4];
@@ -133,15 +218,34 @@ __global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float 
 #pragma unroll
       for (int g = 0; g < 4; ++g) acc[g][r] = 0.f;
     }
-    for (int k = lane; k < K; k += 64) {
-      float wv[4];
+    if ((Hp & 7) == 0) {
+      // eight weights of each gate row and eight inputs per lane and step: 16- and 32-byte loads
+      for (int k = lane * 8; k < K; k += 512) {
+        float wv[4][8];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) wv[g] = ldw(w, (size_t)g * K + k);
+        for (int g = 0; g < 4; ++g) ldw8(w, (size_t)g * K + k, wv[g]);
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float xv = k < in ? xh[r][k] : hp[r][k - in];
+        for (int r = 0; r < R; ++r) {
+          const float *xp = k < in ? xh[r] + k : hp[r] + (k - in);
+          const float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
+          const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
 #pragma unroll
-        for (int g = 0; g < 4; ++g) acc[g][r] = fmaf(wv[g], xv, acc[g][r]);
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[g][r] = fmaf(wv[g][q], xv[q], acc[g][r]);
+        }
+      }
+    } else {
+      for (int k = lane; k < K; k += 64) {
+        float wv[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) wv[g] = ldw(w, (size_t)g * K + k);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const float xv = k < in ? xh[r][k] : hp[r][k - in];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) acc[g][r] = fmaf(wv[g], xv, acc[g][r]);
+        }
       }
     }
 #pragma unroll
@@ -184,10 +288,24 @@ __global__ __launch_bounds__(256) void beam_pred_kernel(ModelDev m, const float 
       ht[r] = h + (size_t)child(min(r0 + r, rows - 1)) * slot_sz + (size_t)(m.L - 1) * Hp;
       acc[r] = 0.f;
     }
-    for (int k = lane; k < Hp; k += 64) {
-      const float wv = ldw(w, k);
+    if ((Hp & 7) == 0) {
+      for (int k = lane * 8; k < Hp; k += 512) {
+        float wv[8];
+        ldw8(w, k, wv);
 #pragma unroll
-      for (int r = 0; r < R; ++r) acc[r] = fmaf(wv, ht[r][k], acc[r]);
+        for (int r = 0; r < R; ++r) {
+          const float4 x0 = *reinterpret_cast<const float4 *>(ht[r] + k), x1 = *reinterpret_cast<const float4 *>(ht[r] + k + 4);
+          const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc[r] = fmaf(wv[q], xv[q], acc[r]);
+        }
+      }
+    } else {
+      for (int k = lane; k < Hp; k += 64) {
+        const float wv = ldw(w, k);
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r] = fmaf(wv, ht[r][k], acc[r]);
+      }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {

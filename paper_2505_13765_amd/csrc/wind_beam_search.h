@@ -60,7 +60,12 @@ void beam_enqueue_logits(wind_model *m, const BeamWs &ws, const float *e_win, in
                          int Bh, hipStream_t s) {
   const ModelDev &d = m->dev;
   const size_t rows = (size_t)Bh * n, rows_pad = round_up(rows, JointCfg::BM), V1 = (size_t)d.V + 1;
-  if (m->dtype == WIND_BF16) {
+  if (m->dtype == WIND_BF16 && d.Hj <= kBeamTinyMaxHj && rows <= (size_t)kBeamTinyMaxRows) {
+    const int split = m->opt_beam_exact ? 1 : 0;
+    const size_t smem = std::max<size_t>((size_t)(split + 1) * 32 * (d.Hj + 8) * 2, 16384);
+    dim3 grid((unsigned)((V1 + 31) / 32), (unsigned)((rows + 31) / 32));
+    beam_logits_tiny_kernel<<<grid, 256, smem, s>>>(d, e_win, p, pi, n, (int)rows, split, ws.logits);
+  } else if (m->dtype == WIND_BF16) {
     bf16_t *z_lo = m->opt_beam_exact ? ws.z_lo : nullptr;
     beam_hidden_kernel<<<(unsigned)rows, 256, 0, s>>>(e_win, p, pi, ws.z, z_lo, n, d.Hj);
     dim3 grid((unsigned)(rows_pad / JointCfg::BM), (unsigned)((V1 + JointCfg::BN - 1) / JointCfg::BN));
