@@ -247,3 +247,17 @@ def test_empty_utterance():
     cfg, o = tiny_model(60)
     best, final, _ = obs.wind_beam_search(o, np.zeros((0, cfg.D), np.float32), 4, 3, 2)
     assert best.tokens == () and best.score == 0.0
+
+
+def test_sharpened_models_keep_every_argmax():
+    # the input generator's peaked variant scales the output layer only: greedy decoding (every
+    # argmax) is unchanged, while the soft-max moves towards one-hot
+    cfg, o = tiny_model(70, V=6, Hp=6, Hj=8, blank_bias=1.0)
+    w = wi.make_weights(cfg, blank_bias=1.0, pred_gain=3.0)
+    o2 = oracle.Oracle.from_config(cfg, wi.sharpened(w, 8.0))
+    enc = make_enc(70, 25, cfg.D)
+    a, b = o.greedy(enc, 3), o2.greedy(enc, 3)
+    assert a[0].tolist() == b[0].tolist() and a[1].tolist() == b[1].tolist()
+    p1 = np.exp(scipy_log_softmax(o.joiner(enc[0], o.decoder_from_scratch([])))).max()
+    p8 = np.exp(scipy_log_softmax(o2.joiner(enc[0], o2.decoder_from_scratch([])))).max()
+    assert p8 > p1
