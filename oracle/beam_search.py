@@ -42,7 +42,11 @@ chosen.  Choices between hypotheses compare accumulated scores; the choice of a 
 pairs compares entries of one window, whose common history cancels: the two kinds are kept apart.  An implementation in lower precision may legitimately choose differently where a margin
 is below its error, and only there; the comparison protocol in tests/ uses these margins.
 
-Pins: tests/test_oracle_beam_search_pins.py.
+Pins (tests/test_oracle_beam_search_pins.py): brute-force enumeration of every alignment of tiny
+lattices, the greedy decoder at beam 1 / window 1, alignment log-probabilities at beam 1, hand-built
+prefix sets.  Parity unpinned: the readings listed above themselves (safeguard, duplicates, what
+happens to a prefix, tie rules), for which the paper refers to its implementation; the pins fix
+what follows from Eq. 1 and the printed steps of Algorithm 3 under those readings.
 """
 from __future__ import annotations
 
