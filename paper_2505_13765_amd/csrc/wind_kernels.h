@@ -1676,14 +1676,20 @@ __device__ __forceinline__ void st_shared_f32x2(float2 *p, float2 v) {
 }
 
 constexpr int kLoopFlagStride = 32;   // one 128-byte line per workgroup's arrival word
-__device__ __forceinline__ bool loop_barrier(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
+// The barrier in two halves, so that work that needs nothing from the other workgroups can fill the
+// time the arrivals take to travel: loop_arrive publishes this workgroup's arrival, loop_wait waits
+// for everybody's.  Between the two a workgroup must not write anything the others read before
+// the barrier, nor read what they write.
+__device__ __forceinline__ void loop_arrive(const LoopDev &lp, unsigned passed) {
   __syncthreads();   // this workgroup's stores of the phase have been issued and acknowledged
+  if (threadIdx.x == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and are visible to the agent before the arrival is
+    __hip_atomic_store(&lp.bar[(1 + blockIdx.x) * kLoopFlagStride], passed + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+__device__ __forceinline__ bool loop_wait(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
+  const unsigned epoch = ++passed;
   if (threadIdx.x < 64) {
-    const unsigned epoch = ++passed;
-    if (threadIdx.x == 0) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and are visible to the agent before the arrival is
-      __hip_atomic_store(&lp.bar[(1 + blockIdx.x) * kLoopFlagStride], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
     // every workgroup publishes the number of barriers it has reached; wave 0 watches all of them,
     // one lane per workgroup (no read-modify-write on a shared word: the arrivals do not queue up)
     unsigned spins = 0;
@@ -1704,12 +1710,14 @@ __device__ __forceinline__ bool loop_barrier(const LoopDev &lp, unsigned &passed
       if (!good) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       ls.ok = good;
     }
-  } else {
-    ++passed;
   }
   __syncthreads();
   asm volatile("" ::: "memory");   // the exchange reads that follow stay behind the wait
   return ls.ok != 0;
+}
+__device__ __forceinline__ bool loop_barrier(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
+  loop_arrive(lp, passed);
+  return loop_wait(lp, passed, ls);
 }
 
 // Sums of 16 / 8 / 4 per-lane values over the wave with a halving exchange: each step a lane keeps
@@ -1840,6 +1848,38 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
   unsigned passed = 0;
   __syncthreads();
+  // The recurrent half of the gate sums, W_hh h, depends on the hidden vector only, which changes
+  // when its utterance emits: it is formed as soon as the new vector is here (while the arrivals of
+  // the projection exchange travel), so that a step, once the label is known, only adds the
+  // label's row of input sums.  rec[b]: this wave's 16 (unit, gate) sums for utterance b, value
+  // 4q + gate in lanes 4q + 16*(gate>>1) + 32*(gate&1) + 0..3.
+  auto recurrent_sums = [&](int ub) {
+    float part[16];   // [unit q][gate]
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int u = wave + 4 * q;
+#pragma unroll
+      for (int gate = 0; gate < 4; ++gate) part[4 * q + gate] = 0.f;
+      if (u >= lp.upw) continue;
+      for (int k = lane * 8; k < Hp; k += 512) {
+        const f32x4 *hs = reinterpret_cast<const f32x4 *>(hfull + (size_t)ub * Hp + k);
+        const f32x4 ha = hs[0], hb2 = hs[1];
+#pragma unroll
+        for (int gate = 0; gate < 4; ++gate) {
+          float wf[8];
+          unpack_bf16x8(*reinterpret_cast<const u32x4 *>(wl + ((size_t)u * 4 + gate) * Hp + k), wf);
+          float a2 = part[4 * q + gate];
+          a2 = fmaf(wf[0], ha.x, a2); a2 = fmaf(wf[1], ha.y, a2); a2 = fmaf(wf[2], ha.z, a2); a2 = fmaf(wf[3], ha.w, a2);
+          a2 = fmaf(wf[4], hb2.x, a2); a2 = fmaf(wf[5], hb2.y, a2); a2 = fmaf(wf[6], hb2.z, a2); a2 = fmaf(wf[7], hb2.w, a2);
+          part[4 * q + gate] = a2;
+        }
+      }
+    }
+    return wave_sum16_scatter(part, lane);
+  };
+  float rec[kLoopMaxB];
+#pragma unroll
+  for (int b = 0; b < kLoopMaxB; ++b) rec[b] = b < B ? recurrent_sums(b) : 0.f;
 
   const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
   long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
@@ -2024,30 +2064,11 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
         addq[q] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (wave + 4 * q < lp.upw && unit < Hp) addq[q] = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok * 4 * Hp + unit * 4);
       }
-      float part[16];   // [unit q][gate]
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int u = wave + 4 * q;
-#pragma unroll
-        for (int gate = 0; gate < 4; ++gate) part[4 * q + gate] = 0.f;
-        if (u >= lp.upw) continue;
-        for (int k = lane * 8; k < Hp; k += 512) {
-          const f32x4 *hs = reinterpret_cast<const f32x4 *>(hfull + (size_t)ub * Hp + k);
-          const f32x4 ha = hs[0], hb2 = hs[1];
-#pragma unroll
-          for (int gate = 0; gate < 4; ++gate) {
-            float wf[8];
-            unpack_bf16x8(*reinterpret_cast<const u32x4 *>(wl + ((size_t)u * 4 + gate) * Hp + k), wf);
-            float a2 = part[4 * q + gate];
-            a2 = fmaf(wf[0], ha.x, a2); a2 = fmaf(wf[1], ha.y, a2); a2 = fmaf(wf[2], ha.z, a2); a2 = fmaf(wf[3], ha.w, a2);
-            a2 = fmaf(wf[4], hb2.x, a2); a2 = fmaf(wf[5], hb2.y, a2); a2 = fmaf(wf[6], hb2.z, a2); a2 = fmaf(wf[7], hb2.w, a2);
-            part[4 * q + gate] = a2;
-          }
-        }
-      }
-      // value 4q + gate lands in lanes 4q + 16*(gate>>1) + 32*(gate&1) + 0..3: every gate's
+      // the recurrent sums were formed when this utterance's hidden vector last changed: every gate's
       // nonlinearity runs on its own lanes, then lane 4q gathers its unit's four
-      const float tot = wave_sum16_scatter(part, lane);
+      float tot = rec[0];
+#pragma unroll
+      for (int b = 1; b < kLoopMaxB; ++b) tot = ub == b ? rec[b] : tot;
       const int q = (lane >> 2) & 3, gate = ((lane >> 4) & 1) * 2 + (lane >> 5);
       float4 aq = addq[0];
       if (q == 1) aq = addq[1];
@@ -2101,7 +2122,14 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       }
     }
     const long long t7 = dbg ? wall_clock64() : 0;
-    if (!loop_barrier(lp, passed, ls)) return;            // exchange 3: the new projections
+    loop_arrive(lp, passed);                              // exchange 3: the new projections ...
+    for (int r = 0; r < n_emit; ++r) {                    // ... and, while the arrivals travel, the next step's recurrent sums
+      const int ub = ls.emit_ub[r];
+      const float v = recurrent_sums(ub);
+#pragma unroll
+      for (int b = 0; b < kLoopMaxB; ++b) rec[b] = ub == b ? v : rec[b];
+    }
+    if (!loop_wait(lp, passed, ls)) return;
     const long long t8 = dbg ? wall_clock64() : 0;
     for (int r = 0; r < n_emit; ++r) {
       const int ub = ls.emit_ub[r];
