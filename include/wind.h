@@ -189,6 +189,14 @@ int wind_beam_decode(wind_model *m, const float *enc_out, int T, int window, int
                      int32_t *out_tokens, int32_t *out_frames, int cap, int32_t *out_count, double *out_score,
                      wind_beam_stats *stats, wind_beam_round_fn on_round, void *user, void *stream);
 
+/*
+ * Device memory, in bytes, of the workspace that a decode call of this shape needs (encoder
+ * projections of every frame, window rows, keys, prediction-network state, ...).  The model owns
+ * one workspace, allocated on the first call and regrown when a later call needs more; this query
+ * lets a caller budget HBM before the call.  HOST pointer.  No GPU work.
+ */
+int wind_workspace_bytes(const wind_model *m, int B, int T, int W, size_t *bytes);
+
 /* Counters of the last decode call; HOST pointer. */
 int wind_get_stats(wind_model *m, wind_stats *out);
 

@@ -16,7 +16,7 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0
 
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
-           "wind_get_kernel_times", "wind_beam_window_scores", "wind_beam_decode")
+           "wind_get_kernel_times", "wind_beam_window_scores", "wind_beam_decode", "wind_workspace_bytes")
 PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
 
@@ -88,6 +88,7 @@ def load_library():
         lib.wind_get_kernel_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.wind_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
         lib.wind_beam_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                          C.c_void_p, C.c_void_p, C.c_int, _I32P, C.POINTER(C.c_double),
                                          C.POINTER(WindBeamStats), C.c_void_p, C.c_void_p, C.c_void_p]
@@ -176,6 +177,11 @@ class WindModel:
         self.greedy_decode(enc_out, lengths, W, S, tok, frm, cnt)
         tok, frm, cnt = tok.cpu().numpy(), frm.cpu().numpy(), cnt.cpu().numpy()
         return [tok[b, : cnt[b]] for b in range(B)], [frm[b, : cnt[b]] for b in range(B)]
+
+    def workspace_bytes(self, B: int, T: int, W: int) -> int:
+        n = C.c_size_t(0)
+        _check(self._lib.wind_workspace_bytes(self._h, int(B), int(T), int(W), C.byref(n)))
+        return int(n.value)
 
     def stats(self) -> WindStats:
         s = WindStats()

@@ -166,42 +166,68 @@ void set_tau(wind_model *m) {
   m->dev.tau_scale = (float)(m->kappa * 2.1e-3 * m->wnorm_max / std::sqrt((double)m->dev.Hj));
 }
 
-int ensure_workspace(wind_model *m, int B, int T, int W) {
+// Where everything of a decode call lives inside the one workspace slab.
+struct WsLayout {
+  size_t total, Mpad, st;
+  bool big_enc;
+  int slot_stride, nparts, nparts_big, nparts_tiny;
+  size_t o_e, o_encb, o_len, o_nact, o_eidx, o_eltok, o_slot, o_slotc, o_rst, o_raux, o_nemit, o_ticket, o_h, o_c, o_hn, o_hb,
+      o_hz, o_p, o_z, o_bl, o_zn, o_parts, o_rl, o_stats, o_dbg, o_lbar, o_lh, o_lp, o_lparts;
+};
+
+WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   const ModelDev &d = m->dev;
-  const size_t Mpad = round_up((size_t)B * W, kRowPad) + kRowPad;   // a 192-row tile may run past the 256 multiple
+  WsLayout w{};
+  w.Mpad = round_up((size_t)B * W, kRowPad) + kRowPad;   // a 192-row tile may run past the 256 multiple
   const int ntiles = (d.V + JointRows1::BN - 1) / JointRows1::BN;
-  const int nparts = ntiles * JointRows1::WAVES_N;
-  const int nparts_big = ((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN) * JointBigCfg::WAVES_N;
-  const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
+  w.nparts = ntiles * JointRows1::WAVES_N;
+  w.nparts_big = ((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN) * JointBigCfg::WAVES_N;
+  w.nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
     off += round_up(bytes, 256);
     return o;
   };
-  const size_t o_e = take((size_t)B * T * d.Hj * 4);
-  const bool big_enc = m->dtype == WIND_BF16 && (size_t)B * T >= kEncRing5MinRows;
-  const size_t o_encb = take(big_enc ? ((size_t)B * T + JointBigCfg::BM) * d.D * 2 : 0);
-  const int slot_stride = B > kTinyRows ? B : kTinyRows;
-  const size_t o_len = take((size_t)B * 4);
-  const size_t o_nact = take(8), o_eidx = take((size_t)B * 4);
-  const size_t o_eltok = take((size_t)B * 4);
-  const size_t o_slot = take((size_t)2 * slot_stride * 16), o_slotc = take((size_t)2 * slot_stride * 4);
-  const size_t o_rst = take((size_t)B * 16), o_raux = take((size_t)B * 16);
-  const size_t o_nemit = take(4), o_ticket = take(8);
-  const size_t st = (size_t)d.L * B * d.Hp * 4;
-  const size_t o_h = take(st), o_c = take(st), o_hn = take(st);
-  const size_t o_hb = take(2 * st);   // four bf16 arrays
-  const size_t o_hz = take((size_t)(d.E > d.Hp ? d.E : d.Hp) * 2 + 256);
-  const size_t o_p = take((size_t)B * d.Hj * 4);
-  const size_t o_z = take(Mpad * d.Hj * 2);
-  const size_t o_bl = take(Mpad * 4), o_zn = take(Mpad * 4);
-  const size_t o_parts = take(Mpad * (size_t)(nparts_tiny > nparts ? nparts_tiny : nparts) * 8);
-  const size_t o_rl = take(Mpad * 4);
-  const size_t o_stats = take(kNumStats * 8);
-  const size_t o_dbg = take(128);
-  const size_t o_lbar = take((size_t)(1 + 256) * kLoopFlagStride * 4), o_lh = take((size_t)kLoopMaxB * d.Hp * 4), o_lp = take((size_t)kLoopMaxB * d.Hj * 4);
-  const size_t o_lparts = take((size_t)2 * kLoopRows * nparts_tiny * 8);
+  w.o_e = take((size_t)B * T * d.Hj * 4);
+  w.big_enc = m->dtype == WIND_BF16 && (size_t)B * T >= kEncRing5MinRows;
+  w.o_encb = take(w.big_enc ? ((size_t)B * T + JointBigCfg::BM) * d.D * 2 : 0);
+  w.slot_stride = B > kTinyRows ? B : kTinyRows;
+  w.o_len = take((size_t)B * 4);
+  w.o_nact = take(8); w.o_eidx = take((size_t)B * 4);
+  w.o_eltok = take((size_t)B * 4);
+  w.o_slot = take((size_t)2 * w.slot_stride * 16); w.o_slotc = take((size_t)2 * w.slot_stride * 4);
+  w.o_rst = take((size_t)B * 16); w.o_raux = take((size_t)B * 16);
+  w.o_nemit = take(4); w.o_ticket = take(8);
+  w.st = (size_t)d.L * B * d.Hp * 4;
+  w.o_h = take(w.st); w.o_c = take(w.st); w.o_hn = take(w.st);
+  w.o_hb = take(2 * w.st);   // four bf16 arrays
+  w.o_hz = take((size_t)(d.E > d.Hp ? d.E : d.Hp) * 2 + 256);
+  w.o_p = take((size_t)B * d.Hj * 4);
+  w.o_z = take(w.Mpad * d.Hj * 2);
+  w.o_bl = take(w.Mpad * 4); w.o_zn = take(w.Mpad * 4);
+  w.o_parts = take(w.Mpad * (size_t)(w.nparts_tiny > w.nparts ? w.nparts_tiny : w.nparts) * 8);
+  w.o_rl = take(w.Mpad * 4);
+  w.o_stats = take(kNumStats * 8);
+  w.o_dbg = take(128);
+  w.o_lbar = take((size_t)(1 + 256) * kLoopFlagStride * 4); w.o_lh = take((size_t)kLoopMaxB * d.Hp * 4);
+  w.o_lp = take((size_t)kLoopMaxB * d.Hj * 4);
+  w.o_lparts = take((size_t)2 * kLoopRows * w.nparts_tiny * 8);
+  w.total = off;
+  return w;
+}
+
+int ensure_workspace(wind_model *m, int B, int T, int W) {
+  const ModelDev &d = m->dev;
+  const WsLayout w = workspace_layout(m, B, T, W);
+  const size_t off = w.total, st = w.st;
+  const bool big_enc = w.big_enc;
+  const int slot_stride = w.slot_stride, nparts = w.nparts, nparts_big = w.nparts_big, nparts_tiny = w.nparts_tiny;
+  const size_t o_e = w.o_e, o_encb = w.o_encb, o_len = w.o_len, o_nact = w.o_nact, o_eidx = w.o_eidx, o_eltok = w.o_eltok,
+               o_slot = w.o_slot, o_slotc = w.o_slotc, o_rst = w.o_rst, o_raux = w.o_raux, o_nemit = w.o_nemit,
+               o_ticket = w.o_ticket, o_h = w.o_h, o_c = w.o_c, o_hn = w.o_hn, o_hb = w.o_hb, o_hz = w.o_hz, o_p = w.o_p,
+               o_z = w.o_z, o_bl = w.o_bl, o_zn = w.o_zn, o_parts = w.o_parts, o_rl = w.o_rl, o_stats = w.o_stats,
+               o_dbg = w.o_dbg, o_lbar = w.o_lbar, o_lh = w.o_lh, o_lp = w.o_lp, o_lparts = w.o_lparts;
   if (off > m->ws_bytes) {
     HIP_TRY(hipDeviceSynchronize());
     if (m->ws) HIP_TRY(hipFree(m->ws));
@@ -740,6 +766,14 @@ int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const
   rc = check_launch("beam window scores");
   if (rc) return rc;
   HIP_TRY(hipStreamSynchronize(s));
+  return WIND_OK;
+}
+
+int wind_workspace_bytes(const wind_model *m, int B, int T, int W, size_t *bytes) {
+  if (!m || !bytes) return fail(WIND_ERR_ARG, "null argument");
+  if (B < 1 || T < 0 || W < 1 || W > WIND_MAX_WINDOW || (long long)B * T > (1ll << 31) - 1)
+    return fail(WIND_ERR_ARG, "B >= 1, T >= 0, 1 <= W <= 64, B*T < 2^31 required");
+  *bytes = workspace_layout(m, B, T, W).total;
   return WIND_OK;
 }
 

@@ -201,6 +201,24 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
+def test_workspace_query_matches_the_shapes(torch_cuda):
+    """wind_workspace_bytes: at least the buffers whose sizes the header names (fp32 encoder projections of
+    every frame, bf16 window rows), growing with every argument, and rejecting shapes out of range."""
+    from paper_2505_13765_amd.binding import WindError
+
+    cfg = wi.CONFIGS["largevocab_b128"]
+    m, _, _ = load(wi.scaled(cfg, 1, 8, 8))
+    full = m.workspace_bytes(128, 2000, 16)
+    assert full >= 128 * 2000 * cfg.Hj * 4 + 128 * 16 * cfg.Hj * 2
+    assert full < 2 * (128 * 2000 * (cfg.Hj * 4 + cfg.D * 2)) + (1 << 28)
+    assert m.workspace_bytes(64, 2000, 16) < full and m.workspace_bytes(128, 1000, 16) < full
+    assert m.workspace_bytes(128, 2000, 4) < full
+    for bad in ((0, 10, 4), (1, -1, 4), (1, 10, 0), (1, 10, 65)):
+        with pytest.raises(WindError):
+            m.workspace_bytes(*bad)
+    m.close()
+
+
 def test_resident_loop_barrier_timeout_is_an_error(torch_cuda):
     """A workgroup that waits too long at a grid barrier gives up and the call fails loudly.  The
     wait limit is set to zero polls from the host, so the condition is reached with every workgroup

@@ -49,6 +49,10 @@ def test_argument_errors_without_gpu(lib):
     assert lib.wind_sequential_decode(None, None, None, 1, 1, 1, None, None, None, 1, None) == binding.WIND_ERR_ARG
     assert lib.wind_get_stats(None, None) == binding.WIND_ERR_ARG
     assert lib.wind_set_option(None, b"graph", 1) == binding.WIND_ERR_ARG
+    n = C.c_size_t(0)
+    assert lib.wind_workspace_bytes(None, 1, 1, 1, C.byref(n)) == binding.WIND_ERR_ARG
+    assert lib.wind_beam_decode(None, None, 0, 4, 4, 2, 1, None, None, 0, None, None, None, None, None, None) == binding.WIND_ERR_ARG
+    assert lib.wind_beam_window_scores(None, None, 1, None, 1, 1, None, None, None, None) == binding.WIND_ERR_ARG
     assert lib.wind_free(None) == binding.WIND_OK
 
 
