@@ -369,7 +369,9 @@ def test_determinism_and_graph_off(torch_cuda):
 
 # ---------------------------------------------------------------------------------------------
 # Full-size workloads in the launch configuration bench.py times.  The oracle checks a sample of
-# utterances one by one; properties that hold at any size are checked on all of them.
+# utterances one by one; properties that hold at any size are checked on all of them.  With
+# WIND_FULL_PARITY=1 in the environment the oracle checks EVERY utterance (about 100 s of CPU on 16
+# threads for the four workloads together).
 FULL = [("greedy_b1", [0]), ("batch32", "sample3"), ("largevocab_b128", "sample3"), ("lowblank_b256", "sample3")]
 
 
@@ -379,6 +381,8 @@ def test_full_size_workloads(torch_cuda, name, which):
     m, o, _ = load(cfg)
     enc, lens = wi.make_batch(cfg)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    if os.environ.get("WIND_FULL_PARITY") == "1":
+        which = list(range(cfg.B))
     if which == "sample3":
         order = np.argsort(lens)
         which = [int(order[0]), int(order[len(order) // 3]), int(order[-1])]
@@ -397,8 +401,9 @@ def test_full_size_workloads(torch_cuda, name, which):
             ref = (toks, frs)
             excl = compare_batch(o, enc, lens, cfg.S, toks, frs, utterances=which, tol=TOL_GAP,
                                  threads=min(16, os.cpu_count() or 1))
-            print(f"{name}: utterances {which} checked against the oracle, excluded near-ties: {excl}")
-            assert excl <= 3
+            shown = which if len(which) <= 8 else f"all {len(which)}"
+            print(f"{name}: utterances {shown} checked against the oracle, excluded near-ties: {excl}")
+            assert excl <= 3 * max(1, len(which) // 3)
         else:
             same = sum(a.tolist() == b.tolist() and c.tolist() == d.tolist()
                        for a, b, c, d in zip(ref[0], toks, ref[1], frs))
