@@ -405,11 +405,14 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
       launch(m, s, WIND_K_JOINT, capturing, joint_kernel<JointBigCfg>, dim3((unsigned)(rows_blocks + big_mt * big_nt)),
              dim3(JointBigCfg::NT), JointBigCfg::SMEM_BYTES, d, c, parity, gx, NT, rows_blocks, big_mt, big_nt);
     }
-    launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
+    if (d.Hj <= 1024)
+      launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t, false>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
+    else
+      launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t, true>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
   } else {
     launch(m, s, WIND_K_JOINT, capturing, joint_exact_kernel<float>, dim3((unsigned)max_rows), dim3(256), (size_t)d.Hj * 4,
            d, c, parity, 1, 0, 0, 0, (const float *)nullptr, 0, (float *)nullptr, (bf16_t *)nullptr);
-    launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<float>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 1);
+    launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<float, false>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 1);
   }
   int rc = check_launch("iteration");
   if (rc) return rc;
@@ -460,6 +463,10 @@ int fetch_stats(wind_model *m, hipStream_t s) {
       std::fprintf(stderr, "[wind debug] resident loop, workgroup 0, avg us per iteration: gather %.2f  mfma+keys %.2f  barrier1 %.2f  decide %.2f | per emitting iteration: lstm %.2f  barrier2 %.2f  hcopy+pred %.2f  barrier3 %.2f  pcopy %.2f  (%lld iterations, %lld emitting)\n",
                    d[0] / 100.0 / d[10], d[1] / 100.0 / d[10], d[2] / 100.0 / d[10], d[3] / 100.0 / d[10], d[4] / 100.0 / (d[11] ? d[11] : 1),
                    d[5] / 100.0 / (d[11] ? d[11] : 1), d[6] / 100.0 / (d[11] ? d[11] : 1), d[7] / 100.0 / (d[11] ? d[11] : 1), d[8] / 100.0 / (d[11] ? d[11] : 1), d[10], d[11]);
+    else if (d[3] > 0 && d[10] == 0 && d[8] == 0)
+      std::fprintf(stderr, "[wind debug] decide kernel, last workgroup avg us: rows %.2f  ticket %.2f  compaction %.2f (%lld launches); rows phase of workgroups with a near-tie %.2f (%lld), without %.2f (%lld)\n",
+                   d[0] / 100.0 / d[3], d[1] / 100.0 / d[3], d[2] / 100.0 / d[3], d[3], d[4] / 100.0 / (d[5] ? d[5] : 1), d[5],
+                   d[6] / 100.0 / (d[7] ? d[7] : 1), d[7]);
     else if (d[5] > 0)
       std::fprintf(stderr, "[wind debug] few-rows kernel, deciding workgroup, avg us: setup+gather %.2f  mfma+keys %.2f  hand-over %.2f  decide %.2f  compact %.2f  (%lld launches)\n",
                    d[0] / 100.0 / d[5], d[1] / 100.0 / d[5], d[2] / 100.0 / d[5], d[3] / 100.0 / d[5], d[4] / 100.0 / d[5], d[5]);
@@ -687,7 +694,7 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)tiny_smem_bytes(m->dev, 64));
+                              m->dev.Hj <= kTinyMaxHj ? (int)tiny_smem_bytes(m->dev, 64) : 32768);   // unused above that size
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)wind_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 154 * 1024);
     if (e == hipSuccess)

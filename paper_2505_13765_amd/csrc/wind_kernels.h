@@ -430,7 +430,7 @@ __global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int p
   if ((int)blockIdx.x < rows_blocks) {
     if (n_rows > c.joint_split_rows || threadIdx.x >= 256) return;
     joint_tile_of_block((int)blockIdx.x, rows_gx, rows_nt, mt, nt);
-    if (mt >= rows_gx) return;   // padding of the group to a multiple of 8
+    if (mt >= rows_gx || nt >= rows_nt) return;   // padding of the group to a multiple of 8 (either mapping)
     const int mi = (n_rows + 64 * rows_gx - 1) / (64 * rows_gx);   // <= 4 by the host's choice of rows_gx
     switch (mi) {
       case 1: joint_rows_tile<1>(m, c, n_rows, mt, nt, smem_raw); break;
@@ -557,7 +557,7 @@ __global__ __launch_bounds__(256) void joint_exact_kernel(ModelDev m, CallDev c,
 // 128*i .. +1]).  Four weight rows are requested together, so that a near-tie costs one memory
 // round trip for up to four candidates.
 template <class WT, int NZ>
-__device__ __forceinline__ void evaluate_candidates(const ModelDev &m, const float2 (&zr)[NZ], int mycol, int nc,
+__device__ __forceinline__ void evaluate_candidates_wide(const ModelDev &m, const float2 (&zr)[NZ], int mycol, int nc,
                                                     int lane, float &bestv, int &besti) {
   const WT *w = reinterpret_cast<const WT *>(m.w_out);
   for (int c0 = 0; c0 < nc; c0 += 4) {
@@ -586,6 +586,48 @@ __device__ __forceinline__ void evaluate_candidates(const ModelDev &m, const flo
   }
 }
 
+template <int NZ>
+__device__ __forceinline__ void evaluate_candidates(const ModelDev &m, const float2 (&ev)[NZ], const float2 (&pv)[NZ],
+                                                    int mycol, int nc, int lane, float &bestv, int &besti) {
+  // ev holds the row's encoder projections e and pv its prediction projections p, as requested by
+  // the caller and not yet looked at; they are combined into z = relu(e + p) only behind the
+  // round's weight requests, so that both requests are in flight together: a near-tie then costs
+  // one trip to memory, not two.  Weights stay packed (two bf16 per register) until used.
+  const bf16_t *w = reinterpret_cast<const bf16_t *>(m.w_out);
+  for (int c0 = 0; c0 < nc; c0 += 4) {
+    const int col0 = __shfl(mycol, c0, kWave), col1 = __shfl(mycol, min(c0 + 1, nc - 1), kWave);
+    const int col2 = __shfl(mycol, min(c0 + 2, nc - 1), kWave), col3 = __shfl(mycol, min(c0 + 3, nc - 1), kWave);
+    const bf16_t *w0 = w + (size_t)col0 * m.Hj, *w1 = w + (size_t)col1 * m.Hj;
+    const bf16_t *w2 = w + (size_t)col2 * m.Hj, *w3 = w + (size_t)col3 * m.Hj;
+    const float o0 = m.b_out[col0], o1 = m.b_out[col1], o2 = m.b_out[col2], o3 = m.b_out[col3];
+    uint32_t x0[NZ], x1[NZ], x2[NZ], x3[NZ];
+#pragma unroll
+    for (int i = 0; i < NZ; ++i) {
+      const int k = 2 * lane + 128 * i;
+      x0[i] = x1[i] = x2[i] = x3[i] = 0u;
+      if (k < m.Hj) {
+        x0[i] = *reinterpret_cast<const uint32_t *>(w0 + k); x1[i] = *reinterpret_cast<const uint32_t *>(w1 + k);
+        x2[i] = *reinterpret_cast<const uint32_t *>(w2 + k); x3[i] = *reinterpret_cast<const uint32_t *>(w3 + k);
+      }
+    }
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NZ; ++i) {
+      const float zx = fmaxf(ev[i].x + pv[i].x, 0.f), zy = fmaxf(ev[i].y + pv[i].y, 0.f);
+      a0 = fmaf(__uint_as_float(x0[i] << 16), zx, a0); a0 = fmaf(__uint_as_float(x0[i] & 0xFFFF0000u), zy, a0);
+      a1 = fmaf(__uint_as_float(x1[i] << 16), zx, a1); a1 = fmaf(__uint_as_float(x1[i] & 0xFFFF0000u), zy, a1);
+      a2 = fmaf(__uint_as_float(x2[i] << 16), zx, a2); a2 = fmaf(__uint_as_float(x2[i] & 0xFFFF0000u), zy, a2);
+      a3 = fmaf(__uint_as_float(x3[i] << 16), zx, a3); a3 = fmaf(__uint_as_float(x3[i] & 0xFFFF0000u), zy, a3);
+    }
+    const float v0 = wave_sum(a0) + o0, v1 = wave_sum(a1) + o1;
+    const float v2 = wave_sum(a2) + o2, v3 = wave_sum(a3) + o3;
+    if (v0 > bestv || (v0 == bestv && col0 < besti)) { bestv = v0; besti = col0; }
+    if (v1 > bestv || (v1 == bestv && col1 < besti)) { bestv = v1; besti = col1; }
+    if (v2 > bestv || (v2 == bestv && col2 < besti)) { bestv = v2; besti = col2; }
+    if (v3 > bestv || (v3 == bestv && col3 < besti)) { bestv = v3; besti = col3; }
+  }
+}
+
 constexpr int kDecideMaxHj = 2048;  // exact_logit keeps Hj/128 float2 per lane
 
 struct DecideShared {
@@ -603,40 +645,64 @@ struct DecideShared {
   float blank[kTinyRows], znorm[kTinyRows];
 };
 
-// Label of one window row, decided by a whole wave: argmax over the row's keys, with every key
-// inside the near-tie band re-evaluated in fp32 (see the header comment of this file).
-// kk0 = this lane's keys of the row for part `lane` (the caller loads them, possibly for several
-// rows at once so that the loads overlap); parts 64 and up are read here.
-template <class WT>
-__device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
-                                          int nparts, int stride, int part_width, float vblank, float znorm,
-                                          float2 kk0, int &n_recheck) {
+// The near-tie path of decide_row: every label key at or above `thresh` is re-evaluated in fp32 (bf16
+// weight row times the hidden vector rebuilt from fp32 e and p) and the argmax over those values and
+// the fp32 blank logit is returned.  NZ = Hj / 128 rounded up: the lanes hold two hidden units per step.
+template <int NZ>
+__device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, int row, int b, int frame, int nparts,
+                                           int stride, int part_width, float vblank, float thresh, float2 kk0) {
   const int lane = threadIdx.x & 63, V = m.V;
   const float2 *prow = c.parts + (size_t)row * stride;
-  float k1 = kk0.x;
-  for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, prow[pi].x);
-  const float kbest = wave_max_f32(k1);
-  const float vbest = key_val(kbest);
-  const float top = fmaxf(vbest, vblank);
-  const float tau = m.tau_scale * znorm + 6.2e-5f * fabsf(top);
-  const float thresh = top - tau;
-  if (vbest < thresh) return V;                  // blank clear of every label
-  // how many label keys are inside the band?
-  int cnt = (key_val(kk0.x) >= thresh) + (key_val(kk0.y) >= thresh);
-  for (int pi = lane + 64; pi < nparts; pi += 64) {
-    const float2 kk = prow[pi];
-    cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
+  float2 ev[NZ], pv[NZ];   // requested here, first looked at behind the weight rows' requests
+  const float *er = c.e + ((size_t)b * c.T + frame) * m.Hj;
+  const float *pr = c.p + (size_t)b * m.Hj;
+#pragma unroll
+  for (int i = 0; i < NZ; ++i) {
+    const int k = 2 * lane + 128 * i;
+    ev[i] = make_float2(0.f, 0.f);
+    pv[i] = make_float2(0.f, 0.f);
+    if (k < m.Hj) {
+      ev[i] = *reinterpret_cast<const float2 *>(er + k);
+      pv[i] = *reinterpret_cast<const float2 *>(pr + k);
+    }
   }
-  cnt = wave_sum_i32(cnt);
-  if (cnt == 1 && vblank < thresh) {
-    // a single label clear of blank and of every other label: find its part
-    int col = kk0.x == kbest ? lane * part_width + key_col(kbest) : -1;
-    for (int pi = lane + 64; pi < nparts; pi += 64)
-      if (prow[pi].x == kbest) col = pi * part_width + key_col(kbest);
-    return wave_max_i32(col);
+  float bestv = vblank;     // blank has the highest id: it wins only if strictly larger
+  int besti = V;
+  // candidate columns, one per lane (lane i holds the i-th), evaluated four at a time
+  int mycol = 0, nc = 0;
+  for (int p0 = 0; p0 < nparts; p0 += 64) {
+    const int pi = p0 + lane;
+    float2 kk = make_float2(kKeyNone, kKeyNone);
+    if (p0 == 0) kk = kk0;
+    else if (pi < nparts) kk = prow[pi];
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      const float key = which ? kk.y : kk.x;
+      unsigned long long mask = __ballot(key_val(key) >= thresh);
+      while (mask) {
+        const int src = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        const float skey = __shfl(key, src, kWave);
+        const int col = (p0 + src) * part_width + key_col(skey);
+        if (lane == nc) mycol = col;
+        if (++nc == 64) {
+          evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bestv, besti);
+          nc = 0;
+        }
+      }
+    }
   }
-  // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
-  ++n_recheck;
+  evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bestv, besti);
+  return besti;
+}
+
+// The same for joint hidden sizes above 1024 (up to kDecideMaxHj): the hidden vector is combined
+// first and the weight rows are requested afterwards, which keeps the live registers within a
+// 1024-thread workgroup's share.
+__device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev &c, int row, int b, int frame, int nparts,
+                                                int stride, int part_width, float vblank, float thresh, float2 kk0) {
+  const int lane = threadIdx.x & 63, V = m.V;
+  const float2 *prow = c.parts + (size_t)row * stride;
   constexpr int NZ = kDecideMaxHj / 128;
   float2 zr[NZ];
   const float *er = c.e + ((size_t)b * c.T + frame) * m.Hj;
@@ -671,14 +737,52 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
         const int col = (p0 + src) * part_width + key_col(skey);
         if (lane == nc) mycol = col;
         if (++nc == 64) {
-          evaluate_candidates<WT, NZ>(m, zr, mycol, nc, lane, bestv, besti);
+          evaluate_candidates_wide<bf16_t, NZ>(m, zr, mycol, nc, lane, bestv, besti);
           nc = 0;
         }
       }
     }
   }
-  evaluate_candidates<WT, NZ>(m, zr, mycol, nc, lane, bestv, besti);
+  evaluate_candidates_wide<bf16_t, NZ>(m, zr, mycol, nc, lane, bestv, besti);
   return besti;
+}
+
+// Label of one window row, decided by a whole wave: argmax over the row's keys, with every key
+// inside the near-tie band re-evaluated in fp32 (see the header comment of this file).
+// kk0 = this lane's keys of the row for part `lane` (the caller loads them, possibly for several
+// rows at once so that the loads overlap); parts 64 and up are read here.
+template <class WT, bool WIDE>
+__device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
+                                          int nparts, int stride, int part_width, float vblank, float znorm,
+                                          float2 kk0, int &n_recheck) {
+  const int lane = threadIdx.x & 63, V = m.V;
+  const float2 *prow = c.parts + (size_t)row * stride;
+  float k1 = kk0.x;
+  for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, prow[pi].x);
+  const float kbest = wave_max_f32(k1);
+  const float vbest = key_val(kbest);
+  const float top = fmaxf(vbest, vblank);
+  const float tau = m.tau_scale * znorm + 6.2e-5f * fabsf(top);
+  const float thresh = top - tau;
+  if (vbest < thresh) return V;                  // blank clear of every label
+  // how many label keys are inside the band?
+  int cnt = (key_val(kk0.x) >= thresh) + (key_val(kk0.y) >= thresh);
+  for (int pi = lane + 64; pi < nparts; pi += 64) {
+    const float2 kk = prow[pi];
+    cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
+  }
+  cnt = wave_sum_i32(cnt);
+  if (cnt == 1 && vblank < thresh) {
+    // a single label clear of blank and of every other label: find its part
+    int col = kk0.x == kbest ? lane * part_width + key_col(kbest) : -1;
+    for (int pi = lane + 64; pi < nparts; pi += 64)
+      if (prow[pi].x == kbest) col = pi * part_width + key_col(kbest);
+    return wave_max_i32(col);
+  }
+  // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
+  ++n_recheck;
+  if constexpr (WIDE) return recheck_row_wide(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0);
+  else return recheck_row<8>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0);
 }
 
 // Keys and row scalars of the first rows a wave decides, requested before anything else is known
@@ -694,7 +798,7 @@ struct RowsAhead {
 // waves), then the first non-blank row by ballot and the pointer / hypothesis update of
 // Algorithm 2.  nparts key pairs per row are valid, rows are `stride` pairs apart.  Ends with a
 // workgroup barrier.
-template <class WT, bool LOCAL>
+template <class WT, bool LOCAL, bool WIDE = false>
 __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int a, int4 st, int cnt,
                                                  int exact_mode, int nparts, int stride, int part_width,
                                                  const RowsAhead &ahead, DecideShared &sh, bool write_out = true) {
@@ -712,7 +816,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
         label = c.row_label[row];
       } else {
         if (exact_mode) label = c.row_label[row];
-        else label = decide_row<WT>(m, c, row, b, t + j, nparts, stride, part_width, vb, zn,
+        else label = decide_row<WT, WIDE>(m, c, row, b, t + j, nparts, stride, part_width, vb, zn,
                                     lane < nparts ? k0 : make_float2(kKeyNone, kKeyNone), n_recheck);
       }
     }
@@ -793,61 +897,76 @@ __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int 
   int *dst_count = c.slot_count + (parity ^ 1) * c.slot_stride;
   int n_act = 0, n_em = 0;
   unsigned sum_rows = 0, sum_useful = 0, sum_recheck = 0, sum_labels = 0, sum_forced = 0, sum_over = 0;
-  for (int base = 0; base < na; base += 64) {
-    const int idx = base + lane;
-    int4 st = make_int4(0, 0, 0, 0);
-    int f = 0, cnt = 0, tok = 0;
-    if (idx < na) {
-      unsigned ev;
-      if (LOCAL) {
-        st = sh.slot[idx]; cnt = sh.cnt[idx]; f = sh.flag[idx]; tok = sh.tok[idx]; ev = sh.event[idx];
-      } else {
-        st = c.res_state[idx];
-        const int4 aux = c.res_aux[idx];
-        cnt = aux.x; f = aux.y; tok = aux.z; ev = (unsigned)aux.w;
+  // The slots' outcomes were written by other workgroups and come from the memory side: the reads of
+  // two rounds of 64 slots go out together, so that they share one round trip.
+  for (int base = 0; base < na; base += 128) {
+    const int idx0 = base + lane, idx1 = base + 64 + lane;
+    int4 st0 = make_int4(0, 0, 0, 0), st1 = st0, aux0 = st0, aux1 = st0;
+    if (!LOCAL) {
+      if (idx0 < na) { st0 = c.res_state[idx0]; aux0 = c.res_aux[idx0]; }
+      if (idx1 < na) { st1 = c.res_state[idx1]; aux1 = c.res_aux[idx1]; }
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int idx = q ? idx1 : idx0;
+      int4 st = q ? st1 : st0;
+      const int4 aux = q ? aux1 : aux0;
+      int f = 0, cnt = 0, tok = 0;
+      if (idx < na) {
+        unsigned ev;
+        if (LOCAL) {
+          st = sh.slot[idx]; cnt = sh.cnt[idx]; f = sh.flag[idx]; tok = sh.tok[idx]; ev = sh.event[idx];
+        } else {
+          cnt = aux.x; f = aux.y; tok = aux.z; ev = (unsigned)aux.w;
+        }
+        sum_rows += ev & 127u; sum_useful += (ev >> 7) & 127u; sum_recheck += (ev >> 21) & 127u;
+        sum_labels += (ev >> 28) & 1u; sum_forced += (ev >> 29) & 1u; sum_over += (ev >> 30) & 1u;
+        atomicAdd(&sh.hist[(ev >> 14) & 127u], 1u);
       }
-      sum_rows += ev & 127u; sum_useful += (ev >> 7) & 127u; sum_recheck += (ev >> 21) & 127u;
-      sum_labels += (ev >> 28) & 1u; sum_forced += (ev >> 29) & 1u; sum_over += (ev >> 30) & 1u;
-      atomicAdd(&sh.hist[(ev >> 14) & 127u], 1u);
+      const unsigned long long ma = __ballot(f & 1), me = __ballot((f >> 1) & 1);
+      const unsigned long long below = (1ull << lane) - 1ull;
+      if (f & 1) {
+        const int pos = n_act + __popcll(ma & below);
+        dst_state[pos] = st;
+        dst_count[pos] = cnt;
+      }
+      if (f & 2) {
+        const int pos = n_em + __popcll(me & below);
+        c.emit_idx[pos] = st.x;
+        c.emit_list_tok[pos] = tok;
+      }
+      n_act += __popcll(ma);
+      n_em += __popcll(me);
     }
-    const unsigned long long ma = __ballot(f & 1), me = __ballot((f >> 1) & 1);
-    const unsigned long long below = (1ull << lane) - 1ull;
-    if (f & 1) {
-      const int pos = n_act + __popcll(ma & below);
-      dst_state[pos] = st;
-      dst_count[pos] = cnt;
-    }
-    if (f & 2) {
-      const int pos = n_em + __popcll(me & below);
-      c.emit_idx[pos] = st.x;
-      c.emit_list_tok[pos] = tok;
-    }
-    n_act += __popcll(ma);
-    n_em += __popcll(me);
   }
   sum_rows = (unsigned)wave_sum_i32((int)sum_rows); sum_useful = (unsigned)wave_sum_i32((int)sum_useful);
   sum_recheck = (unsigned)wave_sum_i32((int)sum_recheck); sum_labels = (unsigned)wave_sum_i32((int)sum_labels);
   sum_forced = (unsigned)wave_sum_i32((int)sum_forced); sum_over = (unsigned)wave_sum_i32((int)sum_over);
-  // one writer per iteration, iterations are ordered on the stream: plain read-modify-write
+  // counters: additions that return nothing, so that the kernel's end does not wait for a read first
   for (int j = lane; j <= kMaxWindow; j += 64)
-    if (sh.hist[j]) c.stats[kStatJump0 + j] += sh.hist[j];
+    if (sh.hist[j]) atomicAdd(&c.stats[kStatJump0 + j], (unsigned long long)sh.hist[j]);
   if (lane == 0) {
     c.n_active[parity ^ 1] = n_act;
     *c.n_emit = n_em;
     *c.ticket = 0u;
-    c.stats[ST_ITER] += 1ull; c.stats[ST_WINDOWS] += (unsigned long long)na;
-    c.stats[ST_ROWS] += sum_rows; c.stats[ST_USEFUL] += sum_useful; c.stats[ST_RECHECK] += sum_recheck;
-    c.stats[ST_LABELS] += sum_labels; c.stats[ST_FORCED] += sum_forced; c.stats[ST_OVERFLOW] += sum_over;
+    atomicAdd(&c.stats[ST_ITER], 1ull); atomicAdd(&c.stats[ST_WINDOWS], (unsigned long long)na);
+    atomicAdd(&c.stats[ST_ROWS], (unsigned long long)sum_rows); atomicAdd(&c.stats[ST_USEFUL], (unsigned long long)sum_useful);
+    if (sum_recheck) atomicAdd(&c.stats[ST_RECHECK], (unsigned long long)sum_recheck);
+    if (sum_labels) atomicAdd(&c.stats[ST_LABELS], (unsigned long long)sum_labels);
+    if (sum_forced) atomicAdd(&c.stats[ST_FORCED], (unsigned long long)sum_forced);
+    if (sum_over) atomicAdd(&c.stats[ST_OVERFLOW], (unsigned long long)sum_over);
   }
 }
 
 // Row argmax, first non-blank by ballot, pointer and hypothesis update, list compaction.
 // One workgroup per active utterance; the last workgroup to finish rebuilds the lists.
-template <class WT>
+// WIDE: joint hidden sizes above 1024 (the near-tie path then keeps the hidden vector in more registers).
+template <class WT, bool WIDE>
 __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int parity, int exact_mode) {
   __shared__ DecideShared sh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int a = blockIdx.x;
+  const long long ts0 = c.dbg ? wall_clock64() : 0;   // option "debug_stamps": where a launch's time goes
   // one round trip: the active count, this slot's state, and the keys / blank logit / norm of the
   // rows this wave decides (their addresses depend on the slot number only)
   const int na = c.n_active[parity];
@@ -872,8 +991,13 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   // which joint kernel wrote the keys: both use rows c.nparts pairs apart, the 256 x 256 kernel
   // fills fewer, wider parts
   const bool big = na * c.W > c.joint_split_rows;
-  decide_utterance<WT, false>(m, c, a, st, cnt, exact_mode, big ? c.nparts_big : c.nparts, c.nparts,
+  decide_utterance<WT, false, WIDE>(m, c, a, st, cnt, exact_mode, big ? c.nparts_big : c.nparts, c.nparts,
                               big ? c.part_width_big : c.part_width, ahead, sh);
+  const long long ts1 = c.dbg ? wall_clock64() : 0;
+  if (c.dbg && threadIdx.x == 0) {   // rows phase of workgroups with / without a near-tie
+    atomicAdd((unsigned long long *)&c.dbg[sh.recheck ? 4 : 6], (unsigned long long)(ts1 - ts0));
+    atomicAdd((unsigned long long *)&c.dbg[sh.recheck ? 5 : 7], 1ull);
+  }
   if (threadIdx.x == 0) {
     __threadfence();
     const unsigned tk = atomicAdd(c.ticket, 1u);
@@ -881,8 +1005,13 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   }
   __syncthreads();
   if (!sh.is_last) return;
+  const long long ts2 = c.dbg ? wall_clock64() : 0;
   __threadfence();
   if (threadIdx.x < 64) compact_lists<false>(c, parity, na, sh);
+  if (c.dbg && threadIdx.x == 0) {
+    const long long ts3 = wall_clock64();
+    c.dbg[0] += ts1 - ts0; c.dbg[1] += ts2 - ts1; c.dbg[2] += ts3 - ts2; c.dbg[3] += 1;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------

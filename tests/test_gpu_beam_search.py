@@ -111,6 +111,24 @@ def test_bf16_models_replay(torch_cuda, name, T, N, K, S, exact, gain):
     m.close()
 
 
+@pytest.mark.parametrize("Hj,V,exact", [(640, 300, 1), (1088, 77, 1), (1088, 300, 0)])
+def test_unusual_shapes_bf16_replay(torch_cuda, Hj, V, exact):
+    """bf16 models with vocabularies that are not a multiple of the column tiles, small D, E, Hp, and a
+    joint hidden size above 1024 (logits then come from the 128 x 128 tile kernel)."""
+    from paper_2505_13765_amd import WindModel
+
+    cfg = wi.WindConfig("odd_beam", 12, 1, 18, 18, 64, 64, 1, 64, Hj, V, "bf16", (8,), 3, 0.7)
+    w = wi.sharpened(wi.make_weights(cfg, blank_bias=2.0, pred_gain=4.0), 4.0)
+    o = oracle.Oracle.from_config(cfg, w)
+    m = WindModel.from_config(cfg, w)
+    m.set_option("beam_exact", exact)
+    enc, _ = wi.make_batch(cfg)
+    stats = replay(o, m, torch_cuda, np.ascontiguousarray(enc[0]), 8, 4, cfg.S, "keep", (2e-4 if exact else 4e-2) * 4,
+                   free_run=False)
+    print(f"odd shapes Hj={Hj} V={V} exact={exact}: {stats}")
+    m.close()
+
+
 def test_beam_one_window_one_is_the_greedy_decoder(torch_cuda):
     # K = 1, N = 1: the best pair of every pass is the frame's argmax, so the search must return what
     # wind_sequential_decode returns (fp32 model: both take their decisions on fp32 logits).

@@ -201,6 +201,35 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
+@pytest.mark.parametrize("Hj,Hp,V,B", [(1088, 64, 300, 20), (2048, 128, 77, 17), (640, 64, 300, 20), (640, 128, 1500, 1),
+                                       (1024, 64, 200, 3), (640, 64, 300, 2)])
+def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B):
+    """bf16 models away from the workloads' shapes: vocabularies whose column tiles are not a multiple of
+    eight (the tile-to-workgroup mapping then takes its other form, and the padded workgroups must
+    stay out), small D, E and Hp, joint hidden sizes above 1024 (the other variant of the near-tie
+    path, none of the few-rows kernels), on every route: rows tiles, 256 x 256 tiles, the few-rows
+    kernel, the resident loop kernel."""
+    cfg = wi.WindConfig("odd", 11, B, 20, 70, 64, 64, 1, Hp, Hj, V, "bf16", (8,), 4, 0.7)
+    w = wi.make_weights(cfg, blank_bias=2.0, pred_gain=4.0)
+    m, o, _ = load(cfg, w)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    first = None
+    for W, split in ((8, None), (2, None), (16, 0)):
+        if split is not None:
+            m.set_option("joint_split_rows", split)
+        toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        check_outputs(cfg, lens, toks, frs)
+        assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 2
+        st = m.stats()
+        assert st.labels == sum(len(t) for t in toks) > 0
+        if first is None:
+            first = toks
+        else:
+            assert all(a.tolist() == b.tolist() for a, b in zip(first, toks))
+    m.close()
+
+
 def test_workspace_query_matches_the_shapes(torch_cuda):
     """wind_workspace_bytes: at least the buffers whose sizes the header names (fp32 encoder projections of
     every frame, bf16 window rows), growing with every argument, and rejecting shapes out of range."""
