@@ -254,8 +254,8 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "beam_exact"  1: the beam-search entry points evaluate bf16 models' joiner rows with an fp32
  *             hidden vector and fp32 FMA instead of the bf16 MFMA pass, so that their choices do
  *             not depend on the rounding of the hidden vector (default 0)
- *   "debug_stamps"  1: the few-rows kernels record phase time stamps, which the next decode
- *             prints to stderr (development aid; default 0)
+ *   "debug_stamps"  1: the few-rows kernels, the resident loop kernel and the decision kernel record
+ *             phase time stamps, which the next decode prints to stderr (development aid; default 0)
  */
 int wind_set_option(wind_model *m, const char *key, int64_t value);
 
