@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <exception>
 #include <map>
 #include <string>
 #include <unordered_map>
@@ -580,7 +581,8 @@ extern "C" {
 
 const char *wind_last_error(void) { return g_err.c_str(); }
 
-int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
+// The host-side conversion of the weights uses standard containers; nothing they throw may cross the C boundary.
+int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try {
   (void)stream;
   if (!w || !out) return fail(WIND_ERR_ARG, "null argument");
   *out = nullptr;
@@ -725,6 +727,8 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) {
   }
   *out = m;
   return WIND_OK;
+} catch (const std::exception &e) {
+  return fail(WIND_ERR_HIP, std::string("wind_load_weights: ") + e.what());
 }
 
 int wind_free(wind_model *m) {

@@ -187,11 +187,9 @@ double beam_logaddexp(double a, double b) {
   return mx + std::log(std::exp(a - mx) + std::exp(b - mx));
 }
 
-}  // namespace
-
-extern "C" int wind_beam_decode(wind_model *m, const float *enc_out, int T, int window, int K, int S, int prefix_mode,
-                                int32_t *out_tokens, int32_t *out_frames, int cap, int32_t *out_count, double *out_score,
-                                wind_beam_stats *stats, wind_beam_round_fn on_round, void *user, void *stream) {
+int beam_decode(wind_model *m, const float *enc_out, int T, int window, int K, int S, int prefix_mode, int32_t *out_tokens,
+                int32_t *out_frames, int cap, int32_t *out_count, double *out_score, wind_beam_stats *stats,
+                wind_beam_round_fn on_round, void *user, void *stream) {
   if (!m || (!enc_out && T > 0) || !out_tokens || !out_frames || !out_count || !out_score)
     return fail(WIND_ERR_ARG, "null argument");
   if (T < 0 || cap < 0) return fail(WIND_ERR_ARG, "T and cap must not be negative");
@@ -475,4 +473,20 @@ extern "C" int wind_beam_decode(wind_model *m, const float *enc_out, int T, int 
   if ((int)best_tok.size() > cap) return fail(WIND_ERR_OVERFLOW, "the best hypothesis has more labels than cap");
   for (size_t i = 0; i < best_tok.size(); ++i) { out_tokens[i] = best_tok[i]; out_frames[i] = fin[best].frames[i]; }
   return WIND_OK;
+}
+
+}  // namespace
+
+// The search keeps its hypotheses in standard containers; nothing they throw may cross the C boundary.
+extern "C" int wind_beam_decode(wind_model *m, const float *enc_out, int T, int window, int K, int S, int prefix_mode,
+                                int32_t *out_tokens, int32_t *out_frames, int cap, int32_t *out_count, double *out_score,
+                                wind_beam_stats *stats, wind_beam_round_fn on_round, void *user, void *stream) {
+  try {
+    return beam_decode(m, enc_out, T, window, K, S, prefix_mode, out_tokens, out_frames, cap, out_count, out_score, stats,
+                       on_round, user, stream);
+  } catch (const std::exception &e) {
+    return fail(WIND_ERR_HIP, std::string("beam search: ") + e.what());
+  } catch (...) {
+    return fail(WIND_ERR_HIP, "beam search: unknown exception");
+  }
 }
