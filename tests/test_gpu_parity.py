@@ -201,15 +201,17 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
-@pytest.mark.parametrize("Hj,Hp,V,B", [(1088, 64, 300, 20), (2048, 128, 77, 17), (640, 64, 300, 20), (640, 128, 1500, 1),
-                                       (1024, 64, 200, 3), (640, 64, 300, 2)])
-def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B):
+@pytest.mark.parametrize("Hj,Hp,V,B,lo,hi", [(1088, 64, 300, 20, 20, 70), (2048, 128, 77, 17, 20, 70), (640, 64, 300, 20, 20, 70),
+                                             (640, 128, 1500, 1, 20, 70), (1024, 64, 200, 3, 20, 70), (640, 64, 300, 2, 20, 70),
+                                             (1088, 64, 300, 72, 200, 240)])
+def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     """bf16 models away from the workloads' shapes: vocabularies whose column tiles are not a multiple of
     eight (the tile-to-workgroup mapping then takes its other form, and the padded workgroups must
     stay out), small D, E and Hp, joint hidden sizes above 1024 (the other variant of the near-tie
     path, none of the few-rows kernels), on every route: rows tiles, 256 x 256 tiles, the few-rows
-    kernel, the resident loop kernel."""
-    cfg = wi.WindConfig("odd", 11, B, 20, 70, 64, 64, 1, Hp, Hj, V, "bf16", (8,), 4, 0.7)
+    kernel, the resident loop kernel; the last case is large enough (B * T >= 16384) for the encoder
+    projection's 256 x 256 tiles."""
+    cfg = wi.WindConfig("odd", 11, B, lo, hi, 64, 64, 1, Hp, Hj, V, "bf16", (8,), 4, 0.7)
     w = wi.make_weights(cfg, blank_bias=2.0, pred_gain=4.0)
     m, o, _ = load(cfg, w)
     enc, lens = wi.make_batch(cfg)
@@ -220,13 +222,16 @@ def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B):
             m.set_option("joint_split_rows", split)
         toks, frs = m.decode(d_enc, d_len, W, cfg.S)
         check_outputs(cfg, lens, toks, frs)
-        assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 2
+        excl = compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP)
+        print(f"unusual shapes Hj={Hj} Hp={Hp} V={V} B={B} W={W}: near-tie exclusions {excl}")
+        assert excl <= 2 + int(lens.sum()) // 4000
         st = m.stats()
         assert st.labels == sum(len(t) for t in toks) > 0
-        if first is None:
-            first = toks
-        else:
-            assert all(a.tolist() == b.tolist() for a, b in zip(first, toks))
+        if excl == 0:   # a near-tie may legitimately fall either way, and differently from window to window
+            if first is None:
+                first = toks
+            else:
+                assert all(a.tolist() == b.tolist() for a, b in zip(first, toks))
     m.close()
 
 
