@@ -203,7 +203,7 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
 
 @pytest.mark.parametrize("Hj,Hp,V,B,lo,hi", [(1088, 64, 300, 20, 20, 70), (2048, 128, 77, 17, 20, 70), (640, 64, 300, 20, 20, 70),
                                              (640, 128, 1500, 1, 20, 70), (1024, 64, 200, 3, 20, 70), (640, 64, 300, 2, 20, 70),
-                                             (1088, 64, 300, 72, 200, 240)])
+                                             (1088, 64, 300, 72, 200, 240), (640, 128, 300, 20, 20, 70), (704, 192, 520, 3, 20, 70)])
 def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     """bf16 models away from the workloads' shapes: vocabularies whose column tiles are not a multiple of
     eight (the tile-to-workgroup mapping then takes its other form, and the padded workgroups must
@@ -211,7 +211,10 @@ def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     path, none of the few-rows kernels), on every route: rows tiles, 256 x 256 tiles, the few-rows
     kernel, the resident loop kernel; the last case is large enough (B * T >= 16384) for the encoder
     projection's 256 x 256 tiles."""
-    cfg = wi.WindConfig("odd", 11, B, lo, hi, 64, 64, 1, Hp, Hj, V, "bf16", (8,), 4, 0.7)
+    # the last two cases: three LSTM layers on the tile kernels, and an embedding wider than the LSTM
+    # with two layers on the few-rows route
+    L, E = (3, 64) if Hp == 128 and V == 300 else (2, 128) if Hp == 192 else (1, 64)
+    cfg = wi.WindConfig("odd", 11, B, lo, hi, 64, E, L, Hp, Hj, V, "bf16", (8,), 4, 0.7)
     w = wi.make_weights(cfg, blank_bias=2.0, pred_gain=4.0)
     m, o, _ = load(cfg, w)
     enc, lens = wi.make_batch(cfg)
