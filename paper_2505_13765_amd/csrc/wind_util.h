@@ -15,16 +15,17 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kWave = 64;
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN-ish, never used for a decision)
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
-  uint32_t u = __float_as_uint(x);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+// fp32 -> bf16, round to nearest even, two values per instruction: gfx950 converts in hardware
+// (v_cvt_pk_bf16_f32), with the same result as the usual integer sequence u + 0x7FFF + ((u >> 16) & 1)
+// on every finite input, ties and denormals included (checked on the device over 2 M values).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) { return pack_bf16x2(x, 0.f) & 0xFFFFu; }
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // load one weight element as fp32
 __device__ __forceinline__ float ldw(const float *p, size_t i) { return p[i]; }
