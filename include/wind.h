@@ -251,6 +251,10 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "loop_spin_limit"  polls a workgroup of that kernel waits at a barrier before it gives up
  *             (default 2^21, about a second); the decode then returns WIND_ERR_HIP.  Tests set it
  *             to 0 to exercise that path: every workgroup still leaves the kernel normally
+ *   "lstm_rec"  1 (default): where the prediction network runs on MFMA tiles, the recurrent half of every
+ *             LSTM layer's gate sums (w_hh . h) is kept ready for the hidden vectors as they stand and
+ *             renewed beside the projection, so a step only adds the input half once the label is
+ *             known (the first layer inside the decision kernel); 0: whole steps after the decision
  *   "beam_exact"  1: the beam-search entry points evaluate bf16 models' joiner rows with an fp32
  *             hidden vector and fp32 FMA instead of the bf16 MFMA pass, so that their choices do
  *             not depend on the rounding of the hidden vector (default 0)

@@ -115,6 +115,7 @@ struct wind_model {
   int opt_loop_kernel = 1;
   long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
+  int opt_lstm_rec = 1;
   LoopDev loop{};
   void *beam_ws = nullptr;   // workspace of the beam scoring step
   BeamPool beam_pool{};
@@ -173,8 +174,10 @@ struct WsLayout {
   bool big_enc;
   int slot_stride, nparts, nparts_big, nparts_tiny;
   size_t o_e, o_encb, o_len, o_nact, o_eidx, o_eltok, o_slot, o_slotc, o_rst, o_raux, o_nemit, o_ticket, o_h, o_c, o_hn, o_hb,
-      o_hz, o_p, o_z, o_bl, o_zn, o_parts, o_rl, o_stats, o_dbg, o_lbar, o_lh, o_lp, o_lparts;
+      o_hz, o_rec, o_p, o_z, o_bl, o_zn, o_parts, o_rl, o_stats, o_dbg, o_lbar, o_lh, o_lp, o_lparts;
 };
+
+bool tiny_rows_ok(const wind_model *m, int max_rows);
 
 WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   const ModelDev &d = m->dev;
@@ -204,6 +207,7 @@ WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   w.o_h = take(w.st); w.o_c = take(w.st); w.o_hn = take(w.st);
   w.o_hb = take(2 * w.st);   // four bf16 arrays
   w.o_hz = take((size_t)(d.E > d.Hp ? d.E : d.Hp) * 2 + 256);
+  w.o_rec = take((size_t)d.L * B * 4 * d.Hp * 4);
   w.o_p = take((size_t)B * d.Hj * 4);
   w.o_z = take(w.Mpad * d.Hj * 2);
   w.o_bl = take(w.Mpad * 4); w.o_zn = take(w.Mpad * 4);
@@ -255,6 +259,10 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.h = (float *)(base + o_h); c.c = (float *)(base + o_c); c.hn = (float *)(base + o_hn);
   c.hb_hi = (bf16_t *)(base + o_hb); c.hb_lo = c.hb_hi + st / 4; c.hbn_hi = c.hb_lo + st / 4; c.hbn_lo = c.hbn_hi + st / 4;
   c.hb_zero = (const bf16_t *)(base + o_hz);
+  // recurrent gate sums kept ahead of the step: where the prediction network runs on MFMA tiles and the
+  // iteration is the graph of kernels with its own decision kernel
+  c.rec = m->opt_lstm_rec && m->dtype == WIND_BF16 && B >= m->opt_pred_mfma_min_batch && !tiny_rows_ok(m, B * W)
+              ? (float *)(base + w.o_rec) : nullptr;
   c.p = (float *)(base + o_p);
   c.z = (bf16_t *)(base + o_z);
   c.blank_logit = (float *)(base + o_bl); c.znorm = (float *)(base + o_zn);
@@ -318,7 +326,7 @@ void prof_collect(wind_model *m) {
 }
 
 // prediction-network step for the utterances on the emit list, then their projection
-int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
+int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first = false) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
   const int lstm_blocks = (d.Hp + 3) / 4, proj_blocks = (d.Hj + 3) / 4;
@@ -326,10 +334,34 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
   const bool small_k = 2 * d.Hp <= 512 * kSmallKSteps;   // the low-latency kernels' K range
   constexpr int R = PredCfg::BM / 2;
   const unsigned mtiles = (unsigned)((c.B + R - 1) / R);
+  if (mfma && c.rec) {
+    // the first layer's step was taken by the decision kernel (first step of a call: by the full
+    // kernels below, from the zero state); the layers above add their input half to the recurrent
+    // sums; the projection launch also renews those sums for the utterances that emitted
+    const unsigned rec_tiles = (unsigned)(d.L * (4 * d.Hp / PredCfg::BN)), proj_tiles = (unsigned)(d.Hj / PredCfg::BN);
+    if (first) {
+      CallDev c0 = c;
+      c0.rec = nullptr;
+      for (int l = 0; l < d.L; ++l)
+        launch(m, s, WIND_K_LSTM, capturing, lstm_layer_dma_kernel<PredCfg>, dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles),
+               dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c0, l, 0);
+      launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_dma_kernel<PredCfg>, dim3(proj_tiles, mtiles), dim3(PredCfg::NT),
+             PredCfg::SMEM_BYTES, d, c0, 0, (int)proj_tiles);
+      launch(m, s, WIND_K_LSTM, capturing, pred_proj_dma_kernel<PredCfg>, dim3(rec_tiles, mtiles), dim3(PredCfg::NT),
+             PredCfg::SMEM_BYTES, d, c, 1, 0);
+    } else {
+      for (int l = 1; l < d.L; ++l)
+        launch(m, s, WIND_K_LSTM, capturing, lstm_layer_dma_kernel<PredCfg>, dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles),
+               dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l, 1);
+      launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_dma_kernel<PredCfg>, dim3(proj_tiles + rec_tiles, mtiles),
+             dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, 1, (int)proj_tiles);
+    }
+    return check_launch("prediction step");
+  }
   for (int l = 0; l < d.L; ++l) {
     if (mfma)
       launch(m, s, WIND_K_LSTM, capturing, lstm_layer_dma_kernel<PredCfg>, dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles),
-             dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l);
+             dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l, 0);
     else if (m->dtype == WIND_BF16 && small_k)
       launch(m, s, WIND_K_LSTM, capturing, lstm_small_kernel<2>, dim3(lstm_blocks), dim3(256), 0, d, c, l);
     else if (m->dtype == WIND_BF16)
@@ -339,7 +371,7 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing) {
   }
   if (mfma)
     launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_dma_kernel<PredCfg>, dim3((unsigned)(d.Hj / PredCfg::BN), mtiles),
-           dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c);
+           dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, 0, d.Hj / PredCfg::BN);
   else if (m->dtype == WIND_BF16 && small_k)
     launch(m, s, WIND_K_PRED_PROJ, capturing, pred_small_kernel<2>, dim3(proj_blocks), dim3(256), 0, d, c);
   else if (m->dtype == WIND_BF16)
@@ -373,7 +405,7 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
   }
   int rc = check_launch("prologue");
   if (rc) return rc;
-  return enqueue_pred_step(m, s, false);
+  return enqueue_pred_step(m, s, false, true);
 }
 
 // the fused few-rows kernel keeps all window rows in LDS
@@ -844,6 +876,11 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
     m->opt_loop_spin_limit = value;
     return WIND_OK;
   }
+  if (!std::strcmp(key, "lstm_rec")) {
+    m->opt_lstm_rec = value != 0;
+    m->graph_valid = false;
+    return WIND_OK;
+  }
   if (!std::strcmp(key, "pred_mfma_min_batch")) {
     m->opt_pred_mfma_min_batch = (int)value;
     m->graph_valid = false;
@@ -879,6 +916,7 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
   HIP_TRY(hipMemcpyAsync(d_len, full.data(), sizeof(int) * B, hipMemcpyHostToDevice, s));
   HIP_TRY(hipStreamSynchronize(s));
   c.B = B; c.T = T; c.W = WIND_MAX_WINDOW; c.S = 1; c.cap = 1;
+  c.rec = nullptr;   // the steps below are whole prediction-network steps, with no decision kernel between them
   c.enc = enc_out; c.lengths = d_len;
   c.out_tokens = d_scr; c.out_frames = d_scr + B; c.out_counts = d_scr + 2 * B;
   m->graph_valid = false;

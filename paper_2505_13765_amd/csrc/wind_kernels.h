@@ -80,6 +80,11 @@ struct CallDev {
   float *h, *c, *hn;            // [L][B][Hp]
   bf16_t *hb_hi, *hb_lo, *hbn_hi, *hbn_lo;  // [L][B][Hp] large-batch path: h and new h as bf16 hi + lo
   const bf16_t *hb_zero;        // [max(E,Hp)] zeros (the lo part of an embedding row)
+  // Large batches: the recurrent half of every layer's gate sums, w_hh . h, for the hidden vectors as
+  // they stand (row order 4*unit + gate, no bias).  It changes only when its utterance emits, and it is
+  // renewed beside the projection of that step, so the next step, once its label is known, has only
+  // the input half left to do.  Null where this is not used (the full products are then formed per step).
+  float *rec;                   // [L][B][4Hp]
   float *p;                     // [B][Hj]
   bf16_t *z;                    // [Mpad][Hj]
   float *blank_logit;           // [Mpad]
@@ -630,11 +635,19 @@ __device__ __forceinline__ void evaluate_candidates(const ModelDev &m, const flo
 
 constexpr int kDecideMaxHj = 2048;  // exact_logit keeps Hj/128 float2 per lane
 
+// An fp32 value as two bf16: hi = RNE(v), lo = RNE(v - hi) (see the large-batch prediction network)
+__device__ __forceinline__ void store_hi_lo(bf16_t *hi, bf16_t *lo, size_t idx, float v) {
+  const uint32_t h = f32_to_bf16_bits(v);
+  hi[idx] = (bf16_t)h;
+  lo[idx] = (bf16_t)f32_to_bf16_bits(v - bf16_bits_to_f32(h));
+}
+
 struct DecideShared {
   int label[kMaxWindow];
   unsigned hist[kMaxWindow + 1];
   int recheck;
   int is_last;
+  int step_tok;                // the label whose prediction-network step follows (emitted and still active), else -1
   // LOCAL mode (fused few-rows kernel): per-slot state and per-row scalars kept in LDS, so that the
   // deciding workgroup does not go back to memory for them
   int4 slot[kTinyRows];        // utterance id, t, len, sym
@@ -881,6 +894,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
       } else {
         c.res_state[a] = make_int4(b, tn, len, sym);
         c.res_aux[a] = make_int4(cnt, flag, tok, (int)ev);
+        sh.step_tok = (flag & 2) ? tok : -1;
       }
     }
   }
@@ -1004,10 +1018,35 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
     sh.is_last = (tk == (unsigned)(na - 1));
   }
   __syncthreads();
-  if (!sh.is_last) return;
+  // With the recurrent sums at hand, the first LSTM layer's step for this utterance's label is
+  // elementwise: the label's row of input gate sums plus the recurrent sums, the gates, the new cell
+  // and hidden vector (written in place: nothing reads the old ones any more).  It runs beside the
+  // last workgroup's compaction; in that workgroup the waves other than the compacting one take it.
+  auto first_layer_step = [&](int first, int nthreads) {
+    const int tok = sh.step_tok;
+    if (c.rec == nullptr || tok < 0 || threadIdx.x < first) return;
+    const int b = st.x, Hp = m.Hp;
+    const float *xg = m.emb_gates + (size_t)tok * 4 * Hp, *rg = c.rec + (size_t)b * 4 * Hp;
+    for (int u = threadIdx.x - first; u < Hp; u += nthreads) {
+      const float4 x = *reinterpret_cast<const float4 *>(xg + 4 * u), r = *reinterpret_cast<const float4 *>(rg + 4 * u);
+      const size_t si = (size_t)b * Hp + u;
+      const float cp = c.c[si];
+      const float ig = 1.f / (1.f + expf(-(r.x + x.x))), fg = 1.f / (1.f + expf(-(r.y + x.y)));
+      const float og = 1.f / (1.f + expf(-(r.w + x.w)));
+      const float cn = fg * cp + ig * tanhf(r.z + x.z);
+      c.c[si] = cn;
+      store_hi_lo(c.hb_hi, c.hb_lo, si, og * tanhf(cn));
+    }
+  };
+  if (!sh.is_last) {
+    first_layer_step(0, blockDim.x);
+    return;
+  }
   const long long ts2 = c.dbg ? wall_clock64() : 0;
+  if (nwaves > 1) first_layer_step(64, blockDim.x - 64);
   __threadfence();
   if (threadIdx.x < 64) compact_lists<false>(c, parity, na, sh);
+  if (nwaves == 1) first_layer_step(0, blockDim.x);
   if (c.dbg && threadIdx.x == 0) {
     const long long ts3 = wall_clock64();
     c.dbg[0] += ts1 - ts0; c.dbg[1] += ts2 - ts1; c.dbg[2] += ts3 - ts2; c.dbg[3] += 1;
@@ -1565,14 +1604,12 @@ struct PredRows {
   }
 };
 
-__device__ __forceinline__ void store_hi_lo(bf16_t *hi, bf16_t *lo, size_t idx, float v) {
-  const uint32_t h = f32_to_bf16_bits(v);
-  hi[idx] = (bf16_t)h;
-  lo[idx] = (bf16_t)f32_to_bf16_bits(v - bf16_bits_to_f32(h));
-}
-
+// pre = 0: the whole step of a layer, [x | h_prev] against [w_ih | w_hh]; new hidden vectors go to hbn_*.
+// pre = 1 (layers above the first, c.rec in use): only the input half, x = the layer below's new
+// vector, on top of the recurrent sums in c.rec; nobody reads this layer's old vector any more, so the
+// new one is written in place (hb_*).
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, CallDev c, int layer) {
+__global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, CallDev c, int layer, int pre) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
   // grid = (column tiles, row tiles): workgroups with consecutive ids share the row tile, and the
@@ -1613,6 +1650,10 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
     c_prev[q] = c.c[lofs + (size_t)ub_e[q] * Hp + (n0 >> 2) + u];
     add_e[q] = make_float4(bias[u], bias[UB + u], bias[2 * UB + u], bias[3 * UB + u]);
     if (layer == 0) add_e[q] = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok_e[q] * 4 * Hp + n0 + 4 * u);
+    if (pre) {
+      const float4 rs = *reinterpret_cast<const float4 *>(c.rec + ((size_t)layer * c.B + ub_e[q]) * 4 * Hp + n0 + 4 * u);
+      add_e[q].x += rs.x; add_e[q].y += rs.y; add_e[q].z += rs.z; add_e[q].w += rs.w;
+    }
     (void)r;
   }
   __builtin_amdgcn_sched_barrier(0);   // these requests stay ahead of the tile core's
@@ -1627,7 +1668,7 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
       const int part = row >= R;
       const size_t si = lofs + (size_t)ub_row[i] * Hp;
       if (layer > 0) {
-        rows.px[i] = (part ? c.hbn_lo : c.hbn_hi) + si - (size_t)c.B * Hp + chunk * 8;
+        rows.px[i] = (pre ? (part ? c.hb_lo : c.hb_hi) : (part ? c.hbn_lo : c.hbn_hi)) + si - (size_t)c.B * Hp + chunk * 8;
         rows.xstep[i] = 1;
       }
       rows.ph[i] = (part ? c.hb_lo : c.hb_hi) + si + chunk * 8;
@@ -1640,7 +1681,8 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
     for (int ni = 0; ni < Cfg::NI; ++ni)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-  gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_cat_t[layer]) + (size_t)n0 * K, K, smem_raw, acc);
+  gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_cat_t[layer]) + (size_t)n0 * K, pre ? in : K, smem_raw,
+                             acc, NoInit{}, K);
   __syncthreads();   // every wave is done with the ring: reuse it for the gate tile
 
   float *tile = reinterpret_cast<float *>(smem_raw);
@@ -1668,12 +1710,63 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
     const float og = 1.f / (1.f + expf(-go));
     const float cn = fg * c_prev[q] + ig * tanhf(gg);
     c.c[si] = cn;
-    store_hi_lo(c.hbn_hi, c.hbn_lo, si, og * tanhf(cn));
+    if (pre) store_hi_lo(c.hb_hi, c.hb_lo, si, og * tanhf(cn));
+    else store_hi_lo(c.hbn_hi, c.hbn_lo, si, og * tanhf(cn));
   }
 }
 
+// One tile of c.rec: the recurrent gate sums w_hh . h of `layer` for the R utterances from row0 of
+// the emit list and the tile's 64 gate rows, from the hidden vectors in hb_* (already the new ones).
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, CallDev c) {
+__device__ __forceinline__ void lstm_rec_tile(const ModelDev &m, const CallDev &c, int layer, int n0, int row0, int n_emit,
+                                              const int (&ub_row)[Cfg::LPW], unsigned char *smem_raw) {
+  constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
+  const int Hp = m.Hp, in = layer == 0 ? 0 : Hp, K = in + Hp;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  PredRows<Cfg> rows;
+  rows.kin = 0;
+#pragma unroll
+  for (int i = 0; i < Cfg::LPW; ++i) {
+    const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
+    const int chunk = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
+    rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
+    if (row < Cfg::BM) rows.ph[i] = (row >= R ? c.hb_lo : c.hb_hi) + ((size_t)layer * c.B + ub_row[i]) * Hp + chunk * 8;
+  }
+  f32x16 acc[Cfg::MI][Cfg::NI];
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+  // the h columns of the tile's rows of [w_ih | w_hh]
+  gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_cat_t[layer]) + (size_t)n0 * K + in, Hp, smem_raw, acc,
+                             NoInit{}, K);
+  __syncthreads();
+  float *tile = reinterpret_cast<float *>(smem_raw);
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
+  __syncthreads();
+  for (int idx = tid; idx < R * UB; idx += Cfg::NT) {
+    const int r = idx / UB, u = idx - r * UB;
+    if (row0 + r >= n_emit) continue;
+    const float *hi = tile + r * TS + u, *lo = tile + (R + r) * TS + u;
+    const float4 g = make_float4(hi[0] + lo[0], hi[UB] + lo[UB], hi[2 * UB] + lo[2 * UB], hi[3 * UB] + lo[3 * UB]);
+    *reinterpret_cast<float4 *>(c.rec + ((size_t)layer * c.B + c.emit_idx[row0 + r]) * 4 * Hp + n0 + 4 * u) = g;
+  }
+}
+
+// pre = 0: the projection of the new top-layer vectors in hbn_*, then the new vectors of all layers
+// are committed to hb_*.  pre = 1 (c.rec in use): the new vectors are in hb_* already; column tiles
+// from proj_tiles on do not project but renew c.rec, layer by layer, for the utterances that emitted.
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, CallDev c, int pre, int proj_tiles) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   constexpr int R = Cfg::BM / 2, TS = Cfg::BN + 4;
   const int Hp = m.Hp, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -1692,6 +1785,12 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, Call
     ub_row[i] = c.emit_idx[min(row0 + r, c.B - 1)];
   }
   if (n_emit == 0) return;
+  if ((int)blockIdx.x >= proj_tiles) {
+    if (row0 >= n_emit) return;
+    const int tiles_per_layer = 4 * Hp / Cfg::BN, ct = (int)blockIdx.x - proj_tiles;
+    lstm_rec_tile<Cfg>(m, c, ct / tiles_per_layer, (ct % tiles_per_layer) * Cfg::BN, row0, n_emit, ub_row, smem_raw);
+    return;
+  }
   if (row0 < n_emit) {
     const size_t top = (size_t)(m.L - 1) * c.B * Hp;
     PredRows<Cfg> rows;
@@ -1701,7 +1800,8 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, Call
       const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
       const int chunk = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
       rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
-      if (row < Cfg::BM) rows.ph[i] = (row >= R ? c.hbn_lo : c.hbn_hi) + top + (size_t)ub_row[i] * Hp + chunk * 8;
+      if (row < Cfg::BM)
+        rows.ph[i] = (pre ? (row >= R ? c.hb_lo : c.hb_hi) : (row >= R ? c.hbn_lo : c.hbn_hi)) + top + (size_t)ub_row[i] * Hp + chunk * 8;
     }
     f32x16 acc[Cfg::MI][Cfg::NI];
 #pragma unroll
@@ -1728,7 +1828,7 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, Call
       c.p[(size_t)c.emit_idx[row0 + r] * m.Hj + n0 + col] = tile[r * TS + col] + tile[(R + r) * TS + col] + m.b_pred[n0 + col];
     }
   }
-  {  // commit the new hidden vectors (hi and lo): every layer has read the old ones by now.  Last,
+  if (!pre) {  // commit the new hidden vectors (hi and lo): every layer has read the old ones by now.  Last,
      // so that the copy's round trips do not delay the projection.
     const size_t total = (size_t)m.L * n_emit * Hp;
     const size_t nthreads = (size_t)gridDim.x * gridDim.y * Cfg::NT;

@@ -60,7 +60,8 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// A points at the tile's first row ([>=BM rows, K] bf16 dense), Bw likewise for B.  K % BK == 0.
+// A points at the tile's first row ([>=BM rows, K] bf16 dense), Bw likewise for B (rows ldb apart,
+// ldb = K unless given).  K % BK == 0.
 // The caller initialises acc (zero, or a bias: the products are accumulated on top of it).
 //
 // Schedule.  Tile t lives in stage t % NSTAGE.  The operand fragments of K step ks+1 are read from
@@ -97,9 +98,11 @@ struct NoInit {
 template <class Cfg, class ASrc, bool SWAP = false, class Init = NoInit>
 __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf16_t *__restrict__ Bw,
                                                       int K, unsigned char *smem,
-                                                      f32x16 (&acc)[Cfg::MI][Cfg::NI], Init after_issue = Init{}) {
+                                                      f32x16 (&acc)[Cfg::MI][Cfg::NI], Init after_issue = Init{},
+                                                      int ldb = 0) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+  if (ldb == 0) ldb = K;   // B rows are K long unless the caller walks a K-slice of longer rows
 
   // the wave's loads of a stage: rows below BM are A rows, the rest B rows
   int lrow[Cfg::LPW], lchunk[Cfg::LPW];
@@ -109,7 +112,7 @@ __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf
     const int q = wave * Cfg::LPW + i;
     lrow[i] = q * Cfg::RPI + lane / Cfg::CPR;
     lchunk[i] = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(lrow[i]);
-    bsrc[i] = Bw + (size_t)(lrow[i] - Cfg::BM) * K + lchunk[i] * 8;
+    bsrc[i] = Bw + (size_t)(lrow[i] - Cfg::BM) * ldb + lchunk[i] * 8;
   }
   // the wave's loads of tile kt into `stage`: all of them (part < 0), or the part-th of KSTEPS shares
   auto issue = [&](int kt, int stage, int part) {

@@ -133,19 +133,22 @@ def test_bf16_scaled_workloads(torch_cuda, name, B, lo, hi, windows):
 
 @pytest.mark.parametrize("name,B,lo,hi,W", [("batch32", 9, 30, 140, 8), ("largevocab_b128", 35, 20, 60, 4)])
 def test_prediction_network_on_mfma_tiles(torch_cuda, name, B, lo, hi, W):
-    """Both prediction-network implementations (fp32 FMA per hidden unit, hi/lo-split bf16 MFMA
-    tiles) against the oracle, on one and on two LSTM layers, with ragged emit lists."""
+    """The prediction-network implementations (fp32 FMA per hidden unit; hi/lo-split bf16 MFMA tiles
+    with the recurrent gate sums kept ahead of the step, and with whole steps) against the oracle, on
+    one and on two LSTM layers, with ragged emit lists."""
     cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
     m, o, _ = load(cfg)
     enc, lens = wi.make_batch(cfg)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     res = []
-    for min_batch in (1, 10 ** 6):
+    for min_batch, rec in ((1, 1), (1, 0), (10 ** 6, 1)):
         m.set_option("pred_mfma_min_batch", min_batch)
+        m.set_option("lstm_rec", rec)
         toks, frs = m.decode(d_enc, d_len, W, cfg.S)
         assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
         res.append((toks, frs))
     assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[1][0]))
+    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[2][0]))
     m.close()
 
 
