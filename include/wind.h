@@ -251,6 +251,11 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "loop_spin_limit"  polls a workgroup of that kernel waits at a barrier before it gives up
  *             (default 2^21, about a second); the decode then returns WIND_ERR_HIP.  Tests set it
  *             to 0 to exercise that path: every workgroup still leaves the kernel normally
+ *   "atomic_lists"  1 (default): in the graph of per-step kernels of bf16 models, every workgroup of the
+ *             decision kernel claims its utterance's place in the next iteration's list of active
+ *             utterances and in the list of utterances that emitted with an atomic counter (the
+ *             order of those lists then varies between runs, the decoded output does not); 0: the
+ *             last workgroup to finish compacts the lists in order
  *   "lstm_rec"  1 (default): where the prediction network runs on MFMA tiles, the recurrent half of every
  *             LSTM layer's gate sums (w_hh . h) is kept ready for the hidden vectors as they stand and
  *             renewed beside the projection, so a step only adds the input half once the label is

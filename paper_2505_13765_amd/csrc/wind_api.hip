@@ -116,6 +116,7 @@ struct wind_model {
   long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
   int opt_lstm_rec = 1;
+  int opt_atomic_lists = 1;
   LoopDev loop{};
   void *beam_ws = nullptr;   // workspace of the beam scoring step
   BeamPool beam_pool{};
@@ -276,6 +277,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
   c.dbg = m->opt_debug_stamps ? (long long *)(base + o_dbg) : nullptr;
+  c.lists_atomic = m->opt_atomic_lists && m->dtype == WIND_BF16 && !tiny_rows_ok(m, B * W);   // the path with build_z_kernel
   m->loop.bar = (unsigned *)(base + o_lbar);
   m->loop.h_x = (float *)(base + o_lh);
   m->loop.p_x = (float *)(base + o_lp);
@@ -874,6 +876,11 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "loop_spin_limit")) {
     if (value < 0 || value > (1ll << 30)) return fail(WIND_ERR_ARG, "loop_spin_limit must be in 0..2^30");
     m->opt_loop_spin_limit = value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "atomic_lists")) {
+    m->opt_atomic_lists = value != 0;
+    m->graph_valid = false;
     return WIND_OK;
   }
   if (!std::strcmp(key, "lstm_rec")) {

@@ -77,6 +77,9 @@ struct CallDev {
   int *emit_list_tok;           // [B] their labels, in the same order
   int *n_emit;                  // [1]
   unsigned *ticket;             // [2] workgroups done: decide_kernel, joint_tiny_kernel
+  int lists_atomic;             // 1: decide_kernel's workgroups claim their places in the next slot table and the
+                                //    emit list with atomic counters (order varies, results do not); 0: the last
+                                //    workgroup to finish compacts res_state / res_aux in slot order
   float *h, *c, *hn;            // [L][B][Hp]
   bf16_t *hb_hi, *hb_lo, *hbn_hi, *hbn_lo;  // [L][B][Hp] large-batch path: h and new h as bf16 hi + lo
   const bf16_t *hb_zero;        // [max(E,Hp)] zeros (the lo part of an embedding row)
@@ -259,6 +262,8 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
   if (a >= c.B) return;
   const int na = c.n_active[parity];
   const int4 st = c.slot_state[parity * c.slot_stride + a];   // same round trip as the count
+  // the counters that this iteration's decision kernel adds to: every reader of their old values is done
+  if (c.lists_atomic && blockIdx.x == 0 && threadIdx.x == 0) { c.n_active[parity ^ 1] = 0; *c.n_emit = 0; }
   if (a >= na) return;
   const int b = st.x, tt = st.y + j;
   const bool valid = tt < st.z;
@@ -892,8 +897,12 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
         sh.flag[a] = flag; sh.tok[a] = tok; sh.event[a] = ev;
         sh.slot[a] = make_int4(b, tn, len, sym); sh.cnt[a] = cnt;
       } else {
-        c.res_state[a] = make_int4(b, tn, len, sym);
-        c.res_aux[a] = make_int4(cnt, flag, tok, (int)ev);
+        if (c.lists_atomic) {   // the calling kernel takes it from here
+          sh.slot[0] = make_int4(b, tn, len, sym); sh.cnt[0] = cnt; sh.flag[0] = flag; sh.tok[0] = tok; sh.event[0] = ev;
+        } else {
+          c.res_state[a] = make_int4(b, tn, len, sym);
+          c.res_aux[a] = make_int4(cnt, flag, tok, (int)ev);
+        }
         sh.step_tok = (flag & 2) ? tok : -1;
       }
     }
@@ -1012,16 +1021,10 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
     atomicAdd((unsigned long long *)&c.dbg[sh.recheck ? 4 : 6], (unsigned long long)(ts1 - ts0));
     atomicAdd((unsigned long long *)&c.dbg[sh.recheck ? 5 : 7], 1ull);
   }
-  if (threadIdx.x == 0) {
-    __threadfence();
-    const unsigned tk = atomicAdd(c.ticket, 1u);
-    sh.is_last = (tk == (unsigned)(na - 1));
-  }
-  __syncthreads();
   // With the recurrent sums at hand, the first LSTM layer's step for this utterance's label is
   // elementwise: the label's row of input gate sums plus the recurrent sums, the gates, the new cell
-  // and hidden vector (written in place: nothing reads the old ones any more).  It runs beside the
-  // last workgroup's compaction; in that workgroup the waves other than the compacting one take it.
+  // and hidden vector (written in place: nothing reads the old ones any more).  Where the
+  // last workgroup compacts the lists, it runs beside that, on the waves other than the compacting one.
   auto first_layer_step = [&](int first, int nthreads) {
     const int tok = sh.step_tok;
     if (c.rec == nullptr || tok < 0 || threadIdx.x < first) return;
@@ -1038,6 +1041,50 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
       store_hi_lo(c.hb_hi, c.hb_lo, si, og * tanhf(cn));
     }
   };
+  if (c.lists_atomic) {
+    // No workgroup waits for the others: each claims its utterance's place in the next slot table and,
+    // with a label, in the emit list, and adds its window's counters.  The order of the lists varies
+    // from run to run; what is computed per utterance does not depend on it.
+    if (threadIdx.x < 16) {
+      const int4 ns = sh.slot[0];
+      const int flag = sh.flag[0];
+      const unsigned ev = sh.event[0];
+      const int k = threadIdx.x;
+      if (k == 0 && (flag & 1)) {
+        const int pos = atomicAdd(&c.n_active[parity ^ 1], 1);
+        c.slot_state[(parity ^ 1) * c.slot_stride + pos] = ns;
+        c.slot_count[(parity ^ 1) * c.slot_stride + pos] = sh.cnt[0];
+      }
+      if (k == 1 && (flag & 2)) {
+        const int pos = atomicAdd(c.n_emit, 1);
+        c.emit_idx[pos] = ns.x;
+        c.emit_list_tok[pos] = sh.tok[0];
+      }
+      unsigned long long add = 0ull;
+      int which = -1;
+      switch (k) {
+        case 2: which = ST_WINDOWS; add = 1ull; break;
+        case 3: which = ST_ROWS; add = ev & 127u; break;
+        case 4: which = ST_USEFUL; add = (ev >> 7) & 127u; break;
+        case 5: which = ST_RECHECK; add = (ev >> 21) & 127u; break;
+        case 6: which = ST_LABELS; add = (ev >> 28) & 1u; break;
+        case 7: which = ST_FORCED; add = (ev >> 29) & 1u; break;
+        case 8: which = ST_OVERFLOW; add = (ev >> 30) & 1u; break;
+        case 9: which = kStatJump0 + (int)((ev >> 14) & 127u); add = 1ull; break;
+        case 10: which = ST_ITER; add = a == 0 ? 1ull : 0ull; break;
+        default: break;
+      }
+      if (which >= 0 && add) atomicAdd(&c.stats[which], add);
+    }
+    first_layer_step(0, blockDim.x);
+    return;
+  }
+  if (threadIdx.x == 0) {
+    __threadfence();
+    const unsigned tk = atomicAdd(c.ticket, 1u);
+    sh.is_last = (tk == (unsigned)(na - 1));
+  }
+  __syncthreads();
   if (!sh.is_last) {
     first_layer_step(0, blockDim.x);
     return;

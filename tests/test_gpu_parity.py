@@ -141,14 +141,21 @@ def test_prediction_network_on_mfma_tiles(torch_cuda, name, B, lo, hi, W):
     enc, lens = wi.make_batch(cfg)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     res = []
-    for min_batch, rec in ((1, 1), (1, 0), (10 ** 6, 1)):
+    stats = []
+    for min_batch, rec, atomic in ((1, 1, 1), (1, 0, 1), (1, 1, 0), (1, 0, 0), (10 ** 6, 1, 1)):
         m.set_option("pred_mfma_min_batch", min_batch)
         m.set_option("lstm_rec", rec)
+        m.set_option("atomic_lists", atomic)   # lists of active / emitting utterances: claimed by atomics, or compacted in order
         toks, frs = m.decode(d_enc, d_len, W, cfg.S)
         assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
         res.append((toks, frs))
-    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[1][0]))
-    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[2][0]))
+        st = m.stats()
+        stats.append((st.iterations, st.windows, st.rows, st.useful_rows, st.labels, st.forced_advances,
+                      list(st.jump_hist)))
+    for other in res[1:]:
+        assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], other[0]))
+        assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], other[1]))
+    assert all(s == stats[0] for s in stats[1:])
     m.close()
 
 
@@ -196,7 +203,7 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
         assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
         st = m.stats()
         res.append((toks, frs))
-        stats.append((st.iterations, st.windows, st.rows, st.useful_rows, st.labels, st.forced_advances, st.rechecks,
+        stats.append((st.iterations, st.windows, st.rows, st.useful_rows, st.labels, st.forced_advances,
                       list(st.jump_hist)))
     assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[1][0]))
     assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], res[1][1]))
