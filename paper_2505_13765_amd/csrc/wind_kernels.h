@@ -803,6 +803,48 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
   else return recheck_row<8>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0);
 }
 
+// Four window rows per wave at once, 16 lanes per row, for rows of at most 32 parts: lane 16 q + s holds
+// the keys of parts s and s + 16 (kA, kB) and the blank logit and norm of row j = the q-th row of this
+// wave; the reductions of decide_row then run inside the rows of 16 lanes, for all four rows in the same
+// instructions.  A row inside the near-tie band goes through decide_row itself, keys re-read by the whole
+// wave through `reload` (part index -> keys).  Writes sh.label[j] for j < W; returns the rows re-decided.
+template <class WT, class Reload>
+__device__ __forceinline__ int decide_rows_quad(const ModelDev &m, const CallDev &c, int a, int4 st, int nparts, int part_width,
+                                                float2 kA, float2 kB, float vblank, float znorm, int j,
+                                                const Reload &reload, DecideShared &sh) {
+  const int lane = threadIdx.x & 63, s = lane & 15, V = m.V;
+  const int n = min(c.W, st.z - st.y);
+  const float kbest = row16_max_f32(fmaxf(kA.x, kB.x));
+  const float vbest = key_val(kbest);
+  const float top = fmaxf(vbest, vblank);
+  const float thresh = top - (m.tau_scale * znorm + 6.2e-5f * fabsf(top));
+  const int cnt = row16_sum_i32((key_val(kA.x) >= thresh) + (key_val(kA.y) >= thresh) + (key_val(kB.x) >= thresh) +
+                                (key_val(kB.y) >= thresh));
+  int col = -1;
+  if (kA.x == kbest) col = s * part_width + key_col(kbest);
+  if (kB.x == kbest) col = (s + 16) * part_width + key_col(kbest);
+  col = row16_max_i32(col);
+  int label = V;
+  bool slow = false;
+  if (j < n && !(vbest < thresh)) {
+    if (cnt == 1 && vblank < thresh) label = col;
+    else slow = true;
+  }
+  int n_recheck = 0;
+  unsigned long long todo = __ballot(slow && s == 0);
+  while (todo) {   // wave-uniform
+    const int q = (__ffsll((long long)todo) - 1) >> 4;
+    todo &= todo - 1;
+    const int jq = __builtin_amdgcn_readlane(j, 16 * q), row = a * c.W + jq;
+    const float2 kk0 = lane < nparts ? reload(row, lane) : make_float2(kKeyNone, kKeyNone);
+    const int l = decide_row<WT, false>(m, c, row, st.x, st.y + jq, nparts, nparts, part_width, readlane_f32(vblank, 16 * q),
+                                        readlane_f32(znorm, 16 * q), kk0, n_recheck);
+    if ((lane >> 4) == q) label = l;
+  }
+  if (s == 0 && j < c.W) sh.label[j] = label;
+  return n_recheck;
+}
+
 // Keys and row scalars of the first rows a wave decides, requested before anything else is known
 // about the utterance so that they share the round trip of the slot table.
 constexpr int kRowsAhead = 4;
@@ -819,11 +861,12 @@ struct RowsAhead {
 template <class WT, bool LOCAL, bool WIDE = false>
 __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int a, int4 st, int cnt,
                                                  int exact_mode, int nparts, int stride, int part_width,
-                                                 const RowsAhead &ahead, DecideShared &sh, bool write_out = true) {
+                                                 const RowsAhead &ahead, DecideShared &sh, bool write_out = true,
+                                                 bool rows_done = false, int pre_recheck = 0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int b = st.x, t = st.y, len = st.z, V = m.V;
   const int n = min(c.W, len - t);
-  int n_recheck = 0;
+  int n_recheck = pre_recheck;   // rows_done: the caller has filled sh.label (see decide_rows_quad)
   if (threadIdx.x == 0) sh.recheck = 0;
   __syncthreads();
   auto one_row = [&](int j, float2 k0, float vb, float zn) {
@@ -843,9 +886,9 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
 #pragma unroll
   for (int q = 0; q < kRowsAhead; ++q) {
     const int j = wave + q * nwaves;
-    if (j < c.W) one_row(j, ahead.kk0[q], ahead.vb[q], ahead.zn[q]);
+    if (!rows_done && j < c.W) one_row(j, ahead.kk0[q], ahead.vb[q], ahead.zn[q]);
   }
-  for (int j = wave + kRowsAhead * nwaves; j < c.W; j += nwaves) {
+  for (int j = wave + kRowsAhead * nwaves; !rows_done && j < c.W; j += nwaves) {
     float2 k0 = make_float2(kKeyNone, kKeyNone);
     float vb = 0.f, zn = 0.f;
     if (!exact_mode && j < n) {
@@ -2284,8 +2327,25 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       for (int i = tid; i < n_rows * c.nparts_tiny; i += 256) lparts[i] = ld_shared_f32x2(parts + i);
       __syncthreads();
     }
+    const bool quad = direct && c.nparts_tiny <= 32;   // four rows per wave decided at once
     for (int a = 0; a < na; ++a) {
       RowsAhead ahead;
+      if (quad) {
+        const int s = lane & 15, j = wave + (lane >> 4) * 4, row = a * W + j;
+        float2 kA = make_float2(kKeyNone, kKeyNone), kB = kA;
+        float vb = 0.f, zn = 0.f;
+        if (j < W) {
+          if (s < c.nparts_tiny) kA = ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s);
+          if (s + 16 < c.nparts_tiny) kB = ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s + 16);
+          vb = sh.blank[row];
+          zn = sh.znorm[row];
+        }
+        auto reload = [&](int r, int part) { return ld_shared_f32x2(parts + (size_t)r * c.nparts_tiny + part); };
+        const int rechecked = decide_rows_quad<bf16_t>(m, cl, a, sh.slot[a], c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
+        decide_utterance<bf16_t, true>(m, cl, a, sh.slot[a], sh.cnt[a], 0, c.nparts_tiny, c.nparts_tiny, kTinyCols, ahead, sh,
+                                       g == 0, true, rechecked);
+        continue;
+      }
 #pragma unroll
       for (int q = 0; q < kRowsAhead; ++q) {
         const int j = wave + q * 4, row = a * W + j;

@@ -58,6 +58,26 @@ __device__ __forceinline__ float readlane_f32(float v, int lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
+// the same four steps alone: reductions over each row of 16 lanes, four independent results per wave
+__device__ __forceinline__ float row16_max_f32(float v) {
+  v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppRowHalfMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppQuadXor2>(v));
+  return fmaxf(v, dpp_f32<kDppQuadXor1>(v));
+}
+__device__ __forceinline__ int row16_max_i32(int v) {
+  v = max(v, dpp_i32<kDppRowMirror>(v));
+  v = max(v, dpp_i32<kDppRowHalfMirror>(v));
+  v = max(v, dpp_i32<kDppQuadXor2>(v));
+  return max(v, dpp_i32<kDppQuadXor1>(v));
+}
+__device__ __forceinline__ int row16_sum_i32(int v) {
+  v += dpp_i32<kDppRowMirror>(v);
+  v += dpp_i32<kDppRowHalfMirror>(v);
+  v += dpp_i32<kDppQuadXor2>(v);
+  return v + dpp_i32<kDppQuadXor1>(v);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f32<kDppRowMirror>(v);
   v += dpp_f32<kDppRowHalfMirror>(v);
