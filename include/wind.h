@@ -239,12 +239,14 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
  *   "profile" 1: time every kernel launch with events (see wind_get_kernel_times); implies no graph
  *   "recheck_kappa_milli"  width of the near-tie band of the bf16 pass, in thousandths
  *   "tiny_rows"  decodes with at most this many window rows (B * W) run window gather, joint and
- *             decision as one kernel per iteration (default 64, the maximum; 0 turns it off)
+ *             decision as one kernel per iteration (at most 64; default 0 = off: the separate
+ *             kernels are faster at every size since the decision kernel takes the first LSTM
+ *             layer's step and no longer compacts the lists)
  *   "joint_split_rows"  iterations with more window rows than this use the 256 x 256 joint tiles,
  *             the others 128-column tiles whose height follows the row count (default: 256 rows
  *             per row tile that it takes to fill the chip; 1024 for V = 8192)
  *   "pred_mfma_min_batch"  smallest B for which the prediction network runs on MFMA tiles
- *             (default 16; bf16 models only; below it one wave per hidden unit does fp32 FMA)
+ *             (default 1; bf16 models only; below it one wave per hidden unit does fp32 FMA)
  *   "loop_kernel"  1 (default): decodes of one or two utterances with at most 32 window rows (bf16, one
  *             LSTM layer, weights that fit the chip's LDS) run the whole loop as one resident kernel
  *             whose workgroups meet at grid barriers; 0: always the graph of per-step kernels

@@ -39,10 +39,12 @@ int fail(int code, const std::string &msg) {
 using JointCfg = TileCfg<128, 128, 64, 64>;            // debug store kernel
 using JointRows1 = JointRowsCfg<1>::type;              // joint_rows_kernel: 128-column tiles, 64..256 rows
 using JointBigCfg = Ring5Cfg<256, 64, 128>;             // more rows than the rows kernel balances: 256 x 256 tiles
-constexpr int kTinyRowsDefault = 64;                    // at most this many window rows: one fused kernel
+constexpr int kTinyRowsDefault = 0;   // the fused few-rows kernel (at most this many window rows) is off by default:
+                                      // since the decision kernel stopped compacting and took over the first LSTM
+                                      // layer, the separate kernels are faster at every size (see option "tiny_rows")
 using EncCfg = TileCfg<128, 128, 64, 64>;
 using PredCfg = DmaCfg<64, 64, 32, 32, 64, 4>;   // 32 utterances (hi and lo rows) x 64 columns, 4-stage ring
-constexpr int kPredMfmaMinBatch = 16;      // below this the FMA prediction network is used
+constexpr int kPredMfmaMinBatch = 1;       // below this the FMA prediction network is used
 constexpr size_t kEncRing5MinRows = 16384;   // B * T from which the encoder projection uses 256 x 256 tiles
 constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height, plus one block
 
@@ -117,6 +119,7 @@ struct wind_model {
   int opt_debug_stamps = 0;
   int opt_lstm_rec = 1;
   int opt_atomic_lists = 1;
+  bool fma_pred_step = false;   // this call's prediction-network steps keep their state in fp32 (the resident loop kernel reads it)
   LoopDev loop{};
   void *beam_ws = nullptr;   // workspace of the beam scoring step
   BeamPool beam_pool{};
@@ -332,7 +335,7 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first =
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
   const int lstm_blocks = (d.Hp + 3) / 4, proj_blocks = (d.Hj + 3) / 4;
-  const bool mfma = m->dtype == WIND_BF16 && c.B >= m->opt_pred_mfma_min_batch;
+  const bool mfma = m->dtype == WIND_BF16 && c.B >= m->opt_pred_mfma_min_batch && !m->fma_pred_step;
   const bool small_k = 2 * d.Hp <= 512 * kSmallKSteps;   // the low-latency kernels' K range
   constexpr int R = PredCfg::BM / 2;
   const unsigned mtiles = (unsigned)((c.B + R - 1) / R);
@@ -549,11 +552,14 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   c.enc = enc; c.lengths = lengths;
   c.out_tokens = out_tokens; c.out_frames = out_frames; c.out_counts = out_counts;
 
-  rc = enqueue_prologue(m, s);
-  if (rc) return rc;
   LoopDev lp = m->loop;
   size_t loop_smem = 0;
-  if (loop_kernel_shape(m, B, W, &lp, &loop_smem)) {
+  const bool use_loop = loop_kernel_shape(m, B, W, &lp, &loop_smem);
+  m->fma_pred_step = use_loop;   // the resident kernel starts from the fp32 state of the start-token step
+  if (use_loop) { c.rec = nullptr; c.lists_atomic = 0; }
+  rc = enqueue_prologue(m, s);
+  if (rc) return rc;
+  if (use_loop) {
     // the whole loop as one resident kernel
     lp.max_iters = (int)std::min<long long>((long long)T * (S + 1) + 2, 1 << 30);
     lp.spin_limit = (unsigned)m->opt_loop_spin_limit;
@@ -924,6 +930,7 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
   HIP_TRY(hipStreamSynchronize(s));
   c.B = B; c.T = T; c.W = WIND_MAX_WINDOW; c.S = 1; c.cap = 1;
   c.rec = nullptr;   // the steps below are whole prediction-network steps, with no decision kernel between them
+  m->fma_pred_step = false;
   c.enc = enc_out; c.lengths = d_len;
   c.out_tokens = d_scr; c.out_frames = d_scr + B; c.out_counts = d_scr + 2 * B;
   m->graph_valid = false;
