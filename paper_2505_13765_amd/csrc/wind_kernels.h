@@ -1119,7 +1119,9 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
       }
       if (which >= 0 && add) atomicAdd(&c.stats[which], add);
     }
-    first_layer_step(0, blockDim.x);
+    // with enough waves, the one that waits for its claims' answers takes no part in the layer step
+    if (nwaves >= 8) first_layer_step(64, blockDim.x - 64);
+    else first_layer_step(0, blockDim.x);
     return;
   }
   if (threadIdx.x == 0) {
