@@ -1970,7 +1970,7 @@ struct LoopShared {
   int n_act, n_emit, ok;
 };
 
-// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: 32 rows of Hj+8 bf16][hfull: B*Hp f32]
+// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: 32 rows of Hj+8 bf16][hhi, hlo: B*Hp bf16 each]
 //      [pfull: B*Hj f32][cst: B*upw f32]
 __host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw) {
   return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + (size_t)kLoopRows * (Hj + 8) * 2 + (size_t)B * Hp * 4 +
@@ -2101,8 +2101,23 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   bf16_t *wl = reinterpret_cast<bf16_t *>(smem_raw);
   bf16_t *wp = wl + (size_t)lp.upw * 4 * Hp;
   bf16_t *zs = wp + (size_t)lp.ppw * Hp;
-  float *hfull = reinterpret_cast<float *>(zs + (size_t)kLoopRows * zstride);
-  float *pfull = hfull + (size_t)B * Hp;
+  // the hidden vectors as bf16 hi + lo (hi = RNE(h), lo = RNE(h - hi), 16 mantissa bits together): the dot
+  // products with the bf16 weights then take one packed instruction per pair and part, with nothing to unpack
+  bf16_t *hhi = zs + (size_t)kLoopRows * zstride, *hlo = hhi + (size_t)B * Hp;
+  float *pfull = reinterpret_cast<float *>(hlo + (size_t)B * Hp);
+  auto put_h2 = [&](int i, float2 v) {   // elements i (even) and i + 1
+    const uint32_t hb = pack_bf16x2(v.x, v.y);
+    *reinterpret_cast<uint32_t *>(hhi + i) = hb;
+    *reinterpret_cast<uint32_t *>(hlo + i) = pack_bf16x2(v.x - __uint_as_float(hb << 16), v.y - __uint_as_float(hb & 0xFFFF0000u));
+  };
+  // sum over this lane's eight k of w[k] * (hi[k] + lo[k]), on top of acc
+  auto dot8 = [&](const bf16_t *wrow, int hofs, float acc) {
+    const u32x4 wv = *reinterpret_cast<const u32x4 *>(wrow);
+    const u32x4 a = *reinterpret_cast<const u32x4 *>(hhi + hofs), b = *reinterpret_cast<const u32x4 *>(hlo + hofs);
+    acc = dot2_bf16(wv.x, a.x, acc); acc = dot2_bf16(wv.y, a.y, acc); acc = dot2_bf16(wv.z, a.z, acc); acc = dot2_bf16(wv.w, a.w, acc);
+    acc = dot2_bf16(wv.x, b.x, acc); acc = dot2_bf16(wv.y, b.y, acc); acc = dot2_bf16(wv.z, b.z, acc); acc = dot2_bf16(wv.w, b.w, acc);
+    return acc;
+  };
   float *cst = pfull + (size_t)B * Hj;
 
   // ---- once: this workgroup's weights, the state after the start-token step, the slot table
@@ -2120,7 +2135,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     if (prow0 + row < Hj) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)(prow0 + row) * Hp + k);
     *reinterpret_cast<u32x4 *>(wp + i) = v;
   }
-  for (int i = tid; i < B * Hp; i += 256) hfull[i] = c.h[i];
+  for (int i = tid * 2; i < B * Hp; i += 512) put_h2(i, *reinterpret_cast<const float2 *>(c.h + i));
   for (int i = tid; i < B * Hj; i += 256) pfull[i] = c.p[i];
   for (int i = tid; i < B * lp.upw; i += 256) {
     const int b = i / lp.upw, u = i - b * lp.upw;
@@ -2183,17 +2198,9 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       for (int gate = 0; gate < 4; ++gate) part[4 * q + gate] = 0.f;
       if (u >= lp.upw) continue;
       for (int k = lane * 8; k < Hp; k += 512) {
-        const f32x4 *hs = reinterpret_cast<const f32x4 *>(hfull + (size_t)ub * Hp + k);
-        const f32x4 ha = hs[0], hb2 = hs[1];
 #pragma unroll
-        for (int gate = 0; gate < 4; ++gate) {
-          float wf[8];
-          unpack_bf16x8(*reinterpret_cast<const u32x4 *>(wl + ((size_t)u * 4 + gate) * Hp + k), wf);
-          float a2 = part[4 * q + gate];
-          a2 = fmaf(wf[0], ha.x, a2); a2 = fmaf(wf[1], ha.y, a2); a2 = fmaf(wf[2], ha.z, a2); a2 = fmaf(wf[3], ha.w, a2);
-          a2 = fmaf(wf[4], hb2.x, a2); a2 = fmaf(wf[5], hb2.y, a2); a2 = fmaf(wf[6], hb2.z, a2); a2 = fmaf(wf[7], hb2.w, a2);
-          part[4 * q + gate] = a2;
-        }
+        for (int gate = 0; gate < 4; ++gate)
+          part[4 * q + gate] = dot8(wl + ((size_t)u * 4 + gate) * Hp + k, ub * Hp + k, part[4 * q + gate]);
       }
     }
     return wave_sum16_scatter(part, lane);
@@ -2429,7 +2436,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     const long long t6 = dbg ? wall_clock64() : 0;
     for (int r = 0; r < n_emit; ++r) {
       const int ub = ls.emit_ub[r];
-      for (int k = tid; k < Hp; k += 256) hfull[(size_t)ub * Hp + k] = ld_shared_f32(&lp.h_x[(size_t)ub * Hp + k]);
+      for (int k = tid * 2; k < Hp; k += 512) put_h2(ub * Hp + k, ld_shared_f32x2(reinterpret_cast<const float2 *>(&lp.h_x[(size_t)ub * Hp + k])));
     }
     __syncthreads();
     // ---- this workgroup's rows of the prediction projection
@@ -2443,16 +2450,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
           const int jl = wave + 4 * (q0 + q);
           part[q] = 0.f;
           if (jl >= lp.ppw) continue;
-          for (int k = lane * 8; k < Hp; k += 512) {
-            const f32x4 *hs = reinterpret_cast<const f32x4 *>(hfull + (size_t)ub * Hp + k);
-            const f32x4 ha = hs[0], hb2 = hs[1];
-            float wf[8];
-            unpack_bf16x8(*reinterpret_cast<const u32x4 *>(wp + (size_t)jl * Hp + k), wf);
-            float a2 = part[q];
-            a2 = fmaf(wf[0], ha.x, a2); a2 = fmaf(wf[1], ha.y, a2); a2 = fmaf(wf[2], ha.z, a2); a2 = fmaf(wf[3], ha.w, a2);
-            a2 = fmaf(wf[4], hb2.x, a2); a2 = fmaf(wf[5], hb2.y, a2); a2 = fmaf(wf[6], hb2.z, a2); a2 = fmaf(wf[7], hb2.w, a2);
-            part[q] = a2;
-          }
+          for (int k = lane * 8; k < Hp; k += 512) part[q] = dot8(wp + (size_t)jl * Hp + k, ub * Hp + k, part[q]);
         }
         const float tot = wave_sum4_scatter(part, lane);   // lanes 4q .. 4q+3 of every row of 16 hold row q's sum
         const int jl = wave + 4 * (q0 + ((lane >> 2) & 3)), j = prow0 + jl;
