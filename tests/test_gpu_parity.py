@@ -213,14 +213,16 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
 
 @pytest.mark.parametrize("Hj,Hp,V,B,lo,hi", [(1088, 64, 300, 20, 20, 70), (2048, 128, 77, 17, 20, 70), (640, 64, 300, 20, 20, 70),
                                              (640, 128, 1500, 1, 20, 70), (1024, 64, 200, 3, 20, 70), (640, 64, 300, 2, 20, 70),
-                                             (1088, 64, 300, 72, 200, 240), (640, 128, 300, 20, 20, 70), (704, 192, 520, 3, 20, 70)])
+                                             (1088, 64, 300, 72, 200, 240), (640, 128, 300, 20, 20, 70), (704, 192, 520, 3, 20, 70),
+                                             (640, 64, 300, 300, 8, 30)])
 def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     """bf16 models away from the workloads' shapes: vocabularies whose column tiles are not a multiple of
     eight (the tile-to-workgroup mapping then takes its other form, and the padded workgroups must
     stay out), small D, E and Hp, joint hidden sizes above 1024 (the other variant of the near-tie
     path, none of the few-rows kernels), on every route: rows tiles, 256 x 256 tiles, the few-rows
-    kernel, the resident loop kernel; the last case is large enough (B * T >= 16384) for the encoder
-    projection's 256 x 256 tiles."""
+    kernel (option tiny_rows), the resident loop kernel; one case is large enough (B * T >= 16384) for the
+    encoder projection's 256 x 256 tiles, the last has more utterances (300) than any workload: that many
+    workgroups claim their places in the lists."""
     # the last two cases: three LSTM layers on the tile kernels, and an embedding wider than the LSTM
     # with two layers on the few-rows route
     L, E = (3, 64) if Hp == 128 and V == 300 else (2, 128) if Hp == 192 else (1, 64)
@@ -230,9 +232,10 @@ def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     enc, lens = wi.make_batch(cfg)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     first = None
-    for W, split in ((8, None), (2, None), (16, 0)):
+    for W, split, tiny in ((8, None, 0), (2, None, 0), (16, 0, 0), (8, None, 64)):
         if split is not None:
             m.set_option("joint_split_rows", split)
+        m.set_option("tiny_rows", tiny)
         toks, frs = m.decode(d_enc, d_len, W, cfg.S)
         check_outputs(cfg, lens, toks, frs)
         excl = compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP)
