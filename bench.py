@@ -292,6 +292,20 @@ def main():
         line["graph_ablation"] = graph_ablation(torch, wi, WindModel, max(1, min(args.steps, 3)), 1)
         line["beam_scoring"] = beam_scoring(torch, wi, WindModel, args.steps)
         line["beam_search"] = beam_search(torch, wi, WindModel)
+    if not args.no_ablation:
+        # the two other batched workloads, whole calls (sequential = Algorithm 1, then their windows)
+        others = {}
+        for name in ("batch32", "lowblank_b256"):
+            if name in (args.workload, args.roofline_workload):
+                continue
+            ocfg, omodel, odev, oframes, ores, _ = run_workload(torch, wi, WindModel, name, None, 2, 1, with_sequential=True)
+            others[name] = {"frames_per_call": oframes,
+                            "ms_per_step": {k: round(v["ms_per_step"], 3) for k, v in ores.items()},
+                            "frames_per_s": {k: round(v["frames_per_s"], 1) for k, v in ores.items()}}
+            omodel.close()
+            del odev, omodel
+            torch.cuda.empty_cache()
+        line["other_workloads"] = others
     if not args.no_roofline:
         rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload, None,
                                                             max(1, min(args.steps, 3)), 1, with_sequential=False)
