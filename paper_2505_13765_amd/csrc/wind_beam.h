@@ -218,6 +218,16 @@ __global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float 
 #pragma unroll
       for (int g = 0; g < 4; ++g) acc[g][r] = 0.f;
     }
+    // lane r finishes row r: its additive term (layer 0: the label's row of emb_gates, which carries the
+    // input sums and both biases) and the parent's cell value are requested here, ahead of the dot
+    // products, so that they do not cost a round trip of their own at the end
+    float4 addv = make_float4(0.f, 0.f, 0.f, 0.f);
+    float cprev = 0.f;
+    if (lane < R && r0 + lane < rows) {
+      addv = *reinterpret_cast<const float4 *>(layer == 0 ? m.emb_gates + (size_t)tok(r0 + lane) * 4 * Hp + unit * 4
+                                                          : m.b_cat[layer] + unit * 4);
+      cprev = c[(size_t)parent(r0 + lane) * slot_sz + (size_t)layer * Hp + unit];
+    }
     if ((Hp & 7) == 0) {
       // eight weights of each gate row and eight inputs per lane and step: 16- and 32-byte loads
       for (int k = lane * 8; k < K; k += 512) {
@@ -255,15 +265,12 @@ __global__ __launch_bounds__(256) void beam_lstm_layer_kernel(ModelDev m, float 
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       if (lane == r && r0 + r < rows) {
-        // layer 0: the label's row of emb_gates carries the input sums and both biases
-        const float *add = layer == 0 ? m.emb_gates + (size_t)tok(r0 + r) * 4 * Hp + unit * 4 : m.b_cat[layer] + unit * 4;
-        const float ig = 1.f / (1.f + expf(-(acc[0][r] + add[0])));
-        const float fg = 1.f / (1.f + expf(-(acc[1][r] + add[1])));
-        const float gg = tanhf(acc[2][r] + add[2]);
-        const float og = 1.f / (1.f + expf(-(acc[3][r] + add[3])));
-        const size_t po = (size_t)parent(r0 + r) * slot_sz + (size_t)layer * Hp + unit;
+        const float ig = 1.f / (1.f + expf(-(acc[0][r] + addv.x)));
+        const float fg = 1.f / (1.f + expf(-(acc[1][r] + addv.y)));
+        const float gg = tanhf(acc[2][r] + addv.z);
+        const float og = 1.f / (1.f + expf(-(acc[3][r] + addv.w)));
         const size_t co = (size_t)child(r0 + r) * slot_sz + (size_t)layer * Hp + unit;
-        const float cn = fg * c[po] + ig * gg;
+        const float cn = fg * cprev + ig * gg;
         c[co] = cn;
         h[co] = og * tanhf(cn);
       }
