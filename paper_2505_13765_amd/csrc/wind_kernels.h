@@ -1970,10 +1970,16 @@ struct LoopShared {
   int n_act, n_emit, ok;
 };
 
-// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: 32 rows of Hj+8 bf16][hhi, hlo: B*Hp bf16 each]
+// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: 32 rows of Hj+8 bf16, at least 16 KB][hhi, hlo: B*Hp bf16 each]
 //      [pfull: B*Hj f32][cst: B*upw f32]
+// bf16 elements of the window-row region zs.  The region also takes the K-split partial sums of the MFMA
+// phase (4 waves x 16 registers x 64 lanes of fp32 = 16 KB), which is the larger of the two for Hj < 248.
+__host__ __device__ inline size_t loop_z_elems(int Hj) {
+  const size_t z = (size_t)kLoopRows * (Hj + 8);
+  return z > 8192 ? z : 8192;
+}
 __host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw) {
-  return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + (size_t)kLoopRows * (Hj + 8) * 2 + (size_t)B * Hp * 4 +
+  return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + loop_z_elems(Hj) * 2 + (size_t)B * Hp * 4 +
          (size_t)B * Hj * 4 + (size_t)B * upw * 4;
 }
 
@@ -2103,7 +2109,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   bf16_t *zs = wp + (size_t)lp.ppw * Hp;
   // the hidden vectors as bf16 hi + lo (hi = RNE(h), lo = RNE(h - hi), 16 mantissa bits together): the dot
   // products with the bf16 weights then take one packed instruction per pair and part, with nothing to unpack
-  bf16_t *hhi = zs + (size_t)kLoopRows * zstride, *hlo = hhi + (size_t)B * Hp;
+  bf16_t *hhi = zs + loop_z_elems(Hj), *hlo = hhi + (size_t)B * Hp;
   float *pfull = reinterpret_cast<float *>(hlo + (size_t)B * Hp);
   auto put_h2 = [&](int i, float2 v) {   // elements i (even) and i + 1
     const uint32_t hb = pack_bf16x2(v.x, v.y);

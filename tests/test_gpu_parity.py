@@ -214,7 +214,7 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
 @pytest.mark.parametrize("Hj,Hp,V,B,lo,hi", [(1088, 64, 300, 20, 20, 70), (2048, 128, 77, 17, 20, 70), (640, 64, 300, 20, 20, 70),
                                              (640, 128, 1500, 1, 20, 70), (1024, 64, 200, 3, 20, 70), (640, 64, 300, 2, 20, 70),
                                              (1088, 64, 300, 72, 200, 240), (640, 128, 300, 20, 20, 70), (704, 192, 520, 3, 20, 70),
-                                             (640, 64, 300, 300, 8, 30)])
+                                             (640, 64, 300, 300, 8, 30), (64, 64, 77, 2, 6, 61), (128, 128, 500, 1, 20, 70)])
 def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     """bf16 models away from the workloads' shapes: vocabularies whose column tiles are not a multiple of
     eight (the tile-to-workgroup mapping then takes its other form, and the padded workgroups must
@@ -222,7 +222,9 @@ def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     path, none of the few-rows kernels), on every route: rows tiles, 256 x 256 tiles, the few-rows
     kernel (option tiny_rows), the resident loop kernel; one case is large enough (B * T >= 16384) for the
     encoder projection's 256 x 256 tiles, the last has more utterances (300) than any workload: that many
-    workgroups claim their places in the lists."""
+    workgroups claim their places in the lists.  The two smallest run the resident loop kernel with a joint
+    hidden size whose window rows take less LDS than the kernel's partial sums (the region must be sized
+    for the larger of the two)."""
     # the last two cases: three LSTM layers on the tile kernels, and an embedding wider than the LSTM
     # with two layers on the few-rows route
     L, E = (3, 64) if Hp == 128 and V == 300 else (2, 128) if Hp == 192 else (1, 64)
