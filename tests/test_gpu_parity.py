@@ -253,6 +253,39 @@ def test_unusual_shapes_bf16(torch_cuda, Hj, Hp, V, B, lo, hi):
     m.close()
 
 
+def test_random_shapes_bf16(torch_cuda):
+    """Seeded random models and batches over the whole range of shapes the library accepts (hidden sizes from
+    64, vocabularies from 5 to 8192 labels, one to three LSTM layers, 1 to 70 utterances, windows 1 to 32,
+    empty utterances), each decoded on the default route and with the options that select the other
+    routes, against the oracle."""
+    rng = np.random.default_rng(20250513)
+    for case in range(16):
+        small = case % 2 == 0   # every other case in the resident loop kernel's range
+        Hj = int(rng.choice([64, 128, 192, 256, 640, 1024] if small else [64, 128, 320, 640, 1024, 1088, 1536]))
+        Hp = int(rng.choice([64, 128, 192, 640] if small else [64, 128, 192, 320]))
+        E = int(rng.choice([64, 128, 256]))
+        L = 1 if small else int(rng.choice([1, 2, 3]))
+        V = int(rng.choice([5, 31, 64, 77, 1024, 2000, 4097, 8192] if small else [5, 31, 77, 128, 300, 1024, 1500, 4097]))
+        B = int(rng.choice([1, 2] if small else [3, 5, 9, 17, 33, 70]))
+        W = int(rng.choice([1, 2, 3, 5, 8, 16, 32]))
+        S = int(rng.choice([1, 2, 4, 10]))
+        lo = int(rng.integers(0, 20))
+        hi = lo + int(rng.integers(1, 50))
+        cfg = wi.WindConfig("random", 500 + case, B, lo, hi, 64, E, L, Hp, Hj, V, "bf16", (W,), S, 0.7)
+        w = wi.make_weights(cfg, blank_bias=float(rng.choice([0.5, 2.0, 4.0])), pred_gain=4.0)
+        m, o, _ = load(cfg, w)
+        enc, lens = wi.make_batch(cfg)
+        d_enc, d_len = to_dev(torch_cuda, enc, lens)
+        print(f"random shapes {case}: Hj={Hj} Hp={Hp} E={E} L={L} V={V} B={B} W={W} S={S} lengths {lo}..{hi}", flush=True)
+        for opts in ({}, {"loop_kernel": 0, "lstm_rec": 0, "atomic_lists": 0}, {"loop_kernel": 0, "tiny_rows": 64}):
+            for k, v in {"loop_kernel": 1, "lstm_rec": 1, "atomic_lists": 1, "tiny_rows": 0, **opts}.items():
+                m.set_option(k, v)
+            toks, frs = m.decode(d_enc, d_len, W, S)
+            check_outputs(cfg, lens, toks, frs)
+            assert compare_batch(o, enc, lens, S, toks, frs, tol=TOL_GAP) <= 2 + int(lens.sum()) // 2000, (case, opts)
+        m.close()
+
+
 def test_workspace_query_matches_the_shapes(torch_cuda):
     """wind_workspace_bytes: at least the buffers whose sizes the header names (fp32 encoder projections of
     every frame, bf16 window rows), growing with every argument, and rejecting shapes out of range."""
