@@ -272,20 +272,34 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
   const float *pr = c.p + (size_t)b * Hj;
   bf16_t *zr = c.z + (size_t)row * Hj;
   float dot = 0.f, nrm = 0.f;
-  for (int k = lane * 4; k < Hj; k += 256) {
-    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (valid) {
-      const float4 ev = *reinterpret_cast<const float4 *>(er + k);
-      const float4 pv = *reinterpret_cast<const float4 *>(pr + k);
-      x.x = fmaxf(ev.x + pv.x, 0.f); x.y = fmaxf(ev.y + pv.y, 0.f);
-      x.z = fmaxf(ev.z + pv.z, 0.f); x.w = fmaxf(ev.w + pv.w, 0.f);
+  // 1024 hidden units per pass: the pass's twelve loads per lane go out together (one round trip)
+  for (int k0 = lane * 4; k0 < Hj; k0 += 1024) {
+    float4 ev[4], pv[4], wb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int k = k0 + 256 * i;
+      ev[i] = pv[i] = wb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k < Hj) {
+        wb[i] = *reinterpret_cast<const float4 *>(m.w_blank + k);
+        if (valid) {
+          ev[i] = *reinterpret_cast<const float4 *>(er + k);
+          pv[i] = *reinterpret_cast<const float4 *>(pr + k);
+        }
+      }
     }
-    const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
-    dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot);
-    dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
-    nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm);
-    nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
-    *reinterpret_cast<uint2 *>(zr + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int k = k0 + 256 * i;
+      if (k >= Hj) continue;
+      float4 x;   // invalid rows: e and p were left at zero
+      x.x = fmaxf(ev[i].x + pv[i].x, 0.f); x.y = fmaxf(ev[i].y + pv[i].y, 0.f);
+      x.z = fmaxf(ev[i].z + pv[i].z, 0.f); x.w = fmaxf(ev[i].w + pv[i].w, 0.f);
+      dot = fmaf(x.x, wb[i].x, dot); dot = fmaf(x.y, wb[i].y, dot);
+      dot = fmaf(x.z, wb[i].z, dot); dot = fmaf(x.w, wb[i].w, dot);
+      nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm);
+      nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+      *reinterpret_cast<uint2 *>(zr + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+    }
   }
   dot = wave_sum(dot);
   nrm = wave_sum(nrm);
@@ -1073,15 +1087,30 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
     if (c.rec == nullptr || tok < 0 || threadIdx.x < first) return;
     const int b = st.x, Hp = m.Hp;
     const float *xg = m.emb_gates + (size_t)tok * 4 * Hp, *rg = c.rec + (size_t)b * 4 * Hp;
-    for (int u = threadIdx.x - first; u < Hp; u += nthreads) {
-      const float4 x = *reinterpret_cast<const float4 *>(xg + 4 * u), r = *reinterpret_cast<const float4 *>(rg + 4 * u);
-      const size_t si = (size_t)b * Hp + u;
-      const float cp = c.c[si];
-      const float ig = 1.f / (1.f + expf(-(r.x + x.x))), fg = 1.f / (1.f + expf(-(r.y + x.y)));
-      const float og = 1.f / (1.f + expf(-(r.w + x.w)));
-      const float cn = fg * cp + ig * tanhf(r.z + x.z);
-      c.c[si] = cn;
-      store_hi_lo(c.hb_hi, c.hb_lo, si, og * tanhf(cn));
+    // up to four units per thread and pass, their loads requested together (one round trip per pass)
+    for (int u0 = threadIdx.x - first; u0 < Hp; u0 += 4 * nthreads) {
+      float4 x[4], r[4];
+      float cp[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int u = u0 + i * nthreads;
+        if (u < Hp) {
+          x[i] = *reinterpret_cast<const float4 *>(xg + 4 * u);
+          r[i] = *reinterpret_cast<const float4 *>(rg + 4 * u);
+          cp[i] = c.c[(size_t)b * Hp + u];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int u = u0 + i * nthreads;
+        if (u >= Hp) continue;
+        const size_t si = (size_t)b * Hp + u;
+        const float ig = 1.f / (1.f + expf(-(r[i].x + x[i].x))), fg = 1.f / (1.f + expf(-(r[i].y + x[i].y)));
+        const float og = 1.f / (1.f + expf(-(r[i].w + x[i].w)));
+        const float cn = fg * cp[i] + ig * tanhf(r[i].z + x[i].z);
+        c.c[si] = cn;
+        store_hi_lo(c.hb_hi, c.hb_lo, si, og * tanhf(cn));
+      }
     }
   };
   if (c.lists_atomic) {
