@@ -1844,6 +1844,11 @@ __device__ __forceinline__ void lstm_rec_tile(const ModelDev &m, const CallDev &
   constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
   const int Hp = m.Hp, in = layer == 0 ? 0 : Hp, K = in + Hp;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the utterances of this thread's rows in the epilogue, requested ahead of the tile core
+  constexpr int EPI = (R * UB + Cfg::NT - 1) / Cfg::NT;
+  int ub_e[EPI];
+#pragma unroll
+  for (int q = 0; q < EPI; ++q) ub_e[q] = c.emit_idx[min(row0 + min((tid + q * Cfg::NT) / UB, R - 1), c.B - 1)];
   PredRows<Cfg> rows;
   rows.kin = 0;
 #pragma unroll
@@ -1874,12 +1879,13 @@ __device__ __forceinline__ void lstm_rec_tile(const ModelDev &m, const CallDev &
       for (int r = 0; r < 16; ++r)
         tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
   __syncthreads();
-  for (int idx = tid; idx < R * UB; idx += Cfg::NT) {
-    const int r = idx / UB, u = idx - r * UB;
-    if (row0 + r >= n_emit) continue;
+#pragma unroll
+  for (int q = 0; q < EPI; ++q) {
+    const int idx = tid + q * Cfg::NT, r = idx / UB, u = idx - r * UB;
+    if (idx >= R * UB || row0 + r >= n_emit) continue;
     const float *hi = tile + r * TS + u, *lo = tile + (R + r) * TS + u;
     const float4 g = make_float4(hi[0] + lo[0], hi[UB] + lo[UB], hi[2 * UB] + lo[2 * UB], hi[3 * UB] + lo[3 * UB]);
-    *reinterpret_cast<float4 *>(c.rec + ((size_t)layer * c.B + c.emit_idx[row0 + r]) * 4 * Hp + n0 + 4 * u) = g;
+    *reinterpret_cast<float4 *>(c.rec + ((size_t)layer * c.B + ub_e[q]) * 4 * Hp + n0 + 4 * u) = g;
   }
 }
 
@@ -1913,6 +1919,15 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, Call
     return;
   }
   if (row0 < n_emit) {
+    // epilogue inputs, requested ahead of the tile core: this thread's column bias and the utterances of
+    // its rows (a thread keeps one column and every (NT / BN)-th row)
+    static_assert(Cfg::NT % Cfg::BN == 0 && R % (Cfg::NT / Cfg::BN) == 0, "epilogue mapping");
+    constexpr int RSTEP = Cfg::NT / Cfg::BN, RPT = R / RSTEP;
+    const int ecol = tid % Cfg::BN, erow = tid / Cfg::BN;
+    const float bias_e = n0 + ecol < m.Hj ? m.b_pred[n0 + ecol] : 0.f;
+    int ub_e[RPT];
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) ub_e[q] = c.emit_idx[min(row0 + erow + q * RSTEP, c.B - 1)];
     const size_t top = (size_t)(m.L - 1) * c.B * Hp;
     PredRows<Cfg> rows;
     rows.kin = 0;
@@ -1943,10 +1958,11 @@ __global__ __launch_bounds__(Cfg::NT) void pred_proj_dma_kernel(ModelDev m, Call
         for (int r = 0; r < 16; ++r)
           tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
     __syncthreads();
-    for (int idx = tid; idx < R * Cfg::BN; idx += Cfg::NT) {
-      const int r = idx / Cfg::BN, col = idx - r * Cfg::BN;
-      if (row0 + r >= n_emit || n0 + col >= m.Hj) continue;
-      c.p[(size_t)c.emit_idx[row0 + r] * m.Hj + n0 + col] = tile[r * TS + col] + tile[(R + r) * TS + col] + m.b_pred[n0 + col];
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) {
+      const int r = erow + q * RSTEP;
+      if (row0 + r >= n_emit || n0 + ecol >= m.Hj) continue;
+      c.p[(size_t)ub_e[q] * m.Hj + n0 + ecol] = tile[r * TS + ecol] + tile[(R + r) * TS + ecol] + bias_e;
     }
   }
   if (!pre) {  // commit the new hidden vectors (hi and lo): every layer has read the old ones by now.  Last,
