@@ -433,14 +433,14 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
   } else if (m->dtype == WIND_BF16) {
     launch(m, s, WIND_K_BUILD_Z, capturing, build_z_kernel, dim3((unsigned)((max_rows + 3) / 4)), dim3(256), 0, d, c, parity);
     {
-      // one launch, two groups of workgroups: the rows path (rows <= joint_split_rows) and the 256 x 256 tiles
+      // one launch for both tile shapes: the rows path (rows <= joint_split_rows) or the 256 x 256 tiles
       const int small_rows = max_rows < c.joint_split_rows ? max_rows : c.joint_split_rows;
       const int NT = (d.V + JointRows1::BN - 1) / JointRows1::BN;
       const int gx = small_rows > 0 ? joint_rows_grid_x(NT, small_rows) : 0;
       const int rows_blocks = (gx * NT + 7) / 8 * 8;
       int big_mt = 0, big_nt = (d.V + JointBigCfg::BN - 1) / JointBigCfg::BN;
       if (max_rows > c.joint_split_rows) big_mt = (max_rows + JointBigCfg::BM - 1) / JointBigCfg::BM;
-      launch(m, s, WIND_K_JOINT, capturing, joint_kernel<JointBigCfg>, dim3((unsigned)(rows_blocks + big_mt * big_nt)),
+      launch(m, s, WIND_K_JOINT, capturing, joint_kernel<JointBigCfg>, dim3((unsigned)std::max(rows_blocks, big_mt * big_nt)),
              dim3(JointBigCfg::NT), JointBigCfg::SMEM_BYTES, d, c, parity, gx, NT, rows_blocks, big_mt, big_nt);
     }
     if (d.Hj <= 1024)

@@ -439,10 +439,10 @@ __device__ __forceinline__ void joint_big_tile(const ModelDev &m, const CallDev 
   joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);   // rows of keys are c.nparts pairs apart for both shapes
 }
 
-// One launch per iteration carries both tile shapes: the first rows_blocks workgroups (a multiple
-// of 8) form the GX x NT grid of the rows path and use four of their eight waves, the others the
-// grid of 256 x 256 tiles.  The iteration's row count decides which of the two groups works; the
-// other group's workgroups return at once.
+// One launch per iteration serves both tile shapes: the iteration's row count decides whether the
+// workgroups form the GX x NT grid of the rows path (rows_blocks of them, using four of their eight
+// waves) or the grid of 256 x 256 tiles; the launch has as many workgroups as the larger of the two
+// grids, and those past the grid in use return at once.
 template <class BigCfg>
 __global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int parity, int rows_gx, int rows_nt,
                                                     int rows_blocks, int big_mt, int big_nt) {
@@ -451,8 +451,8 @@ __global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int p
   const int n_rows = c.n_active[parity] * c.W;
   if (n_rows == 0) return;
   int mt, nt;
-  if ((int)blockIdx.x < rows_blocks) {
-    if (n_rows > c.joint_split_rows || threadIdx.x >= 256) return;
+  if (n_rows <= c.joint_split_rows) {
+    if ((int)blockIdx.x >= rows_blocks || threadIdx.x >= 256) return;
     joint_tile_of_block((int)blockIdx.x, rows_gx, rows_nt, mt, nt);
     if (mt >= rows_gx || nt >= rows_nt) return;   // padding of the group to a multiple of 8 (either mapping)
     const int mi = (n_rows + 64 * rows_gx - 1) / (64 * rows_gx);   // <= 4 by the host's choice of rows_gx
@@ -463,8 +463,8 @@ __global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int p
       default: joint_rows_tile<4>(m, c, n_rows, mt, nt, smem_raw); break;
     }
   } else {
-    if (n_rows <= c.joint_split_rows) return;
-    joint_tile_of_block((int)blockIdx.x - rows_blocks, big_mt, big_nt, mt, nt);
+    if ((int)blockIdx.x >= big_mt * big_nt) return;
+    joint_tile_of_block((int)blockIdx.x, big_mt, big_nt, mt, nt);
     joint_big_tile<BigCfg>(m, c, n_rows, mt, nt, smem_raw);
   }
 }
