@@ -389,7 +389,10 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first =
 int enqueue_prologue(wind_model *m, hipStream_t s) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
-  init_state_kernel<<<1, 256, 0, s>>>(d, c);
+  {
+    const size_t nstate = (size_t)d.L * c.B * d.Hp;
+    init_state_kernel<<<(unsigned)std::min<size_t>(64, (nstate + 4095) / 4096 + 1), 256, 0, s>>>(d, c);
+  }
   if (c.T > 0) {
     if (m->dtype == WIND_BF16 && c.enc_b) {
       const long long rows = (long long)c.B * c.T;

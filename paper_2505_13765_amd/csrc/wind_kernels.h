@@ -106,12 +106,14 @@ struct CallDev {
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) {
   const int tid = threadIdx.x;
-  for (int i = tid; i < kNumStats; i += 256) c.stats[i] = 0ull;
+  // every workgroup zeroes its share of the prediction-network state; the first also builds the lists
   const size_t nstate = (size_t)m.L * c.B * m.Hp;
-  for (size_t i = tid; i < nstate; i += 256) {
+  for (size_t i = (size_t)blockIdx.x * 256 + tid; i < nstate; i += (size_t)gridDim.x * 256) {
     c.h[i] = 0.f; c.c[i] = 0.f; c.hn[i] = 0.f;
     c.hb_hi[i] = 0; c.hb_lo[i] = 0; c.hbn_hi[i] = 0; c.hbn_lo[i] = 0;
   }
+  if (blockIdx.x != 0) return;
+  for (int i = tid; i < kNumStats; i += 256) c.stats[i] = 0ull;
   for (int b = tid; b < c.B; b += 256) {
     int len = c.lengths[b];
     len = len < 0 ? 0 : (len > c.T ? c.T : len);
