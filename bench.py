@@ -313,6 +313,19 @@ def main():
         roof["frames_per_s"] = {k: round(v["frames_per_s"], 1) for k, v in rres.items()}
         roof["ms_per_step"] = {k: round(v["ms_per_step"], 3) for k, v in rres.items()}
         line["roofline"] = roof
+        if not args.no_ablation:
+            # what the two shortenings of the per-iteration kernel chain are worth on this workload
+            # (options "lstm_rec" and "atomic_lists"), whole calls at the roofline window
+            abl = {}
+            for key, opts in (("default", {}), ("whole_lstm_steps", {"lstm_rec": 0}), ("compacted_lists", {"atomic_lists": 0}),
+                              ("both_off", {"lstm_rec": 0, "atomic_lists": 0})):
+                for k, v in {"lstm_rec": 1, "atomic_lists": 1, **opts}.items():
+                    rmodel.set_option(k, v)
+                sec = timed_decodes(torch, rmodel, rdev[0], rdev[1], args.roofline_window, rcfg.S, 2, 1, rdev[2])
+                abl[key] = round(sec * 1e3, 3)
+            rmodel.set_option("lstm_rec", 1)
+            rmodel.set_option("atomic_lists", 1)
+            line["chain_ablation"] = {"workload": f"{rcfg.name} W={args.roofline_window}", "unit": "ms per decode call", **abl}
         rmodel.close()
     print(json.dumps(line))
 
