@@ -9,14 +9,20 @@
 //                  count, and 256 x 256 tiles for the iterations with many rows
 //   decide         per utterance: row argmax from the keys, near-ties re-decided with fp32 dot
 //                  products, first non-blank row by wavefront ballot, pointer / hypothesis update,
-//                  and (last workgroup) the next iteration's slot table and the emit list
-//   lstm_layer xL  one prediction-network step for the utterances that emitted
-//   pred_proj      p = W_pred h + b_pred for those utterances
-// With at most 64 window rows, build_z + joint + decide are one kernel (joint_tiny).  The
-// prediction network has three implementations: MFMA tiles with the hidden state split into bf16
-// hi + lo (large batches), low-latency wave-per-unit kernels (a few utterances), generic FMA (fp32
-// models and everything else).  fp32 models replace build_z + joint by joint_exact (fp32 FMA,
-// argmax taken directly).
+//                  the utterance's place in the next iteration's slot table and in the emit list
+//                  (claimed with atomic counters), and the first LSTM layer's step for the label
+//                  (elementwise, on top of the recurrent gate sums kept in CallDev::rec)
+//   lstm_layer     the layers above the first, for the utterances that emitted: their input half
+//   pred_proj      p = W_pred h + b_pred for those utterances; the same launch renews the
+//                  recurrent gate sums of every layer for them
+// Optionally (CallDev::rec null, lists_atomic 0) the steps are whole LSTM steps after the decision
+// and the last workgroup of decide compacts the lists in order.  With at most 64 window rows,
+// build_z + joint + decide can run as one kernel (joint_tiny; off by default).  The prediction
+// network has three implementations: MFMA tiles with the hidden state split into bf16 hi + lo,
+// low-latency wave-per-unit kernels (the start-token step of the resident loop kernel), generic FMA
+// (fp32 models).  fp32 models replace build_z + joint by joint_exact (fp32 FMA, argmax taken
+// directly).  One or two utterances of a one-layer model run the whole loop as one resident
+// kernel (wind_loop_kernel).
 #pragma once
 #include "wind_mfma.h"
 #include "wind_mfma_dma.h"
