@@ -88,8 +88,22 @@ def roofline_leg(torch, cfg, model, dev, W):
     model.greedy_decode(d_enc, d_len, W, cfg.S, *out)
     st = model.stats()
     kt = model.kernel_times()
+    rows_l, us_l = model.joint_launches()
     model.set_option("profile", 0)
     ms, n = kt["joint"]
+    # the same figure by row count: launches of the decode binned by the window rows they evaluated
+    per_row = 2.0 * cfg.Hj * (cfg.V + 1)
+    edges = [0, 128, 256, 384, 512, 768, 1024, 1280, 1536, 1792, 2048, 3072, 4096]
+    buckets = []
+    for lo, hi in zip(edges[:-1], edges[1:]):
+        sel = [(r, u) for r, u in zip(rows_l, us_l) if lo < r <= hi]
+        if not sel:
+            continue
+        r_sum, u_sum = sum(r for r, _ in sel), sum(u for _, u in sel)
+        tf = per_row * r_sum / (u_sum * 1e-6) / 1e12
+        buckets.append({"rows": f"{lo + 1}-{hi}", "launches": len(sel), "avg_rows": round(r_sum / len(sel), 1),
+                        "avg_us": round(u_sum / len(sel), 2), "share_of_time": round(u_sum / max(sum(us_l), 1e-9), 3),
+                        "tflops": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 3)})
     flops = 2.0 * cfg.Hj * (cfg.V + 1) * st.rows
     achieved = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
     # bytes the joint kernel must move per launch: W_out once, the window rows once, the keys out
@@ -100,6 +114,7 @@ def roofline_leg(torch, cfg, model, dev, W):
         "rows_per_launch": st.rows / max(n, 1), "flops_per_row": 2.0 * cfg.Hj * (cfg.V + 1),
         "kernel_ms": {k: round(v[0], 3) for k, v in kt.items()},
         "kernel_launches": {k: int(v[1]) for k, v in kt.items()},
+        "by_rows": buckets,
     }
 
 

@@ -232,6 +232,16 @@ typedef enum {
 int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
 
 /*
+ * The joint kernel launch by launch, for the roofline report: after a decode call made with option
+ * "profile" = 1 (bf16 models), rows[i] is the number of window rows that loop iteration i
+ * evaluated (the sum of n = min(W, len - t) over its active utterances; Algorithm 2) and us[i] the
+ * duration of that iteration's joint launch in microseconds.  HOST arrays of `cap` entries; *n
+ * receives the number of iterations recorded (at most 16384), of which the first min(*n, cap) are
+ * written.  WIND_ERR_ARG for null pointers.
+ */
+int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, int *n);
+
+/*
  * Tuning knobs, for benchmarks and tests.  key/value pairs:
  *   "graph"   1 (default): the decode loop is replayed from a captured HIP graph; 0: kernels are
  *             launched one by one (the with / without graph rows of Table 5)

@@ -16,7 +16,8 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0
 
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
-           "wind_get_kernel_times", "wind_beam_window_scores", "wind_beam_decode", "wind_workspace_bytes")
+           "wind_get_kernel_times", "wind_get_joint_launches", "wind_beam_window_scores", "wind_beam_decode",
+           "wind_workspace_bytes")
 PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
 
@@ -86,6 +87,8 @@ def load_library():
                                                 C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         lib.wind_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
         lib.wind_get_kernel_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        lib.wind_get_joint_launches.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int,
+                                                C.POINTER(C.c_int)]
         lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.wind_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
@@ -194,6 +197,15 @@ class WindModel:
         n = (C.c_int64 * len(KERNEL_NAMES))()
         _check(self._lib.wind_get_kernel_times(self._h, ms, n))
         return {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_NAMES)}
+
+    def joint_launches(self):
+        """(rows, us) of every joint launch of the last decode made with option "profile" = 1."""
+        n = C.c_int(0)
+        _check(self._lib.wind_get_joint_launches(self._h, (C.c_int32 * 1)(), (C.c_float * 1)(), 0, C.byref(n)))
+        rows = (C.c_int32 * max(n.value, 1))()
+        us = (C.c_float * max(n.value, 1))()
+        _check(self._lib.wind_get_joint_launches(self._h, rows, us, n.value, C.byref(n)))
+        return list(rows[:n.value]), list(us[:n.value])
 
     def beam_window_scores(self, enc_window, dec_out, K: int, out=None):
         """wind_beam_window_scores on device tensors enc_window [n, D] and dec_out [Bh, Hp] (fp32).

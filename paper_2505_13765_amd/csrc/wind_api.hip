@@ -46,6 +46,7 @@ using EncCfg = TileCfg<128, 128, 64, 64>;
 using PredCfg = DmaCfg<64, 64, 32, 32, 64, 4>;   // 32 utterances (hi and lo rows) x 64 columns, 4-stage ring
 constexpr int kPredMfmaMinBatch = 1;       // below this the FMA prediction network is used
 constexpr size_t kEncRing5MinRows = 16384;   // B * T from which the encoder projection uses 256 x 256 tiles
+constexpr int kIterRowsCap = 16384;   // iterations whose row counts profile mode records
 constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height, plus one block
 
 // Row tiles of joint_rows_kernel for a vocabulary of NT 128-column tiles and at most `rows` window
@@ -113,6 +114,7 @@ struct wind_model {
   int opt_graph = 1, opt_unroll = 16;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_joint_split_rows = -1;   // -1: joint_split_default(V)
+  int opt_joint_ws = 1;            // the joint kernel whose waves are split into multipliers and fetchers
   int opt_tiny_rows = kTinyRowsDefault;
   int opt_loop_kernel = 1;
   long long opt_loop_spin_limit = 1ll << 21;
@@ -138,6 +140,8 @@ struct wind_model {
   std::vector<int> ev_kind;   // kind of pair i (events 2i, 2i+1)
   double prof_ms[WIND_NUM_KERNELS] = {0};
   long long prof_n[WIND_NUM_KERNELS] = {0};
+  std::vector<float> joint_us;      // last profiled decode: duration of every joint launch, in launch order
+  std::vector<int> joint_rows;      // and the window rows of its iteration
 };
 
 namespace {
@@ -178,7 +182,7 @@ struct WsLayout {
   bool big_enc;
   int slot_stride, nparts, nparts_big, nparts_tiny;
   size_t o_e, o_encb, o_len, o_nact, o_eidx, o_eltok, o_slot, o_slotc, o_rst, o_raux, o_nemit, o_ticket, o_h, o_c, o_hn, o_hb,
-      o_hz, o_rec, o_p, o_z, o_bl, o_zn, o_parts, o_rl, o_stats, o_dbg, o_lbar, o_lh, o_lp, o_lparts;
+      o_hz, o_rec, o_p, o_z, o_bl, o_zn, o_parts, o_rl, o_stats, o_dbg, o_iter, o_lbar, o_lh, o_lp, o_lparts;
 };
 
 bool tiny_rows_ok(const wind_model *m, int max_rows);
@@ -219,6 +223,7 @@ WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   w.o_rl = take(w.Mpad * 4);
   w.o_stats = take(kNumStats * 8);
   w.o_dbg = take(128);
+  w.o_iter = take((size_t)kIterRowsCap * 4);
   w.o_lbar = take((size_t)(1 + 256) * kLoopFlagStride * 4); w.o_lh = take((size_t)kLoopMaxB * d.Hp * 4);
   w.o_lp = take((size_t)kLoopMaxB * d.Hj * 4);
   w.o_lparts = take((size_t)2 * kLoopRows * w.nparts_tiny * 8);
@@ -275,11 +280,14 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.part_width = JointRows1::WN;
   c.nparts_big = nparts_big;
   c.part_width_big = JointBigCfg::WN;
-  c.joint_split_rows = m->opt_joint_split_rows >= 0 ? m->opt_joint_split_rows : joint_split_default(d.V);
+  c.joint_split_rows = m->opt_joint_ws ? (1 << 30)   // one key format at every row count
+                       : m->opt_joint_split_rows >= 0 ? m->opt_joint_split_rows : joint_split_default(d.V);
   c.nparts_tiny = nparts_tiny;
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
   c.dbg = m->opt_debug_stamps ? (long long *)(base + o_dbg) : nullptr;
+  c.iter_rows = m->opt_profile ? (int *)(base + w.o_iter) : nullptr;
+  c.iter_rows_cap = kIterRowsCap;
   c.lists_atomic = m->opt_atomic_lists && m->dtype == WIND_BF16 && !tiny_rows_ok(m, B * W);   // the path with build_z_kernel
   m->loop.bar = (unsigned *)(base + o_lbar);
   m->loop.h_x = (float *)(base + o_lh);
@@ -325,6 +333,7 @@ void prof_collect(wind_model *m) {
     if (hipEventElapsedTime(&ms, m->ev_pool[2 * i], m->ev_pool[2 * i + 1]) == hipSuccess) {
       m->prof_ms[m->ev_kind[i]] += ms;
       m->prof_n[m->ev_kind[i]] += 1;
+      if (m->ev_kind[i] == WIND_K_JOINT) m->joint_us.push_back(ms * 1000.f);
     }
   }
   m->ev_kind.clear();
@@ -435,7 +444,12 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
            tiny_smem_bytes(d, max_rows), d, c, parity);
   } else if (m->dtype == WIND_BF16) {
     launch(m, s, WIND_K_BUILD_Z, capturing, build_z_kernel, dim3((unsigned)((max_rows + 3) / 4)), dim3(256), 0, d, c, parity);
-    {
+    if (m->opt_joint_ws) {
+      // fill x NT workgroups, each walking as many row tiles as the iteration's row count needs
+      const int NT = (d.V + 127) / 128, fill = NT >= 256 ? 1 : 256 / NT;
+      launch(m, s, WIND_K_JOINT, capturing, joint_ws_kernel, dim3((unsigned)((fill * NT + 7) / 8 * 8)), dim3(512), kWsSmemBytes, d, c,
+             parity, fill, NT);
+    } else {
       // one launch for both tile shapes: the rows path (rows <= joint_split_rows) or the 256 x 256 tiles
       const int small_rows = max_rows < c.joint_split_rows ? max_rows : c.joint_split_rows;
       const int NT = (d.V + JointRows1::BN - 1) / JointRows1::BN;
@@ -581,6 +595,8 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   }
   const int U = m->opt_unroll;
   const bool use_graph = m->opt_graph && !m->opt_profile;   // events cannot sit between graph nodes
+  m->joint_us.clear();
+  m->joint_rows.clear();
   if (use_graph) {
     rc = ensure_graph(m);
     if (rc) return rc;
@@ -610,6 +626,11 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     if (launches > max_launches) return fail(WIND_ERR_HIP, "decode loop did not terminate");
   }
   rc = fetch_stats(m, s);
+  if (c.iter_rows && (rc == WIND_OK || rc == WIND_ERR_OVERFLOW)) {
+    const size_t n = (size_t)std::min<long long>(m->last_stats.iterations, kIterRowsCap);
+    m->joint_rows.resize(n);
+    if (n) HIP_TRY(hipMemcpy(m->joint_rows.data(), c.iter_rows, n * sizeof(int), hipMemcpyDeviceToHost));
+  }
   m->prev_B = B; m->prev_T = T; m->prev_W = W;
   m->prev_iters = m->last_stats.iterations;
   if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
@@ -738,6 +759,8 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
     hipError_t e = hipFuncSetAttribute((const void *)joint_kernel<JointBigCfg>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, JointBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
+    if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               m->dev.Hj <= kTinyMaxHj ? (int)tiny_smem_bytes(m->dev, 64) : 32768);   // unused above that size
     if (e == hipSuccess)
@@ -844,6 +867,16 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches) {
   return WIND_OK;
 }
 
+int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, int *n) {
+  if (!m || !rows || !us || !n || cap < 0) return fail(WIND_ERR_ARG, "null argument");
+  // launches past the last iteration found no active utterance and are left out
+  const size_t have = std::min(m->joint_rows.size(), m->joint_us.size());
+  const size_t k = std::min<size_t>(have, (size_t)cap);
+  for (size_t i = 0; i < k; ++i) { rows[i] = m->joint_rows[i]; us[i] = m->joint_us[i]; }
+  *n = (int)have;
+  return WIND_OK;
+}
+
 int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!m || !key) return fail(WIND_ERR_ARG, "null argument");
   if (!std::strcmp(key, "graph")) { m->opt_graph = value != 0; return WIND_OK; }
@@ -869,6 +902,11 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "tiny_rows")) {
     if (value < 0 || value > 64) return fail(WIND_ERR_ARG, "tiny_rows must be 0..64");
     m->opt_tiny_rows = (int)value;
+    m->graph_valid = false;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "joint_ws")) {
+    m->opt_joint_ws = value != 0;
     m->graph_valid = false;
     return WIND_OK;
   }

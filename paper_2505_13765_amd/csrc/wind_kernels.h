@@ -26,6 +26,7 @@
 #pragma once
 #include "wind_mfma.h"
 #include "wind_mfma_dma.h"
+#include "wind_mfma_ws.h"
 
 namespace wind {
 
@@ -107,6 +108,8 @@ struct CallDev {
   int *row_label;               // [Mpad] (fp32 models)
   unsigned long long *stats;    // [kNumStats]
   long long *dbg;               // optional [8] phase time stamps of the few-rows kernel's deciding workgroup (100 MHz clock)
+  int *iter_rows;               // optional [iter_rows_cap] window rows of every loop iteration, in order (profile mode)
+  int iter_rows_cap;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -272,6 +275,18 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
   const int4 st = c.slot_state[parity * c.slot_stride + a];   // same round trip as the count
   // the counters that this iteration's decision kernel adds to: every reader of their old values is done
   if (c.lists_atomic && blockIdx.x == 0 && threadIdx.x == 0) { c.n_active[parity ^ 1] = 0; *c.n_emit = 0; }
+  if (c.iter_rows && blockIdx.x == 0 && wave == 0 && na > 0) {
+    // profile mode: rows the method evaluates in this iteration = sum of n over the windows; iterations
+    // so far = the decision kernel's counter (complete: that kernel precedes this one in the stream)
+    int rows = 0;
+    for (int i = lane; i < na; i += 64) {
+      const int4 s = c.slot_state[parity * c.slot_stride + i];
+      rows += min(c.W, s.z - s.y);
+    }
+    rows = wave_sum_i32(rows);
+    const unsigned long long it = c.stats[ST_ITER];
+    if (lane == 0 && it < (unsigned long long)c.iter_rows_cap) c.iter_rows[it] = rows;
+  }
   if (a >= na) return;
   const int b = st.x, tt = st.y + j;
   const bool valid = tt < st.z;
@@ -433,7 +448,7 @@ __device__ __forceinline__ void joint_rows_tile(const ModelDev &m, const CallDev
 
 // 256 x 256 tiles on the five-slot ring (see gemm_mainloop_ring5), for iterations with more rows
 // than the rows path balances over the chip.
-template <class Cfg>
+template <class Cfg, bool WEAVE = false>
 __device__ __forceinline__ void joint_big_tile(const ModelDev &m, const CallDev &c, int n_rows, int mt, int nt,
                                                unsigned char *smem_raw) {
   const int row0 = mt * Cfg::BM;
@@ -442,8 +457,9 @@ __device__ __forceinline__ void joint_big_tile(const ModelDev &m, const CallDev 
   f32x16 acc[Cfg::MI][Cfg::NI];
   float bias[Cfg::NI][16];
   joint_load_bias<Cfg>(m, bias, n0);
-  gemm_mainloop_ring5<Cfg, true>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
-                                 smem_raw, acc, JointInitAcc<Cfg>{acc, bias});
+  gemm_mainloop_ring5<Cfg, true, JointInitAcc<Cfg>, WEAVE>(c.z + (size_t)row0 * Hj,
+                                                           reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
+                                                           smem_raw, acc, JointInitAcc<Cfg>{acc, bias});
   joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);   // rows of keys are c.nparts pairs apart for both shapes
 }
 
@@ -474,6 +490,82 @@ __global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int p
     if ((int)blockIdx.x >= big_mt * big_nt) return;
     joint_tile_of_block((int)blockIdx.x, big_mt, big_nt, mt, nt);
     joint_big_tile<BigCfg>(m, c, n_rows, mt, nt, smem_raw);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The joint kernel on the tile core whose waves are split into multipliers and fetchers
+// (wind_mfma_ws.h).  The launch has `fill` x NT workgroups, fill = row tiles that fill the chip for
+// NT column tiles.  Workgroup `lin` owns column tile nt(lin) whatever the row count, so a fetcher
+// requests the first stages of its W_out slice before it knows how many window rows the iteration
+// has; the row count then fixes the row tiles and their height:
+//   R <= 64 fill:  ceil(R / 64) row tiles of 64 rows (workgroups beyond them leave)
+//   else:          rounds = ceil(R / (256 fill)) row tiles per workgroup (mt, mt + fill, ...), each
+//                  64 MI rows high, MI = ceil(R / (64 fill rounds)) in 1..4
+// so every workgroup has the same work at any row count.  Between two tiles of a workgroup one
+// more barrier hands the LDS back to the fetchers, who request the next tile's first stages while
+// the multipliers reduce the finished tile to keys.
+template <int MI>
+__device__ __forceinline__ void joint_ws_tiles(const ModelDev &m, const CallDev &c, int n_rows, int mt0, int mt_step,
+                                               int mt_end, int nt, bool head_done, unsigned char *smem_raw) {
+  using Cfg = WsCfg<MI>;
+  const int n0 = nt * Cfg::BN, Hj = m.Hj;
+  const bf16_t *bw = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj;
+  if (threadIdx.x >= Cfg::NMUL * kWave) {
+    for (int mt = mt0; mt < mt_end && mt * Cfg::BM < n_rows; mt += mt_step) {
+      if (mt != mt0) __builtin_amdgcn_s_barrier();   // the multipliers are done with the LDS
+      if (mt != mt0 || !head_done) ws_fetch_b_head(bw, Hj, smem_raw);
+      ws_fetch<Cfg>(c.z + (size_t)mt * Cfg::BM * Hj, bw, Hj, smem_raw);
+    }
+    wait_vmcnt<0>();
+    return;
+  }
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  float bias[Cfg::NI][16];
+  joint_load_bias<Cfg>(m, bias, n0);
+  for (int mt = mt0; mt < mt_end && mt * Cfg::BM < n_rows; mt += mt_step) {
+    JointInitAcc<Cfg>{acc, bias}();
+    ws_multiply<Cfg, true>(Hj, smem_raw, acc);
+    const int mn = mt + mt_step;
+    if (mn < mt_end && mn * Cfg::BM < n_rows) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+    }
+    joint_keys_epilogue<Cfg>(c, acc, mt * Cfg::BM, nt, c.nparts);
+  }
+}
+
+__global__ __launch_bounds__(512) void joint_ws_kernel(ModelDev m, CallDev c, int parity, int fill, int NT) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int lin = (int)blockIdx.x;
+  const bool fetcher = threadIdx.x >= 4 * kWave;
+  const bool early = NT % 8 == 0;   // the column tile does not depend on the number of row tiles
+  int mt = 0, nt = 0;
+  if (early) {
+    joint_tile_of_block(lin, fill, NT, mt, nt);
+    if (fetcher) ws_fetch_b_head(reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)nt * 128 * m.Hj, m.Hj, smem_raw);
+  }
+  const int n_rows = c.n_active[parity] * c.W;
+  const int fine = (n_rows + 63) / 64;
+  int tiles, mi;   // row tiles in use, their height in units of 64 rows
+  if (fine <= fill) {
+    tiles = fine; mi = 1;
+  } else {
+    const int rounds = (n_rows + 256 * fill - 1) / (256 * fill);
+    tiles = fill * rounds;
+    mi = (n_rows + 64 * tiles - 1) / (64 * tiles);
+  }
+  const int mt_step = tiles < fill ? tiles : fill;
+  if (!early && mt_step > 0) joint_tile_of_block(lin, mt_step, NT, mt, nt);
+  if (n_rows == 0 || mt >= mt_step || nt >= NT) {
+    if (fetcher) wait_vmcnt<0>();
+    return;
+  }
+  switch (mi) {
+    case 1: joint_ws_tiles<1>(m, c, n_rows, mt, mt_step, tiles, nt, early, smem_raw); break;
+    case 2: joint_ws_tiles<2>(m, c, n_rows, mt, mt_step, tiles, nt, early, smem_raw); break;
+    case 3: joint_ws_tiles<3>(m, c, n_rows, mt, mt_step, tiles, nt, early, smem_raw); break;
+    default: joint_ws_tiles<4>(m, c, n_rows, mt, mt_step, tiles, nt, early, smem_raw); break;
   }
 }
 
