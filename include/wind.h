@@ -83,7 +83,8 @@ typedef struct {
 
 /*
  * Copies the weights to the GPU in the layouts the kernels want and returns a model handle.
- * The caller may free its arrays afterwards.  Limits: 1 <= L <= 4; D, E, Hp, Hj >= 1; V >= 1.
+ * Every copy and kernel of the call goes to `stream`, and the call returns after they have
+ * completed: the caller may free its arrays afterwards.  Limits: 1 <= L <= 4; D, E, Hp, Hj >= 1; V >= 1.
  * With WIND_BF16, D, E, Hp and Hj must be multiples of 64 and Hj <= 2048 (WIND_ERR_UNSUPPORTED otherwise).
  */
 int wind_load_weights(const wind_weights *w, void *stream, wind_model **out);
@@ -214,6 +215,30 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
                             void *stream);
 
 /*
+ * Debug: the encoder half of the joiner as a decode call computes it once per call,
+ * e[b, t, :] = W_enc enc_out[b, t, :] + b_enc (the joiner of Algorithms 1 and 2 is linear in the
+ * encoder frame up to its activation, so this half is hoisted out of the loop).  Writes DEVICE float
+ * e_out [B, T, Hj]; rows with t >= lengths[b] are unspecified.  enc_out DEVICE [B, T, D], lengths
+ * DEVICE [B].  Returns after completion.
+ */
+int wind_debug_enc_proj(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, float *e_out,
+                        void *stream);
+
+/*
+ * Debug: what the joint kernel of a decode call leaves behind for the first loop iteration
+ * (Algorithm 2: joined = joiner(window, decoder([])), labels = argmax over each row), bf16 models.
+ * The window rows are r = a * W + j for the a-th utterance with lengths > 0 and its frames
+ * j = 0 .. W-1 (frames at or past the utterance's end: rows of a zero hidden vector).  The label
+ * columns are cut into *nparts parts of *part_width columns; for every row and part the kernel keeps
+ * the two largest logits of the part, each as one fp32 word whose low 7 mantissa bits hold
+ * 127 - (column within the part): value = word with those bits cleared.  keys DEVICE float
+ * [B * W, *nparts, 2] (largest, second), or NULL to query the two sizes only (HOST pointers).  A
+ * part with fewer than two label columns has -3.0e38 in the unused places.  Returns after completion.
+ */
+int wind_debug_joint_keys(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, int W,
+                          float *keys, int32_t *nparts, int32_t *part_width, void *stream);
+
+/*
  * Per-kernel device time, for the roofline report.  With option "profile" = 1 the decode loop is
  * launched kernel by kernel (no graph) and every launch carries an event pair that receives the
  * dispatch's begin and end time stamps (the kernel's own duration, without launch gaps); this call returns
@@ -248,13 +273,6 @@ int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, in
  *   "unroll"  loop iterations per graph launch (default 16, even)
  *   "profile" 1: time every kernel launch with events (see wind_get_kernel_times); implies no graph
  *   "recheck_kappa_milli"  width of the near-tie band of the bf16 pass, in thousandths
- *   "tiny_rows"  decodes with at most this many window rows (B * W) run window gather, joint and
- *             decision as one kernel per iteration (at most 64; default 0 = off: the separate
- *             kernels are faster at every size since the decision kernel takes the first LSTM
- *             layer's step and no longer compacts the lists)
- *   "joint_split_rows"  iterations with more window rows than this use the 256 x 256 joint tiles,
- *             the others 128-column tiles whose height follows the row count (default: 256 rows
- *             per row tile that it takes to fill the chip; 1024 for V = 8192)
  *   "pred_mfma_min_batch"  smallest B for which the prediction network runs on MFMA tiles
  *             (default 1; bf16 models only; below it one wave per hidden unit does fp32 FMA)
  *   "loop_kernel"  1 (default): decodes of one or two utterances with at most 32 window rows (bf16, one
@@ -275,7 +293,7 @@ int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, in
  *   "beam_exact"  1: the beam-search entry points evaluate bf16 models' joiner rows with an fp32
  *             hidden vector and fp32 FMA instead of the bf16 MFMA pass, so that their choices do
  *             not depend on the rounding of the hidden vector (default 0)
- *   "debug_stamps"  1: the few-rows kernels, the resident loop kernel and the decision kernel record
+ *   "debug_stamps"  1: the resident loop kernel and the decision kernel record
  *             phase time stamps, which the next decode prints to stderr (development aid; default 0)
  */
 int wind_set_option(wind_model *m, const char *key, int64_t value);

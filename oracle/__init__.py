@@ -114,6 +114,14 @@ class Oracle:
         lib().oracle_joiner(C.byref(self._m), _p(frame), _p(g), _p(out))
         return out
 
+    def encoder_projection(self, frame: np.ndarray) -> np.ndarray:
+        """W_enc f + b_enc, the encoder half of the joiner's hidden vector ([Hj], fp64)."""
+        frame = np.ascontiguousarray(frame, dtype=np.float32)
+        assert frame.shape == (self.D,)
+        out = np.zeros(self.Hj, dtype=np.float64)
+        lib().oracle_encoder_projection(C.byref(self._m), _p(frame), _p(out))
+        return out
+
     # ---- Algorithm 1 ---------------------------------------------------------------------
     def greedy(self, enc: np.ndarray, S: int, forced: Optional[List[Tuple[int, int, int]]] = None,
                want_log: bool = True):

@@ -12,7 +12,7 @@
  *   oracle_wind        the windowed loop (Method, Algorithm 2), written a second time from the
  *                      algorithm's own steps.  It exists to pin oracle_greedy, not to be compared
  *                      with the GPU.
- *   oracle_joiner, oracle_decoder_step, oracle_decoder_from_scratch
+ *   oracle_joiner, oracle_decoder_step, oracle_decoder_from_scratch, oracle_encoder_projection
  *                      the model pieces, exported so tests can pin them to library routines and
  *                      enumerate tiny lattices by brute force.
  *
@@ -106,6 +106,17 @@ void oracle_decoder_from_scratch(const oracle_model *m, const int32_t *hyp, int 
   memcpy(g, h + (size_t)(m->L - 1) * m->Hp, sizeof(double) * m->Hp);
   free(h);
   free(c);
+}
+
+/* The encoder half of the joiner's hidden vector, W_enc f + b_enc ([Hj]), written out as the same sums
+   oracle_joiner forms (the joiner's first term; the reading of "combines" stated in the header).
+   Exported so that a decoder which forms this half once per frame can be checked on it. */
+void oracle_encoder_projection(const oracle_model *m, const float *f, double *out) {
+  for (int j = 0; j < m->Hj; ++j) {
+    double a = (double)m->b_enc[j];
+    for (int d = 0; d < m->D; ++d) a += (double)m->w_enc[(size_t)j * m->D + d] * (double)f[d];
+    out[j] = a;
+  }
 }
 
 /* joined = joiner(enc[t,:], dec[-1]) -> logits[V+1] */

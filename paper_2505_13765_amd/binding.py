@@ -17,7 +17,7 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
            "wind_get_kernel_times", "wind_get_joint_launches", "wind_beam_window_scores", "wind_beam_decode",
-           "wind_workspace_bytes")
+           "wind_workspace_bytes", "wind_debug_enc_proj", "wind_debug_joint_keys")
 PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
 
@@ -87,6 +87,9 @@ def load_library():
                                                 C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         lib.wind_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
         lib.wind_get_kernel_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        lib.wind_debug_enc_proj.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        lib.wind_debug_joint_keys.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                              C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
         lib.wind_get_joint_launches.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int,
                                                 C.POINTER(C.c_int)]
         lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
@@ -132,7 +135,7 @@ class WindModel:
         ws.w_pred, ws.b_pred = w["w_pred"].ctypes.data, w["b_pred"].ctypes.data
         ws.w_out, ws.b_out = w["w_out"].ctypes.data, w["b_out"].ctypes.data
         h = C.c_void_p()
-        _check(self._lib.wind_load_weights(C.byref(ws), None, C.byref(h)))
+        _check(self._lib.wind_load_weights(C.byref(ws), _stream_ptr(), C.byref(h)))
         self._h = h
 
     @classmethod
@@ -255,6 +258,29 @@ class WindModel:
                                         C.cast(cb, C.c_void_p) if cb is not None else None, None, _stream_ptr())
         _check(rc)
         return tok[: cnt.value].copy(), frm[: cnt.value].copy(), score.value, st
+
+    def debug_enc_proj(self, enc_out, lengths):
+        """e [B, T, Hj] fp32 (numpy) as a decode call computes it; rows past an utterance's end are unspecified."""
+        import torch
+
+        B, T, _ = enc_out.shape
+        out = torch.zeros((B, T, self.Hj), dtype=torch.float32, device=enc_out.device)
+        _check(self._lib.wind_debug_enc_proj(self._h, enc_out.data_ptr(), lengths.data_ptr(), B, T, out.data_ptr(),
+                                             _stream_ptr()))
+        return out.cpu().numpy()
+
+    def debug_joint_keys(self, enc_out, lengths, W: int):
+        """(keys [B*W, nparts, 2] fp32 numpy, part_width): the joint kernel's output for the first iteration."""
+        import torch
+
+        B, T, _ = enc_out.shape
+        nparts, width = C.c_int32(0), C.c_int32(0)
+        _check(self._lib.wind_debug_joint_keys(self._h, None, None, B, T, int(W), None, C.byref(nparts), C.byref(width),
+                                               _stream_ptr()))
+        out = torch.zeros((B * W, nparts.value, 2), dtype=torch.float32, device=enc_out.device)
+        _check(self._lib.wind_debug_joint_keys(self._h, enc_out.data_ptr(), lengths.data_ptr(), B, T, int(W),
+                                               out.data_ptr(), C.byref(nparts), C.byref(width), _stream_ptr()))
+        return out.cpu().numpy(), int(width.value)
 
     def debug_joint_logits(self, enc_out, b: int, t0: int, n: int, prefix: Sequence[int], exact: bool):
         import torch

@@ -37,32 +37,13 @@ int fail(int code, const std::string &msg) {
   } while (0)
 
 using JointCfg = TileCfg<128, 128, 64, 64>;            // debug store kernel
-using JointRows1 = JointRowsCfg<1>::type;              // joint_rows_kernel: 128-column tiles, 64..256 rows
-using JointBigCfg = Ring5Cfg<256, 64, 128>;             // more rows than the rows kernel balances: 256 x 256 tiles
-constexpr int kTinyRowsDefault = 0;   // the fused few-rows kernel (at most this many window rows) is off by default:
-                                      // since the decision kernel stopped compacting and took over the first LSTM
-                                      // layer, the separate kernels are faster at every size (see option "tiny_rows")
+using EncBigCfg = Ring5Cfg<256, 64, 128>;               // encoder projection of large calls: 256 x 256 tiles
 using EncCfg = TileCfg<128, 128, 64, 64>;
 using PredCfg = DmaCfg<64, 64, 32, 32, 64, 4>;   // 32 utterances (hi and lo rows) x 64 columns, 4-stage ring
 constexpr int kPredMfmaMinBatch = 1;       // below this the FMA prediction network is used
 constexpr size_t kEncRing5MinRows = 16384;   // B * T from which the encoder projection uses 256 x 256 tiles
 constexpr int kIterRowsCap = 16384;   // iterations whose row counts profile mode records
 constexpr int kRowPad = 256;  // window-row buffers are padded to a multiple of every tile height, plus one block
-
-// Row tiles of joint_rows_kernel for a vocabulary of NT 128-column tiles and at most `rows` window
-// rows: enough to cover the rows with the tallest tile, and otherwise as many as fill the 256 CUs
-// (but never more than tiles of the smallest height would need).
-int joint_rows_grid_x(int NT, int rows) {
-  const int cover = (rows + 255) / 256, fill = NT >= 256 ? 1 : 256 / NT, fine = (rows + 63) / 64;
-  const int g = fill < fine ? fill : fine;
-  return cover > g ? cover : g;
-}
-// Default hand-over point between the two joint kernels: the rows kernel keeps 256 equal
-// workgroups busy up to 256 rows per row tile.
-int joint_split_default(int V) {
-  const int NT = (V + 127) / 128, fill = NT >= 256 ? 1 : 256 / NT;
-  return 256 * (fill > 4 ? fill : 4);
-}
 
 uint16_t host_bf16(float x) {
   uint32_t u;
@@ -100,6 +81,7 @@ struct BeamPool {
 struct wind_model {
   ModelDev dev{};
   int dtype = WIND_BF16;
+  hipStream_t load_stream = nullptr;   // wind_load_weights: the stream its copies and kernels go to
   std::vector<void *> allocs;
   // workspace
   void *ws = nullptr;
@@ -113,9 +95,6 @@ struct wind_model {
   bool graph_valid = false;
   int opt_graph = 1, opt_unroll = 16;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
-  int opt_joint_split_rows = -1;   // -1: joint_split_default(V)
-  int opt_joint_ws = 1;            // the joint kernel whose waves are split into multipliers and fetchers
-  int opt_tiny_rows = kTinyRowsDefault;
   int opt_loop_kernel = 1;
   long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
@@ -123,6 +102,7 @@ struct wind_model {
   int opt_atomic_lists = 1;
   bool fma_pred_step = false;   // this call's prediction-network steps keep their state in fp32 (the resident loop kernel reads it)
   LoopDev loop{};
+  int *dbg_len = nullptr, *dbg_out = nullptr;   // lengths and outputs of the debug entry points (inside the workspace)
   void *beam_ws = nullptr;   // workspace of the beam scoring step
   BeamPool beam_pool{};
   int opt_beam_exact = 0;
@@ -151,7 +131,9 @@ int upload(wind_model *m, const std::vector<T> &host, const void **dev_out) {
   void *d = nullptr;
   HIP_TRY(hipMalloc(&d, host.size() * sizeof(T) + 256));
   m->allocs.push_back(d);
-  HIP_TRY(hipMemcpy(d, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  // on the caller's stream; the host array is a temporary, so the copy is awaited here
+  HIP_TRY(hipMemcpyAsync(d, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice, m->load_stream));
+  HIP_TRY(hipStreamSynchronize(m->load_stream));
   *dev_out = d;
   return WIND_OK;
 }
@@ -180,20 +162,17 @@ void set_tau(wind_model *m) {
 struct WsLayout {
   size_t total, Mpad, st;
   bool big_enc;
-  int slot_stride, nparts, nparts_big, nparts_tiny;
+  int slot_stride, nparts, nparts_tiny;
   size_t o_e, o_encb, o_len, o_nact, o_eidx, o_eltok, o_slot, o_slotc, o_rst, o_raux, o_nemit, o_ticket, o_h, o_c, o_hn, o_hb,
-      o_hz, o_rec, o_p, o_z, o_bl, o_zn, o_parts, o_rl, o_stats, o_dbg, o_iter, o_lbar, o_lh, o_lp, o_lparts;
+      o_hz, o_rec, o_p, o_z, o_bl, o_zn, o_parts, o_rl, o_stats, o_dbg, o_iter, o_dbglen, o_dbgout, o_lbar, o_lh, o_lp, o_lparts;
 };
-
-bool tiny_rows_ok(const wind_model *m, int max_rows);
 
 WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   const ModelDev &d = m->dev;
   WsLayout w{};
   w.Mpad = round_up((size_t)B * W, kRowPad) + kRowPad;   // a 192-row tile may run past the 256 multiple
-  const int ntiles = (d.V + JointRows1::BN - 1) / JointRows1::BN;
-  w.nparts = ntiles * JointRows1::WAVES_N;
-  w.nparts_big = ((d.V + JointBigCfg::BN - 1) / JointBigCfg::BN) * JointBigCfg::WAVES_N;
+  const int ntiles = (d.V + WsCfg<1>::BN - 1) / WsCfg<1>::BN;
+  w.nparts = ntiles * WsCfg<1>::WAVES_N;
   w.nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -203,7 +182,7 @@ WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   };
   w.o_e = take((size_t)B * T * d.Hj * 4);
   w.big_enc = m->dtype == WIND_BF16 && (size_t)B * T >= kEncRing5MinRows;
-  w.o_encb = take(w.big_enc ? ((size_t)B * T + JointBigCfg::BM) * d.D * 2 : 0);
+  w.o_encb = take(w.big_enc ? ((size_t)B * T + EncBigCfg::BM) * d.D * 2 : 0);
   w.slot_stride = B > kTinyRows ? B : kTinyRows;
   w.o_len = take((size_t)B * 4);
   w.o_nact = take(8); w.o_eidx = take((size_t)B * 4);
@@ -224,6 +203,8 @@ WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   w.o_stats = take(kNumStats * 8);
   w.o_dbg = take(128);
   w.o_iter = take((size_t)kIterRowsCap * 4);
+  w.o_dbglen = take((size_t)B * 4);             // debug entry points: lengths and outputs of their own
+  w.o_dbgout = take((size_t)(3 * B + 2) * 4);
   w.o_lbar = take((size_t)(1 + 256) * kLoopFlagStride * 4); w.o_lh = take((size_t)kLoopMaxB * d.Hp * 4);
   w.o_lp = take((size_t)kLoopMaxB * d.Hj * 4);
   w.o_lparts = take((size_t)2 * kLoopRows * w.nparts_tiny * 8);
@@ -236,7 +217,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   const WsLayout w = workspace_layout(m, B, T, W);
   const size_t off = w.total, st = w.st;
   const bool big_enc = w.big_enc;
-  const int slot_stride = w.slot_stride, nparts = w.nparts, nparts_big = w.nparts_big, nparts_tiny = w.nparts_tiny;
+  const int slot_stride = w.slot_stride, nparts = w.nparts, nparts_tiny = w.nparts_tiny;
   const size_t o_e = w.o_e, o_encb = w.o_encb, o_len = w.o_len, o_nact = w.o_nact, o_eidx = w.o_eidx, o_eltok = w.o_eltok,
                o_slot = w.o_slot, o_slotc = w.o_slotc, o_rst = w.o_rst, o_raux = w.o_raux, o_nemit = w.o_nemit,
                o_ticket = w.o_ticket, o_h = w.o_h, o_c = w.o_c, o_hn = w.o_hn, o_hb = w.o_hb, o_hz = w.o_hz, o_p = w.o_p,
@@ -270,25 +251,23 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.hb_zero = (const bf16_t *)(base + o_hz);
   // recurrent gate sums kept ahead of the step: where the prediction network runs on MFMA tiles and the
   // iteration is the graph of kernels with its own decision kernel
-  c.rec = m->opt_lstm_rec && m->dtype == WIND_BF16 && B >= m->opt_pred_mfma_min_batch && !tiny_rows_ok(m, B * W)
+  c.rec = m->opt_lstm_rec && m->dtype == WIND_BF16 && B >= m->opt_pred_mfma_min_batch
               ? (float *)(base + w.o_rec) : nullptr;
   c.p = (float *)(base + o_p);
   c.z = (bf16_t *)(base + o_z);
   c.blank_logit = (float *)(base + o_bl); c.znorm = (float *)(base + o_zn);
   c.parts = (float2 *)(base + o_parts);
   c.nparts = nparts;
-  c.part_width = JointRows1::WN;
-  c.nparts_big = nparts_big;
-  c.part_width_big = JointBigCfg::WN;
-  c.joint_split_rows = m->opt_joint_ws ? (1 << 30)   // one key format at every row count
-                       : m->opt_joint_split_rows >= 0 ? m->opt_joint_split_rows : joint_split_default(d.V);
+  c.part_width = WsCfg<1>::WN;
   c.nparts_tiny = nparts_tiny;
   c.row_label = (int *)(base + o_rl);
   c.stats = (unsigned long long *)(base + o_stats);
   c.dbg = m->opt_debug_stamps ? (long long *)(base + o_dbg) : nullptr;
   c.iter_rows = m->opt_profile ? (int *)(base + w.o_iter) : nullptr;
   c.iter_rows_cap = kIterRowsCap;
-  c.lists_atomic = m->opt_atomic_lists && m->dtype == WIND_BF16 && !tiny_rows_ok(m, B * W);   // the path with build_z_kernel
+  m->dbg_len = (int *)(base + w.o_dbglen);
+  m->dbg_out = (int *)(base + w.o_dbgout);
+  c.lists_atomic = m->opt_atomic_lists && m->dtype == WIND_BF16;   // the path with build_z_kernel
   m->loop.bar = (unsigned *)(base + o_lbar);
   m->loop.h_x = (float *)(base + o_lh);
   m->loop.p_x = (float *)(base + o_lp);
@@ -406,10 +385,10 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
     if (m->dtype == WIND_BF16 && c.enc_b) {
       const long long rows = (long long)c.B * c.T;
       launch(m, s, WIND_K_ENC_PROJ, false, enc_round_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, d, c);
-      const int tiles_per_utt = (c.T + JointBigCfg::BM - 1) / JointBigCfg::BM;
-      dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + JointBigCfg::BN - 1) / JointBigCfg::BN));
-      launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_ring5_kernel<JointBigCfg>, grid, dim3(JointBigCfg::NT),
-             JointBigCfg::SMEM_BYTES, d, c, tiles_per_utt);
+      const int tiles_per_utt = (c.T + EncBigCfg::BM - 1) / EncBigCfg::BM;
+      dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncBigCfg::BN - 1) / EncBigCfg::BN));
+      launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_ring5_kernel<EncBigCfg>, grid, dim3(EncBigCfg::NT),
+             EncBigCfg::SMEM_BYTES, d, c, tiles_per_utt);
     } else if (m->dtype == WIND_BF16) {
       const int tiles_per_utt = (c.T + EncCfg::BM - 1) / EncCfg::BM;
       dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncCfg::BN - 1) / EncCfg::BN));
@@ -425,13 +404,14 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
   return enqueue_pred_step(m, s, false, true);
 }
 
-// the fused few-rows kernel keeps all window rows in LDS
-bool tiny_rows_ok(const wind_model *m, int max_rows) {
-  return m->dev.Hj <= kTinyMaxHj && max_rows <= m->opt_tiny_rows;
-}
-size_t tiny_smem_bytes(const ModelDev &d, int max_rows) {
-  const size_t z = (size_t)((max_rows + 31) / 32) * 32 * (d.Hj + 8) * 2;
-  return z > 32768 ? z : 32768;
+// the output contraction with its row argmax folded in, for the window rows build_z_kernel wrote
+void enqueue_joint(wind_model *m, hipStream_t s, int parity, bool capturing) {
+  const ModelDev &d = m->dev;
+  const CallDev &c = m->call;
+  // fill x NT workgroups, each walking as many row tiles as the iteration's row count needs
+  const int NT = (d.V + WsCfg<1>::BN - 1) / WsCfg<1>::BN, fill = NT >= 256 ? 1 : 256 / NT;
+  launch(m, s, WIND_K_JOINT, capturing, joint_ws_kernel, dim3((unsigned)((fill * NT + 7) / 8 * 8)), dim3(WsCfg<1>::NT),
+         kWsSmemBytes, d, c, parity, fill, NT);
 }
 
 int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) {
@@ -439,27 +419,9 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
   const CallDev &c = m->call;
   const int max_rows = c.B * c.W;
   const int decide_threads = 64 * (c.W < 16 ? c.W : 16);
-  if (m->dtype == WIND_BF16 && tiny_rows_ok(m, max_rows)) {
-    launch(m, s, WIND_K_JOINT, capturing, joint_tiny_kernel<bf16_t>, dim3((unsigned)c.nparts_tiny), dim3(256),
-           tiny_smem_bytes(d, max_rows), d, c, parity);
-  } else if (m->dtype == WIND_BF16) {
+  if (m->dtype == WIND_BF16) {
     launch(m, s, WIND_K_BUILD_Z, capturing, build_z_kernel, dim3((unsigned)((max_rows + 3) / 4)), dim3(256), 0, d, c, parity);
-    if (m->opt_joint_ws) {
-      // fill x NT workgroups, each walking as many row tiles as the iteration's row count needs
-      const int NT = (d.V + 127) / 128, fill = NT >= 256 ? 1 : 256 / NT;
-      launch(m, s, WIND_K_JOINT, capturing, joint_ws_kernel, dim3((unsigned)((fill * NT + 7) / 8 * 8)), dim3(512), kWsSmemBytes, d, c,
-             parity, fill, NT);
-    } else {
-      // one launch for both tile shapes: the rows path (rows <= joint_split_rows) or the 256 x 256 tiles
-      const int small_rows = max_rows < c.joint_split_rows ? max_rows : c.joint_split_rows;
-      const int NT = (d.V + JointRows1::BN - 1) / JointRows1::BN;
-      const int gx = small_rows > 0 ? joint_rows_grid_x(NT, small_rows) : 0;
-      const int rows_blocks = (gx * NT + 7) / 8 * 8;
-      int big_mt = 0, big_nt = (d.V + JointBigCfg::BN - 1) / JointBigCfg::BN;
-      if (max_rows > c.joint_split_rows) big_mt = (max_rows + JointBigCfg::BM - 1) / JointBigCfg::BM;
-      launch(m, s, WIND_K_JOINT, capturing, joint_kernel<JointBigCfg>, dim3((unsigned)std::max(rows_blocks, big_mt * big_nt)),
-             dim3(JointBigCfg::NT), JointBigCfg::SMEM_BYTES, d, c, parity, gx, NT, rows_blocks, big_mt, big_nt);
-    }
+    enqueue_joint(m, s, parity, capturing);
     if (d.Hj <= 1024)
       launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t, false>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
     else
@@ -578,7 +540,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   if (rc) return rc;
   if (use_loop) {
     // the whole loop as one resident kernel
-    lp.max_iters = (int)std::min<long long>((long long)T * (S + 1) + 2, 1 << 30);
+    lp.max_iters = (int)std::min<long long>((long long)T * ((long long)S + 1) + 2, 1 << 30);
     lp.spin_limit = (unsigned)m->opt_loop_spin_limit;
     HIP_TRY(hipMemsetAsync(lp.bar, 0, (size_t)(1 + lp.G) * kLoopFlagStride * 4, s));
     wind_loop_kernel<<<(unsigned)lp.G, 256, loop_smem, s>>>(m->dev, c, lp);
@@ -605,7 +567,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   long long ahead = 1;
   if (m->prev_B == B && m->prev_T == T && m->prev_W == W && m->prev_iters > 0) ahead = m->prev_iters / U;
   if (ahead < 1) ahead = 1;
-  const long long max_launches = ((long long)T * (S + 1) + 2 * U) / U + 2;  // every iteration moves some pointer or emits
+  const long long max_launches = ((long long)T * ((long long)S + 1) + 2 * U) / U + 2;  // every iteration moves some pointer or emits
   long long launches = 0;
   for (;;) {
     for (long long i = 0; i < ahead; ++i, ++launches) {
@@ -647,7 +609,6 @@ const char *wind_last_error(void) { return g_err.c_str(); }
 
 // The host-side conversion of the weights uses standard containers; nothing they throw may cross the C boundary.
 int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try {
-  (void)stream;
   if (!w || !out) return fail(WIND_ERR_ARG, "null argument");
   *out = nullptr;
   if (w->L < 1 || w->L > WIND_MAX_LAYERS) return fail(WIND_ERR_ARG, "L must be in 1..4");
@@ -663,6 +624,7 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
 
   wind_model *m = new wind_model();
   m->dtype = w->dtype;
+  m->load_stream = (hipStream_t)stream;
   ModelDev &d = m->dev;
   d.D = w->D; d.E = w->E; d.Hp = w->Hp; d.L = w->L; d.Hj = w->Hj; d.V = w->V;
   d.Vpad = (int)round_up((size_t)w->V + 1, 256);
@@ -702,13 +664,13 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
       if (rc == WIND_OK) {
         dim3 grid((unsigned)((w->V + 1 + 63) / 64), (unsigned)((4 * Hp + 63) / 64));
         if (m->dtype == WIND_BF16)
-          emb_gates_kernel<bf16_t><<<grid, 256>>>((const bf16_t *)d.emb, (const bf16_t *)d_ih, d.b_cat[0], (float *)table,
+          emb_gates_kernel<bf16_t><<<grid, 256, 0, m->load_stream>>>((const bf16_t *)d.emb, (const bf16_t *)d_ih, d.b_cat[0], (float *)table,
                                                   w->V + 1, 4 * Hp, w->E);
         else
-          emb_gates_kernel<float><<<grid, 256>>>((const float *)d.emb, (const float *)d_ih, d.b_cat[0], (float *)table,
+          emb_gates_kernel<float><<<grid, 256, 0, m->load_stream>>>((const float *)d.emb, (const float *)d_ih, d.b_cat[0], (float *)table,
                                                  w->V + 1, 4 * Hp, w->E);
         chk(check_launch("emb_gates"));
-        hipError_t e = hipDeviceSynchronize();
+        hipError_t e = hipStreamSynchronize(m->load_stream);
         if (rc == WIND_OK && e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("emb_gates: ") + hipGetErrorString(e));
         d.emb_gates = (const float *)table;
       }
@@ -756,13 +718,7 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
   }
   if (rc == WIND_OK) {
-    hipError_t e = hipFuncSetAttribute((const void *)joint_kernel<JointBigCfg>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, JointBigCfg::SMEM_BYTES);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)joint_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              m->dev.Hj <= kTinyMaxHj ? (int)tiny_smem_bytes(m->dev, 64) : 32768);   // unused above that size
+    hipError_t e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)wind_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 154 * 1024);
     if (e == hipSuccess)
@@ -772,8 +728,8 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
       e = hipFuncSetAttribute((const void *)beam_logits_tiny_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                               2 * 32 * (kBeamTinyMaxHj + 8) * 2);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)enc_proj_ring5_kernel<JointBigCfg>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              JointBigCfg::SMEM_BYTES);
+      e = hipFuncSetAttribute((const void *)enc_proj_ring5_kernel<EncBigCfg>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              EncBigCfg::SMEM_BYTES);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)enc_proj_mfma_kernel<EncCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, EncCfg::SMEM_BYTES);
@@ -899,23 +855,6 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
     m->graph_valid = false;
     return WIND_OK;
   }
-  if (!std::strcmp(key, "tiny_rows")) {
-    if (value < 0 || value > 64) return fail(WIND_ERR_ARG, "tiny_rows must be 0..64");
-    m->opt_tiny_rows = (int)value;
-    m->graph_valid = false;
-    return WIND_OK;
-  }
-  if (!std::strcmp(key, "joint_ws")) {
-    m->opt_joint_ws = value != 0;
-    m->graph_valid = false;
-    return WIND_OK;
-  }
-  if (!std::strcmp(key, "joint_split_rows")) {
-    if (value < 0) return fail(WIND_ERR_ARG, "joint_split_rows must be >= 0");
-    m->opt_joint_split_rows = value > (1 << 30) ? (1 << 30) : (int)value;
-    m->graph_valid = false;
-    return WIND_OK;
-  }
   if (!std::strcmp(key, "loop_kernel")) {
     m->opt_loop_kernel = value != 0;
     return WIND_OK;
@@ -950,39 +889,45 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   return fail(WIND_ERR_ARG, std::string("unknown option ") + key);
 }
 
+// Common start of the debug entry points: workspace for the shape, the call's fields, and a decode
+// prologue (state, encoder projection, start-token step) with the library's own outputs.
+static int debug_prologue(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, int W, hipStream_t s) {
+  int rc = ensure_workspace(m, B, T, W);
+  if (rc) return rc;
+  CallDev &c = m->call;
+  c.B = B; c.T = T; c.W = W; c.S = 1; c.cap = 1;
+  c.rec = nullptr;   // whole prediction-network steps: no decision kernel runs between them
+  c.lists_atomic = 0;
+  m->fma_pred_step = false;
+  m->graph_valid = false;
+  c.enc = enc_out;
+  if (lengths) {
+    c.lengths = lengths;
+  } else {   // every frame of every utterance
+    fill_int_kernel<<<(unsigned)((B + 255) / 256), 256, 0, s>>>(m->dbg_len, B, T);
+    c.lengths = m->dbg_len;
+  }
+  c.out_tokens = m->dbg_out; c.out_frames = m->dbg_out + B; c.out_counts = m->dbg_out + 2 * B;
+  return enqueue_prologue(m, s);
+}
+
 int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, int b, int t0, int n,
-                            const int32_t *prefix, int prefix_len, int exact, float *logits, void *stream) {
+                            const int32_t *prefix, int prefix_len, int exact, float *logits, void *stream) try {
   if (!m || !enc_out || !logits) return fail(WIND_ERR_ARG, "null argument");
   if (B < 1 || T < 1 || b < 0 || b >= B || t0 < 0 || n < 1 || t0 + n > T || n > WIND_MAX_WINDOW)
     return fail(WIND_ERR_ARG, "window out of range");
+  if ((long long)B * T > (1ll << 31) - 1) return fail(WIND_ERR_ARG, "B*T too large");
   if (prefix_len < 0 || (prefix_len > 0 && !prefix)) return fail(WIND_ERR_ARG, "bad prefix");
   for (int i = 0; i < prefix_len; ++i)
     if (prefix[i] < 0 || prefix[i] >= m->dev.V) return fail(WIND_ERR_ARG, "prefix label out of range");
   hipStream_t s = (hipStream_t)stream;
-  int rc = ensure_workspace(m, B, T, WIND_MAX_WINDOW);
-  if (rc) return rc;
+  int rc = debug_prologue(m, enc_out, nullptr, B, T, WIND_MAX_WINDOW, s);   // start-token step on every utterance
   CallDev &c = m->call;
-  // a device array of full lengths, so that every frame is projected
-  std::vector<int> full(B, T);
-  int *d_len = nullptr, *d_scr = nullptr;
-  HIP_TRY(hipMalloc((void **)&d_len, sizeof(int) * B));
-  HIP_TRY(hipMalloc((void **)&d_scr, sizeof(int) * (size_t)(3 * B + 2)));
-  HIP_TRY(hipMemcpyAsync(d_len, full.data(), sizeof(int) * B, hipMemcpyHostToDevice, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  c.B = B; c.T = T; c.W = WIND_MAX_WINDOW; c.S = 1; c.cap = 1;
-  c.rec = nullptr;   // the steps below are whole prediction-network steps, with no decision kernel between them
-  m->fma_pred_step = false;
-  c.enc = enc_out; c.lengths = d_len;
-  c.out_tokens = d_scr; c.out_frames = d_scr + B; c.out_counts = d_scr + 2 * B;
-  m->graph_valid = false;
-  rc = enqueue_prologue(m, s);  // start-token step on every utterance, all frames projected
   for (int i = 0; i < prefix_len && rc == WIND_OK; ++i) {
-    // feed prefix[i] to utterance b only
-    const int one = 1, tok = prefix[i];
-    HIP_TRY(hipMemcpyAsync(c.n_emit, &one, sizeof(int), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(c.emit_idx, &b, sizeof(int), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(c.emit_list_tok, &tok, sizeof(int), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipStreamSynchronize(s));
+    // feed prefix[i] to utterance b only: an emit list of one entry
+    fill_int_kernel<<<1, 256, 0, s>>>(c.n_emit, 1, 1);
+    fill_int_kernel<<<1, 256, 0, s>>>(c.emit_idx, 1, b);
+    fill_int_kernel<<<1, 256, 0, s>>>(c.emit_list_tok, 1, prefix[i]);
     rc = enqueue_pred_step(m, s, false);
   }
   if (rc == WIND_OK) {
@@ -1001,10 +946,54 @@ int wind_debug_joint_logits(wind_model *m, const float *enc_out, int B, int T, i
     rc = check_launch("debug joint");
   }
   hipError_t e = hipStreamSynchronize(s);
-  (void)hipFree(d_len);
-  (void)hipFree(d_scr);
   if (rc == WIND_OK && e != hipSuccess) return fail(WIND_ERR_HIP, std::string("debug sync: ") + hipGetErrorString(e));
   return rc;
+} catch (const std::exception &e) {
+  return fail(WIND_ERR_HIP, std::string("wind_debug_joint_logits: ") + e.what());
+}
+
+int wind_debug_enc_proj(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, float *e_out,
+                        void *stream) try {
+  if (!m || !enc_out || !lengths || !e_out) return fail(WIND_ERR_ARG, "null argument");
+  if (B < 1 || T < 1 || (long long)B * T > (1ll << 31) - 1) return fail(WIND_ERR_ARG, "B >= 1, T >= 1, B*T < 2^31 required");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = debug_prologue(m, enc_out, lengths, B, T, 1, s);
+  if (rc) return rc;
+  HIP_TRY(hipMemcpyAsync(e_out, m->call.e, (size_t)B * T * m->dev.Hj * sizeof(float), hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  return WIND_OK;
+} catch (const std::exception &e) {
+  return fail(WIND_ERR_HIP, std::string("wind_debug_enc_proj: ") + e.what());
+}
+
+int wind_debug_joint_keys(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, int W,
+                          float *keys, int32_t *nparts, int32_t *part_width, void *stream) try {
+  if (!m || !nparts || !part_width) return fail(WIND_ERR_ARG, "null argument");
+  if (m->dtype != WIND_BF16) return fail(WIND_ERR_UNSUPPORTED, "fp32 models take the argmax directly: there are no keys");
+  if (m->dev.Hj > kDecideMaxHj) return fail(WIND_ERR_UNSUPPORTED, "Hj > 2048");
+  if (B < 1 || T < 1 || W < 1 || W > WIND_MAX_WINDOW || (long long)B * T > (1ll << 31) - 1)
+    return fail(WIND_ERR_ARG, "B >= 1, T >= 1, 1 <= W <= 64, B*T < 2^31 required");
+  {
+    const WsLayout w = workspace_layout(m, B, T, W);
+    *nparts = w.nparts;
+    *part_width = WsCfg<1>::WN;
+  }
+  if (!keys) return WIND_OK;
+  if (!enc_out || !lengths) return fail(WIND_ERR_ARG, "null argument");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = debug_prologue(m, enc_out, lengths, B, T, W, s);
+  if (rc) return rc;
+  const CallDev &c = m->call;
+  // the first loop iteration's window rows and their keys, by the kernels a decode call launches
+  build_z_kernel<<<(unsigned)((B * W + 3) / 4), 256, 0, s>>>(m->dev, c, 0);
+  enqueue_joint(m, s, 0, true);
+  rc = check_launch("debug joint keys");
+  if (rc) return rc;
+  HIP_TRY(hipMemcpyAsync(keys, c.parts, (size_t)B * W * c.nparts * sizeof(float2), hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  return WIND_OK;
+} catch (const std::exception &e) {
+  return fail(WIND_ERR_HIP, std::string("wind_debug_joint_keys: ") + e.what());
 }
 
 }  // extern "C"

@@ -3,10 +3,10 @@
 // One loop iteration (Method, Algorithm 2, all active utterances at once), bf16 models:
 //   build_z        window gather: z[r,j,:] = relu(e[b, t_b + j, :] + p[b,:]) in bf16, plus the
 //                  blank logit and the norm of every row in fp32
-//   joint          label logits of every window row on bf16 MFMA; per row and per column part
-//                  the two largest (logit, column) keys are kept, nothing else is stored.  Two
-//                  tile shapes in one launch: 128-column tiles whose height follows the row
-//                  count, and 256 x 256 tiles for the iterations with many rows
+//   joint_ws       label logits of every window row on bf16 MFMA; per row and per 64-column part
+//                  the two largest (logit, column) keys are kept, nothing else is stored.  Tiles of
+//                  128 columns whose height (64 to 256 rows) and number per workgroup follow the
+//                  iteration's row count; four waves of a workgroup multiply, four fetch
 //   decide         per utterance: row argmax from the keys, near-ties re-decided with fp32 dot
 //                  products, first non-blank row by wavefront ballot, pointer / hypothesis update,
 //                  the utterance's place in the next iteration's slot table and in the emit list
@@ -16,13 +16,12 @@
 //   pred_proj      p = W_pred h + b_pred for those utterances; the same launch renews the
 //                  recurrent gate sums of every layer for them
 // Optionally (CallDev::rec null, lists_atomic 0) the steps are whole LSTM steps after the decision
-// and the last workgroup of decide compacts the lists in order.  With at most 64 window rows,
-// build_z + joint + decide can run as one kernel (joint_tiny; off by default).  The prediction
-// network has three implementations: MFMA tiles with the hidden state split into bf16 hi + lo,
-// low-latency wave-per-unit kernels (the start-token step of the resident loop kernel), generic FMA
-// (fp32 models).  fp32 models replace build_z + joint by joint_exact (fp32 FMA, argmax taken
-// directly).  One or two utterances of a one-layer model run the whole loop as one resident
-// kernel (wind_loop_kernel).
+// and the last workgroup of decide compacts the lists in order.  The prediction network has three
+// implementations: MFMA tiles with the hidden state split into bf16 hi + lo, low-latency
+// wave-per-unit kernels (the start-token step of the resident loop kernel), generic FMA (fp32
+// models).  fp32 models replace build_z + joint by joint_exact (fp32 FMA, argmax taken directly).
+// One or two utterances of a one-layer model run the whole loop as one resident kernel
+// (wind_loop_kernel).
 #pragma once
 #include "wind_mfma.h"
 #include "wind_mfma_dma.h"
@@ -32,7 +31,7 @@ namespace wind {
 
 constexpr int kMaxLayers = 4;
 constexpr int kMaxWindow = 64;
-constexpr int kTinyRows = 64;   // the fused few-rows kernel handles at most this many window rows
+constexpr int kTinyRows = 64;   // slots the resident loop kernel keeps in LDS (it runs far fewer)
 constexpr int kStatJump0 = 8;  // index of jump_hist[0] in the device counter array
 constexpr int kNumStats = kStatJump0 + kMaxWindow + 1;
 enum { ST_ITER = 0, ST_WINDOWS, ST_ROWS, ST_USEFUL, ST_LABELS, ST_FORCED, ST_RECHECK, ST_OVERFLOW };
@@ -83,7 +82,7 @@ struct CallDev {
   int *emit_idx;                // [B] utterances that emitted and are still active, in order
   int *emit_list_tok;           // [B] their labels, in the same order
   int *n_emit;                  // [1]
-  unsigned *ticket;             // [2] workgroups done: decide_kernel, joint_tiny_kernel
+  unsigned *ticket;             // [2] workgroups done (decide_kernel)
   int lists_atomic;             // 1: decide_kernel's workgroups claim their places in the next slot table and the
                                 //    emit list with atomic counters (order varies, results do not); 0: the last
                                 //    workgroup to finish compacts res_state / res_aux in slot order
@@ -100,11 +99,9 @@ struct CallDev {
   float *blank_logit;           // [Mpad]
   float *znorm;                 // [Mpad]
   float2 *parts;                // [Mpad][nparts] two largest (logit, column) keys per row and part
-  int nparts;                   // parts per row and label columns per part, as written by the
-  int part_width;               //   small-tile joint kernel (rows <= joint_split_rows)
-  int nparts_big, part_width_big;  // the same for the 256 x 256 kernel (rows > joint_split_rows)
-  int joint_split_rows;         // which of the two joint kernels handles an iteration
-  int nparts_tiny;              // parts per row of the few-rows kernel (32 columns each)
+  int nparts;                   // parts per row and label columns per part, as written by the joint kernel
+  int part_width;
+  int nparts_tiny;              // parts per row of the resident loop kernel (32 columns each)
   int *row_label;               // [Mpad] (fp32 models)
   unsigned long long *stats;    // [kNumStats]
   long long *dbg;               // optional [8] phase time stamps of the few-rows kernel's deciding workgroup (100 MHz clock)
@@ -113,6 +110,10 @@ struct CallDev {
 };
 
 // ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_int_kernel(int *p, int n, int v) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) p[i] = v;
+}
+
 __global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) {
   const int tid = threadIdx.x;
   // every workgroup zeroes its share of the prediction-network state; the first also builds the lists
@@ -410,86 +411,6 @@ __device__ __forceinline__ void joint_keys_epilogue(const CallDev &c, f32x16 (&a
     const float r1 = __shfl_xor(k1, 32, kWave), r2 = __shfl_xor(k2, 32, kWave);
     merge_top2(k1, k2, r1, r2);
     if (lane < 32) c.parts[(size_t)(row_base + mi * 32 + lane) * stride + part] = make_float2(k1, k2);
-  }
-}
-
-// Output contraction of the joiner on bf16 MFMA, with the row argmax folded into the epilogue: the
-// tile's logits never leave registers; each wave reduces its WM x WN block to two keys per row.
-// Direct-to-LDS, multi-stage tile core (both operands are dense bf16 rows in memory: the window
-// rows z and W_out).
-//
-// The number of window rows shrinks from iteration to iteration while the launch grid is fixed (it
-// sits in a captured graph), so the tile height is chosen in the kernel: the grid has GX row
-// tiles, and a workgroup takes 64 * MI rows with the smallest MI in 1..4 for which GX tiles cover
-// the iteration's rows.  All GX x NT workgroups then have equal work whatever the row count, in
-// steps of 64 * GX rows.  Tiles are 128 columns wide; the LDS ring is as deep as 160 KB allow,
-// because with one workgroup per CU the loads in flight, not the bandwidth, set the pace.
-template <int MI>
-struct JointRowsCfg {
-  using type = DmaCfg<64 * MI, 128, 32 * MI, 64, 64, MI == 1 ? 5 : MI == 2 ? 4 : 3>;
-};
-constexpr int kJointRowsSmem = 3 * (256 + 128) * 128;   // the largest of the four rings
-
-template <int MI>
-__device__ __forceinline__ void joint_rows_tile(const ModelDev &m, const CallDev &c, int n_rows, int mt, int nt,
-                                                unsigned char *smem_raw) {
-  using Cfg = typename JointRowsCfg<MI>::type;
-  static_assert(Cfg::SMEM_BYTES <= kJointRowsSmem && Cfg::NT == 256, "ring size, workgroup size");
-  const int row0 = mt * Cfg::BM;
-  if (row0 >= n_rows) return;
-  const int n0 = nt * Cfg::BN, Hj = m.Hj;
-  f32x16 acc[Cfg::MI][Cfg::NI];
-  float bias[Cfg::NI][16];
-  joint_load_bias<Cfg>(m, bias, n0);
-  gemm_mainloop_dma<Cfg, true>(c.z + (size_t)row0 * Hj, reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
-                               smem_raw, acc, JointInitAcc<Cfg>{acc, bias});
-  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);
-}
-
-// 256 x 256 tiles on the five-slot ring (see gemm_mainloop_ring5), for iterations with more rows
-// than the rows path balances over the chip.
-template <class Cfg, bool WEAVE = false>
-__device__ __forceinline__ void joint_big_tile(const ModelDev &m, const CallDev &c, int n_rows, int mt, int nt,
-                                               unsigned char *smem_raw) {
-  const int row0 = mt * Cfg::BM;
-  if (row0 >= n_rows) return;
-  const int n0 = nt * Cfg::BN, Hj = m.Hj;
-  f32x16 acc[Cfg::MI][Cfg::NI];
-  float bias[Cfg::NI][16];
-  joint_load_bias<Cfg>(m, bias, n0);
-  gemm_mainloop_ring5<Cfg, true, JointInitAcc<Cfg>, WEAVE>(c.z + (size_t)row0 * Hj,
-                                                           reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)n0 * Hj, Hj,
-                                                           smem_raw, acc, JointInitAcc<Cfg>{acc, bias});
-  joint_keys_epilogue<Cfg>(c, acc, row0, nt, c.nparts);   // rows of keys are c.nparts pairs apart for both shapes
-}
-
-// One launch per iteration serves both tile shapes: the iteration's row count decides whether the
-// workgroups form the GX x NT grid of the rows path (rows_blocks of them, using four of their eight
-// waves) or the grid of 256 x 256 tiles; the launch has as many workgroups as the larger of the two
-// grids, and those past the grid in use return at once.
-template <class BigCfg>
-__global__ __launch_bounds__(512) void joint_kernel(ModelDev m, CallDev c, int parity, int rows_gx, int rows_nt,
-                                                    int rows_blocks, int big_mt, int big_nt) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  static_assert(BigCfg::NT == 512 && BigCfg::SMEM_BYTES >= kJointRowsSmem, "one launch shape for both paths");
-  const int n_rows = c.n_active[parity] * c.W;
-  if (n_rows == 0) return;
-  int mt, nt;
-  if (n_rows <= c.joint_split_rows) {
-    if ((int)blockIdx.x >= rows_blocks || threadIdx.x >= 256) return;
-    joint_tile_of_block((int)blockIdx.x, rows_gx, rows_nt, mt, nt);
-    if (mt >= rows_gx || nt >= rows_nt) return;   // padding of the group to a multiple of 8 (either mapping)
-    const int mi = (n_rows + 64 * rows_gx - 1) / (64 * rows_gx);   // <= 4 by the host's choice of rows_gx
-    switch (mi) {
-      case 1: joint_rows_tile<1>(m, c, n_rows, mt, nt, smem_raw); break;
-      case 2: joint_rows_tile<2>(m, c, n_rows, mt, nt, smem_raw); break;
-      case 3: joint_rows_tile<3>(m, c, n_rows, mt, nt, smem_raw); break;
-      default: joint_rows_tile<4>(m, c, n_rows, mt, nt, smem_raw); break;
-    }
-  } else {
-    if ((int)blockIdx.x >= big_mt * big_nt) return;
-    joint_tile_of_block((int)blockIdx.x, big_mt, big_nt, mt, nt);
-    joint_big_tile<BigCfg>(m, c, n_rows, mt, nt, smem_raw);
   }
 }
 
@@ -1168,11 +1089,7 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   for (int j = threadIdx.x; j <= kMaxWindow; j += blockDim.x) sh.hist[j] = 0u;
   if (na == 0 && a == 0 && threadIdx.x == 0) c.n_active[parity ^ 1] = 0;  // keep both slots at "done"
   if (a >= na) return;
-  // which joint kernel wrote the keys: both use rows c.nparts pairs apart, the 256 x 256 kernel
-  // fills fewer, wider parts
-  const bool big = na * c.W > c.joint_split_rows;
-  decide_utterance<WT, false, WIDE>(m, c, a, st, cnt, exact_mode, big ? c.nparts_big : c.nparts, c.nparts,
-                              big ? c.part_width_big : c.part_width, ahead, sh);
+  decide_utterance<WT, false, WIDE>(m, c, a, st, cnt, exact_mode, c.nparts, c.nparts, c.part_width, ahead, sh);
   const long long ts1 = c.dbg ? wall_clock64() : 0;
   if (c.dbg && threadIdx.x == 0) {   // rows phase of workgroups with / without a near-tie
     atomicAdd((unsigned long long *)&c.dbg[sh.recheck ? 4 : 6], (unsigned long long)(ts1 - ts0));
@@ -1275,192 +1192,10 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Few window rows (at most 64; one utterance with any window, or a handful of utterances): the
-// whole iteration up to the prediction network in one kernel.  Every workgroup rebuilds the window
-// rows z in LDS from fp32 e and p (cheaper than a kernel boundary), multiplies them with its 32
-// columns of W_out on MFMA, the four waves splitting K and loading their W_out fragments straight
-// from memory into registers (no staging, no barrier inside the K loop), and writes the rows' keys;
-// the last workgroup to finish takes the decisions for every utterance and rebuilds the lists.
+// Column slices of 32 labels: the unit in which the resident loop kernel's workgroups own W_out.
 constexpr int kTinyCols = 32;
-constexpr int kTinyMaxHj = 1024;    // the window rows of the few-rows kernel live in registers, then LDS
-constexpr int kTinyPrefetch = 16;   // W_out fragments (K steps of 16) a wave requests before anything else
-template <class WT>
-__global__ __launch_bounds__(256) void joint_tiny_kernel(ModelDev m, CallDev c, int parity) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  __shared__ DecideShared sh;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int Hj = m.Hj, W = c.W;
-  // round trip 1, all independent: the active count, the slot table (utterance, t, len, sym, count
-  // per active slot, written by the previous iteration's compaction), and this wave's W_out
-  // fragments for its quarter of K
-  const long long ts0 = c.dbg ? wall_clock64() : 0;
-  const int na = c.n_active[parity];
-  if (tid < kTinyRows) {
-    sh.slot[tid] = c.slot_state[parity * c.slot_stride + tid];
-    sh.cnt[tid] = c.slot_count[parity * c.slot_stride + tid];
-  }
-  const int n0 = blockIdx.x * kTinyCols;
-  const int kq = Hj >> 2, k0 = wave * kq, nk = kq >> 4;   // Hj % 64 == 0, so kq % 16 == 0
-  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
-  bf16x8 bpre[kTinyPrefetch];
-#pragma unroll
-  for (int i = 0; i < kTinyPrefetch; ++i)
-    if (i < nk) bpre[i] = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
-  for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
-  if (na == 0) {
-    if (blockIdx.x == 0 && tid == 0) c.n_active[parity ^ 1] = 0;
-    return;
-  }
-  __syncthreads();
-  const int n_rows = na * W;
-  const int RB = (n_rows + 31) >> 5;                 // 32-row blocks in use (1 or 2)
-  const int zstride = Hj + 8;                        // bf16 elements; odd number of 16-byte units
-  bf16_t *zs = reinterpret_cast<bf16_t *>(smem_raw);
-  // round trip 2: window rows into LDS, with their fp32 blank logit and norm.  A wave takes rows
-  // wave, wave + 4, ...; the loads of four rows go out together so that they share one round trip.
-  constexpr int KI = kTinyMaxHj / 256;   // float4 per lane per row
-  for (int q0 = 0; q0 < RB * 8; q0 += 4) {
-    float4 ev[4][KI], pv[4][KI];
-    bool valid[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = wave + 4 * (q0 + q);
-      valid[q] = false;
-      const float *er = c.e, *pr = c.p;
-      if (row < n_rows) {
-        const int a = row / W, j = row - a * W;
-        const int4 st = sh.slot[a];
-        valid[q] = st.y + j < st.z;
-        er = c.e + ((size_t)st.x * c.T + (valid[q] ? st.y + j : 0)) * Hj;
-        pr = c.p + (size_t)st.x * Hj;
-      }
-#pragma unroll
-      for (int i = 0; i < KI; ++i) {
-        const int k = lane * 4 + 256 * i;
-        ev[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        pv[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (valid[q] && k < Hj) {
-          ev[q][i] = *reinterpret_cast<const float4 *>(er + k);
-          pv[q][i] = *reinterpret_cast<const float4 *>(pr + k);
-        }
-      }
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = wave + 4 * (q0 + q);
-      float dot = 0.f, nrm = 0.f;
-#pragma unroll
-      for (int i = 0; i < KI; ++i) {
-        const int k = lane * 4 + 256 * i;
-        if (k < Hj) {
-          float4 x;
-          x.x = fmaxf(ev[q][i].x + pv[q][i].x, 0.f); x.y = fmaxf(ev[q][i].y + pv[q][i].y, 0.f);
-          x.z = fmaxf(ev[q][i].z + pv[q][i].z, 0.f); x.w = fmaxf(ev[q][i].w + pv[q][i].w, 0.f);
-          *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
-          const float4 wb = *reinterpret_cast<const float4 *>(m.w_blank + k);
-          dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
-          nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
-        }
-      }
-      if (row < n_rows) {
-        dot = wave_sum(dot);
-        nrm = wave_sum(nrm);
-        if (lane == 0) { sh.blank[row] = dot + m.b_out[m.V]; sh.znorm[row] = sqrtf(nrm); }
-      }
-    }
-  }
-  __syncthreads();
-  const long long ts1 = c.dbg ? wall_clock64() : 0;
-  // this wave's quarter of K, 32 columns, RB row blocks
-  f32x16 acc[2];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
-  const bf16_t *zrow = zs + (size_t)(lane & 31) * zstride + k0 + (lane >> 5) * 8;
-#pragma unroll
-  for (int i = 0; i < kTinyPrefetch; ++i) {
-    if (i < nk) {
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bpre[i], acc[0], 0, 0, 0);
-      if (RB > 1) {
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(zrow + 32 * zstride + i * 16);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bpre[i], acc[1], 0, 0, 0);
-      }
-    }
-  }
-  for (int i = kTinyPrefetch; i < nk; ++i) {   // Hj > 1024
-    const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
-    const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
-    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag, acc[0], 0, 0, 0);
-    if (RB > 1) {
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(zrow + 32 * zstride + i * 16);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfrag, acc[1], 0, 0, 0);
-    }
-  }
-  __syncthreads();   // every wave is done with z: its LDS is reused for the K-split partial sums
-  float *red = reinterpret_cast<float *>(smem_raw);   // [wave][rb][r][lane]
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) red[((wave * 2 + rb) * 16 + r) * 64 + lane] = acc[rb][r];
-  __syncthreads();
-  if (wave < RB) {
-    const int rb = wave, cip = lane & 31, col = n0 + cip;
-    const bool ok = col < m.V;
-    const float bias = ok ? m.b_out[ok ? col : 0] : kKeyNone;
-    float k1[16], k2[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float v = bias;
-#pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) v += red[((w2 * 2 + rb) * 16 + r) * 64 + lane];
-      k1[r] = make_key(ok ? v : kKeyNone, cip);
-      k2[r] = kKeyNone;
-    }
-    float o1[1], o2[1];
-    RowTop2<16, 0>::run(k1, k2, lane, o1, o2);
-    const int s = rowtop2_first_slot<16>(lane);
-    const int row = rb * 32 + acc_row(0, s, lane);
-    c.parts[(size_t)row * c.nparts_tiny + blockIdx.x] = make_float2(o1[0], o2[0]);
-  }
-  // the last workgroup to get here decides, from the keys in memory and the state it holds in LDS
-  __syncthreads();
-  const long long ts2 = c.dbg ? wall_clock64() : 0;
-  if (tid == 0) {
-    __threadfence();
-    const unsigned tk = atomicAdd(c.ticket + 1, 1u);
-    sh.is_last = (tk == gridDim.x - 1);
-  }
-  __syncthreads();
-  if (!sh.is_last) return;
-  __threadfence();
-  const long long ts3 = c.dbg ? wall_clock64() : 0;
-  for (int a = 0; a < na; ++a) {
-    RowsAhead ahead;
-#pragma unroll
-    for (int q = 0; q < kRowsAhead; ++q) {
-      const int j = wave + q * 4, row = a * W + j;
-      ahead.kk0[q] = make_float2(kKeyNone, kKeyNone);
-      ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
-      if (j < W) {
-        if (lane < c.nparts_tiny) ahead.kk0[q] = c.parts[(size_t)row * c.nparts_tiny + lane];
-        ahead.vb[q] = sh.blank[row];
-        ahead.zn[q] = sh.znorm[row];
-      }
-    }
-    decide_utterance<WT, true>(m, c, a, sh.slot[a], sh.cnt[a], 0, c.nparts_tiny, c.nparts_tiny, kTinyCols, ahead, sh);
-  }
-  const long long ts4 = c.dbg ? wall_clock64() : 0;
-  if (tid < 64) {
-    compact_lists<true>(c, parity, na, sh);
-    if (tid == 0) c.ticket[1] = 0u;
-  }
-  if (c.dbg && tid == 0) {
-    const long long ts5 = wall_clock64();
-    c.dbg[0] += ts1 - ts0; c.dbg[1] += ts2 - ts1; c.dbg[2] += ts3 - ts2; c.dbg[3] += ts4 - ts3; c.dbg[4] += ts5 - ts4; c.dbg[5] += 1;
-  }
-}
+constexpr int kTinyMaxHj = 1024;    // the loop kernel keeps its window rows in registers, then LDS
+constexpr int kTinyPrefetch = 16;   // W_out fragments (K steps of 16) a wave of that kernel keeps in registers
 
 // ---------------------------------------------------------------------------------------------
 // Load time: out[v][r] = bias[r] + sum_k w[r][k] * emb[v][k] for v < nv, r < nr (fp32 accumulation,

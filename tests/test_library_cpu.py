@@ -53,6 +53,10 @@ def test_argument_errors_without_gpu(lib):
     assert lib.wind_workspace_bytes(None, 1, 1, 1, C.byref(n)) == binding.WIND_ERR_ARG
     assert lib.wind_beam_decode(None, None, 0, 4, 4, 2, 1, None, None, 0, None, None, None, None, None, None) == binding.WIND_ERR_ARG
     assert lib.wind_beam_window_scores(None, None, 1, None, 1, 1, None, None, None, None) == binding.WIND_ERR_ARG
+    k = C.c_int32(0)
+    assert lib.wind_debug_enc_proj(None, None, None, 1, 1, None, None) == binding.WIND_ERR_ARG
+    assert lib.wind_debug_joint_keys(None, None, None, 1, 1, 1, None, C.byref(k), C.byref(k), None) == binding.WIND_ERR_ARG
+    assert lib.wind_get_joint_launches(None, None, None, 0, None) == binding.WIND_ERR_ARG
     assert lib.wind_free(None) == binding.WIND_OK
 
 

@@ -197,6 +197,25 @@ def test_joiner_matches_torch_linear():
     assert (z.numpy() == 0).any() and (z.numpy() > 0).any()          # the activation is exercised
 
 
+def test_encoder_projection_matches_torch_linear_and_the_joiner():
+    """The exported encoder half of the joiner's hidden vector: torch's linear in fp64, and the joiner
+    itself rebuilt around it (with the decoder half from torch), so that a wrong operand, a dropped bias
+    or a transposed matrix in it shows."""
+    import torch
+    import torch.nn.functional as F
+
+    cfg, w = tiny_model(12, V=5, D=9, Hp=7, Hj=11)
+    o = oracle.Oracle.from_config(cfg, w)
+    rng = np.random.default_rng(4)
+    f = rng.standard_normal(cfg.D).astype(np.float32)
+    g = rng.standard_normal(cfg.Hp)
+    t = lambda k: torch.from_numpy(w[k]).double()
+    e = o.encoder_projection(f)
+    np.testing.assert_allclose(e, F.linear(torch.from_numpy(f).double(), t("w_enc"), t("b_enc")).numpy(), rtol=0, atol=1e-12)
+    z = F.relu(torch.from_numpy(e) + F.linear(torch.from_numpy(g), t("w_pred"), t("b_pred")))
+    np.testing.assert_allclose(o.joiner(f, g), F.linear(z, t("w_out"), t("b_out")).numpy(), rtol=0, atol=1e-12)
+
+
 # ---------------------------------------------------------------------------------------------
 # Closed forms.
 def test_always_blank_model():
