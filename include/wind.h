@@ -272,7 +272,14 @@ int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, in
  *             launched one by one (the with / without graph rows of Table 5)
  *   "unroll"  loop iterations per graph launch (default 16, even)
  *   "profile" 1: time every kernel launch with events (see wind_get_kernel_times); implies no graph
- *   "recheck_kappa_milli"  width of the near-tie band of the bf16 pass, in thousandths
+ *   "recheck_kappa_milli"  kappa * 1000 (default 8000).  bf16 models screen every window row with a
+ *             bf16 hidden vector and re-decide in fp32 every label within
+ *             tau = kappa * 2.1e-3 * max_v |w_out[v]| * |z| / sqrt(Hj) of the row's largest logit (blank
+ *             included): kappa standard deviations of the difference of two screened logits, under the
+ *             assumption that the hidden units' rounding errors are independent and the weight rows are
+ *             not aligned with z (random or trained dense rows).  For rows aligned with z the error can
+ *             reach 2^-8 |w| |z| (kappa ~ 7.4 sqrt(Hj)); raise kappa for such models: the band only
+ *             costs fp32 re-evaluations, never correctness
  *   "pred_mfma_min_batch"  smallest B for which the prediction network runs on MFMA tiles
  *             (default 1; bf16 models only; below it one wave per hidden unit does fp32 FMA)
  *   "loop_kernel"  1 (default): decodes of one or two utterances with at most 32 window rows (bf16, one

@@ -700,7 +700,9 @@ struct DecideShared {
 
 // The near-tie path of decide_row: every label key at or above `thresh` is re-evaluated in fp32 (bf16
 // weight row times the hidden vector rebuilt from fp32 e and p) and the argmax over those values and
-// the fp32 blank logit is returned.  NZ = Hj / 128 rounded up: the lanes hold two hidden units per step.
+// the fp32 blank logit is returned.  A part whose SECOND key is at or above `thresh` is re-evaluated
+// whole, since the two keys it kept may hide further labels inside the band.
+// NZ = Hj / 128 rounded up: the lanes hold two hidden units per step.
 template <int NZ>
 __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, int row, int b, int frame, int nparts,
                                            int stride, int part_width, float vblank, float thresh, float2 kk0) {
@@ -728,20 +730,31 @@ __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, 
     float2 kk = make_float2(kKeyNone, kKeyNone);
     if (p0 == 0) kk = kk0;
     else if (pi < nparts) kk = prow[pi];
-#pragma unroll
-    for (int which = 0; which < 2; ++which) {
-      const float key = which ? kk.y : kk.x;
-      unsigned long long mask = __ballot(key_val(key) >= thresh);
-      while (mask) {
-        const int src = __ffsll((long long)mask) - 1;
-        mask &= mask - 1;
-        const float skey = __shfl(key, src, kWave);
-        const int col = (p0 + src) * part_width + key_col(skey);
-        if (lane == nc) mycol = col;
+    // A part keeps only its two largest keys.  If the second is inside the band, a third label of
+    // that part may be too, unseen: every column of such a part becomes a candidate.
+    const bool in1 = key_val(kk.x) >= thresh, in2 = key_val(kk.y) >= thresh;
+    unsigned long long whole = __ballot(in2), mask = __ballot(in1 && !in2);
+    while (whole) {
+      const int src = __ffsll((long long)whole) - 1;
+      whole &= whole - 1;
+      const int col0 = (p0 + src) * part_width;
+      for (int i = 0; i < part_width && col0 + i < V; ++i) {
+        if (lane == nc) mycol = col0 + i;
         if (++nc == 64) {
           evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bestv, besti);
           nc = 0;
         }
+      }
+    }
+    while (mask) {
+      const int src = __ffsll((long long)mask) - 1;
+      mask &= mask - 1;
+      const float skey = __shfl(kk.x, src, kWave);
+      const int col = (p0 + src) * part_width + key_col(skey);
+      if (lane == nc) mycol = col;
+      if (++nc == 64) {
+        evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bestv, besti);
+        nc = 0;
       }
     }
   }
@@ -779,20 +792,31 @@ __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev
     float2 kk = make_float2(kKeyNone, kKeyNone);
     if (p0 == 0) kk = kk0;
     else if (pi < nparts) kk = prow[pi];
-#pragma unroll
-    for (int which = 0; which < 2; ++which) {
-      const float key = which ? kk.y : kk.x;
-      unsigned long long mask = __ballot(key_val(key) >= thresh);
-      while (mask) {
-        const int src = __ffsll((long long)mask) - 1;
-        mask &= mask - 1;
-        const float skey = __shfl(key, src, kWave);
-        const int col = (p0 + src) * part_width + key_col(skey);
-        if (lane == nc) mycol = col;
+    // A part keeps only its two largest keys.  If the second is inside the band, a third label of
+    // that part may be too, unseen: every column of such a part becomes a candidate.
+    const bool in1 = key_val(kk.x) >= thresh, in2 = key_val(kk.y) >= thresh;
+    unsigned long long whole = __ballot(in2), mask = __ballot(in1 && !in2);
+    while (whole) {
+      const int src = __ffsll((long long)whole) - 1;
+      whole &= whole - 1;
+      const int col0 = (p0 + src) * part_width;
+      for (int i = 0; i < part_width && col0 + i < V; ++i) {
+        if (lane == nc) mycol = col0 + i;
         if (++nc == 64) {
           evaluate_candidates_wide<bf16_t, NZ>(m, zr, mycol, nc, lane, bestv, besti);
           nc = 0;
         }
+      }
+    }
+    while (mask) {
+      const int src = __ffsll((long long)mask) - 1;
+      mask &= mask - 1;
+      const float skey = __shfl(kk.x, src, kWave);
+      const int col = (p0 + src) * part_width + key_col(skey);
+      if (lane == nc) mycol = col;
+      if (++nc == 64) {
+        evaluate_candidates_wide<bf16_t, NZ>(m, zr, mycol, nc, lane, bestv, besti);
+        nc = 0;
       }
     }
   }

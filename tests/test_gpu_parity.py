@@ -358,6 +358,55 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V):
     m.close()
 
 
+@pytest.mark.parametrize("B", [3, 1])
+def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
+    """The joint kernel keeps two keys per 64-column part.  Here the label that wins in fp32 ranks THIRD
+    inside its part in the bf16 pass, 3e-3 clear of the runner-up in the oracle (so no near-tie exclusion
+    applies): the decision must still be the oracle's, because a part whose second key is inside the
+    near-tie band is re-evaluated whole.  The model is built for it: one part's weight rows are made
+    large, so that the rounding of the hidden vector moves their logits by several 1e-3, and the output
+    biases are then set so that at the first evaluation of utterance 0 every logit is known.  Both deciding
+    kernels are covered: the per-step kernels (B = 3) and the resident loop kernel (B = 1)."""
+    cfg = wi.WindConfig("third_key", 77, B, 12, 20, 64, 64, 1, 64, 256, 200, "bf16", (4,), 3, 0.7)
+    w = wi.make_weights(cfg, blank_bias=0.0, pred_gain=4.0)
+    enc, lens = wi.make_batch(cfg)
+    part = slice(64, 128)
+    scale, found = 1.0, None
+    while found is None and scale <= 64.0:
+        scale *= 2.0
+        w2 = {k: v.copy() for k, v in w.items()}
+        w2["w_out"][part] *= np.float32(scale)          # a power of two: the rows stay bf16 values
+        o = oracle.Oracle.from_config(cfg, w2)
+        g0 = o.decoder_from_scratch([])
+        z = np.maximum(o.encoder_projection(enc[0, 0]) + w2["w_pred"].astype(np.float64) @ g0 + w2["b_pred"], 0.0)
+        zb = wi.round_to_bf16(z.astype(np.float32)).astype(np.float64)
+        wz = w2["w_out"].astype(np.float64) @ z            # true products
+        noise = w2["w_out"].astype(np.float64)[part] @ (zb - z)
+        order = np.argsort(noise)
+        c3, c2, c1 = 64 + int(order[0]), 64 + int(order[-2]), 64 + int(order[-1])
+        if noise[order[-2]] - noise[order[0]] > 1.2e-2:
+            found = (c1, c2, c3)
+    assert found is not None, "no scale gave the rounding noise the construction needs"
+    c1, c2, c3 = found
+    base = 5.0
+    b_out = (base - 1.0 - wz).astype(np.float32)           # every logit of this evaluation: base - 1 ...
+    b_out[c3] = np.float32(base - wz[c3])                   # ... but the winner,
+    b_out[c1] = np.float32(base - 3e-3 - wz[c1])            # the runner-up 3e-3 below it
+    b_out[c2] = np.float32(base - 6e-3 - wz[c2])            # and the third 6e-3 below
+    w2["b_out"] = b_out
+    o = oracle.Oracle.from_config(cfg, w2)
+    ref = o.joiner(enc[0, 0], g0)
+    assert int(np.argmax(ref)) == c3 and np.sort(ref)[-1] - np.sort(ref)[-2] > 2e-3
+    screen = w2["w_out"].astype(np.float64) @ zb + b_out    # what the bf16 pass sees
+    assert screen[c1] > screen[c3] + 1e-3 and screen[c2] > screen[c3] + 1e-3, "the winner must rank third in its part"
+    m, _, _ = load(cfg, w2)
+    d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    toks, frs = m.decode(d_enc, d_len, 4, cfg.S)
+    assert toks[0][0] == c3 and frs[0][0] == 0
+    assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
+    m.close()
+
+
 def test_encoder_projection_against_oracle(torch_cuda):
     """e = W_enc f + b_enc as a decode call computes it, element by element against the oracle, on the
     route of large calls (B * T >= 16384: bf16 rows, 256 x 256 tiles) and on the route of small ones,
