@@ -140,6 +140,23 @@ int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const
                             int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream);
 
 /*
+ * The same scoring step for callers that cannot allocate device memory or wait on the stream:
+ * code under HIP graph capture, serving loops with a fixed memory budget, harnesses that forbid
+ * hipMalloc.  It calls no allocating routine and does not synchronise: the kernels are enqueued on
+ * `stream` and the call returns; the outputs are complete once the stream has passed them.  Its
+ * scratch memory (projected frames, hidden rows, logits, per-row candidates) is a static device
+ * array of WIND_STATIC_SCRATCH_BYTES inside the library, one per GPU, held until the process ends.
+ * Shapes whose scratch layout does not fit are rejected with WIND_ERR_ARG and a message that names
+ * both sizes (the layout grows with Bh * n * (V + 1) * 4 bytes of logits; 16 hypotheses x 16 frames
+ * of a 1024-label model need 1.9 MB).  Every call on a GPU uses that GPU's one array, whatever the
+ * model or stream: calls that overlap in time on one GPU race; serialise them.
+ * Arguments, outputs and tie order as wind_beam_window_scores.
+ */
+#define WIND_STATIC_SCRATCH_BYTES (8u << 20)
+int wind_beam_window_scores_static(wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
+                                   int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream);
+
+/*
  * Method, "A Novel Beam-search Algorithm for WIND", Algorithm 3, whole: beam search over one
  * utterance.  A map from frames to the hypotheses that rest there is kept on the host; the
  * hypotheses of the smallest frame t are taken out, recombined, passed through the prefix step and

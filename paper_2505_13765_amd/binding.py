@@ -17,7 +17,7 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
            "wind_get_kernel_times", "wind_get_joint_launches", "wind_beam_window_scores", "wind_beam_decode",
-           "wind_workspace_bytes", "wind_debug_enc_proj", "wind_debug_joint_keys")
+           "wind_workspace_bytes", "wind_debug_enc_proj", "wind_debug_joint_keys", "wind_beam_window_scores_static")
 PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
 
@@ -94,6 +94,7 @@ def load_library():
                                                 C.POINTER(C.c_int)]
         lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.wind_beam_window_scores_static.argtypes = lib.wind_beam_window_scores.argtypes
         lib.wind_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
         lib.wind_beam_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                          C.c_void_p, C.c_void_p, C.c_int, _I32P, C.POINTER(C.c_double),
@@ -209,6 +210,14 @@ class WindModel:
         us = (C.c_float * max(n.value, 1))()
         _check(self._lib.wind_get_joint_launches(self._h, rows, us, n.value, C.byref(n)))
         return list(rows[:n.value]), list(us[:n.value])
+
+    def beam_window_scores_static(self, enc_window, dec_out, K: int, out):
+        """wind_beam_window_scores_static: enqueues on the current stream and returns; `out` = three device
+        tensors (labels, jumps int32 [Bh, K]; scores fp32 [Bh, K]) that the caller reads after a synchronise."""
+        n, Bh = int(enc_window.shape[0]), int(dec_out.shape[0])
+        lab, jmp, sc = out
+        _check(self._lib.wind_beam_window_scores_static(self._h, enc_window.data_ptr(), n, dec_out.data_ptr(), Bh, int(K),
+                                                        lab.data_ptr(), jmp.data_ptr(), sc.data_ptr(), _stream_ptr()))
 
     def beam_window_scores(self, enc_window, dec_out, K: int, out=None):
         """wind_beam_window_scores on device tensors enc_window [n, D] and dec_out [Bh, Hp] (fp32).

@@ -11,6 +11,7 @@
 #include <cstring>
 #include <exception>
 #include <map>
+#include <mutex>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -65,6 +66,31 @@ struct GraphKey {
   bool operator==(const GraphKey &o) const { return std::memcmp(this, &o, sizeof(GraphKey)) == 0; }
 };
 
+}  // namespace
+
+// Scratch memory of the entry point that allocates nothing: one array per GPU, in the code object.  In
+// host code the name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[WIND_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+char *g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mutex;
+
+// The address of `scratch` on the current device, looked up once per device.
+int static_scratch_address(char **out) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(WIND_ERR_UNSUPPORTED, "device ordinal above 63");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[dev] = (char *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return WIND_OK;
+}
 }  // namespace
 
 // Beam search: state slots of the label sequences it has touched, and staging for its round trips.
@@ -714,6 +740,10 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
     set_tau(m);
   }
   if (rc == WIND_OK) {
+    char *unused = nullptr;
+    rc = static_scratch_address(&unused);   // once per device, here rather than in a call that must not stall
+  }
+  if (rc == WIND_OK) {
     hipError_t e = hipHostMalloc((void **)&m->h_flag, 64, hipHostMallocDefault);
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
   }
@@ -781,25 +811,65 @@ int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *l
   return decode(m, enc_out, lengths, B, T, 1, max_symbols_per_step, out_tokens, out_frames, out_counts, cap, stream);
 }
 
-int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
-                            int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream) {
+static int beam_scores_check(const wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
+                             const int32_t *out_labels, const int32_t *out_jumps, const float *out_scores) {
   if (!m || !enc_window || !dec_out || !out_labels || !out_jumps || !out_scores) return fail(WIND_ERR_ARG, "null argument");
   if (n < 1 || n > kBeamMaxWindow) return fail(WIND_ERR_ARG, "window must have 1..64 frames");
   if (K < 1 || K > kBeamMaxK) return fail(WIND_ERR_ARG, "K must be in 1..32");
   if (Bh < 1 || (long long)Bh * n > 65536) return fail(WIND_ERR_ARG, "Bh >= 1 and Bh * n <= 65536 required");
+  return WIND_OK;
+}
+
+// the scoring step's kernels, on a workspace that is already laid out
+static int beam_scores_enqueue(wind_model *m, const BeamWs &ws, const float *enc_window, int n, const float *dec_out,
+                               int Bh, int K, int32_t *out_labels, int32_t *out_jumps, float *out_scores, hipStream_t s) {
   const ModelDev &d = m->dev;
-  hipStream_t s = (hipStream_t)stream;
-  BeamWs ws;
-  int rc = beam_workspace(m, (size_t)n, (size_t)Bh, (size_t)Bh * n, &ws);
-  if (rc) return rc;
   beam_enqueue_linear(m, d.w_enc, d.b_enc, enc_window, ws.e, n, d.Hj, d.D, true, s);
   beam_enqueue_linear(m, d.w_pred, d.b_pred, dec_out, ws.p, Bh, d.Hj, d.Hp, false, s);
   beam_enqueue_logits(m, ws, ws.e, n, ws.p, beam_identity(), Bh, s);
   beam_enqueue_topk(m, ws, n, Bh, K, out_labels, out_jumps, out_scores, s);
-  rc = check_launch("beam window scores");
+  return check_launch("beam window scores");
+}
+
+int wind_beam_window_scores(wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
+                            int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream) {
+  int rc = beam_scores_check(m, enc_window, n, dec_out, Bh, K, out_labels, out_jumps, out_scores);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  BeamWs ws;
+  rc = beam_workspace(m, (size_t)n, (size_t)Bh, (size_t)Bh * n, &ws);
+  if (rc) return rc;
+  rc = beam_scores_enqueue(m, ws, enc_window, n, dec_out, Bh, K, out_labels, out_jumps, out_scores, s);
   if (rc) return rc;
   HIP_TRY(hipStreamSynchronize(s));
   return WIND_OK;
+}
+
+int wind_beam_window_scores_static(wind_model *m, const float *enc_window, int n, const float *dec_out, int Bh, int K,
+                                   int32_t *out_labels, int32_t *out_jumps, float *out_scores, void *stream) {
+  int rc = beam_scores_check(m, enc_window, n, dec_out, Bh, K, out_labels, out_jumps, out_scores);
+  if (rc) return rc;
+  const size_t rows = (size_t)Bh * n;
+  const size_t need = beam_carve(m, (size_t)n, (size_t)Bh, rows, nullptr, nullptr);
+  if (need > (size_t)WIND_STATIC_SCRATCH_BYTES)
+    return fail(WIND_ERR_ARG, "wind_beam_window_scores_static: this shape needs " + std::to_string(need) +
+                                  " bytes of scratch memory, the static buffer has " +
+                                  std::to_string((size_t)WIND_STATIC_SCRATCH_BYTES));
+  char *base = nullptr;
+  rc = static_scratch_address(&base);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  BeamWs ws;
+  beam_carve(m, (size_t)n, (size_t)Bh, rows, base, &ws);
+  // The buffer keeps the last call's contents.  The one place read before it is written: the rows
+  // between `rows` and the next multiple of the MFMA tile height (whole row tiles are fetched).
+  const size_t rows_pad = round_up(rows, JointCfg::BM), pad_ints = (rows_pad - rows) * m->dev.Hj / 2;   // bf16 pairs
+  if (pad_ints) {
+    const unsigned blocks = (unsigned)std::min<size_t>((pad_ints + 255) / 256, 256);
+    fill_int_kernel<<<blocks, 256, 0, s>>>((int *)(ws.z + rows * m->dev.Hj), (int)pad_ints, 0);
+    fill_int_kernel<<<blocks, 256, 0, s>>>((int *)(ws.z_lo + rows * m->dev.Hj), (int)pad_ints, 0);
+  }
+  return beam_scores_enqueue(m, ws, enc_window, n, dec_out, Bh, K, out_labels, out_jumps, out_scores, s);
 }
 
 int wind_workspace_bytes(const wind_model *m, int B, int T, int W, size_t *bytes) {

@@ -26,8 +26,9 @@ BeamIndex beam_inline(const int *host_values, int n) {
   return ix;
 }
 
-// Carves the scoring workspace for up to n frames, Bh hypotheses and `rows` joiner rows.
-int beam_workspace(wind_model *m, size_t n, size_t Bh, size_t rows, BeamWs *ws) {
+// Lays the scoring workspace for up to n frames, Bh hypotheses and `rows` joiner rows out from `base`
+// (null: sizes only) and returns its size in bytes.
+size_t beam_carve(const wind_model *m, size_t n, size_t Bh, size_t rows, char *base, BeamWs *ws) {
   const ModelDev &d = m->dev;
   const size_t rows_pad = round_up(rows, JointCfg::BM), V1 = (size_t)d.V + 1;
   size_t off = 0;
@@ -35,6 +36,19 @@ int beam_workspace(wind_model *m, size_t n, size_t Bh, size_t rows, BeamWs *ws) 
   const size_t o_e = take(n * d.Hj * 4), o_p = take(Bh * d.Hj * 4);
   const size_t o_z = take(rows_pad * d.Hj * 2), o_zlo = take(rows_pad * d.Hj * 2), o_lg = take(rows * V1 * 4);
   const size_t o_lse = take(rows * 4), o_blp = take(rows * 4), o_cl = take(rows * kBeamMaxK * 4), o_cv = take(rows * kBeamMaxK * 4);
+  if (base && ws) {
+    ws->e = (float *)(base + o_e); ws->p = (float *)(base + o_p); ws->logits = (float *)(base + o_lg);
+    ws->z = (bf16_t *)(base + o_z);
+    ws->z_lo = (bf16_t *)(base + o_zlo);
+    ws->lse = (float *)(base + o_lse); ws->blp = (float *)(base + o_blp); ws->cl = (float *)(base + o_cl);
+    ws->cv = (int *)(base + o_cv);
+  }
+  return off;
+}
+
+// The model's own scoring workspace, allocated on first use and regrown on demand.
+int beam_workspace(wind_model *m, size_t n, size_t Bh, size_t rows, BeamWs *ws) {
+  const size_t off = beam_carve(m, n, Bh, rows, nullptr, nullptr);
   if (off > m->beam_ws_bytes) {
     HIP_TRY(hipDeviceSynchronize());
     if (m->beam_ws) HIP_TRY(hipFree(m->beam_ws));
@@ -44,12 +58,7 @@ int beam_workspace(wind_model *m, size_t n, size_t Bh, size_t rows, BeamWs *ws) 
     m->beam_ws_bytes = off;
     HIP_TRY(hipMemset(m->beam_ws, 0, off));   // the MFMA pass reads whole row tiles
   }
-  char *base = (char *)m->beam_ws;
-  ws->e = (float *)(base + o_e); ws->p = (float *)(base + o_p); ws->logits = (float *)(base + o_lg);
-  ws->z = (bf16_t *)(base + o_z);
-  ws->z_lo = (bf16_t *)(base + o_zlo);
-  ws->lse = (float *)(base + o_lse); ws->blp = (float *)(base + o_blp); ws->cl = (float *)(base + o_cl);
-  ws->cv = (int *)(base + o_cv);
+  beam_carve(m, n, Bh, rows, (char *)m->beam_ws, ws);
   return WIND_OK;
 }
 
