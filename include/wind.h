@@ -274,6 +274,15 @@ typedef enum {
 int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches);
 
 /*
+ * Device time of the last decode call on a model, from events on the call's stream: the whole call,
+ * and the loop alone, i.e. without the once-per-call set-up (state, encoder projection of every frame,
+ * start-token step) — the "decoder-only" kind of time of Table 5, whose total also holds the encoder.
+ * In milliseconds; HOST pointers.  The loop's end is the last launch the call made (with graph replay
+ * that includes the launches that found every utterance finished).  WIND_ERR_ARG before the first call.
+ */
+int wind_get_call_times(wind_model *m, double *total_ms, double *loop_ms);
+
+/*
  * The joint kernel launch by launch, for the roofline report: after a decode call made with option
  * "profile" = 1 (bf16 models), rows[i] is the number of window rows that loop iteration i
  * evaluated (the sum of n = min(W, len - t) over its active utterances; Algorithm 2) and us[i] the
@@ -287,6 +296,9 @@ int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, in
  * Tuning knobs, for benchmarks and tests.  key/value pairs:
  *   "graph"   1 (default): the decode loop is replayed from a captured HIP graph; 0: kernels are
  *             launched one by one (the with / without graph rows of Table 5)
+ *   "host_sync"  1: the loop as a framework runs it without graphs (the rows without graph of Table 5):
+ *             every iteration's kernels are launched one by one and the host waits for them and reads the
+ *             number of active utterances before launching the next iteration (default 0; overrides "graph")
  *   "unroll"  loop iterations per graph launch (default 16, even)
  *   "profile" 1: time every kernel launch with events (see wind_get_kernel_times); implies no graph
  *   "recheck_kappa_milli"  kappa * 1000 (default 8000).  bf16 models screen every window row with a

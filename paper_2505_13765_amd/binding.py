@@ -16,7 +16,7 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0
 
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
-           "wind_get_kernel_times", "wind_get_joint_launches", "wind_beam_window_scores", "wind_beam_decode",
+           "wind_get_kernel_times", "wind_get_joint_launches", "wind_get_call_times", "wind_beam_window_scores", "wind_beam_decode",
            "wind_workspace_bytes", "wind_debug_enc_proj", "wind_debug_joint_keys", "wind_beam_window_scores_static")
 PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
@@ -90,6 +90,7 @@ def load_library():
         lib.wind_debug_enc_proj.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         lib.wind_debug_joint_keys.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                               C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
+        lib.wind_get_call_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         lib.wind_get_joint_launches.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int,
                                                 C.POINTER(C.c_int)]
         lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
@@ -201,6 +202,12 @@ class WindModel:
         n = (C.c_int64 * len(KERNEL_NAMES))()
         _check(self._lib.wind_get_kernel_times(self._h, ms, n))
         return {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_NAMES)}
+
+    def call_times(self):
+        """(total ms, loop-only ms) of the last decode call, device time from events on its stream."""
+        a, b = C.c_double(0), C.c_double(0)
+        _check(self._lib.wind_get_call_times(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     def joint_launches(self):
         """(rows, us) of every joint launch of the last decode made with option "profile" = 1."""

@@ -120,6 +120,9 @@ struct wind_model {
   GraphKey graph_key{};
   bool graph_valid = false;
   int opt_graph = 1, opt_unroll = 16;
+  int opt_host_sync = 0;   // 1: kernels one by one and the host reads the active count after every iteration
+  hipEvent_t ev_call[3] = {nullptr, nullptr, nullptr};   // last decode call: start, loop start, loop end
+  bool have_call_times = false;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_loop_kernel = 1;
   long long opt_loop_spin_limit = 1ll << 21;
@@ -524,7 +527,7 @@ int fetch_stats(wind_model *m, hipStream_t s) {
 bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *smem) {
   const ModelDev &d = m->dev;
   if (m->dtype != WIND_BF16 || d.L != 1 || B > kLoopMaxB || B * W > kLoopRows || d.Hj > kTinyMaxHj) return false;
-  if (!m->opt_loop_kernel || m->opt_profile || !m->opt_graph) return false;
+  if (!m->opt_loop_kernel || m->opt_profile || !m->opt_graph || m->opt_host_sync) return false;
   const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
   const int widest = d.Hp > d.Hj ? d.Hp : d.Hj;
   int G = (widest + 15) / 16;
@@ -562,8 +565,11 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   const bool use_loop = loop_kernel_shape(m, B, W, &lp, &loop_smem);
   m->fma_pred_step = use_loop;   // the resident kernel starts from the fp32 state of the start-token step
   if (use_loop) { c.rec = nullptr; c.lists_atomic = 0; }
+  m->have_call_times = false;
+  HIP_TRY(hipEventRecord(m->ev_call[0], s));
   rc = enqueue_prologue(m, s);
   if (rc) return rc;
+  HIP_TRY(hipEventRecord(m->ev_call[1], s));   // the loop starts here: state set up, every frame projected
   if (use_loop) {
     // the whole loop as one resident kernel
     lp.max_iters = (int)std::min<long long>((long long)T * ((long long)S + 1) + 2, 1 << 30);
@@ -572,47 +578,69 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     wind_loop_kernel<<<(unsigned)lp.G, 256, loop_smem, s>>>(m->dev, c, lp);
     rc = check_launch("resident loop");
     if (rc) return rc;
+    HIP_TRY(hipEventRecord(m->ev_call[2], s));
     HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipMemcpyAsync(m->h_flag + 1, lp.bar, sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (m->h_flag[1] != 0) return fail(WIND_ERR_HIP, "resident loop: a grid barrier timed out (workgroups not all resident?)");
     if (m->h_flag[0] != 0) return fail(WIND_ERR_HIP, "decode loop did not terminate");
+    m->have_call_times = true;
     rc = fetch_stats(m, s);
     if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
     return rc;
   }
   const int U = m->opt_unroll;
-  const bool use_graph = m->opt_graph && !m->opt_profile;   // events cannot sit between graph nodes
+  const bool use_graph = m->opt_graph && !m->opt_profile && !m->opt_host_sync;   // events cannot sit between graph nodes
   m->joint_us.clear();
   m->joint_rows.clear();
   if (use_graph) {
     rc = ensure_graph(m);
     if (rc) return rc;
   }
-  // Launch ahead by what the previous call of the same shape needed, then poll once per replay.
-  long long ahead = 1;
-  if (m->prev_B == B && m->prev_T == T && m->prev_W == W && m->prev_iters > 0) ahead = m->prev_iters / U;
-  if (ahead < 1) ahead = 1;
-  const long long max_launches = ((long long)T * ((long long)S + 1) + 2 * U) / U + 2;  // every iteration moves some pointer or emits
-  long long launches = 0;
-  for (;;) {
-    for (long long i = 0; i < ahead; ++i, ++launches) {
-      if (use_graph) {
-        HIP_TRY(hipGraphLaunch(m->graph_exec, s));
-      } else {
-        for (int it = 0; it < U; ++it) {
-          rc = enqueue_iteration(m, s, it & 1, false);
-          if (rc) return rc;
+  const long long max_iters = (long long)T * ((long long)S + 1) + 2;   // every iteration moves some pointer or emits
+  if (m->opt_host_sync) {
+    // The loop as a framework runs it without graphs (Analysis, "Incorporation with CUDA-graphs", the
+    // rows without graph of Table 5): the kernels of one iteration, then the host waits for them and
+    // reads how many utterances are still active before it launches the next iteration.
+    for (long long it = 0;; ++it) {
+      const int parity = (int)(it & 1);
+      rc = enqueue_iteration(m, s, parity, false);
+      if (rc) return rc;
+      HIP_TRY(hipEventRecord(m->ev_call[2], s));
+      HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active + (parity ^ 1), sizeof(int), hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipStreamSynchronize(s));
+      prof_collect(m);
+      if (*m->h_flag == 0) break;
+      if (it > max_iters) return fail(WIND_ERR_HIP, "decode loop did not terminate");
+    }
+  } else {
+    // Launch ahead by what the previous call of the same shape needed, then poll once per replay.
+    long long ahead = 1;
+    if (m->prev_B == B && m->prev_T == T && m->prev_W == W && m->prev_iters > 0) ahead = m->prev_iters / U;
+    if (ahead < 1) ahead = 1;
+    const long long max_launches = (max_iters + 2 * U) / U + 2;
+    long long launches = 0;
+    for (;;) {
+      for (long long i = 0; i < ahead; ++i, ++launches) {
+        if (use_graph) {
+          HIP_TRY(hipGraphLaunch(m->graph_exec, s));
+        } else {
+          for (int it = 0; it < U; ++it) {
+            rc = enqueue_iteration(m, s, it & 1, false);
+            if (rc) return rc;
+          }
         }
       }
+      ahead = 1;
+      HIP_TRY(hipEventRecord(m->ev_call[2], s));
+      HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipStreamSynchronize(s));
+      prof_collect(m);
+      if (*m->h_flag == 0) break;
+      if (launches > max_launches) return fail(WIND_ERR_HIP, "decode loop did not terminate");
     }
-    ahead = 1;
-    HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    prof_collect(m);
-    if (*m->h_flag == 0) break;
-    if (launches > max_launches) return fail(WIND_ERR_HIP, "decode loop did not terminate");
   }
+  m->have_call_times = true;
   rc = fetch_stats(m, s);
   if (c.iter_rows && (rc == WIND_OK || rc == WIND_ERR_OVERFLOW)) {
     const size_t n = (size_t)std::min<long long>(m->last_stats.iterations, kIterRowsCap);
@@ -739,6 +767,10 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
     m->wnorm_max = std::sqrt(wmax);
     set_tau(m);
   }
+  for (int i = 0; i < 3 && rc == WIND_OK; ++i) {
+    hipError_t e = hipEventCreate(&m->ev_call[i]);
+    if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipEventCreate: ") + hipGetErrorString(e));
+  }
   if (rc == WIND_OK) {
     char *unused = nullptr;
     rc = static_scratch_address(&unused);   // once per device, here rather than in a call that must not stall
@@ -795,6 +827,7 @@ int wind_free(wind_model *m) {
   beam_pool_free(m);
   if (m->h_flag) (void)hipHostFree(m->h_flag);
   for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
+  for (hipEvent_t e : m->ev_call) if (e) (void)hipEventDestroy(e);
   delete m;
   return WIND_OK;
 }
@@ -893,6 +926,17 @@ int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches) {
   return WIND_OK;
 }
 
+int wind_get_call_times(wind_model *m, double *total_ms, double *loop_ms) {
+  if (!m || !total_ms || !loop_ms) return fail(WIND_ERR_ARG, "null argument");
+  if (!m->have_call_times) return fail(WIND_ERR_ARG, "no completed decode call yet");
+  float a = 0.f, b = 0.f;
+  HIP_TRY(hipEventElapsedTime(&a, m->ev_call[0], m->ev_call[2]));
+  HIP_TRY(hipEventElapsedTime(&b, m->ev_call[1], m->ev_call[2]));
+  *total_ms = a;
+  *loop_ms = b;
+  return WIND_OK;
+}
+
 int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, int *n) {
   if (!m || !rows || !us || !n || cap < 0) return fail(WIND_ERR_ARG, "null argument");
   // launches past the last iteration found no active utterance and are left out
@@ -906,6 +950,7 @@ int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, in
 int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!m || !key) return fail(WIND_ERR_ARG, "null argument");
   if (!std::strcmp(key, "graph")) { m->opt_graph = value != 0; return WIND_OK; }
+  if (!std::strcmp(key, "host_sync")) { m->opt_host_sync = value != 0; return WIND_OK; }
   if (!std::strcmp(key, "profile")) {
     m->opt_profile = value != 0;
     for (int k = 0; k < WIND_NUM_KERNELS; ++k) { m->prof_ms[k] = 0.0; m->prof_n[k] = 0; }

@@ -520,21 +520,31 @@ def test_edge_cases(torch_cuda):
     m2.close()
 
 
-def test_determinism_and_graph_off(torch_cuda):
+def test_determinism_and_loop_modes(torch_cuda):
+    """Run to run, and across the ways the loop can be driven (graph replay with two unroll depths, kernels
+    launched one by one, and the host-synchronised loop that waits after every iteration), the output is the
+    same bit for bit — and every mode's output is the oracle's, compared directly, not through another mode."""
     cfg = wi.scaled(wi.CONFIGS["batch32"], 12, 40, 100)
     m, o, _ = load(cfg)
     enc, lens = wi.make_batch(cfg)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
-    a = m.decode(d_enc, d_len, 8, cfg.S)
-    b = m.decode(d_enc, d_len, 8, cfg.S)
-    m.set_option("graph", 0)
-    c = m.decode(d_enc, d_len, 8, cfg.S)
-    m.set_option("graph", 1)
-    m.set_option("unroll", 4)
-    d = m.decode(d_enc, d_len, 8, cfg.S)
-    for other in (b, c, d):
-        assert all(x.tolist() == y.tolist() for x, y in zip(a[0], other[0]))
-        assert all(x.tolist() == y.tolist() for x, y in zip(a[1], other[1]))
+    runs = {}
+    for W in (8, None):
+        for name, opts in (("graph", {}), ("graph again", {}), ("launches", {"graph": 0}), ("unroll 4", {"unroll": 4}),
+                           ("eager", {"host_sync": 1})):
+            for k, v in {"graph": 1, "unroll": 16, "host_sync": 0, **opts}.items():
+                m.set_option(k, v)
+            toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+            assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1, (W, name)
+            total, loop = m.call_times()
+            assert 0.0 < loop <= total
+            runs[(W, name)] = (toks, frs, m.stats().iterations)
+        a = runs[(W, "graph")]
+        for name in ("graph again", "launches", "unroll 4", "eager"):
+            other = runs[(W, name)]
+            assert all(x.tolist() == y.tolist() for x, y in zip(a[0], other[0])), (W, name)
+            assert all(x.tolist() == y.tolist() for x, y in zip(a[1], other[1])), (W, name)
+            assert a[2] == other[2]
     m.close()
 
 
