@@ -247,10 +247,11 @@ int wind_debug_enc_proj(wind_model *m, const float *enc_out, const int32_t *leng
  * The window rows are r = a * W + j for the a-th utterance with lengths > 0 and its frames
  * j = 0 .. W-1 (frames at or past the utterance's end: rows of a zero hidden vector).  The label
  * columns are cut into *nparts parts of *part_width columns; for every row and part the kernel keeps
- * the two largest logits of the part, each as one fp32 word whose low 7 mantissa bits hold
+ * the three largest logits of the part, each as one fp32 word whose low 7 mantissa bits hold
  * 127 - (column within the part): value = word with those bits cleared.  keys DEVICE float
- * [B * W, *nparts, 2] (largest, second), or NULL to query the two sizes only (HOST pointers).  A
- * part with fewer than two label columns has -3.0e38 in the unused places.  Returns after completion.
+ * [B * W, *nparts, 4] (largest, second, third, unused), or NULL to query the two sizes only (HOST
+ * pointers).  A part with fewer than three label columns has -3.0e38 in the unused places.  Returns
+ * after completion.
  */
 int wind_debug_joint_keys(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, int W,
                           float *keys, int32_t *nparts, int32_t *part_width, void *stream);

@@ -286,14 +286,15 @@ class WindModel:
         return out.cpu().numpy()
 
     def debug_joint_keys(self, enc_out, lengths, W: int):
-        """(keys [B*W, nparts, 2] fp32 numpy, part_width): the joint kernel's output for the first iteration."""
+        """(keys [B*W, nparts, 4] fp32 numpy, part_width): the joint kernel's output for the first iteration
+        (largest, second, third key of the part, one unused word)."""
         import torch
 
         B, T, _ = enc_out.shape
         nparts, width = C.c_int32(0), C.c_int32(0)
         _check(self._lib.wind_debug_joint_keys(self._h, None, None, B, T, int(W), None, C.byref(nparts), C.byref(width),
                                                _stream_ptr()))
-        out = torch.zeros((B * W, nparts.value, 2), dtype=torch.float32, device=enc_out.device)
+        out = torch.zeros((B * W, nparts.value, 4), dtype=torch.float32, device=enc_out.device)
         _check(self._lib.wind_debug_joint_keys(self._h, enc_out.data_ptr(), lengths.data_ptr(), B, T, int(W),
                                                out.data_ptr(), C.byref(nparts), C.byref(width), _stream_ptr()))
         return out.cpu().numpy(), int(width.value)

@@ -227,7 +227,7 @@ WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   w.o_p = take((size_t)B * d.Hj * 4);
   w.o_z = take(w.Mpad * d.Hj * 2);
   w.o_bl = take(w.Mpad * 4); w.o_zn = take(w.Mpad * 4);
-  w.o_parts = take(w.Mpad * (size_t)(w.nparts_tiny > w.nparts ? w.nparts_tiny : w.nparts) * 8);
+  w.o_parts = take(w.Mpad * (size_t)std::max(w.nparts_tiny * 8, w.nparts * 16));   // two keys of 32 columns, or three (+ pad) of 64
   w.o_rl = take(w.Mpad * 4);
   w.o_stats = take(kNumStats * 8);
   w.o_dbg = take(128);
@@ -285,7 +285,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   c.p = (float *)(base + o_p);
   c.z = (bf16_t *)(base + o_z);
   c.blank_logit = (float *)(base + o_bl); c.znorm = (float *)(base + o_zn);
-  c.parts = (float2 *)(base + o_parts);
+  c.parts = (float *)(base + o_parts);
   c.nparts = nparts;
   c.part_width = WsCfg<1>::WN;
   c.nparts_tiny = nparts_tiny;
@@ -1104,7 +1104,7 @@ int wind_debug_joint_keys(wind_model *m, const float *enc_out, const int32_t *le
   enqueue_joint(m, s, 0, true);
   rc = check_launch("debug joint keys");
   if (rc) return rc;
-  HIP_TRY(hipMemcpyAsync(keys, c.parts, (size_t)B * W * c.nparts * sizeof(float2), hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipMemcpyAsync(keys, c.parts, (size_t)B * W * c.nparts * sizeof(float4), hipMemcpyDeviceToDevice, s));
   HIP_TRY(hipStreamSynchronize(s));
   return WIND_OK;
 } catch (const std::exception &e) {

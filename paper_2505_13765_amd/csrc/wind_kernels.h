@@ -98,7 +98,9 @@ struct CallDev {
   bf16_t *z;                    // [Mpad][Hj]
   float *blank_logit;           // [Mpad]
   float *znorm;                 // [Mpad]
-  float2 *parts;                // [Mpad][nparts] two largest (logit, column) keys per row and part
+  // Keys: per window row and column part the largest (logit, column) keys of the part.  The joint kernel
+  // writes three per entry (four words, the last unused); the resident loop kernel keeps two (two words).
+  float *parts;                 // [Mpad][nparts][4] (joint kernel) or [rows][nparts_tiny][2] (loop kernel)
   int nparts;                   // parts per row and label columns per part, as written by the joint kernel
   int part_width;
   int nparts_tiny;              // parts per row of the resident loop kernel (32 columns each)
@@ -387,8 +389,20 @@ struct JointInitAcc {
   }
 };
 
-// Epilogue of the joint kernels: (logit, column) keys, per-row top-2 over the wave's WN columns,
-// one float2 per (row, part) to memory.  The logits never leave registers.
+// The keys of entry idx of a key array with KW words per entry (2: two keys; 4: three keys and a pad).
+template <int KW>
+__device__ __forceinline__ float4 load_keys(const float *parts, size_t idx) {
+  if constexpr (KW == 4) {
+    return reinterpret_cast<const float4 *>(parts)[idx];
+  } else {
+    const float2 k = reinterpret_cast<const float2 *>(parts)[idx];
+    return make_float4(k.x, k.y, kKeyNone, kKeyNone);
+  }
+}
+__device__ __forceinline__ float4 no_keys() { return make_float4(kKeyNone, kKeyNone, kKeyNone, kKeyNone); }
+
+// Epilogue of the joint kernel: (logit, column) keys, per-row top-3 over the wave's WN columns,
+// one float4 per (row, part) to memory.  The logits never leave registers.
 template <class Cfg>
 __device__ __forceinline__ void joint_keys_epilogue(const CallDev &c, f32x16 (&acc)[Cfg::MI][Cfg::NI],
                                                     int row0, int nt, int stride) {
@@ -397,20 +411,24 @@ __device__ __forceinline__ void joint_keys_epilogue(const CallDev &c, f32x16 (&a
   const int part = nt * Cfg::WAVES_N + wn, row_base = row0 + wm * Cfg::WM;
   // Keys are built with the column codes of the lower lane half; the upper half's columns are 4
   // higher, i.e. code bit 2 cleared (it is always set in the lower half's codes).  All keys of a
-  // lane shift alike, so the correction waits until the lane's two winners are known.
+  // lane shift alike, so the correction waits until the lane's three winners are known.
   const unsigned fix = ~(unsigned)(4 * (lane >> 5));
 #pragma unroll
   for (int mi = 0; mi < Cfg::MI; ++mi) {
-    float k1 = kKeyNone, k2 = kKeyNone;
+    float k1 = kKeyNone, k2 = kKeyNone, k3 = kKeyNone;
 #pragma unroll
     for (int ni = 0; ni < Cfg::NI; ++ni)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) push_top2(k1, k2, make_key(acc[mi][ni][r], ni * 32 + 8 * (r >> 2) + (r & 3)));
+      for (int r = 0; r < 16; ++r) push_top3(k1, k2, k3, make_key(acc[mi][ni][r], ni * 32 + 8 * (r >> 2) + (r & 3)));
     k1 = __uint_as_float(__float_as_uint(k1) & fix);
     k2 = __uint_as_float(__float_as_uint(k2) & fix);
-    const float r1 = __shfl_xor(k1, 32, kWave), r2 = __shfl_xor(k2, 32, kWave);
-    merge_top2(k1, k2, r1, r2);
-    if (lane < 32) c.parts[(size_t)(row_base + mi * 32 + lane) * stride + part] = make_float2(k1, k2);
+    k3 = __uint_as_float(__float_as_uint(k3) & fix);
+    const float r1 = __shfl_xor(k1, 32, kWave), r2 = __shfl_xor(k2, 32, kWave), r3 = __shfl_xor(k3, 32, kWave);
+    push_top3(k1, k2, k3, r1);
+    push_top3(k1, k2, k3, r2);
+    push_top3(k1, k2, k3, r3);
+    if (lane < 32)
+      reinterpret_cast<float4 *>(c.parts)[(size_t)(row_base + mi * 32 + lane) * stride + part] = make_float4(k1, k2, k3, kKeyNone);
   }
 }
 
@@ -688,6 +706,13 @@ struct DecideShared {
   int recheck;
   int is_last;
   int step_tok;                // the label whose prediction-network step follows (emitted and still active), else -1
+  // a row whose near-tie path met a column part to be re-evaluated whole leaves that part to the whole
+  // workgroup: the part (-1: none) and the best fp32 logit found so far (its label is in label[])
+  int pend_part[kMaxWindow];
+  float pend_v[kMaxWindow];
+  int n_pend;                  // rows with such a part in this window
+  float coop_v[16];            // per wave: best fp32 logit and label among its share of the part's columns
+  int coop_i[16];
   // LOCAL mode (fused few-rows kernel): per-slot state and per-row scalars kept in LDS, so that the
   // deciding workgroup does not go back to memory for them
   int4 slot[kTinyRows];        // utterance id, t, len, sym
@@ -703,11 +728,14 @@ struct DecideShared {
 // the fp32 blank logit is returned.  A part whose SECOND key is at or above `thresh` is re-evaluated
 // whole, since the two keys it kept may hide further labels inside the band.
 // NZ = Hj / 128 rounded up: the lanes hold two hidden units per step.
-template <int NZ>
+// With `defer`, the first such part is not evaluated here: it is returned in `deferred` with the best
+// logit of everything else in `best_out`, for the workgroup to evaluate together (see decide_utterance).
+template <int NZ, int KW>
 __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, int row, int b, int frame, int nparts,
-                                           int stride, int part_width, float vblank, float thresh, float2 kk0) {
+                                           int stride, int part_width, float vblank, float thresh, float4 kk0,
+                                           bool defer, int &deferred, float &best_out) {
   const int lane = threadIdx.x & 63, V = m.V;
-  const float2 *prow = c.parts + (size_t)row * stride;
+  const size_t prow = (size_t)row * stride;
   float2 ev[NZ], pv[NZ];   // requested here, first looked at behind the weight rows' requests
   const float *er = c.e + ((size_t)b * c.T + frame) * m.Hj;
   const float *pr = c.p + (size_t)b * m.Hj;
@@ -727,16 +755,19 @@ __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, 
   int mycol = 0, nc = 0;
   for (int p0 = 0; p0 < nparts; p0 += 64) {
     const int pi = p0 + lane;
-    float2 kk = make_float2(kKeyNone, kKeyNone);
+    float4 kk = no_keys();
     if (p0 == 0) kk = kk0;
-    else if (pi < nparts) kk = prow[pi];
-    // A part keeps only its two largest keys.  If the second is inside the band, a third label of
-    // that part may be too, unseen: every column of such a part becomes a candidate.
+    else if (pi < nparts) kk = load_keys<KW>(c.parts, prow + pi);
+    // A part keeps only its largest keys (three from the joint kernel, two in the resident loop kernel).
+    // If the last of them is inside the band, a further label of that part may be too, unseen: every
+    // column of such a part becomes a candidate.
     const bool in1 = key_val(kk.x) >= thresh, in2 = key_val(kk.y) >= thresh;
-    unsigned long long whole = __ballot(in2), mask = __ballot(in1 && !in2);
+    const bool all_in = KW == 4 ? key_val(kk.z) >= thresh : in2;
+    unsigned long long whole = __ballot(all_in), mask = __ballot(in1 && !all_in), mask2 = __ballot(in2 && !all_in);
     while (whole) {
       const int src = __ffsll((long long)whole) - 1;
       whole &= whole - 1;
+      if (defer && deferred < 0) { deferred = p0 + src; continue; }
       const int col0 = (p0 + src) * part_width;
       for (int i = 0; i < part_width && col0 + i < V; ++i) {
         if (lane == nc) mycol = col0 + i;
@@ -746,29 +777,36 @@ __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, 
         }
       }
     }
-    while (mask) {
-      const int src = __ffsll((long long)mask) - 1;
-      mask &= mask - 1;
-      const float skey = __shfl(kk.x, src, kWave);
-      const int col = (p0 + src) * part_width + key_col(skey);
-      if (lane == nc) mycol = col;
-      if (++nc == 64) {
-        evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bestv, besti);
-        nc = 0;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      unsigned long long todo = which ? mask2 : mask;
+      while (todo) {
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const float skey = __shfl(which ? kk.y : kk.x, src, kWave);
+        const int col = (p0 + src) * part_width + key_col(skey);
+        if (lane == nc) mycol = col;
+        if (++nc == 64) {
+          evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bestv, besti);
+          nc = 0;
+        }
       }
     }
   }
   evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bestv, besti);
+  best_out = bestv;
   return besti;
 }
 
 // The same for joint hidden sizes above 1024 (up to kDecideMaxHj): the hidden vector is combined
 // first and the weight rows are requested afterwards, which keeps the live registers within a
 // 1024-thread workgroup's share.
+template <int KW>
 __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev &c, int row, int b, int frame, int nparts,
-                                                int stride, int part_width, float vblank, float thresh, float2 kk0) {
+                                                int stride, int part_width, float vblank, float thresh, float4 kk0,
+                                                bool defer, int &deferred, float &best_out) {
   const int lane = threadIdx.x & 63, V = m.V;
-  const float2 *prow = c.parts + (size_t)row * stride;
+  const size_t prow = (size_t)row * stride;
   constexpr int NZ = kDecideMaxHj / 128;
   float2 zr[NZ];
   const float *er = c.e + ((size_t)b * c.T + frame) * m.Hj;
@@ -789,16 +827,19 @@ __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev
   int mycol = 0, nc = 0;
   for (int p0 = 0; p0 < nparts; p0 += 64) {
     const int pi = p0 + lane;
-    float2 kk = make_float2(kKeyNone, kKeyNone);
+    float4 kk = no_keys();
     if (p0 == 0) kk = kk0;
-    else if (pi < nparts) kk = prow[pi];
-    // A part keeps only its two largest keys.  If the second is inside the band, a third label of
-    // that part may be too, unseen: every column of such a part becomes a candidate.
+    else if (pi < nparts) kk = load_keys<KW>(c.parts, prow + pi);
+    // A part keeps only its largest keys (three from the joint kernel, two in the resident loop kernel).
+    // If the last of them is inside the band, a further label of that part may be too, unseen: every
+    // column of such a part becomes a candidate.
     const bool in1 = key_val(kk.x) >= thresh, in2 = key_val(kk.y) >= thresh;
-    unsigned long long whole = __ballot(in2), mask = __ballot(in1 && !in2);
+    const bool all_in = KW == 4 ? key_val(kk.z) >= thresh : in2;
+    unsigned long long whole = __ballot(all_in), mask = __ballot(in1 && !all_in), mask2 = __ballot(in2 && !all_in);
     while (whole) {
       const int src = __ffsll((long long)whole) - 1;
       whole &= whole - 1;
+      if (defer && deferred < 0) { deferred = p0 + src; continue; }
       const int col0 = (p0 + src) * part_width;
       for (int i = 0; i < part_width && col0 + i < V; ++i) {
         if (lane == nc) mycol = col0 + i;
@@ -808,19 +849,24 @@ __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev
         }
       }
     }
-    while (mask) {
-      const int src = __ffsll((long long)mask) - 1;
-      mask &= mask - 1;
-      const float skey = __shfl(kk.x, src, kWave);
-      const int col = (p0 + src) * part_width + key_col(skey);
-      if (lane == nc) mycol = col;
-      if (++nc == 64) {
-        evaluate_candidates_wide<bf16_t, NZ>(m, zr, mycol, nc, lane, bestv, besti);
-        nc = 0;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      unsigned long long todo = which ? mask2 : mask;
+      while (todo) {
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const float skey = __shfl(which ? kk.y : kk.x, src, kWave);
+        const int col = (p0 + src) * part_width + key_col(skey);
+        if (lane == nc) mycol = col;
+        if (++nc == 64) {
+          evaluate_candidates_wide<bf16_t, NZ>(m, zr, mycol, nc, lane, bestv, besti);
+          nc = 0;
+        }
       }
     }
   }
   evaluate_candidates_wide<bf16_t, NZ>(m, zr, mycol, nc, lane, bestv, besti);
+  best_out = bestv;
   return besti;
 }
 
@@ -828,14 +874,14 @@ __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev
 // inside the near-tie band re-evaluated in fp32 (see the header comment of this file).
 // kk0 = this lane's keys of the row for part `lane` (the caller loads them, possibly for several
 // rows at once so that the loads overlap); parts 64 and up are read here.
-template <class WT, bool WIDE>
+template <class WT, bool WIDE, int KW>
 __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
                                           int nparts, int stride, int part_width, float vblank, float znorm,
-                                          float2 kk0, int &n_recheck) {
+                                          float4 kk0, int &n_recheck, bool defer, int &deferred, float &best_out) {
   const int lane = threadIdx.x & 63, V = m.V;
-  const float2 *prow = c.parts + (size_t)row * stride;
+  const size_t prow = (size_t)row * stride;
   float k1 = kk0.x;
-  for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, prow[pi].x);
+  for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, load_keys<KW>(c.parts, prow + pi).x);
   const float kbest = wave_max_f32(k1);
   const float vbest = key_val(kbest);
   const float top = fmaxf(vbest, vblank);
@@ -843,23 +889,25 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
   const float thresh = top - tau;
   if (vbest < thresh) return V;                  // blank clear of every label
   // how many label keys are inside the band?
-  int cnt = (key_val(kk0.x) >= thresh) + (key_val(kk0.y) >= thresh);
+  int cnt = (key_val(kk0.x) >= thresh) + (key_val(kk0.y) >= thresh) + (key_val(kk0.z) >= thresh);
   for (int pi = lane + 64; pi < nparts; pi += 64) {
-    const float2 kk = prow[pi];
-    cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh);
+    const float4 kk = load_keys<KW>(c.parts, prow + pi);
+    cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh) + (key_val(kk.z) >= thresh);
   }
   cnt = wave_sum_i32(cnt);
   if (cnt == 1 && vblank < thresh) {
     // a single label clear of blank and of every other label: find its part
     int col = kk0.x == kbest ? lane * part_width + key_col(kbest) : -1;
     for (int pi = lane + 64; pi < nparts; pi += 64)
-      if (prow[pi].x == kbest) col = pi * part_width + key_col(kbest);
+      if (load_keys<KW>(c.parts, prow + pi).x == kbest) col = pi * part_width + key_col(kbest);
     return wave_max_i32(col);
   }
   // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
   ++n_recheck;
-  if constexpr (WIDE) return recheck_row_wide(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0);
-  else return recheck_row<8>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0);
+  if constexpr (WIDE)
+    return recheck_row_wide<KW>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0, defer, deferred, best_out);
+  else
+    return recheck_row<8, KW>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0, defer, deferred, best_out);
 }
 
 // Four window rows per wave at once, 16 lanes per row, for rows of at most 32 parts: lane 16 q + s holds
@@ -895,9 +943,12 @@ __device__ __forceinline__ int decide_rows_quad(const ModelDev &m, const CallDev
     const int q = (__ffsll((long long)todo) - 1) >> 4;
     todo &= todo - 1;
     const int jq = __builtin_amdgcn_readlane(j, 16 * q), row = a * c.W + jq;
-    const float2 kk0 = lane < nparts ? reload(row, lane) : make_float2(kKeyNone, kKeyNone);
-    const int l = decide_row<WT, false>(m, c, row, st.x, st.y + jq, nparts, nparts, part_width, readlane_f32(vblank, 16 * q),
-                                        readlane_f32(znorm, 16 * q), kk0, n_recheck);
+    float4 kk0 = no_keys();
+    if (lane < nparts) { const float2 k2 = reload(row, lane); kk0.x = k2.x; kk0.y = k2.y; }
+    int none = -1;
+    float unused = 0.f;
+    const int l = decide_row<WT, false, 2>(m, c, row, st.x, st.y + jq, nparts, nparts, part_width, readlane_f32(vblank, 16 * q),
+                                        readlane_f32(znorm, 16 * q), kk0, n_recheck, false, none, unused);
     if ((lane >> 4) == q) label = l;
   }
   if (s == 0 && j < c.W) sh.label[j] = label;
@@ -908,7 +959,7 @@ __device__ __forceinline__ int decide_rows_quad(const ModelDev &m, const CallDev
 // about the utterance so that they share the round trip of the slot table.
 constexpr int kRowsAhead = 4;
 struct RowsAhead {
-  float2 kk0[kRowsAhead];
+  float4 kk0[kRowsAhead];
   float vb[kRowsAhead], zn[kRowsAhead];
 };
 
@@ -926,21 +977,26 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
   const int b = st.x, t = st.y, len = st.z, V = m.V;
   const int n = min(c.W, len - t);
   int n_recheck = pre_recheck;   // rows_done: the caller has filled sh.label (see decide_rows_quad)
-  if (threadIdx.x == 0) sh.recheck = 0;
+  if (threadIdx.x == 0) { sh.recheck = 0; sh.n_pend = 0; }
   __syncthreads();
-  auto one_row = [&](int j, float2 k0, float vb, float zn) {
-    int label = V;
+  constexpr int KW = LOCAL ? 2 : 4;   // the resident loop kernel keeps two keys per part, the joint kernel three
+  auto one_row = [&](int j, float4 k0, float vb, float zn) {
+    int label = V, deferred = -1;
+    float best = 0.f;
     if (j < n) {
       const int row = a * c.W + j;
       if constexpr (sizeof(WT) == 4) {   // fp32 models take the argmax in joint_exact_kernel
         label = c.row_label[row];
       } else {
         if (exact_mode) label = c.row_label[row];
-        else label = decide_row<WT, WIDE>(m, c, row, b, t + j, nparts, stride, part_width, vb, zn,
-                                    lane < nparts ? k0 : make_float2(kKeyNone, kKeyNone), n_recheck);
+        else label = decide_row<WT, WIDE, KW>(m, c, row, b, t + j, nparts, stride, part_width, vb, zn,
+                                        lane < nparts ? k0 : no_keys(), n_recheck, !LOCAL, deferred, best);
       }
     }
-    if (lane == 0) sh.label[j] = label;
+    if (lane == 0) {
+      sh.label[j] = label; sh.pend_part[j] = deferred; sh.pend_v[j] = best;
+      if (deferred >= 0) atomicAdd(&sh.n_pend, 1);
+    }
   };
 #pragma unroll
   for (int q = 0; q < kRowsAhead; ++q) {
@@ -948,11 +1004,11 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
     if (!rows_done && j < c.W) one_row(j, ahead.kk0[q], ahead.vb[q], ahead.zn[q]);
   }
   for (int j = wave + kRowsAhead * nwaves; !rows_done && j < c.W; j += nwaves) {
-    float2 k0 = make_float2(kKeyNone, kKeyNone);
+    float4 k0 = no_keys();
     float vb = 0.f, zn = 0.f;
     if (!exact_mode && j < n) {
       const int row = a * c.W + j;
-      if (lane < nparts) k0 = c.parts[(size_t)row * stride + lane];
+      if (lane < nparts) k0 = load_keys<KW>(c.parts, (size_t)row * stride + lane);
       vb = LOCAL ? sh.blank[row] : c.blank_logit[row];
       zn = LOCAL ? sh.znorm[row] : c.znorm[row];
     }
@@ -960,6 +1016,56 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
   }
   if (lane == 0 && n_recheck) atomicAdd(&sh.recheck, n_recheck);
   __syncthreads();
+  if constexpr (!LOCAL && sizeof(WT) == 2) {
+    // Column parts left to the workgroup (a part's second key inside the near-tie band: all of its
+    // columns are candidates).  Every wave takes four of the part's columns per round, so a part of 64
+    // costs a 16-wave workgroup one trip to memory where the row's own wave would need sixteen.
+    for (int j = 0; !rows_done && sh.n_pend > 0 && j < n; ++j) {
+      const int part = sh.pend_part[j];   // the same for every thread
+      if (part < 0) continue;
+      const int col0 = part * part_width, ncol = min(part_width, V - col0);
+      float bv = -INFINITY;
+      int bi = 0x7FFFFFFF;
+      if (4 * wave < ncol) {
+        const float *er = c.e + ((size_t)b * c.T + t + j) * m.Hj, *pr = c.p + (size_t)b * m.Hj;
+        constexpr int NZ = WIDE ? kDecideMaxHj / 128 : 8;
+        float2 ev[NZ], pv[WIDE ? 1 : NZ];   // WIDE: the hidden vector is combined at once (fewer live registers)
+#pragma unroll
+        for (int i = 0; i < NZ; ++i) {
+          const int k = 2 * lane + 128 * i;
+          float2 e2 = make_float2(0.f, 0.f), p2 = make_float2(0.f, 0.f);
+          if (k < m.Hj) {
+            e2 = *reinterpret_cast<const float2 *>(er + k);
+            p2 = *reinterpret_cast<const float2 *>(pr + k);
+          }
+          if constexpr (WIDE) {
+            ev[i] = make_float2(fmaxf(e2.x + p2.x, 0.f), fmaxf(e2.y + p2.y, 0.f));
+          } else {
+            ev[i] = e2;
+            pv[i] = p2;
+          }
+        }
+        for (int c0 = 4 * wave; c0 < ncol; c0 += 4 * nwaves) {
+          const int nc = min(4, ncol - c0), mycol = col0 + c0 + min(lane, nc - 1);
+          if constexpr (WIDE) evaluate_candidates_wide<bf16_t, NZ>(m, ev, mycol, nc, lane, bv, bi);
+          else evaluate_candidates<NZ>(m, ev, pv, mycol, nc, lane, bv, bi);
+        }
+      }
+      if (lane == 0 && wave < 16) { sh.coop_v[wave] = bv; sh.coop_i[wave] = bi; }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        float best = sh.pend_v[j];
+        int label = sh.label[j];
+        for (int w2 = 0; w2 < min(nwaves, 16); ++w2) {
+          const float v = sh.coop_v[w2];
+          const int i = sh.coop_i[w2];
+          if (v > best || (v == best && i < label)) { best = v; label = i; }
+        }
+        sh.label[j] = label;
+      }
+      __syncthreads();
+    }
+  }
   if (wave == 0) {
     const bool nb = lane < n && sh.label[lane] != V;
     const unsigned long long mask = __ballot(nb);
@@ -1101,11 +1207,11 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
 #pragma unroll
   for (int q = 0; q < kRowsAhead; ++q) {
     const int j = wave + q * nwaves;
-    ahead.kk0[q] = make_float2(kKeyNone, kKeyNone);
+    ahead.kk0[q] = no_keys();
     ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
     if (!exact_mode && j < c.W) {
       const int row = a * c.W + j;
-      if (lane < c.nparts) ahead.kk0[q] = c.parts[(size_t)row * c.nparts + lane];
+      if (lane < c.nparts) ahead.kk0[q] = load_keys<4>(c.parts, (size_t)row * c.nparts + lane);
       ahead.vb[q] = c.blank_logit[row];
       ahead.zn[q] = c.znorm[row];
     }
@@ -2084,7 +2190,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   const float b_blank = m.b_out[m.V];
   CallDev cl = c;   // the decision code reads the keys through parts and, for near-ties, the current projections through p
   cl.p = pfull;
-  cl.parts = reinterpret_cast<float2 *>(zs);   // the iteration's keys are copied over the window rows once those are used up
+  cl.parts = reinterpret_cast<float *>(zs);   // the iteration's keys are copied over the window rows once those are used up
   constexpr int KI = kTinyMaxHj / 256;
   float4 wblank[KI];
 #pragma unroll
@@ -2268,11 +2374,14 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
 #pragma unroll
       for (int q = 0; q < kRowsAhead; ++q) {
         const int j = wave + q * 4, row = a * W + j;
-        ahead.kk0[q] = make_float2(kKeyNone, kKeyNone);
+        ahead.kk0[q] = no_keys();
         ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
         if (j < W) {
-          if (lane < c.nparts_tiny)
-            ahead.kk0[q] = direct ? ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + lane) : lparts[(size_t)row * c.nparts_tiny + lane];
+          if (lane < c.nparts_tiny) {
+            const float2 k2 = direct ? ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + lane) : lparts[(size_t)row * c.nparts_tiny + lane];
+            ahead.kk0[q].x = k2.x;
+            ahead.kk0[q].y = k2.y;
+          }
           ahead.vb[q] = sh.blank[row];
           ahead.zn[q] = sh.znorm[row];
         }

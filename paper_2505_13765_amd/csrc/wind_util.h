@@ -129,6 +129,12 @@ __device__ __forceinline__ void push_top2(float &a1, float &a2, float k) {
   a2 = __builtin_amdgcn_fmed3f(k, a1, a2);
   a1 = fmaxf(a1, k);
 }
+// the same for the three largest (a1 >= a2 >= a3)
+__device__ __forceinline__ void push_top3(float &a1, float &a2, float &a3, float k) {
+  a3 = __builtin_amdgcn_fmed3f(k, a2, a3);
+  a2 = __builtin_amdgcn_fmed3f(k, a1, a2);
+  a1 = fmaxf(a1, k);
+}
 __device__ __forceinline__ float wave_max_f32(float v) {
   v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
   v = fmaxf(v, dpp_f32<kDppRowHalfMirror>(v));

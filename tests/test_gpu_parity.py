@@ -324,8 +324,8 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V):
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     keys, width = m.debug_joint_keys(d_enc, d_len, W)
     nparts = keys.shape[1]
-    assert keys.shape == (B * W, nparts, 2) and nparts * width >= cfg.V   # whole tiles: the last parts may be empty
-    val, col = decode_keys(keys, width)
+    assert keys.shape == (B * W, nparts, 4) and nparts * width >= cfg.V   # whole tiles: the last parts may be empty
+    val, col = decode_keys(keys[:, :, :3], width)
     g0 = o.decoder_from_scratch([])
     rng = np.random.default_rng(B * 1000 + W)
     rows = set(rng.choice(B * W, size=min(B * W, 96), replace=False).tolist())
@@ -339,20 +339,16 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V):
             ref = w["b_out"][: cfg.V].astype(np.float64)
         for p in range(nparts):
             lo, hi = p * width, min((p + 1) * width, cfg.V)
-            if hi <= lo:
-                assert val[r, p, 0] < -1e38 and val[r, p, 1] < -1e38
-                continue
             part = np.sort(ref[lo:hi])[::-1]
-            c1, c2 = int(col[r, p, 0]), int(col[r, p, 1])
-            assert lo <= c1 < hi, (r, p, c1)
-            assert abs(val[r, p, 0] - ref[c1]) < TOL_BF16 and ref[c1] > part[0] - TOL_BF16, (r, p)
-            worst = max(worst, abs(val[r, p, 0] - ref[c1]))
-            if hi - lo >= 2:
-                assert lo <= c2 < hi and c2 != c1, (r, p, c1, c2)
-                assert abs(val[r, p, 1] - ref[c2]) < TOL_BF16 and ref[c2] > part[1] - TOL_BF16, (r, p)
-                assert val[r, p, 0] >= val[r, p, 1]
-            else:
-                assert val[r, p, 1] < -1e38
+            cols = [int(col[r, p, k]) for k in range(3)]
+            for k in range(3):
+                if k >= hi - lo:                      # fewer label columns than keys: the place stays empty
+                    assert val[r, p, k] < -1e38, (r, p, k)
+                    continue
+                assert lo <= cols[k] < hi and cols[k] not in cols[:k], (r, p, cols)
+                assert abs(val[r, p, k] - ref[cols[k]]) < TOL_BF16 and ref[cols[k]] > part[k] - TOL_BF16, (r, p, k)
+                assert k == 0 or val[r, p, k - 1] >= val[r, p, k]
+                worst = max(worst, abs(val[r, p, k] - ref[cols[k]]))
     print(f"{name} B={B} W={W} V={cfg.V}: {len(rows)} rows x {nparts} parts, max |key - oracle logit| = {worst:.3e}")
     assert worst > 1e-6
     m.close()
@@ -360,17 +356,18 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V):
 
 @pytest.mark.parametrize("B", [3, 1])
 def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
-    """The joint kernel keeps two keys per 64-column part.  Here the label that wins in fp32 ranks THIRD
-    inside its part in the bf16 pass, 3e-3 clear of the runner-up in the oracle (so no near-tie exclusion
-    applies): the decision must still be the oracle's, because a part whose second key is inside the
-    near-tie band is re-evaluated whole.  The model is built for it: one part's weight rows are made
+    """The joint kernel keeps three keys per 64-column part (the resident loop kernel two per 32 columns).
+    Here the label that wins in fp32 ranks FOURTH (third in the loop kernel's case) inside its part in the
+    bf16 pass, 3e-3 clear of the runner-up in the oracle (so no near-tie exclusion applies): the decision
+    must still be the oracle's, because a part whose last kept key is inside the near-tie band is
+    re-evaluated whole.  The model is built for it: one part's weight rows are made
     large, so that the rounding of the hidden vector moves their logits by several 1e-3, and the output
     biases are then set so that at the first evaluation of utterance 0 every logit is known.  Both deciding
     kernels are covered: the per-step kernels (B = 3) and the resident loop kernel (B = 1)."""
     cfg = wi.WindConfig("third_key", 77, B, 12, 20, 64, 64, 1, 64, 256, 200, "bf16", (4,), 3, 0.7)
     w = wi.make_weights(cfg, blank_bias=0.0, pred_gain=4.0)
     enc, lens = wi.make_batch(cfg)
-    part = slice(64, 128)
+    part = slice(64, 96)                                   # inside one 64-column part and one 32-column part
     scale, found = 1.0, None
     while found is None and scale <= 64.0:
         scale *= 2.0
@@ -383,26 +380,27 @@ def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
         wz = w2["w_out"].astype(np.float64) @ z            # true products
         noise = w2["w_out"].astype(np.float64)[part] @ (zb - z)
         order = np.argsort(noise)
-        c3, c2, c1 = 64 + int(order[0]), 64 + int(order[-2]), 64 + int(order[-1])
-        if noise[order[-2]] - noise[order[0]] > 1.2e-2:
-            found = (c1, c2, c3)
+        win = 64 + int(order[0])                            # the rounding lowers this label's logit the most
+        others = [64 + int(order[-1 - k]) for k in range(3)]   # and raises these three the most
+        if noise[order[-3]] - noise[order[0]] > 1.5e-2:
+            found = (win, others)
     assert found is not None, "no scale gave the rounding noise the construction needs"
-    c1, c2, c3 = found
+    win, others = found
     base = 5.0
     b_out = (base - 1.0 - wz).astype(np.float32)           # every logit of this evaluation: base - 1 ...
-    b_out[c3] = np.float32(base - wz[c3])                   # ... but the winner,
-    b_out[c1] = np.float32(base - 3e-3 - wz[c1])            # the runner-up 3e-3 below it
-    b_out[c2] = np.float32(base - 6e-3 - wz[c2])            # and the third 6e-3 below
+    b_out[win] = np.float32(base - wz[win])                 # ... but the winner
+    for k, col in enumerate(others):                        # and three labels 3e-3, 6e-3, 9e-3 below it
+        b_out[col] = np.float32(base - 3e-3 * (k + 1) - wz[col])
     w2["b_out"] = b_out
     o = oracle.Oracle.from_config(cfg, w2)
     ref = o.joiner(enc[0, 0], g0)
-    assert int(np.argmax(ref)) == c3 and np.sort(ref)[-1] - np.sort(ref)[-2] > 2e-3
+    assert int(np.argmax(ref)) == win and np.sort(ref)[-1] - np.sort(ref)[-2] > 2e-3
     screen = w2["w_out"].astype(np.float64) @ zb + b_out    # what the bf16 pass sees
-    assert screen[c1] > screen[c3] + 1e-3 and screen[c2] > screen[c3] + 1e-3, "the winner must rank third in its part"
+    assert all(screen[col] > screen[win] + 1e-3 for col in others), "the winner must rank fourth in its part"
     m, _, _ = load(cfg, w2)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     toks, frs = m.decode(d_enc, d_len, 4, cfg.S)
-    assert toks[0][0] == c3 and frs[0][0] == 0
+    assert toks[0][0] == win and frs[0][0] == 0
     assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
     m.close()
 
