@@ -40,7 +40,8 @@ typedef enum {
   WIND_ERR_ARG = -1,        /* null pointer, size out of range, inconsistent shapes */
   WIND_ERR_HIP = -2,        /* a HIP runtime call failed; see wind_last_error()      */
   WIND_ERR_OVERFLOW = -3,   /* an utterance produced more than `cap` labels          */
-  WIND_ERR_UNSUPPORTED = -4 /* a shape the kernels do not cover                      */
+  WIND_ERR_UNSUPPORTED = -4,/* a shape the kernels do not cover                      */
+  WIND_ERR_UNFINISHED = -5  /* an asynchronous decode ran out of its iteration budget */
 } wind_status;
 
 typedef enum { WIND_F32 = 0, WIND_BF16 = 1 } wind_dtype;
@@ -109,6 +110,28 @@ int wind_free(wind_model *m);
 int wind_greedy_decode(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T,
                        int W, int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
                        int32_t *out_counts, int cap, void *stream);
+
+/*
+ * wind_greedy_decode without the wait and without the library's own memory: everything the decode
+ * needs lives in `workspace` (DEVICE, 256-byte aligned, at least wind_workspace_bytes(m, B, T, W) bytes;
+ * contents on entry do not matter, the caller keeps it alive until the call has completed), the kernels
+ * are enqueued on `stream`, and the call returns.  The loop's length depends on the data, and nothing
+ * polls here: the call enqueues max_iterations loop iterations (rounded up to whole graph replays of
+ * "unroll" iterations; T * (S + 1) + 2 always suffices and is the cap), and the iterations past the end
+ * of the decode cost a few empty launches each.  wind_get_stats of a previous call of the same shape
+ * (its `iterations`) tells how many a workload needs.
+ * Completion: the next wind_get_stats on the model waits for `stream`, and returns WIND_OK, or
+ * WIND_ERR_OVERFLOW (as wind_greedy_decode), or WIND_ERR_UNFINISHED if utterances were still active
+ * after max_iterations (outputs and counts then hold the labels found up to there).  Until then the
+ * model accepts no other decode call.  Other arguments as wind_greedy_decode.  Returns WIND_ERR_ARG for
+ * a null, misaligned or too small workspace (the message names both sizes) and max_iterations < 1,
+ * WIND_ERR_UNSUPPORTED with options "graph" = 0, "profile" or "host_sync".  The first call of a shape
+ * captures and instantiates its graph (host-side work and runtime allocations).
+ */
+int wind_greedy_decode_async(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, int W,
+                             int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames,
+                             int32_t *out_counts, int cap, void *workspace, size_t workspace_bytes,
+                             int64_t max_iterations, void *stream);
 
 /*
  * Method, Algorithm 1 (the standard frame-by-frame loop; Table 1's window-size-1 row), batched
@@ -215,7 +238,8 @@ int wind_beam_decode(wind_model *m, const float *enc_out, int T, int window, int
  */
 int wind_workspace_bytes(const wind_model *m, int B, int T, int W, size_t *bytes);
 
-/* Counters of the last decode call; HOST pointer. */
+/* Counters of the last decode call; HOST pointer.  After wind_greedy_decode_async this call completes that
+ * decode first (it waits for its stream) and returns its status. */
 int wind_get_stats(wind_model *m, wind_stats *out);
 
 /*

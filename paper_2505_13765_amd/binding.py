@@ -12,10 +12,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 WIND_MAX_LAYERS = 4
 WIND_MAX_WINDOW = 64
 WIND_F32, WIND_BF16 = 0, 1
-WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED = 0, -1, -2, -3, -4
+WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED, WIND_ERR_UNFINISHED = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
-           "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
+           "wind_greedy_decode_async", "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
            "wind_get_kernel_times", "wind_get_joint_launches", "wind_get_call_times", "wind_beam_window_scores", "wind_beam_decode",
            "wind_workspace_bytes", "wind_debug_enc_proj", "wind_debug_joint_keys", "wind_beam_window_scores_static")
 PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
@@ -82,6 +82,9 @@ def load_library():
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         lib.wind_sequential_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        lib.wind_greedy_decode_async.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t,
+                                                 C.c_int64, C.c_void_p]
         lib.wind_get_stats.argtypes = [C.c_void_p, C.POINTER(WindStats)]
         lib.wind_debug_joint_logits.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                 C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -172,6 +175,17 @@ class WindModel:
         else:
             rc = self._lib.wind_greedy_decode(*args, W, *tail)
         return _check(rc, allow_overflow)
+
+    def greedy_decode_async(self, enc_out, lengths, W: int, S: int, out_tokens, out_frames, out_counts, workspace,
+                            max_iterations: int) -> None:
+        """wind_greedy_decode_async: enqueues on the current stream and returns; `workspace` is a device tensor
+        of at least workspace_bytes(B, T, W) bytes.  stats() completes the call and raises on its errors."""
+        B, T, _ = enc_out.shape
+        _check(self._lib.wind_greedy_decode_async(self._h, enc_out.data_ptr(), lengths.data_ptr(), int(B), int(T), int(W),
+                                                  int(S), out_tokens.data_ptr(), out_frames.data_ptr(),
+                                                  out_counts.data_ptr(), int(out_tokens.shape[1]), workspace.data_ptr(),
+                                                  int(workspace.numel() * workspace.element_size()), int(max_iterations),
+                                                  _stream_ptr()))
 
     def decode(self, enc_out, lengths, W: Optional[int], S: int, cap: Optional[int] = None):
         """Convenience wrapper: allocates outputs with torch and returns per-utterance numpy lists."""

@@ -123,6 +123,10 @@ struct wind_model {
   int opt_host_sync = 0;   // 1: kernels one by one and the host reads the active count after every iteration
   hipEvent_t ev_call[3] = {nullptr, nullptr, nullptr};   // last decode call: start, loop start, loop end
   bool have_call_times = false;
+  // an asynchronous decode that wind_get_stats has not completed yet
+  bool async_pending = false, async_loop = false;
+  hipStream_t async_stream = nullptr;
+  unsigned *async_bar = nullptr;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_loop_kernel = 1;
   long long opt_loop_spin_limit = 1ll << 21;
@@ -241,10 +245,30 @@ WsLayout workspace_layout(const wind_model *m, int B, int T, int W) {
   return w;
 }
 
+void carve_workspace(wind_model *m, const WsLayout &w, char *base, int B);
+
+// The model's own workspace: allocated on first use, regrown when a call needs more.
 int ensure_workspace(wind_model *m, int B, int T, int W) {
-  const ModelDev &d = m->dev;
   const WsLayout w = workspace_layout(m, B, T, W);
-  const size_t off = w.total, st = w.st;
+  if (w.total > m->ws_bytes) {
+    HIP_TRY(hipDeviceSynchronize());
+    if (m->ws) HIP_TRY(hipFree(m->ws));
+    m->ws = nullptr;
+    m->ws_bytes = 0;
+    m->graph_valid = false;
+    HIP_TRY(hipMalloc(&m->ws, w.total));
+    m->ws_bytes = w.total;
+    // window-row buffers are read tile-wide: start them defined
+    HIP_TRY(hipMemset(m->ws, 0, w.total));
+  }
+  carve_workspace(m, w, (char *)m->ws, B);
+  return WIND_OK;
+}
+
+// Points the call's arrays into a workspace laid out by workspace_layout.
+void carve_workspace(wind_model *m, const WsLayout &w, char *base, int B) {
+  const ModelDev &d = m->dev;
+  const size_t st = w.st;
   const bool big_enc = w.big_enc;
   const int slot_stride = w.slot_stride, nparts = w.nparts, nparts_tiny = w.nparts_tiny;
   const size_t o_e = w.o_e, o_encb = w.o_encb, o_len = w.o_len, o_nact = w.o_nact, o_eidx = w.o_eidx, o_eltok = w.o_eltok,
@@ -252,18 +276,7 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
                o_ticket = w.o_ticket, o_h = w.o_h, o_c = w.o_c, o_hn = w.o_hn, o_hb = w.o_hb, o_hz = w.o_hz, o_p = w.o_p,
                o_z = w.o_z, o_bl = w.o_bl, o_zn = w.o_zn, o_parts = w.o_parts, o_rl = w.o_rl, o_stats = w.o_stats,
                o_dbg = w.o_dbg, o_lbar = w.o_lbar, o_lh = w.o_lh, o_lp = w.o_lp, o_lparts = w.o_lparts;
-  if (off > m->ws_bytes) {
-    HIP_TRY(hipDeviceSynchronize());
-    if (m->ws) HIP_TRY(hipFree(m->ws));
-    m->ws = nullptr;
-    m->ws_bytes = 0;
-    m->graph_valid = false;
-    HIP_TRY(hipMalloc(&m->ws, off));
-    m->ws_bytes = off;
-    // window-row buffers are read tile-wide: start them defined
-    HIP_TRY(hipMemset(m->ws, 0, off));
-  }
-  char *base = (char *)m->ws;
+  (void)d;
   CallDev &c = m->call;
   c.e = (float *)(base + o_e);
   c.enc_b = big_enc ? (bf16_t *)(base + o_encb) : nullptr;
@@ -301,7 +314,6 @@ int ensure_workspace(wind_model *m, int B, int T, int W) {
   m->loop.h_x = (float *)(base + o_lh);
   m->loop.p_x = (float *)(base + o_lp);
   m->loop.parts_x = (float2 *)(base + o_lparts);
-  return WIND_OK;
 }
 
 int check_launch(const char *what) {
@@ -513,9 +525,6 @@ int fetch_stats(wind_model *m, hipStream_t s) {
       std::fprintf(stderr, "[wind debug] decide kernel, last workgroup avg us: rows %.2f  ticket %.2f  compaction %.2f (%lld launches); rows phase of workgroups with a near-tie %.2f (%lld), without %.2f (%lld)\n",
                    d[0] / 100.0 / d[3], d[1] / 100.0 / d[3], d[2] / 100.0 / d[3], d[3], d[4] / 100.0 / (d[5] ? d[5] : 1), d[5],
                    d[6] / 100.0 / (d[7] ? d[7] : 1), d[7]);
-    else if (d[5] > 0)
-      std::fprintf(stderr, "[wind debug] few-rows kernel, deciding workgroup, avg us: setup+gather %.2f  mfma+keys %.2f  hand-over %.2f  decide %.2f  compact %.2f  (%lld launches)\n",
-                   d[0] / 100.0 / d[5], d[1] / 100.0 / d[5], d[2] / 100.0 / d[5], d[3] / 100.0 / d[5], d[4] / 100.0 / d[5], d[5]);
     (void)hipMemset(m->call.dbg, 0, 128);
   }
   return h[ST_OVERFLOW] ? WIND_ERR_OVERFLOW : WIND_OK;
@@ -542,9 +551,14 @@ bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *s
   return *smem + 6144 <= 160 * 1024;   // room for the kernel's static LDS
 }
 
+// One decode call.  ext_ws null: the model's own workspace, and the call returns when the decode has
+// finished.  ext_ws given: the caller's workspace, at most max_iters loop iterations are enqueued and
+// the call returns at once; wind_get_stats completes it (finish_async).
 int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T, int W, int S,
-           int32_t *out_tokens, int32_t *out_frames, int32_t *out_counts, int cap, void *stream) {
+           int32_t *out_tokens, int32_t *out_frames, int32_t *out_counts, int cap, void *stream,
+           void *ext_ws = nullptr, size_t ext_bytes = 0, long long async_iters = 0) {
   if (!m) return fail(WIND_ERR_ARG, "model is null");
+  if (m->async_pending) return fail(WIND_ERR_ARG, "an asynchronous decode is pending on this model: call wind_get_stats first");
   if (!lengths || !out_tokens || !out_frames || !out_counts) return fail(WIND_ERR_ARG, "null pointer argument");
   if (B < 1 || T < 0 || cap < 1) return fail(WIND_ERR_ARG, "B >= 1, T >= 0, cap >= 1 required");
   if (T > 0 && !enc) return fail(WIND_ERR_ARG, "enc_out is null");
@@ -553,8 +567,22 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   if ((long long)B * T > (1ll << 31) - 1) return fail(WIND_ERR_ARG, "B*T too large");
   if (m->dtype == WIND_BF16 && m->dev.Hj > kDecideMaxHj) return fail(WIND_ERR_UNSUPPORTED, "Hj > 2048");
   hipStream_t s = (hipStream_t)stream;
-  int rc = ensure_workspace(m, B, T, W);
-  if (rc) return rc;
+  const bool async = ext_ws != nullptr;
+  int rc = WIND_OK;
+  if (async) {
+    const WsLayout w = workspace_layout(m, B, T, W);
+    if (ext_bytes < w.total)
+      return fail(WIND_ERR_ARG, "workspace of " + std::to_string(ext_bytes) + " bytes, this shape needs " + std::to_string(w.total));
+    if ((uintptr_t)ext_ws % 256) return fail(WIND_ERR_ARG, "workspace must be 256-byte aligned");
+    if (async_iters < 1) return fail(WIND_ERR_ARG, "max_iterations must be >= 1");
+    carve_workspace(m, w, (char *)ext_ws, B);
+    // the caller's memory may hold anything: the window rows are fetched tile-wide, so they start defined
+    const size_t zi = w.Mpad * (size_t)m->dev.Hj / 2;
+    fill_int_kernel<<<(unsigned)std::min<size_t>((zi + 255) / 256, 2048), 256, 0, s>>>((int *)m->call.z, (int)zi, 0);
+  } else {
+    rc = ensure_workspace(m, B, T, W);
+    if (rc) return rc;
+  }
   CallDev &c = m->call;
   c.B = B; c.T = T; c.W = W; c.S = S; c.cap = cap;
   c.enc = enc; c.lengths = lengths;
@@ -563,6 +591,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   LoopDev lp = m->loop;
   size_t loop_smem = 0;
   const bool use_loop = loop_kernel_shape(m, B, W, &lp, &loop_smem);
+  const long long max_iters = (long long)T * ((long long)S + 1) + 2;   // every iteration moves some pointer or emits
   m->fma_pred_step = use_loop;   // the resident kernel starts from the fp32 state of the start-token step
   if (use_loop) { c.rec = nullptr; c.lists_atomic = 0; }
   m->have_call_times = false;
@@ -572,13 +601,20 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   HIP_TRY(hipEventRecord(m->ev_call[1], s));   // the loop starts here: state set up, every frame projected
   if (use_loop) {
     // the whole loop as one resident kernel
-    lp.max_iters = (int)std::min<long long>((long long)T * ((long long)S + 1) + 2, 1 << 30);
+    lp.max_iters = (int)std::min<long long>(async ? std::min(async_iters, max_iters) : max_iters, 1 << 30);
     lp.spin_limit = (unsigned)m->opt_loop_spin_limit;
-    HIP_TRY(hipMemsetAsync(lp.bar, 0, (size_t)(1 + lp.G) * kLoopFlagStride * 4, s));
+    {
+      const int bar_ints = (1 + lp.G) * kLoopFlagStride;
+      fill_int_kernel<<<(unsigned)((bar_ints + 255) / 256), 256, 0, s>>>((int *)lp.bar, bar_ints, 0);
+    }
     wind_loop_kernel<<<(unsigned)lp.G, 256, loop_smem, s>>>(m->dev, c, lp);
     rc = check_launch("resident loop");
     if (rc) return rc;
     HIP_TRY(hipEventRecord(m->ev_call[2], s));
+    if (async) {
+      m->async_pending = true; m->async_loop = true; m->async_stream = s; m->async_bar = lp.bar;
+      return WIND_OK;
+    }
     HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipMemcpyAsync(m->h_flag + 1, lp.bar, sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
@@ -597,7 +633,16 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     rc = ensure_graph(m);
     if (rc) return rc;
   }
-  const long long max_iters = (long long)T * ((long long)S + 1) + 2;   // every iteration moves some pointer or emits
+  if (async) {
+    // no polling: the iterations the caller allows, in whole replays; kernels of iterations past the
+    // end of the decode find no active utterance and leave at once
+    if (!use_graph) return fail(WIND_ERR_UNSUPPORTED, "the asynchronous decode needs graph replay (options graph, profile, host_sync)");
+    const long long replays = (std::min(async_iters, max_iters) + U - 1) / U;
+    for (long long i = 0; i < replays; ++i) HIP_TRY(hipGraphLaunch(m->graph_exec, s));
+    HIP_TRY(hipEventRecord(m->ev_call[2], s));
+    m->async_pending = true; m->async_loop = false; m->async_stream = s;
+    return WIND_OK;
+  }
   if (m->opt_host_sync) {
     // The loop as a framework runs it without graphs (Analysis, "Incorporation with CUDA-graphs", the
     // rows without graph of Table 5): the kernels of one iteration, then the host waits for them and
@@ -913,11 +958,44 @@ int wind_workspace_bytes(const wind_model *m, int B, int T, int W, size_t *bytes
   return WIND_OK;
 }
 
+// Completes an asynchronous decode: waits for its stream, reads the counters and the loop's end state.
+static int finish_async(wind_model *m) {
+  hipStream_t s = m->async_stream;
+  m->async_pending = false;
+  m->h_flag[0] = m->h_flag[1] = 0;
+  HIP_TRY(hipMemcpyAsync(m->h_flag, m->call.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
+  if (m->async_loop) HIP_TRY(hipMemcpyAsync(m->h_flag + 2, m->async_bar, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (m->async_loop && m->h_flag[2] != 0)
+    return fail(WIND_ERR_HIP, "resident loop: a grid barrier timed out (workgroups not all resident?)");
+  int rc = fetch_stats(m, s);
+  m->have_call_times = true;
+  m->prev_B = m->call.B; m->prev_T = m->call.T; m->prev_W = m->call.W;
+  m->prev_iters = m->last_stats.iterations;
+  // whole replays are an even number of iterations, so the last one left its count in the first slot
+  if (m->h_flag[0] != 0) {
+    if (rc == WIND_OK || rc == WIND_ERR_OVERFLOW)
+      return fail(WIND_ERR_UNFINISHED, "the decode did not finish within max_iterations: outputs hold the labels found so far");
+  }
+  if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
+  return rc;
+}
+
 int wind_get_stats(wind_model *m, wind_stats *out) {
   if (!m || !out) return fail(WIND_ERR_ARG, "null argument");
-  if (!m->have_stats) return fail(WIND_ERR_ARG, "no decode call yet");
+  int rc = WIND_OK;
+  if (m->async_pending) rc = finish_async(m);
+  if (!m->have_stats) return rc != WIND_OK ? rc : fail(WIND_ERR_ARG, "no decode call yet");
   *out = m->last_stats;
-  return WIND_OK;
+  return rc;
+}
+
+int wind_greedy_decode_async(wind_model *m, const float *enc_out, const int32_t *lengths, int B, int T, int W,
+                             int max_symbols_per_step, int32_t *out_tokens, int32_t *out_frames, int32_t *out_counts,
+                             int cap, void *workspace, size_t workspace_bytes, int64_t max_iterations, void *stream) {
+  if (!workspace) return fail(WIND_ERR_ARG, "workspace is null");
+  return decode(m, enc_out, lengths, B, T, W, max_symbols_per_step, out_tokens, out_frames, out_counts, cap, stream,
+                workspace, workspace_bytes, (long long)max_iterations);
 }
 
 int wind_get_kernel_times(wind_model *m, double *ms, int64_t *launches) {

@@ -546,6 +546,49 @@ def test_determinism_and_loop_modes(torch_cuda):
     m.close()
 
 
+@pytest.mark.parametrize("name,B,lo,hi,W", [("batch32", 9, 30, 140, 8), ("greedy_b1", 1, 150, 150, 16), ("largevocab_b128", 20, 20, 70, 4)])
+def test_async_decode_on_a_caller_workspace(torch_cuda, name, B, lo, hi, W):
+    """wind_greedy_decode_async (caller's workspace, no wait) against wind_greedy_decode: same labels, frames,
+    counts and counters, with a workspace full of NaN patterns, with the iteration budget at its cap and at
+    exactly what the decode needs; too small a budget or workspace is reported, and the model works on."""
+    from paper_2505_13765_amd.binding import WindError, WIND_ERR_UNFINISHED, WIND_ERR_ARG
+
+    torch = torch_cuda
+    cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
+    m, o, _ = load(cfg)
+    enc, lens = wi.make_batch(cfg)
+    d_enc, d_len = to_dev(torch, enc, lens)
+    T = enc.shape[1]
+    toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+    st = m.stats()
+    ref = (st.iterations, st.windows, st.rows, st.labels, st.forced_advances)
+    cap = T * cfg.S
+    ws = torch.full((m.workspace_bytes(B, T, W) + 256,), 0xFF, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:][: m.workspace_bytes(B, T, W)]
+    for budget in (T * (cfg.S + 1) + 2, st.iterations):
+        out = (torch.full((B, cap), -5, dtype=torch.int32, device="cuda"), torch.full((B, cap), -5, dtype=torch.int32, device="cuda"),
+               torch.full((B,), -5, dtype=torch.int32, device="cuda"))
+        m.greedy_decode_async(d_enc, d_len, W, cfg.S, *out, ws, budget)
+        st2 = m.stats()                       # waits for the stream and completes the call
+        assert (st2.iterations, st2.windows, st2.rows, st2.labels, st2.forced_advances) == ref
+        cnt = out[2].cpu().numpy()
+        assert cnt.tolist() == [len(t) for t in toks]
+        tok, frm = out[0].cpu().numpy(), out[1].cpu().numpy()
+        for b in range(B):
+            assert tok[b, : cnt[b]].tolist() == toks[b].tolist() and frm[b, : cnt[b]].tolist() == frs[b].tolist()
+    if st.iterations > 40:
+        m.greedy_decode_async(d_enc, d_len, W, cfg.S, *out, ws, st.iterations // 2)
+        with pytest.raises(WindError) as err:
+            m.stats()
+        assert err.value.code == WIND_ERR_UNFINISHED
+    with pytest.raises(WindError) as err:
+        m.greedy_decode_async(d_enc, d_len, W, cfg.S, *out, ws[: ws.numel() // 2], 10)
+    assert err.value.code == WIND_ERR_ARG and "needs" in str(err.value)
+    toks3, frs3 = m.decode(d_enc, d_len, W, cfg.S)
+    assert all(a.tolist() == b.tolist() for a, b in zip(toks, toks3))
+    m.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # Full-size workloads in the launch configuration bench.py times: EVERY utterance is checked against
 # the oracle (about 100 s of CPU on 16 threads for the four workloads together).  WIND_SAMPLE_PARITY=1

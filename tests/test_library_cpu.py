@@ -47,6 +47,7 @@ def test_argument_errors_without_gpu(lib):
     assert lib.wind_load_weights(C.byref(w), None, C.byref(out)) == binding.WIND_ERR_ARG   # null weight pointers
     assert lib.wind_greedy_decode(None, None, None, 1, 1, 1, 1, None, None, None, 1, None) == binding.WIND_ERR_ARG
     assert lib.wind_sequential_decode(None, None, None, 1, 1, 1, None, None, None, 1, None) == binding.WIND_ERR_ARG
+    assert lib.wind_greedy_decode_async(None, None, None, 1, 1, 1, 1, None, None, None, 1, None, 0, 1, None) == binding.WIND_ERR_ARG
     assert lib.wind_get_stats(None, None) == binding.WIND_ERR_ARG
     assert lib.wind_set_option(None, b"graph", 1) == binding.WIND_ERR_ARG
     n = C.c_size_t(0)
