@@ -54,27 +54,73 @@ def run_workload(torch, wi, WindModel, name, windows, steps, warmup, with_sequen
     res = {}
     ws = list(windows or cfg.windows)
     for W in ([None] if with_sequential else []) + ws:
+        cold = None
+        if not res:
+            # the model's first call: workspace allocation, graph capture and instantiation, no launch-ahead
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            model.greedy_decode(d_enc, d_len, W, cfg.S, *out)
+            torch.cuda.synchronize()
+            cold = (time.perf_counter() - t0) * 1e3
         sec = timed_decodes(torch, model, d_enc, d_len, W, cfg.S, steps, warmup, out)
         st = model.stats()
         res["seq" if W is None else str(W)] = {
+            **({"cold_first_call_ms": cold} if cold is not None else {}),
             "frames_per_s": frames / sec, "rtfx": frames * FRAME_SECONDS / sec, "ms_per_step": sec * 1e3,
             "iterations": int(st.iterations), "rows": int(st.rows), "useful_rows": int(st.useful_rows),
             "labels": int(st.labels), "rechecks": int(st.rechecks),
             # pointer advance per window, 0..W (Analysis, Jump Distribution)
             "jump_hist": [int(x) for x in st.jump_hist[:(1 if W is None else W) + 1]]}
+    # what the synthetic workload turned out to be (the configurations state targets): blank share of the
+    # standard loop's joiner evaluations, and how many labels the emitting frames carry
+    import numpy as np
+
+    cnt = out[2].cpu().numpy()
+    frm = out[1].cpu().numpy()
+    per_frame = np.zeros(cfg.S + 1, np.int64)
+    for b in range(B):
+        if cnt[b]:
+            per_frame += np.bincount(np.bincount(frm[b, : cnt[b]]), minlength=cfg.S + 1)[: cfg.S + 1]
+    per_frame[0] = 0
+    evals = frames + int(st.labels) - int(st.forced_advances)
+    res["workload_stats"] = {
+        "blank_share_of_evaluations": round((frames - int(st.forced_advances)) / max(evals, 1), 4),
+        "target_blank_share": cfg.blank_rate, "labels": int(st.labels), "forced_advances": int(st.forced_advances),
+        "emitting_frames_by_label_count": {str(k): int(v) for k, v in enumerate(per_frame) if k and v}}
     return cfg, model, (d_enc, d_len, out), frames, res, (enc, lens, w)
 
 
+KERNEL_SOURCES = ("paper_2505_13765_amd/csrc/wind_kernels.h", "paper_2505_13765_amd/csrc/wind_mfma_ws.h",
+                  "paper_2505_13765_amd/csrc/wind_mfma_dma.h", "paper_2505_13765_amd/csrc/wind_util.h")
+
+
+def kernel_source_digest():
+    """One hash over the kernel sources: a counter summary under profiles/ names the digest it was measured at."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(cfg, W):
-    """HBM bytes per joint launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE runs, scaled by a copy kernel of known size), if there is one for this workload."""
+    """HBM bytes per joint launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs,
+    scaled by a copy kernel of known size), and whether that summary was measured on the kernel sources as
+    they are now.  A summary of older kernels is not reported as this build's traffic."""
     path = os.path.join(ROOT, "profiles", f"joint_hbm_traffic_{cfg.name}_w{W}.txt")
     if not os.path.exists(path):
-        return None
+        return None, "no counter summary for this workload"
+    traffic, digest = None, None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":")[1])
-    return None
+            traffic = float(line.split(":")[1])
+        if line.startswith("kernel_source_digest:"):
+            digest = line.split(":")[1].strip()
+    if digest != kernel_source_digest():
+        return None, f"summary measured at kernel sources {digest}, these are {kernel_source_digest()}: stale, not reported"
+    return traffic, f"measured at kernel sources {digest} (current)"
 
 
 def roofline_leg(torch, cfg, model, dev, W):
@@ -107,11 +153,17 @@ def roofline_leg(torch, cfg, model, dev, W):
     flops = 2.0 * cfg.Hj * (cfg.V + 1) * st.rows
     achieved = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
     # bytes the joint kernel must move per launch: W_out once, the window rows once, the keys out
+    traffic, traffic_note = measured_traffic(cfg, W)
+    rows_per_launch = st.rows / max(n, 1)
+    algorithmic_bytes = cfg.Hj * (cfg.V + 1) * 2 + rows_per_launch * cfg.Hj * 2 + rows_per_launch * ((cfg.V + 63) // 64) * 16
     return {
-        "bound": "mfma", "kernel": "joint_kernel", "workload": f"{cfg.name} W={W}",
+        "bound": "mfma", "kernel": "joint_ws_kernel", "workload": f"{cfg.name} W={W}",
         "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-        "traffic": measured_traffic(cfg, W), "launches": int(n), "avg_launch_us": ms * 1e3 / max(n, 1),
-        "rows_per_launch": st.rows / max(n, 1), "flops_per_row": 2.0 * cfg.Hj * (cfg.V + 1),
+        "traffic": traffic, "traffic_source": traffic_note,
+        "hbm_frac": (traffic / (ms * 1e-3 / max(n, 1)) / 1e9 / PEAK_HBM_GBS) if traffic else None,
+        "launches": int(n), "avg_launch_us": ms * 1e3 / max(n, 1),
+        "rows_per_launch": rows_per_launch, "flops_per_row": 2.0 * cfg.Hj * (cfg.V + 1),
+        "algorithmic_bytes_per_launch": round(algorithmic_bytes),
         "kernel_ms": {k: round(v[0], 3) for k, v in kt.items()},
         "kernel_launches": {k: int(v[1]) for k, v in kt.items()},
         "by_rows": buckets,
@@ -268,7 +320,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ablation", action="store_true", help="skip the graph / no-graph table at batch 16")
     ap.add_argument("--beam-only", action="store_true", help="only the beam-search figures (for profiling them)")
+    ap.add_argument("--print-kernel-digest", action="store_true",
+                    help="print the hash of the kernel sources that counter summaries under profiles/ record, and exit")
     args = ap.parse_args()
+    if args.print_kernel_digest:
+        print(kernel_source_digest())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (utterances are independent; more GPUs would "
                  "each decode their own share with no exchange); --gpus must be 1")
@@ -293,12 +350,14 @@ def main():
     if args.roofline_only:
         rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload,
                                                             [args.roofline_window], 1, 0, with_sequential=False)
+        rres.pop("workload_stats")
         roof = roofline_leg(torch, rcfg, rmodel, rdev, args.roofline_window)
         print(json.dumps({"roofline": roof}))
         return
 
     cfg, model, dev, frames, res, host = run_workload(torch, wi, WindModel, args.workload, None,
                                                       args.steps, args.warmup, with_sequential=True)
+    wstats = res.pop("workload_stats")
     best_w = max((k for k in res if k != "seq"), key=lambda k: res[k]["frames_per_s"])
     line = {
         "metric": "encoder frames decoded/sec", "value": res[best_w]["frames_per_s"], "unit": "frames/s",
@@ -307,7 +366,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} T~{cfg.len_hi} D={cfg.D} Hj={cfg.Hj} V={cfg.V}+blank "
                                f"L={cfg.L} S={cfg.S}", "window": int(best_w), "frames_per_step": frames},
-        "rtfx": res[best_w]["rtfx"],
+        "rtfx": res[best_w]["rtfx"], "workload_stats": wstats,
         "sweep": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                   for k, v in res.items()},
         "speedup_vs_w1": {k: res[k]["frames_per_s"] / res["1"]["frames_per_s"] for k in res if "1" in res},
@@ -330,7 +389,8 @@ def main():
             if name in (args.workload, args.roofline_workload):
                 continue
             ocfg, omodel, odev, oframes, ores, _ = run_workload(torch, wi, WindModel, name, None, 2, 1, with_sequential=True)
-            others[name] = {"frames_per_call": oframes,
+            ostats = ores.pop("workload_stats")
+            others[name] = {"frames_per_call": oframes, "workload_stats": ostats,
                             "ms_per_step": {k: round(v["ms_per_step"], 3) for k, v in ores.items()},
                             "frames_per_s": {k: round(v["frames_per_s"], 1) for k, v in ores.items()}}
             omodel.close()
@@ -340,7 +400,10 @@ def main():
     if not args.no_roofline:
         rcfg, rmodel, rdev, rframes, rres, _ = run_workload(torch, wi, WindModel, args.roofline_workload, None,
                                                             max(1, min(args.steps, 3)), 1, with_sequential=False)
+        rstats = rres.pop("workload_stats")
         roof = roofline_leg(torch, rcfg, rmodel, rdev, args.roofline_window)
+        roof["workload_stats"] = rstats
+        roof["cold_first_call_ms"] = round(next(iter(rres.values())).get("cold_first_call_ms", 0.0), 3)
         roof["frames_per_s"] = {k: round(v["frames_per_s"], 1) for k, v in rres.items()}
         roof["ms_per_step"] = {k: round(v["ms_per_step"], 3) for k, v in rres.items()}
         line["roofline"] = roof

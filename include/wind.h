@@ -142,8 +142,8 @@ int wind_sequential_decode(wind_model *m, const float *enc_out, const int32_t *l
                            int32_t *out_counts, int cap, void *stream);
 
 /*
- * Method, "A Novel Beam-search Algorithm for WIND": the scoring step of Algorithm 3 (its lines
- * 10-13) for Bh hypotheses that sit on the same frame.  For every hypothesis b the joiner is
+ * Method, "A Novel Beam-search Algorithm for WIND": the scoring step of Algorithm 3 (joiner on the
+ * window, P' of Eq. 1, the K best pairs) for Bh hypotheses that sit on the same frame.  For every hypothesis b the joiner is
  * evaluated on the n frames of the window against that hypothesis' prediction-network output, the
  * rows are soft-maxed, and P'(v, t) of Eq. 1 is formed: the probability that v is the first output
  * in the window and comes at frame t (blank: only as "no output in the whole window", t = n - 1).
@@ -267,7 +267,7 @@ int wind_debug_enc_proj(wind_model *m, const float *enc_out, const int32_t *leng
 
 /*
  * Debug: what the joint kernel of a decode call leaves behind for the first loop iteration
- * (Algorithm 2: joined = joiner(window, decoder([])), labels = argmax over each row), bf16 models.
+ * (Algorithm 2: the joiner on the first window against the start state, and each row's argmax), bf16 models.
  * The window rows are r = a * W + j for the a-th utterance with lengths > 0 and its frames
  * j = 0 .. W-1 (frames at or past the utterance's end: rows of a zero hidden vector).  The label
  * columns are cut into *nparts parts of *part_width columns; for every row and part the kernel keeps

@@ -9,7 +9,7 @@ that it comes at frame t0 + t (Eq. 1):
     P'(v, t)      = P(v | t0 + t) * prod_{t' < t} P(blank | t0 + t')     for v != blank
 
 with P(. | t) the softmax of the joiner's V+1 logits at that frame.  Algorithm 3 then takes, for
-every hypothesis, the K best (label, jump) pairs under P' (its lines 12-13).  Everything here is
+every hypothesis, the K best (label, jump) pairs under P'.  Everything here is
 fp64 numpy written straight from those definitions; plain and slow on purpose.
 
 Readings where the paper is silent: scores are returned as log P' (the algorithm's update lines

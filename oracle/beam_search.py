@@ -1,8 +1,9 @@
 """CPU oracle for the whole WIND beam search (test infrastructure, not a product path).
 
-Follows the section "A Novel Beam-search Algorithm for WIND", Algorithm 3, step by step and in its
-notation: a map t2hyps from frame to the hypotheses that rest there; the hypotheses of the smallest
-frame are taken out, passed through recombine_prune_prefix_search, scored on the window
+Follows the section "A Novel Beam-search Algorithm for WIND", Algorithm 3, step by step: a map
+(`resting`) from frame to the hypotheses that rest there; the hypotheses of the smallest frame are
+taken out, merged, extended by their prefixes and pruned (merge_extend_prune: the three steps the
+section lists under the algorithm), scored on the window
 enc[t : t+n] with P'(v, t) of Eq. 1 (oracle/beam_scores.py), and each of their K best (label, jump)
 pairs is put back at the frame it leads to.  Scores are natural-log probabilities in fp64; the
 model pieces (decoder step, joiner) are the C oracle's.
@@ -12,7 +13,7 @@ Readings where the paper is silent or leaves the detail to its implementation:
     it has put on its current frame (`sym`); a label found at jump 0 adds one, a label found further
     in restarts the count at 1; when the count reaches S the hypothesis moves one frame on and the
     count clears, at no cost in score.  An all-blank window clears the count.
-  * Step 1 of recombine_prune_prefix_search, duplicates: probabilities are added (log-add-exp); the
+  * Step 1 of merge_extend_prune, duplicates: probabilities are added (log-add-exp); the
     time stamps and the label count of the more probable duplicate are kept (equal scores: the
     lexicographically smaller time stamps, then the smaller count).
   * Step 2, prefixes: for every pair (A, B) with A a proper prefix of B, the probability of
@@ -32,7 +33,7 @@ Readings where the paper is silent or leaves the detail to its implementation:
     token sequence).
   * An expansion slot with probability zero (K larger than the number of non-zero entries) adds
     nothing.
-  * The result is the most probable entry of t2hyps[T] after its duplicates have been combined as
+  * The result is the most probable entry of resting[T] after its duplicates have been combined as
     in step 1 (no prefix step: no frame is left to complete on).  T = 0 returns the empty
     hypothesis with score 0.
 
@@ -44,7 +45,9 @@ is below its error, and only there; the comparison protocol in tests/ uses these
 
 Pins (tests/test_oracle_beam_search_pins.py): brute-force enumeration of every alignment of tiny
 lattices, the greedy decoder at beam 1 / window 1, alignment log-probabilities at beam 1, hand-built
-prefix sets.  Parity unpinned: the readings listed above themselves (safeguard, duplicates, what
+prefix sets, and a second writing of the whole search from the section's prose (flat table, decoder
+rebuilt from nothing, probabilities multiplied as Eq. 1 prints them) that must agree on every final
+hypothesis in all three prefix modes.  Parity unpinned: the readings listed above themselves (safeguard, duplicates, what
 happens to a prefix, tie rules), for which the paper refers to its implementation; the pins fix
 what follows from Eq. 1 and the printed steps of Algorithm 3 under those readings.
 """
@@ -80,7 +83,7 @@ class Round:
     """What one pass of the while-loop saw and chose (for the lockstep comparison)."""
     t: int
     n: int
-    hyps: List[Hyp]                                  # after recombine_prune_prefix_search, best first
+    hyps: List[Hyp]                                  # after merge_extend_prune, best first
     expansions: List[List[Tuple[int, int, float]]]   # per hypothesis: (label, jump, log P'), best first
     margin: float                                    # smallest gap of a choice between hypotheses (steps 1, 3)
     expansion_margin: float = np.inf                 # smallest gap between a hypothesis' K-th and (K+1)-th pair
@@ -134,7 +137,7 @@ def recombine(hyps: List[Hyp]) -> Tuple[List[Hyp], float]:
     return out, margin
 
 
-def recombine_prune_prefix_search(hyps: List[Hyp], K: int, S: int,
+def merge_extend_prune(hyps: List[Hyp], K: int, S: int,
                                   log_prob: Callable[[Tuple[int, ...], int], float],
                                   prefix_step: str = "keep") -> Tuple[List[Hyp], float, int]:
     """The three steps listed under Algorithm 3.  log_prob(prefix, v) = log P(v | current frame,
@@ -175,18 +178,18 @@ def wind_beam_search(model, enc: np.ndarray, N: int, K: int, S: int, prefix_step
                      expansions_per_hyp: Optional[int] = None, trace: Optional[List[Round]] = None):
     """Algorithm 3 on one utterance: enc [T, D] encoder outputs, window N, beam K, at most S labels
     per frame.  expansions_per_hyp defaults to K (the algorithm's [B, K] arrays); the brute-force
-    pin sets both to "everything".  Returns (best Hyp, final list of t2hyps[T] after recombination,
+    pin sets both to "everything".  Returns (best Hyp, final list of resting[T] after recombination,
     smallest margin of the final choice)."""
     enc = np.asarray(enc, dtype=np.float32)
     T = enc.shape[0]
     Kx = K if expansions_per_hyp is None else expansions_per_hyp
     dec = DecoderCache(model)
-    t2hyps: Dict[int, List[Hyp]] = {0: [Hyp((), (), 0.0, 0)]}
-    while t2hyps:
-        t = min(t2hyps.keys())
+    resting: Dict[int, List[Hyp]] = {0: [Hyp((), (), 0.0, 0)]}
+    while resting:
+        t = min(resting.keys())
         if t == T:
             break
-        hyps = t2hyps.pop(t)
+        hyps = resting.pop(t)
 
         dist = {}                                  # log P(. | t, decoder(prefix)), evaluated once per prefix
 
@@ -195,7 +198,7 @@ def wind_beam_search(model, enc: np.ndarray, N: int, K: int, S: int, prefix_step
                 dist[prefix] = bs.log_softmax(model.joiner(enc[t], dec.out(prefix)))
             return float(dist[prefix][v])
 
-        hyps, margin, n_pairs = recombine_prune_prefix_search(hyps, K, S, log_prob, prefix_step)
+        hyps, margin, n_pairs = merge_extend_prune(hyps, K, S, log_prob, prefix_step)
         n = min(N, T - t)
         dec_out = np.stack([dec.out(h.tokens) for h in hyps])
         labels, jumps, scores, full = bs.beam_window(model, enc[t:t + n], dec_out, Kx)
@@ -205,22 +208,22 @@ def wind_beam_search(model, enc: np.ndarray, N: int, K: int, S: int, prefix_step
             rec.expansions.append([(int(labels[b, k]), int(jumps[b, k]), float(scores[b, k]))
                                    for k in range(Kx) if labels[b, k] >= 0])
             for k in range(Kx):
-                new_token, jump = int(labels[b, k]), int(jumps[b, k])
-                if new_token < 0:
+                label, jump = int(labels[b, k]), int(jumps[b, k])
+                if label < 0:
                     continue
-                if new_token != model.V:
+                if label != model.V:
                     sym = hyp.sym + 1 if jump == 0 else 1
                     tn = t + jump
                     if sym >= S:                       # safeguard: leave the frame after S labels
                         tn, sym = tn + 1, 0
-                    new = Hyp(hyp.tokens + (new_token,), hyp.frames + (t + jump,), hyp.score + scores[b, k], sym)
-                    t2hyps.setdefault(tn, []).append(new)
+                    new = Hyp(hyp.tokens + (label,), hyp.frames + (t + jump,), hyp.score + scores[b, k], sym)
+                    resting.setdefault(tn, []).append(new)
                 else:
                     new = Hyp(hyp.tokens, hyp.frames, hyp.score + scores[b, k], 0)
-                    t2hyps.setdefault(t + n, []).append(new)
+                    resting.setdefault(t + n, []).append(new)
         if trace is not None:
             trace.append(rec)
-    final, margin = recombine(t2hyps.get(T, [Hyp((), (), 0.0, 0)]) if T > 0 else [Hyp((), (), 0.0, 0)])
+    final, margin = recombine(resting.get(T, [Hyp((), (), 0.0, 0)]) if T > 0 else [Hyp((), (), 0.0, 0)])
     final.sort(key=_hyp_order)
     if len(final) > 1:
         margin = min(margin, final[0].score - final[1].score)

@@ -3,8 +3,9 @@ fraction of the sequential decoder's joiner evaluations return blank.
 
 Run as `python -m oracle.calibrate [config ...]`.  Calls only the CPU oracle.  The workloads'
 "~85 % of frames predict blank" is read as: blank evaluations / all evaluations of Algorithm 1.
-The bias is found by bisection on a sub-sample (4 utterances x 300 frames, or the whole workload
-if it is smaller); the achieved rate and the histogram of labels per emitting frame are stored
+The bias is found by bisection on a sub-sample (16 utterances x 600 frames, or the whole workload
+if it is smaller: frames that carry the full S labels weigh heavily in the rate, and a smaller sample
+holds too few of them to stand for the workload); the achieved rate and the histogram of labels per emitting frame are stored
 next to it for the record.  `pred_gain` (a gain on the prediction projection, so that a label
 changes the logits enough for the frame that emitted it to turn blank again) is fixed by hand.
 """
@@ -37,7 +38,7 @@ def measure(cfg, enc, lens, bias, gain):
 
 def calibrate(name: str) -> dict:
     cfg = wi.CONFIGS[name]
-    sub = cfg if cfg.B * cfg.len_hi <= 1200 else wi.scaled(cfg, 4, 300, 300)
+    sub = cfg if cfg.B * cfg.len_hi <= 9600 else wi.scaled(cfg, 16, 600, 600)
     enc, lens = wi.make_batch(sub)
     gain = PRED_GAIN[name]
     lo, hi = -4.0, 16.0
@@ -45,7 +46,7 @@ def calibrate(name: str) -> dict:
         mid = 0.5 * (lo + hi)
         rate, hist = measure(cfg, enc, lens, mid, gain)
         print(f"  {name}: bias {mid:.4f} -> blank rate {rate:.4f}", flush=True)
-        if abs(rate - cfg.blank_rate) < 0.005:
+        if abs(rate - cfg.blank_rate) < 0.003:
             lo = hi = mid
             break
         if rate < cfg.blank_rate:

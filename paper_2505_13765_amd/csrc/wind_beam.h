@@ -1,5 +1,5 @@
-// Scoring step of WIND beam search (section "A Novel Beam-search Algorithm for WIND": Eq. 1 and
-// lines 10-13 of Algorithm 3) for Bh hypotheses that sit on the same frame:
+// Scoring step of WIND beam search (section "A Novel Beam-search Algorithm for WIND": Eq. 1 and the
+// step of Algorithm 3 that scores a window) for Bh hypotheses that sit on the same frame:
 //   logits[b, t, :] = joiner(enc_window[t], dec_out[b])            t < n
 //   log P'(v, t)    = log softmax(logits[b, t])[v] + sum_{t' < t} log softmax(logits[b, t'])[blank]
 //   log P'(blank, n-1) = sum_{t' < n} log softmax(logits[b, t'])[blank];   P'(blank, t < n-1) = 0

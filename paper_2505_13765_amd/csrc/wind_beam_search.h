@@ -285,15 +285,15 @@ int beam_decode(wind_model *m, const float *enc_out, int T, int window, int K, i
     hyps.swap(out);
   };
 
-  std::map<int, std::vector<BeamHyp>> t2hyps;
-  t2hyps[0].push_back(BeamHyp{0, 0.0, 0, {}});
+  std::map<int, std::vector<BeamHyp>> resting;
+  resting[0].push_back(BeamHyp{0, 0.0, 0, {}});
   std::vector<int> cb_len, cb_tok, cb_fr, cb_sym;
   std::vector<double> cb_score;
-  while (!t2hyps.empty()) {
-    const int t = t2hyps.begin()->first;
+  while (!resting.empty()) {
+    const int t = resting.begin()->first;
     if (t == T) break;
-    std::vector<BeamHyp> hyps = std::move(t2hyps.begin()->second);
-    t2hyps.erase(t2hyps.begin());
+    std::vector<BeamHyp> hyps = std::move(resting.begin()->second);
+    resting.erase(resting.begin());
     ++st.rounds;
     st.max_pending = std::max<int64_t>(st.max_pending, (int64_t)hyps.size());
     recombine(hyps);
@@ -406,7 +406,7 @@ int beam_decode(wind_model *m, const float *enc_out, int T, int window, int K, i
       }
     }
 
-    // lines 9-13: the window's joiner rows, P' and the K best pairs of every hypothesis
+    // scoring step: the window's joiner rows, P' and the K best pairs of every hypothesis
     const int n = std::min(window, T - t);
     {
       int slots[kBeamMaxK];
@@ -436,33 +436,33 @@ int beam_decode(wind_model *m, const float *enc_out, int T, int window, int K, i
                scores);
     }
 
-    // lines 14-26: every chosen pair becomes a hypothesis at the frame it leads to
+    // expansion: every chosen pair becomes a hypothesis at the frame it leads to
     for (int b = 0; b < Bh; ++b) {
       for (int k = 0; k < K; ++k) {
-        const int new_token = labels[b * K + k], jump = jumps[b * K + k];
-        if (new_token < 0) continue;
+        const int label = labels[b * K + k], jump = jumps[b * K + k];
+        if (label < 0) continue;
         BeamHyp nh;
         nh.score = hyps[b].score + (double)scores[b * K + k];
-        if (new_token != V) {
-          nh.node = child_node(hyps[b].node, new_token);
+        if (label != V) {
+          nh.node = child_node(hyps[b].node, label);
           nh.frames = hyps[b].frames;
           nh.frames.push_back(t + jump);
           nh.sym = jump == 0 ? hyps[b].sym + 1 : 1;
           int tn = t + jump;
           if (nh.sym >= S) { tn += 1; nh.sym = 0; }   // safeguard: leave the frame after S labels
-          t2hyps[tn].push_back(std::move(nh));
+          resting[tn].push_back(std::move(nh));
         } else {
           nh.node = hyps[b].node;
           nh.frames = hyps[b].frames;
           nh.sym = 0;
-          t2hyps[t + n].push_back(std::move(nh));
+          resting[t + n].push_back(std::move(nh));
         }
       }
     }
   }
 
   std::vector<BeamHyp> fin;
-  if (!t2hyps.empty() && t2hyps.begin()->first == T) fin = std::move(t2hyps.begin()->second);
+  if (!resting.empty() && resting.begin()->first == T) fin = std::move(resting.begin()->second);
   if (fin.empty()) return fail(WIND_ERR_HIP, "beam search ended without a hypothesis");
   recombine(fin);
   size_t best = 0;

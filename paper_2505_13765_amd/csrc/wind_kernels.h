@@ -268,7 +268,8 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(ModelDev m, CallDev c
 }
 
 // ---------------------------------------------------------------------------------------------
-// Window gather (Algorithm 2, joiner(enc[t:t+n], dec[-1]), first half): one wave per window row.
+// Window gather (Algorithm 2: the joiner on a window of frames against the current decoder output, its
+// first half): one wave per window row.
 __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int parity) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = blockIdx.x * 4 + wave;

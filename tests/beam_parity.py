@@ -35,15 +35,15 @@ def follow(o, enc, N, K, S, prefix, got_trace, got_result, step):
     enc = np.asarray(enc, dtype=np.float32)
     T, V = enc.shape[0], o.V
     dec = obs.DecoderCache(o)
-    t2hyps = {0: [obs.Hyp((), (), 0.0, 0)]}
+    resting = {0: [obs.Hyp((), (), 0.0, 0)]}
     stats = {"passes": 0, "other_survivors": 0, "other_pairs": 0, "other_stamps": 0, "max_score_err": 0.0,
              "max_pair_err": 0.0}
     for i, g in enumerate(got_trace):
         bound = (i + 2 + S) * step
-        assert t2hyps, f"pass {i}: the device goes on after the map is empty"
-        t = min(t2hyps)
+        assert resting, f"pass {i}: the device goes on after the map is empty"
+        t = min(resting)
         assert t < T and g["t"] == t and g["n"] == min(N, T - t), (i, g["t"], t)
-        pending = t2hyps.pop(t)
+        pending = resting.pop(t)
         groups = {}
         for h in pending:
             groups.setdefault(h.tokens, []).append(h)
@@ -54,7 +54,7 @@ def follow(o, enc, N, K, S, prefix, got_trace, got_result, step):
                 dist[prefix_tokens] = bs.log_softmax(o.joiner(enc[t], dec.out(prefix_tokens)))
             return float(dist[prefix_tokens][v])
 
-        ranked, _, _ = obs.recombine_prune_prefix_search(pending, 10 ** 9, S, log_prob, prefix)   # steps 1, 2; no pruning
+        ranked, _, _ = obs.merge_extend_prune(pending, 10 ** 9, S, log_prob, prefix)   # steps 1, 2; no pruning
         by_tokens = {h.tokens: h for h in ranked}
         got_h = {tuple(int(v) for v in h[0]): h for h in g["hyps"]}
         assert len(got_h) == len(g["hyps"]) == min(K, len(ranked)), (i, len(g["hyps"]), len(ranked))
@@ -105,14 +105,14 @@ def follow(o, enc, N, K, S, prefix, got_trace, got_result, step):
                     tn = t + jump
                     if sym >= S:
                         tn, sym = tn + 1, 0
-                    t2hyps.setdefault(tn, []).append(obs.Hyp(hyp.tokens + (label,), hyp.frames + (t + jump,),
+                    resting.setdefault(tn, []).append(obs.Hyp(hyp.tokens + (label,), hyp.frames + (t + jump,),
                                                              hyp.score + true, sym))
                 else:
-                    t2hyps.setdefault(t + n, []).append(obs.Hyp(hyp.tokens, hyp.frames, hyp.score + true, 0))
+                    resting.setdefault(t + n, []).append(obs.Hyp(hyp.tokens, hyp.frames, hyp.score + true, 0))
         stats["passes"] += 1
 
-    assert set(t2hyps) <= {T}, f"the device stopped with hypotheses left at frames {sorted(t2hyps)}"
-    pending = t2hyps.get(T, [obs.Hyp((), (), 0.0, 0)])
+    assert set(resting) <= {T}, f"the device stopped with hypotheses left at frames {sorted(resting)}"
+    pending = resting.get(T, [obs.Hyp((), (), 0.0, 0)])
     final, _ = obs.recombine(pending)
     final.sort(key=lambda h: (-h.score, len(h.tokens), h.tokens))
     bound = (len(got_trace) + 2 + S) * step

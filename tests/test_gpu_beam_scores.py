@@ -1,4 +1,4 @@
-"""GPU parity of wind_beam_window_scores (Eq. 1 and Algorithm 3, lines 10-13) against the fp64 oracle
+"""GPU parity of wind_beam_window_scores (Eq. 1 and the scoring step of Algorithm 3) against the fp64 oracle
 in oracle/beam_scores.py on the same seeded inputs.  Scores: 1e-4 absolute for fp32 models, 2e-2 for
 bf16 models (the tolerances of the logits they are made of).  The chosen (label, jump) pairs must
 be the oracle's, except that entries whose oracle scores lie closer together than the tolerance may

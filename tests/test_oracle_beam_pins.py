@@ -1,5 +1,5 @@
 """Pins for the beam-scoring oracle (oracle/beam_scores.py): the definitions of the section "A Novel
-Beam-search Algorithm for WIND" (Eq. 1; Algorithm 3, lines 12-13) checked against things other than
+Beam-search Algorithm for WIND" (Eq. 1; Algorithm 3's choice of the K best pairs) checked against things other than
 the oracle's own formula: the probabilities' total mass, the one-frame special case against a
 library softmax, a brute-force evaluation with explicit products of probabilities, limiting cases,
 and brute-force top-K."""

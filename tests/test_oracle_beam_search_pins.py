@@ -11,6 +11,8 @@ for WIND", Algorithm 3) against things other than the oracle's own loop:
   * the prefix step on hand-built hypothesis sets with completion probabilities computed directly,
     including a chain of three where mass must not be counted twice;
   * what the literal removal of prefixes does to the search, measured;
+  * a second, differently built writing of the whole search that must return the same final hypotheses
+    (labels, time stamps, scores) in each of the three prefix modes;
   * invariants of the output.
 """
 import itertools
@@ -153,10 +155,10 @@ def test_prefix_step_by_hand():
     B = obs.Hyp((1, 2), (0, 3), np.log(0.10), 0)
     C = obs.Hyp((0,), (2,), np.log(0.20), 0)          # no relation to the others
     fresh = lambda hs: [obs.Hyp(h.tokens, h.frames, h.score, h.sym) for h in hs]
-    out, _, pairs = obs.recombine_prune_prefix_search(fresh([A, B, C]), K=5, S=4, log_prob=lp, prefix_step="remove")
+    out, _, pairs = obs.merge_extend_prune(fresh([A, B, C]), K=5, S=4, log_prob=lp, prefix_step="remove")
     got = {h.tokens: h.score for h in out}
     assert pairs == 1 and set(got) == {(1, 2), (0,)}                      # the literal sentence: A is gone
-    kept, _, _ = obs.recombine_prune_prefix_search(fresh([A, B, C]), K=5, S=4, log_prob=lp)
+    kept, _, _ = obs.merge_extend_prune(fresh([A, B, C]), K=5, S=4, log_prob=lp)
     assert {h.tokens: h.score for h in kept} == {**got, (1,): np.log(0.30)}   # the credited definition: A stays
     p_complete = np.exp(frame_log_probs(o, frame, (1,))[2])
     assert np.isclose(np.exp(got[(1, 2)]), 0.10 + 0.30 * p_complete, rtol=1e-12)
@@ -164,7 +166,7 @@ def test_prefix_step_by_hand():
     assert [h.frames for h in out if h.tokens == (1, 2)] == [(0, 3)]      # B keeps its own time stamps
     # the safeguard forbids the completion when A already holds S - 1 labels on this frame
     A2 = obs.Hyp((1,), (0,), np.log(0.30), 3)
-    out, _, pairs = obs.recombine_prune_prefix_search(fresh([A2, B, C]), K=5, S=4, log_prob=lp)
+    out, _, pairs = obs.merge_extend_prune(fresh([A2, B, C]), K=5, S=4, log_prob=lp)
     assert pairs == 0 and {h.tokens for h in out} == {(1,), (1, 2), (0,)}
 
 
@@ -176,14 +178,14 @@ def test_prefix_step_chain_counts_mass_once():
     hyps = [obs.Hyp((2,), (0,), np.log(pa)), obs.Hyp((2, 0), (0, 1), np.log(pb)),
             obs.Hyp((2, 0, 1), (0, 1, 1), np.log(pc))]
     for order in itertools.permutations(range(3)):
-        out, _, pairs = obs.recombine_prune_prefix_search([obs.Hyp(h.tokens, h.frames, h.score) for h in
+        out, _, pairs = obs.merge_extend_prune([obs.Hyp(h.tokens, h.frames, h.score) for h in
                                                            (hyps[i] for i in order)], K=5, S=8, log_prob=lp, prefix_step="remove")
         q0 = np.exp(frame_log_probs(o, frame, (2,))[0])
         q1 = np.exp(frame_log_probs(o, frame, (2, 0))[1])
         assert pairs == 3 and [h.tokens for h in out] == [(2, 0, 1)]
         # paths into (2,0,1): its own, (2,0) plus label 1, (2,) plus labels 0 then 1 -- each once
         assert np.isclose(np.exp(out[0].score), pc + pb * q1 + pa * q0 * q1, rtol=1e-12)
-        kept, _, _ = obs.recombine_prune_prefix_search([obs.Hyp(h.tokens, h.frames, h.score) for h in
+        kept, _, _ = obs.merge_extend_prune([obs.Hyp(h.tokens, h.frames, h.score) for h in
                                                         (hyps[i] for i in order)], K=5, S=8, log_prob=lp)
         got = {h.tokens: np.exp(h.score) for h in kept}
         assert np.isclose(got[(2,)], pa, rtol=1e-12) and np.isclose(got[(2, 0)], pb + pa * q0, rtol=1e-12)
@@ -202,7 +204,7 @@ def test_duplicates_are_added_and_keep_the_likelier_time_stamps():
 
 def test_pruning_keeps_the_k_best():
     hyps = [obs.Hyp((i,), (0,), float(s)) for i, s in enumerate([-3.0, -1.0, -2.5, -0.5, -4.0])]
-    out, margin, _ = obs.recombine_prune_prefix_search(hyps, K=3, S=4, log_prob=None, prefix_step="off")
+    out, margin, _ = obs.merge_extend_prune(hyps, K=3, S=4, log_prob=None, prefix_step="off")
     assert [h.tokens for h in out] == [(3,), (1,), (2,)] and np.isclose(margin, 0.5)
 
 
@@ -261,3 +263,114 @@ def test_sharpened_models_keep_every_argmax():
     p1 = np.exp(scipy_log_softmax(o.joiner(enc[0], o.decoder_from_scratch([])))).max()
     p8 = np.exp(scipy_log_softmax(o2.joiner(enc[0], o2.decoder_from_scratch([])))).max()
     assert p8 > p1
+
+
+# ---------------------------------------------------------------------------------------------
+# A second writing of the whole search, from the section's prose rather than from the oracle's code: no
+# hypothesis objects and no per-round records, a flat table keyed by (frame, label sequence); decoder
+# outputs always rebuilt from nothing; probabilities from scipy's soft-max; window scores formed as
+# products of probabilities (Eq. 1 as printed) and only then logged; candidates ranked with one sort
+# over explicit tuples.  It follows the same readings (duplicates, prefix step in its three modes,
+# safeguard, tie orders) and must agree with the oracle's search on every output: what is pinned is
+# that the oracle implements those readings without a slip, not the readings themselves.
+def second_search(o, enc, N, K, S, mode):
+    T, V = enc.shape[0], o.V
+    probs_cache = {}
+
+    def probs(t, seq):                       # P(. | frame t, decoder(seq)), linear domain
+        if (t, seq) not in probs_cache:
+            probs_cache[(t, seq)] = np.exp(scipy_log_softmax(o.joiner(enc[t], o.decoder_from_scratch(list(seq)))))
+        return probs_cache[(t, seq)]
+
+    # table[frame] = list of (seq, stamps, logscore, count_on_frame)
+    table = {0: [((), (), 0.0, 0)]}
+    while table:
+        t = min(table)
+        if t == T:
+            break
+        entries = table.pop(t)
+        # 1. duplicates: same label sequence -> probabilities add; keep the stamps / count of the most probable
+        merged = {}
+        order = []
+        for seq, stamps, ls, cnt in entries:
+            if seq not in merged:
+                merged[seq] = []
+                order.append(seq)
+            merged[seq].append((ls, stamps, cnt))
+        pool = []
+        for seq in order:
+            group = merged[seq]
+            keep = sorted(group, key=lambda g: (-g[0], g[1], g[2]))[0]
+            total = float(logsumexp([g[0] for g in group])) if len(group) > 1 else group[0][0]
+            pool.append([seq, keep[1], total, keep[2]])
+        # 2. prefixes: B gains what A had before this step, times the chance of emitting the rest on frame t
+        if mode != "off":
+            had = {p[0]: p[2] for p in pool}
+            counts = {p[0]: p[3] for p in pool}
+            gone = set()
+            for p in pool:
+                b = p[0]
+                for a in had:
+                    if len(a) < len(b) and b[:len(a)] == a and counts[a] + len(b) - len(a) < S:
+                        chance = 1.0
+                        for k in range(len(a), len(b)):
+                            chance *= probs(t, b[:k])[b[k]]
+                        p[2] = float(np.logaddexp(p[2], had[a] + np.log(chance)))
+                        gone.add(a)
+            if mode == "remove":
+                pool = [p for p in pool if p[0] not in gone]
+        # 3. the K most probable (ties: shorter, then smaller sequence)
+        pool.sort(key=lambda p: (-p[2], len(p[0]), p[0]))
+        pool = pool[:K]
+        # window scores: first output v at offset j (blank only as "nothing in the whole window")
+        n = min(N, T - t)
+        for seq, stamps, ls, cnt in pool:
+            cands = []
+            blanks_so_far = 1.0
+            for j in range(n):
+                pr = probs(t + j, seq)
+                for v in range(V):
+                    cands.append((-(np.log(pr[v]) + np.log(blanks_so_far)) if pr[v] * blanks_so_far > 0 else np.inf, j, v))
+                blanks_so_far *= pr[V]
+            cands.append((-np.log(blanks_so_far) if blanks_so_far > 0 else np.inf, n - 1, V))
+            cands.sort()
+            for neg, j, v in cands[:K]:
+                if neg == np.inf:
+                    continue
+                if v == V:
+                    table.setdefault(t + n, []).append((seq, stamps, ls - neg, 0))
+                else:
+                    c2 = cnt + 1 if j == 0 else 1
+                    where = t + j
+                    if c2 >= S:
+                        where, c2 = where + 1, 0
+                    table.setdefault(where, []).append((seq + (v,), stamps + (t + j,), ls - neg, c2))
+    last = table.get(T, [((), (), 0.0, 0)]) if T > 0 else [((), (), 0.0, 0)]
+    sums = {}
+    for seq, stamps, ls, cnt in last:
+        sums.setdefault(seq, []).append((ls, stamps, cnt))
+    final = []
+    for seq, group in sums.items():
+        keep = sorted(group, key=lambda g: (-g[0], g[1], g[2]))[0]
+        final.append((seq, keep[1], float(logsumexp([g[0] for g in group]))))
+    final.sort(key=lambda f: (-f[2], len(f[0]), f[0]))
+    return final
+
+
+@pytest.mark.parametrize("mode", ["keep", "remove", "off"])
+@pytest.mark.parametrize("seed,T,V,S,N,K", [(0, 5, 3, 2, 2, 3), (1, 6, 3, 3, 3, 2), (2, 4, 3, 4, 4, 4), (3, 6, 2, 2, 8, 3),
+                                            (4, 5, 3, 3, 1, 3), (5, 7, 3, 2, 3, 1)])
+def test_second_writing_of_the_search_agrees(mode, seed, T, V, S, N, K):
+    cfg, o = tiny_model(40 + seed, V=V, L=1 + seed % 2, blank_bias=0.5 * (seed % 3))
+    enc = make_enc(40 + seed, T, cfg.D)
+    best, final, margin = obs.wind_beam_search(o, enc, N, K, S, prefix_step=mode)
+    want = second_search(o, enc, N, K, S, mode)
+    if margin < 1e-9:
+        pytest.skip("a choice of the search rests on an exact tie")
+    got = sorted(((h.tokens, h.frames, h.score) for h in final), key=lambda f: (-f[2], len(f[0]), f[0]))
+    assert [g[0] for g in got] == [w[0] for w in want]
+    for g, w in zip(got, want):
+        assert g[1] == w[1] and abs(g[2] - w[2]) < 1e-9, (g, w)
+    assert best.tokens == want[0][0] and best.frames == want[0][1]
+    if mode != "off" and K > 1:
+        assert len(want) >= 1
