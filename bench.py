@@ -90,8 +90,8 @@ def run_workload(torch, wi, WindModel, name, windows, steps, warmup, with_sequen
     return cfg, model, (d_enc, d_len, out), frames, res, (enc, lens, w)
 
 
-KERNEL_SOURCES = ("paper_2505_13765_amd/csrc/wind_kernels.h", "paper_2505_13765_amd/csrc/wind_mfma_ws.h",
-                  "paper_2505_13765_amd/csrc/wind_mfma_dma.h", "paper_2505_13765_amd/csrc/wind_util.h")
+KERNEL_SOURCES = tuple("paper_2505_13765_amd/csrc/" + f for f in (
+    "wind_types.h", "wind_enc_kernels.h", "wind_joint_kernels.h", "wind_mfma_ws.h", "wind_mfma_dma.h", "wind_util.h"))
 
 
 def kernel_source_digest():

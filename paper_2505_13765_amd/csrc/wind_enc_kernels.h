@@ -1,0 +1,232 @@
+// Once-per-call kernels (state set-up, encoder projection) and the window gather of every iteration.
+#pragma once
+#include "wind_types.h"
+
+namespace wind {
+
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_int_kernel(int *p, int n, int v) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) p[i] = v;
+}
+
+__global__ __launch_bounds__(256) void init_state_kernel(ModelDev m, CallDev c) {
+  const int tid = threadIdx.x;
+  // every workgroup zeroes its share of the prediction-network state; the first also builds the lists
+  const size_t nstate = (size_t)m.L * c.B * m.Hp;
+  for (size_t i = (size_t)blockIdx.x * 256 + tid; i < nstate; i += (size_t)gridDim.x * 256) {
+    c.h[i] = 0.f; c.c[i] = 0.f; c.hn[i] = 0.f;
+    c.hb_hi[i] = 0; c.hb_lo[i] = 0; c.hbn_hi[i] = 0; c.hbn_lo[i] = 0;
+  }
+  if (blockIdx.x != 0) return;
+  for (int i = tid; i < kNumStats; i += 256) c.stats[i] = 0ull;
+  for (int b = tid; b < c.B; b += 256) {
+    int len = c.lengths[b];
+    len = len < 0 ? 0 : (len > c.T ? c.T : len);
+    c.len[b] = len;
+    c.out_counts[b] = 0;
+    c.emit_idx[b] = b;         // the first prediction-network step runs on every utterance
+    c.emit_list_tok[b] = m.V;  // on the start token
+  }
+  __syncthreads();
+  if (tid < 64) {              // slot table of parity 0: the non-empty utterances, in order
+    int na = 0;
+    for (int base = 0; base < c.B; base += 64) {
+      const int b = base + tid;
+      const int len = b < c.B ? c.len[b] : 0;
+      const unsigned long long mk = __ballot(len > 0);
+      if (len > 0) {
+        const int pos = na + __popcll(mk & ((1ull << tid) - 1ull));
+        c.slot_state[pos] = make_int4(b, 0, len, 0);
+        c.slot_count[pos] = 0;
+      }
+      na += __popcll(mk);
+    }
+    if (tid == 0) {
+      c.n_active[0] = na;
+      c.n_active[1] = 0;
+      *c.n_emit = c.B;
+      c.ticket[0] = 0u;
+      c.ticket[1] = 0u;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// e[b,t,:] = W_enc enc_out[b,t,:] + b_enc for t < len[b]: bf16 MFMA, fp32 accumulate, fp32 out.
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void enc_proj_mfma_kernel(ModelDev m, CallDev c, int tiles_per_utt) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+  const int b = blockIdx.x / tiles_per_utt, t0 = (blockIdx.x % tiles_per_utt) * Cfg::BM;
+  const int len = c.len[b];
+  if (t0 >= len) return;
+  const int n0 = blockIdx.y * Cfg::BN, D = m.D;
+  const float *base = c.enc + (size_t)b * c.T * D;
+  auto aload = [&](int, int row, int k) -> u32x4 {
+    int t = t0 + row;
+    t = t < len ? t : len - 1;
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(base + (size_t)t * D + k);
+    const f32x4 x0 = src[0], x1 = src[1];
+    u32x4 o;
+    o.x = pack_bf16x2(x0.x, x0.y); o.y = pack_bf16x2(x0.z, x0.w);
+    o.z = pack_bf16x2(x1.x, x1.y); o.w = pack_bf16x2(x1.z, x1.w);
+    return o;
+  };
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  gemm_mainloop<Cfg>(aload, reinterpret_cast<const bf16_t *>(m.w_enc) + (size_t)n0 * D, D, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int col = n0 + wn * Cfg::WN + ni * 32 + (lane & 31);
+    if (col >= m.Hj) continue;
+    const float bias = m.b_enc[col];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = t0 + wm * Cfg::WM + acc_row(mi, r, lane);
+        if (t < len) c.e[((size_t)b * c.T + t) * m.Hj + col] = acc[mi][ni][r] + bias;
+      }
+  }
+}
+
+// Large calls: the encoder outputs are first rounded to bf16 rows (valid frames only), so that the
+// projection can use the direct-to-LDS tile core at full tile size.
+__global__ __launch_bounds__(256) void enc_round_kernel(ModelDev m, CallDev c) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long row = (long long)blockIdx.x * 4 + wave;
+  if (row >= (long long)c.B * c.T) return;
+  const int b = (int)(row / c.T), t = (int)(row - (long long)b * c.T);
+  if (t >= c.len[b]) return;
+  const float *src = c.enc + (size_t)row * m.D;
+  bf16_t *dst = c.enc_b + (size_t)row * m.D;
+  for (int k = lane * 4; k < m.D; k += 256) {
+    const float4 x = *reinterpret_cast<const float4 *>(src + k);
+    *reinterpret_cast<uint2 *>(dst + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+  }
+}
+
+// e = W_enc enc + b_enc on 256 x 256 tiles of the five-slot ring: a row tile is 256 consecutive
+// frames of one utterance (rows past its length are computed and dropped).
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void enc_proj_ring5_kernel(ModelDev m, CallDev c, int tiles_per_utt) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int b = blockIdx.x / tiles_per_utt, t0 = (blockIdx.x % tiles_per_utt) * Cfg::BM;
+  const int len = c.len[b];
+  if (t0 >= len) return;
+  const int n0 = blockIdx.y * Cfg::BN, D = m.D;
+  f32x16 acc[Cfg::MI][Cfg::NI];
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+  gemm_mainloop_ring5<Cfg>(c.enc_b + ((size_t)b * c.T + t0) * D, reinterpret_cast<const bf16_t *>(m.w_enc) + (size_t)n0 * D, D,
+                           smem_raw, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int ni = 0; ni < Cfg::NI; ++ni) {
+    const int col = n0 + wn * Cfg::WN + ni * 32 + (lane & 31);
+    if (col >= m.Hj) continue;
+    const float bias = m.b_enc[col];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = t0 + wm * Cfg::WM + acc_row(mi, r, lane);
+        if (t < len) c.e[((size_t)b * c.T + t) * m.Hj + col] = acc[mi][ni][r] + bias;
+      }
+  }
+}
+
+// fp32 models: out[row, j] = bias[j] + sum_k w[j,k] x[row,k] for the valid frames of each utterance.
+__global__ __launch_bounds__(256) void enc_proj_f32_kernel(ModelDev m, CallDev c) {
+  extern __shared__ float xs[];
+  const int b = blockIdx.y, t = blockIdx.x;
+  if (t >= c.len[b]) return;
+  const float *x = c.enc + ((size_t)b * c.T + t) * m.D;
+  for (int k = threadIdx.x; k < m.D; k += 256) xs[k] = x[k];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float *w = reinterpret_cast<const float *>(m.w_enc);
+  for (int j = wave; j < m.Hj; j += 4) {
+    float a = 0.f;
+    for (int k = lane; k < m.D; k += 64) a = fmaf(w[(size_t)j * m.D + k], xs[k], a);
+    a = wave_sum(a);
+    if (lane == 0) c.e[((size_t)b * c.T + t) * m.Hj + j] = a + m.b_enc[j];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Window gather (Algorithm 2: the joiner on a window of frames against the current decoder output, its
+// first half): one wave per window row.
+__global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int parity) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * 4 + wave;
+  const int a = row / c.W, j = row - a * c.W;
+  if (a >= c.B) return;
+  const int na = c.n_active[parity];
+  const int4 st = c.slot_state[parity * c.slot_stride + a];   // same round trip as the count
+  // the counters that this iteration's decision kernel adds to: every reader of their old values is done
+  if (c.lists_atomic && blockIdx.x == 0 && threadIdx.x == 0) { c.n_active[parity ^ 1] = 0; *c.n_emit = 0; }
+  if (c.iter_rows && blockIdx.x == 0 && wave == 0 && na > 0) {
+    // profile mode: rows the method evaluates in this iteration = sum of n over the windows; iterations
+    // so far = the decision kernel's counter (complete: that kernel precedes this one in the stream)
+    int rows = 0;
+    for (int i = lane; i < na; i += 64) {
+      const int4 s = c.slot_state[parity * c.slot_stride + i];
+      rows += min(c.W, s.z - s.y);
+    }
+    rows = wave_sum_i32(rows);
+    const unsigned long long it = c.stats[ST_ITER];
+    if (lane == 0 && it < (unsigned long long)c.iter_rows_cap) c.iter_rows[it] = rows;
+  }
+  if (a >= na) return;
+  const int b = st.x, tt = st.y + j;
+  const bool valid = tt < st.z;
+  const int Hj = m.Hj;
+  const float *er = c.e + ((size_t)b * c.T + (valid ? tt : 0)) * Hj;
+  const float *pr = c.p + (size_t)b * Hj;
+  bf16_t *zr = c.z + (size_t)row * Hj;
+  float dot = 0.f, nrm = 0.f;
+  // 1024 hidden units per pass: the pass's twelve loads per lane go out together (one round trip)
+  for (int k0 = lane * 4; k0 < Hj; k0 += 1024) {
+    float4 ev[4], pv[4], wb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int k = k0 + 256 * i;
+      ev[i] = pv[i] = wb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k < Hj) {
+        wb[i] = *reinterpret_cast<const float4 *>(m.w_blank + k);
+        if (valid) {
+          ev[i] = *reinterpret_cast<const float4 *>(er + k);
+          pv[i] = *reinterpret_cast<const float4 *>(pr + k);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int k = k0 + 256 * i;
+      if (k >= Hj) continue;
+      float4 x;   // invalid rows: e and p were left at zero
+      x.x = fmaxf(ev[i].x + pv[i].x, 0.f); x.y = fmaxf(ev[i].y + pv[i].y, 0.f);
+      x.z = fmaxf(ev[i].z + pv[i].z, 0.f); x.w = fmaxf(ev[i].w + pv[i].w, 0.f);
+      dot = fmaf(x.x, wb[i].x, dot); dot = fmaf(x.y, wb[i].y, dot);
+      dot = fmaf(x.z, wb[i].z, dot); dot = fmaf(x.w, wb[i].w, dot);
+      nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm);
+      nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+      *reinterpret_cast<uint2 *>(zr + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+    }
+  }
+  dot = wave_sum(dot);
+  nrm = wave_sum(nrm);
+  if (lane == 0) {
+    c.blank_logit[row] = dot + m.b_out[m.V];
+    c.znorm[row] = sqrtf(nrm);
+  }
+}
+
+}  // namespace wind

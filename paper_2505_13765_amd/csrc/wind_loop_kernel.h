@@ -1,0 +1,574 @@
+// The whole decode loop of one or two utterances as one resident kernel.
+#pragma once
+#include "wind_types.h"
+#include "wind_decide_kernels.h"
+#include "wind_pred_kernels.h"
+
+namespace wind {
+
+// ---------------------------------------------------------------------------------------------
+// Small decodes as ONE resident kernel.  With one or two utterances and at most 32 window rows the
+// loop of Algorithm 2 is a chain of short dependent steps, and between kernels every hand-over costs
+// a launch gap plus cold caches.  Here G workgroups stay on the chip for the whole decode; each
+// keeps its slice of the weights next to its ALUs for all iterations: 32 columns of W_out as MFMA
+// fragments in registers, the recurrent weights of `upw` LSTM units and `ppw` rows of W_pred in LDS.
+// What an iteration needs from the other workgroups goes through three exchanges in memory, each
+// behind a grid barrier: the rows' keys (every workgroup then takes the same decisions and keeps
+// the same pointers, so no state travels), the new hidden vector, the new projection.  An
+// iteration without a label has one barrier.
+//
+// The barrier is one arrival word per workgroup that only grows; a workgroup that waits longer than
+// spin_limit polls, or sees the abort word set, sets it and leaves the kernel, so every wave
+// reaches the end whatever happens to the others.  The host treats a set abort word as an error.  All G workgroups must be
+// resident at once; the host launches at most one per CU.
+struct LoopDev {
+  unsigned *bar;       // word 0: abort; word (1 + g) * 32: barriers workgroup g has reached; all zero at launch
+  float *h_x;          // [B][Hp] new hidden vectors
+  float *p_x;          // [B][Hj] new projections
+  float2 *parts_x;     // [2][32][nparts_tiny] keys, by iteration parity
+  int G, upw, ppw;     // workgroups; LSTM units and W_pred rows per workgroup (multiples of 4)
+  int max_iters;       // more iterations than any decode of this call can take
+  unsigned spin_limit;
+};
+constexpr int kLoopMaxB = 2;
+constexpr int kLoopRows = 32;
+
+struct LoopShared {
+  int4 nslot[kLoopMaxB];
+  int ncnt[kLoopMaxB];
+  int emit_ub[kLoopMaxB], emit_tok[kLoopMaxB];
+  int n_act, n_emit, ok;
+};
+
+// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: 32 rows of Hj+8 bf16, at least 16 KB][hhi, hlo: B*Hp bf16 each]
+//      [pfull: B*Hj f32][cst: B*upw f32]
+// bf16 elements of the window-row region zs.  The region also takes the K-split partial sums of the MFMA
+// phase (4 waves x 16 registers x 64 lanes of fp32 = 16 KB), which is the larger of the two for Hj < 248.
+__host__ __device__ inline size_t loop_z_elems(int Hj) {
+  const size_t z = (size_t)kLoopRows * (Hj + 8);
+  return z > 8192 ? z : 8192;
+}
+__host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw) {
+  return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + loop_z_elems(Hj) * 2 + (size_t)B * Hp * 4 +
+         (size_t)B * Hj * 4 + (size_t)B * upw * 4;
+}
+
+// Values that another workgroup of the running kernel wrote are read and written with agent-scope
+// atomics (they go past the caches that are private to a CU or an XCD), so that the barrier needs
+// no cache invalidation and the read-only operands stay in L2 from iteration to iteration.
+__device__ __forceinline__ float ld_shared_f32(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_shared_f32(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_shared_f32x2(const float2 *p) {
+  const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+}
+__device__ __forceinline__ void st_shared_f32x2(float2 *p, float2 v) {
+  const unsigned long long u = (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kLoopFlagStride = 32;   // one 128-byte line per workgroup's arrival word
+// The barrier in two halves, so that work that needs nothing from the other workgroups can fill the
+// time the arrivals take to travel: loop_arrive publishes this workgroup's arrival, loop_wait waits
+// for everybody's.  Between the two a workgroup must not write anything the others read before
+// the barrier, nor read what they write.
+__device__ __forceinline__ void loop_arrive(const LoopDev &lp, unsigned passed) {
+  __syncthreads();   // this workgroup's stores of the phase have been issued and acknowledged
+  if (threadIdx.x == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and are visible to the agent before the arrival is
+    __hip_atomic_store(&lp.bar[(1 + blockIdx.x) * kLoopFlagStride], passed + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+__device__ __forceinline__ bool loop_wait(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
+  const unsigned epoch = ++passed;
+  if (threadIdx.x < 64) {
+    // every workgroup publishes the number of barriers it has reached; wave 0 watches all of them,
+    // one lane per workgroup (no read-modify-write on a shared word: the arrivals do not queue up)
+    unsigned spins = 0;
+    int good = 1;
+    for (;;) {
+      bool here = true;
+      for (int w0 = 0; w0 < lp.G; w0 += 64) {
+        const int w = w0 + (int)threadIdx.x;
+        unsigned v = epoch;
+        if (w < lp.G) v = __hip_atomic_load(&lp.bar[(1 + w) * kLoopFlagStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        here = here && (int)(v - epoch) >= 0;
+      }
+      if (__all(here)) break;
+      const unsigned ab = __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (++spins > lp.spin_limit || ab) { good = 0; break; }
+    }
+    if (threadIdx.x == 0) {
+      if (!good) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ls.ok = good;
+    }
+  }
+  __syncthreads();
+  asm volatile("" ::: "memory");   // the exchange reads that follow stay behind the wait
+  return ls.ok != 0;
+}
+__device__ __forceinline__ bool loop_barrier(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
+  loop_arrive(lp, passed);
+  return loop_wait(lp, passed, ls);
+}
+
+// Sums of 16 / 8 / 4 per-lane values over the wave with a halving exchange: each step a lane keeps
+// half of its values and adds the partner's copies of them, until one value is left, which the
+// last steps sum over the lanes that still hold parts of it.  The steps that carry the most values
+// pair lanes inside a row of 16 with DPP permutations (row mirror, half mirror); the lane bit that
+// decides which half is kept gives the value's index one bit per step:
+//   16 values: index = b3 b2 b4 b5 (lane bits), i.e. value v ends up, complete, in the four lanes
+//              32*(v&1) + 16*((v>>1)&1) + 4*(v>>2) + 0..3
+//    8 values: index = b3 b2 b4; lanes 16*(v&1) + 4*(v>>1) + 0..3 and the same + 32
+//    4 values: index = b3 b2; lanes 4*v + 0..3 of every row
+__device__ __forceinline__ float wave_sum16_scatter(const float (&v)[16], int lane) {
+  float a[8], b[4], c2[2];
+  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0, u4 = (lane & 16) != 0, u5 = (lane & 32) != 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = (u3 ? v[i + 8] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 8]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = (u2 ? a[i + 4] : a[i]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[i] : a[i + 4]);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) c2[i] = (u4 ? b[i + 2] : b[i]) + __shfl_xor(u4 ? b[i] : b[i + 2], 16, kWave);
+  float d = (u5 ? c2[1] : c2[0]) + __shfl_xor(u5 ? c2[0] : c2[1], 32, kWave);
+  d += dpp_f32<kDppQuadXor2>(d);
+  d += dpp_f32<kDppQuadXor1>(d);
+  return d;
+}
+__device__ __forceinline__ float wave_sum8_scatter(const float (&v)[8], int lane) {
+  float a[4], b[2];
+  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0, u4 = (lane & 16) != 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = (u3 ? v[i + 4] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 4]);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) b[i] = (u2 ? a[i + 2] : a[i]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[i] : a[i + 2]);
+  float d = (u4 ? b[1] : b[0]) + __shfl_xor(u4 ? b[0] : b[1], 16, kWave);
+  d += __shfl_xor(d, 32, kWave);
+  d += dpp_f32<kDppQuadXor2>(d);
+  d += dpp_f32<kDppQuadXor1>(d);
+  return d;
+}
+__device__ __forceinline__ float wave_sum4_scatter(const float (&v)[4], int lane) {
+  float a[2];
+  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) a[i] = (u3 ? v[i + 2] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 2]);
+  float d = (u2 ? a[1] : a[0]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[0] : a[1]);
+  d += __shfl_xor(d, 16, kWave);
+  d += __shfl_xor(d, 32, kWave);
+  d += dpp_f32<kDppQuadXor2>(d);
+  d += dpp_f32<kDppQuadXor1>(d);
+  return d;
+}
+
+__global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, LoopDev lp) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  __shared__ DecideShared sh;
+  __shared__ LoopShared ls;
+  __shared__ unsigned long long lstats[kNumStats];   // workgroup 0: the call's counters, written out at the end
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = blockIdx.x;
+  const int Hj = m.Hj, Hp = m.Hp, W = c.W, B = c.B;
+  const int zstride = Hj + 8;
+  bf16_t *wl = reinterpret_cast<bf16_t *>(smem_raw);
+  bf16_t *wp = wl + (size_t)lp.upw * 4 * Hp;
+  bf16_t *zs = wp + (size_t)lp.ppw * Hp;
+  // the hidden vectors as bf16 hi + lo (hi = RNE(h), lo = RNE(h - hi), 16 mantissa bits together): the dot
+  // products with the bf16 weights then take one packed instruction per pair and part, with nothing to unpack
+  bf16_t *hhi = zs + loop_z_elems(Hj), *hlo = hhi + (size_t)B * Hp;
+  float *pfull = reinterpret_cast<float *>(hlo + (size_t)B * Hp);
+  auto put_h2 = [&](int i, float2 v) {   // elements i (even) and i + 1
+    const uint32_t hb = pack_bf16x2(v.x, v.y);
+    *reinterpret_cast<uint32_t *>(hhi + i) = hb;
+    *reinterpret_cast<uint32_t *>(hlo + i) = pack_bf16x2(v.x - __uint_as_float(hb << 16), v.y - __uint_as_float(hb & 0xFFFF0000u));
+  };
+  // sum over this lane's eight k of w[k] * (hi[k] + lo[k]), on top of acc
+  auto dot8 = [&](const bf16_t *wrow, int hofs, float acc) {
+    const u32x4 wv = *reinterpret_cast<const u32x4 *>(wrow);
+    const u32x4 a = *reinterpret_cast<const u32x4 *>(hhi + hofs), b = *reinterpret_cast<const u32x4 *>(hlo + hofs);
+    acc = dot2_bf16(wv.x, a.x, acc); acc = dot2_bf16(wv.y, a.y, acc); acc = dot2_bf16(wv.z, a.z, acc); acc = dot2_bf16(wv.w, a.w, acc);
+    acc = dot2_bf16(wv.x, b.x, acc); acc = dot2_bf16(wv.y, b.y, acc); acc = dot2_bf16(wv.z, b.z, acc); acc = dot2_bf16(wv.w, b.w, acc);
+    return acc;
+  };
+  float *cst = pfull + (size_t)B * Hj;
+
+  // ---- once: this workgroup's weights, the state after the start-token step, the slot table
+  const int unit0 = g * lp.upw, prow0 = g * lp.ppw;
+  for (int i = tid * 8; i < lp.upw * 4 * Hp; i += 256 * 8) {
+    const int row = i / Hp, k = i - row * Hp;           // row = 4 * local unit + gate
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (unit0 + (row >> 2) < Hp)
+      v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.w_cat[0]) + ((size_t)unit0 * 4 + row) * Hp + k);
+    *reinterpret_cast<u32x4 *>(wl + i) = v;
+  }
+  for (int i = tid * 8; i < lp.ppw * Hp; i += 256 * 8) {
+    const int row = i / Hp, k = i - row * Hp;
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (prow0 + row < Hj) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)(prow0 + row) * Hp + k);
+    *reinterpret_cast<u32x4 *>(wp + i) = v;
+  }
+  for (int i = tid * 2; i < B * Hp; i += 512) put_h2(i, *reinterpret_cast<const float2 *>(c.h + i));
+  for (int i = tid; i < B * Hj; i += 256) pfull[i] = c.p[i];
+  for (int i = tid; i < B * lp.upw; i += 256) {
+    const int b = i / lp.upw, u = i - b * lp.upw;
+    cst[i] = unit0 + u < Hp ? c.c[(size_t)b * Hp + unit0 + u] : 0.f;
+  }
+  if (tid < kLoopMaxB) {
+    sh.slot[tid] = c.slot_state[tid];
+    sh.cnt[tid] = c.slot_count[tid];
+  }
+  for (int i = tid; i < kNumStats; i += 256) lstats[i] = 0ull;
+  // Read-only operands are fetched ahead into this XCD's L2, which nothing invalidates while the
+  // kernel runs: here this workgroup's columns of every row of emb_gates, below the encoder
+  // projections of the window after the current one.
+  float warm = 0.f, pend[2] = {0.f, 0.f};
+  {
+    const int lines = (lp.upw * 16 + 127) / 128;   // 128-byte lines per table row slice
+    for (int i = tid; i < (m.V + 1) * lines; i += 256) {
+      const int v = i / lines, l = i - v * lines;
+      const size_t off = (size_t)v * 4 * Hp + (size_t)unit0 * 4 + l * 32;
+      if (unit0 * 4 + l * 32 < 4 * Hp) warm += m.emb_gates[off];
+    }
+  }
+  int na = c.n_active[0];
+  // W_out fragments of this workgroup's 32 columns, this wave's quarter of K
+  const bool has_cols = g < c.nparts_tiny;
+  const int n0 = (has_cols ? g : 0) * kTinyCols;
+  const int kq = Hj >> 2, k0 = wave * kq, nk = kq >> 4;
+  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
+  bf16x8 bfrag[kTinyPrefetch];
+#pragma unroll
+  for (int i = 0; i < kTinyPrefetch; ++i)
+    if (i < nk) bfrag[i] = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
+  const int cip = lane & 31, col = n0 + cip;
+  const bool col_ok = has_cols && col < m.V;
+  const float col_bias = col_ok ? m.b_out[col_ok ? col : 0] : kKeyNone;
+  const float b_blank = m.b_out[m.V];
+  CallDev cl = c;   // the decision code reads the keys through parts and, for near-ties, the current projections through p
+  cl.p = pfull;
+  cl.parts = reinterpret_cast<float *>(zs);   // the iteration's keys are copied over the window rows once those are used up
+  constexpr int KI = kTinyMaxHj / 256;
+  float4 wblank[KI];
+#pragma unroll
+  for (int i = 0; i < KI; ++i) {
+    const int k = lane * 4 + 256 * i;
+    wblank[i] = k < Hj ? *reinterpret_cast<const float4 *>(m.w_blank + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  unsigned passed = 0;
+  __syncthreads();
+  // The recurrent half of the gate sums, W_hh h, depends on the hidden vector only, which changes
+  // when its utterance emits: it is formed as soon as the new vector is here (while the arrivals of
+  // the projection exchange travel), so that a step, once the label is known, only adds the
+  // label's row of input sums.  rec[b]: this wave's 16 (unit, gate) sums for utterance b, value
+  // 4q + gate in lanes 4q + 16*(gate>>1) + 32*(gate&1) + 0..3.
+  auto recurrent_sums = [&](int ub) {
+    float part[16];   // [unit q][gate]
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int u = wave + 4 * q;
+#pragma unroll
+      for (int gate = 0; gate < 4; ++gate) part[4 * q + gate] = 0.f;
+      if (u >= lp.upw) continue;
+      for (int k = lane * 8; k < Hp; k += 512) {
+#pragma unroll
+        for (int gate = 0; gate < 4; ++gate)
+          part[4 * q + gate] = dot8(wl + ((size_t)u * 4 + gate) * Hp + k, ub * Hp + k, part[4 * q + gate]);
+      }
+    }
+    return wave_sum16_scatter(part, lane);
+  };
+  float rec[kLoopMaxB];
+#pragma unroll
+  for (int b = 0; b < kLoopMaxB; ++b) rec[b] = b < B ? recurrent_sums(b) : 0.f;
+
+  const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
+  long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
+  for (int it = 0; it < lp.max_iters && na > 0; ++it) {
+    const int par = it & 1;
+    const long long t0 = dbg ? wall_clock64() : 0;
+    const int n_rows = na * W;
+    float2 *parts = lp.parts_x + (size_t)par * kLoopRows * c.nparts_tiny;
+    for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
+    // ---- window rows into LDS with their fp32 blank logit and norm (every workgroup: all rows)
+    for (int q0 = 0; q0 < 8; q0 += 4) {
+      if (q0 * 4 >= n_rows) continue;   // no window rows in this pass (what those rows of z hold is never looked at)
+      float4 ev[4][KI];
+      bool valid[4];
+      int arow[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = wave + 4 * (q0 + q);
+        valid[q] = false;
+        arow[q] = 0;
+        const float *er = c.e;
+        if (row < n_rows) {
+          const int a = row >= W ? 1 : 0, j = row - a * W;   // at most two utterances
+          const int4 st = sh.slot[a];
+          valid[q] = st.y + j < st.z;
+          arow[q] = st.x;
+          er = c.e + ((size_t)st.x * c.T + (valid[q] ? st.y + j : 0)) * Hj;
+        }
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+          const int k = lane * 4 + 256 * i;
+          ev[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (valid[q] && k < Hj) ev[q][i] = *reinterpret_cast<const float4 *>(er + k);
+        }
+      }
+      float dn[8];   // [q][blank-logit part, squared norm]
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = wave + 4 * (q0 + q);
+        float dot = 0.f, nrm = 0.f;
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+          const int k = lane * 4 + 256 * i;
+          if (k < Hj && row < n_rows) {   // rows past the windows: what z holds there is never looked at
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (valid[q]) {
+              const float4 pv = *reinterpret_cast<const float4 *>(pfull + (size_t)arow[q] * Hj + k);
+              x.x = fmaxf(ev[q][i].x + pv.x, 0.f); x.y = fmaxf(ev[q][i].y + pv.y, 0.f);
+              x.z = fmaxf(ev[q][i].z + pv.z, 0.f); x.w = fmaxf(ev[q][i].w + pv.w, 0.f);
+            }
+            *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+            const float4 wb = wblank[i];
+            dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
+            nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+          }
+        }
+        dn[2 * q] = dot;
+        dn[2 * q + 1] = nrm;
+      }
+      const float tot = wave_sum8_scatter(dn, lane);   // lane 4q: row q's dot; lane 4q + 16: its squared norm
+      const int rowq = wave + 4 * (q0 + ((lane >> 2) & 3));
+      if (rowq < n_rows && (lane & 0x23) == 0) {
+        if (lane & 16) sh.znorm[rowq] = sqrtf(tot);
+        else sh.blank[rowq] = tot + b_blank;
+      }
+    }
+    // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
+    // are consumed one iteration later, so that no wave ever waits for these loads.
+    {
+      warm += pend[0] + pend[1];
+      pend[0] = 0.f; pend[1] = 0.f;
+      const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
+      for (int a = 0; a < na; ++a) {
+        const int4 st = sh.slot[a];
+        const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
+        const int l = tid & 31;
+        for (int tr = t_first + (tid >> 5), i2 = 0; tr < t_end; tr += 8, ++i2)
+          if (l < lines_per_row) pend[i2 & 1] += c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+      }
+    }
+    __syncthreads();
+    const long long t1 = dbg ? wall_clock64() : 0;
+    // ---- this workgroup's 32 columns: K split over the four waves, W_out from registers
+    if (has_cols) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      const bf16_t *zrow = zs + (size_t)(lane & 31) * zstride + k0 + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < kTinyPrefetch; ++i)
+        if (i < nk) {
+          const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag[i], acc, 0, 0, 0);
+        }
+      __syncthreads();   // every wave is done with z: its LDS takes the K-split partial sums
+      float *red = reinterpret_cast<float *>(zs);   // [wave][r][lane]
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
+      __syncthreads();
+      if (wave == 0) {
+        float k1[16], k2[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = col_bias;
+#pragma unroll
+          for (int w2 = 0; w2 < 4; ++w2) v += red[(w2 * 16 + r) * 64 + lane];
+          k1[r] = make_key(col_ok ? v : kKeyNone, cip);
+          k2[r] = kKeyNone;
+        }
+        float o1[1], o2[1];
+        RowTop2<16, 0>::run(k1, k2, lane, o1, o2);
+        const int s0 = rowtop2_first_slot<16>(lane);
+        st_shared_f32x2(&parts[(size_t)acc_row(0, s0, lane) * c.nparts_tiny + g], make_float2(o1[0], o2[0]));
+      }
+    }
+    const long long t2 = dbg ? wall_clock64() : 0;
+    if (!loop_barrier(lp, passed, ls)) return;            // exchange 1: every row's keys are in memory
+    const long long t3 = dbg ? wall_clock64() : 0;
+    // ---- the decisions, taken alike by every workgroup; workgroup 0 writes the outputs
+    // With at most 64 parts per row and 4 rows per wave the decision only looks at the keys its
+    // caller hands it, which are read here straight from the exchange buffer; otherwise the keys
+    // are copied to LDS first.
+    float2 *lparts = reinterpret_cast<float2 *>(zs);
+    const bool direct = c.nparts_tiny <= 64 && W <= 4 * kRowsAhead;
+    if (!direct) {
+      for (int i = tid; i < n_rows * c.nparts_tiny; i += 256) lparts[i] = ld_shared_f32x2(parts + i);
+      __syncthreads();
+    }
+    const bool quad = direct && c.nparts_tiny <= 32;   // four rows per wave decided at once
+    for (int a = 0; a < na; ++a) {
+      RowsAhead ahead;
+      if (quad) {
+        const int s = lane & 15, j = wave + (lane >> 4) * 4, row = a * W + j;
+        float2 kA = make_float2(kKeyNone, kKeyNone), kB = kA;
+        float vb = 0.f, zn = 0.f;
+        if (j < W) {
+          if (s < c.nparts_tiny) kA = ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s);
+          if (s + 16 < c.nparts_tiny) kB = ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s + 16);
+          vb = sh.blank[row];
+          zn = sh.znorm[row];
+        }
+        auto reload = [&](int r, int part) { return ld_shared_f32x2(parts + (size_t)r * c.nparts_tiny + part); };
+        const int rechecked = decide_rows_quad<bf16_t>(m, cl, a, sh.slot[a], c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
+        decide_utterance<bf16_t, true>(m, cl, a, sh.slot[a], sh.cnt[a], 0, c.nparts_tiny, c.nparts_tiny, kTinyCols, ahead, sh,
+                                       g == 0, true, rechecked);
+        continue;
+      }
+#pragma unroll
+      for (int q = 0; q < kRowsAhead; ++q) {
+        const int j = wave + q * 4, row = a * W + j;
+        ahead.kk0[q] = no_keys();
+        ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
+        if (j < W) {
+          if (lane < c.nparts_tiny) {
+            const float2 k2 = direct ? ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + lane) : lparts[(size_t)row * c.nparts_tiny + lane];
+            ahead.kk0[q].x = k2.x;
+            ahead.kk0[q].y = k2.y;
+          }
+          ahead.vb[q] = sh.blank[row];
+          ahead.zn[q] = sh.znorm[row];
+        }
+      }
+      decide_utterance<bf16_t, true>(m, cl, a, sh.slot[a], sh.cnt[a], 0, c.nparts_tiny, c.nparts_tiny, kTinyCols, ahead, sh,
+                                     g == 0);
+    }
+    if (wave == 0) {
+      // survivors keep their order; the emit list is the survivors that produced a label
+      if (lane == 0) {
+        int n_act = 0, n_em = 0;
+        for (int a = 0; a < na; ++a) {
+          const int f = sh.flag[a];
+          if (f & 2) { ls.emit_ub[n_em] = sh.slot[a].x; ls.emit_tok[n_em] = sh.tok[a]; ++n_em; }
+          if (f & 1) { ls.nslot[n_act] = sh.slot[a]; ls.ncnt[n_act] = sh.cnt[a]; ++n_act; }
+          if (g == 0) {   // the window's counters (see decide_utterance for the packing)
+            const unsigned ev = sh.event[a];
+            lstats[ST_ROWS] += ev & 127u; lstats[ST_USEFUL] += (ev >> 7) & 127u; lstats[ST_RECHECK] += (ev >> 21) & 127u;
+            lstats[ST_LABELS] += (ev >> 28) & 1u; lstats[ST_FORCED] += (ev >> 29) & 1u; lstats[ST_OVERFLOW] += (ev >> 30) & 1u;
+            lstats[kStatJump0 + ((ev >> 14) & 127u)] += 1ull;
+          }
+        }
+        if (g == 0) { lstats[ST_ITER] += 1ull; lstats[ST_WINDOWS] += (unsigned long long)na; }
+        ls.n_act = n_act;
+        ls.n_emit = n_em;
+      }
+    }
+    __syncthreads();
+    na = ls.n_act;
+    const int n_emit = ls.n_emit;
+    if (tid < na) { sh.slot[tid] = ls.nslot[tid]; sh.cnt[tid] = ls.ncnt[tid]; }
+    __syncthreads();
+    const long long t4 = dbg ? wall_clock64() : 0;
+    if (dbg) { tsum[0] += t1 - t0; tsum[1] += t2 - t1; tsum[2] += t3 - t2; tsum[3] += t4 - t3; ++n_it; }
+    if (n_emit == 0 || na == 0) continue;
+    // ---- one LSTM step for the utterances that emitted: this workgroup's units, weights from LDS
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r], tok = ls.emit_tok[r];
+      // the label's input gate sums of this wave's (at most four) units: one round trip for all
+      float4 addq[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int unit = unit0 + wave + 4 * q;
+        addq[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (wave + 4 * q < lp.upw && unit < Hp) addq[q] = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok * 4 * Hp + unit * 4);
+      }
+      // the recurrent sums were formed when this utterance's hidden vector last changed: every gate's
+      // nonlinearity runs on its own lanes, then lane 4q gathers its unit's four
+      float tot = rec[0];
+#pragma unroll
+      for (int b = 1; b < kLoopMaxB; ++b) tot = ub == b ? rec[b] : tot;
+      const int q = (lane >> 2) & 3, gate = ((lane >> 4) & 1) * 2 + (lane >> 5);
+      float4 aq = addq[0];
+      if (q == 1) aq = addq[1];
+      if (q == 2) aq = addq[2];
+      if (q == 3) aq = addq[3];
+      const float pre = tot + (gate == 0 ? aq.x : gate == 1 ? aq.y : gate == 2 ? aq.z : aq.w);
+      const float act = gate == 2 ? tanhf(pre) : 1.f / (1.f + expf(-pre));
+      const int base = lane & 12;
+      const float ig = __shfl(act, base, kWave), fg = __shfl(act, base + 32, kWave);
+      const float gg = __shfl(act, base + 16, kWave), og = __shfl(act, base + 48, kWave);
+      const int u = wave + 4 * q, unit = unit0 + u;
+      if ((lane & 0x33) == 0 && u < lp.upw && unit < Hp) {
+        const float cn = fg * cst[ub * lp.upw + u] + ig * gg;
+        cst[ub * lp.upw + u] = cn;
+        st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit], og * tanhf(cn));
+      }
+    }
+    const long long t5 = dbg ? wall_clock64() : 0;
+    if (!loop_barrier(lp, passed, ls)) return;            // exchange 2: the new hidden vectors
+    const long long t6 = dbg ? wall_clock64() : 0;
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r];
+      for (int k = tid * 2; k < Hp; k += 512) put_h2(ub * Hp + k, ld_shared_f32x2(reinterpret_cast<const float2 *>(&lp.h_x[(size_t)ub * Hp + k])));
+    }
+    __syncthreads();
+    // ---- this workgroup's rows of the prediction projection
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r];
+      // this wave's rows jl = wave + 4q, q < ppw / 4, four at a time
+      for (int q0 = 0; q0 * 4 < lp.ppw; q0 += 4) {
+        float part[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int jl = wave + 4 * (q0 + q);
+          part[q] = 0.f;
+          if (jl >= lp.ppw) continue;
+          for (int k = lane * 8; k < Hp; k += 512) part[q] = dot8(wp + (size_t)jl * Hp + k, ub * Hp + k, part[q]);
+        }
+        const float tot = wave_sum4_scatter(part, lane);   // lanes 4q .. 4q+3 of every row of 16 hold row q's sum
+        const int jl = wave + 4 * (q0 + ((lane >> 2) & 3)), j = prow0 + jl;
+        if ((lane & 0x33) == 0 && jl < lp.ppw && j < Hj) st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], tot + m.b_pred[j]);
+      }
+    }
+    const long long t7 = dbg ? wall_clock64() : 0;
+    loop_arrive(lp, passed);                              // exchange 3: the new projections ...
+    for (int r = 0; r < n_emit; ++r) {                    // ... and, while the arrivals travel, the next step's recurrent sums
+      const int ub = ls.emit_ub[r];
+      const float v = recurrent_sums(ub);
+#pragma unroll
+      for (int b = 0; b < kLoopMaxB; ++b) rec[b] = ub == b ? v : rec[b];
+    }
+    if (!loop_wait(lp, passed, ls)) return;
+    const long long t8 = dbg ? wall_clock64() : 0;
+    for (int r = 0; r < n_emit; ++r) {
+      const int ub = ls.emit_ub[r];
+      for (int k = tid; k < Hj; k += 256) pfull[(size_t)ub * Hj + k] = ld_shared_f32(&lp.p_x[(size_t)ub * Hj + k]);
+    }
+    __syncthreads();
+    if (dbg) {
+      const long long t9 = wall_clock64();
+      tsum[4] += t5 - t4; tsum[5] += t6 - t5; tsum[6] += t7 - t6; tsum[7] += t8 - t7; tsum[8] += t9 - t8; ++n_em_it;
+    }
+  }
+  if (dbg) {
+    for (int i = 0; i < 9; ++i) c.dbg[i] += tsum[i];
+    c.dbg[10] += n_it; c.dbg[11] += n_em_it;
+  }
+  __syncthreads();
+  if (g == 0) {
+    for (int i = tid; i < kNumStats; i += 256) c.stats[i] = lstats[i];
+    if (tid == 0) {
+      c.n_active[0] = na;   // zero unless max_iters ran out
+      c.n_active[1] = na;
+    }
+  }
+  if (warm == 1.2345e-30f && lp.spin_limit == 0u) lp.h_x[0] = warm;   // keeps the warming loads alive; never true
+}
+
+}  // namespace wind
