@@ -96,7 +96,7 @@ void oracle_decoder_step(const oracle_model *m, int token, double *h, double *c)
   free(gates);
 }
 
-/* dec = decoder(hyp) computed from nothing: zero state, the start id V, then every label of hyp.
+/* The decoder output for a label sequence hyp, computed from nothing: zero state, the start id V, then every label of hyp.
    g receives the top layer's h ([Hp]). */
 void oracle_decoder_from_scratch(const oracle_model *m, const int32_t *hyp, int n, double *g) {
   size_t sz = (size_t)m->L * m->Hp;
@@ -119,7 +119,7 @@ void oracle_encoder_projection(const oracle_model *m, const float *f, double *ou
   }
 }
 
-/* joined = joiner(enc[t,:], dec[-1]) -> logits[V+1] */
+/* The joiner on one encoder frame f and one decoder output g -> logits[V+1] */
 void oracle_joiner(const oracle_model *m, const float *f, const double *g, double *logits) {
   double *z = (double *)malloc(sizeof(double) * (size_t)m->Hj);
   for (int j = 0; j < m->Hj; ++j) {
@@ -163,9 +163,9 @@ int oracle_greedy(const oracle_model *m, const float *enc, int len, int S,
   double *h = (double *)calloc(sz, sizeof(double)), *c = (double *)calloc(sz, sizeof(double));
   double *logits = (double *)malloc(sizeof(double) * (size_t)(m->V + 1));
   int t = 0, u = 0, sym = 0, nl = 0, rc = 0;
-  oracle_decoder_step(m, blank, h, c);                       /* dec = decoder([]) */
+  oracle_decoder_step(m, blank, h, c);                       /* decoder output before any label */
   while (t < len) {
-    const double *g = h + (size_t)(m->L - 1) * m->Hp;        /* dec[-1] */
+    const double *g = h + (size_t)(m->L - 1) * m->Hp;        /* the top layer's hidden vector */
     oracle_joiner(m, enc + (size_t)t * m->D, g, logits);
     int i1, i2;
     top2(logits, m->V + 1, &i1, &i2);
@@ -180,8 +180,8 @@ int oracle_greedy(const oracle_model *m, const float *enc, int len, int S,
     }
     if (label != blank) {
       if (u >= cap) { rc = -1; break; }
-      tokens[u] = label; frames[u] = t; ++u;                 /* hyp.append(label) */
-      oracle_decoder_step(m, label, h, c);                   /* dec = decoder(hyp) */
+      tokens[u] = label; frames[u] = t; ++u;                 /* the label joins the hypothesis ... */
+      oracle_decoder_step(m, label, h, c);                   /* ... and is fed to the decoder; the frame stays */
       if (++sym == S) { t += 1; sym = 0; }
     } else {
       t += 1; sym = 0;
@@ -212,10 +212,10 @@ int oracle_wind(const oracle_model *m, const float *enc, int len, int W, int S,
   while (t < len) {
     const double *g = h + (size_t)(m->L - 1) * m->Hp;
     int n = W < len - t ? W : len - t;
-    for (int j = 0; j < n; ++j) {                            /* joined = joiner(enc[t:t+n], dec[-1]) */
+    for (int j = 0; j < n; ++j) {                            /* the joiner on the window's n frames, one decoder output */
       oracle_joiner(m, enc + (size_t)(t + j) * m->D, g, joined + (size_t)j * V1);
       int i2;
-      top2(joined + (size_t)j * V1, V1, &labels[j], &i2);    /* labels = argmax(joined, dim=-1) */
+      top2(joined + (size_t)j * V1, V1, &labels[j], &i2);    /* each row's most probable id */
     }
     if (calls) {
       if (nc >= calls_cap) { rc = -1; break; }
