@@ -318,6 +318,16 @@ int wind_get_call_times(wind_model *m, double *total_ms, double *loop_ms);
 int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, int *n);
 
 /*
+ * How the last decode call ran its loop (the loop of Algorithm 2, for one or two utterances, can run
+ * as one resident kernel; option "loop_kernel"): *workgroups receives the number of workgroups of
+ * that kernel, 0 if the call replayed the graph of per-step kernels instead; *one_l2 receives 1 if
+ * those workgroups all sat on one XCD and exchanged their values through its L2 (option
+ * "loop_one_xcd"), else 0.  Completes a pending asynchronous decode first.  HOST pointers;
+ * WIND_ERR_ARG for null pointers.
+ */
+int wind_get_loop_info(wind_model *m, int *workgroups, int *one_l2);
+
+/*
  * Tuning knobs, for benchmarks and tests.  key/value pairs:
  *   "graph"   1 (default): the decode loop is replayed from a captured HIP graph; 0: kernels are
  *             launched one by one (the with / without graph rows of Table 5)
@@ -339,6 +349,10 @@ int wind_get_joint_launches(wind_model *m, int32_t *rows, float *us, int cap, in
  *   "loop_kernel"  1 (default): decodes of one or two utterances with at most 32 window rows (bf16, one
  *             LSTM layer, weights that fit the chip's LDS) run the whole loop as one resident kernel
  *             whose workgroups meet at grid barriers; 0: always the graph of per-step kernels
+ *   "loop_one_xcd"  1 (default): where 32 workgroups suffice for that kernel (and the window rows number
+ *             at most 16), they are placed on the CUs of one XCD and exchange through its L2, which
+ *             shortens every grid barrier; the kernel checks the placement itself and falls back to
+ *             device-wide stores if it is not as expected.  0: spread over the chip
  *   "loop_spin_limit"  polls a workgroup of that kernel waits at a barrier before it gives up
  *             (default 2^21, about a second); the decode then returns WIND_ERR_HIP.  Tests set it
  *             to 0 to exercise that path: every workgroup still leaves the kernel normally

@@ -17,7 +17,8 @@ WIND_OK, WIND_ERR_ARG, WIND_ERR_HIP, WIND_ERR_OVERFLOW, WIND_ERR_UNSUPPORTED, WI
 EXPORTS = ("wind_load_weights", "wind_free", "wind_greedy_decode", "wind_sequential_decode",
            "wind_greedy_decode_async", "wind_get_stats", "wind_debug_joint_logits", "wind_set_option", "wind_last_error",
            "wind_get_kernel_times", "wind_get_joint_launches", "wind_get_call_times", "wind_beam_window_scores", "wind_beam_decode",
-           "wind_workspace_bytes", "wind_debug_enc_proj", "wind_debug_joint_keys", "wind_beam_window_scores_static")
+           "wind_workspace_bytes", "wind_debug_enc_proj", "wind_debug_joint_keys", "wind_beam_window_scores_static",
+           "wind_get_loop_info")
 PREFIX_MODES = {"off": 0, "keep": 1, "remove": 2}
 KERNEL_NAMES = ("enc_proj", "build_z", "joint", "decide", "lstm", "pred_proj")
 
@@ -94,6 +95,7 @@ def load_library():
         lib.wind_debug_joint_keys.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                               C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
         lib.wind_get_call_times.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        lib.wind_get_loop_info.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         lib.wind_get_joint_launches.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int,
                                                 C.POINTER(C.c_int)]
         lib.wind_beam_window_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
@@ -222,6 +224,12 @@ class WindModel:
         a, b = C.c_double(0), C.c_double(0)
         _check(self._lib.wind_get_call_times(self._h, C.byref(a), C.byref(b)))
         return a.value, b.value
+
+    def loop_info(self):
+        """(workgroups of the resident loop kernel in the last decode call, or 0; whether they shared one L2)."""
+        g, one = C.c_int(0), C.c_int(0)
+        _check(self._lib.wind_get_loop_info(self._h, C.byref(g), C.byref(one)))
+        return int(g.value), bool(one.value)
 
     def joint_launches(self):
         """(rows, us) of every joint launch of the last decode made with option "profile" = 1."""

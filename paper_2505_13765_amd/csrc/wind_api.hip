@@ -129,6 +129,7 @@ struct wind_model {
   unsigned *async_bar = nullptr;
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_loop_kernel = 1;
+  int opt_loop_one_xcd = 1;
   long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
   int opt_lstm_rec = 1;
@@ -143,6 +144,7 @@ struct wind_model {
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
+  int loop_info[2] = {0, 0};   // last decode call: workgroups of the resident loop kernel (0: not used), whether they shared one L2
   long long prev_iters = 0;
   int prev_B = 0, prev_T = 0, prev_W = 0;
   wind_stats last_stats{};
@@ -532,23 +534,30 @@ int fetch_stats(wind_model *m, hipStream_t s) {
 
 // Shape of the resident loop kernel for this call, or false if the call does not qualify: bf16, one
 // LSTM layer, at most 2 utterances and 32 window rows, every workgroup's weight slice within LDS,
-// at most one workgroup per CU.
+// at most one workgroup per CU.  First choice: at most 32 workgroups, which fit the CUs of one XCD
+// and then exchange through its L2 (a wave takes up to five LSTM units; window rows limited to 16 so
+// that the larger weight slices still fit LDS); otherwise 16 units per workgroup, spread over the chip.
 bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *smem) {
   const ModelDev &d = m->dev;
   if (m->dtype != WIND_BF16 || d.L != 1 || B > kLoopMaxB || B * W > kLoopRows || d.Hj > kTinyMaxHj) return false;
   if (!m->opt_loop_kernel || m->opt_profile || !m->opt_graph || m->opt_host_sync) return false;
   const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
-  const int widest = d.Hp > d.Hj ? d.Hp : d.Hj;
-  int G = (widest + 15) / 16;
-  if (G < nparts_tiny) G = nparts_tiny;
-  if (G > 256) return false;
-  lp->G = G;
-  lp->upw = ((d.Hp + G - 1) / G + 3) / 4 * 4;
-  lp->ppw = ((d.Hj + G - 1) / G + 3) / 4 * 4;
-  *smem = loop_smem_bytes(d.Hp, d.Hj, B, lp->upw, lp->ppw);
-  if (lp->upw > 16 || lp->ppw > 16) return false;                   // a wave steps at most four units / rows
   if (nparts_tiny * 8 > (d.Hj + 8) * 2) return false;              // a row's keys fit where its hidden vector was
-  return *smem + 6144 <= 160 * 1024;   // room for the kernel's static LDS
+  const int widest = d.Hp > d.Hj ? d.Hp : d.Hj;
+  for (int near = m->opt_loop_one_xcd ? 1 : 0; near >= 0; --near) {
+    int G = near ? kLoopNearG : (widest + 15) / 16;
+    if (G < nparts_tiny) { if (near) continue; G = nparts_tiny; }
+    if (G > 256) return false;
+    lp->G = G;
+    lp->step = near ? 8 : 1;
+    lp->zrows = near && B * W <= 16 ? 16 : kLoopRows;
+    lp->upw = ((d.Hp + G - 1) / G + 3) / 4 * 4;
+    lp->ppw = ((d.Hj + G - 1) / G + 3) / 4 * 4;
+    *smem = loop_smem_bytes(d.Hp, d.Hj, B, lp->upw, lp->ppw, lp->zrows);
+    if (lp->upw > 20 || lp->ppw > 32) continue;                      // a wave steps at most five units
+    if (*smem + 6144 <= 160 * 1024 && *smem <= kLoopMaxSmem) return true;   // room for the kernel's static LDS
+  }
+  return false;
 }
 
 // One decode call.  ext_ws null: the model's own workspace, and the call returns when the decode has
@@ -592,6 +601,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   size_t loop_smem = 0;
   const bool use_loop = loop_kernel_shape(m, B, W, &lp, &loop_smem);
   const long long max_iters = (long long)T * ((long long)S + 1) + 2;   // every iteration moves some pointer or emits
+  m->loop_info[0] = m->loop_info[1] = 0;
   m->fma_pred_step = use_loop;   // the resident kernel starts from the fp32 state of the start-token step
   if (use_loop) { c.rec = nullptr; c.lists_atomic = 0; }
   m->have_call_times = false;
@@ -607,17 +617,19 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
       const int bar_ints = (1 + lp.G) * kLoopFlagStride;
       fill_int_kernel<<<(unsigned)((bar_ints + 255) / 256), 256, 0, s>>>((int *)lp.bar, bar_ints, 0);
     }
-    wind_loop_kernel<<<(unsigned)lp.G, 256, loop_smem, s>>>(m->dev, c, lp);
+    wind_loop_kernel<<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);
     rc = check_launch("resident loop");
     if (rc) return rc;
     HIP_TRY(hipEventRecord(m->ev_call[2], s));
     if (async) {
       m->async_pending = true; m->async_loop = true; m->async_stream = s; m->async_bar = lp.bar;
+      m->loop_info[0] = lp.G; m->loop_info[1] = 0;
       return WIND_OK;
     }
     HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(m->h_flag + 1, lp.bar, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(m->h_flag + 1, lp.bar, 2 * sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    m->loop_info[0] = lp.G; m->loop_info[1] = m->h_flag[2] == 2;
     if (m->h_flag[1] != 0) return fail(WIND_ERR_HIP, "resident loop: a grid barrier timed out (workgroups not all resident?)");
     if (m->h_flag[0] != 0) return fail(WIND_ERR_HIP, "decode loop did not terminate");
     m->have_call_times = true;
@@ -827,7 +839,7 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   if (rc == WIND_OK) {
     hipError_t e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)wind_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 154 * 1024);
+      e = hipFuncSetAttribute((const void *)wind_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLoopMaxSmem);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
@@ -964,8 +976,9 @@ static int finish_async(wind_model *m) {
   m->async_pending = false;
   m->h_flag[0] = m->h_flag[1] = 0;
   HIP_TRY(hipMemcpyAsync(m->h_flag, m->call.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
-  if (m->async_loop) HIP_TRY(hipMemcpyAsync(m->h_flag + 2, m->async_bar, sizeof(int), hipMemcpyDeviceToHost, s));
+  if (m->async_loop) HIP_TRY(hipMemcpyAsync(m->h_flag + 2, m->async_bar, 2 * sizeof(int), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
+  if (m->async_loop) m->loop_info[1] = m->h_flag[3] == 2;
   if (m->async_loop && m->h_flag[2] != 0)
     return fail(WIND_ERR_HIP, "resident loop: a grid barrier timed out (workgroups not all resident?)");
   int rc = fetch_stats(m, s);
@@ -979,6 +992,14 @@ static int finish_async(wind_model *m) {
   }
   if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
   return rc;
+}
+
+int wind_get_loop_info(wind_model *m, int *workgroups, int *one_l2) {
+  if (!m || !workgroups || !one_l2) return fail(WIND_ERR_ARG, "null argument");
+  if (m->async_pending) { const int rc = finish_async(m); if (rc != WIND_OK && rc != WIND_ERR_OVERFLOW && rc != WIND_ERR_UNFINISHED) return rc; }
+  *workgroups = m->loop_info[0];
+  *one_l2 = m->loop_info[1];
+  return WIND_OK;
 }
 
 int wind_get_stats(wind_model *m, wind_stats *out) {
@@ -1050,6 +1071,10 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   }
   if (!std::strcmp(key, "loop_kernel")) {
     m->opt_loop_kernel = value != 0;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "loop_one_xcd")) {
+    m->opt_loop_one_xcd = value != 0;
     return WIND_OK;
   }
   if (!std::strcmp(key, "loop_spin_limit")) {

@@ -21,55 +21,74 @@ namespace wind {
 // spin_limit polls, or sees the abort word set, sets it and leaves the kernel, so every wave
 // reaches the end whatever happens to the others.  The host treats a set abort word as an error.  All G workgroups must be
 // resident at once; the host launches at most one per CU.
+//
+// Placement.  Workgroups are dealt to the chip's eight XCDs in turn by their launch index, and each XCD
+// has an L2 of its own.  With at most 32 workgroups (one per CU of an XCD) the host launches eight
+// times as many and only every eighth takes part (step = 8), which puts all of them behind ONE L2:
+// an exchanged value is then stored through to that L2 and read from it, instead of travelling to
+// the memory side and back (a barrier takes 0.6 us instead of 1.5 us).  The kernel checks the
+// placement itself: the workgroups publish their XCD number in a first barrier that uses the
+// everywhere-valid device-wide stores, and keep those stores unless all numbers are equal.
 struct LoopDev {
-  unsigned *bar;       // word 0: abort; word (1 + g) * 32: barriers workgroup g has reached; all zero at launch
+  unsigned *bar;       // word 0: abort; word 1: 2 if the workgroups shared one L2, 1 if not; word (1 + g) * 32: barriers workgroup g has reached, the next word its XCD number + 1; all zero at launch
   float *h_x;          // [B][Hp] new hidden vectors
   float *p_x;          // [B][Hj] new projections
   float2 *parts_x;     // [2][32][nparts_tiny] keys, by iteration parity
   int G, upw, ppw;     // workgroups; LSTM units and W_pred rows per workgroup (multiples of 4)
+  int step;            // launch index of workgroup g is g * step (8: all on one XCD, 1: spread over the chip)
+  int zrows;           // rows of the window-row region of LDS (16 or 32)
   int max_iters;       // more iterations than any decode of this call can take
   unsigned spin_limit;
 };
 constexpr int kLoopMaxB = 2;
+constexpr int kLoopNearG = 32;                 // CUs of one XCD
+constexpr size_t kLoopMaxSmem = 154 * 1024;    // dynamic LDS the kernel may be launched with
 constexpr int kLoopRows = 32;
 
 struct LoopShared {
   int4 nslot[kLoopMaxB];
   int ncnt[kLoopMaxB];
   int emit_ub[kLoopMaxB], emit_tok[kLoopMaxB];
-  int n_act, n_emit, ok;
+  int n_act, n_emit, ok, near;
 };
 
-// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: 32 rows of Hj+8 bf16, at least 16 KB][hhi, hlo: B*Hp bf16 each]
+// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: zrows rows of Hj+8 bf16, at least 16 KB][hhi, hlo: B*Hp bf16 each]
 //      [pfull: B*Hj f32][cst: B*upw f32]
 // bf16 elements of the window-row region zs.  The region also takes the K-split partial sums of the MFMA
 // phase (4 waves x 16 registers x 64 lanes of fp32 = 16 KB), which is the larger of the two for Hj < 248.
-__host__ __device__ inline size_t loop_z_elems(int Hj) {
-  const size_t z = (size_t)kLoopRows * (Hj + 8);
+__host__ __device__ inline size_t loop_z_elems(int Hj, int zrows) {
+  const size_t z = (size_t)zrows * (Hj + 8);
   return z > 8192 ? z : 8192;
 }
-__host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw) {
-  return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + loop_z_elems(Hj) * 2 + (size_t)B * Hp * 4 +
+__host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw, int zrows) {
+  return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + loop_z_elems(Hj, zrows) * 2 + (size_t)B * Hp * 4 +
          (size_t)B * Hj * 4 + (size_t)B * upw * 4;
 }
 
-// Values that another workgroup of the running kernel wrote are read and written with agent-scope
-// atomics (they go past the caches that are private to a CU or an XCD), so that the barrier needs
-// no cache invalidation and the read-only operands stay in L2 from iteration to iteration.
+// Values that another workgroup of the running kernel wrote are read with agent-scope atomic loads
+// (they skip the CU's own cache) and written with atomic stores, so that the barrier needs no cache
+// invalidation and the read-only operands stay in L2 from iteration to iteration.  `near`: all
+// workgroups share one L2, a store need only reach that (workgroup scope: written through the CU's
+// cache); otherwise it goes to the memory side (agent scope).
+__device__ __forceinline__ void st_shared_u32(unsigned *p, unsigned v, bool near) {
+  if (near) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  else __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ float ld_shared_f32(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void st_shared_f32(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void st_shared_f32(float *p, float v, bool near) {
+  st_shared_u32(reinterpret_cast<unsigned *>(p), __float_as_uint(v), near);
 }
 __device__ __forceinline__ float2 ld_shared_f32x2(const float2 *p) {
   const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
                                                  __HIP_MEMORY_SCOPE_AGENT);
   return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
 }
-__device__ __forceinline__ void st_shared_f32x2(float2 *p, float2 v) {
+__device__ __forceinline__ void st_shared_f32x2(float2 *p, float2 v, bool near) {
   const unsigned long long u = (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32);
-  __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (near) __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  else __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 constexpr int kLoopFlagStride = 32;   // one 128-byte line per workgroup's arrival word
@@ -77,11 +96,12 @@ constexpr int kLoopFlagStride = 32;   // one 128-byte line per workgroup's arriv
 // time the arrivals take to travel: loop_arrive publishes this workgroup's arrival, loop_wait waits
 // for everybody's.  Between the two a workgroup must not write anything the others read before
 // the barrier, nor read what they write.
-__device__ __forceinline__ void loop_arrive(const LoopDev &lp, unsigned passed) {
-  __syncthreads();   // this workgroup's stores of the phase have been issued and acknowledged
+__device__ __forceinline__ void loop_arrive(const LoopDev &lp, int g, bool near, unsigned passed) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // every lane's own stores of the phase have been acknowledged
+  __syncthreads();
   if (threadIdx.x == 0) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and are visible to the agent before the arrival is
-    __hip_atomic_store(&lp.bar[(1 + blockIdx.x) * kLoopFlagStride], passed + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!near) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and are visible to the agent before the arrival is
+    st_shared_u32(&lp.bar[(1 + g) * kLoopFlagStride], passed + 1, near);
   }
 }
 __device__ __forceinline__ bool loop_wait(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
@@ -112,8 +132,8 @@ __device__ __forceinline__ bool loop_wait(const LoopDev &lp, unsigned &passed, L
   asm volatile("" ::: "memory");   // the exchange reads that follow stay behind the wait
   return ls.ok != 0;
 }
-__device__ __forceinline__ bool loop_barrier(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
-  loop_arrive(lp, passed);
+__device__ __forceinline__ bool loop_barrier(const LoopDev &lp, int g, bool near, unsigned &passed, LoopShared &ls) {
+  loop_arrive(lp, g, near, passed);
   return loop_wait(lp, passed, ls);
 }
 
@@ -171,7 +191,8 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   __shared__ DecideShared sh;
   __shared__ LoopShared ls;
   __shared__ unsigned long long lstats[kNumStats];   // workgroup 0: the call's counters, written out at the end
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = blockIdx.x;
+  if (blockIdx.x % lp.step) return;   // launched only so that the workgroups that take part land on one XCD
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = blockIdx.x / lp.step;
   const int Hj = m.Hj, Hp = m.Hp, W = c.W, B = c.B;
   const int zstride = Hj + 8;
   bf16_t *wl = reinterpret_cast<bf16_t *>(smem_raw);
@@ -179,7 +200,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   bf16_t *zs = wp + (size_t)lp.ppw * Hp;
   // the hidden vectors as bf16 hi + lo (hi = RNE(h), lo = RNE(h - hi), 16 mantissa bits together): the dot
   // products with the bf16 weights then take one packed instruction per pair and part, with nothing to unpack
-  bf16_t *hhi = zs + loop_z_elems(Hj), *hlo = hhi + (size_t)B * Hp;
+  bf16_t *hhi = zs + loop_z_elems(Hj, lp.zrows), *hlo = hhi + (size_t)B * Hp;
   float *pfull = reinterpret_cast<float *>(hlo + (size_t)B * Hp);
   auto put_h2 = [&](int i, float2 v) {   // elements i (even) and i + 1
     const uint32_t hb = pack_bf16x2(v.x, v.y);
@@ -264,7 +285,18 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   // when its utterance emits: it is formed as soon as the new vector is here (while the arrivals of
   // the projection exchange travel), so that a step, once the label is known, only adds the
   // label's row of input sums.  rec[b]: this wave's 16 (unit, gate) sums for utterance b, value
-  // 4q + gate in lanes 4q + 16*(gate>>1) + 32*(gate&1) + 0..3.
+  // 4q + gate in lanes 4q + 16*(gate>>1) + 32*(gate&1) + 0..3.  A wave's fifth unit (upw = 20) has its
+  // four sums in rec5[b], gate v in lanes 4v .. 4v+3 of every row of 16.
+  auto recurrent_sums5 = [&](int ub) {
+    float part[4] = {0.f, 0.f, 0.f, 0.f};
+    const int u = wave + 16;
+    if (u < lp.upw)
+      for (int k = lane * 8; k < Hp; k += 512) {
+#pragma unroll
+        for (int gate = 0; gate < 4; ++gate) part[gate] = dot8(wl + ((size_t)u * 4 + gate) * Hp + k, ub * Hp + k, part[gate]);
+      }
+    return wave_sum4_scatter(part, lane);
+  };
   auto recurrent_sums = [&](int ub) {
     float part[16];   // [unit q][gate]
 #pragma unroll
@@ -281,9 +313,34 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     }
     return wave_sum16_scatter(part, lane);
   };
-  float rec[kLoopMaxB];
+  const bool five = lp.upw > 16;
+  float rec[kLoopMaxB], rec5[kLoopMaxB];
 #pragma unroll
-  for (int b = 0; b < kLoopMaxB; ++b) rec[b] = b < B ? recurrent_sums(b) : 0.f;
+  for (int b = 0; b < kLoopMaxB; ++b) {
+    rec[b] = b < B ? recurrent_sums(b) : 0.f;
+    rec5[b] = b < B && five ? recurrent_sums5(b) : 0.f;
+  }
+  // ---- where the workgroups sit: XCD numbers through a first barrier with device-wide stores
+  bool near = false;
+  {
+    unsigned xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    xcc &= 15u;
+    if (tid == 0) st_shared_u32(&lp.bar[(1 + g) * kLoopFlagStride + 1], xcc + 1u, false);
+    if (!loop_barrier(lp, g, false, passed, ls)) return;
+    if (tid < 64) {
+      bool same = true;
+      for (int w0 = 0; w0 < lp.G; w0 += 64) {
+        const int w = w0 + tid;
+        if (w < lp.G) same = same && __hip_atomic_load(&lp.bar[(1 + w) * kLoopFlagStride + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == xcc + 1u;
+      }
+      same = __all(same);
+      if (tid == 0) ls.near = same && lp.step > 1;
+    }
+    __syncthreads();
+    near = ls.near != 0;
+    if (g == 0 && tid == 0) lp.bar[1] = near ? 2u : 1u;   // for the host: which stores this launch used
+  }
 
   const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
   long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
@@ -371,7 +428,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       f32x16 acc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-      const bf16_t *zrow = zs + (size_t)(lane & 31) * zstride + k0 + (lane >> 5) * 8;
+      const bf16_t *zrow = zs + (size_t)min(lane & 31, lp.zrows - 1) * zstride + k0 + (lane >> 5) * 8;   // rows past the region repeat its last row; never looked at
 #pragma unroll
       for (int i = 0; i < kTinyPrefetch; ++i)
         if (i < nk) {
@@ -396,11 +453,11 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
         float o1[1], o2[1];
         RowTop2<16, 0>::run(k1, k2, lane, o1, o2);
         const int s0 = rowtop2_first_slot<16>(lane);
-        st_shared_f32x2(&parts[(size_t)acc_row(0, s0, lane) * c.nparts_tiny + g], make_float2(o1[0], o2[0]));
+        st_shared_f32x2(&parts[(size_t)acc_row(0, s0, lane) * c.nparts_tiny + g], make_float2(o1[0], o2[0]), near);
       }
     }
     const long long t2 = dbg ? wall_clock64() : 0;
-    if (!loop_barrier(lp, passed, ls)) return;            // exchange 1: every row's keys are in memory
+    if (!loop_barrier(lp, g, near, passed, ls)) return;   // exchange 1: every row's keys are in memory
     const long long t3 = dbg ? wall_clock64() : 0;
     // ---- the decisions, taken alike by every workgroup; workgroup 0 writes the outputs
     // With at most 64 parts per row and 4 rows per wave the decision only looks at the keys its
@@ -507,11 +564,29 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       if ((lane & 0x33) == 0 && u < lp.upw && unit < Hp) {
         const float cn = fg * cst[ub * lp.upw + u] + ig * gg;
         cst[ub * lp.upw + u] = cn;
-        st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit], og * tanhf(cn));
+        st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit], og * tanhf(cn), near);
+      }
+      if (five) {   // the wave's fifth unit: gate v on lanes 4v .. 4v+3
+        const int u5 = wave + 16, unit5 = unit0 + u5;
+        const bool ok5 = u5 < lp.upw && unit5 < Hp;
+        float4 a5 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok5) a5 = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok * 4 * Hp + unit5 * 4);
+        float tot5 = rec5[0];
+#pragma unroll
+        for (int b = 1; b < kLoopMaxB; ++b) tot5 = ub == b ? rec5[b] : tot5;
+        const int gate5 = (lane >> 2) & 3;
+        const float pre5 = tot5 + (gate5 == 0 ? a5.x : gate5 == 1 ? a5.y : gate5 == 2 ? a5.z : a5.w);
+        const float act5 = gate5 == 2 ? tanhf(pre5) : 1.f / (1.f + expf(-pre5));
+        const float i5 = __shfl(act5, 0, kWave), f5 = __shfl(act5, 4, kWave), g5 = __shfl(act5, 8, kWave), o5 = __shfl(act5, 12, kWave);
+        if (lane == 0 && ok5) {
+          const float cn = f5 * cst[ub * lp.upw + u5] + i5 * g5;
+          cst[ub * lp.upw + u5] = cn;
+          st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit5], o5 * tanhf(cn), near);
+        }
       }
     }
     const long long t5 = dbg ? wall_clock64() : 0;
-    if (!loop_barrier(lp, passed, ls)) return;            // exchange 2: the new hidden vectors
+    if (!loop_barrier(lp, g, near, passed, ls)) return;   // exchange 2: the new hidden vectors
     const long long t6 = dbg ? wall_clock64() : 0;
     for (int r = 0; r < n_emit; ++r) {
       const int ub = ls.emit_ub[r];
@@ -533,16 +608,16 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
         }
         const float tot = wave_sum4_scatter(part, lane);   // lanes 4q .. 4q+3 of every row of 16 hold row q's sum
         const int jl = wave + 4 * (q0 + ((lane >> 2) & 3)), j = prow0 + jl;
-        if ((lane & 0x33) == 0 && jl < lp.ppw && j < Hj) st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], tot + m.b_pred[j]);
+        if ((lane & 0x33) == 0 && jl < lp.ppw && j < Hj) st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], tot + m.b_pred[j], near);
       }
     }
     const long long t7 = dbg ? wall_clock64() : 0;
-    loop_arrive(lp, passed);                              // exchange 3: the new projections ...
+    loop_arrive(lp, g, near, passed);                     // exchange 3: the new projections ...
     for (int r = 0; r < n_emit; ++r) {                    // ... and, while the arrivals travel, the next step's recurrent sums
       const int ub = ls.emit_ub[r];
-      const float v = recurrent_sums(ub);
+      const float v = recurrent_sums(ub), v5 = five ? recurrent_sums5(ub) : 0.f;
 #pragma unroll
-      for (int b = 0; b < kLoopMaxB; ++b) rec[b] = ub == b ? v : rec[b];
+      for (int b = 0; b < kLoopMaxB; ++b) { rec[b] = ub == b ? v : rec[b]; rec5[b] = ub == b ? v5 : rec5[b]; }
     }
     if (!loop_wait(lp, passed, ls)) return;
     const long long t8 = dbg ? wall_clock64() : 0;

@@ -159,30 +159,42 @@ def test_prediction_network_on_mfma_tiles(torch_cuda, name, B, lo, hi, W):
     m.close()
 
 
-@pytest.mark.parametrize("name,B,lo,hi,W", [("greedy_b1", 1, 150, 150, 16), ("greedy_b1", 1, 130, 130, 1), ("greedy_b1", 1, 120, 120, 32),
-                                            ("greedy_b1", 1, 90, 90, 5), ("greedy_b1", 2, 60, 120, 16), ("batch32", 2, 50, 90, 3)])
-def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W):
+@pytest.mark.parametrize("name,B,lo,hi,W,near", [("greedy_b1", 1, 150, 150, 16, True), ("greedy_b1", 1, 130, 130, 1, True),
+                                                 ("greedy_b1", 1, 120, 120, 32, False), ("greedy_b1", 1, 90, 90, 5, True),
+                                                 ("greedy_b1", 2, 60, 120, 16, False), ("batch32", 2, 50, 90, 3, False)])
+def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W, near):
     """One or two utterances with at most 32 window rows decode in one resident kernel whose
     workgroups exchange keys, hidden vectors and projections behind grid barriers; it must agree
     with the oracle and, label for label and counter for counter, with the graph of per-step
-    kernels (loop_kernel = 0)."""
+    kernels (loop_kernel = 0).  Both placements of its workgroups are run: 32 on one XCD, exchanging
+    through its L2 (shapes marked `near`: their larger weight slices and the window rows fit LDS),
+    and spread over the chip; the library reports which one a call used."""
     cfg = wi.scaled(wi.CONFIGS[name], B, lo, hi)
     m, o, _ = load(cfg)
     enc, lens = wi.make_batch(cfg)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     res, stats = [], []
-    for lk in (1, 0):
+    for lk, one in ((1, 1), (1, 0), (0, 1)):
         m.set_option("loop_kernel", lk)
+        m.set_option("loop_one_xcd", one)
         toks, frs = m.decode(d_enc, d_len, W, cfg.S)
+        g, one_l2 = m.loop_info()
+        if lk == 0:
+            assert (g, one_l2) == (0, False)
+        elif one and near:
+            assert (g, one_l2) == (32, True)     # the placement the kernel expects is what this machine gives
+        else:
+            assert g == 40 and not one_l2
         check_outputs(cfg, lens, toks, frs)
         assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
         st = m.stats()
         res.append((toks, frs))
         stats.append((st.iterations, st.windows, st.rows, st.useful_rows, st.labels, st.forced_advances,
                       list(st.jump_hist)))
-    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], res[1][0]))
-    assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], res[1][1]))
-    assert stats[0] == stats[1]
+    for other in res[1:]:
+        assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], other[0]))
+        assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], other[1]))
+    assert stats[0] == stats[1] == stats[2]
     m.close()
 
 

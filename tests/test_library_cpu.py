@@ -59,6 +59,7 @@ def test_argument_errors_without_gpu(lib):
     assert lib.wind_debug_joint_keys(None, None, None, 1, 1, 1, None, C.byref(k), C.byref(k), None) == binding.WIND_ERR_ARG
     assert lib.wind_get_joint_launches(None, None, None, 0, None) == binding.WIND_ERR_ARG
     assert lib.wind_get_call_times(None, None, None) == binding.WIND_ERR_ARG
+    assert lib.wind_get_loop_info(None, None, None) == binding.WIND_ERR_ARG
     assert lib.wind_free(None) == binding.WIND_OK
 
 
