@@ -535,14 +535,15 @@ int fetch_stats(wind_model *m, hipStream_t s) {
 // Shape of the resident loop kernel for this call, or false if the call does not qualify: bf16, one
 // LSTM layer, at most 2 utterances and 32 window rows, every workgroup's weight slice within LDS,
 // at most one workgroup per CU.  First choice: at most 32 workgroups, which fit the CUs of one XCD
-// and then exchange through its L2 (a wave takes up to five LSTM units; window rows limited to 16 so
-// that the larger weight slices still fit LDS); otherwise 16 units per workgroup, spread over the chip.
+// and then exchange through its L2 (window rows limited to 16 so that the larger weight slices
+// still fit LDS); otherwise 16 units per workgroup, spread over the chip.
 bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *smem) {
   const ModelDev &d = m->dev;
   if (m->dtype != WIND_BF16 || d.L != 1 || B > kLoopMaxB || B * W > kLoopRows || d.Hj > kTinyMaxHj) return false;
   if (!m->opt_loop_kernel || m->opt_profile || !m->opt_graph || m->opt_host_sync) return false;
   const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
   if (nparts_tiny * 8 > (d.Hj + 8) * 2) return false;              // a row's keys fit where its hidden vector was
+  if (d.Hp % 64 || d.Hj % 64) return false;                        // K of every matrix-core product splits over four waves in steps of 16
   const int widest = d.Hp > d.Hj ? d.Hp : d.Hj;
   for (int near = m->opt_loop_one_xcd ? 1 : 0; near >= 0; --near) {
     int G = near ? kLoopNearG : (widest + 15) / 16;
@@ -554,7 +555,7 @@ bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *s
     lp->upw = ((d.Hp + G - 1) / G + 3) / 4 * 4;
     lp->ppw = ((d.Hj + G - 1) / G + 3) / 4 * 4;
     *smem = loop_smem_bytes(d.Hp, d.Hj, B, lp->upw, lp->ppw, lp->zrows);
-    if (lp->upw > 20 || lp->ppw > 32) continue;                      // a wave steps at most five units
+    if (lp->upw * 4 + lp->ppw > kLoopProdRows) continue;             // gate rows and projection rows go through the matrix cores in one pass
     if (*smem + 6144 <= 160 * 1024 && *smem <= kLoopMaxSmem) return true;   // room for the kernel's static LDS
   }
   return false;

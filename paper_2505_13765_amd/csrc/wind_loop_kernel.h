@@ -44,6 +44,7 @@ constexpr int kLoopMaxB = 2;
 constexpr int kLoopNearG = 32;                 // CUs of one XCD
 constexpr size_t kLoopMaxSmem = 154 * 1024;    // dynamic LDS the kernel may be launched with
 constexpr int kLoopRows = 32;
+constexpr int kLoopProdRows = 128;   // most weight rows (gate rows + projection rows) of one workgroup
 
 struct LoopShared {
   int4 nslot[kLoopMaxB];
@@ -52,8 +53,9 @@ struct LoopShared {
   int n_act, n_emit, ok, near;
 };
 
-// LDS: [wl: upw*4 rows of Hp bf16][wp: ppw rows of Hp bf16][zs: zrows rows of Hj+8 bf16, at least 16 KB][hhi, hlo: B*Hp bf16 each]
-//      [pfull: B*Hj f32][cst: B*upw f32]
+// LDS: [wl: upw*4 rows of Hp+8 bf16][wp: ppw rows of Hp+8 bf16][zs: zrows rows of Hj+8 bf16, at least 16 KB]
+//      [hhi, hlo: B*Hp bf16 each][pfull: B*Hj f32][cst: B*upw f32][recs: B*upw*4 f32]
+// (rows padded by 16 bytes: 32 lanes that read the same k of 32 consecutive rows then hit different banks)
 // bf16 elements of the window-row region zs.  The region also takes the K-split partial sums of the MFMA
 // phase (4 waves x 16 registers x 64 lanes of fp32 = 16 KB), which is the larger of the two for Hj < 248.
 __host__ __device__ inline size_t loop_z_elems(int Hj, int zrows) {
@@ -61,7 +63,7 @@ __host__ __device__ inline size_t loop_z_elems(int Hj, int zrows) {
   return z > 8192 ? z : 8192;
 }
 __host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw, int zrows) {
-  return (size_t)upw * 4 * Hp * 2 + (size_t)ppw * Hp * 2 + loop_z_elems(Hj, zrows) * 2 + (size_t)B * Hp * 4 +
+  return (size_t)(upw * 4 + ppw) * (Hp + 8) * 2 + (size_t)B * upw * 16 + loop_z_elems(Hj, zrows) * 2 + (size_t)B * Hp * 4 +
          (size_t)B * Hj * 4 + (size_t)B * upw * 4;
 }
 
@@ -137,29 +139,12 @@ __device__ __forceinline__ bool loop_barrier(const LoopDev &lp, int g, bool near
   return loop_wait(lp, passed, ls);
 }
 
-// Sums of 16 / 8 / 4 per-lane values over the wave with a halving exchange: each step a lane keeps
-// half of its values and adds the partner's copies of them, until one value is left, which the
-// last steps sum over the lanes that still hold parts of it.  The steps that carry the most values
-// pair lanes inside a row of 16 with DPP permutations (row mirror, half mirror); the lane bit that
-// decides which half is kept gives the value's index one bit per step:
-//   16 values: index = b3 b2 b4 b5 (lane bits), i.e. value v ends up, complete, in the four lanes
-//              32*(v&1) + 16*((v>>1)&1) + 4*(v>>2) + 0..3
-//    8 values: index = b3 b2 b4; lanes 16*(v&1) + 4*(v>>1) + 0..3 and the same + 32
-//    4 values: index = b3 b2; lanes 4*v + 0..3 of every row
-__device__ __forceinline__ float wave_sum16_scatter(const float (&v)[16], int lane) {
-  float a[8], b[4], c2[2];
-  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0, u4 = (lane & 16) != 0, u5 = (lane & 32) != 0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) a[i] = (u3 ? v[i + 8] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 8]);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) b[i] = (u2 ? a[i + 4] : a[i]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[i] : a[i + 4]);
-#pragma unroll
-  for (int i = 0; i < 2; ++i) c2[i] = (u4 ? b[i + 2] : b[i]) + __shfl_xor(u4 ? b[i] : b[i + 2], 16, kWave);
-  float d = (u5 ? c2[1] : c2[0]) + __shfl_xor(u5 ? c2[0] : c2[1], 32, kWave);
-  d += dpp_f32<kDppQuadXor2>(d);
-  d += dpp_f32<kDppQuadXor1>(d);
-  return d;
-}
+// Sums of 8 per-lane values over the wave with a halving exchange: each step a lane keeps half of
+// its values and adds the partner's copies of them, until one value is left, which the last steps
+// sum over the lanes that still hold parts of it.  The steps that carry the most values pair lanes
+// inside a row of 16 with DPP permutations (row mirror, half mirror); the lane bit that decides
+// which half is kept gives the value's index one bit per step: index = b3 b2 b4 (lane bits), i.e.
+// value v ends up, complete, in lanes 16*(v&1) + 4*(v>>1) + 0..3 and the same + 32.
 __device__ __forceinline__ float wave_sum8_scatter(const float (&v)[8], int lane) {
   float a[4], b[2];
   const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0, u4 = (lane & 16) != 0;
@@ -173,17 +158,49 @@ __device__ __forceinline__ float wave_sum8_scatter(const float (&v)[8], int lane
   d += dpp_f32<kDppQuadXor1>(d);
   return d;
 }
-__device__ __forceinline__ float wave_sum4_scatter(const float (&v)[4], int lane) {
-  float a[2];
-  const bool u3 = (lane & 8) != 0, u2 = (lane & 4) != 0;
+
+// One wave's share of (32 * NBLK weight rows) x (hidden vectors) on the matrix cores: nks steps of 16 along
+// K from hsrc (first operand: this lane's row of hi / lo vectors) and wsrc[blk] (second operand: this
+// lane's weight row of block blk).  Lane n < 32 then holds row n's sums against first-operand rows
+// 0..3 in registers 0..3; hi + lo per utterance go to red_w[row][b].
+template <int NBLK>
+__device__ __forceinline__ void loop_rows_times_h(const bf16_t *hsrc, const bf16_t *const (&wsrc)[4], int nks, float *red_w,
+                                                  int lane, int n_wrows, int B) {
+  f32x16 acc[NBLK];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) a[i] = (u3 ? v[i + 2] : v[i]) + dpp_f32<kDppRowMirror>(u3 ? v[i] : v[i + 2]);
-  float d = (u2 ? a[1] : a[0]) + dpp_f32<kDppRowHalfMirror>(u2 ? a[0] : a[1]);
-  d += __shfl_xor(d, 16, kWave);
-  d += __shfl_xor(d, 32, kWave);
-  d += dpp_f32<kDppQuadXor2>(d);
-  d += dpp_f32<kDppQuadXor1>(d);
-  return d;
+  for (int blk = 0; blk < NBLK; ++blk) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[blk][r] = 0.f;
+  }
+  // operands one step ahead of the products, so that an LDS read's latency hides behind the previous step
+  bf16x8 hv = *reinterpret_cast<const bf16x8 *>(hsrc), wv[NBLK];
+#pragma unroll
+  for (int blk = 0; blk < NBLK; ++blk) wv[blk] = *reinterpret_cast<const bf16x8 *>(wsrc[blk]);
+  for (int i = 0; i < nks; ++i) {
+    const int nx = min(i + 1, nks - 1) * 16;   // the last step reads its own operands again
+    const bf16x8 hn = *reinterpret_cast<const bf16x8 *>(hsrc + nx);
+    bf16x8 wn[NBLK];
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) wn[blk] = *reinterpret_cast<const bf16x8 *>(wsrc[blk] + nx);
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hv, wv[blk], acc[blk], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1 + NBLK, 0);   // the reads of the next step ...
+    __builtin_amdgcn_sched_group_barrier(0x008, NBLK, 0);       // ... then this step's products
+    hv = hn;
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) wv[blk] = wn[blk];
+  }
+  if (lane < 32) {
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) {
+      const int row = blk * 32 + lane;
+      if (row < n_wrows) {
+#pragma unroll
+        for (int b = 0; b < kLoopMaxB; ++b)
+          if (b < B) red_w[(size_t)row * kLoopMaxB + b] = acc[blk][2 * b] + acc[blk][2 * b + 1];
+      }
+    }
+  }
 }
 
 __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, LoopDev lp) {
@@ -195,9 +212,10 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = blockIdx.x / lp.step;
   const int Hj = m.Hj, Hp = m.Hp, W = c.W, B = c.B;
   const int zstride = Hj + 8;
+  const int wstride = Hp + 8, nr = lp.upw * 4;   // row stride of the weights in LDS; (unit, gate) rows of this workgroup
   bf16_t *wl = reinterpret_cast<bf16_t *>(smem_raw);
-  bf16_t *wp = wl + (size_t)lp.upw * 4 * Hp;
-  bf16_t *zs = wp + (size_t)lp.ppw * Hp;
+  bf16_t *wp = wl + (size_t)nr * wstride;
+  bf16_t *zs = wp + (size_t)lp.ppw * wstride;
   // the hidden vectors as bf16 hi + lo (hi = RNE(h), lo = RNE(h - hi), 16 mantissa bits together): the dot
   // products with the bf16 weights then take one packed instruction per pair and part, with nothing to unpack
   bf16_t *hhi = zs + loop_z_elems(Hj, lp.zrows), *hlo = hhi + (size_t)B * Hp;
@@ -207,30 +225,23 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     *reinterpret_cast<uint32_t *>(hhi + i) = hb;
     *reinterpret_cast<uint32_t *>(hlo + i) = pack_bf16x2(v.x - __uint_as_float(hb << 16), v.y - __uint_as_float(hb & 0xFFFF0000u));
   };
-  // sum over this lane's eight k of w[k] * (hi[k] + lo[k]), on top of acc
-  auto dot8 = [&](const bf16_t *wrow, int hofs, float acc) {
-    const u32x4 wv = *reinterpret_cast<const u32x4 *>(wrow);
-    const u32x4 a = *reinterpret_cast<const u32x4 *>(hhi + hofs), b = *reinterpret_cast<const u32x4 *>(hlo + hofs);
-    acc = dot2_bf16(wv.x, a.x, acc); acc = dot2_bf16(wv.y, a.y, acc); acc = dot2_bf16(wv.z, a.z, acc); acc = dot2_bf16(wv.w, a.w, acc);
-    acc = dot2_bf16(wv.x, b.x, acc); acc = dot2_bf16(wv.y, b.y, acc); acc = dot2_bf16(wv.z, b.z, acc); acc = dot2_bf16(wv.w, b.w, acc);
-    return acc;
-  };
   float *cst = pfull + (size_t)B * Hj;
+  float *recs = cst + (size_t)B * lp.upw;   // [B][nr] recurrent halves of the gate sums, see below
 
   // ---- once: this workgroup's weights, the state after the start-token step, the slot table
   const int unit0 = g * lp.upw, prow0 = g * lp.ppw;
-  for (int i = tid * 8; i < lp.upw * 4 * Hp; i += 256 * 8) {
+  for (int i = tid * 8; i < nr * Hp; i += 256 * 8) {
     const int row = i / Hp, k = i - row * Hp;           // row = 4 * local unit + gate
     u32x4 v = u32x4{0u, 0u, 0u, 0u};
     if (unit0 + (row >> 2) < Hp)
       v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.w_cat[0]) + ((size_t)unit0 * 4 + row) * Hp + k);
-    *reinterpret_cast<u32x4 *>(wl + i) = v;
+    *reinterpret_cast<u32x4 *>(wl + (size_t)row * wstride + k) = v;
   }
   for (int i = tid * 8; i < lp.ppw * Hp; i += 256 * 8) {
     const int row = i / Hp, k = i - row * Hp;
     u32x4 v = u32x4{0u, 0u, 0u, 0u};
     if (prow0 + row < Hj) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16_t *>(m.w_pred) + (size_t)(prow0 + row) * Hp + k);
-    *reinterpret_cast<u32x4 *>(wp + i) = v;
+    *reinterpret_cast<u32x4 *>(wp + (size_t)row * wstride + k) = v;
   }
   for (int i = tid * 2; i < B * Hp; i += 512) put_h2(i, *reinterpret_cast<const float2 *>(c.h + i));
   for (int i = tid; i < B * Hj; i += 256) pfull[i] = c.p[i];
@@ -281,45 +292,44 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
   unsigned passed = 0;
   __syncthreads();
+  // Products of this workgroup's weight rows with the hidden vectors, on the matrix cores: sum over k of
+  // w[row][k] * (hi[b][k] + lo[b][k]) for n_wrows rows of bf16 weights in LDS and every utterance b.  The
+  // utterances' hi and lo vectors are rows 2b and 2b + 1 of the first operand (its other rows are zero),
+  // 32 weight rows the second, so lane n < 32 ends up with its weight row's sums in its first registers;
+  // K is split over the four waves, whose partial sums go to red[wave][row][b] (the window-row region,
+  // which is free whenever this runs).  Up to 128 rows: four independent accumulator blocks in flight.
+  // The projection rows follow the gate rows in LDS with the same stride, so one pass can cover both.
+  float *red = reinterpret_cast<float *>(zs);
+  auto red_sum = [&](int row, int b) {
+    float v = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) v += red[((size_t)w2 * kLoopProdRows + row) * kLoopMaxB + b];
+    return v;
+  };
+  auto weight_rows_times_h = [&](const bf16_t *wbase, int n_wrows) {
+    const int kq4 = Hp >> 2, kbeg = wave * kq4, nks = kq4 >> 4;
+    const int mrow = lane & 31, kh = (lane >> 5) * 8;
+    // rows of the first operand past the utterances' repeat the first: their sums are never looked at
+    const bf16_t *hsrc = ((mrow & 1) ? hlo : hhi) + (size_t)(mrow < 2 * B ? (mrow >> 1) : 0) * Hp + kbeg + kh;
+    const bf16_t *wsrc[4];
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)   // weight rows past the last repeat it, likewise
+      wsrc[blk] = wbase + (size_t)min(blk * 32 + mrow, n_wrows - 1) * wstride + kbeg + kh;
+    float *red_w = red + (size_t)wave * kLoopProdRows * kLoopMaxB;
+    if (n_wrows <= 32) loop_rows_times_h<1>(hsrc, wsrc, nks, red_w, lane, n_wrows, B);
+    else if (n_wrows <= 64) loop_rows_times_h<2>(hsrc, wsrc, nks, red_w, lane, n_wrows, B);
+    else if (n_wrows <= 96) loop_rows_times_h<3>(hsrc, wsrc, nks, red_w, lane, n_wrows, B);
+    else loop_rows_times_h<4>(hsrc, wsrc, nks, red_w, lane, n_wrows, B);
+  };
   // The recurrent half of the gate sums, W_hh h, depends on the hidden vector only, which changes
   // when its utterance emits: it is formed as soon as the new vector is here (while the arrivals of
   // the projection exchange travel), so that a step, once the label is known, only adds the
-  // label's row of input sums.  rec[b]: this wave's 16 (unit, gate) sums for utterance b, value
-  // 4q + gate in lanes 4q + 16*(gate>>1) + 32*(gate&1) + 0..3.  A wave's fifth unit (upw = 20) has its
-  // four sums in rec5[b], gate v in lanes 4v .. 4v+3 of every row of 16.
-  auto recurrent_sums5 = [&](int ub) {
-    float part[4] = {0.f, 0.f, 0.f, 0.f};
-    const int u = wave + 16;
-    if (u < lp.upw)
-      for (int k = lane * 8; k < Hp; k += 512) {
-#pragma unroll
-        for (int gate = 0; gate < 4; ++gate) part[gate] = dot8(wl + ((size_t)u * 4 + gate) * Hp + k, ub * Hp + k, part[gate]);
-      }
-    return wave_sum4_scatter(part, lane);
-  };
-  auto recurrent_sums = [&](int ub) {
-    float part[16];   // [unit q][gate]
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int u = wave + 4 * q;
-#pragma unroll
-      for (int gate = 0; gate < 4; ++gate) part[4 * q + gate] = 0.f;
-      if (u >= lp.upw) continue;
-      for (int k = lane * 8; k < Hp; k += 512) {
-#pragma unroll
-        for (int gate = 0; gate < 4; ++gate)
-          part[4 * q + gate] = dot8(wl + ((size_t)u * 4 + gate) * Hp + k, ub * Hp + k, part[4 * q + gate]);
-      }
-    }
-    return wave_sum16_scatter(part, lane);
-  };
-  const bool five = lp.upw > 16;
-  float rec[kLoopMaxB], rec5[kLoopMaxB];
-#pragma unroll
-  for (int b = 0; b < kLoopMaxB; ++b) {
-    rec[b] = b < B ? recurrent_sums(b) : 0.f;
-    rec5[b] = b < B && five ? recurrent_sums5(b) : 0.f;
-  }
+  // label's row of input sums.  recs[b][4 * local unit + gate].
+  weight_rows_times_h(wl, nr);
+  __syncthreads();
+  if (tid < nr)
+    for (int b = 0; b < B; ++b) recs[b * nr + tid] = red_sum(tid, b);
+  __syncthreads();
   // ---- where the workgroups sit: XCD numbers through a first barrier with device-wide stores
   bool near = false;
   {
@@ -535,53 +545,22 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     if (dbg) { tsum[0] += t1 - t0; tsum[1] += t2 - t1; tsum[2] += t3 - t2; tsum[3] += t4 - t3; ++n_it; }
     if (n_emit == 0 || na == 0) continue;
     // ---- one LSTM step for the utterances that emitted: this workgroup's units, weights from LDS
+    // thread 4u + gate: that gate of the workgroup's unit u (the label's input sums are one coalesced read)
     for (int r = 0; r < n_emit; ++r) {
       const int ub = ls.emit_ub[r], tok = ls.emit_tok[r];
-      // the label's input gate sums of this wave's (at most four) units: one round trip for all
-      float4 addq[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int unit = unit0 + wave + 4 * q;
-        addq[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (wave + 4 * q < lp.upw && unit < Hp) addq[q] = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok * 4 * Hp + unit * 4);
-      }
-      // the recurrent sums were formed when this utterance's hidden vector last changed: every gate's
-      // nonlinearity runs on its own lanes, then lane 4q gathers its unit's four
-      float tot = rec[0];
-#pragma unroll
-      for (int b = 1; b < kLoopMaxB; ++b) tot = ub == b ? rec[b] : tot;
-      const int q = (lane >> 2) & 3, gate = ((lane >> 4) & 1) * 2 + (lane >> 5);
-      float4 aq = addq[0];
-      if (q == 1) aq = addq[1];
-      if (q == 2) aq = addq[2];
-      if (q == 3) aq = addq[3];
-      const float pre = tot + (gate == 0 ? aq.x : gate == 1 ? aq.y : gate == 2 ? aq.z : aq.w);
-      const float act = gate == 2 ? tanhf(pre) : 1.f / (1.f + expf(-pre));
-      const int base = lane & 12;
-      const float ig = __shfl(act, base, kWave), fg = __shfl(act, base + 32, kWave);
-      const float gg = __shfl(act, base + 16, kWave), og = __shfl(act, base + 48, kWave);
-      const int u = wave + 4 * q, unit = unit0 + u;
-      if ((lane & 0x33) == 0 && u < lp.upw && unit < Hp) {
-        const float cn = fg * cst[ub * lp.upw + u] + ig * gg;
-        cst[ub * lp.upw + u] = cn;
-        st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit], og * tanhf(cn), near);
-      }
-      if (five) {   // the wave's fifth unit: gate v on lanes 4v .. 4v+3
-        const int u5 = wave + 16, unit5 = unit0 + u5;
-        const bool ok5 = u5 < lp.upw && unit5 < Hp;
-        float4 a5 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ok5) a5 = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok * 4 * Hp + unit5 * 4);
-        float tot5 = rec5[0];
-#pragma unroll
-        for (int b = 1; b < kLoopMaxB; ++b) tot5 = ub == b ? rec5[b] : tot5;
-        const int gate5 = (lane >> 2) & 3;
-        const float pre5 = tot5 + (gate5 == 0 ? a5.x : gate5 == 1 ? a5.y : gate5 == 2 ? a5.z : a5.w);
-        const float act5 = gate5 == 2 ? tanhf(pre5) : 1.f / (1.f + expf(-pre5));
-        const float i5 = __shfl(act5, 0, kWave), f5 = __shfl(act5, 4, kWave), g5 = __shfl(act5, 8, kWave), o5 = __shfl(act5, 12, kWave);
-        if (lane == 0 && ok5) {
-          const float cn = f5 * cst[ub * lp.upw + u5] + i5 * g5;
-          cst[ub * lp.upw + u5] = cn;
-          st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit5], o5 * tanhf(cn), near);
+      if (tid < nr) {
+        const int ul = tid >> 2, gate = tid & 3, unit = unit0 + ul;
+        const bool ok = unit < Hp;
+        float pre = 0.f;
+        if (ok) pre = recs[ub * nr + tid] + m.emb_gates[(size_t)tok * 4 * Hp + (size_t)unit0 * 4 + tid];
+        const float act = gate == 2 ? tanhf(pre) : 1.f / (1.f + expf(-pre));
+        const int base = lane & ~3;
+        const float ig = __shfl(act, base, kWave), fg = __shfl(act, base + 1, kWave);
+        const float gg = __shfl(act, base + 2, kWave), og = __shfl(act, base + 3, kWave);
+        if (gate == 0 && ok) {
+          const float cn = fg * cst[ub * lp.upw + ul] + ig * gg;
+          cst[ub * lp.upw + ul] = cn;
+          st_shared_f32(&lp.h_x[(size_t)ub * Hp + unit], og * tanhf(cn), near);
         }
       }
     }
@@ -593,32 +572,25 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       for (int k = tid * 2; k < Hp; k += 512) put_h2(ub * Hp + k, ld_shared_f32x2(reinterpret_cast<const float2 *>(&lp.h_x[(size_t)ub * Hp + k])));
     }
     __syncthreads();
-    // ---- this workgroup's rows of the prediction projection
-    for (int r = 0; r < n_emit; ++r) {
-      const int ub = ls.emit_ub[r];
-      // this wave's rows jl = wave + 4q, q < ppw / 4, four at a time
-      for (int q0 = 0; q0 * 4 < lp.ppw; q0 += 4) {
-        float part[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int jl = wave + 4 * (q0 + q);
-          part[q] = 0.f;
-          if (jl >= lp.ppw) continue;
-          for (int k = lane * 8; k < Hp; k += 512) part[q] = dot8(wp + (size_t)jl * Hp + k, ub * Hp + k, part[q]);
-        }
-        const float tot = wave_sum4_scatter(part, lane);   // lanes 4q .. 4q+3 of every row of 16 hold row q's sum
-        const int jl = wave + 4 * (q0 + ((lane >> 2) & 3)), j = prow0 + jl;
-        if ((lane & 0x33) == 0 && jl < lp.ppw && j < Hj) st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], tot + m.b_pred[j], near);
+    // ---- this workgroup's rows of the prediction projection, and in the same pass over the new vectors
+    // the recurrent sums of the next step (rows nr .. nr + ppw - 1 and 0 .. nr - 1 of the weights in LDS)
+    weight_rows_times_h(wl, nr + lp.ppw);
+    __syncthreads();
+    if (tid < lp.ppw && prow0 + tid < Hj) {
+      const int j = prow0 + tid;
+      const float bj = m.b_pred[j];
+      for (int r = 0; r < n_emit; ++r) {
+        const int ub = ls.emit_ub[r];
+        st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], red_sum(nr + tid, ub) + bj, near);
       }
     }
     const long long t7 = dbg ? wall_clock64() : 0;
     loop_arrive(lp, g, near, passed);                     // exchange 3: the new projections ...
-    for (int r = 0; r < n_emit; ++r) {                    // ... and, while the arrivals travel, the next step's recurrent sums
-      const int ub = ls.emit_ub[r];
-      const float v = recurrent_sums(ub), v5 = five ? recurrent_sums5(ub) : 0.f;
-#pragma unroll
-      for (int b = 0; b < kLoopMaxB; ++b) { rec[b] = ub == b ? v : rec[b]; rec5[b] = ub == b ? v5 : rec5[b]; }
-    }
+    if (tid < nr)                                         // ... and, while the arrivals travel, the recurrent sums are put by
+      for (int r = 0; r < n_emit; ++r) {
+        const int ub = ls.emit_ub[r];
+        recs[ub * nr + tid] = red_sum(tid, ub);
+      }
     if (!loop_wait(lp, passed, ls)) return;
     const long long t8 = dbg ? wall_clock64() : 0;
     for (int r = 0; r < n_emit; ++r) {
