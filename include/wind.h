@@ -349,6 +349,9 @@ int wind_get_loop_info(wind_model *m, int *workgroups, int *one_l2);
  *   "loop_kernel"  1 (default): decodes of one or two utterances with at most 32 window rows (bf16, one
  *             LSTM layer, weights that fit the chip's LDS) run the whole loop as one resident kernel
  *             whose workgroups meet at grid barriers; 0: always the graph of per-step kernels
+ *   "loop_fused"  1 (default): with at most 16 window rows and a joint hidden size that is a multiple of 128,
+ *             at most 640, that kernel builds the window rows directly as matrix-core operands; 0: it
+ *             stages them in LDS (the form for every other shape)
  *   "loop_one_xcd"  1 (default): where 32 workgroups suffice for that kernel (and the window rows number
  *             at most 16), they are placed on the CUs of one XCD and exchange through its L2, which
  *             shortens every grid barrier; the kernel checks the placement itself and falls back to

@@ -130,6 +130,7 @@ struct wind_model {
   int opt_pred_mfma_min_batch = kPredMfmaMinBatch;
   int opt_loop_kernel = 1;
   int opt_loop_one_xcd = 1;
+  int opt_loop_fused = 1;
   long long opt_loop_spin_limit = 1ll << 21;
   int opt_debug_stamps = 0;
   int opt_lstm_rec = 1;
@@ -545,13 +546,15 @@ bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *s
   if (nparts_tiny * 8 > (d.Hj + 8) * 2) return false;              // a row's keys fit where its hidden vector was
   if (d.Hp % 64 || d.Hj % 64) return false;                        // K of every matrix-core product splits over four waves in steps of 16
   const int widest = d.Hp > d.Hj ? d.Hp : d.Hj;
+  // at most 16 window rows and a joint width in steps of 128: the rows go straight into matrix-core operands
+  const bool fused = m->opt_loop_fused && B * W <= 16 && d.Hj % 128 == 0 && d.Hj <= 128 * kFusedSteps;
   for (int near = m->opt_loop_one_xcd ? 1 : 0; near >= 0; --near) {
     int G = near ? kLoopNearG : (widest + 15) / 16;
     if (G < nparts_tiny) { if (near) continue; G = nparts_tiny; }
     if (G > 256) return false;
     lp->G = G;
     lp->step = near ? 8 : 1;
-    lp->zrows = near && B * W <= 16 ? 16 : kLoopRows;
+    lp->zrows = fused ? 0 : near && B * W <= 16 ? 16 : kLoopRows;
     lp->upw = ((d.Hp + G - 1) / G + 3) / 4 * 4;
     lp->ppw = ((d.Hj + G - 1) / G + 3) / 4 * 4;
     *smem = loop_smem_bytes(d.Hp, d.Hj, B, lp->upw, lp->ppw, lp->zrows);
@@ -618,7 +621,8 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
       const int bar_ints = (1 + lp.G) * kLoopFlagStride;
       fill_int_kernel<<<(unsigned)((bar_ints + 255) / 256), 256, 0, s>>>((int *)lp.bar, bar_ints, 0);
     }
-    wind_loop_kernel<<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);
+    if (lp.zrows == 0) wind_loop_kernel<true><<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);
+    else wind_loop_kernel<false><<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);
     rc = check_launch("resident loop");
     if (rc) return rc;
     HIP_TRY(hipEventRecord(m->ev_call[2], s));
@@ -840,7 +844,9 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   if (rc == WIND_OK) {
     hipError_t e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)wind_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLoopMaxSmem);
+      e = hipFuncSetAttribute((const void *)wind_loop_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLoopMaxSmem);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)wind_loop_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLoopMaxSmem);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);
@@ -1072,6 +1078,10 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   }
   if (!std::strcmp(key, "loop_kernel")) {
     m->opt_loop_kernel = value != 0;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "loop_fused")) {
+    m->opt_loop_fused = value != 0;
     return WIND_OK;
   }
   if (!std::strcmp(key, "loop_one_xcd")) {

@@ -36,7 +36,7 @@ struct LoopDev {
   float2 *parts_x;     // [2][32][nparts_tiny] keys, by iteration parity
   int G, upw, ppw;     // workgroups; LSTM units and W_pred rows per workgroup (multiples of 4)
   int step;            // launch index of workgroup g is g * step (8: all on one XCD, 1: spread over the chip)
-  int zrows;           // rows of the window-row region of LDS (16 or 32)
+  int zrows;           // rows of the window-row region of LDS (16 or 32; 0: none, the rows go straight into matrix-core operands)
   int max_iters;       // more iterations than any decode of this call can take
   unsigned spin_limit;
 };
@@ -54,7 +54,7 @@ struct LoopShared {
 };
 
 // LDS: [wl: upw*4 rows of Hp+8 bf16][wp: ppw rows of Hp+8 bf16][zs: zrows rows of Hj+8 bf16, at least 16 KB]
-//      [hhi, hlo: B*Hp bf16 each][pfull: B*Hj f32][cst: B*upw f32][recs: B*upw*4 f32]
+//      [hhi, hlo: B*Hp bf16 each][pfull: B*Hj f32][cst: B*upw f32][recs: B*upw*4 f32][wbl: Hj f32, fused form only]
 // (rows padded by 16 bytes: 32 lanes that read the same k of 32 consecutive rows then hit different banks)
 // bf16 elements of the window-row region zs.  The region also takes the K-split partial sums of the MFMA
 // phase (4 waves x 16 registers x 64 lanes of fp32 = 16 KB), which is the larger of the two for Hj < 248.
@@ -62,8 +62,11 @@ __host__ __device__ inline size_t loop_z_elems(int Hj, int zrows) {
   const size_t z = (size_t)zrows * (Hj + 8);
   return z > 8192 ? z : 8192;
 }
+// the fused form of the window phase (zrows == 0) keeps the blank column of W_out in LDS as fp32
+__host__ __device__ inline size_t loop_wblank_elems(int Hj, int zrows) { return zrows == 0 ? (size_t)Hj : 0; }
+constexpr int kFusedSteps = 5;   // K steps of 32 per wave in that form: Hj <= 4 * 32 * 5
 __host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw, int zrows) {
-  return (size_t)(upw * 4 + ppw) * (Hp + 8) * 2 + (size_t)B * upw * 16 + loop_z_elems(Hj, zrows) * 2 + (size_t)B * Hp * 4 +
+  return (size_t)(upw * 4 + ppw) * (Hp + 8) * 2 + (size_t)B * upw * 16 + loop_z_elems(Hj, zrows) * 2 + loop_wblank_elems(Hj, zrows) * 4 + (size_t)B * Hp * 4 +
          (size_t)B * Hj * 4 + (size_t)B * upw * 4;
 }
 
@@ -203,6 +206,7 @@ __device__ __forceinline__ void loop_rows_times_h(const bf16_t *hsrc, const bf16
   }
 }
 
+template <bool FUSED>
 __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, LoopDev lp) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   __shared__ DecideShared sh;
@@ -227,6 +231,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   };
   float *cst = pfull + (size_t)B * Hj;
   float *recs = cst + (size_t)B * lp.upw;   // [B][nr] recurrent halves of the gate sums, see below
+  float *wbl = recs + (size_t)B * nr;       // [Hj] blank column of W_out (fused form)
 
   // ---- once: this workgroup's weights, the state after the start-token step, the slot table
   const int unit0 = g * lp.upw, prow0 = g * lp.ppw;
@@ -271,24 +276,47 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   const bool has_cols = g < c.nparts_tiny;
   const int n0 = (has_cols ? g : 0) * kTinyCols;
   const int kq = Hj >> 2, k0 = wave * kq, nk = kq >> 4;
+  // separate form: 32 x 32 x 16 products, lane = (column lane & 31, K half lane >> 5)
   const bf16_t *wrow = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)(n0 + (lane & 31)) * Hj + k0 + (lane >> 5) * 8;
-  bf16x8 bfrag[kTinyPrefetch];
+  bf16x8 bfrag[FUSED ? 1 : kTinyPrefetch];
+  if constexpr (!FUSED) {
 #pragma unroll
-  for (int i = 0; i < kTinyPrefetch; ++i)
-    if (i < nk) bfrag[i] = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
+    for (int i = 0; i < kTinyPrefetch; ++i)
+      if (i < nk) bfrag[i] = *reinterpret_cast<const bf16x8 *>(wrow + i * 16);
+  }
   const int cip = lane & 31, col = n0 + cip;
   const bool col_ok = has_cols && col < m.V;
   const float col_bias = col_ok ? m.b_out[col_ok ? col : 0] : kKeyNone;
+  // fused form: 16 x 16 x 32 products, two tiles of 16 columns, lane = (column lane & 15, K group lane >> 4)
+  const int ns32 = kq >> 5;
+  bf16x8 bfrag16[FUSED ? 2 : 1][FUSED ? kFusedSteps : 1];
+  float bias16[2] = {kKeyNone, kKeyNone};
+  bool ok16[2] = {false, false};
+  if constexpr (FUSED) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int cc = n0 + 16 * t + (lane & 15);
+      ok16[t] = has_cols && cc < m.V;
+      if (ok16[t]) bias16[t] = m.b_out[cc];
+      const bf16_t *wr = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)cc * Hj + k0 + (lane >> 4) * 8;   // rows up to Vpad exist
+#pragma unroll
+      for (int i = 0; i < kFusedSteps; ++i)
+        if (i < ns32) bfrag16[t][i] = *reinterpret_cast<const bf16x8 *>(wr + i * 32);
+    }
+    for (int k = tid; k < Hj; k += 256) wbl[k] = m.w_blank[k];
+  }
   const float b_blank = m.b_out[m.V];
   CallDev cl = c;   // the decision code reads the keys through parts and, for near-ties, the current projections through p
   cl.p = pfull;
   cl.parts = reinterpret_cast<float *>(zs);   // the iteration's keys are copied over the window rows once those are used up
-  constexpr int KI = kTinyMaxHj / 256;
+  constexpr int KI = FUSED ? 1 : kTinyMaxHj / 256;
   float4 wblank[KI];
+  if constexpr (!FUSED) {
 #pragma unroll
-  for (int i = 0; i < KI; ++i) {
-    const int k = lane * 4 + 256 * i;
-    wblank[i] = k < Hj ? *reinterpret_cast<const float4 *>(m.w_blank + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < KI; ++i) {
+      const int k = lane * 4 + 256 * i;
+      wblank[i] = k < Hj ? *reinterpret_cast<const float4 *>(m.w_blank + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
   }
   unsigned passed = 0;
   __syncthreads();
@@ -360,111 +388,223 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     const int n_rows = na * W;
     float2 *parts = lp.parts_x + (size_t)par * kLoopRows * c.nparts_tiny;
     for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
-    // ---- window rows into LDS with their fp32 blank logit and norm (every workgroup: all rows)
-    for (int q0 = 0; q0 < 8; q0 += 4) {
-      if (q0 * 4 >= n_rows) continue;   // no window rows in this pass (what those rows of z hold is never looked at)
-      float4 ev[4][KI];
-      bool valid[4];
-      int arow[4];
+    f32x4 facc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    if constexpr (FUSED) {
+      // ---- window rows straight into matrix-core operands: lane = (row lane & 15, K group lane >> 4) reads 8
+      // consecutive projections per step of 32 of this wave's quarter of K, adds the prediction
+      // projection, applies the ReLU and rounds: that is its part of the first operand of a 16 x 16 x 32
+      // product against the W_out fragments in registers.  The fp32 blank logit and norm of the row
+      // are summed over the K groups by lane exchanges and over the waves through LDS, like the products.
+      const int row = lane & 15, kofs = k0 + (lane >> 4) * 8;
+      bool valid = false;
+      int arow = 0;
+      const float *er = c.e;
+      if (row < n_rows) {
+        const int a = row >= W ? 1 : 0, j = row - a * W;   // at most two utterances
+        const int4 st = sh.slot[a];
+        valid = st.y + j < st.z;
+        arow = st.x;
+        er = c.e + ((size_t)st.x * c.T + (valid ? st.y + j : 0)) * Hj;
+      }
+      float4 ev[kFusedSteps][2];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row = wave + 4 * (q0 + q);
-        valid[q] = false;
-        arow[q] = 0;
-        const float *er = c.e;
-        if (row < n_rows) {
-          const int a = row >= W ? 1 : 0, j = row - a * W;   // at most two utterances
-          const int4 st = sh.slot[a];
-          valid[q] = st.y + j < st.z;
-          arow[q] = st.x;
-          er = c.e + ((size_t)st.x * c.T + (valid[q] ? st.y + j : 0)) * Hj;
-        }
-#pragma unroll
-        for (int i = 0; i < KI; ++i) {
-          const int k = lane * 4 + 256 * i;
-          ev[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (valid[q] && k < Hj) ev[q][i] = *reinterpret_cast<const float4 *>(er + k);
+      for (int i = 0; i < kFusedSteps; ++i) {
+        ev[i][0] = make_float4(0.f, 0.f, 0.f, 0.f);
+        ev[i][1] = ev[i][0];
+        if (valid && i < ns32) {
+          ev[i][0] = *reinterpret_cast<const float4 *>(er + kofs + i * 32);
+          ev[i][1] = *reinterpret_cast<const float4 *>(er + kofs + i * 32 + 4);
         }
       }
-      float dn[8];   // [q][blank-logit part, squared norm]
+      // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
+      // are consumed one iteration later, so that no wave ever waits for these loads.
+      {
+        warm += pend[0] + pend[1];
+        pend[0] = 0.f; pend[1] = 0.f;
+        const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
+        for (int a = 0; a < na; ++a) {
+          const int4 st = sh.slot[a];
+          const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
+          const int l = tid & 31;
+          for (int tr = t_first + (tid >> 5), i2 = 0; tr < t_end; tr += 8, ++i2)
+            if (l < lines_per_row) pend[i2 & 1] += c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+        }
+      }
+      float dot = 0.f, nrm = 0.f;
+      const float *pr = pfull + (size_t)arow * Hj + kofs;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row = wave + 4 * (q0 + q);
-        float dot = 0.f, nrm = 0.f;
+      for (int i = 0; i < kFusedSteps; ++i)
+        if (i < ns32) {
+          float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          if (valid) {
+            const float4 p0 = *reinterpret_cast<const float4 *>(pr + i * 32), p1 = *reinterpret_cast<const float4 *>(pr + i * 32 + 4);
+            x[0] = fmaxf(ev[i][0].x + p0.x, 0.f); x[1] = fmaxf(ev[i][0].y + p0.y, 0.f);
+            x[2] = fmaxf(ev[i][0].z + p0.z, 0.f); x[3] = fmaxf(ev[i][0].w + p0.w, 0.f);
+            x[4] = fmaxf(ev[i][1].x + p1.x, 0.f); x[5] = fmaxf(ev[i][1].y + p1.y, 0.f);
+            x[6] = fmaxf(ev[i][1].z + p1.z, 0.f); x[7] = fmaxf(ev[i][1].w + p1.w, 0.f);
+          }
+          const float4 w0 = *reinterpret_cast<const float4 *>(wbl + kofs + i * 32), w1 = *reinterpret_cast<const float4 *>(wbl + kofs + i * 32 + 4);
+          dot = fmaf(x[0], w0.x, dot); dot = fmaf(x[1], w0.y, dot); dot = fmaf(x[2], w0.z, dot); dot = fmaf(x[3], w0.w, dot);
+          dot = fmaf(x[4], w1.x, dot); dot = fmaf(x[5], w1.y, dot); dot = fmaf(x[6], w1.z, dot); dot = fmaf(x[7], w1.w, dot);
 #pragma unroll
-        for (int i = 0; i < KI; ++i) {
-          const int k = lane * 4 + 256 * i;
-          if (k < Hj && row < n_rows) {   // rows past the windows: what z holds there is never looked at
-            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (valid[q]) {
-              const float4 pv = *reinterpret_cast<const float4 *>(pfull + (size_t)arow[q] * Hj + k);
-              x.x = fmaxf(ev[q][i].x + pv.x, 0.f); x.y = fmaxf(ev[q][i].y + pv.y, 0.f);
-              x.z = fmaxf(ev[q][i].z + pv.z, 0.f); x.w = fmaxf(ev[q][i].w + pv.w, 0.f);
-            }
-            *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
-            const float4 wb = wblank[i];
-            dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
-            nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+          for (int e2 = 0; e2 < 8; ++e2) nrm = fmaf(x[e2], x[e2], nrm);
+          const u32x4 zu = u32x4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
+          const bf16x8 zf = __builtin_bit_cast(bf16x8, zu);
+          facc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf, bfrag16[0][i], facc[0], 0, 0, 0);
+          facc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf, bfrag16[1][i], facc[1], 0, 0, 0);
+        }
+      dot += __shfl_xor(dot, 16, kWave); nrm += __shfl_xor(nrm, 16, kWave);
+      dot += __shfl_xor(dot, 32, kWave); nrm += __shfl_xor(nrm, 32, kWave);
+      // partial sums of this wave's quarter of K: fred[wave][tile][r][80] (register r of lane l: row 4 * (l >> 4) + r,
+      // column 16 * tile + (l & 15); 80 floats per r so that the readers below hit different banks), then
+      // fbn[wave][blank part, squared norm][row]
+      float *fred = reinterpret_cast<float *>(zs), *fbn = fred + 4 * 2 * 4 * 80;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) fred[((wave * 2 + t) * 4 + r) * 80 + lane] = facc[t][r];
+      }
+      if (lane < 16) {
+        fbn[(wave * 2 + 0) * 16 + lane] = dot;
+        fbn[(wave * 2 + 1) * 16 + lane] = nrm;
+      }
+      __syncthreads();
+      const long long t1 = dbg ? wall_clock64() : 0;
+      if (dbg) tsum[0] += t1 - t0;
+      // wave w finishes rows 4w .. 4w + 3: lane = (row 4w + (lane >> 4), column lane & 15 of either tile)
+      {
+        const int rr = lane >> 4, cj = lane & 15, orow = 4 * wave + rr;
+        float k1 = kKeyNone, k2 = kKeyNone;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          float v = bias16[t];
+#pragma unroll
+          for (int w2 = 0; w2 < 4; ++w2) v += fred[((w2 * 2 + t) * 4 + rr) * 80 + 16 * wave + cj];
+          push_top2(k1, k2, make_key(ok16[t] ? v : kKeyNone, 16 * t + cj));
+        }
+        merge_top2(k1, k2, dpp_f32<kDppRowMirror>(k1), dpp_f32<kDppRowMirror>(k2));
+        merge_top2(k1, k2, dpp_f32<kDppRowHalfMirror>(k1), dpp_f32<kDppRowHalfMirror>(k2));
+        merge_top2(k1, k2, dpp_f32<kDppQuadXor2>(k1), dpp_f32<kDppQuadXor2>(k2));
+        merge_top2(k1, k2, dpp_f32<kDppQuadXor1>(k1), dpp_f32<kDppQuadXor1>(k2));
+        if (has_cols && cj == 0) st_shared_f32x2(&parts[(size_t)orow * c.nparts_tiny + g], make_float2(k1, k2), near);
+      }
+      if (tid < 16 && tid < n_rows) {
+        float d2 = b_blank, n2 = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) { d2 += fbn[(w2 * 2 + 0) * 16 + tid]; n2 += fbn[(w2 * 2 + 1) * 16 + tid]; }
+        sh.blank[tid] = d2;
+        sh.znorm[tid] = sqrtf(n2);
+      }
+      if (dbg) tsum[1] += wall_clock64() - t1;
+    } else {
+      // ---- window rows into LDS with their fp32 blank logit and norm (every workgroup: all rows)
+      for (int q0 = 0; q0 < 8; q0 += 4) {
+        if (q0 * 4 >= n_rows) continue;   // no window rows in this pass (what those rows of z hold is never looked at)
+        float4 ev[4][KI];
+        bool valid[4];
+        int arow[4];
+  #pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row = wave + 4 * (q0 + q);
+          valid[q] = false;
+          arow[q] = 0;
+          const float *er = c.e;
+          if (row < n_rows) {
+            const int a = row >= W ? 1 : 0, j = row - a * W;   // at most two utterances
+            const int4 st = sh.slot[a];
+            valid[q] = st.y + j < st.z;
+            arow[q] = st.x;
+            er = c.e + ((size_t)st.x * c.T + (valid[q] ? st.y + j : 0)) * Hj;
+          }
+  #pragma unroll
+          for (int i = 0; i < KI; ++i) {
+            const int k = lane * 4 + 256 * i;
+            ev[q][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (valid[q] && k < Hj) ev[q][i] = *reinterpret_cast<const float4 *>(er + k);
           }
         }
-        dn[2 * q] = dot;
-        dn[2 * q + 1] = nrm;
-      }
-      const float tot = wave_sum8_scatter(dn, lane);   // lane 4q: row q's dot; lane 4q + 16: its squared norm
-      const int rowq = wave + 4 * (q0 + ((lane >> 2) & 3));
-      if (rowq < n_rows && (lane & 0x23) == 0) {
-        if (lane & 16) sh.znorm[rowq] = sqrtf(tot);
-        else sh.blank[rowq] = tot + b_blank;
-      }
-    }
-    // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
-    // are consumed one iteration later, so that no wave ever waits for these loads.
-    {
-      warm += pend[0] + pend[1];
-      pend[0] = 0.f; pend[1] = 0.f;
-      const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
-      for (int a = 0; a < na; ++a) {
-        const int4 st = sh.slot[a];
-        const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
-        const int l = tid & 31;
-        for (int tr = t_first + (tid >> 5), i2 = 0; tr < t_end; tr += 8, ++i2)
-          if (l < lines_per_row) pend[i2 & 1] += c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
-      }
-    }
-    __syncthreads();
-    const long long t1 = dbg ? wall_clock64() : 0;
-    // ---- this workgroup's 32 columns: K split over the four waves, W_out from registers
-    if (has_cols) {
-      f32x16 acc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-      const bf16_t *zrow = zs + (size_t)min(lane & 31, lp.zrows - 1) * zstride + k0 + (lane >> 5) * 8;   // rows past the region repeat its last row; never looked at
-#pragma unroll
-      for (int i = 0; i < kTinyPrefetch; ++i)
-        if (i < nk) {
-          const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag[i], acc, 0, 0, 0);
+        float dn[8];   // [q][blank-logit part, squared norm]
+  #pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row = wave + 4 * (q0 + q);
+          float dot = 0.f, nrm = 0.f;
+  #pragma unroll
+          for (int i = 0; i < KI; ++i) {
+            const int k = lane * 4 + 256 * i;
+            if (k < Hj && row < n_rows) {   // rows past the windows: what z holds there is never looked at
+              float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+              if (valid[q]) {
+                const float4 pv = *reinterpret_cast<const float4 *>(pfull + (size_t)arow[q] * Hj + k);
+                x.x = fmaxf(ev[q][i].x + pv.x, 0.f); x.y = fmaxf(ev[q][i].y + pv.y, 0.f);
+                x.z = fmaxf(ev[q][i].z + pv.z, 0.f); x.w = fmaxf(ev[q][i].w + pv.w, 0.f);
+              }
+              *reinterpret_cast<uint2 *>(zs + (size_t)row * zstride + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+              const float4 wb = wblank[i];
+              dot = fmaf(x.x, wb.x, dot); dot = fmaf(x.y, wb.y, dot); dot = fmaf(x.z, wb.z, dot); dot = fmaf(x.w, wb.w, dot);
+              nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm); nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
+            }
+          }
+          dn[2 * q] = dot;
+          dn[2 * q + 1] = nrm;
         }
-      __syncthreads();   // every wave is done with z: its LDS takes the K-split partial sums
-      float *red = reinterpret_cast<float *>(zs);   // [wave][r][lane]
-#pragma unroll
-      for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
+        const float tot = wave_sum8_scatter(dn, lane);   // lane 4q: row q's dot; lane 4q + 16: its squared norm
+        const int rowq = wave + 4 * (q0 + ((lane >> 2) & 3));
+        if (rowq < n_rows && (lane & 0x23) == 0) {
+          if (lane & 16) sh.znorm[rowq] = sqrtf(tot);
+          else sh.blank[rowq] = tot + b_blank;
+        }
+      }
+      // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
+      // are consumed one iteration later, so that no wave ever waits for these loads.
+      {
+        warm += pend[0] + pend[1];
+        pend[0] = 0.f; pend[1] = 0.f;
+        const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
+        for (int a = 0; a < na; ++a) {
+          const int4 st = sh.slot[a];
+          const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
+          const int l = tid & 31;
+          for (int tr = t_first + (tid >> 5), i2 = 0; tr < t_end; tr += 8, ++i2)
+            if (l < lines_per_row) pend[i2 & 1] += c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+        }
+      }
       __syncthreads();
-      if (wave == 0) {
-        float k1[16], k2[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = col_bias;
-#pragma unroll
-          for (int w2 = 0; w2 < 4; ++w2) v += red[(w2 * 16 + r) * 64 + lane];
-          k1[r] = make_key(col_ok ? v : kKeyNone, cip);
-          k2[r] = kKeyNone;
+      const long long t1 = dbg ? wall_clock64() : 0;
+      if (dbg) { tsum[0] += t1 - t0; }
+      // ---- this workgroup's 32 columns: K split over the four waves, W_out from registers
+      if (has_cols) {
+        f32x16 acc;
+  #pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        const bf16_t *zrow = zs + (size_t)min(lane & 31, lp.zrows - 1) * zstride + k0 + (lane >> 5) * 8;   // rows past the region repeat its last row; never looked at
+  #pragma unroll
+        for (int i = 0; i < kTinyPrefetch; ++i)
+          if (i < nk) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(zrow + i * 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag[i], acc, 0, 0, 0);
+          }
+        __syncthreads();   // every wave is done with z: its LDS takes the K-split partial sums
+        float *red = reinterpret_cast<float *>(zs);   // [wave][r][lane]
+  #pragma unroll
+        for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
+        __syncthreads();
+        if (wave == 0) {
+          float k1[16], k2[16];
+  #pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float v = col_bias;
+  #pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) v += red[(w2 * 16 + r) * 64 + lane];
+            k1[r] = make_key(col_ok ? v : kKeyNone, cip);
+            k2[r] = kKeyNone;
+          }
+          float o1[1], o2[1];
+          RowTop2<16, 0>::run(k1, k2, lane, o1, o2);
+          const int s0 = rowtop2_first_slot<16>(lane);
+          st_shared_f32x2(&parts[(size_t)acc_row(0, s0, lane) * c.nparts_tiny + g], make_float2(o1[0], o2[0]), near);
         }
-        float o1[1], o2[1];
-        RowTop2<16, 0>::run(k1, k2, lane, o1, o2);
-        const int s0 = rowtop2_first_slot<16>(lane);
-        st_shared_f32x2(&parts[(size_t)acc_row(0, s0, lane) * c.nparts_tiny + g], make_float2(o1[0], o2[0]), near);
       }
+      if (dbg) tsum[1] += wall_clock64() - t1;
     }
     const long long t2 = dbg ? wall_clock64() : 0;
     if (!loop_barrier(lp, g, near, passed, ls)) return;   // exchange 1: every row's keys are in memory
@@ -542,7 +682,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     if (tid < na) { sh.slot[tid] = ls.nslot[tid]; sh.cnt[tid] = ls.ncnt[tid]; }
     __syncthreads();
     const long long t4 = dbg ? wall_clock64() : 0;
-    if (dbg) { tsum[0] += t1 - t0; tsum[1] += t2 - t1; tsum[2] += t3 - t2; tsum[3] += t4 - t3; ++n_it; }
+    if (dbg) { tsum[2] += t3 - t2; tsum[3] += t4 - t3; ++n_it; }
     if (n_emit == 0 || na == 0) continue;
     // ---- one LSTM step for the utterances that emitted: this workgroup's units, weights from LDS
     // thread 4u + gate: that gate of the workgroup's unit u (the label's input sums are one coalesced read)

@@ -174,9 +174,10 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W, near):
     enc, lens = wi.make_batch(cfg)
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     res, stats = [], []
-    for lk, one in ((1, 1), (1, 0), (0, 1)):
+    for lk, one, fused in ((1, 1, 1), (1, 1, 0), (1, 0, 1), (0, 1, 1)):
         m.set_option("loop_kernel", lk)
         m.set_option("loop_one_xcd", one)
+        m.set_option("loop_fused", fused)   # window rows built as matrix-core operands, or staged in LDS
         toks, frs = m.decode(d_enc, d_len, W, cfg.S)
         g, one_l2 = m.loop_info()
         if lk == 0:
@@ -194,7 +195,7 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W, near):
     for other in res[1:]:
         assert all(a.tolist() == b.tolist() for a, b in zip(res[0][0], other[0]))
         assert all(a.tolist() == b.tolist() for a, b in zip(res[0][1], other[1]))
-    assert stats[0] == stats[1] == stats[2]
+    assert stats[0] == stats[1] == stats[2] == stats[3]
     m.close()
 
 
