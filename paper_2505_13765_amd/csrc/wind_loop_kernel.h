@@ -64,6 +64,7 @@ __host__ __device__ inline size_t loop_z_elems(int Hj, int zrows) {
 }
 // the fused form of the window phase (zrows == 0) keeps the blank column of W_out in LDS as fp32
 __host__ __device__ inline size_t loop_wblank_elems(int Hj, int zrows) { return zrows == 0 ? (size_t)Hj : 0; }
+constexpr int kFusedRedFloats = 4 * 2 * 4 * 80 + 4 * 2 * 16;   // partial sums of the fused window phase, see there
 constexpr int kFusedSteps = 5;   // K steps of 32 per wave in that form: Hj <= 4 * 32 * 5
 __host__ __device__ inline size_t loop_smem_bytes(int Hp, int Hj, int B, int upw, int ppw, int zrows) {
   return (size_t)(upw * 4 + ppw) * (Hp + 8) * 2 + (size_t)B * upw * 16 + loop_z_elems(Hj, zrows) * 2 + loop_wblank_elems(Hj, zrows) * 4 + (size_t)B * Hp * 4 +
@@ -262,7 +263,8 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   // Read-only operands are fetched ahead into this XCD's L2, which nothing invalidates while the
   // kernel runs: here this workgroup's columns of every row of emb_gates, below the encoder
   // projections of the window after the current one.
-  float warm = 0.f, pend[2] = {0.f, 0.f};
+  constexpr int kTouchSteps = FUSED ? 2 : 4;   // rows of the next window a thread touches: 8 * kTouchSteps >= W
+  float warm = 0.f, pend[kLoopMaxB * kTouchSteps] = {};
   {
     const int lines = (lp.upw * 16 + 127) / 128;   // 128-byte lines per table row slice
     for (int i = tid; i < (m.V + 1) * lines; i += 256) {
@@ -327,7 +329,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   // K is split over the four waves, whose partial sums go to red[wave][row][b] (the window-row region,
   // which is free whenever this runs).  Up to 128 rows: four independent accumulator blocks in flight.
   // The projection rows follow the gate rows in LDS with the same stride, so one pass can cover both.
-  float *red = reinterpret_cast<float *>(zs);
+  float *red = reinterpret_cast<float *>(zs) + (FUSED ? kFusedRedFloats : 0);   // fused form: behind the window phase's own sums
   auto red_sum = [&](int row, int b) {
     float v = 0.f;
 #pragma unroll
@@ -381,6 +383,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
 
   const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
+  int rec_due = 0, rec_ub[kLoopMaxB] = {0, 0};   // fused form: utterances whose recurrent sums are still to be renewed
   long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
   for (int it = 0; it < lp.max_iters && na > 0; ++it) {
     const int par = it & 1;
@@ -388,6 +391,10 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     const int n_rows = na * W;
     float2 *parts = lp.parts_x + (size_t)par * kLoopRows * c.nparts_tiny;
     for (int j = tid; j <= kMaxWindow; j += 256) sh.hist[j] = 0u;
+    // last iteration's touches of this window's lines (see below) are consumed here, before this iteration's
+    // loads are issued: by now they have long arrived
+#pragma unroll
+    for (int i = 0; i < kLoopMaxB * kTouchSteps; ++i) { warm += pend[i]; pend[i] = 0.f; }
     f32x4 facc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
     if constexpr (FUSED) {
       // ---- window rows straight into matrix-core operands: lane = (row lane & 15, K group lane >> 4) reads 8
@@ -416,20 +423,26 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
           ev[i][1] = *reinterpret_cast<const float4 *>(er + kofs + i * 32 + 4);
         }
       }
-      // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
-      // are consumed one iteration later, so that no wave ever waits for these loads.
+      // Touch the lines of the window after this one, so that they sit in L2 when it is their turn.  The
+      // values are consumed one iteration later (each into a register of its own: nothing waits for them here).
       {
-        warm += pend[0] + pend[1];
-        pend[0] = 0.f; pend[1] = 0.f;
         const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
-        for (int a = 0; a < na; ++a) {
-          const int4 st = sh.slot[a];
-          const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
-          const int l = tid & 31;
-          for (int tr = t_first + (tid >> 5), i2 = 0; tr < t_end; tr += 8, ++i2)
-            if (l < lines_per_row) pend[i2 & 1] += c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+        // every load is issued by every lane, with its row and line clamped into the utterance's frames: a
+        // load under a condition would have to merge with the register's old value, and wait for it
+#pragma unroll
+        for (int a = 0; a < kLoopMaxB; ++a) {
+          const int4 st = sh.slot[min(a, na - 1)];
+          const int l = min(tid & 31, lines_per_row - 1);
+#pragma unroll
+          for (int i2 = 0; i2 < kTouchSteps; ++i2) {
+            const int tr = max(min(st.y + W + (tid >> 5) + 8 * i2, st.z - 1), 0);
+            pend[a * kTouchSteps + i2] = c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+          }
         }
       }
+      // While the loads travel: the recurrent sums that the last iteration's new hidden vectors call for
+      // (they are needed by the next LSTM step, not before).
+      if (rec_due) weight_rows_times_h(wl, nr);
       float dot = 0.f, nrm = 0.f;
       const float *pr = pfull + (size_t)arow * Hj + kofs;
 #pragma unroll
@@ -458,7 +471,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       // partial sums of this wave's quarter of K: fred[wave][tile][r][80] (register r of lane l: row 4 * (l >> 4) + r,
       // column 16 * tile + (l & 15); 80 floats per r so that the readers below hit different banks), then
       // fbn[wave][blank part, squared norm][row]
-      float *fred = reinterpret_cast<float *>(zs), *fbn = fred + 4 * 2 * 4 * 80;
+      float *fred = reinterpret_cast<float *>(zs), *fbn = fred + 4 * 2 * 4 * 80;   // kFusedRedFloats in all
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
 #pragma unroll
@@ -471,6 +484,11 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       __syncthreads();
       const long long t1 = dbg ? wall_clock64() : 0;
       if (dbg) tsum[0] += t1 - t0;
+      if (rec_due) {
+        if (tid < nr)
+          for (int r = 0; r < rec_due; ++r) recs[rec_ub[r] * nr + tid] = red_sum(tid, rec_ub[r]);
+        rec_due = 0;
+      }
       // wave w finishes rows 4w .. 4w + 3: lane = (row 4w + (lane >> 4), column lane & 15 of either tile)
       {
         const int rr = lane >> 4, cj = lane & 15, orow = 4 * wave + rr;
@@ -554,18 +572,21 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
           else sh.blank[rowq] = tot + b_blank;
         }
       }
-      // Touch the lines of the window after this one (every XCD's L2 wants its own copy).  The values
-      // are consumed one iteration later, so that no wave ever waits for these loads.
+      // Touch the lines of the window after this one, so that they sit in L2 when it is their turn.  The
+      // values are consumed one iteration later (each into a register of its own: nothing waits for them here).
       {
-        warm += pend[0] + pend[1];
-        pend[0] = 0.f; pend[1] = 0.f;
         const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
-        for (int a = 0; a < na; ++a) {
-          const int4 st = sh.slot[a];
-          const int t_first = st.y + W, t_end = min(st.y + 2 * W, st.z);
-          const int l = tid & 31;
-          for (int tr = t_first + (tid >> 5), i2 = 0; tr < t_end; tr += 8, ++i2)
-            if (l < lines_per_row) pend[i2 & 1] += c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+        // every load is issued by every lane, with its row and line clamped into the utterance's frames: a
+        // load under a condition would have to merge with the register's old value, and wait for it
+#pragma unroll
+        for (int a = 0; a < kLoopMaxB; ++a) {
+          const int4 st = sh.slot[min(a, na - 1)];
+          const int l = min(tid & 31, lines_per_row - 1);
+#pragma unroll
+          for (int i2 = 0; i2 < kTouchSteps; ++i2) {
+            const int tr = max(min(st.y + W + (tid >> 5) + 8 * i2, st.z - 1), 0);
+            pend[a * kTouchSteps + i2] = c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+          }
         }
       }
       __syncthreads();
@@ -712,25 +733,32 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       for (int k = tid * 2; k < Hp; k += 512) put_h2(ub * Hp + k, ld_shared_f32x2(reinterpret_cast<const float2 *>(&lp.h_x[(size_t)ub * Hp + k])));
     }
     __syncthreads();
-    // ---- this workgroup's rows of the prediction projection, and in the same pass over the new vectors
-    // the recurrent sums of the next step (rows nr .. nr + ppw - 1 and 0 .. nr - 1 of the weights in LDS)
-    weight_rows_times_h(wl, nr + lp.ppw);
+    // ---- this workgroup's rows of the prediction projection; the recurrent sums of the next step, which
+    // want the same new vectors, in the same pass (rows nr .. nr + ppw - 1 and 0 .. nr - 1 of the weights
+    // in LDS), or, in the fused form, put off to the time the next window's loads take
+    const int prow_red = FUSED ? 0 : nr;
+    if constexpr (FUSED) weight_rows_times_h(wp, lp.ppw);
+    else weight_rows_times_h(wl, nr + lp.ppw);
     __syncthreads();
     if (tid < lp.ppw && prow0 + tid < Hj) {
       const int j = prow0 + tid;
       const float bj = m.b_pred[j];
       for (int r = 0; r < n_emit; ++r) {
         const int ub = ls.emit_ub[r];
-        st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], red_sum(nr + tid, ub) + bj, near);
+        st_shared_f32(&lp.p_x[(size_t)ub * Hj + j], red_sum(prow_red + tid, ub) + bj, near);
       }
     }
     const long long t7 = dbg ? wall_clock64() : 0;
     loop_arrive(lp, g, near, passed);                     // exchange 3: the new projections ...
-    if (tid < nr)                                         // ... and, while the arrivals travel, the recurrent sums are put by
+    if constexpr (FUSED) {
+      rec_due = n_emit;
+      for (int r = 0; r < n_emit; ++r) rec_ub[r] = ls.emit_ub[r];
+    } else if (tid < nr) {                                // ... and, while the arrivals travel, the recurrent sums are put by
       for (int r = 0; r < n_emit; ++r) {
         const int ub = ls.emit_ub[r];
         recs[ub * nr + tid] = red_sum(tid, ub);
       }
+    }
     if (!loop_wait(lp, passed, ls)) return;
     const long long t8 = dbg ? wall_clock64() : 0;
     for (int r = 0; r < n_emit; ++r) {
