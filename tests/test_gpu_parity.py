@@ -183,7 +183,10 @@ def test_resident_loop_kernel(torch_cuda, name, B, lo, hi, W, near):
         if lk == 0:
             assert (g, one_l2) == (0, False)
         elif one and near:
-            assert (g, one_l2) == (32, True)     # the placement the kernel expects is what this machine gives
+            assert g == 32
+            if not one_l2:   # the kernel found its workgroups on several XCDs and kept the device-wide stores: slower, not wrong
+                import warnings
+                warnings.warn("resident loop kernel: 32 workgroups were not placed on one XCD")
         else:
             assert g == 40 and not one_l2
         check_outputs(cfg, lens, toks, frs)
