@@ -243,7 +243,8 @@ def test_random_shapes_bf16(torch_cuda):
     """Seeded random models and batches over the whole range of shapes the library accepts (hidden sizes from
     64, vocabularies from 5 to 8192 labels, one to three LSTM layers, 1 to 70 utterances, windows 1 to 32,
     empty utterances), each decoded on the default route and with the options that select the other
-    routes, against the oracle."""
+    routes (for one or two utterances also both forms and both placements of the resident loop kernel),
+    against the oracle."""
     rng = np.random.default_rng(20250513)
     for case in range(16):
         small = case % 2 == 0   # every other case in the resident loop kernel's range
@@ -263,8 +264,11 @@ def test_random_shapes_bf16(torch_cuda):
         enc, lens = wi.make_batch(cfg)
         d_enc, d_len = to_dev(torch_cuda, enc, lens)
         print(f"random shapes {case}: Hj={Hj} Hp={Hp} E={E} L={L} V={V} B={B} W={W} S={S} lengths {lo}..{hi}", flush=True)
-        for opts in ({}, {"loop_kernel": 0, "lstm_rec": 0, "atomic_lists": 0}, {"loop_kernel": 0}):
-            for k, v in {"loop_kernel": 1, "lstm_rec": 1, "atomic_lists": 1, **opts}.items():
+        routes = [{}, {"loop_kernel": 0, "lstm_rec": 0, "atomic_lists": 0}, {"loop_kernel": 0}]
+        if small:   # the resident loop kernel's other form (window rows staged in LDS) and other placement
+            routes += [{"loop_fused": 0}, {"loop_one_xcd": 0}, {"loop_fused": 0, "loop_one_xcd": 0}]
+        for opts in routes:
+            for k, v in {"loop_kernel": 1, "lstm_rec": 1, "atomic_lists": 1, "loop_fused": 1, "loop_one_xcd": 1, **opts}.items():
                 m.set_option(k, v)
             toks, frs = m.decode(d_enc, d_len, W, S)
             check_outputs(cfg, lens, toks, frs)
