@@ -145,6 +145,7 @@ struct wind_model {
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
+  int cu_count = 0;            // CUs of the device the model was loaded on (the resident loop kernel wants one per workgroup)
   int loop_info[2] = {0, 0};   // last decode call: workgroups of the resident loop kernel (0: not used), whether they shared one L2
   long long prev_iters = 0;
   int prev_B = 0, prev_T = 0, prev_W = 0;
@@ -549,9 +550,10 @@ bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *s
   // at most 16 window rows and a joint width in steps of 128: the rows go straight into matrix-core operands
   const bool fused = m->opt_loop_fused && B * W <= 16 && d.Hj % 128 == 0 && d.Hj <= 128 * kFusedSteps;
   for (int near = m->opt_loop_one_xcd ? 1 : 0; near >= 0; --near) {
+    if (near && m->cu_count < 8 * kLoopNearG) continue;   // eight XCDs of at least 32 CUs each
     int G = near ? kLoopNearG : (widest + 15) / 16;
     if (G < nparts_tiny) { if (near) continue; G = nparts_tiny; }
-    if (G > 256) return false;
+    if (G > 256 || G > m->cu_count) return false;
     lp->G = G;
     lp->step = near ? 8 : 1;
     lp->zrows = fused ? 0 : near && B * W <= 16 ? 16 : kLoopRows;
@@ -741,6 +743,11 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   wind_model *m = new wind_model();
   m->dtype = w->dtype;
   m->load_stream = (hipStream_t)stream;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+      m->cu_count = cus;
+  }
   ModelDev &d = m->dev;
   d.D = w->D; d.E = w->E; d.Hp = w->Hp; d.L = w->L; d.Hj = w->Hj; d.V = w->V;
   d.Vpad = (int)round_up((size_t)w->V + 1, 256);
