@@ -230,7 +230,7 @@ struct Ring5Cfg {
   static_assert(WN <= 128 && SMEM_BYTES <= 160 * 1024, "limits");
 };
 
-template <class Cfg, bool SWAP = false, class Init = NoInit, bool WEAVE = false>
+template <class Cfg, bool SWAP = false, class Init = NoInit>
 __device__ __forceinline__ void gemm_mainloop_ring5(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Bw,
                                                     int K, unsigned char *smem,
                                                     f32x16 (&acc)[Cfg::MI][Cfg::NI], Init after_issue = Init{}) {
@@ -290,16 +290,6 @@ __device__ __forceinline__ void gemm_mainloop_ring5(const bf16_t *__restrict__ A
                            : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
   };
   auto plus2 = [](int s) { return s + 2 >= Cfg::NSLOT ? s + 2 - Cfg::NSLOT : s + 2; };
-  // WEAVE: one LDS read behind each of the first MFMAs of a K step instead of all reads in front of
-  // them: a wave issues in order, and a burst of reads that queues at the LDS holds its MFMAs back
-  auto weave = [] {
-#pragma unroll
-    for (int q = 0; q < Cfg::MI + Cfg::NI; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-  };
-
   static_assert(Cfg::LPU == Cfg::KSTEPS, "one A load per K step");
   wait_vmcnt<2 * Cfg::LPU + 1>();   // A0, B0 have landed
   __builtin_amdgcn_s_barrier();
@@ -312,9 +302,8 @@ __device__ __forceinline__ void gemm_mainloop_ring5(const bf16_t *__restrict__ A
     for (int ks = 0; ks + 1 < Cfg::KSTEPS; ++ks) {
       load_frags((ks + 1) & 1, sa, sb, ks + 1);
       issue_a1(ks + 1, kt + 2, sprev);
-      if (!WEAVE) __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_sched_barrier(0);
       mfma_step(ks & 1);
-      if (WEAVE) weave();
       __builtin_amdgcn_sched_barrier(0);
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of tile kt are complete
@@ -325,9 +314,8 @@ __device__ __forceinline__ void gemm_mainloop_ring5(const bf16_t *__restrict__ A
     issue_a1(0, kt + 3, sb);
     const int na = plus2(sa), nb = plus2(sb);
     load_frags(0, na, nb, 0);
-    if (!WEAVE) __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_sched_barrier(0);
     mfma_step(1);
-    if (WEAVE) weave();
     __builtin_amdgcn_sched_barrier(0);
     sa = na;
     sb = nb;
