@@ -176,23 +176,31 @@ __device__ __forceinline__ void loop_rows_times_h(const bf16_t *hsrc, const bf16
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[blk][r] = 0.f;
   }
-  // operands one step ahead of the products, so that an LDS read's latency hides behind the previous step
-  bf16x8 hv = *reinterpret_cast<const bf16x8 *>(hsrc), wv[NBLK];
+  // Two sets of operand registers take turns: while the products of one step run, the reads of the next
+  // step land in the other set, and nothing has to be moved between them (a move would wait for its read).
+  bf16x8 hv[2], wv[2][NBLK];
+  auto read_step = [&](int set, int i) {
+    const int ofs = min(i, nks - 1) * 16;   // past the end: the last step again, never used
+    hv[set] = *reinterpret_cast<const bf16x8 *>(hsrc + ofs);
 #pragma unroll
-  for (int blk = 0; blk < NBLK; ++blk) wv[blk] = *reinterpret_cast<const bf16x8 *>(wsrc[blk]);
-  for (int i = 0; i < nks; ++i) {
-    const int nx = min(i + 1, nks - 1) * 16;   // the last step reads its own operands again
-    const bf16x8 hn = *reinterpret_cast<const bf16x8 *>(hsrc + nx);
-    bf16x8 wn[NBLK];
+    for (int blk = 0; blk < NBLK; ++blk) wv[set][blk] = *reinterpret_cast<const bf16x8 *>(wsrc[blk] + ofs);
+  };
+  auto products = [&](int set) {
 #pragma unroll
-    for (int blk = 0; blk < NBLK; ++blk) wn[blk] = *reinterpret_cast<const bf16x8 *>(wsrc[blk] + nx);
-#pragma unroll
-    for (int blk = 0; blk < NBLK; ++blk) acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hv, wv[blk], acc[blk], 0, 0, 0);
+    for (int blk = 0; blk < NBLK; ++blk) acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hv[set], wv[set][blk], acc[blk], 0, 0, 0);
+  };
+  read_step(0, 0);
+  for (int i = 0; i < nks; i += 2) {
+    read_step(1, i + 1);
+    products(0);
     __builtin_amdgcn_sched_group_barrier(0x100, 1 + NBLK, 0);   // the reads of the next step ...
     __builtin_amdgcn_sched_group_barrier(0x008, NBLK, 0);       // ... then this step's products
-    hv = hn;
-#pragma unroll
-    for (int blk = 0; blk < NBLK; ++blk) wv[blk] = wn[blk];
+    if (i + 1 < nks) {
+      read_step(0, i + 2);
+      products(1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1 + NBLK, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, NBLK, 0);
+    }
   }
   if (lane < 32) {
 #pragma unroll
