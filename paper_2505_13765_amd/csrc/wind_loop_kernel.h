@@ -452,19 +452,27 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       // (they are needed by the next LSTM step, not before).
       if (rec_due) weight_rows_times_h(wl, nr);
       float dot = 0.f, nrm = 0.f;
-      const float *pr = pfull + (size_t)arow * Hj + kofs;
+      const float *pr = pfull + (size_t)arow * Hj + kofs, *wr = wbl + kofs;
+      // the LDS operands of a step (projection, blank column) are read one step ahead, into registers that take turns
+      float4 po[2][2], wo[2][2];
+      auto read_ops = [&](int set, int i) {
+        const int ofs = min(i, ns32 - 1) * 32;   // past the end: the last step again, never used
+        po[set][0] = *reinterpret_cast<const float4 *>(pr + ofs); po[set][1] = *reinterpret_cast<const float4 *>(pr + ofs + 4);
+        wo[set][0] = *reinterpret_cast<const float4 *>(wr + ofs); wo[set][1] = *reinterpret_cast<const float4 *>(wr + ofs + 4);
+      };
+      read_ops(0, 0);
 #pragma unroll
       for (int i = 0; i < kFusedSteps; ++i)
         if (i < ns32) {
-          float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          if (valid) {
-            const float4 p0 = *reinterpret_cast<const float4 *>(pr + i * 32), p1 = *reinterpret_cast<const float4 *>(pr + i * 32 + 4);
-            x[0] = fmaxf(ev[i][0].x + p0.x, 0.f); x[1] = fmaxf(ev[i][0].y + p0.y, 0.f);
-            x[2] = fmaxf(ev[i][0].z + p0.z, 0.f); x[3] = fmaxf(ev[i][0].w + p0.w, 0.f);
-            x[4] = fmaxf(ev[i][1].x + p1.x, 0.f); x[5] = fmaxf(ev[i][1].y + p1.y, 0.f);
-            x[6] = fmaxf(ev[i][1].z + p1.z, 0.f); x[7] = fmaxf(ev[i][1].w + p1.w, 0.f);
-          }
-          const float4 w0 = *reinterpret_cast<const float4 *>(wbl + kofs + i * 32), w1 = *reinterpret_cast<const float4 *>(wbl + kofs + i * 32 + 4);
+          read_ops((i + 1) & 1, i + 1);
+          const float4 p0 = po[i & 1][0], p1 = po[i & 1][1], w0 = wo[i & 1][0], w1 = wo[i & 1][1];
+          float x[8];
+          x[0] = fmaxf(ev[i][0].x + p0.x, 0.f); x[1] = fmaxf(ev[i][0].y + p0.y, 0.f);
+          x[2] = fmaxf(ev[i][0].z + p0.z, 0.f); x[3] = fmaxf(ev[i][0].w + p0.w, 0.f);
+          x[4] = fmaxf(ev[i][1].x + p1.x, 0.f); x[5] = fmaxf(ev[i][1].y + p1.y, 0.f);
+          x[6] = fmaxf(ev[i][1].z + p1.z, 0.f); x[7] = fmaxf(ev[i][1].w + p1.w, 0.f);
+#pragma unroll
+          for (int e2 = 0; e2 < 8; ++e2) x[e2] = valid ? x[e2] : 0.f;   // rows past the utterance's end are zero rows
           dot = fmaf(x[0], w0.x, dot); dot = fmaf(x[1], w0.y, dot); dot = fmaf(x[2], w0.z, dot); dot = fmaf(x[3], w0.w, dot);
           dot = fmaf(x[4], w1.x, dot); dot = fmaf(x[5], w1.y, dot); dot = fmaf(x[6], w1.z, dot); dot = fmaf(x[7], w1.w, dot);
 #pragma unroll
