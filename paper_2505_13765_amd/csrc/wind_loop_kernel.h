@@ -359,6 +359,46 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     else if (n_wrows <= 96) loop_rows_times_h<3>(hsrc, wsrc, nks, red_w, lane, n_wrows, B);
     else loop_rows_times_h<4>(hsrc, wsrc, nks, red_w, lane, n_wrows, B);
   };
+  // One wave's block of 32 gate rows (blk = 0 .. 2) against the hidden vectors, K unsplit, for the utterances on
+  // the emit list: lane n < 32 ends with gate row 32 blk + n's sums and puts them into recs itself.  Four sets
+  // of operand registers and two accumulators take turns, so that neither a read nor a product waits for
+  // the one before it.
+  auto recurrent_block = [&](int blk, int n_em) {
+    if (blk * 32 >= nr) return;
+    const int mrow = lane & 31, kh = (lane >> 5) * 8, nks = Hp >> 4;   // Hp is a multiple of 64: nks of 4
+    const bf16_t *hsrc = ((mrow & 1) ? hlo : hhi) + (size_t)(mrow < 2 * B ? (mrow >> 1) : 0) * Hp + kh;
+    const bf16_t *wsrc = wl + (size_t)min(blk * 32 + mrow, nr - 1) * wstride + kh;
+    f32x16 acc2[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc2[q][r] = 0.f;
+    bf16x8 hv[4], wv[4];   // four steps of operands in flight: an LDS read takes about as long as three products
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      hv[q] = *reinterpret_cast<const bf16x8 *>(hsrc + q * 16);
+      wv[q] = *reinterpret_cast<const bf16x8 *>(wsrc + q * 16);
+    }
+    for (int i = 0; i < nks; i += 4) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc2[q & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hv[q], wv[q], acc2[q & 1], 0, 0, 0);
+        const int ofs = min(i + 4 + q, nks - 1) * 16;   // past the end: the last step again, never used
+        hv[q] = *reinterpret_cast<const bf16x8 *>(hsrc + ofs);
+        wv[q] = *reinterpret_cast<const bf16x8 *>(wsrc + ofs);
+      }
+    }
+    const int row = blk * 32 + lane;
+    if (lane < 32 && row < nr)
+      for (int r = 0; r < n_em; ++r) {
+        const int ub = ls.emit_ub[r];
+        float v = 0.f;
+#pragma unroll
+        for (int b = 0; b < kLoopMaxB; ++b)
+          if (b == ub) v = (acc2[0][2 * b] + acc2[1][2 * b]) + (acc2[0][2 * b + 1] + acc2[1][2 * b + 1]);
+        recs[ub * nr + row] = v;
+      }
+  };
   // The recurrent half of the gate sums, W_hh h, depends on the hidden vector only, which changes
   // when its utterance emits: it is formed as soon as the new vector is here (while the arrivals of
   // the projection exchange travel), so that a step, once the label is known, only adds the
@@ -391,7 +431,6 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
 
   const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
-  int rec_due = 0, rec_ub[kLoopMaxB] = {0, 0};   // fused form: utterances whose recurrent sums are still to be renewed
   long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
   for (int it = 0; it < lp.max_iters && na > 0; ++it) {
     const int par = it & 1;
@@ -448,9 +487,6 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
           }
         }
       }
-      // While the loads travel: the recurrent sums that the last iteration's new hidden vectors call for
-      // (they are needed by the next LSTM step, not before).
-      if (rec_due) weight_rows_times_h(wl, nr);
       float dot = 0.f, nrm = 0.f;
       const float *pr = pfull + (size_t)arow * Hj + kofs, *wr = wbl + kofs;
       // the LDS operands of a step (projection, blank column) are read one step ahead, into registers that take turns
@@ -500,11 +536,6 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       __syncthreads();
       const long long t1 = dbg ? wall_clock64() : 0;
       if (dbg) tsum[0] += t1 - t0;
-      if (rec_due) {
-        if (tid < nr)
-          for (int r = 0; r < rec_due; ++r) recs[rec_ub[r] * nr + tid] = red_sum(tid, rec_ub[r]);
-        rec_due = 0;
-      }
       // wave w finishes rows 4w .. 4w + 3: lane = (row 4w + (lane >> 4), column lane & 15 of either tile)
       {
         const int rr = lane >> 4, cj = lane & 15, orow = 4 * wave + rr;
@@ -767,8 +798,9 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     const long long t7 = dbg ? wall_clock64() : 0;
     loop_arrive(lp, g, near, passed);                     // exchange 3: the new projections ...
     if constexpr (FUSED) {
-      rec_due = n_emit;
-      for (int r = 0; r < n_emit; ++r) rec_ub[r] = ls.emit_ub[r];
+      // ... and, while wave 0 watches the arrivals, each other wave renews the recurrent sums of a block of 32 gate
+      // rows over the whole of K (they are wanted by the next label's step, not before)
+      if (wave >= 1) recurrent_block(wave - 1, n_emit);
     } else if (tid < nr) {                                // ... and, while the arrivals travel, the recurrent sums are put by
       for (int r = 0; r < n_emit; ++r) {
         const int ub = ls.emit_ub[r];
