@@ -110,30 +110,33 @@ __device__ __forceinline__ void loop_arrive(const LoopDev &lp, int g, bool near,
     st_shared_u32(&lp.bar[(1 + g) * kLoopFlagStride], passed + 1, near);
   }
 }
+// Wave 0's part of the wait: every workgroup publishes the number of barriers it has reached; wave 0 watches
+// all of them, one lane per workgroup (no read-modify-write on a shared word: the arrivals do not queue
+// up).  Leaves the verdict in ls.ok (read by the others behind the next workgroup barrier) and returns it.
+__device__ __forceinline__ bool loop_poll(const LoopDev &lp, unsigned epoch, LoopShared &ls) {
+  unsigned spins = 0;
+  int good = 1;
+  for (;;) {
+    bool here = true;
+    for (int w0 = 0; w0 < lp.G; w0 += 64) {
+      const int w = w0 + (int)threadIdx.x;
+      unsigned v = epoch;
+      if (w < lp.G) v = __hip_atomic_load(&lp.bar[(1 + w) * kLoopFlagStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      here = here && (int)(v - epoch) >= 0;
+    }
+    if (__all(here)) break;
+    const unsigned ab = __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (++spins > lp.spin_limit || ab) { good = 0; break; }
+  }
+  if (threadIdx.x == 0) {
+    if (!good) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ls.ok = good;
+  }
+  return good != 0;
+}
 __device__ __forceinline__ bool loop_wait(const LoopDev &lp, unsigned &passed, LoopShared &ls) {
   const unsigned epoch = ++passed;
-  if (threadIdx.x < 64) {
-    // every workgroup publishes the number of barriers it has reached; wave 0 watches all of them,
-    // one lane per workgroup (no read-modify-write on a shared word: the arrivals do not queue up)
-    unsigned spins = 0;
-    int good = 1;
-    for (;;) {
-      bool here = true;
-      for (int w0 = 0; w0 < lp.G; w0 += 64) {
-        const int w = w0 + (int)threadIdx.x;
-        unsigned v = epoch;
-        if (w < lp.G) v = __hip_atomic_load(&lp.bar[(1 + w) * kLoopFlagStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        here = here && (int)(v - epoch) >= 0;
-      }
-      if (__all(here)) break;
-      const unsigned ab = __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (++spins > lp.spin_limit || ab) { good = 0; break; }
-    }
-    if (threadIdx.x == 0) {
-      if (!good) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      ls.ok = good;
-    }
-  }
+  if (threadIdx.x < 64) loop_poll(lp, epoch, ls);
   __syncthreads();
   asm volatile("" ::: "memory");   // the exchange reads that follow stay behind the wait
   return ls.ok != 0;
@@ -797,23 +800,50 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     }
     const long long t7 = dbg ? wall_clock64() : 0;
     loop_arrive(lp, g, near, passed);                     // exchange 3: the new projections ...
+    long long t8 = 0;
     if constexpr (FUSED) {
-      // ... and, while wave 0 watches the arrivals, each other wave renews the recurrent sums of a block of 32 gate
-      // rows over the whole of K (they are wanted by the next label's step, not before)
-      if (wave >= 1) recurrent_block(wave - 1, n_emit);
-    } else if (tid < nr) {                                // ... and, while the arrivals travel, the recurrent sums are put by
+      // ... and, while wave 0 watches the arrivals and then copies the new projections in, each other wave renews
+      // the recurrent sums of a block of 32 gate rows over the whole of K (they are wanted by the next label's
+      // step, not before)
+      const unsigned epoch = ++passed;
+      if (wave >= 1) {
+        recurrent_block(wave - 1, n_emit);
+      } else if (loop_poll(lp, epoch, ls)) {
+        asm volatile("" ::: "memory");   // the exchange reads that follow stay behind the wait
+        t8 = dbg ? wall_clock64() : 0;
+        constexpr int KP = (128 * kFusedSteps + 63) / 64;   // Hj <= 128 * kFusedSteps
+        for (int r = 0; r < n_emit; ++r) {
+          const int ub = ls.emit_ub[r];
+          float pv[KP];
+#pragma unroll
+          for (int i = 0; i < KP; ++i) {
+            const int k = lane + 64 * i;
+            pv[i] = ld_shared_f32(&lp.p_x[(size_t)ub * Hj + min(k, Hj - 1)]);
+          }
+#pragma unroll
+          for (int i = 0; i < KP; ++i) {
+            const int k = lane + 64 * i;
+            if (k < Hj) pfull[(size_t)ub * Hj + k] = pv[i];
+          }
+        }
+      }
+      __syncthreads();
+      if (!ls.ok) return;
+    } else {
+      if (tid < nr) {                                     // ... and, while the arrivals travel, the recurrent sums are put by
+        for (int r = 0; r < n_emit; ++r) {
+          const int ub = ls.emit_ub[r];
+          recs[ub * nr + tid] = red_sum(tid, ub);
+        }
+      }
+      if (!loop_wait(lp, passed, ls)) return;
+      t8 = dbg ? wall_clock64() : 0;
       for (int r = 0; r < n_emit; ++r) {
         const int ub = ls.emit_ub[r];
-        recs[ub * nr + tid] = red_sum(tid, ub);
+        for (int k = tid; k < Hj; k += 256) pfull[(size_t)ub * Hj + k] = ld_shared_f32(&lp.p_x[(size_t)ub * Hj + k]);
       }
+      __syncthreads();
     }
-    if (!loop_wait(lp, passed, ls)) return;
-    const long long t8 = dbg ? wall_clock64() : 0;
-    for (int r = 0; r < n_emit; ++r) {
-      const int ub = ls.emit_ub[r];
-      for (int k = tid; k < Hj; k += 256) pfull[(size_t)ub * Hj + k] = ld_shared_f32(&lp.p_x[(size_t)ub * Hj + k]);
-    }
-    __syncthreads();
     if (dbg) {
       const long long t9 = wall_clock64();
       tsum[4] += t5 - t4; tsum[5] += t6 - t5; tsum[6] += t7 - t6; tsum[7] += t8 - t7; tsum[8] += t9 - t8; ++n_em_it;
