@@ -354,6 +354,54 @@ struct RowsAhead {
   float vb[kRowsAhead], zn[kRowsAhead];
 };
 
+// What a decided window does to its utterance (Algorithm 2's update, with the cap on labels per frame):
+// i = the smallest row whose label is not blank (label_i), or -1; n = rows of the window.  Writes the
+// label and its frame to the outputs if write_out.  Returns the new state (utterance, t, len, labels
+// on the frame), the label count, flag (bit 0: the utterance goes on, bit 1: it goes on and emitted),
+// the label, and the window's counters packed into one word: n (7 bits), useful rows (7), jump (7),
+// rechecks (7), emitted, forced on, overflow.
+struct WindowOutcome {
+  int4 slot;
+  int cnt, flag, tok;
+  unsigned ev;
+};
+__device__ __forceinline__ WindowOutcome window_outcome(const CallDev &c, int4 st, int cnt, int n, int i, int label_i, int V,
+                                                        int recheck, bool write_out) {
+  const int b = st.x, t = st.y, len = st.z;
+  int tn = t, sym = st.w;
+  int jump, emitted = 0, forced = 0, tok = V, overflow = 0;
+  if (i < 0) {
+    tn += n; sym = 0; jump = n;
+  } else {
+    tok = label_i;
+    if (cnt < c.cap) {
+      if (write_out) {
+        c.out_tokens[(size_t)b * c.cap + cnt] = tok;
+        c.out_frames[(size_t)b * c.cap + cnt] = t + i;
+      }
+      ++cnt;
+    } else {
+      overflow = 1;
+    }
+    tn += i;
+    sym = (i == 0) ? sym + 1 : 1;
+    jump = i;
+    emitted = 1;
+    if (sym >= c.S) { tn += 1; sym = 0; jump += 1; forced = 1; }
+  }
+  if (emitted && write_out) c.out_counts[b] = cnt;
+  const int active = tn < len;
+  WindowOutcome wo;
+  wo.slot = make_int4(b, tn, len, sym);
+  wo.cnt = cnt;
+  wo.flag = active | ((emitted & active) << 1);
+  wo.tok = tok;
+  const int useful = i < 0 ? n : i + 1;
+  wo.ev = (unsigned)n | ((unsigned)useful << 7) | ((unsigned)jump << 14) | ((unsigned)min(recheck, 127) << 21) |
+          ((unsigned)emitted << 28) | ((unsigned)forced << 29) | ((unsigned)overflow << 30);
+  return wo;
+}
+
 // One utterance (slot a of the active list, state st = (utterance, t, len, sym), cnt labels so
 // far), handled by the whole calling workgroup: one wave per window row (rows round-robin over the
 // waves), then the first non-blank row by ballot and the pointer / hypothesis update of
@@ -462,36 +510,10 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
     const unsigned long long mask = __ballot(nb);
     if (lane == 0) {
       const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
-      int tn = t, sym = st.w;
-      int jump, emitted = 0, forced = 0, tok = V, overflow = 0;
-      if (i < 0) {
-        tn += n; sym = 0; jump = n;
-      } else {
-        tok = sh.label[i];
-        if (cnt < c.cap) {
-          if (write_out) {
-            c.out_tokens[(size_t)b * c.cap + cnt] = tok;
-            c.out_frames[(size_t)b * c.cap + cnt] = t + i;
-          }
-          ++cnt;
-        } else {
-          overflow = 1;
-        }
-        tn += i;
-        sym = (i == 0) ? sym + 1 : 1;
-        jump = i;
-        emitted = 1;
-        if (sym >= c.S) { tn += 1; sym = 0; jump += 1; forced = 1; }
-      }
-      if (emitted && write_out) c.out_counts[b] = cnt;
-      const int active = tn < len;
-      const int flag = active | ((emitted & active) << 1);
-      // counters of this window, summed by the compacting wave: n (7 bits), useful rows (7), jump (7),
-      // rechecks (7), emitted, forced, overflow
-      const int useful = i < 0 ? n : i + 1;
-      const unsigned ev = (unsigned)n | ((unsigned)useful << 7) | ((unsigned)jump << 14) |
-                          ((unsigned)min(sh.recheck, 127) << 21) | ((unsigned)emitted << 28) |
-                          ((unsigned)forced << 29) | ((unsigned)overflow << 30);
+      const WindowOutcome wo = window_outcome(c, st, cnt, n, i, i < 0 ? V : sh.label[i], V, sh.recheck, write_out);
+      const int tn = wo.slot.y, sym = wo.slot.w, flag = wo.flag, tok = wo.tok;
+      const unsigned ev = wo.ev;
+      cnt = wo.cnt;
       if (LOCAL) {
         sh.flag[a] = flag; sh.tok[a] = tok; sh.event[a] = ev;
         sh.slot[a] = make_int4(b, tn, len, sym); sh.cnt[a] = cnt;

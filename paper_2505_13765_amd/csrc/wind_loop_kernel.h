@@ -51,6 +51,7 @@ struct LoopShared {
   int ncnt[kLoopMaxB];
   int emit_ub[kLoopMaxB], emit_tok[kLoopMaxB];
   int n_act, n_emit, ok, near;
+  int rechecked[4];   // near-tie rows each wave re-decided in this window
 };
 
 // LDS: [wl: upw*4 rows of Hp+8 bf16][wp: ppw rows of Hp+8 bf16][zs: zrows rows of Hj+8 bf16, at least 16 KB]
@@ -691,6 +692,48 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       __syncthreads();
     }
     const bool quad = direct && c.nparts_tiny <= 32;   // four rows per wave decided at once
+    int n_emit = 0;
+    if (quad && na == 1) {
+      // One utterance: its rows four per wave, then first non-blank row, update, lists and counters in one
+      // go by wave 0: two workgroup barriers in all.
+      const int4 st = sh.slot[0];
+      const int s = lane & 15, j = wave + (lane >> 4) * 4;
+      float2 kA = make_float2(kKeyNone, kKeyNone), kB = kA;
+      float vb = 0.f, zn = 0.f;
+      if (j < W) {
+        if (s < c.nparts_tiny) kA = ld_shared_f32x2(parts + (size_t)j * c.nparts_tiny + s);
+        if (s + 16 < c.nparts_tiny) kB = ld_shared_f32x2(parts + (size_t)j * c.nparts_tiny + s + 16);
+        vb = sh.blank[j];
+        zn = sh.znorm[j];
+      }
+      auto reload = [&](int r, int part) { return ld_shared_f32x2(parts + (size_t)r * c.nparts_tiny + part); };
+      const int rechecked = decide_rows_quad<bf16_t>(m, cl, 0, st, c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
+      if (lane == 0) ls.rechecked[wave] = rechecked;
+      __syncthreads();
+      if (wave == 0) {
+        const int n = min(W, st.z - st.y);
+        const unsigned long long mask = __ballot(lane < n && sh.label[lane] != m.V);
+        if (lane == 0) {
+          const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
+          const int rc = ls.rechecked[0] + ls.rechecked[1] + ls.rechecked[2] + ls.rechecked[3];
+          const WindowOutcome wo = window_outcome(cl, st, sh.cnt[0], n, i, i < 0 ? m.V : sh.label[i], m.V, rc, g == 0);
+          ls.n_act = wo.flag & 1;
+          ls.n_emit = (wo.flag >> 1) & 1;
+          if (wo.flag & 2) { ls.emit_ub[0] = wo.slot.x; ls.emit_tok[0] = wo.tok; }
+          if (wo.flag & 1) { sh.slot[0] = wo.slot; sh.cnt[0] = wo.cnt; }
+          if (g == 0) {
+            const unsigned ev = wo.ev;
+            lstats[ST_ROWS] += ev & 127u; lstats[ST_USEFUL] += (ev >> 7) & 127u; lstats[ST_RECHECK] += (ev >> 21) & 127u;
+            lstats[ST_LABELS] += (ev >> 28) & 1u; lstats[ST_FORCED] += (ev >> 29) & 1u; lstats[ST_OVERFLOW] += (ev >> 30) & 1u;
+            lstats[kStatJump0 + ((ev >> 14) & 127u)] += 1ull;
+            lstats[ST_ITER] += 1ull; lstats[ST_WINDOWS] += 1ull;
+          }
+        }
+      }
+      __syncthreads();
+      na = ls.n_act;
+      n_emit = ls.n_emit;
+    } else {
     for (int a = 0; a < na; ++a) {
       RowsAhead ahead;
       if (quad) {
@@ -749,9 +792,10 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     }
     __syncthreads();
     na = ls.n_act;
-    const int n_emit = ls.n_emit;
+    n_emit = ls.n_emit;
     if (tid < na) { sh.slot[tid] = ls.nslot[tid]; sh.cnt[tid] = ls.ncnt[tid]; }
     __syncthreads();
+    }
     const long long t4 = dbg ? wall_clock64() : 0;
     if (dbg) { tsum[2] += t3 - t2; tsum[3] += t4 - t3; ++n_it; }
     if (n_emit == 0 || na == 0) continue;
