@@ -435,6 +435,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
 
   const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
+  unsigned rs[kStatJump0] = {};   // thread 0 of workgroup 0: counters of the windows it applied itself (fewer than 2^32 each)
   long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
   for (int it = 0; it < lp.max_iters && na > 0; ++it) {
     const int par = it & 1;
@@ -723,10 +724,11 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
           if (wo.flag & 1) { sh.slot[0] = wo.slot; sh.cnt[0] = wo.cnt; }
           if (g == 0) {
             const unsigned ev = wo.ev;
-            lstats[ST_ROWS] += ev & 127u; lstats[ST_USEFUL] += (ev >> 7) & 127u; lstats[ST_RECHECK] += (ev >> 21) & 127u;
-            lstats[ST_LABELS] += (ev >> 28) & 1u; lstats[ST_FORCED] += (ev >> 29) & 1u; lstats[ST_OVERFLOW] += (ev >> 30) & 1u;
+            // this thread's registers take the counters (a chain of read-modify-writes in LDS would be a microsecond)
+            rs[ST_ROWS] += ev & 127u; rs[ST_USEFUL] += (ev >> 7) & 127u; rs[ST_RECHECK] += (ev >> 21) & 127u;
+            rs[ST_LABELS] += (ev >> 28) & 1u; rs[ST_FORCED] += (ev >> 29) & 1u; rs[ST_OVERFLOW] += (ev >> 30) & 1u;
+            rs[ST_ITER] += 1u; rs[ST_WINDOWS] += 1u;
             lstats[kStatJump0 + ((ev >> 14) & 127u)] += 1ull;
-            lstats[ST_ITER] += 1ull; lstats[ST_WINDOWS] += 1ull;
           }
         }
       }
@@ -899,6 +901,9 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
   __syncthreads();
   if (g == 0) {
+    if (tid == 0)
+      for (int i = 0; i < kStatJump0; ++i) lstats[i] += rs[i];
+    __syncthreads();
     for (int i = tid; i < kNumStats; i += 256) c.stats[i] = lstats[i];
     if (tid == 0) {
       c.n_active[0] = na;   // zero unless max_iters ran out
