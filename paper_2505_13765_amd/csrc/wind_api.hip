@@ -622,6 +622,9 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     {
       const int bar_ints = (1 + lp.G) * kLoopFlagStride;
       fill_int_kernel<<<(unsigned)((bar_ints + 255) / 256), 256, 0, s>>>((int *)lp.bar, bar_ints, 0);
+      // the key exchange starts out as "two iterations old": all tag bits set, the first iterations' tag is 0
+      const int key_ints = 2 * kLoopRows * ((m->dev.V + kTinyCols - 1) / kTinyCols) * 2;
+      fill_int_kernel<<<(unsigned)((key_ints + 255) / 256), 256, 0, s>>>((int *)lp.parts_x, key_ints, -1);
     }
     if (lp.zrows == 0) wind_loop_kernel<true><<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);
     else wind_loop_kernel<false><<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);

@@ -52,6 +52,7 @@ struct LoopShared {
   int emit_ub[kLoopMaxB], emit_tok[kLoopMaxB];
   int n_act, n_emit, ok, near;
   int rechecked[4];   // near-tie rows each wave re-decided in this window
+  int fresh[4];       // whether each wave got this iteration's keys (else the kernel ends)
 };
 
 // LDS: [wl: upw*4 rows of Hp+8 bf16][wp: ppw rows of Hp+8 bf16][zs: zrows rows of Hj+8 bf16, at least 16 KB]
@@ -435,6 +436,36 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
 
   const bool dbg = c.dbg != nullptr && g == 0 && tid == 0;
+  // With at most 64 parts per row and 4 rows per wave the decision only looks at the keys its caller hands it,
+  // read straight from the exchange buffer; with at most 32 parts a wave decides four rows at once.  In the
+  // fused form those keys carry the iteration's parity (key_with_tag), and the first exchange has no barrier:
+  // a reader asks for the keys until all it needs are this iteration's.
+  const bool direct = c.nparts_tiny <= 64 && W <= 4 * kRowsAhead;
+  const bool quad = direct && c.nparts_tiny <= 32;
+  const bool tagged = FUSED && quad;
+  // The two key pairs (parts s and s + 16) of window row `row` for the four-rows-at-once decision.  Tagged keys are
+  // asked for again until every lane of the wave has this iteration's (bounded like a barrier's wait: false when
+  // the limit is reached or another workgroup gave up); the tag is taken out again.
+  auto read_quad_keys = [&](const float2 *parts, int row, bool in_window, int s, int tag, float2 &kA, float2 &kB) {
+    const float2 none = make_float2(kKeyNone, kKeyNone);
+    const bool hasA = in_window && s < c.nparts_tiny, hasB = in_window && s + 16 < c.nparts_tiny;
+    unsigned spins = 0;
+    for (;;) {
+      kA = hasA ? ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s) : none;
+      kB = hasB ? ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s + 16) : none;
+      if (!tagged) return true;
+      const bool fresh = (!hasA || key_tag(kA.y) == tag) && (!hasB || key_tag(kB.y) == tag);
+      if (__all(fresh)) break;
+      const unsigned ab = __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (++spins > lp.spin_limit || ab) {
+        if (lane == 0) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return false;
+      }
+    }
+    kA.y = key_with_tag(kA.y, 0);
+    kB.y = key_with_tag(kB.y, 0);
+    return true;
+  };
   unsigned rs[kStatJump0] = {};   // thread 0 of workgroup 0: counters of the windows it applied itself (fewer than 2^32 each)
   long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
   for (int it = 0; it < lp.max_iters && na > 0; ++it) {
@@ -556,6 +587,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
         merge_top2(k1, k2, dpp_f32<kDppRowHalfMirror>(k1), dpp_f32<kDppRowHalfMirror>(k2));
         merge_top2(k1, k2, dpp_f32<kDppQuadXor2>(k1), dpp_f32<kDppQuadXor2>(k2));
         merge_top2(k1, k2, dpp_f32<kDppQuadXor1>(k1), dpp_f32<kDppQuadXor1>(k2));
+        if (tagged) k2 = key_with_tag(k2, (it >> 1) & 1);
         if (has_cols && cj == 0) st_shared_f32x2(&parts[(size_t)orow * c.nparts_tiny + g], make_float2(k1, k2), near);
       }
       if (tid < 16 && tid < n_rows) {
@@ -680,37 +712,41 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       if (dbg) tsum[1] += wall_clock64() - t1;
     }
     const long long t2 = dbg ? wall_clock64() : 0;
-    if (!loop_barrier(lp, g, near, passed, ls)) return;   // exchange 1: every row's keys are in memory
+    if (tagged) __syncthreads();                           // exchange 1: tagged keys, asked for until they are this iteration's;
+    else if (!loop_barrier(lp, g, near, passed, ls)) return;   // ... otherwise behind a barrier: every row's keys are in memory
     const long long t3 = dbg ? wall_clock64() : 0;
     // ---- the decisions, taken alike by every workgroup; workgroup 0 writes the outputs
     // With at most 64 parts per row and 4 rows per wave the decision only looks at the keys its
     // caller hands it, which are read here straight from the exchange buffer; otherwise the keys
     // are copied to LDS first.
     float2 *lparts = reinterpret_cast<float2 *>(zs);
-    const bool direct = c.nparts_tiny <= 64 && W <= 4 * kRowsAhead;
     if (!direct) {
       for (int i = tid; i < n_rows * c.nparts_tiny; i += 256) lparts[i] = ld_shared_f32x2(parts + i);
       __syncthreads();
     }
-    const bool quad = direct && c.nparts_tiny <= 32;   // four rows per wave decided at once
     int n_emit = 0;
     if (quad && na == 1) {
       // One utterance: its rows four per wave, then first non-blank row, update, lists and counters in one
       // go by wave 0: two workgroup barriers in all.
       const int4 st = sh.slot[0];
       const int s = lane & 15, j = wave + (lane >> 4) * 4;
-      float2 kA = make_float2(kKeyNone, kKeyNone), kB = kA;
+      float2 kA, kB;
+      const bool fresh = read_quad_keys(parts, j, j < W, s, (it >> 1) & 1, kA, kB);
       float vb = 0.f, zn = 0.f;
       if (j < W) {
-        if (s < c.nparts_tiny) kA = ld_shared_f32x2(parts + (size_t)j * c.nparts_tiny + s);
-        if (s + 16 < c.nparts_tiny) kB = ld_shared_f32x2(parts + (size_t)j * c.nparts_tiny + s + 16);
         vb = sh.blank[j];
         zn = sh.znorm[j];
       }
-      auto reload = [&](int r, int part) { return ld_shared_f32x2(parts + (size_t)r * c.nparts_tiny + part); };
-      const int rechecked = decide_rows_quad<bf16_t>(m, cl, 0, st, c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
-      if (lane == 0) ls.rechecked[wave] = rechecked;
+      auto reload = [&](int r, int part) {
+        float2 k = ld_shared_f32x2(parts + (size_t)r * c.nparts_tiny + part);
+        if (tagged) k.y = key_with_tag(k.y, 0);
+        return k;
+      };
+      int rechecked = 0;
+      if (fresh) rechecked = decide_rows_quad<bf16_t>(m, cl, 0, st, c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
+      if (lane == 0) { ls.rechecked[wave] = rechecked; ls.fresh[wave] = fresh; }
       __syncthreads();
+      if (!(ls.fresh[0] && ls.fresh[1] && ls.fresh[2] && ls.fresh[3])) return;   // some wave gave up waiting for keys
       if (wave == 0) {
         const int n = min(W, st.z - st.y);
         const unsigned long long mask = __ballot(lane < n && sh.label[lane] != m.V);
@@ -740,15 +776,19 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       RowsAhead ahead;
       if (quad) {
         const int s = lane & 15, j = wave + (lane >> 4) * 4, row = a * W + j;
-        float2 kA = make_float2(kKeyNone, kKeyNone), kB = kA;
+        float2 kA, kB;
+        const bool fresh = read_quad_keys(parts, row, j < W, s, (it >> 1) & 1, kA, kB);
+        if (tagged && !__syncthreads_and(fresh)) return;   // some wave gave up waiting for keys
         float vb = 0.f, zn = 0.f;
         if (j < W) {
-          if (s < c.nparts_tiny) kA = ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s);
-          if (s + 16 < c.nparts_tiny) kB = ld_shared_f32x2(parts + (size_t)row * c.nparts_tiny + s + 16);
           vb = sh.blank[row];
           zn = sh.znorm[row];
         }
-        auto reload = [&](int r, int part) { return ld_shared_f32x2(parts + (size_t)r * c.nparts_tiny + part); };
+        auto reload = [&](int r, int part) {
+          float2 k = ld_shared_f32x2(parts + (size_t)r * c.nparts_tiny + part);
+          if (tagged) k.y = key_with_tag(k.y, 0);
+          return k;
+        };
         const int rechecked = decide_rows_quad<bf16_t>(m, cl, a, sh.slot[a], c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
         decide_utterance<bf16_t, true>(m, cl, a, sh.slot[a], sh.cnt[a], 0, c.nparts_tiny, c.nparts_tiny, kTinyCols, ahead, sh,
                                        g == 0, true, rechecked);

@@ -119,6 +119,16 @@ __device__ __forceinline__ float make_key(float v, int col_in_part) {
 __device__ __forceinline__ int key_col(float k) { return (int)(kKeyColMask - (__float_as_uint(k) & kKeyColMask)); }
 __device__ __forceinline__ float key_val(float k) { return __uint_as_float(__float_as_uint(k) & ~kKeyColMask); }
 
+// A tag bit in a key: the lowest bit of the value field (one more bit of truncation, 2^-15 relative in all).
+// The resident loop kernel marks the second key of every (first, second) pair it exchanges with the
+// iteration's parity, so that a reader can tell this iteration's pair from the one two iterations old
+// without a separate flag.
+constexpr uint32_t kKeyTagBit = 128u;
+__device__ __forceinline__ float key_with_tag(float k, int tag) {
+  return __uint_as_float((__float_as_uint(k) & ~kKeyTagBit) | (tag ? kKeyTagBit : 0u));
+}
+__device__ __forceinline__ int key_tag(float k) { return (int)((__float_as_uint(k) >> 7) & 1u); }
+
 // top-2 of the union of two sorted pairs (a1 >= a2), (b1 >= b2)
 __device__ __forceinline__ void merge_top2(float &a1, float &a2, float b1, float b2) {
   const float m = fmaxf(a2, b2);
