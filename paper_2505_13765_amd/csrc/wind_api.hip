@@ -539,8 +539,10 @@ int fetch_stats(wind_model *m, hipStream_t s) {
 // at most one workgroup per CU.  First choice: at most 32 workgroups, which fit the CUs of one XCD
 // and then exchange through its L2 (window rows limited to 16 so that the larger weight slices
 // still fit LDS); otherwise 16 units per workgroup, spread over the chip.
-bool loop_kernel_shape(const wind_model *m, int B, int W, LoopDev *lp, size_t *smem) {
+bool loop_kernel_shape(const wind_model *m, int B, int T, int W, LoopDev *lp, size_t *smem) {
   const ModelDev &d = m->dev;
+  // the kernel indexes the projected frames, the label table and the exchange buffers with 32 bits
+  if ((unsigned long long)B * (unsigned long long)T * d.Hj >= (1ull << 31) || (unsigned long long)(d.V + 1) * 4 * d.Hp >= (1ull << 31)) return false;
   if (m->dtype != WIND_BF16 || d.L != 1 || B > kLoopMaxB || B * W > kLoopRows || d.Hj > kTinyMaxHj) return false;
   if (!m->opt_loop_kernel || m->opt_profile || !m->opt_graph || m->opt_host_sync) return false;
   const int nparts_tiny = (d.V + kTinyCols - 1) / kTinyCols;
@@ -605,7 +607,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
 
   LoopDev lp = m->loop;
   size_t loop_smem = 0;
-  const bool use_loop = loop_kernel_shape(m, B, W, &lp, &loop_smem);
+  const bool use_loop = loop_kernel_shape(m, B, T, W, &lp, &loop_smem);
   const long long max_iters = (long long)T * ((long long)S + 1) + 2;   // every iteration moves some pointer or emits
   m->loop_info[0] = m->loop_info[1] = 0;
   m->fma_pred_step = use_loop;   // the resident kernel starts from the fp32 state of the start-token step
@@ -626,8 +628,18 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
       const int key_ints = 2 * kLoopRows * ((m->dev.V + kTinyCols - 1) / kTinyCols) * 2;
       fill_int_kernel<<<(unsigned)((key_ints + 255) / 256), 256, 0, s>>>((int *)lp.parts_x, key_ints, -1);
     }
-    if (lp.zrows == 0) wind_loop_kernel<true><<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);
-    else wind_loop_kernel<false><<<(unsigned)(lp.G * lp.step), 256, loop_smem, s>>>(m->dev, c, lp);
+    {
+      const dim3 grid((unsigned)(lp.G * lp.step));
+      switch (lp.zrows == 0 ? m->dev.Hj / 128 : 0) {   // fused form: one instance per number of K steps
+        case 0: wind_loop_kernel<0><<<grid, 256, loop_smem, s>>>(m->dev, c, lp); break;
+        case 1: wind_loop_kernel<1><<<grid, 256, loop_smem, s>>>(m->dev, c, lp); break;
+        case 2: wind_loop_kernel<2><<<grid, 256, loop_smem, s>>>(m->dev, c, lp); break;
+        case 3: wind_loop_kernel<3><<<grid, 256, loop_smem, s>>>(m->dev, c, lp); break;
+        case 4: wind_loop_kernel<4><<<grid, 256, loop_smem, s>>>(m->dev, c, lp); break;
+        case 5: wind_loop_kernel<5><<<grid, 256, loop_smem, s>>>(m->dev, c, lp); break;
+        default: return fail(WIND_ERR_UNSUPPORTED, "resident loop: no fused instance for this joint width");
+      }
+    }
     rc = check_launch("resident loop");
     if (rc) return rc;
     HIP_TRY(hipEventRecord(m->ev_call[2], s));
@@ -853,10 +865,11 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   }
   if (rc == WIND_OK) {
     hipError_t e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)wind_loop_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLoopMaxSmem);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)wind_loop_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLoopMaxSmem);
+    static_assert(kFusedSteps == 5, "one resident loop instance per number of fused K steps: here and at the launch");
+    const void *loop_instances[] = {(const void *)wind_loop_kernel<0>, (const void *)wind_loop_kernel<1>, (const void *)wind_loop_kernel<2>,
+                                    (const void *)wind_loop_kernel<3>, (const void *)wind_loop_kernel<4>, (const void *)wind_loop_kernel<5>};
+    for (const void *k : loop_instances)
+      if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLoopMaxSmem);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)joint_mfma_store_kernel<JointCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, JointCfg::SMEM_BYTES);

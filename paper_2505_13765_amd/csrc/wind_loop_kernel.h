@@ -51,8 +51,7 @@ struct LoopShared {
   int ncnt[kLoopMaxB];
   int emit_ub[kLoopMaxB], emit_tok[kLoopMaxB];
   int n_act, n_emit, ok, near;
-  int rechecked[4];   // near-tie rows each wave re-decided in this window
-  int fresh[4];       // whether each wave got this iteration's keys (else the kernel ends)
+  int rechecked[4];   // near-tie rows each wave re-decided in this window; -1: the wave did not get this iteration's keys (the kernel ends)
 };
 
 // LDS: [wl: upw*4 rows of Hp+8 bf16][wp: ppw rows of Hp+8 bf16][zs: zrows rows of Hj+8 bf16, at least 16 KB]
@@ -127,8 +126,10 @@ __device__ __forceinline__ bool loop_poll(const LoopDev &lp, unsigned epoch, Loo
       here = here && (int)(v - epoch) >= 0;
     }
     if (__all(here)) break;
-    const unsigned ab = __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (++spins > lp.spin_limit || ab) { good = 0; break; }
+    // the word that says another workgroup gave up is looked at every sixteenth time only: asking for it
+    // takes as long as asking for the arrivals again
+    if (++spins > lp.spin_limit) { good = 0; break; }
+    if ((spins & 15u) == 0 && __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { good = 0; break; }
   }
   if (threadIdx.x == 0) {
     if (!good) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -220,8 +221,12 @@ __device__ __forceinline__ void loop_rows_times_h(const bf16_t *hsrc, const bf16
   }
 }
 
-template <bool FUSED>
+// NS: 0 = the window rows go through LDS; 1 .. kFusedSteps = the fused form for Hj = 128 NS (the number of
+// K steps of 32 in a wave's quarter of K; a constant, because matrix-core products under a condition
+// make the compiler move the accumulators in and out of their registers around every step).
+template <int NS>
 __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, LoopDev lp) {
+  constexpr bool FUSED = NS > 0;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   __shared__ DecideShared sh;
   __shared__ LoopShared ls;
@@ -303,8 +308,8 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   const bool col_ok = has_cols && col < m.V;
   const float col_bias = col_ok ? m.b_out[col_ok ? col : 0] : kKeyNone;
   // fused form: 16 x 16 x 32 products, two tiles of 16 columns, lane = (column lane & 15, K group lane >> 4)
-  const int ns32 = kq >> 5;
-  bf16x8 bfrag16[FUSED ? 2 : 1][FUSED ? kFusedSteps : 1];
+  constexpr int ns32 = FUSED ? NS : 1;   // = (Hj / 4) / 32 in the fused form
+  bf16x8 bfrag16[FUSED ? 2 : 1][ns32];
   float bias16[2] = {kKeyNone, kKeyNone};
   bool ok16[2] = {false, false};
   if constexpr (FUSED) {
@@ -315,8 +320,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       if (ok16[t]) bias16[t] = m.b_out[cc];
       const bf16_t *wr = reinterpret_cast<const bf16_t *>(m.w_out) + (size_t)cc * Hj + k0 + (lane >> 4) * 8;   // rows up to Vpad exist
 #pragma unroll
-      for (int i = 0; i < kFusedSteps; ++i)
-        if (i < ns32) bfrag16[t][i] = *reinterpret_cast<const bf16x8 *>(wr + i * 32);
+      for (int i = 0; i < ns32; ++i) bfrag16[t][i] = *reinterpret_cast<const bf16x8 *>(wr + i * 32);
     }
     for (int k = tid; k < Hj; k += 256) wbl[k] = m.w_blank[k];
   }
@@ -456,8 +460,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       if (!tagged) return true;
       const bool fresh = (!hasA || key_tag(kA.y) == tag) && (!hasB || key_tag(kB.y) == tag);
       if (__all(fresh)) break;
-      const unsigned ab = __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (++spins > lp.spin_limit || ab) {
+      if (++spins > lp.spin_limit || ((spins & 15u) == 0 && __hip_atomic_load(lp.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
         if (lane == 0) __hip_atomic_store(lp.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return false;
       }
@@ -466,7 +469,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
     kB.y = key_with_tag(kB.y, 0);
     return true;
   };
-  unsigned rs[kStatJump0] = {};   // thread 0 of workgroup 0: counters of the windows it applied itself (fewer than 2^32 each)
+  unsigned rs[kStatJump0] = {};   // thread 64 of workgroup 0: counters of the single-utterance windows (fewer than 2^32 each)
   long long tsum[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, n_it = 0, n_em_it = 0;
   for (int it = 0; it < lp.max_iters && na > 0; ++it) {
     const int par = it & 1;
@@ -486,42 +489,40 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       // product against the W_out fragments in registers.  The fp32 blank logit and norm of the row
       // are summed over the K groups by lane exchanges and over the waves through LDS, like the products.
       const int row = lane & 15, kofs = k0 + (lane >> 4) * 8;
-      bool valid = false;
+      // A row past the utterance's end (or past the last window) reads the utterance's first frame instead:
+      // nothing looks at what such a row yields, and loads under a lane's condition would have to wait
+      // for and merge with the registers' old values.
       int arow = 0;
-      const float *er = c.e;
+      unsigned eofs = 0;   // the host has checked that B * T * Hj fits 32 bits
       if (row < n_rows) {
         const int a = row >= W ? 1 : 0, j = row - a * W;   // at most two utterances
         const int4 st = sh.slot[a];
-        valid = st.y + j < st.z;
         arow = st.x;
-        er = c.e + ((size_t)st.x * c.T + (valid ? st.y + j : 0)) * Hj;
+        eofs = ((unsigned)st.x * (unsigned)c.T + (unsigned)(st.y + j < st.z ? st.y + j : 0)) * (unsigned)Hj;
       }
-      float4 ev[kFusedSteps][2];
+      const float *er = c.e + eofs + kofs;
+      float4 ev[ns32][2];
 #pragma unroll
-      for (int i = 0; i < kFusedSteps; ++i) {
-        ev[i][0] = make_float4(0.f, 0.f, 0.f, 0.f);
-        ev[i][1] = ev[i][0];
-        if (valid && i < ns32) {
-          ev[i][0] = *reinterpret_cast<const float4 *>(er + kofs + i * 32);
-          ev[i][1] = *reinterpret_cast<const float4 *>(er + kofs + i * 32 + 4);
-        }
+      for (int i = 0; i < ns32; ++i) {
+        ev[i][0] = *reinterpret_cast<const float4 *>(er + i * 32);
+        ev[i][1] = *reinterpret_cast<const float4 *>(er + i * 32 + 4);
       }
       // Touch the lines of the window after this one, so that they sit in L2 when it is their turn.  The
       // values are consumed one iteration later (each into a register of its own: nothing waits for them here).
       {
         const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
-        // every load is issued by every lane, with its row and line clamped into the utterance's frames: a
-        // load under a condition would have to merge with the register's old value, and wait for it
+        // every lane issues every load, with its row and line clamped into the utterance's frames
+        const int l = min(tid & 31, lines_per_row - 1);
 #pragma unroll
-        for (int a = 0; a < kLoopMaxB; ++a) {
-          const int4 st = sh.slot[min(a, na - 1)];
-          const int l = min(tid & 31, lines_per_row - 1);
+        for (int a = 0; a < kLoopMaxB; ++a)
+          if (a < na) {
+            const int4 st = sh.slot[a];
 #pragma unroll
-          for (int i2 = 0; i2 < kTouchSteps; ++i2) {
-            const int tr = max(min(st.y + W + (tid >> 5) + 8 * i2, st.z - 1), 0);
-            pend[a * kTouchSteps + i2] = c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+            for (int i2 = 0; i2 < kTouchSteps; ++i2) {
+              const int tr = max(min(st.y + W + (tid >> 5) + 8 * i2, st.z - 1), 0);
+              pend[a * kTouchSteps + i2] = c.e[((unsigned)st.x * (unsigned)c.T + (unsigned)tr) * (unsigned)Hj + (unsigned)(l * 32)];
+            }
           }
-        }
       }
       float dot = 0.f, nrm = 0.f;
       const float *pr = pfull + (size_t)arow * Hj + kofs, *wr = wbl + kofs;
@@ -534,26 +535,23 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       };
       read_ops(0, 0);
 #pragma unroll
-      for (int i = 0; i < kFusedSteps; ++i)
-        if (i < ns32) {
-          read_ops((i + 1) & 1, i + 1);
-          const float4 p0 = po[i & 1][0], p1 = po[i & 1][1], w0 = wo[i & 1][0], w1 = wo[i & 1][1];
-          float x[8];
-          x[0] = fmaxf(ev[i][0].x + p0.x, 0.f); x[1] = fmaxf(ev[i][0].y + p0.y, 0.f);
-          x[2] = fmaxf(ev[i][0].z + p0.z, 0.f); x[3] = fmaxf(ev[i][0].w + p0.w, 0.f);
-          x[4] = fmaxf(ev[i][1].x + p1.x, 0.f); x[5] = fmaxf(ev[i][1].y + p1.y, 0.f);
-          x[6] = fmaxf(ev[i][1].z + p1.z, 0.f); x[7] = fmaxf(ev[i][1].w + p1.w, 0.f);
+      for (int i = 0; i < ns32; ++i) {
+        read_ops((i + 1) & 1, i + 1);
+        const float4 p0 = po[i & 1][0], p1 = po[i & 1][1], w0 = wo[i & 1][0], w1 = wo[i & 1][1];
+        float x[8];
+        x[0] = fmaxf(ev[i][0].x + p0.x, 0.f); x[1] = fmaxf(ev[i][0].y + p0.y, 0.f);
+        x[2] = fmaxf(ev[i][0].z + p0.z, 0.f); x[3] = fmaxf(ev[i][0].w + p0.w, 0.f);
+        x[4] = fmaxf(ev[i][1].x + p1.x, 0.f); x[5] = fmaxf(ev[i][1].y + p1.y, 0.f);
+        x[6] = fmaxf(ev[i][1].z + p1.z, 0.f); x[7] = fmaxf(ev[i][1].w + p1.w, 0.f);
+        dot = fmaf(x[0], w0.x, dot); dot = fmaf(x[1], w0.y, dot); dot = fmaf(x[2], w0.z, dot); dot = fmaf(x[3], w0.w, dot);
+        dot = fmaf(x[4], w1.x, dot); dot = fmaf(x[5], w1.y, dot); dot = fmaf(x[6], w1.z, dot); dot = fmaf(x[7], w1.w, dot);
 #pragma unroll
-          for (int e2 = 0; e2 < 8; ++e2) x[e2] = valid ? x[e2] : 0.f;   // rows past the utterance's end are zero rows
-          dot = fmaf(x[0], w0.x, dot); dot = fmaf(x[1], w0.y, dot); dot = fmaf(x[2], w0.z, dot); dot = fmaf(x[3], w0.w, dot);
-          dot = fmaf(x[4], w1.x, dot); dot = fmaf(x[5], w1.y, dot); dot = fmaf(x[6], w1.z, dot); dot = fmaf(x[7], w1.w, dot);
-#pragma unroll
-          for (int e2 = 0; e2 < 8; ++e2) nrm = fmaf(x[e2], x[e2], nrm);
-          const u32x4 zu = u32x4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
-          const bf16x8 zf = __builtin_bit_cast(bf16x8, zu);
-          facc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf, bfrag16[0][i], facc[0], 0, 0, 0);
-          facc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf, bfrag16[1][i], facc[1], 0, 0, 0);
-        }
+        for (int e2 = 0; e2 < 8; ++e2) nrm = fmaf(x[e2], x[e2], nrm);
+        const u32x4 zu = u32x4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
+        const bf16x8 zf = __builtin_bit_cast(bf16x8, zu);
+        facc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf, bfrag16[0][i], facc[0], 0, 0, 0);
+        facc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(zf, bfrag16[1][i], facc[1], 0, 0, 0);
+      }
       dot += __shfl_xor(dot, 16, kWave); nrm += __shfl_xor(nrm, 16, kWave);
       dot += __shfl_xor(dot, 32, kWave); nrm += __shfl_xor(nrm, 32, kWave);
       // partial sums of this wave's quarter of K: fred[wave][tile][r][80] (register r of lane l: row 4 * (l >> 4) + r,
@@ -616,7 +614,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
             const int4 st = sh.slot[a];
             valid[q] = st.y + j < st.z;
             arow[q] = st.x;
-            er = c.e + ((size_t)st.x * c.T + (valid[q] ? st.y + j : 0)) * Hj;
+            er = c.e + ((unsigned)st.x * (unsigned)c.T + (unsigned)(valid[q] ? st.y + j : 0)) * (unsigned)Hj;   // fits 32 bits: checked by the host
           }
   #pragma unroll
           for (int i = 0; i < KI; ++i) {
@@ -660,18 +658,19 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       // values are consumed one iteration later (each into a register of its own: nothing waits for them here).
       {
         const int lines_per_row = (Hj * 4 + 127) / 128;   // at most 32: eight rows per step, 32 lanes each
-        // every load is issued by every lane, with its row and line clamped into the utterance's frames: a
-        // load under a condition would have to merge with the register's old value, and wait for it
+        // every lane issues every load, with its row and line clamped into the utterance's frames: a load
+        // under a lane's condition would have to merge with the register's old value, and wait for it
+        const int l = min(tid & 31, lines_per_row - 1);
 #pragma unroll
-        for (int a = 0; a < kLoopMaxB; ++a) {
-          const int4 st = sh.slot[min(a, na - 1)];
-          const int l = min(tid & 31, lines_per_row - 1);
+        for (int a = 0; a < kLoopMaxB; ++a)
+          if (a < na) {
+            const int4 st = sh.slot[a];
 #pragma unroll
-          for (int i2 = 0; i2 < kTouchSteps; ++i2) {
-            const int tr = max(min(st.y + W + (tid >> 5) + 8 * i2, st.z - 1), 0);
-            pend[a * kTouchSteps + i2] = c.e[((size_t)st.x * c.T + tr) * Hj + l * 32];
+            for (int i2 = 0; i2 < kTouchSteps; ++i2) {
+              const int tr = max(min(st.y + W + (tid >> 5) + 8 * i2, st.z - 1), 0);
+              pend[a * kTouchSteps + i2] = c.e[((unsigned)st.x * (unsigned)c.T + (unsigned)tr) * (unsigned)Hj + (unsigned)(l * 32)];
+            }
           }
-        }
       }
       __syncthreads();
       const long long t1 = dbg ? wall_clock64() : 0;
@@ -744,27 +743,33 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       };
       int rechecked = 0;
       if (fresh) rechecked = decide_rows_quad<bf16_t>(m, cl, 0, st, c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
-      if (lane == 0) { ls.rechecked[wave] = rechecked; ls.fresh[wave] = fresh; }
+      if (lane == 0) ls.rechecked[wave] = fresh ? rechecked : -1;
       __syncthreads();
-      if (!(ls.fresh[0] && ls.fresh[1] && ls.fresh[2] && ls.fresh[3])) return;   // some wave gave up waiting for keys
-      if (wave == 0) {
+      // what the rest needs from LDS, asked for in one go: the waves' verdicts, the rows' labels, the label count
+      const int v0 = ls.rechecked[0], v1 = ls.rechecked[1], v2 = ls.rechecked[2], v3 = ls.rechecked[3];
+      const int lab = sh.label[lane & 15], cnt0 = sh.cnt[0];
+      if ((v0 | v1 | v2 | v3) < 0) return;   // some wave gave up waiting for keys
+      // Wave 0 applies the outcome to the loop's own state; in workgroup 0 wave 1 works out the same outcome beside
+      // it and does what only the caller sees: the outputs and the call's counters.
+      if (wave == 0 || (wave == 1 && g == 0)) {
         const int n = min(W, st.z - st.y);
-        const unsigned long long mask = __ballot(lane < n && sh.label[lane] != m.V);
+        const unsigned long long mask = __ballot(lane < n && lab != m.V);
+        const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
+        const int label_i = i < 0 ? m.V : __builtin_amdgcn_readlane(lab, i);
         if (lane == 0) {
-          const int i = mask ? __ffsll((long long)mask) - 1 : -1;   // smallest i with labels[i] != blank
-          const int rc = ls.rechecked[0] + ls.rechecked[1] + ls.rechecked[2] + ls.rechecked[3];
-          const WindowOutcome wo = window_outcome(cl, st, sh.cnt[0], n, i, i < 0 ? m.V : sh.label[i], m.V, rc, g == 0);
-          ls.n_act = wo.flag & 1;
-          ls.n_emit = (wo.flag >> 1) & 1;
-          if (wo.flag & 2) { ls.emit_ub[0] = wo.slot.x; ls.emit_tok[0] = wo.tok; }
-          if (wo.flag & 1) { sh.slot[0] = wo.slot; sh.cnt[0] = wo.cnt; }
-          if (g == 0) {
+          const WindowOutcome wo = window_outcome(cl, st, cnt0, n, i, label_i, m.V, v0 + v1 + v2 + v3, wave == 1);
+          if (wave == 0) {
+            ls.n_act = wo.flag & 1;
+            ls.n_emit = (wo.flag >> 1) & 1;
+            if (wo.flag & 2) { ls.emit_ub[0] = wo.slot.x; ls.emit_tok[0] = wo.tok; }
+            if (wo.flag & 1) { sh.slot[0] = wo.slot; sh.cnt[0] = wo.cnt; }
+          } else {
             const unsigned ev = wo.ev;
             // this thread's registers take the counters (a chain of read-modify-writes in LDS would be a microsecond)
             rs[ST_ROWS] += ev & 127u; rs[ST_USEFUL] += (ev >> 7) & 127u; rs[ST_RECHECK] += (ev >> 21) & 127u;
             rs[ST_LABELS] += (ev >> 28) & 1u; rs[ST_FORCED] += (ev >> 29) & 1u; rs[ST_OVERFLOW] += (ev >> 30) & 1u;
             rs[ST_ITER] += 1u; rs[ST_WINDOWS] += 1u;
-            lstats[kStatJump0 + ((ev >> 14) & 127u)] += 1ull;
+            atomicAdd(&lstats[kStatJump0 + ((ev >> 14) & 127u)], 1ull);   // nobody waits for the sum
           }
         }
       }
@@ -897,20 +902,14 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       } else if (loop_poll(lp, epoch, ls)) {
         asm volatile("" ::: "memory");   // the exchange reads that follow stay behind the wait
         t8 = dbg ? wall_clock64() : 0;
-        constexpr int KP = (128 * kFusedSteps + 63) / 64;   // Hj <= 128 * kFusedSteps
+        constexpr int KP = 2 * ns32;   // Hj = 128 NS = 64 KP
         for (int r = 0; r < n_emit; ++r) {
           const int ub = ls.emit_ub[r];
           float pv[KP];
 #pragma unroll
-          for (int i = 0; i < KP; ++i) {
-            const int k = lane + 64 * i;
-            pv[i] = ld_shared_f32(&lp.p_x[(size_t)ub * Hj + min(k, Hj - 1)]);
-          }
+          for (int i = 0; i < KP; ++i) pv[i] = ld_shared_f32(&lp.p_x[(unsigned)(ub * Hj + lane + 64 * i)]);
 #pragma unroll
-          for (int i = 0; i < KP; ++i) {
-            const int k = lane + 64 * i;
-            if (k < Hj) pfull[(size_t)ub * Hj + k] = pv[i];
-          }
+          for (int i = 0; i < KP; ++i) pfull[ub * Hj + lane + 64 * i] = pv[i];
         }
       }
       __syncthreads();
@@ -941,7 +940,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
   }
   __syncthreads();
   if (g == 0) {
-    if (tid == 0)
+    if (tid == 64)   // the thread that kept the counters of the windows of single utterances
       for (int i = 0; i < kStatJump0; ++i) lstats[i] += rs[i];
     __syncthreads();
     for (int i = tid; i < kNumStats; i += 256) c.stats[i] = lstats[i];
