@@ -728,6 +728,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       // One utterance: its rows four per wave, then first non-blank row, update, lists and counters in one
       // go by wave 0: two workgroup barriers in all.
       const int4 st = sh.slot[0];
+      const int cnt0 = sh.cnt[0];   // read on this side of the workgroup barrier below: wave 0 writes the new count right behind it
       const int s = lane & 15, j = wave + (lane >> 4) * 4;
       float2 kA, kB;
       const bool fresh = read_quad_keys(parts, j, j < W, s, (it >> 1) & 1, kA, kB);
@@ -745,9 +746,9 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
       if (fresh) rechecked = decide_rows_quad<bf16_t>(m, cl, 0, st, c.nparts_tiny, kTinyCols, kA, kB, vb, zn, j, reload, sh);
       if (lane == 0) ls.rechecked[wave] = fresh ? rechecked : -1;
       __syncthreads();
-      // what the rest needs from LDS, asked for in one go: the waves' verdicts, the rows' labels, the label count
+      // what the rest needs from LDS, asked for in one go: the waves' verdicts and the rows' labels
       const int v0 = ls.rechecked[0], v1 = ls.rechecked[1], v2 = ls.rechecked[2], v3 = ls.rechecked[3];
-      const int lab = sh.label[lane & 15], cnt0 = sh.cnt[0];
+      const int lab = sh.label[lane & 15];
       if ((v0 | v1 | v2 | v3) < 0) return;   // some wave gave up waiting for keys
       // Wave 0 applies the outcome to the loop's own state; in workgroup 0 wave 1 works out the same outcome beside
       // it and does what only the caller sees: the outputs and the call's counters.
@@ -854,7 +855,7 @@ __global__ __launch_bounds__(256) void wind_loop_kernel(ModelDev m, CallDev c, L
         const int ul = tid >> 2, gate = tid & 3, unit = unit0 + ul;
         const bool ok = unit < Hp;
         float pre = 0.f;
-        if (ok) pre = recs[ub * nr + tid] + m.emb_gates[(size_t)tok * 4 * Hp + (size_t)unit0 * 4 + tid];
+        if (ok) pre = recs[ub * nr + tid] + m.emb_gates[(unsigned)tok * 4u * (unsigned)Hp + (unsigned)(unit0 * 4 + tid)];   // fits 32 bits: checked by the host
         const float act = gate == 2 ? tanhf(pre) : 1.f / (1.f + expf(-pre));
         const int base = lane & ~3;
         const float ig = __shfl(act, base, kWave), fg = __shfl(act, base + 1, kWave);
