@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwind.so")
 SOURCES = ["wind_api.hip"]
 DEPS = ["wind_api.hip", "wind_kernels.h", "wind_types.h", "wind_enc_kernels.h", "wind_joint_kernels.h", "wind_decide_kernels.h",
-        "wind_pred_kernels.h", "wind_loop_kernel.h", "wind_mfma.h", "wind_mfma_dma.h", "wind_mfma_ws.h", "wind_util.h", "wind_beam.h",
+        "wind_pred_kernels.h", "wind_loop_kernel.h", "wind_mfma.h", "wind_mfma_dma.h", "wind_mfma_ws.h", "wind_mfma_wide.h", "wind_util.h", "wind_beam.h",
         "wind_beam_search.h", os.path.join("..", "..", "include", "wind.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

@@ -115,10 +115,12 @@ struct wind_model {
   CallDev call{};
   // loop replay
   hipStream_t cap_stream = nullptr;
-  hipGraph_t graph = nullptr;
-  hipGraphExec_t graph_exec = nullptr;
+  hipGraph_t graph[2] = {nullptr, nullptr};            // [1]: the iterations with joint_wide_kernel
+  hipGraphExec_t graph_exec[2] = {nullptr, nullptr};
   GraphKey graph_key{};
   bool graph_valid = false;
+  int opt_joint_wide = 1;       // 0: never, 1: iterations with more than wide_rows window rows, 2: always (where the model allows)
+  long long prev_wide_iters = 0, last_wide_iters = 0;   // iterations of the previous / last call that had more than wide_rows window rows
   int opt_graph = 1, opt_unroll = 16;
   int opt_host_sync = 0;   // 1: kernels one by one and the host reads the active count after every iteration
   hipEvent_t ev_call[3] = {nullptr, nullptr, nullptr};   // last decode call: start, loop start, loop end
@@ -282,6 +284,7 @@ void carve_workspace(wind_model *m, const WsLayout &w, char *base, int B) {
                o_dbg = w.o_dbg, o_lbar = w.o_lbar, o_lh = w.o_lh, o_lp = w.o_lp, o_lparts = w.o_lparts;
   (void)d;
   CallDev &c = m->call;
+  c.Mpad = (int)w.Mpad;
   c.e = (float *)(base + o_e);
   c.enc_b = big_enc ? (bf16_t *)(base + o_encb) : nullptr;
   c.len = (int *)(base + o_len);
@@ -449,24 +452,46 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
   return enqueue_pred_step(m, s, false, true);
 }
 
+// The joint kernel on 256-column tiles (joint_wide_kernel) pays off from 192-row tiles on: with `wfill` row
+// tiles filling the chip, for iterations with more than 128 wfill window rows.  Returns that threshold (0 with
+// option joint_wide = 2: every iteration), or -1 if the model or the call never runs the kernel.
+int wide_threshold_rows(const wind_model *m, int B, int W) {
+  const ModelDev &d = m->dev;
+  if (m->dtype != WIND_BF16 || !d.w_out_slab || m->opt_joint_wide == 0) return -1;
+  const int NT = (d.V + WideCfg<1>::BN - 1) / WideCfg<1>::BN, wfill = NT >= 256 ? 1 : 256 / NT;
+  const int thr = m->opt_joint_wide == 2 ? 0 : 128 * wfill;
+  const unsigned long long z_bytes = (round_up((size_t)B * W, kRowPad) + kRowPad) * (unsigned long long)d.Hj * 2;
+  if (z_bytes >= (1ull << 32)) return -1;   // the kernel's buffer descriptors take 32-bit sizes
+  return (long long)B * W > thr ? thr : -1;
+}
+
 // the output contraction with its row argmax folded in, for the window rows build_z_kernel wrote
-void enqueue_joint(wind_model *m, hipStream_t s, int parity, bool capturing) {
+// (wide: in slab layout, for joint_wide_kernel)
+void enqueue_joint(wind_model *m, hipStream_t s, int parity, bool capturing, bool wide) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
+  if (wide) {
+    const int NT = (d.V + WideCfg<1>::BN - 1) / WideCfg<1>::BN, fill = NT >= 256 ? 1 : 256 / NT;
+    const int spec = (long long)c.B * c.W > 128 * fill;   // tiles of at least 192 rows can occur
+    launch(m, s, WIND_K_JOINT, capturing, joint_wide_kernel, dim3((unsigned)((fill * NT + 7) / 8 * 8)), dim3(WideCfg<1>::NT),
+           kWideSmemBytes, d, c, parity, fill, NT, spec);
+    return;
+  }
   // fill x NT workgroups, each walking as many row tiles as the iteration's row count needs
   const int NT = (d.V + WsCfg<1>::BN - 1) / WsCfg<1>::BN, fill = NT >= 256 ? 1 : 256 / NT;
   launch(m, s, WIND_K_JOINT, capturing, joint_ws_kernel, dim3((unsigned)((fill * NT + 7) / 8 * 8)), dim3(WsCfg<1>::NT),
          kWsSmemBytes, d, c, parity, fill, NT);
 }
 
-int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) {
+int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing, bool wide) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
   const int max_rows = c.B * c.W;
   const int decide_threads = 64 * (c.W < 16 ? c.W : 16);
   if (m->dtype == WIND_BF16) {
-    launch(m, s, WIND_K_BUILD_Z, capturing, build_z_kernel, dim3((unsigned)((max_rows + 3) / 4)), dim3(256), 0, d, c, parity);
-    enqueue_joint(m, s, parity, capturing);
+    launch(m, s, WIND_K_BUILD_Z, capturing, build_z_kernel, dim3((unsigned)((max_rows + 3) / 4)), dim3(256), 0, d, c, parity,
+           wide ? 1 : 0, wide_threshold_rows(m, c.B, c.W));
+    enqueue_joint(m, s, parity, capturing, wide);
     if (d.Hj <= 1024)
       launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t, false>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
     else
@@ -481,24 +506,33 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing) 
   return enqueue_pred_step(m, s, capturing);
 }
 
+// The loop's graphs: `unroll` iterations with joint_ws_kernel, and, where the call can have iterations
+// for joint_wide_kernel, the same with that kernel (either graph is right for any row count).
 int ensure_graph(wind_model *m) {
   GraphKey key{};
   key.call = m->call;
   key.unroll = m->opt_unroll;
   if (m->graph_valid && key == m->graph_key) return WIND_OK;
-  if (m->graph_exec) { (void)hipGraphExecDestroy(m->graph_exec); m->graph_exec = nullptr; }
-  if (m->graph) { (void)hipGraphDestroy(m->graph); m->graph = nullptr; }
+  for (int g = 0; g < 2; ++g) {
+    if (m->graph_exec[g]) { (void)hipGraphExecDestroy(m->graph_exec[g]); m->graph_exec[g] = nullptr; }
+    if (m->graph[g]) { (void)hipGraphDestroy(m->graph[g]); m->graph[g] = nullptr; }
+  }
   m->graph_valid = false;
   if (!m->cap_stream) HIP_TRY(hipStreamCreateWithFlags(&m->cap_stream, hipStreamNonBlocking));
-  HIP_TRY(hipStreamBeginCapture(m->cap_stream, hipStreamCaptureModeThreadLocal));
-  int rc = WIND_OK;
-  for (int it = 0; it < m->opt_unroll && rc == WIND_OK; ++it) rc = enqueue_iteration(m, m->cap_stream, it & 1, true);
-  hipGraph_t g = nullptr;
-  hipError_t e = hipStreamEndCapture(m->cap_stream, &g);
-  if (rc != WIND_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
-  if (e != hipSuccess) return fail(WIND_ERR_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
-  m->graph = g;
-  HIP_TRY(hipGraphInstantiate(&m->graph_exec, m->graph, nullptr, nullptr, 0));
+  const int wide_rows = wide_threshold_rows(m, m->call.B, m->call.W);
+  const bool want[2] = {wide_rows != 0, wide_rows >= 0};
+  for (int w = 0; w < 2; ++w) {
+    if (!want[w]) continue;
+    HIP_TRY(hipStreamBeginCapture(m->cap_stream, hipStreamCaptureModeThreadLocal));
+    int rc = WIND_OK;
+    for (int it = 0; it < m->opt_unroll && rc == WIND_OK; ++it) rc = enqueue_iteration(m, m->cap_stream, it & 1, true, w == 1);
+    hipGraph_t g = nullptr;
+    hipError_t e = hipStreamEndCapture(m->cap_stream, &g);
+    if (rc != WIND_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
+    if (e != hipSuccess) return fail(WIND_ERR_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    m->graph[w] = g;
+    HIP_TRY(hipGraphInstantiate(&m->graph_exec[w], m->graph[w], nullptr, nullptr, 0));
+  }
   m->graph_key = key;
   m->graph_valid = true;
   return WIND_OK;
@@ -517,6 +551,7 @@ int fetch_stats(wind_model *m, hipStream_t s) {
   st.labels = (int64_t)h[ST_LABELS];
   st.forced_advances = (int64_t)h[ST_FORCED];
   st.rechecks = (int64_t)h[ST_RECHECK];
+  m->last_wide_iters = (long long)h[ST_WIDE];
   for (int i = 0; i <= WIND_MAX_WINDOW; ++i) st.jump_hist[i] = (int64_t)h[kStatJump0 + i];
   m->have_stats = true;
   if (m->call.dbg) {
@@ -661,6 +696,18 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   }
   const int U = m->opt_unroll;
   const bool use_graph = m->opt_graph && !m->opt_profile && !m->opt_host_sync;   // events cannot sit between graph nodes
+  // Which joint kernel the iterations of a block of U run (either is right for any row count; the choice is
+  // about speed): joint_wide_kernel while the call has more than wide_rows window rows per iteration.  The
+  // row count only falls during a call, so from a count read back, active utterances x W; for blocks enqueued
+  // ahead of any count, from how many such iterations the previous call of the same shape had.
+  const int wide_rows = wide_threshold_rows(m, B, W);
+  const bool same_shape = m->prev_B == B && m->prev_T == T && m->prev_W == W && m->prev_iters > 0;
+  auto wide_by_count = [&](long long active) { return wide_rows >= 0 && active * W > wide_rows; };
+  auto wide_by_history = [&](long long block) {
+    if (wide_rows < 0) return false;
+    if (wide_rows == 0) return true;
+    return same_shape ? block * U + U / 2 < m->prev_wide_iters : block == 0 && wide_by_count(B);
+  };
   m->joint_us.clear();
   m->joint_rows.clear();
   if (use_graph) {
@@ -672,7 +719,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     // end of the decode find no active utterance and leave at once
     if (!use_graph) return fail(WIND_ERR_UNSUPPORTED, "the asynchronous decode needs graph replay (options graph, profile, host_sync)");
     const long long replays = (std::min(async_iters, max_iters) + U - 1) / U;
-    for (long long i = 0; i < replays; ++i) HIP_TRY(hipGraphLaunch(m->graph_exec, s));
+    for (long long i = 0; i < replays; ++i) HIP_TRY(hipGraphLaunch(m->graph_exec[wide_by_history(i) ? 1 : 0], s));
     HIP_TRY(hipEventRecord(m->ev_call[2], s));
     m->async_pending = true; m->async_loop = false; m->async_stream = s;
     return WIND_OK;
@@ -683,7 +730,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     // reads how many utterances are still active before it launches the next iteration.
     for (long long it = 0;; ++it) {
       const int parity = (int)(it & 1);
-      rc = enqueue_iteration(m, s, parity, false);
+      rc = enqueue_iteration(m, s, parity, false, wide_by_count(it == 0 ? B : *m->h_flag));
       if (rc) return rc;
       HIP_TRY(hipEventRecord(m->ev_call[2], s));
       HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active + (parity ^ 1), sizeof(int), hipMemcpyDeviceToHost, s));
@@ -699,18 +746,21 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     if (ahead < 1) ahead = 1;
     const long long max_launches = (max_iters + 2 * U) / U + 2;
     long long launches = 0;
+    bool polled = false;
     for (;;) {
       for (long long i = 0; i < ahead; ++i, ++launches) {
+        const bool wide = polled ? wide_by_count(*m->h_flag) : wide_by_history(launches);
         if (use_graph) {
-          HIP_TRY(hipGraphLaunch(m->graph_exec, s));
+          HIP_TRY(hipGraphLaunch(m->graph_exec[wide ? 1 : 0], s));
         } else {
           for (int it = 0; it < U; ++it) {
-            rc = enqueue_iteration(m, s, it & 1, false);
+            rc = enqueue_iteration(m, s, it & 1, false, wide);
             if (rc) return rc;
           }
         }
       }
       ahead = 1;
+      polled = true;
       HIP_TRY(hipEventRecord(m->ev_call[2], s));
       HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
       HIP_TRY(hipStreamSynchronize(s));
@@ -728,6 +778,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   }
   m->prev_B = B; m->prev_T = T; m->prev_W = W;
   m->prev_iters = m->last_stats.iterations;
+  m->prev_wide_iters = m->last_wide_iters;
   if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
   return rc;
 }
@@ -834,6 +885,14 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   chk(upload_matrix(m, w->w_pred, w->Hj, Hp, w->Hj, &d.w_pred));
   chk(upload(m, std::vector<float>(w->b_pred, w->b_pred + w->Hj), &tmp)); d.b_pred = (const float *)tmp;
   chk(upload_matrix(m, w->w_out, (size_t)w->V + 1, w->Hj, d.Vpad, &d.w_out));
+  d.w_out_slab = nullptr;
+  if (m->dtype == WIND_BF16 && w->Hj >= kWideMinK && (unsigned long long)d.Vpad * w->Hj * 2 < (1ull << 32)) {
+    // the same rows in slabs of 32 hidden units, for joint_wide_kernel
+    std::vector<uint16_t> h((size_t)d.Vpad * w->Hj, 0);
+    for (size_t v = 0; v <= (size_t)w->V; ++v)
+      for (size_t k = 0; k < (size_t)w->Hj; ++k) h[((k >> 5) * d.Vpad + v) * 32 + (k & 31)] = host_bf16(w->w_out[v * w->Hj + k]);
+    chk(upload(m, h, &d.w_out_slab));
+  }
   chk(upload(m, std::vector<float>(w->b_out, w->b_out + w->V + 1), &tmp)); d.b_out = (const float *)tmp;
   {
     std::vector<float> wb(w->Hj);
@@ -865,6 +924,7 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   }
   if (rc == WIND_OK) {
     hipError_t e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)joint_wide_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWideSmemBytes);
     static_assert(kFusedSteps == 5, "one resident loop instance per number of fused K steps: here and at the launch");
     const void *loop_instances[] = {(const void *)wind_loop_kernel<0>, (const void *)wind_loop_kernel<1>, (const void *)wind_loop_kernel<2>,
                                     (const void *)wind_loop_kernel<3>, (const void *)wind_loop_kernel<4>, (const void *)wind_loop_kernel<5>};
@@ -905,8 +965,10 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
 int wind_free(wind_model *m) {
   if (!m) return WIND_OK;
   (void)hipDeviceSynchronize();
-  if (m->graph_exec) (void)hipGraphExecDestroy(m->graph_exec);
-  if (m->graph) (void)hipGraphDestroy(m->graph);
+  for (int g = 0; g < 2; ++g) {
+    if (m->graph_exec[g]) (void)hipGraphExecDestroy(m->graph_exec[g]);
+    if (m->graph[g]) (void)hipGraphDestroy(m->graph[g]);
+  }
   if (m->cap_stream) (void)hipStreamDestroy(m->cap_stream);
   for (void *p : m->allocs) (void)hipFree(p);
   if (m->ws) (void)hipFree(m->ws);
@@ -1116,6 +1178,13 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
     m->opt_loop_spin_limit = value;
     return WIND_OK;
   }
+  if (!std::strcmp(key, "joint_wide")) {
+    if (value < 0 || value > 2) return fail(WIND_ERR_ARG, "joint_wide must be 0 (never), 1 (iterations with many rows) or 2 (always)");
+    m->opt_joint_wide = (int)value;
+    m->graph_valid = false;
+    m->prev_iters = 0;
+    return WIND_OK;
+  }
   if (!std::strcmp(key, "atomic_lists")) {
     m->opt_atomic_lists = value != 0;
     m->graph_valid = false;
@@ -1237,8 +1306,9 @@ int wind_debug_joint_keys(wind_model *m, const float *enc_out, const int32_t *le
   if (rc) return rc;
   const CallDev &c = m->call;
   // the first loop iteration's window rows and their keys, by the kernels a decode call launches
-  build_z_kernel<<<(unsigned)((B * W + 3) / 4), 256, 0, s>>>(m->dev, c, 0);
-  enqueue_joint(m, s, 0, true);
+  const bool wide = wide_threshold_rows(m, B, W) >= 0 && (long long)B * W > wide_threshold_rows(m, B, W);
+  build_z_kernel<<<(unsigned)((B * W + 3) / 4), 256, 0, s>>>(m->dev, c, 0, wide ? 1 : 0, -1);
+  enqueue_joint(m, s, 0, true, wide);
   rc = check_launch("debug joint keys");
   if (rc) return rc;
   HIP_TRY(hipMemcpyAsync(keys, c.parts, (size_t)B * W * c.nparts * sizeof(float4), hipMemcpyDeviceToDevice, s));

@@ -163,7 +163,10 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(ModelDev m, CallDev c
 // ---------------------------------------------------------------------------------------------
 // Window gather (Algorithm 2: the joiner on a window of frames against the current decoder output, its
 // first half): one wave per window row.
-__global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int parity) {
+// slab: z in slabs of 32 hidden units, [Hj / 32][Mpad][32], as joint_wide_kernel reads it, instead of dense rows.
+// wide_rows > 0: iterations with more window rows than that are counted (ST_WIDE; the host's choice of the
+// joint kernel for the next call of the same shape rests on it).
+__global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int parity, int slab, int wide_rows) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = blockIdx.x * 4 + wave;
   const int a = row / c.W, j = row - a * c.W;
@@ -172,6 +175,7 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
   const int4 st = c.slot_state[parity * c.slot_stride + a];   // same round trip as the count
   // the counters that this iteration's decision kernel adds to: every reader of their old values is done
   if (c.lists_atomic && blockIdx.x == 0 && threadIdx.x == 0) { c.n_active[parity ^ 1] = 0; *c.n_emit = 0; }
+  if (wide_rows > 0 && blockIdx.x == 0 && threadIdx.x == 0 && na * c.W > wide_rows) c.stats[ST_WIDE] += 1ull;   // one writer per iteration
   if (c.iter_rows && blockIdx.x == 0 && wave == 0 && na > 0) {
     // profile mode: rows the method evaluates in this iteration = sum of n over the windows; iterations
     // so far = the decision kernel's counter (complete: that kernel precedes this one in the stream)
@@ -190,7 +194,8 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
   const int Hj = m.Hj;
   const float *er = c.e + ((size_t)b * c.T + (valid ? tt : 0)) * Hj;
   const float *pr = c.p + (size_t)b * Hj;
-  bf16_t *zr = c.z + (size_t)row * Hj;
+  bf16_t *zr = slab ? c.z + (size_t)row * 32 : c.z + (size_t)row * Hj;
+  const size_t slab_elems = (size_t)c.Mpad * 32;
   float dot = 0.f, nrm = 0.f;
   // 1024 hidden units per pass: the pass's twelve loads per lane go out together (one round trip)
   for (int k0 = lane * 4; k0 < Hj; k0 += 1024) {
@@ -218,7 +223,8 @@ __global__ __launch_bounds__(256) void build_z_kernel(ModelDev m, CallDev c, int
       dot = fmaf(x.z, wb[i].z, dot); dot = fmaf(x.w, wb[i].w, dot);
       nrm = fmaf(x.x, x.x, nrm); nrm = fmaf(x.y, x.y, nrm);
       nrm = fmaf(x.z, x.z, nrm); nrm = fmaf(x.w, x.w, nrm);
-      *reinterpret_cast<uint2 *>(zr + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+      bf16_t *zp = slab ? zr + (size_t)(k >> 5) * slab_elems + (k & 31) : zr + k;
+      *reinterpret_cast<uint2 *>(zp) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
     }
   }
   dot = wave_sum(dot);

@@ -71,6 +71,21 @@ __device__ __forceinline__ float4 load_keys(const float *parts, size_t idx) {
 }
 __device__ __forceinline__ float4 no_keys() { return make_float4(kKeyNone, kKeyNone, kKeyNone, kKeyNone); }
 
+// The column codes of a lower-half lane's 32 values of one 64-column part (two accumulator blocks), held in
+// registers: as literals they cost a second instruction per key.  inf: key_inf().
+struct KeyConsts {
+  uint32_t code[32];
+  float inf;
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+      code[r] = kKeyColMask - (uint32_t)((r >> 4) * 32 + 8 * ((r & 15) >> 2) + (r & 3));
+      asm volatile("" : "+v"(code[r]));
+    }
+    inf = key_inf();
+  }
+};
+
 // Epilogue of the joint kernel: (logit, column) keys, per-row top-3 over the wave's WN columns,
 // one float4 per (row, part) to memory.  The logits never leave registers.
 template <class Cfg>
@@ -83,13 +98,17 @@ __device__ __forceinline__ void joint_keys_epilogue(const CallDev &c, f32x16 (&a
   // higher, i.e. code bit 2 cleared (it is always set in the lower half's codes).  All keys of a
   // lane shift alike, so the correction waits until the lane's three winners are known.
   const unsigned fix = ~(unsigned)(4 * (lane >> 5));
+  static_assert(Cfg::NI == 2, "one 64-column part per wave");
+  KeyConsts kc;
+  kc.init();
 #pragma unroll
   for (int mi = 0; mi < Cfg::MI; ++mi) {
     float k1 = kKeyNone, k2 = kKeyNone, k3 = kKeyNone;
 #pragma unroll
     for (int ni = 0; ni < Cfg::NI; ++ni)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) push_top3(k1, k2, k3, make_key(acc[mi][ni][r], ni * 32 + 8 * (r >> 2) + (r & 3)));
+      for (int r = 0; r < 16; ++r)
+        push_top3(k1, k2, k3, __uint_as_float((__float_as_uint(acc[mi][ni][r]) & ~kKeyColMask) | kc.code[16 * ni + r]), kc.inf);
     k1 = __uint_as_float(__float_as_uint(k1) & fix);
     k2 = __uint_as_float(__float_as_uint(k2) & fix);
     k3 = __uint_as_float(__float_as_uint(k3) & fix);
@@ -175,6 +194,110 @@ __global__ __launch_bounds__(512) void joint_ws_kernel(ModelDev m, CallDev c, in
     case 2: joint_ws_tiles<2>(m, c, n_rows, mt, mt_step, tiles, nt, early, smem_raw); break;
     case 3: joint_ws_tiles<3>(m, c, n_rows, mt, mt_step, tiles, nt, early, smem_raw); break;
     default: joint_ws_tiles<4>(m, c, n_rows, mt, mt_step, tiles, nt, early, smem_raw); break;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The joint kernel on 256-column tiles (wind_mfma_wide.h), for iterations with many window rows:
+// W_out and the window rows are read in their slab layouts (ModelDev::w_out_slab; CallDev::z as
+// the gather kernel writes it in slab mode).  The launch has `fill` x NT workgroups of four waves,
+// fill = row tiles that fill the chip for NT column tiles of 256; tile heights and rounds follow the
+// row count as in joint_ws_kernel, and the result (keys per row and 64-column part) is the same,
+// bit for bit: every logit is the same chain of MFMAs over K in the same order.
+// Keys of one row block and one 64-column part from its two finished accumulator blocks (lo: columns 0..31 of
+// the part, hi: 32..63), see joint_keys_epilogue.
+__device__ __forceinline__ void joint_wide_keys(const CallDev &c, const KeyConsts &kc, const f32x16 &lo, const f32x16 &hi,
+                                                int row, int part) {
+  const int lane = threadIdx.x & 63;
+  const unsigned fix = ~(unsigned)(4 * (lane >> 5));
+  float k1 = kKeyNone, k2 = kKeyNone, k3 = kKeyNone;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) push_top3(k1, k2, k3, __uint_as_float((__float_as_uint(lo[r]) & ~kKeyColMask) | kc.code[r]), kc.inf);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) push_top3(k1, k2, k3, __uint_as_float((__float_as_uint(hi[r]) & ~kKeyColMask) | kc.code[16 + r]), kc.inf);
+  k1 = __uint_as_float(__float_as_uint(k1) & fix);
+  k2 = __uint_as_float(__float_as_uint(k2) & fix);
+  k3 = __uint_as_float(__float_as_uint(k3) & fix);
+  const float r1 = __shfl_xor(k1, 32, kWave), r2 = __shfl_xor(k2, 32, kWave), r3 = __shfl_xor(k3, 32, kWave);
+  push_top3(k1, k2, k3, r1);
+  push_top3(k1, k2, k3, r2);
+  push_top3(k1, k2, k3, r3);
+  if (lane < 32 && row < c.Mpad && part < c.nparts)   // 256-column tiles may reach past the last 128-column tile's parts
+    reinterpret_cast<float4 *>(c.parts)[(size_t)row * c.nparts + part] = make_float4(k1, k2, k3, kKeyNone);
+}
+
+// a_spec: the A loads that do not depend on the tile height are on their way for the first tile (requested
+// before the row count was known, for `tiles` row tiles)
+template <int MI>
+__device__ __forceinline__ void joint_wide_tiles(const ModelDev &m, const CallDev &c, i32x4 rs_a, i32x4 rs_b, int mt0, int mt_step,
+                                                 int tiles, int nt, bool b_head_done, bool a_spec, unsigned char *smem_raw) {
+  using Cfg = WideCfg<MI>;
+  const int n0 = nt * Cfg::BN, KS = m.Hj / 32;
+  const uint32_t slab_b = (uint32_t)m.Vpad * 64u, slab_a = (uint32_t)c.Mpad * 64u;
+  const int wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1, lane = threadIdx.x & 63;
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  bf16x8 af[2][Cfg::MI], bfr[2][Cfg::NI];
+  float bias[Cfg::NI][16];
+  joint_load_bias<Cfg>(m, bias, n0);
+  for (int mt = mt0; mt < tiles; mt += mt_step) {
+    if (!b_head_done) wide_head_b(rs_b, slab_b, n0, KS, smem_raw);
+    wide_mainloop<Cfg>(rs_a, slab_a, rs_b, slab_b, KS, mt, tiles, n0, c.Mpad, a_spec, smem_raw, acc, af, bfr, JointInitAcc<Cfg>{acc, bias});
+    b_head_done = a_spec = false;
+    if (mt + mt_step < tiles) {   // the next tile's first loads go out before this tile's keys are formed
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      wide_head_b(rs_b, slab_b, n0, KS, smem_raw);
+      b_head_done = true;
+    }
+    KeyConsts kc;
+    kc.init();
+    wide_last_step<Cfg>(acc, af[1], bfr[1], [&](int mi, int p, const f32x16 &lo, const f32x16 &hi) {
+      joint_wide_keys(c, kc, lo, hi, (mt + tiles * (2 * mi + wm)) * 32 + (lane & 31), nt * 4 + wn * 2 + p);
+    });
+  }
+}
+
+// spec: the launch may request window rows before it knows their number (the row tiles then number `fill`
+// and are at least 192 rows high unless the count says otherwise, in which case those loads are thrown away)
+__global__ __launch_bounds__(256) void joint_wide_kernel(ModelDev m, CallDev c, int parity, int fill, int NT, int spec) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int lin = (int)blockIdx.x, KS = m.Hj / 32;
+  const bool early = NT % 8 == 0;   // the column tile does not depend on the number of row tiles
+  const uint32_t slab_b = (uint32_t)m.Vpad * 64u, slab_a = (uint32_t)c.Mpad * 64u;
+  const i32x4 rs_b = wide_rsrc(m.w_out_slab, slab_b * (uint32_t)KS), rs_a = wide_rsrc(c.z, slab_a * (uint32_t)KS);
+  int mt = 0, nt = 0;
+  bool a_spec = false;
+  if (early) {
+    joint_tile_of_block(lin, fill, NT, mt, nt);
+    wide_head_b(rs_b, slab_b, nt * 256, KS, smem_raw);
+    if (spec) { wide_head_a(rs_a, slab_a, mt, fill, c.Mpad, 0, kWideSpecLoads, KS, smem_raw); a_spec = true; }
+  }
+  const int n_rows = c.n_active[parity] * c.W;
+  const int fine = (n_rows + 63) / 64;
+  int tiles, mi;   // row tiles in use, their height in units of 64 rows
+  if (fine <= fill) {
+    tiles = fine; mi = 1;
+  } else {
+    const int rounds = (n_rows + 256 * fill - 1) / (256 * fill);
+    tiles = fill * rounds;
+    mi = (n_rows + 64 * tiles - 1) / (64 * tiles);
+  }
+  const int mt_step = tiles < fill ? tiles : fill;
+  if (!early && mt_step > 0) joint_tile_of_block(lin, mt_step, NT, mt, nt);
+  if (n_rows == 0 || mt >= mt_step || nt >= NT) {
+    wait_vmcnt<0>();
+    return;
+  }
+  if (a_spec && (tiles != fill || mi < kWideSpecLoads)) {   // not the rows this tile needs: let them land, then start over
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    a_spec = false;
+  }
+  switch (mi) {
+    case 1: joint_wide_tiles<1>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
+    case 2: joint_wide_tiles<2>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
+    case 3: joint_wide_tiles<3>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
+    default: joint_wide_tiles<4>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
   }
 }
 

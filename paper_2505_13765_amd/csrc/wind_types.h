@@ -3,15 +3,16 @@
 #include "wind_mfma.h"
 #include "wind_mfma_dma.h"
 #include "wind_mfma_ws.h"
+#include "wind_mfma_wide.h"
 
 namespace wind {
 
 constexpr int kMaxLayers = 4;
 constexpr int kMaxWindow = 64;
 constexpr int kTinyRows = 64;   // slots the resident loop kernel keeps in LDS (it runs far fewer)
-constexpr int kStatJump0 = 8;  // index of jump_hist[0] in the device counter array
+constexpr int kStatJump0 = 9;  // index of jump_hist[0] in the device counter array
 constexpr int kNumStats = kStatJump0 + kMaxWindow + 1;
-enum { ST_ITER = 0, ST_WINDOWS, ST_ROWS, ST_USEFUL, ST_LABELS, ST_FORCED, ST_RECHECK, ST_OVERFLOW };
+enum { ST_ITER = 0, ST_WINDOWS, ST_ROWS, ST_USEFUL, ST_LABELS, ST_FORCED, ST_RECHECK, ST_OVERFLOW, ST_WIDE };   // ST_WIDE: iterations with more window rows than the gather kernel was told
 
 // Weights on the device.  WT-typed matrices are bf16 (bf16 models) or fp32 (fp32 models).
 struct ModelDev {
@@ -32,6 +33,7 @@ struct ModelDev {
   const void *w_pred;           // [Hj, Hp]
   const float *b_pred;          // [Hj]
   const void *w_out;            // [Vpad, Hj]; row V = blank
+  const void *w_out_slab;       // bf16 models: the same matrix in slabs of 32 K values, [Hj / 32][Vpad][32] (wide joint tiles)
   const float *b_out;           // [V+1]
   const float *w_blank;         // [Hj] fp32 copy of row V
   float tau_scale;              // near-tie band = tau_scale * |z|_2 (+ key truncation)
@@ -72,7 +74,7 @@ struct CallDev {
   // the input half left to do.  Null where this is not used (the full products are then formed per step).
   float *rec;                   // [L][B][4Hp]
   float *p;                     // [B][Hj]
-  bf16_t *z;                    // [Mpad][Hj]
+  bf16_t *z;                    // [Mpad][Hj]; in iterations that run joint_wide_kernel, slabs of 32 K values: [Hj / 32][Mpad][32]
   float *blank_logit;           // [Mpad]
   float *znorm;                 // [Mpad]
   // Keys: per window row and column part the largest (logit, column) keys of the part.  The joint kernel
@@ -81,6 +83,7 @@ struct CallDev {
   int nparts;                   // parts per row and label columns per part, as written by the joint kernel
   int part_width;
   int nparts_tiny;              // parts per row of the resident loop kernel (32 columns each)
+  int Mpad;                     // rows of z, blank_logit, znorm, parts
   int *row_label;               // [Mpad] (fp32 models)
   unsigned long long *stats;    // [kNumStats]
   long long *dbg;               // optional [8] phase time stamps of the few-rows kernel's deciding workgroup (100 MHz clock)

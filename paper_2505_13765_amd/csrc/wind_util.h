@@ -140,6 +140,18 @@ __device__ __forceinline__ void push_top2(float &a1, float &a2, float k) {
   a1 = fmaxf(a1, k);
 }
 // the same for the three largest (a1 >= a2 >= a3)
+// (the maximum as the median with +infinity: fmaxf would first quieten a possible NaN, one more
+// instruction per element of the joint kernels' epilogues, whose keys are never NaN)
+__device__ __forceinline__ float key_inf() {
+  float inf = __builtin_inff();
+  asm volatile("" : "+v"(inf));   // opaque, so that the median is not folded back into a maximum
+  return inf;
+}
+__device__ __forceinline__ void push_top3(float &a1, float &a2, float &a3, float k, float inf) {
+  a3 = __builtin_amdgcn_fmed3f(k, a2, a3);
+  a2 = __builtin_amdgcn_fmed3f(k, a1, a2);
+  a1 = __builtin_amdgcn_fmed3f(a1, k, inf);
+}
 __device__ __forceinline__ void push_top3(float &a1, float &a2, float &a3, float k) {
   a3 = __builtin_amdgcn_fmed3f(k, a2, a3);
   a2 = __builtin_amdgcn_fmed3f(k, a1, a2);

@@ -128,6 +128,11 @@ def test_bf16_scaled_workloads(torch_cuda, name, B, lo, hi, windows):
             assert all(a.tolist() == b.tolist() for a, b in zip(first[1], frs))
     toks_s, frs_s = m.decode(d_enc, d_len, None, cfg.S)
     assert compare_batch(o, enc, lens, cfg.S, toks_s, frs_s, tol=TOL_GAP) <= 2
+    # every iteration on the joint kernel with 256-column tiles (a decode call picks it for many rows only)
+    m.set_option("joint_wide", 2)
+    toks_w, frs_w = m.decode(d_enc, d_len, windows[-1], cfg.S)
+    assert all(a.tolist() == b.tolist() for a, b in zip(first[0], toks_w))
+    assert all(a.tolist() == b.tolist() for a, b in zip(first[1], frs_w))
     m.close()
 
 
@@ -264,11 +269,11 @@ def test_random_shapes_bf16(torch_cuda):
         enc, lens = wi.make_batch(cfg)
         d_enc, d_len = to_dev(torch_cuda, enc, lens)
         print(f"random shapes {case}: Hj={Hj} Hp={Hp} E={E} L={L} V={V} B={B} W={W} S={S} lengths {lo}..{hi}", flush=True)
-        routes = [{}, {"loop_kernel": 0, "lstm_rec": 0, "atomic_lists": 0}, {"loop_kernel": 0}]
+        routes = [{}, {"loop_kernel": 0, "lstm_rec": 0, "atomic_lists": 0}, {"loop_kernel": 0}, {"loop_kernel": 0, "joint_wide": 2}]
         if small:   # the resident loop kernel's other form (window rows staged in LDS) and other placement
             routes += [{"loop_fused": 0}, {"loop_one_xcd": 0}, {"loop_fused": 0, "loop_one_xcd": 0}]
         for opts in routes:
-            for k, v in {"loop_kernel": 1, "lstm_rec": 1, "atomic_lists": 1, "loop_fused": 1, "loop_one_xcd": 1, **opts}.items():
+            for k, v in {"loop_kernel": 1, "lstm_rec": 1, "atomic_lists": 1, "loop_fused": 1, "loop_one_xcd": 1, "joint_wide": 1, **opts}.items():
                 m.set_option(k, v)
             toks, frs = m.decode(d_enc, d_len, W, S)
             check_outputs(cfg, lens, toks, frs)
@@ -328,11 +333,15 @@ def decode_keys(keys, width):
                                         ("largevocab_b128", 47, 16, None), ("largevocab_b128", 63, 16, None),
                                         ("largevocab_b128", 83, 16, None), ("largevocab_b128", 128, 16, None),
                                         ("batch32", 9, 8, None), ("batch32", 20, 5, 300), ("lowblank_b256", 70, 16, None)])
-def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V):
-    """The joint kernel a decode call launches (direct-to-LDS rings, transposed accumulation, bias as the
-    accumulators' start value, key packing, every tile height), checked on what it writes: for every
+@pytest.mark.parametrize("wide", [1, 2])
+def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V, wide):
+    """The joint kernels a decode call launches (direct-to-LDS rings, transposed accumulation, bias as the
+    accumulators' start value, key packing, every tile height), checked on what they write: for every
     sampled window row and every column part, each key's value must be the oracle's logit of the key's
-    column to 2e-2, and the two columns must be the part's two largest oracle logits up to 2e-2."""
+    column to 2e-2, and the two columns must be the part's two largest oracle logits up to 2e-2.
+    wide = 1: the kernel a decode call would pick for this row count (256-column tiles above 1024 rows
+    on the large-vocabulary model); wide = 2: the 256-column kernel at every row count (tiles of 64 to 256
+    rows, row tiles in rounds, a column-tile count that is not a multiple of eight)."""
     base = wi.CONFIGS[name]
     cfg = wi.scaled(base, B, W + 2, 2 * W)
     if V is not None:
@@ -342,6 +351,7 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V):
     enc, lens = wi.make_batch(cfg)
     lens[B // 2] = max(1, W // 2)          # a window that runs past its utterance's end: zero rows
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
+    m.set_option("joint_wide", wide)
     keys, width = m.debug_joint_keys(d_enc, d_len, W)
     nparts = keys.shape[1]
     assert keys.shape == (B * W, nparts, 4) and nparts * width >= cfg.V   # whole tiles: the last parts may be empty
@@ -369,7 +379,7 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V):
                 assert abs(val[r, p, k] - ref[cols[k]]) < TOL_BF16 and ref[cols[k]] > part[k] - TOL_BF16, (r, p, k)
                 assert k == 0 or val[r, p, k - 1] >= val[r, p, k]
                 worst = max(worst, abs(val[r, p, k] - ref[cols[k]]))
-    print(f"{name} B={B} W={W} V={cfg.V}: {len(rows)} rows x {nparts} parts, max |key - oracle logit| = {worst:.3e}")
+    print(f"{name} B={B} W={W} V={cfg.V} wide={wide}: {len(rows)} rows x {nparts} parts, max |key - oracle logit| = {worst:.3e}")
     assert worst > 1e-6
     m.close()
 
