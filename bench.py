@@ -91,7 +91,7 @@ def run_workload(torch, wi, WindModel, name, windows, steps, warmup, with_sequen
 
 
 KERNEL_SOURCES = tuple("paper_2505_13765_amd/csrc/" + f for f in (
-    "wind_types.h", "wind_enc_kernels.h", "wind_joint_kernels.h", "wind_mfma_ws.h", "wind_mfma_dma.h", "wind_util.h"))
+    "wind_types.h", "wind_enc_kernels.h", "wind_joint_kernels.h", "wind_mfma_ws.h", "wind_mfma_wide.h", "wind_mfma_dma.h", "wind_util.h"))
 
 
 def kernel_source_digest():
@@ -155,9 +155,15 @@ def roofline_leg(torch, cfg, model, dev, W):
     # bytes the joint kernel must move per launch: W_out once, the window rows once, the keys out
     traffic, traffic_note = measured_traffic(cfg, W)
     rows_per_launch = st.rows / max(n, 1)
+    # iterations above this many window rows run joint_wide_kernel (256-column tiles of at least 192 rows), the rest joint_ws_kernel
+    nt_wide = (cfg.V + 255) // 256
+    wide_rows = 128 * max(1, 256 // nt_wide)
+    n_wide = sum(1 for r in rows_l if r > wide_rows)
     algorithmic_bytes = cfg.Hj * (cfg.V + 1) * 2 + rows_per_launch * cfg.Hj * 2 + rows_per_launch * ((cfg.V + 63) // 64) * 16
     return {
-        "bound": "mfma", "kernel": "joint_ws_kernel", "workload": f"{cfg.name} W={W}",
+        "bound": "mfma", "kernel": "joint_ws_kernel + joint_wide_kernel", "workload": f"{cfg.name} W={W}",
+        "kernel_split": {"joint_wide_kernel": {"rows_above": wide_rows, "launches": n_wide},
+                         "joint_ws_kernel": {"launches": len(rows_l) - n_wide}},
         "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
         "traffic": traffic, "traffic_source": traffic_note,
         "hbm_frac": (traffic / (ms * 1e-3 / max(n, 1)) / 1e9 / PEAK_HBM_GBS) if traffic else None,

@@ -472,9 +472,8 @@ void enqueue_joint(wind_model *m, hipStream_t s, int parity, bool capturing, boo
   const CallDev &c = m->call;
   if (wide) {
     const int NT = (d.V + WideCfg<1>::BN - 1) / WideCfg<1>::BN, fill = NT >= 256 ? 1 : 256 / NT;
-    const int spec = (long long)c.B * c.W > 128 * fill;   // tiles of at least 192 rows can occur
     launch(m, s, WIND_K_JOINT, capturing, joint_wide_kernel, dim3((unsigned)((fill * NT + 7) / 8 * 8)), dim3(WideCfg<1>::NT),
-           kWideSmemBytes, d, c, parity, fill, NT, spec);
+           kWideSmemBytes, d, c, parity, fill, NT);
     return;
   }
   // fill x NT workgroups, each walking as many row tiles as the iteration's row count needs

@@ -226,11 +226,9 @@ __device__ __forceinline__ void joint_wide_keys(const CallDev &c, const KeyConst
     reinterpret_cast<float4 *>(c.parts)[(size_t)row * c.nparts + part] = make_float4(k1, k2, k3, kKeyNone);
 }
 
-// a_spec: the A loads that do not depend on the tile height are on their way for the first tile (requested
-// before the row count was known, for `tiles` row tiles)
 template <int MI>
 __device__ __forceinline__ void joint_wide_tiles(const ModelDev &m, const CallDev &c, i32x4 rs_a, i32x4 rs_b, int mt0, int mt_step,
-                                                 int tiles, int nt, bool b_head_done, bool a_spec, unsigned char *smem_raw) {
+                                                 int tiles, int nt, bool b_head_done, unsigned char *smem_raw) {
   using Cfg = WideCfg<MI>;
   const int n0 = nt * Cfg::BN, KS = m.Hj / 32;
   const uint32_t slab_b = (uint32_t)m.Vpad * 64u, slab_a = (uint32_t)c.Mpad * 64u;
@@ -241,8 +239,8 @@ __device__ __forceinline__ void joint_wide_tiles(const ModelDev &m, const CallDe
   joint_load_bias<Cfg>(m, bias, n0);
   for (int mt = mt0; mt < tiles; mt += mt_step) {
     if (!b_head_done) wide_head_b(rs_b, slab_b, n0, KS, smem_raw);
-    wide_mainloop<Cfg>(rs_a, slab_a, rs_b, slab_b, KS, mt, tiles, n0, c.Mpad, a_spec, smem_raw, acc, af, bfr, JointInitAcc<Cfg>{acc, bias});
-    b_head_done = a_spec = false;
+    wide_mainloop<Cfg>(rs_a, slab_a, rs_b, slab_b, KS, mt, tiles, n0, c.Mpad, smem_raw, acc, af, bfr, JointInitAcc<Cfg>{acc, bias});
+    b_head_done = false;
     if (mt + mt_step < tiles) {   // the next tile's first loads go out before this tile's keys are formed
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
@@ -257,20 +255,16 @@ __device__ __forceinline__ void joint_wide_tiles(const ModelDev &m, const CallDe
   }
 }
 
-// spec: the launch may request window rows before it knows their number (the row tiles then number `fill`
-// and are at least 192 rows high unless the count says otherwise, in which case those loads are thrown away)
-__global__ __launch_bounds__(256) void joint_wide_kernel(ModelDev m, CallDev c, int parity, int fill, int NT, int spec) {
+__global__ __launch_bounds__(256) void joint_wide_kernel(ModelDev m, CallDev c, int parity, int fill, int NT) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   const int lin = (int)blockIdx.x, KS = m.Hj / 32;
   const bool early = NT % 8 == 0;   // the column tile does not depend on the number of row tiles
   const uint32_t slab_b = (uint32_t)m.Vpad * 64u, slab_a = (uint32_t)c.Mpad * 64u;
   const i32x4 rs_b = wide_rsrc(m.w_out_slab, slab_b * (uint32_t)KS), rs_a = wide_rsrc(c.z, slab_a * (uint32_t)KS);
   int mt = 0, nt = 0;
-  bool a_spec = false;
   if (early) {
     joint_tile_of_block(lin, fill, NT, mt, nt);
     wide_head_b(rs_b, slab_b, nt * 256, KS, smem_raw);
-    if (spec) { wide_head_a(rs_a, slab_a, mt, fill, c.Mpad, 0, kWideSpecLoads, KS, smem_raw); a_spec = true; }
   }
   const int n_rows = c.n_active[parity] * c.W;
   const int fine = (n_rows + 63) / 64;
@@ -288,16 +282,11 @@ __global__ __launch_bounds__(256) void joint_wide_kernel(ModelDev m, CallDev c, 
     wait_vmcnt<0>();
     return;
   }
-  if (a_spec && (tiles != fill || mi < kWideSpecLoads)) {   // not the rows this tile needs: let them land, then start over
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    a_spec = false;
-  }
   switch (mi) {
-    case 1: joint_wide_tiles<1>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
-    case 2: joint_wide_tiles<2>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
-    case 3: joint_wide_tiles<3>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
-    default: joint_wide_tiles<4>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, a_spec, smem_raw); break;
+    case 1: joint_wide_tiles<1>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, smem_raw); break;
+    case 2: joint_wide_tiles<2>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, smem_raw); break;
+    case 3: joint_wide_tiles<3>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, smem_raw); break;
+    default: joint_wide_tiles<4>(m, c, rs_a, rs_b, mt, mt_step, tiles, nt, early, smem_raw); break;
   }
 }
 

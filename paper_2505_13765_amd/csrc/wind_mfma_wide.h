@@ -15,13 +15,14 @@
 // the one being multiplied: twice the look-ahead, in time, of 64-wide K tiles.
 //
 // LDS: B ring (5 x 256 rows x 64 B), then A ring (5 x 256 rows x 64 B, of which 64 MI are used).
-// Neither depends on the tile height, so the first stages can be requested before the number of
-// rows is known.  The 16-byte chunk c of row r is stored at chunk position c ^ ((r >> 2) & 3): the
+// The B ring's first stages are requested before the number of rows is known.  (Requesting the A
+// rows as well at that point, for the tallest tile, was tried: no gain, the first stage's arrival is
+// not what the row count waits for.)  The 16-byte chunk c of row r is stored at chunk position c ^ ((r >> 2) & 3): the
 // fragment reads of 16 consecutive rows then fall on 16 distinct 16-byte slots modulo 256 bytes.
 //
 // Rows of a tile: the tile `mt` of `tiles` owns the 32-row blocks mt + tiles * q, q = 0 .. 2 MI - 1
 // (block q sits at rows 32 q of the LDS stage); wave (wm, wn) multiplies blocks q = 2 mi + wm with
-// columns 128 wn .. 128 wn + 127.  Blocks with small q belong to the tile at every tile height.
+// columns 128 wn .. 128 wn + 127.
 // Loads: a group of 16 rows per wave-wide load; wave w fetches A groups 4 i + w (i < MI) and B groups
 // 4 w + i (i < 4) of every stage.  The loads are buffer loads: descriptor and slab offset in scalar
 // registers, lane offsets that never change, so a refill costs the wave two instructions (measured
@@ -51,15 +52,12 @@ struct WideCfg {
   static constexpr int WM = 32 * MI_, WN = 128, WAVES_M = 2, WAVES_N = 2, NWAVES = 4, NT = 256;
   static constexpr int LB = 4, LA = MI_;             // loads per wave and stage
   static constexpr int LPW = LA + LB;
-  static constexpr int XA = MI_ > 3 ? MI_ - 3 : 0;   // A loads per wave and stage beyond the three requested ahead of the row count
-  static constexpr int SA = MI_ - XA;
   static_assert(4 * LPW < 64, "vmcnt range");
 };
 constexpr int kWideStages = 5, kWideStage = 256 * 64;
 constexpr int kWideABase = kWideStages * kWideStage;
 constexpr int kWideSmemBytes = 2 * kWideStages * kWideStage;
 constexpr int kWideMinK = 320;     // ten stages: the ring's start-up and its tail do not overlap
-constexpr int kWideSpecLoads = 3;  // A loads per wave and stage that every tile height of at least 192 rows shares
 static_assert(kWideSmemBytes <= 160 * 1024, "LDS");
 
 // Buffer descriptor of a dense byte range (raw buffer, offsets beyond `bytes` read as zero).
@@ -98,23 +96,20 @@ __device__ __forceinline__ void wide_head_b(i32x4 rs_b, uint32_t slab_b, int n0,
     for (int i = 0; i < 4; ++i)
       wide_load(rs_b, smem + s * kWideStage + (wave * 4 + i) * 1024, wide_boff(n0, wave * 4 + i), (uint32_t)(s < KS ? s : KS - 1) * slab_b);
 }
-// A loads i0 .. i1 - 1 of the wave, for the ring's five stages.
-__device__ __forceinline__ void wide_head_a(i32x4 rs_a, uint32_t slab_a, int mt, int tiles, int a_rows, int i0, int i1, int KS,
-                                            unsigned char *smem) {
+// The wave's first NA A loads of every stage, for the ring's five stages.
+template <int NA>
+__device__ __forceinline__ void wide_head_a(i32x4 rs_a, uint32_t slab_a, int mt, int tiles, int a_rows, int KS, unsigned char *smem) {
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 #pragma unroll
   for (int s = 0; s < kWideStages; ++s)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (i >= i0 && i < i1)
-        wide_load(rs_a, smem + kWideABase + s * kWideStage + (4 * i + wave) * 1024, wide_aoff(mt, tiles, 4 * i + wave, a_rows),
-                  (uint32_t)(s < KS ? s : KS - 1) * slab_a);
+    for (int i = 0; i < NA; ++i)
+      wide_load(rs_a, smem + kWideABase + s * kWideStage + (4 * i + wave) * 1024, wide_aoff(mt, tiles, 4 * i + wave, a_rows),
+                (uint32_t)(s < KS ? s : KS - 1) * slab_a);
 }
-
 // The K loop up to, but not including, the last K step, whose operand fragments are left in af[1],
 // bfr[1] (wide_last_step).  rs_a / rs_b: descriptors of the slab layouts of A and B.  The B loads of
-// stages 0..4 are on their way (wide_head_b), and, if a_head_done, the first min(MI, 3) A loads per
-// stage (wide_head_a).  K = 32 KS, KS >= 10.  acc is set by `after_issue`, which runs behind the
+// stages 0..4 are on their way (wide_head_b); the A loads follow here.  K = 32 KS, KS >= 10.  acc is set by `after_issue`, which runs behind the
 // first loads.  The transposed block is accumulated (MFMA operands exchanged): acc[mi][ni] holds B
 // rows down the registers and A rows across the lanes.
 // DBGF (micro-benchmarks only) bit 0: st[0] = time of the first barrier's passing (100 MHz clock), st[1] =
@@ -122,14 +117,13 @@ __device__ __forceinline__ void wide_head_a(i32x4 rs_a, uint32_t slab_a, int mt,
 // refills; bit 2: no fragment reads after the first.
 template <class Cfg, class Init, int DBGF = 0>
 __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4 rs_b, uint32_t slab_b, int KS, int mt, int tiles,
-                                              int n0, int a_rows, bool a_head_done, unsigned char *smem,
+                                              int n0, int a_rows, unsigned char *smem,
                                               f32x16 (&acc)[Cfg::MI][Cfg::NI], bf16x8 (&af)[2][Cfg::MI], bf16x8 (&bfr)[2][Cfg::NI],
                                               Init after_issue, long long *st = nullptr) {
   constexpr bool DBG = DBGF & 1, NOLOAD = DBGF & 2, NOREAD = DBGF & 4;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int wm = wave >> 1, wn = wave & 1;
-  if (!a_head_done) wide_head_a(rs_a, slab_a, mt, tiles, a_rows, 0, Cfg::SA, KS, smem);
-  if (Cfg::XA) wide_head_a(rs_a, slab_a, mt, tiles, a_rows, Cfg::SA, Cfg::MI, KS, smem);
+  wide_head_a<Cfg::LA>(rs_a, slab_a, mt, tiles, a_rows, KS, smem);
   uint32_t aoff[Cfg::LA], boff[Cfg::LB];
 #pragma unroll
   for (int i = 0; i < Cfg::LA; ++i) aoff[i] = wide_aoff(mt, tiles, 4 * i + wave, a_rows);
@@ -182,8 +176,9 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
   };
   auto no_load = [](int) {};
 
-  // every B load of the head and A of stage 0 have landed
-  if (Cfg::XA) wait_vmcnt<4 * Cfg::XA>(); else wait_vmcnt<4 * Cfg::SA>();
+  // the head's loads that follow those of a stage (B first, then A): the later stages' A loads
+  constexpr int H = Cfg::LA;
+  wait_vmcnt<4 * H>();   // stage 0 has landed
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   long long t_loop = 0, t_wait = 0;
@@ -219,7 +214,6 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
   using T = integral_constant<bool, true>;
   using F = integral_constant<bool, false>;
   // start-up: behind the last head load of tile j + 1 sit the head's loads of later tiles and the refills so far
-  constexpr int H = Cfg::XA ? Cfg::XA : Cfg::SA;
   body(integral_constant<int, 3 * H>{}, F{}, T{});
   body(integral_constant<int, 2 * H + Cfg::LPW>{}, T{}, T{});
   body(integral_constant<int, H + 2 * Cfg::LPW>{}, T{}, T{});
