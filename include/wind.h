@@ -364,6 +364,13 @@ int wind_get_loop_info(wind_model *m, int *workgroups, int *one_l2);
  *             utterances and in the list of utterances that emitted with an atomic counter (the
  *             order of those lists then varies between runs, the decoded output does not); 0: the
  *             last workgroup to finish compacts the lists in order
+ *   "joint_wide"  which iterations of the graph of per-step kernels evaluate the joiner's output layer on
+ *             256-column tiles (bf16 models with Hj >= 320) instead of 128-column tiles: 1 (default) those
+ *             with so many window rows that the tiles are at least 192 rows high when they fill the
+ *             chip (above 1024 rows for 8192 labels, above 2048 for 4096), chosen per graph replay from
+ *             the active count the host last read back or from the previous call of the same shape; 0
+ *             none; 2 all.  The decoded output does not depend on it: both kernels form every logit by
+ *             the same operations in the same order
  *   "lstm_rec"  1 (default): where the prediction network runs on MFMA tiles, the recurrent half of every
  *             LSTM layer's gate sums (w_hh . h) is kept ready for the hidden vectors as they stand and
  *             renewed beside the projection, so a step only adds the input half once the label is

@@ -119,6 +119,7 @@ struct wind_model {
   hipGraphExec_t graph_exec[2] = {nullptr, nullptr};
   GraphKey graph_key{};
   bool graph_valid = false;
+  int opt_enc_wide = 1;         // large calls: encoder projection on the 256-column tile core (where the model allows)
   int opt_joint_wide = 1;       // 0: never, 1: iterations with more than wide_rows window rows, 2: always (where the model allows)
   long long prev_wide_iters = 0, last_wide_iters = 0;   // iterations of the previous / last call that had more than wide_rows window rows
   int opt_graph = 1, opt_unroll = 16;
@@ -422,6 +423,14 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first =
   return check_launch("prediction step");
 }
 
+// Large calls of bf16 models whose input size the 256-column tile core takes (ten K stages of 32 at least, buffer
+// descriptors with 32-bit sizes) run the encoder projection on it (option enc_wide).
+bool enc_wide_ok(const wind_model *m, int B, int T) {
+  const ModelDev &d = m->dev;
+  if (!m->opt_enc_wide || !d.w_enc_slab || d.D < kWideMinK || d.D % 32) return false;
+  return ((unsigned long long)B * T + 256) * d.D * 2 < (1ull << 32);
+}
+
 int enqueue_prologue(wind_model *m, hipStream_t s) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
@@ -432,11 +441,18 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
   if (c.T > 0) {
     if (m->dtype == WIND_BF16 && c.enc_b) {
       const long long rows = (long long)c.B * c.T;
-      launch(m, s, WIND_K_ENC_PROJ, false, enc_round_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, d, c);
-      const int tiles_per_utt = (c.T + EncBigCfg::BM - 1) / EncBigCfg::BM;
-      dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncBigCfg::BN - 1) / EncBigCfg::BN));
-      launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_ring5_kernel<EncBigCfg>, grid, dim3(EncBigCfg::NT),
-             EncBigCfg::SMEM_BYTES, d, c, tiles_per_utt);
+      const bool wide = enc_wide_ok(m, c.B, c.T);
+      launch(m, s, WIND_K_ENC_PROJ, false, enc_round_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, d, c, wide ? 1 : 0);
+      if (wide) {
+        const int tiles_per_utt = (c.T + 255) / 256, n_row_tiles = c.B * tiles_per_utt, n_col_tiles = (d.Hj + 255) / 256;
+        launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_wide_kernel, dim3((unsigned)((n_row_tiles + 7) / 8 * 8 * n_col_tiles)), dim3(256),
+               kWideSmemBytes, d, c, tiles_per_utt, n_row_tiles, n_col_tiles);
+      } else {
+        const int tiles_per_utt = (c.T + EncBigCfg::BM - 1) / EncBigCfg::BM;
+        dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncBigCfg::BN - 1) / EncBigCfg::BN));
+        launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_ring5_kernel<EncBigCfg>, grid, dim3(EncBigCfg::NT),
+               EncBigCfg::SMEM_BYTES, d, c, tiles_per_utt);
+      }
     } else if (m->dtype == WIND_BF16) {
       const int tiles_per_utt = (c.T + EncCfg::BM - 1) / EncCfg::BM;
       dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncCfg::BN - 1) / EncCfg::BN));
@@ -880,6 +896,15 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   }
   const void *tmp = nullptr;
   chk(upload_matrix(m, w->w_enc, w->Hj, w->D, round_up(w->Hj, 256), &d.w_enc));
+  d.w_enc_slab = nullptr;
+  if (m->dtype == WIND_BF16 && w->D >= kWideMinK && w->D % 32 == 0) {
+    // the same rows in slabs of 32 inputs, for enc_proj_wide_kernel
+    const size_t hj_pad = round_up(w->Hj, 256);
+    std::vector<uint16_t> h(hj_pad * w->D, 0);
+    for (size_t j = 0; j < (size_t)w->Hj; ++j)
+      for (size_t k = 0; k < (size_t)w->D; ++k) h[((k >> 5) * hj_pad + j) * 32 + (k & 31)] = host_bf16(w->w_enc[j * w->D + k]);
+    chk(upload(m, h, &d.w_enc_slab));
+  }
   chk(upload(m, std::vector<float>(w->b_enc, w->b_enc + w->Hj), &tmp)); d.b_enc = (const float *)tmp;
   chk(upload_matrix(m, w->w_pred, w->Hj, Hp, w->Hj, &d.w_pred));
   chk(upload(m, std::vector<float>(w->b_pred, w->b_pred + w->Hj), &tmp)); d.b_pred = (const float *)tmp;
@@ -924,6 +949,7 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
   if (rc == WIND_OK) {
     hipError_t e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)joint_wide_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWideSmemBytes);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)enc_proj_wide_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWideSmemBytes);
     static_assert(kFusedSteps == 5, "one resident loop instance per number of fused K steps: here and at the launch");
     const void *loop_instances[] = {(const void *)wind_loop_kernel<0>, (const void *)wind_loop_kernel<1>, (const void *)wind_loop_kernel<2>,
                                     (const void *)wind_loop_kernel<3>, (const void *)wind_loop_kernel<4>, (const void *)wind_loop_kernel<5>};
@@ -1175,6 +1201,10 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   if (!std::strcmp(key, "loop_spin_limit")) {
     if (value < 0 || value > (1ll << 30)) return fail(WIND_ERR_ARG, "loop_spin_limit must be in 0..2^30");
     m->opt_loop_spin_limit = value;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "enc_wide")) {
+    m->opt_enc_wide = value != 0;
     return WIND_OK;
   }
   if (!std::strcmp(key, "joint_wide")) {

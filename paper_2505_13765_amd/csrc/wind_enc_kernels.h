@@ -93,17 +93,20 @@ __global__ __launch_bounds__(Cfg::NT) void enc_proj_mfma_kernel(ModelDev m, Call
 
 // Large calls: the encoder outputs are first rounded to bf16 rows (valid frames only), so that the
 // projection can use the direct-to-LDS tile core at full tile size.
-__global__ __launch_bounds__(256) void enc_round_kernel(ModelDev m, CallDev c) {
+// (slab: in slabs of 32 inputs, [D / 32][B*T + 256][32], for enc_proj_wide_kernel)
+__global__ __launch_bounds__(256) void enc_round_kernel(ModelDev m, CallDev c, int slab) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long long row = (long long)blockIdx.x * 4 + wave;
   if (row >= (long long)c.B * c.T) return;
   const int b = (int)(row / c.T), t = (int)(row - (long long)b * c.T);
   if (t >= c.len[b]) return;
   const float *src = c.enc + (size_t)row * m.D;
-  bf16_t *dst = c.enc_b + (size_t)row * m.D;
+  const size_t slab_elems = ((size_t)c.B * c.T + 256) * 32;
+  bf16_t *dst = slab ? c.enc_b + (size_t)row * 32 : c.enc_b + (size_t)row * m.D;
   for (int k = lane * 4; k < m.D; k += 256) {
     const float4 x = *reinterpret_cast<const float4 *>(src + k);
-    *reinterpret_cast<uint2 *>(dst + k) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+    bf16_t *p = slab ? dst + (size_t)(k >> 5) * slab_elems + (k & 31) : dst + k;
+    *reinterpret_cast<uint2 *>(p) = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
   }
 }
 
@@ -139,6 +142,69 @@ __global__ __launch_bounds__(Cfg::NT) void enc_proj_ring5_kernel(ModelDev m, Cal
         const int t = t0 + wm * Cfg::WM + acc_row(mi, r, lane);
         if (t < len) c.e[((size_t)b * c.T + t) * m.Hj + col] = acc[mi][ni][r] + bias;
       }
+  }
+}
+
+// The same product on the 256-column tile core of wind_mfma_wide.h (four waves of up to 512 registers, operands
+// in slabs of 32 inputs, five-stage ring).  A row tile is up to 256 consecutive frames of one utterance, as high
+// as the frames left need (64 MI rows); the four column tiles of a row tile get launch ids that differ by
+// multiples of 8, so that they run on one XCD and the frames come from memory once.  Every output is the same
+// chain of MFMAs over D as in the other kernels.
+template <int MI>
+__device__ __forceinline__ void enc_proj_wide_tile(const ModelDev &m, const CallDev &c, int b, int t0, int len, int n0,
+                                                   unsigned char *smem_raw) {
+  using Cfg = WideCfg<MI>;
+  const int KS = m.D / 32, hj_pad = (m.Hj + 255) / 256 * 256;
+  const long long rows_total = (long long)c.B * c.T + 256;
+  const uint32_t slab_a = (uint32_t)rows_total * 64u, slab_b = (uint32_t)hj_pad * 64u;
+  const i32x4 rs_a = wide_rsrc(c.enc_b, slab_a * (uint32_t)KS), rs_b = wide_rsrc(m.w_enc_slab, slab_b * (uint32_t)KS);
+  const int wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1, lane = threadIdx.x & 63;
+  f32x16 acc[Cfg::MI][Cfg::NI];
+  bf16x8 af[2][Cfg::MI], bfr[2][Cfg::NI];
+  wide_head_b(rs_b, slab_b, n0, KS, smem_raw);
+  auto zero = [&]() {
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+  };
+  wide_mainloop<Cfg>(rs_a, slab_a, rs_b, slab_b, KS, 0, 1, n0, (int)rows_total, smem_raw, acc, af, bfr, zero, nullptr, b * c.T + t0);
+  // Transposed blocks: a lane holds four runs of four consecutive columns of one row, 16 stores of 16 bytes per
+  // block pair.  (Not transposed, a store would write 32 consecutive columns of a row, whole cache lines, but
+  // four times as many store instructions: 0.88 against 0.67 ms on the 128 x 2000-frame batch.)
+  wide_last_step<Cfg>(acc, af[1], bfr[1], [&](int mi, int p, const f32x16 &lo, const f32x16 &hi) {
+    const int t = t0 + (2 * mi + wm) * 32 + (lane & 31);
+    if (t >= len) return;
+    float *out = c.e + ((size_t)b * c.T + t) * m.Hj;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = n0 + wn * 128 + 64 * p + 32 * h + 8 * g + 4 * (lane >> 5);
+        if (col >= m.Hj) continue;   // Hj is a multiple of 64: whole groups of four
+        const float4 bias = *reinterpret_cast<const float4 *>(m.b_enc + col);
+        const f32x16 &v = h ? hi : lo;
+        *reinterpret_cast<float4 *>(out + col) = make_float4(v[4 * g] + bias.x, v[4 * g + 1] + bias.y, v[4 * g + 2] + bias.z, v[4 * g + 3] + bias.w);
+      }
+  });
+}
+
+__global__ __launch_bounds__(256) void enc_proj_wide_kernel(ModelDev m, CallDev c, int tiles_per_utt, int n_row_tiles, int n_col_tiles) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int id = (int)blockIdx.x, q = id >> 3;
+  const int rt = (q / n_col_tiles) * 8 + (id & 7), ct = q % n_col_tiles;
+  if (rt >= n_row_tiles) return;
+  const int b = rt / tiles_per_utt, t0 = (rt % tiles_per_utt) * 256;
+  const int len = c.len[b];
+  if (t0 >= len) return;
+  const int mi = (min(len - t0, 256) + 63) / 64;
+  switch (mi) {
+    case 1: enc_proj_wide_tile<1>(m, c, b, t0, len, ct * 256, smem_raw); break;
+    case 2: enc_proj_wide_tile<2>(m, c, b, t0, len, ct * 256, smem_raw); break;
+    case 3: enc_proj_wide_tile<3>(m, c, b, t0, len, ct * 256, smem_raw); break;
+    default: enc_proj_wide_tile<4>(m, c, b, t0, len, ct * 256, smem_raw); break;
   }
 }
 

@@ -3,10 +3,13 @@
 // One loop iteration (Method, Algorithm 2, all active utterances at once), bf16 models:
 //   build_z        window gather: z[r,j,:] = relu(e[b, t_b + j, :] + p[b,:]) in bf16, plus the
 //                  blank logit and the norm of every row in fp32
-//   joint_ws       label logits of every window row on bf16 MFMA; per row and per 64-column part
-//                  the two largest (logit, column) keys are kept, nothing else is stored.  Tiles of
-//                  128 columns whose height (64 to 256 rows) and number per workgroup follow the
-//                  iteration's row count; four waves of a workgroup multiply, four fetch
+//   joint_ws /     label logits of every window row on bf16 MFMA; per row and per 64-column part
+//   joint_wide     the three largest (logit, column) keys are kept, nothing else is stored.  Tiles
+//                  whose height (64 to 256 rows) and number per workgroup follow the iteration's
+//                  row count: 128 columns wide, four waves of a workgroup multiplying and four
+//                  fetching (joint_ws), or, in iterations with many rows, 256 columns wide on four
+//                  waves of up to 512 registers that do both (joint_wide; build_z then writes z in
+//                  slabs of 32 hidden units)
 //   decide         per utterance: row argmax from the keys, near-ties re-decided with fp32 dot
 //                  products, first non-blank row by wavefront ballot, pointer / hypothesis update,
 //                  the utterance's place in the next iteration's slot table and in the emit list

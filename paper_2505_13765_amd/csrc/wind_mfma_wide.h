@@ -80,9 +80,10 @@ __device__ __forceinline__ uint32_t wide_boff(int n0, int gb) {
   const int lane = threadIdx.x & 63, brow = 16 * gb + (lane >> 2);
   return (uint32_t)((n0 + brow) * 64 + (((lane & 3) ^ ((brow >> 2) & 3)) * 16));
 }
-__device__ __forceinline__ uint32_t wide_aoff(int mt, int tiles, int g, int a_rows) {
+// (row0: where the tiles' row numbering starts in A; with tiles = 1 and mt = 0 a tile is the 64 MI rows from row0 on)
+__device__ __forceinline__ uint32_t wide_aoff(int mt, int tiles, int g, int a_rows, int row0 = 0) {
   const int lane = threadIdx.x & 63, trow = 16 * g + (lane >> 2);
-  int grow = (mt + tiles * (trow >> 5)) * 32 + (trow & 31);
+  int grow = row0 + (mt + tiles * (trow >> 5)) * 32 + (trow & 31);
   grow = grow < a_rows ? grow : a_rows - 1;   // blocks past the end of A: any row, its keys are not stored
   return (uint32_t)(grow * 64 + (((lane & 3) ^ ((trow >> 2) & 3)) * 16));
 }
@@ -98,35 +99,38 @@ __device__ __forceinline__ void wide_head_b(i32x4 rs_b, uint32_t slab_b, int n0,
 }
 // The wave's first NA A loads of every stage, for the ring's five stages.
 template <int NA>
-__device__ __forceinline__ void wide_head_a(i32x4 rs_a, uint32_t slab_a, int mt, int tiles, int a_rows, int KS, unsigned char *smem) {
+__device__ __forceinline__ void wide_head_a(i32x4 rs_a, uint32_t slab_a, int mt, int tiles, int a_rows, int KS, unsigned char *smem,
+                                            int row0 = 0) {
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 #pragma unroll
   for (int s = 0; s < kWideStages; ++s)
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-      wide_load(rs_a, smem + kWideABase + s * kWideStage + (4 * i + wave) * 1024, wide_aoff(mt, tiles, 4 * i + wave, a_rows),
+      wide_load(rs_a, smem + kWideABase + s * kWideStage + (4 * i + wave) * 1024, wide_aoff(mt, tiles, 4 * i + wave, a_rows, row0),
                 (uint32_t)(s < KS ? s : KS - 1) * slab_a);
 }
 // The K loop up to, but not including, the last K step, whose operand fragments are left in af[1],
 // bfr[1] (wide_last_step).  rs_a / rs_b: descriptors of the slab layouts of A and B.  The B loads of
 // stages 0..4 are on their way (wide_head_b); the A loads follow here.  K = 32 KS, KS >= 10.  acc is set by `after_issue`, which runs behind the
-// first loads.  The transposed block is accumulated (MFMA operands exchanged): acc[mi][ni] holds B
-// rows down the registers and A rows across the lanes.
+// first loads.  SWAP: the transposed block is accumulated (MFMA operands exchanged): acc[mi][ni] holds B
+// rows down the registers and A rows across the lanes (an epilogue that reduces over B rows then works
+// inside a lane); otherwise A rows down the registers and B rows across the lanes (rows of C are then
+// stored 32 consecutive columns per instruction).
 // DBGF (micro-benchmarks only) bit 0: st[0] = time of the first barrier's passing (100 MHz clock), st[1] =
 // shader clock ticks in the loop, st[2] = of those, ticks waiting for loads and at the barrier; bit 1: no
 // refills; bit 2: no fragment reads after the first.
-template <class Cfg, class Init, int DBGF = 0>
+template <class Cfg, class Init, int DBGF = 0, bool SWAP = true>
 __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4 rs_b, uint32_t slab_b, int KS, int mt, int tiles,
                                               int n0, int a_rows, unsigned char *smem,
                                               f32x16 (&acc)[Cfg::MI][Cfg::NI], bf16x8 (&af)[2][Cfg::MI], bf16x8 (&bfr)[2][Cfg::NI],
-                                              Init after_issue, long long *st = nullptr) {
+                                              Init after_issue, long long *st = nullptr, int row0 = 0) {
   constexpr bool DBG = DBGF & 1, NOLOAD = DBGF & 2, NOREAD = DBGF & 4;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int wm = wave >> 1, wn = wave & 1;
-  wide_head_a<Cfg::LA>(rs_a, slab_a, mt, tiles, a_rows, KS, smem);
+  wide_head_a<Cfg::LA>(rs_a, slab_a, mt, tiles, a_rows, KS, smem, row0);
   uint32_t aoff[Cfg::LA], boff[Cfg::LB];
 #pragma unroll
-  for (int i = 0; i < Cfg::LA; ++i) aoff[i] = wide_aoff(mt, tiles, 4 * i + wave, a_rows);
+  for (int i = 0; i < Cfg::LA; ++i) aoff[i] = wide_aoff(mt, tiles, 4 * i + wave, a_rows, row0);
 #pragma unroll
   for (int i = 0; i < Cfg::LB; ++i) boff[i] = wide_boff(n0, wave * 4 + i);
   unsigned char *const lds_a = smem + kWideABase + wave * 1024, *const lds_b = smem + wave * 4 * 1024;
@@ -164,7 +168,8 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
 #pragma unroll
     for (int x = 0; x < NMFMA; ++x) {
       const int mi = x / Cfg::NI, ni = x % Cfg::NI;
-      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0);
+      acc[mi][ni] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0)
+                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
       if (!NOREAD) {
 #pragma unroll
         for (int y = 0; y < PER; ++y)
@@ -227,16 +232,18 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
 }
 
 // The last K step.  Every accumulator's final MFMA writes a fresh value that the VALU can read, and
-// fin(mi, p, lo, hi) gets the finished transposed blocks of columns 64 p .. 64 p + 31 and 64 p + 32 ..
+// fin(mi, p, lo, hi) gets the finished blocks (transposed with SWAP) of columns 64 p .. 64 p + 31 and 64 p + 32 ..
 // 64 p + 63 (p = 0, 1 within the wave's 128 columns) of row block mi while the next pair's MFMAs run.
-template <class Cfg, class Fin>
+template <class Cfg, class Fin, bool SWAP = true>
 __device__ __forceinline__ void wide_last_step(f32x16 (&acc)[Cfg::MI][Cfg::NI], const bf16x8 (&af)[Cfg::MI],
                                                const bf16x8 (&bfr)[Cfg::NI], Fin fin) {
   f32x16 r[2][2];
   auto last = [&](int k) {
     const int mi = k >> 1, p = k & 1;
-    r[k & 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p], af[mi], acc[mi][2 * p], 0, 0, 0);
-    r[k & 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p + 1], af[mi], acc[mi][2 * p + 1], 0, 0, 0);
+    r[k & 1][0] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p], af[mi], acc[mi][2 * p], 0, 0, 0)
+                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[2 * p], acc[mi][2 * p], 0, 0, 0);
+    r[k & 1][1] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p + 1], af[mi], acc[mi][2 * p + 1], 0, 0, 0)
+                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[2 * p + 1], acc[mi][2 * p + 1], 0, 0, 0);
   };
   last(0);
 #pragma unroll

@@ -29,6 +29,7 @@ struct ModelDev {
   const void *w_cat_t[kMaxLayers]; // bf16 models: the same rows grouped for MFMA tiles, see lstm_layer_dma_kernel
   const float *b_cat_t[kMaxLayers];
   const void *w_enc;            // [Hj_pad, D]
+  const void *w_enc_slab;       // bf16 models: the same matrix in slabs of 32 inputs, [D / 32][Hj_pad][32] (wide tiles), or null
   const float *b_enc;           // [Hj]
   const void *w_pred;           // [Hj, Hp]
   const float *b_pred;          // [Hj]
@@ -46,7 +47,8 @@ struct CallDev {
   const int *lengths;           // [B] as given
   int *out_tokens, *out_frames, *out_counts;
   float *e;                     // [B*T, Hj]
-  bf16_t *enc_b;                // [B*T + 256, D] encoder outputs rounded to bf16 (large calls only, else null)
+  bf16_t *enc_b;                // [B*T + 256, D] encoder outputs rounded to bf16 (large calls only, else null); for
+                                //   enc_proj_wide_kernel in slabs of 32 inputs, [D / 32][B*T + 256][32]
   int *len;                     // [B] clamped to [0,T]
   // Active utterances live in a slot table, ping-pong by iteration parity: slot a of the current
   // parity holds everything an iteration needs to know about its a-th active utterance, so that a

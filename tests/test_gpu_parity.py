@@ -437,26 +437,37 @@ def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
 
 def test_encoder_projection_against_oracle(torch_cuda):
     """e = W_enc f + b_enc as a decode call computes it, element by element against the oracle, on the
-    route of large calls (B * T >= 16384: bf16 rows, 256 x 256 tiles) and on the route of small ones,
-    with ragged lengths (a row tile that ends inside an utterance's padding)."""
+    routes of large calls (B * T >= 16384: bf16 rows; 256-column tiles on four waves that multiply and fetch,
+    with option enc_wide = 0 the 256 x 256 tiles of eight waves) and on the route of small ones,
+    with ragged lengths (row tiles of every height that end inside an utterance's padding).  The two
+    large-call routes form every output by the same operations in the same order: identical bits."""
     for B, T in ((9, 2000), (3, 300)):
         cfg = wi.scaled(wi.CONFIGS["largevocab_b128"], B, T - 50, T)
         m, o, _ = load(cfg)
         enc, lens = wi.make_batch(cfg)
         lens[1], lens[B - 1] = T // 3, 257
+        if B == 9:
+            lens[2], lens[3], lens[4] = 256 + 70, 512 + 130, 1024 + 192     # last row tiles of 128, 192 and 256 rows
         assert (B * enc.shape[1] >= 16384) == (B == 9)
         d_enc, d_len = to_dev(torch_cuda, enc, lens)
-        e = m.debug_enc_proj(d_enc, d_len)
-        rng = np.random.default_rng(B)
-        worst = 0.0
-        for b in range(B):
-            ts = {0, int(lens[b]) - 1, min(255, int(lens[b]) - 1), min(256, int(lens[b]) - 1)}
-            ts |= set(rng.integers(0, lens[b], size=6).tolist())
-            for t in ts:
-                ref = o.encoder_projection(enc[b, t])
-                worst = max(worst, float(np.abs(e[b, t] - ref).max()))
-        print(f"encoder projection B={B} T={enc.shape[1]}: max |e - oracle| = {worst:.3e}")
-        assert worst < TOL_F32      # exact bf16 products, fp32 accumulation
+        routes = {}
+        for wide in ((1, 0) if B == 9 else (1,)):
+            m.set_option("enc_wide", wide)
+            e = m.debug_enc_proj(d_enc, d_len)
+            routes[wide] = e
+            rng = np.random.default_rng(B)
+            worst = 0.0
+            for b in range(B):
+                ts = {0, int(lens[b]) - 1, min(255, int(lens[b]) - 1), min(256, int(lens[b]) - 1)}
+                ts |= set(rng.integers(0, lens[b], size=6).tolist())
+                for t in ts:
+                    ref = o.encoder_projection(enc[b, t])
+                    worst = max(worst, float(np.abs(e[b, t] - ref).max()))
+            print(f"encoder projection B={B} T={enc.shape[1]} enc_wide={wide}: max |e - oracle| = {worst:.3e}")
+            assert worst < TOL_F32      # exact bf16 products, fp32 accumulation
+        if len(routes) == 2:
+            for b in range(B):
+                assert np.array_equal(routes[0][b, : lens[b]], routes[1][b, : lens[b]]), b
         m.close()
 
 
