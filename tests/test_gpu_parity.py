@@ -332,6 +332,7 @@ def decode_keys(keys, width):
 @pytest.mark.parametrize("name,B,W,V", [("largevocab_b128", 15, 16, None), ("largevocab_b128", 31, 16, None),
                                         ("largevocab_b128", 47, 16, None), ("largevocab_b128", 63, 16, None),
                                         ("largevocab_b128", 83, 16, None), ("largevocab_b128", 128, 16, None),
+                                        ("largevocab_b128", 168, 16, None),   # 2688 rows: two row tiles per workgroup in both kernels
                                         ("batch32", 9, 8, None), ("batch32", 20, 5, 300), ("lowblank_b256", 70, 16, None)])
 @pytest.mark.parametrize("wide", [1, 2])
 def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V, wide):
@@ -359,7 +360,7 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V, wide):
     g0 = o.decoder_from_scratch([])
     rng = np.random.default_rng(B * 1000 + W)
     rows = set(rng.choice(B * W, size=min(B * W, 96), replace=False).tolist())
-    rows |= {0, B * W - 1, (B // 2) * W + W - 1} | {r for r in (63, 64, 255, 256, 767, 768, 1023, 1024) if r < B * W}
+    rows |= {0, B * W - 1, (B // 2) * W + W - 1} | {r for r in (63, 64, 255, 256, 767, 768, 1023, 1024, 2047, 2048, 2303, 2304) if r < B * W}
     worst = 0.0
     for r in sorted(rows):
         b, j = divmod(r, W)
