@@ -170,7 +170,7 @@ __device__ __forceinline__ void enc_proj_wide_tile(const ModelDev &m, const Call
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
   };
-  wide_mainloop<Cfg>(rs_a, slab_a, rs_b, slab_b, KS, 0, 1, n0, (int)rows_total, smem_raw, acc, af, bfr, zero, nullptr, b * c.T + t0);
+  wide_mainloop<Cfg>(rs_a, slab_a, rs_b, slab_b, KS, 0, 1, n0, (int)rows_total, smem_raw, acc, af, bfr, zero, b * c.T + t0);
   // Transposed blocks: a lane holds four runs of four consecutive columns of one row, 16 stores of 16 bytes per
   // block pair.  (Not transposed, a store would write 32 consecutive columns of a row, whole cache lines, but
   // four times as many store instructions: 0.88 against 0.67 ms on the 128 x 2000-frame batch.)

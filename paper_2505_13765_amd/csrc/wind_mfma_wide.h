@@ -70,7 +70,11 @@ __device__ __forceinline__ i32x4 wide_rsrc(const void *base, uint32_t bytes) {
   r[3] = 0x00020000;
   return r;
 }
-// 16 bytes per lane from rsrc[soff + voff] to LDS: lane l's bytes land at dst + 16 l.
+// 16 bytes per lane from rsrc[soff + voff] to LDS: lane l's bytes land at dst + 16 l.  The compiler has no
+// builtin for the 16-byte form, hence the assembly; it writes M0 (the LDS address), which the compiler sets
+// itself before each of its own uses, and its completion is counted in vmcnt like any load's, which the
+// code that calls this waits for by hand (the compiler's own counts do not know of these loads: any wait it
+// inserts for a load of its own is then only stricter than needed, loads returning in order).
 __device__ __forceinline__ void wide_load(i32x4 rsrc, unsigned char *dst, uint32_t voff, uint32_t soff) {
   const uint32_t m = (uint32_t)(uintptr_t)(lds_ptr *)dst;
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(m), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
@@ -111,20 +115,15 @@ __device__ __forceinline__ void wide_head_a(i32x4 rs_a, uint32_t slab_a, int mt,
 }
 // The K loop up to, but not including, the last K step, whose operand fragments are left in af[1],
 // bfr[1] (wide_last_step).  rs_a / rs_b: descriptors of the slab layouts of A and B.  The B loads of
-// stages 0..4 are on their way (wide_head_b); the A loads follow here.  K = 32 KS, KS >= 10.  acc is set by `after_issue`, which runs behind the
-// first loads.  SWAP: the transposed block is accumulated (MFMA operands exchanged): acc[mi][ni] holds B
-// rows down the registers and A rows across the lanes (an epilogue that reduces over B rows then works
-// inside a lane); otherwise A rows down the registers and B rows across the lanes (rows of C are then
-// stored 32 consecutive columns per instruction).
-// DBGF (micro-benchmarks only) bit 0: st[0] = time of the first barrier's passing (100 MHz clock), st[1] =
-// shader clock ticks in the loop, st[2] = of those, ticks waiting for loads and at the barrier; bit 1: no
-// refills; bit 2: no fragment reads after the first.
-template <class Cfg, class Init, int DBGF = 0, bool SWAP = true>
+// stages 0..4 are on their way (wide_head_b); the A loads follow here.  K = 32 KS, KS >= 10.  acc is set
+// by `after_issue`, which runs behind the first loads.  The transposed block is accumulated (MFMA operands
+// exchanged): acc[mi][ni] holds B rows down the registers and A rows across the lanes, so that an epilogue
+// which reduces over B rows works inside a lane.
+template <class Cfg, class Init>
 __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4 rs_b, uint32_t slab_b, int KS, int mt, int tiles,
                                               int n0, int a_rows, unsigned char *smem,
                                               f32x16 (&acc)[Cfg::MI][Cfg::NI], bf16x8 (&af)[2][Cfg::MI], bf16x8 (&bfr)[2][Cfg::NI],
-                                              Init after_issue, long long *st = nullptr, int row0 = 0) {
-  constexpr bool DBG = DBGF & 1, NOLOAD = DBGF & 2, NOREAD = DBGF & 4;
+                                              Init after_issue, int row0 = 0) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int wm = wave >> 1, wn = wave & 1;
   wide_head_a<Cfg::LA>(rs_a, slab_a, mt, tiles, a_rows, KS, smem, row0);
@@ -136,11 +135,11 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
   unsigned char *const lds_a = smem + kWideABase + wave * 1024, *const lds_b = smem + wave * 4 * 1024;
   uint32_t so_a = 5 * slab_a, so_b = 5 * slab_b;   // slab offsets of the next tiles to fetch
   auto issue_a1 = [&](int i, int stage_off) {
-    if (!NOLOAD) wide_load(rs_a, lds_a + stage_off + i * 4096, aoff[i], so_a);
+    wide_load(rs_a, lds_a + stage_off + i * 4096, aoff[i], so_a);
     if (i == Cfg::LA - 1) so_a += slab_a;
   };
   auto issue_b1 = [&](int i, int stage_off) {
-    if (!NOLOAD) wide_load(rs_b, lds_b + stage_off + i * 1024, boff[i], so_b);
+    wide_load(rs_b, lds_b + stage_off + i * 1024, boff[i], so_b);
     if (i == Cfg::LB - 1) so_b += slab_b;
   };
   after_issue();
@@ -168,13 +167,10 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
 #pragma unroll
     for (int x = 0; x < NMFMA; ++x) {
       const int mi = x / Cfg::NI, ni = x % Cfg::NI;
-      acc[mi][ni] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0)
-                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
-      if (!NOREAD) {
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0);
 #pragma unroll
-        for (int y = 0; y < PER; ++y)
-          if (x * PER + y < NREAD) read_frag(x * PER + y, set ^ 1, off, rks);
-      }
+      for (int y = 0; y < PER; ++y)
+        if (x * PER + y < NREAD) read_frag(x * PER + y, set ^ 1, off, rks);
       load(x);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -186,8 +182,6 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
   wait_vmcnt<4 * H>();   // stage 0 has landed
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  long long t_loop = 0, t_wait = 0;
-  if (DBG) { st[0] = wall_clock64(); t_loop = __builtin_amdgcn_s_memtime(); }
 #pragma unroll
   for (int q = 0; q < NREAD; ++q) read_frag(q, 0, 0, 0);
   // Byte offsets of the stages within their rings: cur = the stage being multiplied, prv = the one before.
@@ -202,12 +196,9 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
       }
     });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of stage j are complete
-    long long tw = 0;
-    if (DBG) tw = __builtin_amdgcn_s_memtime();
     wait_vmcnt<decltype(WAITN)::value>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (DBG) t_wait += __builtin_amdgcn_s_memtime() - tw;
     kstep(1, nxt, 0, [&](int x) {
       if constexpr (decltype(RB)::value) {
         if (x % Cfg::MI == Cfg::MI - 1) issue_b1(x / Cfg::MI, cur);   // one load every MI MFMAs
@@ -228,22 +219,19 @@ __device__ __forceinline__ void wide_mainloop(i32x4 rs_a, uint32_t slab_a, i32x4
   body(integral_constant<int, Cfg::LPW>{}, F{}, F{});
   body(integral_constant<int, 0>{}, F{}, F{});             // j = KS - 2
   kstep(0, cur, 1, no_load);                               // last stage, first K step
-  if (DBG) { st[1] = __builtin_amdgcn_s_memtime() - t_loop; st[2] = t_wait; }
 }
 
 // The last K step.  Every accumulator's final MFMA writes a fresh value that the VALU can read, and
-// fin(mi, p, lo, hi) gets the finished blocks (transposed with SWAP) of columns 64 p .. 64 p + 31 and 64 p + 32 ..
+// fin(mi, p, lo, hi) gets the finished transposed blocks of columns 64 p .. 64 p + 31 and 64 p + 32 ..
 // 64 p + 63 (p = 0, 1 within the wave's 128 columns) of row block mi while the next pair's MFMAs run.
-template <class Cfg, class Fin, bool SWAP = true>
+template <class Cfg, class Fin>
 __device__ __forceinline__ void wide_last_step(f32x16 (&acc)[Cfg::MI][Cfg::NI], const bf16x8 (&af)[Cfg::MI],
                                                const bf16x8 (&bfr)[Cfg::NI], Fin fin) {
   f32x16 r[2][2];
   auto last = [&](int k) {
     const int mi = k >> 1, p = k & 1;
-    r[k & 1][0] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p], af[mi], acc[mi][2 * p], 0, 0, 0)
-                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[2 * p], acc[mi][2 * p], 0, 0, 0);
-    r[k & 1][1] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p + 1], af[mi], acc[mi][2 * p + 1], 0, 0, 0)
-                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[2 * p + 1], acc[mi][2 * p + 1], 0, 0, 0);
+    r[k & 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p], af[mi], acc[mi][2 * p], 0, 0, 0);
+    r[k & 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[2 * p + 1], af[mi], acc[mi][2 * p + 1], 0, 0, 0);
   };
   last(0);
 #pragma unroll
