@@ -40,6 +40,7 @@ int fail(int code, const std::string &msg) {
 using JointCfg = TileCfg<128, 128, 64, 64>;            // debug store kernel
 using EncBigCfg = Ring5Cfg<256, 64, 128>;               // encoder projection of large calls: 256 x 256 tiles
 using EncCfg = TileCfg<128, 128, 64, 64>;
+using EncSmallCfg = TileCfg<64, 64, 32, 32>;   // calls whose 128 x 128 tiles would leave most CUs idle (same sums, same order)
 using PredCfg = DmaCfg<64, 64, 32, 32, 64, 4>;   // 32 utterances (hi and lo rows) x 64 columns, 4-stage ring
 constexpr int kPredMfmaMinBatch = 1;       // below this the FMA prediction network is used
 constexpr size_t kEncRing5MinRows = 16384;   // B * T from which the encoder projection uses 256 x 256 tiles
@@ -148,6 +149,7 @@ struct wind_model {
   double kappa = 8.0;
   double wnorm_max = 0.0;
   int *h_flag = nullptr;  // pinned
+  unsigned long long *h_stats = nullptr;   // pinned, behind h_flag in the same allocation: the call's counters
   int cu_count = 0;            // CUs of the device the model was loaded on (the resident loop kernel wants one per workgroup)
   int loop_info[2] = {0, 0};   // last decode call: workgroups of the resident loop kernel (0: not used), whether they shared one L2
   long long prev_iters = 0;
@@ -456,8 +458,15 @@ int enqueue_prologue(wind_model *m, hipStream_t s) {
     } else if (m->dtype == WIND_BF16) {
       const int tiles_per_utt = (c.T + EncCfg::BM - 1) / EncCfg::BM;
       dim3 grid((unsigned)(c.B * tiles_per_utt), (unsigned)((d.Hj + EncCfg::BN - 1) / EncCfg::BN));
-      launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_mfma_kernel<EncCfg>, grid, dim3(EncCfg::NT), EncCfg::SMEM_BYTES, d, c,
-             tiles_per_utt);
+      if (grid.x * grid.y < 128) {   // a single short utterance: a quarter of the tile on four times the workgroups
+        const int small_per_utt = (c.T + EncSmallCfg::BM - 1) / EncSmallCfg::BM;
+        dim3 sgrid((unsigned)(c.B * small_per_utt), (unsigned)((d.Hj + EncSmallCfg::BN - 1) / EncSmallCfg::BN));
+        launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_mfma_kernel<EncSmallCfg>, sgrid, dim3(EncSmallCfg::NT), EncSmallCfg::SMEM_BYTES,
+               d, c, small_per_utt);
+      } else {
+        launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_mfma_kernel<EncCfg>, grid, dim3(EncCfg::NT), EncCfg::SMEM_BYTES, d, c,
+               tiles_per_utt);
+      }
     } else {
       launch(m, s, WIND_K_ENC_PROJ, false, enc_proj_f32_kernel, dim3((unsigned)c.T, (unsigned)c.B), dim3(256),
              (size_t)d.D * 4, d, c);
@@ -553,10 +562,15 @@ int ensure_graph(wind_model *m) {
   return WIND_OK;
 }
 
-int fetch_stats(wind_model *m, hipStream_t s) {
-  unsigned long long h[kNumStats];
-  HIP_TRY(hipMemcpyAsync(h, m->call.stats, sizeof(h), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
+// The call's counters on their way to pinned memory (h_stats); read_stats takes them from there once
+// the stream has passed the copy.
+int enqueue_stats_copy(wind_model *m, hipStream_t s) {
+  HIP_TRY(hipMemcpyAsync(m->h_stats, m->call.stats, kNumStats * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+  return WIND_OK;
+}
+
+int read_stats(wind_model *m) {
+  const unsigned long long *h = m->h_stats;
   wind_stats &st = m->last_stats;
   std::memset(&st, 0, sizeof(st));
   st.iterations = (int64_t)h[ST_ITER];
@@ -582,6 +596,13 @@ int fetch_stats(wind_model *m, hipStream_t s) {
     (void)hipMemset(m->call.dbg, 0, 128);
   }
   return h[ST_OVERFLOW] ? WIND_ERR_OVERFLOW : WIND_OK;
+}
+
+int fetch_stats(wind_model *m, hipStream_t s) {
+  int rc = enqueue_stats_copy(m, s);
+  if (rc) return rc;
+  HIP_TRY(hipStreamSynchronize(s));
+  return read_stats(m);
 }
 
 // Shape of the resident loop kernel for this call, or false if the call does not qualify: bf16, one
@@ -673,10 +694,9 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     lp.spin_limit = (unsigned)m->opt_loop_spin_limit;
     {
       const int bar_ints = (1 + lp.G) * kLoopFlagStride;
-      fill_int_kernel<<<(unsigned)((bar_ints + 255) / 256), 256, 0, s>>>((int *)lp.bar, bar_ints, 0);
       // the key exchange starts out as "two iterations old": all tag bits set, the first iterations' tag is 0
       const int key_ints = 2 * kLoopRows * ((m->dev.V + kTinyCols - 1) / kTinyCols) * 2;
-      fill_int_kernel<<<(unsigned)((key_ints + 255) / 256), 256, 0, s>>>((int *)lp.parts_x, key_ints, -1);
+      loop_prepare_kernel<<<(unsigned)((bar_ints + key_ints + 255) / 256), 256, 0, s>>>((int *)lp.bar, bar_ints, (int *)lp.parts_x, key_ints);
     }
     {
       const dim3 grid((unsigned)(lp.G * lp.step));
@@ -700,12 +720,14 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     }
     HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipMemcpyAsync(m->h_flag + 1, lp.bar, 2 * sizeof(int), hipMemcpyDeviceToHost, s));
+    rc = enqueue_stats_copy(m, s);   // with the flags: one wait for the call
+    if (rc) return rc;
     HIP_TRY(hipStreamSynchronize(s));
     m->loop_info[0] = lp.G; m->loop_info[1] = m->h_flag[2] == 2;
     if (m->h_flag[1] != 0) return fail(WIND_ERR_HIP, "resident loop: a grid barrier timed out (workgroups not all resident?)");
     if (m->h_flag[0] != 0) return fail(WIND_ERR_HIP, "decode loop did not terminate");
     m->have_call_times = true;
-    rc = fetch_stats(m, s);
+    rc = read_stats(m);
     if (rc == WIND_ERR_OVERFLOW) return fail(rc, "an utterance produced more labels than cap");
     return rc;
   }
@@ -943,8 +965,9 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
     rc = static_scratch_address(&unused);   // once per device, here rather than in a call that must not stall
   }
   if (rc == WIND_OK) {
-    hipError_t e = hipHostMalloc((void **)&m->h_flag, 64, hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void **)&m->h_flag, 64 + kNumStats * sizeof(unsigned long long), hipHostMallocDefault);
     if (e != hipSuccess) rc = fail(WIND_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
+    else m->h_stats = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(m->h_flag) + 64);
   }
   if (rc == WIND_OK) {
     hipError_t e = hipFuncSetAttribute((const void *)joint_ws_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kWsSmemBytes);
@@ -967,6 +990,9 @@ int wind_load_weights(const wind_weights *w, void *stream, wind_model **out) try
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)enc_proj_mfma_kernel<EncCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, EncCfg::SMEM_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)enc_proj_mfma_kernel<EncSmallCfg>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, EncSmallCfg::SMEM_BYTES);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void *)lstm_layer_dma_kernel<PredCfg>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, PredCfg::SMEM_BYTES);

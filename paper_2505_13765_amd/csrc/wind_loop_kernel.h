@@ -221,6 +221,15 @@ __device__ __forceinline__ void loop_rows_times_h(const bf16_t *hsrc, const bf16
   }
 }
 
+// What the resident loop kernel expects to find before its launch, in one launch: the arrival words and the
+// abort word at zero, the exchanged keys all ones ("two iterations old": the first iterations' tag is 0).
+__global__ __launch_bounds__(256) void loop_prepare_kernel(int *bar, int bar_ints, int *keys, int key_ints) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < bar_ints + key_ints; i += gridDim.x * 256) {
+    if (i < bar_ints) bar[i] = 0;
+    else keys[i - bar_ints] = -1;
+  }
+}
+
 // NS: 0 = the window rows go through LDS; 1 .. kFusedSteps = the fused form for Hj = 128 NS (the number of
 // K steps of 32 in a wave's quarter of K; a constant, because matrix-core products under a condition
 // make the compiler move the accumulators in and out of their registers around every step).
