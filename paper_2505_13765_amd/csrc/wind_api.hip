@@ -718,9 +718,9 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
       m->loop_info[0] = lp.G; m->loop_info[1] = 0;
       return WIND_OK;
     }
-    HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(m->h_flag + 1, lp.bar, 2 * sizeof(int), hipMemcpyDeviceToHost, s));
-    rc = enqueue_stats_copy(m, s);   // with the flags: one wait for the call
+    static_assert(kNumStats <= 128, "loop_collect_kernel: one thread per counter");
+    loop_collect_kernel<<<1, 128, 0, s>>>(c.n_active, lp.bar, c.stats, kNumStats, m->h_flag, m->h_stats);   // one launch, one wait
+    rc = check_launch("resident loop results");
     if (rc) return rc;
     HIP_TRY(hipStreamSynchronize(s));
     m->loop_info[0] = lp.G; m->loop_info[1] = m->h_flag[2] == 2;
@@ -800,6 +800,8 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
       polled = true;
       HIP_TRY(hipEventRecord(m->ev_call[2], s));
       HIP_TRY(hipMemcpyAsync(m->h_flag, c.n_active, sizeof(int), hipMemcpyDeviceToHost, s));
+      rc = enqueue_stats_copy(m, s);   // final once the count is zero: the last poll needs no second wait
+      if (rc) return rc;
       HIP_TRY(hipStreamSynchronize(s));
       prof_collect(m);
       if (*m->h_flag == 0) break;
@@ -807,7 +809,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
     }
   }
   m->have_call_times = true;
-  rc = fetch_stats(m, s);
+  rc = m->opt_host_sync ? fetch_stats(m, s) : read_stats(m);
   if (c.iter_rows && (rc == WIND_OK || rc == WIND_ERR_OVERFLOW)) {
     const size_t n = (size_t)std::min<long long>(m->last_stats.iterations, kIterRowsCap);
     m->joint_rows.resize(n);

@@ -230,6 +230,17 @@ __global__ __launch_bounds__(256) void loop_prepare_kernel(int *bar, int bar_int
   }
 }
 
+// What the host reads after a decode by the resident loop kernel, in one launch instead of three copies:
+// the active count, the loop's abort and placement words, and the call's counters, written straight
+// into pinned host memory (h_flag, h_stats: device-visible addresses of it).
+__global__ __launch_bounds__(128) void loop_collect_kernel(const int *n_active, const unsigned *bar, const unsigned long long *stats,
+                                                          int n_stats, int *h_flag, unsigned long long *h_stats) {
+  const int i = threadIdx.x;
+  if (i == 0) h_flag[0] = n_active[0];
+  if (i == 1 || i == 2) h_flag[i] = (int)bar[i - 1];
+  if (i < n_stats) h_stats[i] = stats[i];
+}
+
 // NS: 0 = the window rows go through LDS; 1 .. kFusedSteps = the fused form for Hj = 128 NS (the number of
 // K steps of 32 in a wave's quarter of K; a constant, because matrix-core products under a condition
 // make the compiler move the accumulators in and out of their registers around every step).
