@@ -439,10 +439,11 @@ def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
 def test_encoder_projection_against_oracle(torch_cuda):
     """e = W_enc f + b_enc as a decode call computes it, element by element against the oracle, on the
     routes of large calls (B * T >= 16384: bf16 rows; 256-column tiles on four waves that multiply and fetch,
-    with option enc_wide = 0 the 256 x 256 tiles of eight waves) and on the route of small ones,
+    with option enc_wide = 0 the 256 x 256 tiles of eight waves) and on the routes of small ones
+    (128 x 128 tiles; 64 x 64 tiles where those would be fewer than 128),
     with ragged lengths (row tiles of every height that end inside an utterance's padding).  The two
     large-call routes form every output by the same operations in the same order: identical bits."""
-    for B, T in ((9, 2000), (3, 300)):
+    for B, T in ((9, 2000), (3, 300), (8, 600)):
         cfg = wi.scaled(wi.CONFIGS["largevocab_b128"], B, T - 50, T)
         m, o, _ = load(cfg)
         enc, lens = wi.make_batch(cfg)
