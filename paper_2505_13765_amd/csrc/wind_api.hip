@@ -139,6 +139,7 @@ struct wind_model {
   int opt_debug_stamps = 0;
   int opt_lstm_rec = 1;
   int opt_atomic_lists = 1;
+  int opt_decide_two = 1;       // rows of 65 .. 128 key parts: both halves of a row's keys in the decision kernel's first round trip
   bool fma_pred_step = false;   // this call's prediction-network steps keep their state in fp32 (the resident loop kernel reads it)
   LoopDev loop{};
   int *dbg_len = nullptr, *dbg_out = nullptr;   // lengths and outputs of the debug entry points (inside the workspace)
@@ -516,7 +517,9 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing, 
     launch(m, s, WIND_K_BUILD_Z, capturing, build_z_kernel, dim3((unsigned)((max_rows + 3) / 4)), dim3(256), 0, d, c, parity,
            wide ? 1 : 0, wide_threshold_rows(m, c.B, c.W));
     enqueue_joint(m, s, parity, capturing, wide);
-    if (d.Hj <= 1024)
+    if (d.Hj <= 1024 && c.nparts > 64 && c.nparts <= 128 && c.W <= 16 && m->opt_decide_two)   // one row per wave, two key loads per lane
+      launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t, false, true>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
+    else if (d.Hj <= 1024)
       launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t, false>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
     else
       launch(m, s, WIND_K_DECIDE, capturing, decide_kernel<bf16_t, true>, dim3((unsigned)c.B), dim3(decide_threads), 0, d, c, parity, 0);
@@ -1244,6 +1247,11 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
   }
   if (!std::strcmp(key, "atomic_lists")) {
     m->opt_atomic_lists = value != 0;
+    m->graph_valid = false;
+    return WIND_OK;
+  }
+  if (!std::strcmp(key, "decide_two")) {
+    m->opt_decide_two = value != 0;
     m->graph_valid = false;
     return WIND_OK;
   }

@@ -123,7 +123,7 @@ struct DecideShared {
 // logit of everything else in `best_out`, for the workgroup to evaluate together (see decide_utterance).
 template <int NZ, int KW>
 __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, int row, int b, int frame, int nparts,
-                                           int stride, int part_width, float vblank, float thresh, float4 kk0,
+                                           int stride, int part_width, float vblank, float thresh, float4 kk0, bool have1, float4 kk1,
                                            bool defer, int &deferred, float &best_out) {
   const int lane = threadIdx.x & 63, V = m.V;
   const size_t prow = (size_t)row * stride;
@@ -148,6 +148,7 @@ __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, 
     const int pi = p0 + lane;
     float4 kk = no_keys();
     if (p0 == 0) kk = kk0;
+    else if (have1 && p0 == 64) kk = kk1;
     else if (pi < nparts) kk = load_keys<KW>(c.parts, prow + pi);
     // A part keeps only its largest keys (three from the joint kernel, two in the resident loop kernel).
     // If the last of them is inside the band, a further label of that part may be too, unseen: every
@@ -194,7 +195,7 @@ __device__ __forceinline__ int recheck_row(const ModelDev &m, const CallDev &c, 
 // 1024-thread workgroup's share.
 template <int KW>
 __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev &c, int row, int b, int frame, int nparts,
-                                                int stride, int part_width, float vblank, float thresh, float4 kk0,
+                                                int stride, int part_width, float vblank, float thresh, float4 kk0, bool have1, float4 kk1,
                                                 bool defer, int &deferred, float &best_out) {
   const int lane = threadIdx.x & 63, V = m.V;
   const size_t prow = (size_t)row * stride;
@@ -220,6 +221,7 @@ __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev
     const int pi = p0 + lane;
     float4 kk = no_keys();
     if (p0 == 0) kk = kk0;
+    else if (have1 && p0 == 64) kk = kk1;
     else if (pi < nparts) kk = load_keys<KW>(c.parts, prow + pi);
     // A part keeps only its largest keys (three from the joint kernel, two in the resident loop kernel).
     // If the last of them is inside the band, a further label of that part may be too, unseen: every
@@ -264,15 +266,19 @@ __device__ __forceinline__ int recheck_row_wide(const ModelDev &m, const CallDev
 // Label of one window row, decided by a whole wave: argmax over the row's keys, with every key
 // inside the near-tie band re-evaluated in fp32 (see the header comment of this file).
 // kk0 = this lane's keys of the row for part `lane` (the caller loads them, possibly for several
-// rows at once so that the loads overlap); parts 64 and up are read here.
+// rows at once so that the loads overlap); parts 64 and up are read here, except that with have1 the
+// caller also brings kk1, the keys of part lane + 64 (all there is to read for up to 128 parts: the
+// row then costs no second trip to memory).
 template <class WT, bool WIDE, int KW>
 __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, int row, int b, int frame,
                                           int nparts, int stride, int part_width, float vblank, float znorm,
-                                          float4 kk0, int &n_recheck, bool defer, int &deferred, float &best_out) {
+                                          float4 kk0, bool have1, float4 kk1, int &n_recheck, bool defer, int &deferred,
+                                          float &best_out) {
   const int lane = threadIdx.x & 63, V = m.V;
   const size_t prow = (size_t)row * stride;
+  auto keys_at = [&](int pi) -> float4 { return have1 && pi == lane + 64 ? kk1 : load_keys<KW>(c.parts, prow + pi); };
   float k1 = kk0.x;
-  for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, load_keys<KW>(c.parts, prow + pi).x);
+  for (int pi = lane + 64; pi < nparts; pi += 64) k1 = fmaxf(k1, keys_at(pi).x);
   const float kbest = wave_max_f32(k1);
   const float vbest = key_val(kbest);
   const float top = fmaxf(vbest, vblank);
@@ -282,7 +288,7 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
   // how many label keys are inside the band?
   int cnt = (key_val(kk0.x) >= thresh) + (key_val(kk0.y) >= thresh) + (key_val(kk0.z) >= thresh);
   for (int pi = lane + 64; pi < nparts; pi += 64) {
-    const float4 kk = load_keys<KW>(c.parts, prow + pi);
+    const float4 kk = keys_at(pi);
     cnt += (key_val(kk.x) >= thresh) + (key_val(kk.y) >= thresh) + (key_val(kk.z) >= thresh);
   }
   cnt = wave_sum_i32(cnt);
@@ -290,15 +296,17 @@ __device__ __forceinline__ int decide_row(const ModelDev &m, const CallDev &c, i
     // a single label clear of blank and of every other label: find its part
     int col = kk0.x == kbest ? lane * part_width + key_col(kbest) : -1;
     for (int pi = lane + 64; pi < nparts; pi += 64)
-      if (load_keys<KW>(c.parts, prow + pi).x == kbest) col = pi * part_width + key_col(kbest);
+      if (keys_at(pi).x == kbest) col = pi * part_width + key_col(kbest);
     return wave_max_i32(col);
   }
   // near tie: fp32 logits of every candidate, hidden vector rebuilt from fp32 e and p
   ++n_recheck;
   if constexpr (WIDE)
-    return recheck_row_wide<KW>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0, defer, deferred, best_out);
+    return recheck_row_wide<KW>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0, have1, kk1, defer, deferred,
+                                best_out);
   else
-    return recheck_row<8, KW>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0, defer, deferred, best_out);
+    return recheck_row<8, KW>(m, c, row, b, frame, nparts, stride, part_width, vblank, thresh, kk0, have1, kk1, defer, deferred,
+                              best_out);
 }
 
 // Four window rows per wave at once, 16 lanes per row, for rows of at most 32 parts: lane 16 q + s holds
@@ -339,7 +347,7 @@ __device__ __forceinline__ int decide_rows_quad(const ModelDev &m, const CallDev
     int none = -1;
     float unused = 0.f;
     const int l = decide_row<WT, false, 2>(m, c, row, st.x, st.y + jq, nparts, nparts, part_width, readlane_f32(vblank, 16 * q),
-                                        readlane_f32(znorm, 16 * q), kk0, n_recheck, false, none, unused);
+                                        readlane_f32(znorm, 16 * q), kk0, false, no_keys(), n_recheck, false, none, unused);
     if ((lane >> 4) == q) label = l;
   }
   if (s == 0 && j < c.W) sh.label[j] = label;
@@ -348,11 +356,17 @@ __device__ __forceinline__ int decide_rows_quad(const ModelDev &m, const CallDev
 
 // Keys and row scalars of the first rows a wave decides, requested before anything else is known
 // about the utterance so that they share the round trip of the slot table.
+// TWO: also the keys of part lane + 64 (rows of 65 .. 128 parts), for a wave that decides a single row.
 constexpr int kRowsAhead = 4;
-struct RowsAhead {
-  float4 kk0[kRowsAhead];
-  float vb[kRowsAhead], zn[kRowsAhead];
+template <int N, bool TWO>
+struct RowsAheadT {
+  static constexpr int kRows = N;
+  static constexpr bool kTwo = TWO;
+  float4 kk0[N];
+  float4 kk1[TWO ? N : 1];
+  float vb[N], zn[N];
 };
+using RowsAhead = RowsAheadT<kRowsAhead, false>;
 
 // What a decided window does to its utterance (Algorithm 2's update, with the cap on labels per frame):
 // i = the smallest row whose label is not blank (label_i), or -1; n = rows of the window.  Writes the
@@ -407,10 +421,10 @@ __device__ __forceinline__ WindowOutcome window_outcome(const CallDev &c, int4 s
 // waves), then the first non-blank row by ballot and the pointer / hypothesis update of
 // Algorithm 2.  nparts key pairs per row are valid, rows are `stride` pairs apart.  Ends with a
 // workgroup barrier.
-template <class WT, bool LOCAL, bool WIDE = false>
+template <class WT, bool LOCAL, bool WIDE = false, class RA = RowsAhead>
 __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDev &c, int a, int4 st, int cnt,
                                                  int exact_mode, int nparts, int stride, int part_width,
-                                                 const RowsAhead &ahead, DecideShared &sh, bool write_out = true,
+                                                 const RA &ahead, DecideShared &sh, bool write_out = true,
                                                  bool rows_done = false, int pre_recheck = 0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int b = st.x, t = st.y, len = st.z, V = m.V;
@@ -419,7 +433,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
   if (threadIdx.x == 0) { sh.recheck = 0; sh.n_pend = 0; }
   __syncthreads();
   constexpr int KW = LOCAL ? 2 : 4;   // the resident loop kernel keeps two keys per part, the joint kernel three
-  auto one_row = [&](int j, float4 k0, float vb, float zn) {
+  auto one_row = [&](int j, float4 k0, bool have1, float4 k1, float vb, float zn) {
     int label = V, deferred = -1;
     float best = 0.f;
     if (j < n) {
@@ -429,7 +443,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
       } else {
         if (exact_mode) label = c.row_label[row];
         else label = decide_row<WT, WIDE, KW>(m, c, row, b, t + j, nparts, stride, part_width, vb, zn,
-                                        lane < nparts ? k0 : no_keys(), n_recheck, !LOCAL, deferred, best);
+                                        lane < nparts ? k0 : no_keys(), have1, k1, n_recheck, !LOCAL, deferred, best);
       }
     }
     if (lane == 0) {
@@ -438,11 +452,13 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
     }
   };
 #pragma unroll
-  for (int q = 0; q < kRowsAhead; ++q) {
+  for (int q = 0; q < RA::kRows; ++q) {
     const int j = wave + q * nwaves;
-    if (!rows_done && j < c.W) one_row(j, ahead.kk0[q], ahead.vb[q], ahead.zn[q]);
+    float4 k1 = no_keys();
+    if constexpr (RA::kTwo) k1 = ahead.kk1[q];
+    if (!rows_done && j < c.W) one_row(j, ahead.kk0[q], RA::kTwo, k1, ahead.vb[q], ahead.zn[q]);
   }
-  for (int j = wave + kRowsAhead * nwaves; !rows_done && j < c.W; j += nwaves) {
+  for (int j = wave + RA::kRows * nwaves; !rows_done && j < c.W; j += nwaves) {
     float4 k0 = no_keys();
     float vb = 0.f, zn = 0.f;
     if (!exact_mode && j < n) {
@@ -451,7 +467,7 @@ __device__ __forceinline__ void decide_utterance(const ModelDev &m, const CallDe
       vb = LOCAL ? sh.blank[row] : c.blank_logit[row];
       zn = LOCAL ? sh.znorm[row] : c.znorm[row];
     }
-    one_row(j, k0, vb, zn);
+    one_row(j, k0, false, no_keys(), vb, zn);
   }
   if (lane == 0 && n_recheck) atomicAdd(&sh.recheck, n_recheck);
   __syncthreads();
@@ -605,7 +621,9 @@ __device__ __forceinline__ void compact_lists(const CallDev &c, int parity, int 
 // Row argmax, first non-blank by ballot, pointer and hypothesis update, list compaction.
 // One workgroup per active utterance; the last workgroup to finish rebuilds the lists.
 // WIDE: joint hidden sizes above 1024 (the near-tie path then keeps the hidden vector in more registers).
-template <class WT, bool WIDE>
+// TWO: rows of 65 .. 128 column parts in windows of at most one row per wave: each wave asks for both halves
+// of its row's keys in the first round trip (and for no rows beyond its first, which it does not have).
+template <class WT, bool WIDE, bool TWO = false>
 __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int parity, int exact_mode) {
   __shared__ DecideShared sh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
@@ -616,15 +634,18 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   const int na = c.n_active[parity];
   const int4 st = c.slot_state[parity * c.slot_stride + a];
   const int cnt = c.slot_count[parity * c.slot_stride + a];
-  RowsAhead ahead;
+  using RA = RowsAheadT<TWO ? 1 : kRowsAhead, TWO>;
+  RA ahead;
 #pragma unroll
-  for (int q = 0; q < kRowsAhead; ++q) {
+  for (int q = 0; q < RA::kRows; ++q) {
     const int j = wave + q * nwaves;
     ahead.kk0[q] = no_keys();
+    if (TWO) ahead.kk1[q] = no_keys();
     ahead.vb[q] = 0.f; ahead.zn[q] = 0.f;
     if (!exact_mode && j < c.W) {
       const int row = a * c.W + j;
       if (lane < c.nparts) ahead.kk0[q] = load_keys<4>(c.parts, (size_t)row * c.nparts + lane);
+      if (TWO && lane + 64 < c.nparts) ahead.kk1[q] = load_keys<4>(c.parts, (size_t)row * c.nparts + lane + 64);
       ahead.vb[q] = c.blank_logit[row];
       ahead.zn[q] = c.znorm[row];
     }
@@ -632,7 +653,7 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
   for (int j = threadIdx.x; j <= kMaxWindow; j += blockDim.x) sh.hist[j] = 0u;
   if (na == 0 && a == 0 && threadIdx.x == 0) c.n_active[parity ^ 1] = 0;  // keep both slots at "done"
   if (a >= na) return;
-  decide_utterance<WT, false, WIDE>(m, c, a, st, cnt, exact_mode, c.nparts, c.nparts, c.part_width, ahead, sh);
+  decide_utterance<WT, false, WIDE, RA>(m, c, a, st, cnt, exact_mode, c.nparts, c.nparts, c.part_width, ahead, sh);
   const long long ts1 = c.dbg ? wall_clock64() : 0;
   if (c.dbg && threadIdx.x == 0) {   // rows phase of workgroups with / without a near-tie
     atomicAdd((unsigned long long *)&c.dbg[sh.recheck ? 4 : 6], (unsigned long long)(ts1 - ts0));

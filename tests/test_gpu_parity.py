@@ -133,6 +133,14 @@ def test_bf16_scaled_workloads(torch_cuda, name, B, lo, hi, windows):
     toks_w, frs_w = m.decode(d_enc, d_len, windows[-1], cfg.S)
     assert all(a.tolist() == b.tolist() for a, b in zip(first[0], toks_w))
     assert all(a.tolist() == b.tolist() for a, b in zip(first[1], frs_w))
+    # rows of more than 64 key parts: the decision kernel that fetches the second half of a row's keys later
+    # (the default asks for both halves at once where a wave decides one row)
+    m.set_option("joint_wide", 1)
+    m.set_option("decide_two", 0)
+    for W in windows:
+        toks_1, frs_1 = m.decode(d_enc, d_len, W, cfg.S)
+        assert all(a.tolist() == b.tolist() for a, b in zip(first[0], toks_1))
+        assert all(a.tolist() == b.tolist() for a, b in zip(first[1], frs_1))
     m.close()
 
 
@@ -385,8 +393,8 @@ def test_joint_kernel_keys_against_oracle(torch_cuda, name, B, W, V, wide):
     m.close()
 
 
-@pytest.mark.parametrize("B", [3, 1])
-def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
+@pytest.mark.parametrize("B,V,col0", [(3, 200, 64), (1, 200, 64), (3, 4300, 4160)])
+def test_third_label_of_a_part_inside_the_band(torch_cuda, B, V, col0):
     """The joint kernel keeps three keys per 64-column part (the resident loop kernel two per 32 columns).
     Here the label that wins in fp32 ranks FOURTH (third in the loop kernel's case) inside its part in the
     bf16 pass, 3e-3 clear of the runner-up in the oracle (so no near-tie exclusion applies): the decision
@@ -394,11 +402,12 @@ def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
     re-evaluated whole.  The model is built for it: one part's weight rows are made
     large, so that the rounding of the hidden vector moves their logits by several 1e-3, and the output
     biases are then set so that at the first evaluation of utterance 0 every logit is known.  Both deciding
-    kernels are covered: the per-step kernels (B = 3) and the resident loop kernel (B = 1)."""
-    cfg = wi.WindConfig("third_key", 77, B, 12, 20, 64, 64, 1, 64, 256, 200, "bf16", (4,), 3, 0.7)
+    kernels are covered: the per-step kernels (B = 3) and the resident loop kernel (B = 1); with 4300 labels the
+    part is the 66th of its row, among those whose keys a wave of the decision kernel holds in a second register set."""
+    cfg = wi.WindConfig("third_key", 77, B, 12, 20, 64, 64, 1, 64, 256, V, "bf16", (4,), 3, 0.7)
     w = wi.make_weights(cfg, blank_bias=0.0, pred_gain=4.0)
     enc, lens = wi.make_batch(cfg)
-    part = slice(64, 96)                                   # inside one 64-column part and one 32-column part
+    part = slice(col0, col0 + 32)                          # inside one 64-column part and one 32-column part
     scale, found = 1.0, None
     while found is None and scale <= 64.0:
         scale *= 2.0
@@ -411,8 +420,8 @@ def test_third_label_of_a_part_inside_the_band(torch_cuda, B):
         wz = w2["w_out"].astype(np.float64) @ z            # true products
         noise = w2["w_out"].astype(np.float64)[part] @ (zb - z)
         order = np.argsort(noise)
-        win = 64 + int(order[0])                            # the rounding lowers this label's logit the most
-        others = [64 + int(order[-1 - k]) for k in range(3)]   # and raises these three the most
+        win = col0 + int(order[0])                          # the rounding lowers this label's logit the most
+        others = [col0 + int(order[-1 - k]) for k in range(3)]   # and raises these three the most
         if noise[order[-3]] - noise[order[0]] > 1.5e-2:
             found = (win, others)
     assert found is not None, "no scale gave the rounding noise the construction needs"
