@@ -139,6 +139,7 @@ struct wind_model {
   int opt_debug_stamps = 0;
   int opt_lstm_rec = 1;
   int opt_atomic_lists = 1;
+  int opt_slot_rows = 1;        // the iteration's prediction-network launches take their rows by slot (CallDev::slot_rows)
   int opt_decide_two = 1;       // rows of 65 .. 128 key parts: both halves of a row's keys in the decision kernel's first round trip
   bool fma_pred_step = false;   // this call's prediction-network steps keep their state in fp32 (the resident loop kernel reads it)
   LoopDev loop{};
@@ -321,6 +322,7 @@ void carve_workspace(wind_model *m, const WsLayout &w, char *base, int B) {
   m->dbg_len = (int *)(base + w.o_dbglen);
   m->dbg_out = (int *)(base + w.o_dbgout);
   c.lists_atomic = m->opt_atomic_lists && m->dtype == WIND_BF16;   // the path with build_z_kernel
+  c.slot_rows = m->opt_slot_rows && c.lists_atomic && c.rec != nullptr && m->dev.L > 1;   // only layers above the first use it
   m->loop.bar = (unsigned *)(base + o_lbar);
   m->loop.h_x = (float *)(base + o_lh);
   m->loop.p_x = (float *)(base + o_lp);
@@ -371,7 +373,7 @@ void prof_collect(wind_model *m) {
 }
 
 // prediction-network step for the utterances on the emit list, then their projection
-int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first = false) {
+int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first = false, int parity = 0) {
   const ModelDev &d = m->dev;
   const CallDev &c = m->call;
   const int lstm_blocks = (d.Hp + 3) / 4, proj_blocks = (d.Hj + 3) / 4;
@@ -389,15 +391,17 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first =
       c0.rec = nullptr;
       for (int l = 0; l < d.L; ++l)
         launch(m, s, WIND_K_LSTM, capturing, lstm_layer_dma_kernel<PredCfg>, dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles),
-               dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c0, l, 0);
+               dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c0, l, 0, 0);
       launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_dma_kernel<PredCfg>, dim3(proj_tiles, mtiles), dim3(PredCfg::NT),
              PredCfg::SMEM_BYTES, d, c0, 0, (int)proj_tiles);
       launch(m, s, WIND_K_LSTM, capturing, pred_proj_dma_kernel<PredCfg>, dim3(rec_tiles, mtiles), dim3(PredCfg::NT),
              PredCfg::SMEM_BYTES, d, c, 1, 0);
     } else {
+      // the layers above the first take their rows by slot (asked for at once) or through the emit list; the
+      // projection launch always goes through the list (by slot it was slower: 6.6 -> 7.0 us on the B = 128 workload)
       for (int l = 1; l < d.L; ++l)
         launch(m, s, WIND_K_LSTM, capturing, lstm_layer_dma_kernel<PredCfg>, dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles),
-               dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l, 1);
+               dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l, c.slot_rows ? 2 : 1, parity);
       launch(m, s, WIND_K_PRED_PROJ, capturing, pred_proj_dma_kernel<PredCfg>, dim3(proj_tiles + rec_tiles, mtiles),
              dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, 1, (int)proj_tiles);
     }
@@ -406,7 +410,7 @@ int enqueue_pred_step(wind_model *m, hipStream_t s, bool capturing, bool first =
   for (int l = 0; l < d.L; ++l) {
     if (mfma)
       launch(m, s, WIND_K_LSTM, capturing, lstm_layer_dma_kernel<PredCfg>, dim3((unsigned)(4 * d.Hp / PredCfg::BN), mtiles),
-             dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l, 0);
+             dim3(PredCfg::NT), PredCfg::SMEM_BYTES, d, c, l, 0, 0);
     else if (m->dtype == WIND_BF16 && small_k)
       launch(m, s, WIND_K_LSTM, capturing, lstm_small_kernel<2>, dim3(lstm_blocks), dim3(256), 0, d, c, l);
     else if (m->dtype == WIND_BF16)
@@ -530,7 +534,7 @@ int enqueue_iteration(wind_model *m, hipStream_t s, int parity, bool capturing, 
   }
   int rc = check_launch("iteration");
   if (rc) return rc;
-  return enqueue_pred_step(m, s, capturing);
+  return enqueue_pred_step(m, s, capturing, false, parity);
 }
 
 // The loop's graphs: `unroll` iterations with joint_ws_kernel, and, where the call can have iterations
@@ -685,7 +689,7 @@ int decode(wind_model *m, const float *enc, const int32_t *lengths, int B, int T
   const long long max_iters = (long long)T * ((long long)S + 1) + 2;   // every iteration moves some pointer or emits
   m->loop_info[0] = m->loop_info[1] = 0;
   m->fma_pred_step = use_loop;   // the resident kernel starts from the fp32 state of the start-token step
-  if (use_loop) { c.rec = nullptr; c.lists_atomic = 0; }
+  if (use_loop) { c.rec = nullptr; c.lists_atomic = 0; c.slot_rows = 0; }
   m->have_call_times = false;
   HIP_TRY(hipEventRecord(m->ev_call[0], s));
   rc = enqueue_prologue(m, s);
@@ -1250,6 +1254,11 @@ int wind_set_option(wind_model *m, const char *key, int64_t value) {
     m->graph_valid = false;
     return WIND_OK;
   }
+  if (!std::strcmp(key, "slot_rows")) {
+    m->opt_slot_rows = value != 0;
+    m->graph_valid = false;
+    return WIND_OK;
+  }
   if (!std::strcmp(key, "decide_two")) {
     m->opt_decide_two = value != 0;
     m->graph_valid = false;
@@ -1284,6 +1293,7 @@ static int debug_prologue(wind_model *m, const float *enc_out, const int32_t *le
   c.B = B; c.T = T; c.W = W; c.S = 1; c.cap = 1;
   c.rec = nullptr;   // whole prediction-network steps: no decision kernel runs between them
   c.lists_atomic = 0;
+  c.slot_rows = 0;
   m->fma_pred_step = false;
   m->graph_valid = false;
   c.enc = enc_out;

@@ -690,7 +690,9 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
         const float og = 1.f / (1.f + expf(-(r[i].w + x[i].w)));
         const float cn = fg * cp[i] + ig * tanhf(r[i].z + x[i].z);
         c.c[si] = cn;
-        store_hi_lo(c.hb_hi, c.hb_lo, si, og * tanhf(cn));
+        const float hv = og * tanhf(cn);
+        store_hi_lo(c.hb_hi, c.hb_lo, si, hv);
+        if (c.slot_rows) store_hi_lo(c.hbn_hi, c.hbn_lo, (size_t)a * Hp + u, hv);   // the layer's row of this SLOT
       }
     }
   };
@@ -729,6 +731,8 @@ __global__ __launch_bounds__(1024) void decide_kernel(ModelDev m, CallDev c, int
       }
       if (which >= 0 && add) atomicAdd(&c.stats[which], add);
     }
+    // what the prediction-network launches need to know about this slot's row
+    if (c.slot_rows && threadIdx.x == 32) reinterpret_cast<int *>(c.res_aux)[a] = sh.step_tok >= 0 ? st.x : -1;
     // with enough waves, the one that waits for its claims' answers takes no part in the layer step
     if (nwaves >= 8) first_layer_step(64, blockDim.x - 64);
     else first_layer_step(0, blockDim.x);

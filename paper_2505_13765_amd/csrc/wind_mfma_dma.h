@@ -91,7 +91,8 @@ struct DenseRows {
 // 32 x 32 block (B rows down the registers, A rows across the lanes), which lets an epilogue that
 // reduces over B rows work inside a lane.
 // `after_issue` runs once the first stages are on their way and before anything is awaited: the
-// place for a caller to finish setting up acc from values it loaded earlier, behind the loads' latency.
+// place for a caller to finish setting up acc from values it loaded earlier, behind the loads' latency,
+// or to find out, in the same round trip as the first stages, whether the tile is wanted at all (`drop`).
 struct NoInit {
   __device__ __forceinline__ void operator()() const {}
 };
@@ -99,7 +100,7 @@ template <class Cfg, class ASrc, bool SWAP = false, class Init = NoInit>
 __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf16_t *__restrict__ Bw,
                                                       int K, unsigned char *smem,
                                                       f32x16 (&acc)[Cfg::MI][Cfg::NI], Init after_issue = Init{},
-                                                      int ldb = 0) {
+                                                      int ldb = 0, const bool *drop = nullptr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
   if (ldb == 0) ldb = K;   // B rows are K long unless the caller walks a K-slice of longer rows
@@ -130,6 +131,11 @@ __device__ __forceinline__ void gemm_mainloop_dma_src(const ASrc &asrc, const bf
 #pragma unroll
   for (int s = 0; s < Cfg::NSTAGE; ++s) issue(s < KT ? s : KT - 1, s, -1);
   after_issue();
+  // `drop` (the same for every thread of the workgroup): after_issue found that the tile is not wanted
+  if (drop && *drop) {
+    wait_vmcnt<0>();
+    return;
+  }
 
   // fragment addressing: lane l reads row l%32 of a 32-row block, k chunk 2*ks + l/32
   const int frow = lane & 31, kc = lane >> 5, sw = lds_swizzle<Cfg::CPR>(frow);

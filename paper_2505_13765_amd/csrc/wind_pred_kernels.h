@@ -378,9 +378,119 @@ struct PredRows {
 // pre = 1 (layers above the first, c.rec in use): only the input half, x = the layer below's new
 // vector, on top of the recurrent sums in c.rec; nobody reads this layer's old vector any more, so the
 // new one is written in place (hb_*).
+// pre = 2 (CallDev::slot_rows; layers above the first): as pre = 1, with the rows taken by slot.  Row a of the
+// launch is the a-th active utterance of the iteration (parity: which half of the slot table), its input
+// vector the layer below's row a of hbn_*, whether that utterance emitted or not; res_aux[a] says which
+// utterance it is and whether it steps.  Nothing about the rows' addresses depends on a load, so the
+// operands are asked for first and the slot's data travel in the same round trip.  The new vector goes to
+// row a of this layer in hbn_* (and in place to hb_*).
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, CallDev c, int layer, int pre) {
+__device__ __forceinline__ void lstm_layer_slot_rows(const ModelDev &m, const CallDev &c, int layer, int parity, unsigned char *smem_raw) {
+  constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
+  const int row0 = blockIdx.y * R, n0 = blockIdx.x * Cfg::BN;
+  const int Hp = m.Hp, in = Hp, K = in + Hp;
+  const size_t lofs = (size_t)layer * c.B * Hp;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  PredRows<Cfg> rows;
+  rows.kin = in / Cfg::BK;
+#pragma unroll
+  for (int i = 0; i < Cfg::LPW; ++i) {
+    const int row = (wave * Cfg::LPW + i) * Cfg::RPI + lane / Cfg::CPR;
+    const int chunk = (lane % Cfg::CPR) ^ lds_swizzle<Cfg::CPR>(row);
+    rows.px[i] = c.hb_zero; rows.ph[i] = c.hb_zero; rows.xstep[i] = 0;
+    if (row < Cfg::BM) {
+      const int part = row >= R, slot = min(row0 + (part ? row - R : row), c.B - 1);
+      rows.px[i] = (part ? c.hbn_lo : c.hbn_hi) + lofs - (size_t)c.B * Hp + (size_t)slot * Hp + chunk * 8;
+      rows.xstep[i] = 1;
+    }
+  }
+  f32x16 acc[Cfg::MI][Cfg::NI];
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+  constexpr int EPI = (R * UB + Cfg::NT - 1) / Cfg::NT;   // (row, unit) pairs per thread in the epilogue
+  int ub_e[EPI], tok_e[EPI];
+  float c_prev[EPI];
+  float4 add_e[EPI], rec_e[EPI];
+  bool drop = false;
+  const float *bias = m.b_cat_t[layer] + n0;
+  // asked for ahead of the operand stages, and not waited for before them (loads return in order: what is
+  // older than the stages does not disturb the tile core's counting of its own loads)
+  const int na = c.n_active[parity];
+  const int *slot_ub = reinterpret_cast<const int *>(c.res_aux);   // per slot: the utterance if it steps, else -1
+  int info[EPI];
+#pragma unroll
+  for (int q = 0; q < EPI; ++q) {
+    info[q] = slot_ub[min(row0 + min((tid + q * Cfg::NT) / UB, R - 1), c.B - 1)];   // slots past the count: stale, not used
+    const int u = (tid + q * Cfg::NT) % UB;
+    add_e[q] = make_float4(bias[u], bias[UB + u], bias[2 * UB + u], bias[3 * UB + u]);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  auto slot_data = [&]() {
+    drop = row0 >= na;
+#pragma unroll
+    for (int q = 0; q < EPI; ++q) {
+      const bool live = row0 + min((tid + q * Cfg::NT) / UB, R - 1) < na;
+      tok_e[q] = live ? info[q] : -1;   // >= 0: steps
+      ub_e[q] = tok_e[q] >= 0 ? tok_e[q] : 0;
+    }
+    if (drop) return;
+#pragma unroll
+    for (int q = 0; q < EPI; ++q) {
+      const int u = (tid + q * Cfg::NT) % UB;
+      c_prev[q] = 0.f;
+      rec_e[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (tok_e[q] >= 0) {   // requested here, looked at in the epilogue
+        c_prev[q] = c.c[lofs + (size_t)ub_e[q] * Hp + (n0 >> 2) + u];
+        rec_e[q] = *reinterpret_cast<const float4 *>(c.rec + ((size_t)layer * c.B + ub_e[q]) * 4 * Hp + n0 + 4 * u);
+      }
+    }
+  };
+  gemm_mainloop_dma_src<Cfg>(rows, reinterpret_cast<const bf16_t *>(m.w_cat_t[layer]) + (size_t)n0 * K, in, smem_raw, acc, slot_data,
+                             K, &drop);
+  if (drop) return;
+  __syncthreads();   // every wave is done with the ring: reuse it for the gate tile
+  float *tile = reinterpret_cast<float *>(smem_raw);
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+#pragma unroll
+  for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        tile[(wm * Cfg::WM + acc_row(mi, r, lane)) * TS + wn * Cfg::WN + ni * 32 + (lane & 31)] = acc[mi][ni][r];
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < EPI; ++q) {
+    const int idx = tid + q * Cfg::NT;
+    const int r = idx / UB, u = idx - r * UB;
+    if (idx >= R * UB || tok_e[q] < 0) continue;
+    const float *hi = tile + r * TS + u, *lo = tile + (R + r) * TS + u;
+    const float gi = hi[0] + lo[0] + (add_e[q].x + rec_e[q].x);
+    const float gf = hi[UB] + lo[UB] + (add_e[q].y + rec_e[q].y);
+    const float gg = hi[2 * UB] + lo[2 * UB] + (add_e[q].z + rec_e[q].z);
+    const float go = hi[3 * UB] + lo[3 * UB] + (add_e[q].w + rec_e[q].w);
+    const size_t si = lofs + (size_t)ub_e[q] * Hp + (n0 >> 2) + u;
+    const float ig = 1.f / (1.f + expf(-gi)), fg = 1.f / (1.f + expf(-gf));
+    const float og = 1.f / (1.f + expf(-go));
+    const float cn = fg * c_prev[q] + ig * tanhf(gg);
+    c.c[si] = cn;
+    const float hv = og * tanhf(cn);
+    store_hi_lo(c.hb_hi, c.hb_lo, si, hv);
+    store_hi_lo(c.hbn_hi, c.hbn_lo, lofs + (size_t)(row0 + r) * Hp + (n0 >> 2) + u, hv);
+  }
+}
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, CallDev c, int layer, int pre, int parity) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  if (pre == 2) {
+    lstm_layer_slot_rows<Cfg>(m, c, layer, parity, smem_raw);
+    return;
+  }
   constexpr int R = Cfg::BM / 2, UB = Cfg::BN / 4, TS = Cfg::BN + 4;
   // grid = (column tiles, row tiles): workgroups with consecutive ids share the row tile, and the
   // row tiles of one column tile land on the same XCD (id mod 8), which then fetches that slice of
@@ -413,18 +523,15 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
   // additive term (bias, or the label's row of input gate sums) of this thread's pairs
   const float *bias = m.b_cat_t[layer] + n0;
   float c_prev[EPI];
-  float4 add_e[EPI];
+  float4 add_e[EPI], rec_e[EPI];   // both only looked at in the epilogue: no wait for them ahead of the tile core
 #pragma unroll
   for (int q = 0; q < EPI; ++q) {
-    const int idx = tid + q * Cfg::NT, r = min(idx / UB, R - 1), u = idx % UB;
+    const int idx = tid + q * Cfg::NT, u = idx % UB;
     c_prev[q] = c.c[lofs + (size_t)ub_e[q] * Hp + (n0 >> 2) + u];
     add_e[q] = make_float4(bias[u], bias[UB + u], bias[2 * UB + u], bias[3 * UB + u]);
     if (layer == 0) add_e[q] = *reinterpret_cast<const float4 *>(m.emb_gates + (size_t)tok_e[q] * 4 * Hp + n0 + 4 * u);
-    if (pre) {
-      const float4 rs = *reinterpret_cast<const float4 *>(c.rec + ((size_t)layer * c.B + ub_e[q]) * 4 * Hp + n0 + 4 * u);
-      add_e[q].x += rs.x; add_e[q].y += rs.y; add_e[q].z += rs.z; add_e[q].w += rs.w;
-    }
-    (void)r;
+    rec_e[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (pre) rec_e[q] = *reinterpret_cast<const float4 *>(c.rec + ((size_t)layer * c.B + ub_e[q]) * 4 * Hp + n0 + 4 * u);
   }
   __builtin_amdgcn_sched_barrier(0);   // these requests stay ahead of the tile core's
   PredRows<Cfg> rows;
@@ -471,10 +578,10 @@ __global__ __launch_bounds__(Cfg::NT) void lstm_layer_dma_kernel(ModelDev m, Cal
     const int r = idx / UB, u = idx - r * UB;
     if (idx >= R * UB || row0 + r >= n_emit) continue;
     const float *hi = tile + r * TS + u, *lo = tile + (R + r) * TS + u;
-    const float gi = hi[0] + lo[0] + add_e[q].x;
-    const float gf = hi[UB] + lo[UB] + add_e[q].y;
-    const float gg = hi[2 * UB] + lo[2 * UB] + add_e[q].z;
-    const float go = hi[3 * UB] + lo[3 * UB] + add_e[q].w;
+    const float gi = hi[0] + lo[0] + (add_e[q].x + rec_e[q].x);
+    const float gf = hi[UB] + lo[UB] + (add_e[q].y + rec_e[q].y);
+    const float gg = hi[2 * UB] + lo[2 * UB] + (add_e[q].z + rec_e[q].z);
+    const float go = hi[3 * UB] + lo[3 * UB] + (add_e[q].w + rec_e[q].w);
     const size_t si = lofs + (size_t)ub_e[q] * Hp + (n0 >> 2) + u;
     const float ig = 1.f / (1.f + expf(-gi)), fg = 1.f / (1.f + expf(-gf));
     const float og = 1.f / (1.f + expf(-go));

@@ -67,6 +67,11 @@ struct CallDev {
   int lists_atomic;             // 1: decide_kernel's workgroups claim their places in the next slot table and the
                                 //    emit list with atomic counters (order varies, results do not); 0: the last
                                 //    workgroup to finish compacts res_state / res_aux in slot order
+  int slot_rows;                // 1 (large batches of models with more than one layer, with rec and lists_atomic): the LSTM
+                                //    launches of the layers above the first take their rows by SLOT: row a = the a-th active
+                                //    utterance of the iteration, whether it emitted or not.  Its new hidden vectors sit in
+                                //    hbn_*[layer][a], and word a of res_aux (as ints) is the utterance if it steps, else -1:
+                                //    a launch can ask for its operand rows before it knows anything about the iteration
   float *h, *c, *hn;            // [L][B][Hp]
   bf16_t *hb_hi, *hb_lo, *hbn_hi, *hbn_lo;  // [L][B][Hp] large-batch path: h and new h as bf16 hi + lo
   const bf16_t *hb_zero;        // [max(E,Hp)] zeros (the lo part of an embedding row)

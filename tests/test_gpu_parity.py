@@ -155,10 +155,12 @@ def test_prediction_network_on_mfma_tiles(torch_cuda, name, B, lo, hi, W):
     d_enc, d_len = to_dev(torch_cuda, enc, lens)
     res = []
     stats = []
-    for min_batch, rec, atomic in ((1, 1, 1), (1, 0, 1), (1, 1, 0), (1, 0, 0), (10 ** 6, 1, 1)):
+    # slot: the layers above the first take their rows by slot of the active list instead of through the emit list
+    for min_batch, rec, atomic, slot in ((1, 1, 1, 1), (1, 1, 1, 0), (1, 0, 1, 1), (1, 1, 0, 1), (1, 0, 0, 1), (10 ** 6, 1, 1, 1)):
         m.set_option("pred_mfma_min_batch", min_batch)
         m.set_option("lstm_rec", rec)
         m.set_option("atomic_lists", atomic)   # lists of active / emitting utterances: claimed by atomics, or compacted in order
+        m.set_option("slot_rows", slot)
         toks, frs = m.decode(d_enc, d_len, W, cfg.S)
         assert compare_batch(o, enc, lens, cfg.S, toks, frs, tol=TOL_GAP) <= 1
         res.append((toks, frs))
