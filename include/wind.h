@@ -375,6 +375,16 @@ int wind_get_loop_info(wind_model *m, int *workgroups, int *one_l2);
  *             LSTM layer's gate sums (w_hh . h) is kept ready for the hidden vectors as they stand and
  *             renewed beside the projection, so a step only adds the input half once the label is
  *             known (the first layer inside the decision kernel); 0: whole steps after the decision
+ *   "slot_rows"  1 (default): with "lstm_rec" and "atomic_lists", in models of more than one LSTM layer, the
+ *             layers above the first take their rows by slot of the iteration's list of active utterances
+ *             (rows of utterances that do not step are computed and dropped), so that their kernels can ask
+ *             for their operands before they have read anything about the iteration; 0: through the list of
+ *             utterances that emitted.  The decoded output does not depend on it
+ *   "decide_two"  1 (default): for rows of 65 .. 128 column parts (4097 .. 8192 labels) and windows of at most
+ *             16 rows, a wave of the decision kernel asks for both halves of its row's keys at once; 0: for the
+ *             second half once the first has been looked at (the form for every other shape)
+ *   "enc_wide"  1 (default): large calls of bf16 models with D >= 320 run the encoder projection on the
+ *             256-column tile core; 0: on 256 x 256 tiles of eight waves.  Same bits either way
  *   "beam_exact"  1: the beam-search entry points evaluate bf16 models' joiner rows with an fp32
  *             hidden vector and fp32 FMA instead of the bf16 MFMA pass, so that their choices do
  *             not depend on the rounding of the hidden vector (default 0)
